@@ -1,0 +1,189 @@
+"""ctypes binding of the C oracle (test infrastructure; see ``conv_oracle.c``).
+
+The definitions it evaluates -- forward, backward-data and backward-filter of a
+convolutional layer as used by back-propagation through the ConvNet that the
+paper trains (its data-parallelism and model-parallelism paragraphs) -- are
+written out in the header comment of ``conv_oracle.c``.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "conv_oracle.c")
+_LIB = os.path.join(_HERE, "libconv_oracle.so")
+
+_lib = None
+
+_c_dp = ctypes.POINTER(ctypes.c_double)
+_c_ip = ctypes.POINTER(ctypes.c_int64)
+_c_i32p = ctypes.POINTER(ctypes.c_int32)
+
+
+def build(force=False):
+    """Compile ``conv_oracle.c`` into ``libconv_oracle.so`` next to it."""
+    if (not force and os.path.exists(_LIB)
+            and os.path.getmtime(_LIB) >= os.path.getmtime(_SRC)):
+        return _LIB
+    cmd = ["gcc", "-O2", "-fopenmp", "-std=c99", "-Wall", "-Wextra", "-shared",
+           "-fPIC", "-o", _LIB, _SRC]
+    subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+        dims = [ctypes.c_int] * 9
+        for name in ("oracle_conv_fwd", "oracle_conv_bwd_data", "oracle_conv_bwd_filter"):
+            f = getattr(_lib, name)
+            f.argtypes = [_c_dp, _c_dp, _c_dp] + dims
+            f.restype = None
+        for name in ("oracle_conv_fwd_at", "oracle_conv_bwd_data_at",
+                     "oracle_conv_bwd_filter_at"):
+            f = getattr(_lib, name)
+            f.argtypes = [_c_dp, _c_dp] + dims + [_c_ip, ctypes.c_int64, _c_dp]
+            f.restype = None
+        _lib.oracle_relu_fwd.argtypes = [_c_dp, _c_dp, ctypes.c_int64]
+        _lib.oracle_relu_bwd.argtypes = [_c_dp, _c_dp, _c_dp, ctypes.c_int64]
+        _lib.oracle_maxpool3x3s2_fwd.argtypes = [_c_dp, _c_dp, _c_i32p, ctypes.c_int64,
+                                                 ctypes.c_int, ctypes.c_int]
+        _lib.oracle_maxpool3x3s2_bwd.argtypes = [_c_dp, _c_dp, _c_dp, ctypes.c_int64,
+                                                 ctypes.c_int, ctypes.c_int]
+        _lib.oracle_out_extent.argtypes = [ctypes.c_int] * 4
+        _lib.oracle_out_extent.restype = ctypes.c_int
+        _lib.oracle_pool_extent.argtypes = [ctypes.c_int]
+        _lib.oracle_pool_extent.restype = ctypes.c_int
+        _lib.oracle_num_threads.restype = ctypes.c_int
+        _lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _p(a):
+    return a.ctypes.data_as(_c_dp)
+
+
+def num_threads():
+    return int(_load().oracle_num_threads())
+
+
+def set_num_threads(t):
+    _load().oracle_set_num_threads(int(t))
+
+
+def out_extent(size, filt, stride, pad):
+    return int(_load().oracle_out_extent(size, filt, stride, pad))
+
+
+def pool_extent(size):
+    return int(_load().oracle_pool_extent(size))
+
+
+def conv_fwd(x, w, stride, pad):
+    x, w = _f64(x), _f64(w)
+    N, C, H, W = x.shape
+    K, C2, R, S = w.shape
+    assert C == C2
+    P, Q = out_extent(H, R, stride, pad), out_extent(W, S, stride, pad)
+    y = np.empty((N, K, P, Q), dtype=np.float64)
+    _load().oracle_conv_fwd(_p(x), _p(w), _p(y), N, C, H, W, K, R, S, stride, pad)
+    return y
+
+
+def conv_bwd_data(dy, w, H, W, stride, pad):
+    dy, w = _f64(dy), _f64(w)
+    N, K, P, Q = dy.shape
+    K2, C, R, S = w.shape
+    assert K == K2
+    assert P == out_extent(H, R, stride, pad) and Q == out_extent(W, S, stride, pad)
+    dx = np.empty((N, C, H, W), dtype=np.float64)
+    _load().oracle_conv_bwd_data(_p(dy), _p(w), _p(dx), N, C, H, W, K, R, S, stride, pad)
+    return dx
+
+
+def conv_bwd_filter(x, dy, R, S, stride, pad):
+    x, dy = _f64(x), _f64(dy)
+    N, C, H, W = x.shape
+    N2, K, P, Q = dy.shape
+    assert N == N2
+    assert P == out_extent(H, R, stride, pad) and Q == out_extent(W, S, stride, pad)
+    dw = np.empty((K, C, R, S), dtype=np.float64)
+    _load().oracle_conv_bwd_filter(_p(x), _p(dy), _p(dw), N, C, H, W, K, R, S, stride, pad)
+    return dw
+
+
+def _idx(idx):
+    return np.ascontiguousarray(np.asarray(idx, dtype=np.int64).ravel())
+
+
+def conv_fwd_at(x, w, stride, pad, idx):
+    """y.ravel()[idx] by the forward definition, one element at a time."""
+    x, w, idx = _f64(x), _f64(w), _idx(idx)
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    out = np.empty(idx.shape, dtype=np.float64)
+    _load().oracle_conv_fwd_at(_p(x), _p(w), N, C, H, W, K, R, S, stride, pad,
+                               idx.ctypes.data_as(_c_ip), idx.size, _p(out))
+    return out
+
+
+def conv_bwd_data_at(dy, w, H, W, stride, pad, idx):
+    """dx.ravel()[idx] by the backward-data definition, one element at a time."""
+    dy, w, idx = _f64(dy), _f64(w), _idx(idx)
+    N, K, _, _ = dy.shape
+    _, C, R, S = w.shape
+    out = np.empty(idx.shape, dtype=np.float64)
+    _load().oracle_conv_bwd_data_at(_p(dy), _p(w), N, C, H, W, K, R, S, stride, pad,
+                                    idx.ctypes.data_as(_c_ip), idx.size, _p(out))
+    return out
+
+
+def conv_bwd_filter_at(x, dy, R, S, stride, pad, idx):
+    """dw.ravel()[idx] by the backward-filter definition, one element at a time."""
+    x, dy, idx = _f64(x), _f64(dy), _idx(idx)
+    N, C, H, W = x.shape
+    _, K, _, _ = dy.shape
+    out = np.empty(idx.shape, dtype=np.float64)
+    _load().oracle_conv_bwd_filter_at(_p(x), _p(dy), N, C, H, W, K, R, S, stride, pad,
+                                      idx.ctypes.data_as(_c_ip), idx.size, _p(out))
+    return out
+
+
+def relu_fwd(x):
+    x = _f64(x)
+    y = np.empty_like(x)
+    _load().oracle_relu_fwd(_p(x), _p(y), x.size)
+    return y
+
+
+def relu_bwd(x, dy):
+    x, dy = _f64(x), _f64(dy)
+    dx = np.empty_like(x)
+    _load().oracle_relu_bwd(_p(x), _p(dy), _p(dx), x.size)
+    return dx
+
+
+def maxpool3x3s2_fwd(x, return_arg=False):
+    x = _f64(x)
+    N, C, H, W = x.shape
+    PH, PW = pool_extent(H), pool_extent(W)
+    y = np.empty((N, C, PH, PW), dtype=np.float64)
+    arg = np.empty((N, C, PH, PW), dtype=np.int32)
+    _load().oracle_maxpool3x3s2_fwd(_p(x), _p(y), arg.ctypes.data_as(_c_i32p), N * C, H, W)
+    return (y, arg) if return_arg else y
+
+
+def maxpool3x3s2_bwd(x, dy):
+    x, dy = _f64(x), _f64(dy)
+    N, C, H, W = x.shape
+    dx = np.empty_like(x)
+    _load().oracle_maxpool3x3s2_bwd(_p(x), _p(dy), _p(dx), N * C, H, W)
+    return dx

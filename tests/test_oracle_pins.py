@@ -1,0 +1,397 @@
+"""Pins of the CPU oracle against what the mathematics fixes.
+
+The paper prints no worked example, so every pin here is a closed form, an
+identity, a reduction to a textbook routine, a brute force in a different
+formulation, or a hand-worked fixture.  They are chosen so that a dropped
+term, a flipped filter, a wrong sign of the padding, a transposed index or a
+wrong output extent fails at least one of them.
+"""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1312_5853_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+SHAPES = [
+    # N, C, H, W, K, R, S, stride, pad
+    (2, 3, 7, 9, 4, 3, 3, 1, 1),
+    (1, 2, 8, 8, 3, 5, 5, 1, 2),
+    (2, 3, 11, 10, 2, 3, 2, 2, 1),
+    (1, 1, 23, 23, 2, 11, 11, 4, 2),     # first-layer geometry, floor in the extent
+    (3, 2, 6, 5, 3, 3, 3, 1, 0),
+    (1, 2, 5, 6, 2, 3, 3, 2, 3),         # pad >= R/2 and > 1
+    (2, 1, 9, 9, 1, 1, 1, 3, 0),
+]
+
+
+def extent(size, filt, stride, pad):
+    # written independently of the oracle's C helper
+    return (size + 2 * pad - filt) // stride + 1
+
+
+def rnd(shape, seed):
+    return synth.gaussian(shape, seed).astype(np.float64)
+
+
+# ---------------------------------------------------------------- fixture ---
+def test_handworked_fixture():
+    g = json.load(open(os.path.join(GOLDEN, "handworked_3x3.json")))
+    x, w, dy = (np.array(g[k], dtype=np.float64) for k in ("x", "w", "dy"))
+    a = g["stride1_pad0"]
+    np.testing.assert_array_equal(oracle.conv_fwd(x, w, 1, 0), np.array(a["y"], dtype=np.float64))
+    np.testing.assert_array_equal(oracle.conv_bwd_data(dy, w, 3, 3, 1, 0), np.array(a["dx"], dtype=np.float64))
+    np.testing.assert_array_equal(oracle.conv_bwd_filter(x, dy, 2, 2, 1, 0), np.array(a["dw"], dtype=np.float64))
+    b = g["stride2_pad1"]
+    np.testing.assert_array_equal(oracle.conv_fwd(x, w, 2, 1), np.array(b["y"], dtype=np.float64))
+
+
+def test_out_extent_values():
+    assert oracle.out_extent(224, 11, 4, 2) == 55       # floor of 217/4, plus 1
+    assert oracle.out_extent(27, 5, 1, 2) == 27
+    assert oracle.out_extent(13, 3, 1, 1) == 13
+    assert oracle.out_extent(32, 5, 1, 2) == 32
+    for h in (223, 224, 225, 226):
+        assert oracle.out_extent(h, 11, 4, 2) == 55
+    assert oracle.out_extent(227, 11, 4, 2) == 56
+    assert oracle.pool_extent(55) == 27 and oracle.pool_extent(27) == 13 and oracle.pool_extent(13) == 6
+
+
+# ------------------------------------------------------------ closed form ---
+@pytest.mark.parametrize("shape", SHAPES)
+def test_all_ones_closed_form(shape):
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = extent(H, R, st, pad), extent(W, S, st, pad)
+    cnt_r = np.array([sum(0 <= p * st - pad + r < H for r in range(R)) for p in range(P)])
+    cnt_s = np.array([sum(0 <= q * st - pad + s < W for s in range(S)) for q in range(Q)])
+    y = oracle.conv_fwd(np.ones((N, C, H, W)), np.ones((K, C, R, S)), st, pad)
+    assert y.shape == (N, K, P, Q)
+    np.testing.assert_array_equal(y, np.broadcast_to(C * np.outer(cnt_r, cnt_s), y.shape))
+
+    hit_h = np.array([sum(p * st - pad + r == h for p in range(P) for r in range(R)) for h in range(H)])
+    hit_w = np.array([sum(q * st - pad + s == v for q in range(Q) for s in range(S)) for v in range(W)])
+    dx = oracle.conv_bwd_data(np.ones((N, K, P, Q)), np.ones((K, C, R, S)), H, W, st, pad)
+    np.testing.assert_array_equal(dx, np.broadcast_to(K * np.outer(hit_h, hit_w), dx.shape))
+
+    val_r = np.array([sum(0 <= p * st - pad + r < H for p in range(P)) for r in range(R)])
+    val_s = np.array([sum(0 <= q * st - pad + s < W for q in range(Q)) for s in range(S)])
+    dw = oracle.conv_bwd_filter(np.ones((N, C, H, W)), np.ones((N, K, P, Q)), R, S, st, pad)
+    np.testing.assert_array_equal(dw, np.broadcast_to(N * np.outer(val_r, val_s), dw.shape))
+
+
+# --------------------------------------- brute force, different formulation ---
+def slices_fwd(x, w, st, pad):
+    """pad-and-slice formulation: one strided slab of the padded input per tap."""
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    P, Q = extent(H, R, st, pad), extent(W, S, st, pad)
+    xp = np.zeros((N, C, H + 2 * pad, W + 2 * pad))
+    xp[:, :, pad:pad + H, pad:pad + W] = x
+    y = np.zeros((N, K, P, Q))
+    for c in range(C):          # same (c, r, s) order as the definition so integer sums match exactly
+        for r in range(R):
+            for s in range(S):
+                slab = xp[:, c, r:r + st * (P - 1) + 1:st, s:s + st * (Q - 1) + 1:st]
+                y += slab[:, None, :, :] * w[None, :, c, r, s, None, None]
+    return y
+
+
+def gather_dgrad(dy, w, H, W, st, pad):
+    """gather formulation: each dx element collects the taps that reach it."""
+    N, K, P, Q = dy.shape
+    _, C, R, S = w.shape
+    dx = np.zeros((N, C, H, W))
+    for h in range(H):
+        for v in range(W):
+            for r in range(R):
+                for s in range(S):
+                    th, tv = h + pad - r, v + pad - s
+                    if th % st or tv % st:
+                        continue
+                    p, q = th // st, tv // st
+                    if 0 <= p < P and 0 <= q < Q:
+                        dx[:, :, h, v] += dy[:, :, p, q] @ w[:, :, r, s]
+    return dx
+
+
+def outer_wgrad(x, dy, R, S, st, pad):
+    """outer-product formulation: one K x C rank-1 update per (n, p, q, r, s)."""
+    N, C, H, W = x.shape
+    _, K, P, Q = dy.shape
+    dw = np.zeros((K, C, R, S))
+    for n, p, q in itertools.product(range(N), range(P), range(Q)):
+        for r in range(R):
+            for s in range(S):
+                h, v = p * st - pad + r, q * st - pad + s
+                if 0 <= h < H and 0 <= v < W:
+                    dw[:, :, r, s] += np.outer(dy[n, :, p, q], x[n, :, h, v])
+    return dw
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_brute_force_small_integers_bitwise(shape):
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = extent(H, R, st, pad), extent(W, S, st, pad)
+    x = synth.small_integers((N, C, H, W), 1).astype(np.float64)
+    w = synth.small_integers((K, C, R, S), 2).astype(np.float64)
+    dy = synth.small_integers((N, K, P, Q), 3).astype(np.float64)
+    np.testing.assert_array_equal(oracle.conv_fwd(x, w, st, pad), slices_fwd(x, w, st, pad))
+    np.testing.assert_array_equal(oracle.conv_bwd_data(dy, w, H, W, st, pad), gather_dgrad(dy, w, H, W, st, pad))
+    np.testing.assert_array_equal(oracle.conv_bwd_filter(x, dy, R, S, st, pad), outer_wgrad(x, dy, R, S, st, pad))
+
+
+# ------------------------------------------------------------------ deltas ---
+def test_delta_filter_is_a_shift():
+    N, C, H, W, R, S, pad = 2, 3, 6, 7, 3, 3, 1
+    x = rnd((N, C, H, W), 11)
+    for r0, s0 in itertools.product(range(R), range(S)):
+        w = np.zeros((C, C, R, S))
+        for c in range(C):
+            w[c, c, r0, s0] = 1.0
+        y = oracle.conv_fwd(x, w, 1, pad)
+        want = np.zeros_like(x)
+        for p in range(H):
+            for q in range(W):
+                h, v = p - pad + r0, q - pad + s0
+                if 0 <= h < H and 0 <= v < W:
+                    want[:, :, p, q] = x[:, :, h, v]
+        np.testing.assert_array_equal(y, want)
+        if (r0, s0) == (pad, pad):
+            np.testing.assert_array_equal(y, x)      # centre tap: identity, no flip either way
+    # an off-centre tap distinguishes correlation from flipped convolution
+    w = np.zeros((C, C, R, S))
+    for c in range(C):
+        w[c, c, 0, 2] = 1.0
+    y = oracle.conv_fwd(x, w, 1, pad)
+    assert y[0, 0, 2, 2] == x[0, 0, 1, 3]
+
+
+def test_delta_input_reads_out_the_filter():
+    C, H, W, K, R, S = 2, 12, 12, 3, 5, 5
+    w = rnd((K, C, R, S), 12)
+    for st, pad, (c0, h0, v0) in [(1, 2, (1, 5, 6)), (2, 2, (0, 6, 4)), (3, 0, (1, 7, 7))]:
+        x = np.zeros((1, C, H, W))
+        x[0, c0, h0, v0] = 1.0
+        y = oracle.conv_fwd(x, w, st, pad)
+        P, Q = y.shape[2:]
+        want = np.zeros_like(y)
+        for p in range(P):
+            for q in range(Q):
+                r, s = h0 + pad - p * st, v0 + pad - q * st
+                if 0 <= r < R and 0 <= s < S:
+                    want[0, :, p, q] = w[:, c0, r, s]
+        np.testing.assert_array_equal(y, want)
+
+
+# ----------------------------------------------------------------- adjoint ---
+@pytest.mark.parametrize("shape", SHAPES)
+def test_adjoint_identities(shape):
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = extent(H, R, st, pad), extent(W, S, st, pad)
+    x, w, g = rnd((N, C, H, W), 21), rnd((K, C, R, S), 22), rnd((N, K, P, Q), 23)
+    a = np.sum(oracle.conv_fwd(x, w, st, pad) * g)
+    b = np.sum(x * oracle.conv_bwd_data(g, w, H, W, st, pad))
+    c = np.sum(w * oracle.conv_bwd_filter(x, g, R, S, st, pad))
+    scale = np.sum(np.abs(oracle.conv_fwd(np.abs(x), np.abs(w), st, pad) * np.abs(g)))
+    assert abs(a - b) <= 1e-12 * scale
+    assert abs(a - c) <= 1e-12 * scale
+
+
+# ------------------------------------------------------ finite differences ---
+def test_finite_differences_every_element():
+    """L(x, w) = <conv(x, w), g> is bilinear, so a unit step in one coordinate
+    changes L by exactly that coordinate's gradient (no truncation error)."""
+    N, C, H, W, K, R, S, st, pad = 1, 2, 6, 5, 3, 3, 3, 2, 1
+    P, Q = extent(H, R, st, pad), extent(W, S, st, pad)
+    x, w, g = rnd((N, C, H, W), 31), rnd((K, C, R, S), 32), rnd((N, K, P, Q), 33)
+    L0 = np.sum(oracle.conv_fwd(x, w, st, pad) * g)
+    dx = oracle.conv_bwd_data(g, w, H, W, st, pad)
+    dw = oracle.conv_bwd_filter(x, g, R, S, st, pad)
+    for i in range(x.size):
+        xe = x.copy().ravel()
+        xe[i] += 1.0
+        L1 = np.sum(oracle.conv_fwd(xe.reshape(x.shape), w, st, pad) * g)
+        assert abs((L1 - L0) - dx.ravel()[i]) <= 1e-11 * (1 + abs(L0))
+    for i in range(w.size):
+        we = w.copy().ravel()
+        we[i] += 1.0
+        L1 = np.sum(oracle.conv_fwd(x, we.reshape(w.shape), st, pad) * g)
+        assert abs((L1 - L0) - dw.ravel()[i]) <= 1e-11 * (1 + abs(L0))
+
+
+def test_finite_differences_tiny_config_sampled():
+    L = synth.LAYERS["tiny"]
+    x, w, g = synth.layer_tensors("tiny", 4)
+    x, w, g = x.astype(np.float64), w.astype(np.float64), g.astype(np.float64)
+    st, pad = L["stride"], L["pad"]
+    dx = oracle.conv_bwd_data(g, w, L["H"], L["W"], st, pad)
+    dw = oracle.conv_bwd_filter(x, g, L["R"], L["S"], st, pad)
+    for i in synth.sample_indices(x.size, 12, 5):
+        e = np.zeros(x.size)
+        e[i] = 1.0
+        dL = np.sum(oracle.conv_fwd(e.reshape(x.shape), w, st, pad) * g)     # L(x+e) - L(x) by linearity
+        assert abs(dL - dx.ravel()[i]) <= 1e-12 * max(1.0, np.abs(dx).max())
+    for i in synth.sample_indices(w.size, 12, 6):
+        e = np.zeros(w.size)
+        e[i] = 1.0
+        dL = np.sum(oracle.conv_fwd(x, e.reshape(w.shape), st, pad) * g)
+        assert abs(dL - dw.ravel()[i]) <= 1e-12 * max(1.0, np.abs(dw).max())
+
+
+# --------------------------------------------- reductions to textbook ops ---
+def test_1x1_is_a_matrix_product():
+    N, C, H, W, K = 2, 5, 4, 3, 7
+    x, w = rnd((N, C, H, W), 41), rnd((K, C, 1, 1), 42)
+    y = oracle.conv_fwd(x, w, 1, 0)
+    for n in range(N):
+        want = w[:, :, 0, 0] @ x[n].reshape(C, H * W)
+        np.testing.assert_allclose(y[n].reshape(K, H * W), want, rtol=1e-13, atol=1e-13)
+    g = rnd(y.shape, 43)
+    dx = oracle.conv_bwd_data(g, w, H, W, 1, 0)
+    dw = oracle.conv_bwd_filter(x, g, 1, 1, 1, 0)
+    for n in range(N):
+        np.testing.assert_allclose(dx[n].reshape(C, H * W), w[:, :, 0, 0].T @ g[n].reshape(K, H * W),
+                                   rtol=1e-13, atol=1e-13)
+    want_dw = sum(g[n].reshape(K, H * W) @ x[n].reshape(C, H * W).T for n in range(N))
+    np.testing.assert_allclose(dw[:, :, 0, 0], want_dw, rtol=1e-13, atol=1e-13)
+
+
+def test_full_size_filter_is_a_dot_product():
+    N, C, H, W, K = 3, 2, 5, 4, 3
+    x, w = rnd((N, C, H, W), 44), rnd((K, C, H, W), 45)
+    y = oracle.conv_fwd(x, w, 1, 0)
+    assert y.shape == (N, K, 1, 1)
+    np.testing.assert_allclose(y[:, :, 0, 0], x.reshape(N, -1) @ w.reshape(K, -1).T, rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("st", [2, 3, 4])
+def test_stride_is_subsampled_stride_one(st):
+    N, C, H, W, K, R, S, pad = 2, 2, 13, 12, 3, 3, 5, 2
+    x, w = rnd((N, C, H, W), 46), rnd((K, C, R, S), 47)
+    y1 = oracle.conv_fwd(x, w, 1, pad)
+    ys = oracle.conv_fwd(x, w, st, pad)
+    np.testing.assert_array_equal(ys, y1[:, :, ::st, ::st][:, :, :ys.shape[2], :ys.shape[3]])
+    assert ys.shape[2] == extent(H, R, st, pad) and ys.shape[3] == extent(W, S, st, pad)
+
+
+# -------------------------------------------------- linearity, equivariance ---
+def test_linearity_and_shift():
+    N, C, H, W, K, R, S, st, pad = 2, 2, 8, 8, 3, 3, 3, 1, 1
+    x1, x2, w = rnd((N, C, H, W), 51), rnd((N, C, H, W), 52), rnd((K, C, R, S), 53)
+    lhs = oracle.conv_fwd(2.0 * x1 - 0.5 * x2, w, st, pad)
+    rhs = 2.0 * oracle.conv_fwd(x1, w, st, pad) - 0.5 * oracle.conv_fwd(x2, w, st, pad)
+    np.testing.assert_allclose(lhs, rhs, rtol=1e-12, atol=1e-12)
+    # one-pixel shift of an input whose border ring is zero shifts the output
+    x = np.zeros((1, C, 10, 10))
+    x[:, :, 3:7, 3:7] = rnd((1, C, 4, 4), 54)
+    xs = np.roll(x, (1, 1), axis=(2, 3))
+    y, ys = oracle.conv_fwd(x, w, 1, 1), oracle.conv_fwd(xs, w, 1, 1)
+    np.testing.assert_array_equal(np.roll(y, (1, 1), axis=(2, 3)), ys)
+
+
+# ------------------- the decompositions the paper's two schemes depend on ---
+def test_data_parallel_batch_split():
+    """Data parallelism: each GPU sees a slice of the mini-batch; activations and
+    input gradients are per sample, filter gradients add over the shards."""
+    N, C, H, W, K, R, S, st, pad = 4, 3, 9, 9, 4, 3, 3, 2, 1
+    P, Q = extent(H, R, st, pad), extent(W, S, st, pad)
+    x, w, g = rnd((N, C, H, W), 61), rnd((K, C, R, S), 62), rnd((N, K, P, Q), 63)
+    y = oracle.conv_fwd(x, w, st, pad)
+    np.testing.assert_array_equal(y[1:3], oracle.conv_fwd(x[1:3], w, st, pad))
+    dx = oracle.conv_bwd_data(g, w, H, W, st, pad)
+    np.testing.assert_array_equal(dx[3:], oracle.conv_bwd_data(g[3:], w, H, W, st, pad))
+    dw = oracle.conv_bwd_filter(x, g, R, S, st, pad)
+    parts = oracle.conv_bwd_filter(x[:1], g[:1], R, S, st, pad) + oracle.conv_bwd_filter(x[1:], g[1:], R, S, st, pad)
+    np.testing.assert_allclose(dw, parts, rtol=1e-13, atol=1e-13)
+
+
+def test_model_parallel_filter_split():
+    """Model parallelism: a layer's filters are split in two halves; outputs
+    concatenate over channels, input gradients add over the halves, and a
+    split of the input channels adds in the forward pass."""
+    N, C, H, W, K, R, S, st, pad = 2, 4, 7, 7, 6, 3, 3, 1, 1
+    x, w = rnd((N, C, H, W), 64), rnd((K, C, R, S), 65)
+    y = oracle.conv_fwd(x, w, st, pad)
+    g = rnd(y.shape, 66)
+    np.testing.assert_array_equal(y[:, :3], oracle.conv_fwd(x, w[:3], st, pad))
+    np.testing.assert_array_equal(y[:, 3:], oracle.conv_fwd(x, w[3:], st, pad))
+    dx = oracle.conv_bwd_data(g, w, H, W, st, pad)
+    halves = oracle.conv_bwd_data(g[:, :3], w[:3], H, W, st, pad) + oracle.conv_bwd_data(g[:, 3:], w[3:], H, W, st, pad)
+    np.testing.assert_allclose(dx, halves, rtol=1e-13, atol=1e-13)
+    dw = oracle.conv_bwd_filter(x, g, R, S, st, pad)
+    np.testing.assert_array_equal(dw[3:], oracle.conv_bwd_filter(x, g[:, 3:], R, S, st, pad))
+    yc = oracle.conv_fwd(x[:, :2], w[:, :2], st, pad) + oracle.conv_fwd(x[:, 2:], w[:, 2:], st, pad)
+    np.testing.assert_allclose(y, yc, rtol=1e-13, atol=1e-13)
+
+
+# ------------------------------------------------- element-wise entry points ---
+@pytest.mark.parametrize("shape", SHAPES)
+def test_elementwise_entry_points_match_full(shape):
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = extent(H, R, st, pad), extent(W, S, st, pad)
+    x, w, g = rnd((N, C, H, W), 71), rnd((K, C, R, S), 72), rnd((N, K, P, Q), 73)
+    y = oracle.conv_fwd(x, w, st, pad)
+    dx = oracle.conv_bwd_data(g, w, H, W, st, pad)
+    dw = oracle.conv_bwd_filter(x, g, R, S, st, pad)
+    iy = np.arange(y.size)
+    np.testing.assert_array_equal(oracle.conv_fwd_at(x, w, st, pad, iy), y.ravel())
+    np.testing.assert_array_equal(oracle.conv_bwd_filter_at(x, g, R, S, st, pad, np.arange(dw.size)), dw.ravel())
+    # the gather order differs from the scatter order: equal up to rounding only
+    np.testing.assert_allclose(oracle.conv_bwd_data_at(g, w, H, W, st, pad, np.arange(dx.size)), dx.ravel(),
+                               rtol=1e-12, atol=1e-13)
+    xi = synth.small_integers((N, C, H, W), 74)
+    wi = synth.small_integers((K, C, R, S), 75)
+    gi = synth.small_integers((N, K, P, Q), 76)
+    np.testing.assert_array_equal(oracle.conv_bwd_data_at(gi, wi, H, W, st, pad, np.arange(dx.size)),
+                                  gather_dgrad(gi.astype(np.float64), wi.astype(np.float64), H, W, st, pad).ravel())
+
+
+# -------------------------------------------------------------------- glue ---
+def test_relu():
+    x = np.array([-2.0, -0.0, 0.0, 1e-300, 3.0])
+    np.testing.assert_array_equal(oracle.relu_fwd(x), [0.0, 0.0, 0.0, 1e-300, 3.0])
+    np.testing.assert_array_equal(oracle.relu_bwd(x, np.full(5, 7.0)), [0.0, 0.0, 0.0, 7.0, 7.0])
+
+
+def test_maxpool_brute_force_and_ties():
+    x = rnd((2, 3, 13, 11), 81)
+    y, arg = oracle.maxpool3x3s2_fwd(x, return_arg=True)
+    assert y.shape == (2, 3, 6, 5)
+    for i in range(6):
+        for j in range(5):
+            win = x[:, :, 2 * i:2 * i + 3, 2 * j:2 * j + 3].reshape(2, 3, 9)
+            np.testing.assert_array_equal(y[:, :, i, j], win.max(axis=2))
+            a = win.argmax(axis=2)                       # numpy: first maximum
+            np.testing.assert_array_equal(arg[:, :, i, j], (2 * i + a // 3) * 11 + (2 * j + a % 3))
+    g = rnd(y.shape, 82)
+    dx = oracle.maxpool3x3s2_bwd(x, g)
+    want = np.zeros_like(x)
+    for n, c, i, j in itertools.product(range(2), range(3), range(6), range(5)):
+        a = arg[n, c, i, j]
+        want[n, c, a // 11, a % 11] += g[n, c, i, j]
+    np.testing.assert_array_equal(dx, want)
+    assert abs(dx.sum() - g.sum()) < 1e-12
+    # all-equal window: the first element in row-major order takes the gradient
+    z = np.zeros((1, 1, 3, 3))
+    dz = oracle.maxpool3x3s2_bwd(z, np.ones((1, 1, 1, 1)))
+    assert dz[0, 0, 0, 0] == 1.0 and dz.sum() == 1.0
+    # overlapping windows sharing one maximum accumulate
+    z = np.zeros((1, 1, 5, 5))
+    z[0, 0, 2, 2] = 9.0
+    dz = oracle.maxpool3x3s2_bwd(z, np.ones((1, 1, 2, 2)))
+    assert dz[0, 0, 2, 2] == 4.0
+
+
+def test_oracle_does_not_import_the_product():
+    import subprocess
+    import sys
+    code = ("import sys, oracle; "
+            "bad=[m for m in sys.modules if m.startswith('paper_1312_5853_amd')]; "
+            "sys.exit(1 if bad else 0)")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    assert subprocess.run([sys.executable, "-c", code], cwd=root).returncode == 0
