@@ -1,0 +1,165 @@
+/*
+ * convnet_hotpath.h -- C ABI of the MI355X (gfx950) convolution hot path.
+ *
+ * The library computes the three passes of a convolutional layer that dominate
+ * a synchronous-SGD training step of the ConvNet studied in "Multi-GPU
+ * Training of ConvNets" (arXiv 1312.5853): the forward pass (a layer's filters
+ * convolve its input -- model-parallelism paragraph), and the two halves of
+ * back-propagation through it (gradients with respect to the layer input and
+ * with respect to all filter parameters -- optimisation and data-parallelism
+ * paragraphs).  One call handles one GPU's share: a data-parallel mini-batch
+ * shard, or one model-parallel column (a subset of filters and channels).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Layout: activations NCHW, filters KCRS, dense and contiguous unless a
+ *    batch stride is given.  x, dx: [N][C][H][W];  w, dw: [K][C][R][S];
+ *    y, dy: [N][K][P][Q] with P = floor((H + 2*pad - R)/stride) + 1 and Q
+ *    likewise from W and S.  H and W are ALWAYS the layer's input extent, in all
+ *    three passes (with stride > 1 they cannot be recovered from P and Q).
+ *    One stride and one symmetric zero padding for both axes; no dilation, no
+ *    groups, no bias, no filter flip (cross-correlation).
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *    never allocates, frees or keeps them.  Scratch memory comes from the `ws`
+ *    argument (device pointer, 256-byte aligned, at least
+ *    conv_workspace_bytes() bytes); its contents are undefined afterwards.
+ *  - Outputs are fully overwritten (no accumulation into the destination, every
+ *    element written -- dx positions that no window touches receive 0).
+ *  - dtype: CONV_DTYPE_F32  = fp32 tensors, fp32 MFMA arithmetic.
+ *           CONV_DTYPE_BF16 = x, w, dy hold bfloat16 (2 bytes, already rounded
+ *           by the caller); products accumulate in fp32; outputs (y, dx, dw)
+ *           are fp32.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Work is enqueued; returning does not imply completion.  Calls on one
+ *    stream that share a workspace are ordered by the stream; calls on
+ *    different streams must not share a workspace.
+ *  - Results are bit-for-bit reproducible from run to run (fixed reduction
+ *    order, no floating-point atomics).
+ *  - Return value: CONV_OK or a negative conv_status.  All argument checks run
+ *    on the host before any GPU call; nothing is enqueued when a call fails a
+ *    check.  No C++ exception crosses this boundary.
+ *  - Limits: every tensor (including batch-strided spans) must occupy fewer
+ *    than 2^31 bytes; tensor base pointers must be 16-byte aligned.
+ */
+#ifndef CONVNET_HOTPATH_H
+#define CONVNET_HOTPATH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum conv_status {
+    CONV_OK = 0,
+    CONV_ERR_INVALID_ARG = -1,         /* null pointer, non-positive extent, stride <= 0, pad < 0, P or Q <= 0,
+                                          batch stride smaller than one sample */
+    CONV_ERR_TOO_LARGE = -2,           /* a tensor span reaches 2^31 bytes */
+    CONV_ERR_BAD_DTYPE = -3,
+    CONV_ERR_WORKSPACE_TOO_SMALL = -4, /* ws is NULL or ws_bytes < conv_workspace_bytes() while scratch is needed */
+    CONV_ERR_MISALIGNED = -5,          /* tensor base not 16-byte aligned, or ws not 256-byte aligned */
+    CONV_ERR_HIP = -6                  /* the HIP runtime refused a launch; hipGetLastError() text via conv_last_hip_error() */
+} conv_status;
+
+enum { CONV_DTYPE_F32 = 0, CONV_DTYPE_BF16 = 1 };
+enum { CONV_OP_FWD = 0, CONV_OP_BWD_DATA = 1, CONV_OP_BWD_FILTER = 2 };
+
+/*
+ * Forward pass of a convolutional layer (the layer's K filters convolve its
+ * input; model-parallelism paragraph):
+ *   y[n,k,p,q] = sum_{c,r,s} x[n,c,p*stride-pad+r,q*stride-pad+s] * w[k,c,r,s]
+ * with x read as zero outside its extent.
+ *   x  in   device, [N][C][H][W]
+ *   w  in   device, [K][C][R][S]
+ *   y  out  device, [N][K][P][Q], fp32
+ */
+int conv_fwd(const void *x, const void *w, void *y,
+             int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+             int dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Backward-data pass (back-propagation of the error to the layer input;
+ * optimisation paragraph):
+ *   dx[n,c,h,w] = sum over (k,p,q,r,s) with p*stride-pad+r = h and
+ *                 q*stride-pad+s = w of dy[n,k,p,q] * w[k,c,r,s]
+ *   dy in   device, [N][K][P][Q]
+ *   w  in   device, [K][C][R][S]
+ *   dx out  device, [N][C][H][W], fp32
+ */
+int conv_bwd_data(const void *dy, const void *w, void *dx,
+                  int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                  int dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Backward-filter pass (gradient with respect to all filter parameters from
+ * this GPU's subset of the samples; data-parallelism paragraph):
+ *   dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x[n,c,p*stride-pad+r,q*stride-pad+s]
+ *   x  in   device, [N][C][H][W]
+ *   dy in   device, [N][K][P][Q]
+ *   dw out  device, [K][C][R][S], fp32 (this shard's sum; adding the shards of
+ *           a data-parallel step is the caller's all-reduce)
+ */
+int conv_bwd_filter(const void *x, const void *dy, void *dw,
+                    int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                    int dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Batch-strided variants: sample n of the activation tensor on the layer's
+ * input side (x / dx) starts x_batch_stride ELEMENTS after sample n-1, and
+ * likewise y_batch_stride for the output side (y / dy); within a sample the
+ * [channel][row][col] block is dense.  They let one model-parallel column read
+ * and write a channel slice of a wider NCHW tensor in place (the two-column
+ * architecture of the model-parallelism paragraph).  Strides must be at least
+ * one sample (C*H*W resp. K*P*Q); 0 means dense.
+ */
+int conv_fwd_ex(const void *x, const void *w, void *y,
+                int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                int64_t x_batch_stride, int64_t y_batch_stride,
+                int dtype, void *ws, size_t ws_bytes, void *stream);
+int conv_bwd_data_ex(const void *dy, const void *w, void *dx,
+                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                     int64_t x_batch_stride, int64_t y_batch_stride,
+                     int dtype, void *ws, size_t ws_bytes, void *stream);
+int conv_bwd_filter_ex(const void *x, const void *dy, void *dw,
+                       int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                       int64_t x_batch_stride, int64_t y_batch_stride,
+                       int dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Scratch bytes the given pass needs for these extents (op = CONV_OP_*).
+ * Pure host arithmetic; returns 0 for invalid arguments.  The figure depends
+ * only on the arguments, never on the device or on earlier calls.
+ */
+size_t conv_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int S,
+                            int stride, int pad, int dtype);
+
+/* Static, NUL-terminated description of a conv_status value. */
+const char *conv_status_string(int status);
+
+/* Text of the HIP error behind the calling thread's last CONV_ERR_HIP ("" if none). */
+const char *conv_last_hip_error(void);
+
+/*
+ * Glue layers between the convolutions of the five-layer stack (they belong to
+ * the Krizhevsky architecture the paper trains; the paper's text does not
+ * spell them out).  fp32 tensors, device pointers, 4-byte aligned, fully
+ * overwritten outputs, same stream and error conventions as above.
+ *
+ *   relu_fwd:  y[i]  = x[i] > 0 ? x[i] : 0                     (y may alias x)
+ *   relu_bwd:  dx[i] = x[i] > 0 ? dy[i] : 0   (x = forward input or output; dx may alias dy)
+ *   maxpool3x3s2_fwd: per plane, y[i,j] = max of the 3x3 window at (2i, 2j); no padding;
+ *                     output extent floor((H-3)/2)+1 per axis; `planes` = N*C.
+ *   maxpool3x3s2_bwd: dx = 0, then every dy[i,j] is added to the window element the
+ *                     forward pass selected (first maximum in row-major window order);
+ *                     overlapping windows accumulate in a fixed order.
+ */
+int relu_fwd(const void *x, void *y, int64_t count, void *stream);
+int relu_bwd(const void *x, const void *dy, void *dx, int64_t count, void *stream);
+int maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream);
+int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONVNET_HOTPATH_H */

@@ -1,0 +1,227 @@
+"""ctypes binding of ``libconvnet_hotpath.so`` (see ``include/convnet_hotpath.h``).
+
+Argument marshalling only: every function here hands device pointers, extents
+and a HIP stream to the C ABI entry point of the same name.  PyTorch supplies
+device memory and streams; no arithmetic of the convolution path happens in
+Python.  If the library has not been built this module raises -- there is no
+fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconvnet_hotpath.so")
+
+OK = 0
+ERR_INVALID_ARG, ERR_TOO_LARGE, ERR_BAD_DTYPE, ERR_WORKSPACE, ERR_MISALIGNED, ERR_HIP = -1, -2, -3, -4, -5, -6
+DTYPE_F32, DTYPE_BF16 = 0, 1
+OP_FWD, OP_BWD_DATA, OP_BWD_FILTER = 0, 1, 2
+
+EXPORTS = (
+    "conv_fwd", "conv_bwd_data", "conv_bwd_filter",
+    "conv_fwd_ex", "conv_bwd_data_ex", "conv_bwd_filter_ex",
+    "conv_workspace_bytes", "conv_status_string", "conv_last_hip_error",
+    "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
+)
+
+_lib = None
+
+
+class ConvError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().conv_status_string(status).decode()
+        if status == ERR_HIP:
+            msg += ": " + lib().conv_last_hip_error().decode()
+        super().__init__("%s failed with status %d (%s)" % (where, status, msg))
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            "%s is missing: build it with `python -m paper_1312_5853_amd.build` "
+            "(there is no fallback implementation)" % LIB_PATH)
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t
+    dims = [i] * 9
+    for name in ("conv_fwd", "conv_bwd_data", "conv_bwd_filter"):
+        f = getattr(L, name)
+        f.argtypes = [vp, vp, vp] + dims + [i, vp, sz, vp]
+        f.restype = i
+        f = getattr(L, name + "_ex")
+        f.argtypes = [vp, vp, vp] + dims + [i64, i64, i, vp, sz, vp]
+        f.restype = i
+    L.conv_workspace_bytes.argtypes = [i] + dims + [i]
+    L.conv_workspace_bytes.restype = sz
+    L.conv_status_string.argtypes = [i]
+    L.conv_status_string.restype = ctypes.c_char_p
+    L.conv_last_hip_error.argtypes = []
+    L.conv_last_hip_error.restype = ctypes.c_char_p
+    L.relu_fwd.argtypes = [vp, vp, i64, vp]
+    L.relu_bwd.argtypes = [vp, vp, vp, i64, vp]
+    L.maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, vp]
+    L.maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, vp]
+    for name in ("relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd"):
+        getattr(L, name).restype = i
+    _lib = L
+    return L
+
+
+def status_string(status):
+    return lib().conv_status_string(int(status)).decode()
+
+
+def workspace_bytes(op, N, C, H, W, K, R, S, stride, pad, dtype=DTYPE_F32):
+    return int(lib().conv_workspace_bytes(op, N, C, H, W, K, R, S, stride, pad, dtype))
+
+
+def _stream_handle(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _dtype_of(t):
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    raise TypeError("unsupported tensor dtype %s" % t.dtype)
+
+
+def out_extent(size, filt, stride, pad):
+    return (size + 2 * pad - filt) // stride + 1
+
+
+class Workspace:
+    """A growable device scratch buffer handed to the library as `ws`."""
+
+    def __init__(self, device="cuda"):
+        self.device = device
+        self.buf = None
+
+    def get(self, nbytes):
+        if nbytes == 0:
+            return None, 0
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        return self.buf, self.buf.numel()
+
+
+_default_ws = None
+
+
+def _ws(ws):
+    global _default_ws
+    if ws is not None:
+        return ws
+    if _default_ws is None:
+        _default_ws = Workspace()
+    return _default_ws
+
+
+def _run(name, op, a, b, out, dims, x_bs, y_bs, dtype, ws, stream):
+    need = workspace_bytes(op, *dims, dtype)
+    buf, nbytes = _ws(ws).get(need)
+    wsp = ctypes.c_void_p(buf.data_ptr()) if buf is not None else ctypes.c_void_p(0)
+    if x_bs or y_bs:
+        rc = getattr(lib(), name + "_ex")(_ptr(a), _ptr(b), _ptr(out), *dims, int(x_bs), int(y_bs), dtype,
+                                          wsp, nbytes, _stream_handle(stream))
+    else:
+        rc = getattr(lib(), name)(_ptr(a), _ptr(b), _ptr(out), *dims, dtype, wsp, nbytes, _stream_handle(stream))
+    if rc != OK:
+        raise ConvError(rc, name)
+    return out
+
+
+def _batch_stride(t):
+    """Batch stride in elements of an NCHW tensor whose samples are dense (a
+    channel slice of a wider tensor qualifies); 0 when the whole tensor is."""
+    n, c, h, w = t.shape
+    if t.stride(3) != 1 or t.stride(2) != w or t.stride(1) != h * w:
+        raise ValueError("the [channel][row][col] block of every sample must be dense")
+    return 0 if (n == 1 or t.stride(0) == c * h * w) else t.stride(0)
+
+
+def conv_fwd(x, w, stride, pad, y=None, ws=None, stream=None):
+    """x [N,C,H,W], w [K,C,R,S] -> y [N,K,P,Q] fp32.  x and y may be channel
+    slices of wider NCHW tensors (their batch strides are passed on)."""
+    N, C, H, W = x.shape
+    K, Cw, R, S = w.shape
+    if C != Cw or not w.is_contiguous():
+        raise ValueError("filter tensor does not match the input")
+    P, Q = out_extent(H, R, stride, pad), out_extent(W, S, stride, pad)
+    if y is None:
+        y = torch.empty((N, K, P, Q), dtype=torch.float32, device=x.device)
+    dims = (N, C, H, W, K, R, S, stride, pad)
+    return _run("conv_fwd", OP_FWD, x, w, y, dims, _batch_stride(x), _batch_stride(y), _dtype_of(x), ws, stream)
+
+
+def conv_bwd_data(dy, w, H, W, stride, pad, dx=None, ws=None, stream=None):
+    """dy [N,K,P,Q], w [K,C,R,S] -> dx [N,C,H,W] fp32 (H, W: the layer's input extent)."""
+    N = dy.shape[0]
+    K, C, R, S = w.shape
+    if dy.shape[1] != K or not w.is_contiguous():
+        raise ValueError("filter tensor does not match the output gradient")
+    if dx is None:
+        dx = torch.empty((N, C, H, W), dtype=torch.float32, device=dy.device)
+    dims = (N, C, H, W, K, R, S, stride, pad)
+    return _run("conv_bwd_data", OP_BWD_DATA, dy, w, dx, dims, _batch_stride(dx), _batch_stride(dy), _dtype_of(dy),
+                ws, stream)
+
+
+def conv_bwd_filter(x, dy, R, S, stride, pad, dw=None, ws=None, stream=None):
+    """x [N,C,H,W], dy [N,K,P,Q] -> dw [K,C,R,S] fp32."""
+    N, C, H, W = x.shape
+    K = dy.shape[1]
+    if dw is None:
+        dw = torch.empty((K, C, R, S), dtype=torch.float32, device=x.device)
+    dims = (N, C, H, W, K, R, S, stride, pad)
+    return _run("conv_bwd_filter", OP_BWD_FILTER, x, dy, dw, dims, _batch_stride(x), _batch_stride(dy),
+                _dtype_of(x), ws, stream)
+
+
+def _check(rc, where):
+    if rc != OK:
+        raise ConvError(rc, where)
+
+
+def relu_fwd(x, y=None, stream=None):
+    if y is None:
+        y = torch.empty_like(x)
+    _check(lib().relu_fwd(_ptr(x), _ptr(y), x.numel(), _stream_handle(stream)), "relu_fwd")
+    return y
+
+
+def relu_bwd(x, dy, dx=None, stream=None):
+    if dx is None:
+        dx = torch.empty_like(dy)
+    _check(lib().relu_bwd(_ptr(x), _ptr(dy), _ptr(dx), x.numel(), _stream_handle(stream)), "relu_bwd")
+    return dx
+
+
+def maxpool3x3s2_fwd(x, y=None, stream=None):
+    N, C, H, W = x.shape
+    if y is None:
+        y = torch.empty((N, C, (H - 3) // 2 + 1, (W - 3) // 2 + 1), dtype=x.dtype, device=x.device)
+    _check(lib().maxpool3x3s2_fwd(_ptr(x), _ptr(y), N * C, H, W, _stream_handle(stream)), "maxpool3x3s2_fwd")
+    return y
+
+
+def maxpool3x3s2_bwd(x, dy, dx=None, stream=None):
+    N, C, H, W = x.shape
+    if dx is None:
+        dx = torch.empty_like(x)
+    _check(lib().maxpool3x3s2_bwd(_ptr(x), _ptr(dy), _ptr(dx), N * C, H, W, _stream_handle(stream)),
+           "maxpool3x3s2_bwd")
+    return dx

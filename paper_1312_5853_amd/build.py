@@ -1,0 +1,50 @@
+"""Builds the C-ABI shared library from ``csrc/`` with hipcc for gfx950.
+
+Run as ``python -m paper_1312_5853_amd.build``; the library lands next to this
+file as ``libconvnet_hotpath.so`` (kept out of version control).
+"""
+import os
+import subprocess
+import sys
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(_HERE, "csrc", "convnet_hotpath.hip")
+LIB = os.path.join(_HERE, "libconvnet_hotpath.so")
+DEPS = [SRC, os.path.join(_HERE, "csrc", "plan.h"), os.path.join(_HERE, "csrc", "fastdiv.h"),
+        os.path.join(os.path.dirname(_HERE), "include", "convnet_hotpath.h")]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-Wall",
+    # no packed-fp32 instruction selection
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+]
+
+
+def is_stale():
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(d) > t for d in DEPS)
+
+
+def build(keep_temps_dir=None, verbose=False):
+    """Compile unconditionally.  keep_temps_dir: directory for the ISA listing."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB, SRC]
+    cwd = None
+    if keep_temps_dir:
+        os.makedirs(keep_temps_dir, exist_ok=True)
+        cmd.insert(1, "-save-temps")
+        cwd = keep_temps_dir
+    res = subprocess.run(cmd, cwd=cwd, capture_output=True, text=True)
+    err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
+    if verbose or res.returncode != 0:
+        sys.stderr.write(err + "\n")
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + err)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(keep_temps_dir=os.environ.get("CONVNET_KEEP_TEMPS"), verbose=True)
+    print(LIB)

@@ -1,0 +1,800 @@
+// HIP kernels (gfx950 / CDNA4) and C-ABI entry points of the convolution hot
+// path: forward, backward-data and backward-filter of a convolutional layer as
+// implicit GEMMs on the fp32 matrix cores, plus the ReLU / max-pool glue of
+// the five-layer stack.  Signatures and conventions are documented in
+// include/convnet_hotpath.h.
+//
+// GEMM views (NCHW activations, KCRS filters, P x Q output extent):
+//   forward         y  [K      x N*P*Q] = w  [K x C*R*S]  *  im2col(x)  [C*R*S x N*P*Q]
+//   backward-data   dx [C      x N*H*W] = w' [C x K*R*S]  *  col2im-gather(dy)
+//   backward-filter dw [K      x C*R*S] = dy [K x N*P*Q]  *  im2col(x)^T, split over N*P*Q
+// The im2col matrices are never materialised in HBM: each work-group gathers
+// the 16-deep slice it needs straight from the NCHW tensor into LDS.
+#include <hip/hip_runtime.h>
+
+#include <stdio.h>
+#include <string.h>
+
+#include "../../include/convnet_hotpath.h"
+#include "plan.h"
+
+using namespace convnet;
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kThreads = 256;        // 4 wavefronts of 64
+constexpr int kPitch = kChunk + 4;   // LDS row pitch (floats): 16 lanes x b128 cover all 64 banks once
+constexpr int kInvalidTap = -(1 << 29);
+
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// ---------------------------------------------------------------------------
+// Preparation: tap table and filter re-layout (tiny, one launch per call)
+// ---------------------------------------------------------------------------
+//
+// Tap table: entry g of the reduction index (channel-like index a, filter row
+// r, filter column s) holds {offset, dr, ds, 0}: the BYTE offset (fp32 elements) added to a
+// column's base address and the row / column displacement whose bounds decide
+// whether the tap reads data or padding.
+//   sign = +1 (forward, backward-filter): a = input channel c; reads
+//            x[c][hb + r][wb + s]
+//   sign = -1 (backward-data): a = filter k; reads dy[k][hb - r][wb - s]
+// With row_pitch = col_pitch = 0 the offset names the plane only (strided
+// backward-data computes the in-plane position itself).
+// Entries past `len` are marked so that their bounds test always fails.
+__global__ void build_tap_table(int4 *__restrict__ tab, int tab_len, int len, int RS, int S,
+                                int plane, int row_pitch, int col_pitch, int sign)
+{
+    int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= tab_len) return;
+    int4 e;
+    if (g < len) {
+        int a = g / RS, rs = g - a * RS;
+        int r = rs / S, s = rs - r * S;
+        e.x = 4 * (a * plane + sign * (r * row_pitch + s * col_pitch));
+        e.y = sign * r;
+        e.z = sign * s;
+        e.w = 0;
+    } else {
+        e.x = 0; e.y = kInvalidTap; e.z = kInvalidTap; e.w = 0;
+    }
+    tab[g] = e;
+}
+
+// Filters re-laid-out as wt[chunk][Mpad][16] (zero padded): the 16-deep slice a
+// work-group stages per step is one contiguous block.
+//   transposed = 0: row m = filter k,  reduction index g = (c, r, s)
+//   transposed = 1: row m = channel c, reduction index g = (k, r, s)
+__global__ void relayout_filters(const float *__restrict__ w, float *__restrict__ wt,
+                                 int M, int Mpad, int Kg, int Kgpad, int C, int RS, int transposed)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)Mpad * Kgpad;
+    if (i >= total) return;
+    int e = (int)(i % kChunk);
+    int64_t t = i / kChunk;
+    int m = (int)(t % Mpad);
+    int chunk = (int)(t / Mpad);
+    int g = chunk * kChunk + e;
+    float v = 0.f;
+    if (m < M && g < Kg) {
+        if (!transposed) {
+            v = w[(int64_t)m * Kg + g];
+        } else {
+            int k = g / RS, rs = g - k * RS;
+            v = w[((int64_t)k * C + m) * RS + rs];
+        }
+    }
+    wt[i] = v;
+}
+
+__global__ void widen_bf16(const unsigned short *__restrict__ src, float *__restrict__ dst, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = __uint_as_float((unsigned)src[i] << 16);
+}
+
+// ---------------------------------------------------------------------------
+// Shared inner product: one 16-deep step of the work-group tile from LDS
+// ---------------------------------------------------------------------------
+//
+// LDS tiles are [row][16] with pitch kPitch.  v_mfma_f32_32x32x2_f32 takes, per
+// lane, A[row = lane%32][k = lane/32] and B[k = lane/32][col = lane%32].  The 16
+// reduction elements of a step are fed in the order (t, 8+t), t = 0..7, so the
+// lower half-wave reads elements 0..7 and the upper half 8..15 of its row: two
+// b128 reads per 32-row tile.  Any order works as long as A and B agree.
+template <int TM, int TN>
+__device__ __forceinline__ void mma_step(const float *__restrict__ As, const float *__restrict__ Bs,
+                                         int a_row0, int b_row0, int lane, f32x16 (&acc)[TM][TN])
+{
+    const int l32 = lane & 31, half = lane >> 5;
+    f32x4 a[TM][2], b[TN][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const f32x4 *p = reinterpret_cast<const f32x4 *>(As + (a_row0 + i * 32 + l32) * kPitch + half * 8);
+        a[i][0] = p[0];
+        a[i][1] = p[1];
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const f32x4 *p = reinterpret_cast<const f32x4 *>(Bs + (b_row0 + j * 32 + l32) * kPitch + half * 8);
+        b[j][0] = p[0];
+        b[j][1] = p[1];
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][t >> 2][t & 3], b[j][t >> 2][t & 3],
+                                                                 acc[i][j], 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------
+// Forward and backward-data: out[n][m][oh][ow] = sum_g A[m][g] * gather(g; n, oh, ow)
+// ---------------------------------------------------------------------------
+struct ColGemmArgs {
+    const float *At;      // re-laid-out filters [chunks][Mpad][16]
+    const int4 *tab;      // tap table
+    const float *src;     // gathered tensor (x or dy)
+    float *dst;           // y or dx
+    int M, Mpad, nchunks;
+    int OH, OW;           // extent the GEMM columns enumerate (with n): P,Q or H,W
+    int LH, LW;           // extent of the gathered tensor's planes
+    int ncols;            // N*OH*OW
+    int src_bs, dst_bs;   // batch strides in elements
+    int mul, add;         // window origin: hb = oh*mul + add, wb = ow*mul + add
+    int mtiles, ntiles;
+    FastDiv div_plane, div_ow, div_stride;
+};
+
+enum { kGatherDirect = 0, kGatherStridedBwd = 1 };
+
+template <int TM, int TN, int WM, int WN, int GATHER>
+__global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int EPT = BN / 16;             // gathered elements per thread per step
+    constexpr int A4 = BM * 4;               // float4 loads of the filter slice per step
+    constexpr int A4T = (A4 + kThreads - 1) / kThreads;
+    static_assert(WM * WN == 4, "four waves per work-group");
+    static_assert(BN >= 64 && (kThreads % BN == 0 || BN % kThreads == 0), "column roles");
+
+    __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
+
+    // Work-groups are dealt round-robin to the 8 XCDs; give each XCD whole
+    // column tiles (all row tiles of a column tile share its gathered slice
+    // through that XCD's L2).
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, loc = bid >> 3;
+    const int mt = loc % p.mtiles;
+    const int nt = (loc / p.mtiles) * 8 + xcd;
+    if (nt >= p.ntiles) return;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // --- gather role: one fixed GEMM column per thread, EPT taps of each step
+    const int jc = tid % BN;
+    const int grp = uniform(tid / BN);       // which EPT-wide part of the 16 taps
+    const int j = n0 + jc;
+    int hb, wb, base;
+    {
+        const bool colok = j < p.ncols;
+        const int jj = colok ? j : 0;
+        const int n = (int)fastdiv((uint32_t)jj, p.div_plane);
+        const int rem = jj - n * (p.OH * p.OW);
+        const int oh = (int)fastdiv((uint32_t)rem, p.div_ow);
+        const int ow = rem - oh * p.OW;
+        hb = oh * p.mul + p.add;
+        wb = ow * p.mul + p.add;
+        if (GATHER == kGatherDirect) base = 4 * (n * p.src_bs + hb * p.LW + wb);   // bytes
+        else base = 4 * (n * p.src_bs);
+        if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
+    }
+
+    f32x4 areg[A4T];
+    float breg[EPT];
+    bool bok[EPT];
+    const char *src_bytes = reinterpret_cast<const char *>(p.src);
+
+    auto load_step = [&](int chunk) {
+        const f32x4 *ablk = reinterpret_cast<const f32x4 *>(p.At + ((size_t)chunk * p.Mpad + m0) * kChunk);
+#pragma unroll
+        for (int i = 0; i < A4T; ++i) {
+            int idx = tid + i * kThreads;
+            if (A4 % kThreads == 0 || idx < A4) areg[i] = ablk[idx];
+        }
+        const int4 *t = p.tab + chunk * kChunk + grp * EPT;
+        int4 tap[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) tap[e] = t[e];      // wave-uniform: scalar loads
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) {
+            bool ok;
+            int off;
+            if (GATHER == kGatherDirect) {
+                const int hh = hb + tap[e].y, ww = wb + tap[e].z;
+                ok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+                off = base + tap[e].x;
+            } else {
+                // backward-data with stride > 1: output row h receives tap r only
+                // from the window row (h + pad - r)/stride, when that divides
+                const int th = hb + tap[e].y, tw = wb + tap[e].z;
+                ok = (th >= 0) & (tw >= 0);
+                const int ph = (int)fastdiv((uint32_t)(ok ? th : 0), p.div_stride);
+                const int qw = (int)fastdiv((uint32_t)(ok ? tw : 0), p.div_stride);
+                ok = ok & (ph * (int)p.div_stride.d == th) & (qw * (int)p.div_stride.d == tw) &
+                     (ph < p.LH) & (qw < p.LW);
+                off = base + tap[e].x + 4 * (ph * p.LW + qw);
+            }
+            // the load is always issued (address 0 when the tap is padding); the
+            // zero is substituted when the value is consumed, after the MFMAs
+            breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(ok ? off : 0));
+            bok[e] = ok;
+        }
+    };
+
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A4T; ++i) {
+            int idx = tid + i * kThreads;
+            if (A4 % kThreads == 0 || idx < A4)
+                *reinterpret_cast<f32x4 *>(&As[buf][(idx >> 2) * kPitch + (idx & 3) * 4]) = areg[i];
+        }
+        float *brow = &Bs[buf][jc * kPitch + grp * EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; e += 4) {
+            f32x4 v = {bok[e] ? breg[e] : 0.f, bok[e + 1] ? breg[e + 1] : 0.f, bok[e + 2] ? breg[e + 2] : 0.f,
+                       bok[e + 3] ? breg[e + 3] : 0.f};
+            *reinterpret_cast<f32x4 *>(brow + e) = v;
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    load_step(0);
+    store_step(0);
+    __syncthreads();
+    for (int chunk = 0; chunk < p.nchunks; ++chunk) {
+        const int buf = chunk & 1;
+        const bool more = chunk + 1 < p.nchunks;
+        if (more) load_step(chunk + 1);
+        mma_step<TM, TN>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
+        if (more) store_step(buf ^ 1);
+        __syncthreads();
+    }
+
+    // --- epilogue.  Accumulator register v of lane l holds row
+    // 8*(v/4) + 4*(l/32) + v%4 and column l%32 of its 32 x 32 tile.
+    const int l32 = lane & 31, half = lane >> 5;
+    const int plane = p.OH * p.OW;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+        const int n = (int)fastdiv((uint32_t)col, p.div_plane);
+        const int rem = col - n * plane;
+        float *out = p.dst + (size_t)n * p.dst_bs + rem;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.M) out[(size_t)row * plane] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Backward-filter: dw[k][g] = sum_j dy[k][j] * im2col(x)[g][j],  j = (n, p, q)
+// ---------------------------------------------------------------------------
+struct WgradArgs {
+    const float *dy;
+    const float *x;
+    const int4 *tab;      // forward-style tap table over g = (c, r, s)
+    float *out;           // dw, or partial sums [split][K][CRS]
+    int K, CRS;
+    int P, Q, H, W, stride, pad;
+    int dy_bs, x_bs;
+    int J;                // N*P*Q
+    int chunks_per_split;
+    int mtiles, ntiles;
+    FastDiv div_plane, div_q;
+};
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int RA = BM / 16, RB = BN / 16;    // rows per thread per step
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
+
+    const int tiles = p.mtiles * p.ntiles;
+    const int split = blockIdx.x / tiles;
+    const int tile = blockIdx.x - split * tiles;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // loader role: reduction position jj of the step, rows g, g+16, ...
+    const int jj = tid & 15, g = tid >> 4;
+    const int PQ = p.P * p.Q;
+
+    int boff[RB], bdr[RB], bds[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        const int4 tap = p.tab[n0 + g + 16 * i];     // table is padded past CRS with failing taps
+        boff[i] = tap.x; bdr[i] = tap.y; bds[i] = tap.z;
+    }
+
+    const int jbeg = split * p.chunks_per_split * kChunk;
+    int jend = jbeg + p.chunks_per_split * kChunk;
+    if (jend > p.J) jend = p.J;
+    const int nsteps = (jend - jbeg + kChunk - 1) / kChunk;
+
+    float areg[RA], breg[RB];
+    bool aok[RA], bok[RB];
+    const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
+    const char *x_bytes = reinterpret_cast<const char *>(p.x);
+
+    auto load_step = [&](int step) {
+        const int j = jbeg + step * kChunk + jj;
+        const bool jok = j < jend;
+        const int js = jok ? j : jbeg;
+        const int n = (int)fastdiv((uint32_t)js, p.div_plane);
+        const int pq = js - n * PQ;
+        const int pp = (int)fastdiv((uint32_t)pq, p.div_q);
+        const int qq = pq - pp * p.Q;
+        const int hb0 = pp * p.stride - p.pad;
+        const int wb = qq * p.stride - p.pad;
+        const int abase = 4 * (n * p.dy_bs + pq);                  // bytes
+        const int bbase = 4 * (n * p.x_bs + hb0 * p.W + wb);
+        const int hb = jok ? hb0 : kInvalidTap;
+#pragma unroll
+        for (int i = 0; i < RA; ++i) {
+            const int k = m0 + g + 16 * i;
+            const bool ok = jok & (k < p.K);
+            areg[i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(ok ? abase + 4 * k * PQ : 0));
+            aok[i] = ok;
+        }
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            const int hh = hb + bdr[i], ww = wb + bds[i];
+            const bool ok = ((unsigned)hh < (unsigned)p.H) & ((unsigned)ww < (unsigned)p.W);
+            breg[i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0));
+            bok[i] = ok;
+        }
+    };
+
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < RA; ++i) As[buf][(g + 16 * i) * kPitch + jj] = aok[i] ? areg[i] : 0.f;
+#pragma unroll
+        for (int i = 0; i < RB; ++i) Bs[buf][(g + 16 * i) * kPitch + jj] = bok[i] ? breg[i] : 0.f;
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    if (nsteps > 0) {
+        load_step(0);
+        store_step(0);
+    }
+    __syncthreads();
+    for (int step = 0; step < nsteps; ++step) {
+        const int buf = step & 1;
+        const bool more = step + 1 < nsteps;
+        if (more) load_step(step + 1);
+        mma_step<TM, TN>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
+        if (more) store_step(buf ^ 1);
+        __syncthreads();
+    }
+
+    const int l32 = lane & 31, half = lane >> 5;
+    float *out = p.out + (size_t)split * p.K * p.CRS;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.CRS) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.CRS + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// Fixed-order sum of the split partials: dw[i] = part[0][i] + part[1][i] + ...
+__global__ void reduce_partials(const float *__restrict__ part, float *__restrict__ dw, int count, int nsplit)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= count) return;
+    float s = part[i];
+    for (int k = 1; k < nsplit; ++k) s += part[(size_t)k * count + i];
+    dw[i] = s;
+}
+
+// ---------------------------------------------------------------------------
+// Glue layers
+// ---------------------------------------------------------------------------
+__global__ void relu_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) { float v = x[i]; y[i] = v > 0.f ? v : 0.f; }
+}
+
+__global__ void relu_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
+                                float *__restrict__ dx, int64_t n)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dx[i] = x[i] > 0.f ? dy[i] : 0.f;
+}
+
+// index (within the plane) of the first maximum of the 3x3 window at (2i, 2j)
+__device__ __forceinline__ int pool_argmax(const float *__restrict__ xp, int W, int i, int j, float &m)
+{
+    int best = (2 * i) * W + 2 * j;
+    m = xp[best];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int s = 0; s < 3; ++s) {
+            int at = (2 * i + r) * W + (2 * j + s);
+            float v = xp[at];
+            if (v > m) { m = v; best = at; }
+        }
+    return best;
+}
+
+__global__ void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int64_t total,
+                                   int H, int W, int PH, int PW)
+{
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    int j = (int)(t % PW);
+    int64_t u = t / PW;
+    int i = (int)(u % PH);
+    int64_t pl = u / PH;
+    float m;
+    pool_argmax(x + pl * H * W, W, i, j, m);
+    y[t] = m;
+}
+
+// One thread per input element: it visits the (at most four) windows that
+// contain it, in row-major window order, and adds the gradient of each window
+// whose first maximum it is.  No atomics, fixed order.
+__global__ void maxpool_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
+                                   float *__restrict__ dx, int64_t total, int H, int W, int PH, int PW)
+{
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    int w = (int)(t % W);
+    int64_t u = t / W;
+    int h = (int)(u % H);
+    int64_t pl = u / H;
+    const float *xp = x + pl * H * W;
+    const float *gp = dy + pl * PH * PW;
+    const int self = h * W + w;
+    int i_lo = h >= 2 ? (h - 1) / 2 : 0, i_hi = h / 2;
+    int j_lo = w >= 2 ? (w - 1) / 2 : 0, j_hi = w / 2;
+    if (i_hi > PH - 1) i_hi = PH - 1;
+    if (j_hi > PW - 1) j_hi = PW - 1;
+    float s = 0.f;
+    for (int i = i_lo; i <= i_hi; ++i)
+        for (int j = j_lo; j <= j_hi; ++j) {
+            float m;
+            if (pool_argmax(xp, W, i, j, m) == self) s += gp[i * PW + j];
+        }
+    dx[t] = s;
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e)
+{
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s", hipGetErrorString(e));
+    return kErrHip;
+}
+
+int check_launch()
+{
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? kStatusOk : hip_fail(e);
+}
+
+bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+template <int GATHER>
+void launch_colgemm(const TileShape &t, const ColGemmArgs &a, int grid, hipStream_t st)
+{
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_kernel<2, 2, 2, 2, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((colgemm_kernel<3, 1, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
+    else if (t.TM == 2) hipLaunchKernelGGL((colgemm_kernel<2, 1, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((colgemm_kernel<1, 2, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
+}
+
+void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
+{
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((wgrad_kernel<2, 2, 2, 2>), dim3(grid), dim3(kThreads), 0, st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((wgrad_kernel<3, 1, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
+    else if (t.TM == 2) hipLaunchKernelGGL((wgrad_kernel<2, 1, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((wgrad_kernel<1, 2, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
+}
+
+int grid1d(int64_t n, int block) { return (int)((n + block - 1) / block); }
+
+// Common front end of the three passes: checks, plan, workspace carving.
+int prepare(int op, const void *a, const void *b, void *out, int N, int C, int H, int W, int K, int R, int S,
+            int stride, int pad, int64_t x_bs, int64_t y_bs, int dtype, void *ws, size_t ws_bytes,
+            Problem &pb, Plan &pl)
+{
+    if (!a || !b || !out) return kErrInvalidArg;
+    int rc = make_problem(pb, N, C, H, W, K, R, S, stride, pad, x_bs, y_bs, dtype);
+    if (rc != kStatusOk) return rc;
+    if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out, 16)) return kErrMisaligned;
+    pl = make_plan(op, pb);
+    if (pl.total > 0) {
+        if (!ws || ws_bytes < pl.total) return kErrWorkspace;
+        if (!aligned(ws, 256)) return kErrMisaligned;
+    }
+    return kStatusOk;
+}
+
+const float *as_f32(const void *src, int64_t count, int dtype, char *ws, const Plan &pl, int slot, hipStream_t st)
+{
+    if (dtype == kDtypeF32) return static_cast<const float *>(src);
+    float *dst = reinterpret_cast<float *>(ws + pl.cvt_off[slot]);
+    hipLaunchKernelGGL(widen_bf16, dim3(grid1d(count, 256)), dim3(256), 0, st,
+                       static_cast<const unsigned short *>(src), dst, count);
+    return dst;
+}
+
+int run_colgemm(int op, const void *act, const void *w, void *out, const Problem &pb, const Plan &pl,
+                void *ws, hipStream_t st)
+{
+    char *wsb = static_cast<char *>(ws);
+    int4 *tab = reinterpret_cast<int4 *>(wsb + pl.tab_off);
+    float *wt = reinterpret_cast<float *>(wsb + pl.wt_off);
+    const int RS = pb.R * pb.S;
+    const bool fwd = op == kOpFwd;
+    const int64_t act_elems = (int64_t)pb.N * (fwd ? pb.x_bs : pb.y_bs);
+    const float *actf = as_f32(act, act_elems, pb.dtype, wsb, pl, 0, st);
+    const float *wf = as_f32(w, (int64_t)pb.K * pb.C * RS, pb.dtype, wsb, pl, 1, st);
+
+    if (fwd)
+        hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len,
+                           pl.Kg, RS, pb.S, pb.H * pb.W, pb.W, 1, 1);
+    else
+        hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len,
+                           pl.Kg, RS, pb.S, pb.P * pb.Q, pb.stride == 1 ? pb.Q : 0,
+                           pb.stride == 1 ? 1 : 0, -1);
+    hipLaunchKernelGGL(relayout_filters, dim3(grid1d((int64_t)pl.Mpad * pl.Kgpad, 256)), dim3(256), 0, st, wf, wt,
+                       pl.M, pl.Mpad, pl.Kg, pl.Kgpad, pb.C, RS, fwd ? 0 : 1);
+
+    ColGemmArgs a;
+    a.At = wt; a.tab = tab; a.src = actf; a.dst = static_cast<float *>(out);
+    a.M = pl.M; a.Mpad = pl.Mpad; a.nchunks = pl.Kgpad / kChunk;
+    if (fwd) {
+        a.OH = pb.P; a.OW = pb.Q; a.LH = pb.H; a.LW = pb.W;
+        a.src_bs = (int)pb.x_bs; a.dst_bs = (int)pb.y_bs;
+        a.mul = pb.stride; a.add = -pb.pad;
+    } else {
+        a.OH = pb.H; a.OW = pb.W; a.LH = pb.P; a.LW = pb.Q;
+        a.src_bs = (int)pb.y_bs; a.dst_bs = (int)pb.x_bs;
+        a.mul = 1; a.add = pb.pad;
+    }
+    a.ncols = pb.N * a.OH * a.OW;
+    a.mtiles = pl.Mpad / pl.tile.bm();
+    a.ntiles = ceil_div(a.ncols, pl.tile.bn());
+    a.div_plane = make_fastdiv((uint32_t)(a.OH * a.OW));
+    a.div_ow = make_fastdiv((uint32_t)a.OW);
+    a.div_stride = make_fastdiv((uint32_t)pb.stride);
+    const int grid = a.mtiles * round_up(a.ntiles, 8);
+    if (!fwd && pb.stride > 1) launch_colgemm<kGatherStridedBwd>(pl.tile, a, grid, st);
+    else launch_colgemm<kGatherDirect>(pl.tile, a, grid, st);
+    return check_launch();
+}
+
+int run_wgrad(const void *x, const void *dy, void *dw, const Problem &pb, const Plan &pl, void *ws, hipStream_t st)
+{
+    char *wsb = static_cast<char *>(ws);
+    int4 *tab = reinterpret_cast<int4 *>(wsb + pl.tab_off);
+    const int RS = pb.R * pb.S;
+    const float *xf = as_f32(x, (int64_t)pb.N * pb.x_bs, pb.dtype, wsb, pl, 0, st);
+    const float *dyf = as_f32(dy, (int64_t)pb.N * pb.y_bs, pb.dtype, wsb, pl, 1, st);
+    hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len, pl.Kg, RS,
+                       pb.S, pb.H * pb.W, pb.W, 1, 1);
+    WgradArgs a;
+    a.dy = dyf; a.x = xf; a.tab = tab;
+    a.out = pl.nsplit > 1 ? reinterpret_cast<float *>(wsb + pl.part_off) : static_cast<float *>(dw);
+    a.K = pb.K; a.CRS = pl.Kg;
+    a.P = pb.P; a.Q = pb.Q; a.H = pb.H; a.W = pb.W; a.stride = pb.stride; a.pad = pb.pad;
+    a.dy_bs = (int)pb.y_bs; a.x_bs = (int)pb.x_bs;
+    a.J = pb.N * pb.P * pb.Q;
+    a.chunks_per_split = pl.chunks_per_split;
+    a.mtiles = pl.Mpad / pl.tile.bm();
+    a.ntiles = ceil_div(pl.Kg, pl.tile.bn());
+    a.div_plane = make_fastdiv((uint32_t)(pb.P * pb.Q));
+    a.div_q = make_fastdiv((uint32_t)pb.Q);
+    launch_wgrad(pl.tile, a, a.mtiles * a.ntiles * pl.nsplit, st);
+    int rc = check_launch();
+    if (rc != kStatusOk) return rc;
+    if (pl.nsplit > 1) {
+        const int count = pb.K * pl.Kg;
+        hipLaunchKernelGGL(reduce_partials, dim3(grid1d(count, 256)), dim3(256), 0, st, a.out,
+                           static_cast<float *>(dw), count, pl.nsplit);
+        rc = check_launch();
+    }
+    return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_fwd_ex(const void *x, const void *w, void *y, int N, int C, int H, int W, int K, int R, int S, int stride,
+                int pad, int64_t x_batch_stride, int64_t y_batch_stride, int dtype, void *ws, size_t ws_bytes,
+                void *stream)
+{
+    Problem pb; Plan pl;
+    int rc = prepare(kOpFwd, x, w, y, N, C, H, W, K, R, S, stride, pad, x_batch_stride, y_batch_stride, dtype, ws,
+                     ws_bytes, pb, pl);
+    if (rc != kStatusOk) return rc;
+    return run_colgemm(kOpFwd, x, w, y, pb, pl, ws, static_cast<hipStream_t>(stream));
+}
+
+int conv_bwd_data_ex(const void *dy, const void *w, void *dx, int N, int C, int H, int W, int K, int R, int S,
+                     int stride, int pad, int64_t x_batch_stride, int64_t y_batch_stride, int dtype, void *ws,
+                     size_t ws_bytes, void *stream)
+{
+    Problem pb; Plan pl;
+    int rc = prepare(kOpBwdData, dy, w, dx, N, C, H, W, K, R, S, stride, pad, x_batch_stride, y_batch_stride, dtype,
+                     ws, ws_bytes, pb, pl);
+    if (rc != kStatusOk) return rc;
+    return run_colgemm(kOpBwdData, dy, w, dx, pb, pl, ws, static_cast<hipStream_t>(stream));
+}
+
+int conv_bwd_filter_ex(const void *x, const void *dy, void *dw, int N, int C, int H, int W, int K, int R, int S,
+                       int stride, int pad, int64_t x_batch_stride, int64_t y_batch_stride, int dtype, void *ws,
+                       size_t ws_bytes, void *stream)
+{
+    Problem pb; Plan pl;
+    int rc = prepare(kOpBwdFilter, x, dy, dw, N, C, H, W, K, R, S, stride, pad, x_batch_stride, y_batch_stride,
+                     dtype, ws, ws_bytes, pb, pl);
+    if (rc != kStatusOk) return rc;
+    return run_wgrad(x, dy, dw, pb, pl, ws, static_cast<hipStream_t>(stream));
+}
+
+int conv_fwd(const void *x, const void *w, void *y, int N, int C, int H, int W, int K, int R, int S, int stride,
+             int pad, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_fwd_ex(x, w, y, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype, ws, ws_bytes, stream);
+}
+
+int conv_bwd_data(const void *dy, const void *w, void *dx, int N, int C, int H, int W, int K, int R, int S,
+                  int stride, int pad, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_bwd_data_ex(dy, w, dx, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype, ws, ws_bytes, stream);
+}
+
+int conv_bwd_filter(const void *x, const void *dy, void *dw, int N, int C, int H, int W, int K, int R, int S,
+                    int stride, int pad, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_bwd_filter_ex(x, dy, dw, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype, ws, ws_bytes, stream);
+}
+
+size_t conv_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int dtype)
+{
+    if (op != kOpFwd && op != kOpBwdData && op != kOpBwdFilter) return 0;
+    Problem pb;
+    if (make_problem(pb, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype) != kStatusOk) return 0;
+    return make_plan(op, pb).total;
+}
+
+const char *conv_status_string(int status)
+{
+    switch (status) {
+    case kStatusOk: return "ok";
+    case kErrInvalidArg: return "invalid argument (null pointer, non-positive extent or empty output)";
+    case kErrTooLarge: return "tensor too large (a span reaches 2^31 bytes)";
+    case kErrBadDtype: return "unknown dtype";
+    case kErrWorkspace: return "workspace missing or too small";
+    case kErrMisaligned: return "pointer not sufficiently aligned";
+    case kErrHip: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+const char *conv_last_hip_error(void) { return g_hip_error; }
+
+int relu_fwd(const void *x, void *y, int64_t count, void *stream)
+{
+    if (!x || !y || count < 0) return kErrInvalidArg;
+    if (count == 0) return kStatusOk;
+    if (!aligned(x, 4) || !aligned(y, 4)) return kErrMisaligned;
+    hipLaunchKernelGGL(relu_fwd_kernel, dim3(grid1d(count, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float *>(x), static_cast<float *>(y), count);
+    return check_launch();
+}
+
+int relu_bwd(const void *x, const void *dy, void *dx, int64_t count, void *stream)
+{
+    if (!x || !dy || !dx || count < 0) return kErrInvalidArg;
+    if (count == 0) return kStatusOk;
+    if (!aligned(x, 4) || !aligned(dy, 4) || !aligned(dx, 4)) return kErrMisaligned;
+    hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid1d(count, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx), count);
+    return check_launch();
+}
+
+static int pool_checks(int64_t planes, int H, int W, int &PH, int &PW)
+{
+    if (planes <= 0 || H < 3 || W < 3) return kErrInvalidArg;
+    PH = (H - 3) / 2 + 1;
+    PW = (W - 3) / 2 + 1;
+    if ((double)planes * H * W * 4.0 >= (double)((int64_t)1 << 40)) return kErrTooLarge;
+    return kStatusOk;
+}
+
+int maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream)
+{
+    if (!x || !y) return kErrInvalidArg;
+    int PH, PW;
+    int rc = pool_checks(planes, H, W, PH, PW);
+    if (rc != kStatusOk) return rc;
+    if (!aligned(x, 4) || !aligned(y, 4)) return kErrMisaligned;
+    const int64_t total = planes * PH * PW;
+    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid1d(total, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float *>(x), static_cast<float *>(y), total, H, W, PH, PW);
+    return check_launch();
+}
+
+int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream)
+{
+    if (!x || !dy || !dx) return kErrInvalidArg;
+    int PH, PW;
+    int rc = pool_checks(planes, H, W, PH, PW);
+    if (rc != kStatusOk) return rc;
+    if (!aligned(x, 4) || !aligned(dy, 4) || !aligned(dx, 4)) return kErrMisaligned;
+    const int64_t total = planes * H * W;
+    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid1d(total, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx), total,
+                       H, W, PH, PW);
+    return check_launch();
+}
+
+}  // extern "C"

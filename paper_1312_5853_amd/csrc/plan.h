@@ -1,0 +1,172 @@
+// Host-side planning for the convolution passes: argument checks, derived
+// extents, tile-shape choice, split count of the backward-filter reduction and
+// the workspace layout.  Plain C++ with no HIP dependency, so the same header
+// compiles into a CPU-only self-test.
+#ifndef CONVNET_PLAN_H
+#define CONVNET_PLAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fastdiv.h"
+
+namespace convnet {
+
+constexpr int kStatusOk = 0;
+constexpr int kErrInvalidArg = -1;
+constexpr int kErrTooLarge = -2;
+constexpr int kErrBadDtype = -3;
+constexpr int kErrWorkspace = -4;
+constexpr int kErrMisaligned = -5;
+constexpr int kErrHip = -6;
+
+constexpr int kOpFwd = 0, kOpBwdData = 1, kOpBwdFilter = 2;
+constexpr int kDtypeF32 = 0, kDtypeBf16 = 1;
+
+constexpr int kChunk = 16;            // reduction elements staged in LDS per step
+constexpr int kTapTablePad = 256;     // tap table length is rounded up to this
+constexpr int64_t kMaxSpanBytes = (int64_t)1 << 31;
+constexpr int kTargetGroups = 768;    // work-groups wanted in flight: 3 per CU on 256 CUs
+
+struct Problem {
+    int N, C, H, W, K, R, S, stride, pad;
+    int P, Q;
+    int64_t x_bs, y_bs;               // batch strides in elements
+    int dtype;
+};
+
+// Tile shape of one work-group (4 waves): each wave owns TM x TN MFMA tiles of
+// 32 x 32; waves are laid out WM x WN.
+struct TileShape {
+    int TM, TN, WM, WN;
+    int bm() const { return TM * WM * 32; }
+    int bn() const { return TN * WN * 32; }
+};
+
+constexpr TileShape kTile128x128 = {2, 2, 2, 2};
+constexpr TileShape kTile96x128 = {3, 1, 1, 4};
+constexpr TileShape kTile64x128 = {2, 1, 1, 4};
+constexpr TileShape kTile32x256 = {1, 2, 1, 4};
+
+inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Row-tile choice: the block height that pads M (rows of the GEMM view) least;
+// ties go to the taller block (more reuse of the gathered operand).
+inline TileShape pick_tile(int M)
+{
+    const TileShape cand[4] = {kTile128x128, kTile96x128, kTile64x128, kTile32x256};
+    TileShape best = cand[0];
+    int best_cost = round_up(M, best.bm());
+    for (int i = 1; i < 4; ++i) {
+        int cost = round_up(M, cand[i].bm());
+        if (cost < best_cost) { best = cand[i]; best_cost = cost; }
+    }
+    return best;
+}
+
+inline int out_extent(int in, int filt, int stride, int pad)
+{
+    int span = in + 2 * pad - filt;
+    return span < 0 ? 0 : span / stride + 1;
+}
+
+// Fills P, Q and checks everything that can be checked without touching the GPU.
+inline int make_problem(Problem &pb, int N, int C, int H, int W, int K, int R, int S,
+                        int stride, int pad, int64_t x_bs, int64_t y_bs, int dtype)
+{
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0) return kErrInvalidArg;
+    if (stride <= 0 || pad < 0) return kErrInvalidArg;
+    if (dtype != kDtypeF32 && dtype != kDtypeBf16) return kErrBadDtype;
+    // keep every intermediate below 2^31 before multiplying extents together
+    if (pad > (1 << 20) || stride > (1 << 20)) return kErrTooLarge;
+    if ((int64_t)H + 2 * (int64_t)pad < R || (int64_t)W + 2 * (int64_t)pad < S) return kErrInvalidArg;
+    pb.N = N; pb.C = C; pb.H = H; pb.W = W; pb.K = K; pb.R = R; pb.S = S;
+    pb.stride = stride; pb.pad = pad; pb.dtype = dtype;
+    pb.P = out_extent(H, R, stride, pad);
+    pb.Q = out_extent(W, S, stride, pad);
+    if (pb.P <= 0 || pb.Q <= 0) return kErrInvalidArg;
+    const int64_t x_sample = (int64_t)C * H * W, y_sample = (int64_t)K * pb.P * pb.Q;
+    const int64_t w_elems = (int64_t)K * C * R * S;
+    if (x_bs == 0) x_bs = x_sample;
+    if (y_bs == 0) y_bs = y_sample;
+    if (x_bs < x_sample || y_bs < y_sample) return kErrInvalidArg;
+    pb.x_bs = x_bs; pb.y_bs = y_bs;
+    const int64_t fat = 4;   // widest element the kernels index with 32-bit offsets
+    if (x_sample >= kMaxSpanBytes / fat || y_sample >= kMaxSpanBytes / fat) return kErrTooLarge;
+    if (x_bs >= kMaxSpanBytes / fat || y_bs >= kMaxSpanBytes / fat) return kErrTooLarge;
+    if ((int64_t)N * x_bs * fat >= kMaxSpanBytes) return kErrTooLarge;
+    if ((int64_t)N * y_bs * fat >= kMaxSpanBytes) return kErrTooLarge;
+    if (w_elems * fat >= kMaxSpanBytes) return kErrTooLarge;
+    if ((int64_t)C * R * S >= (1 << 28) || (int64_t)K * R * S >= (1 << 28)) return kErrTooLarge;
+    return kStatusOk;
+}
+
+// What one pass needs in the workspace, in bytes from its 256-aligned base.
+struct Plan {
+    int op;
+    TileShape tile;
+    int M;            // rows of the GEMM view: K (fwd, wgrad) or C (dgrad)
+    int Mpad;
+    int Kg;           // fwd: C*R*S, dgrad: K*R*S, wgrad: C*R*S (columns of dw)
+    int Kgpad;        // Kg rounded up to kChunk
+    int tab_len;      // tap table entries
+    int nsplit;       // wgrad: partial sums over the (n, p, q) reduction
+    int chunks_per_split;
+    size_t tab_off, tab_bytes;
+    size_t wt_off, wt_bytes;          // re-laid-out filters (fwd, dgrad)
+    size_t part_off, part_bytes;      // wgrad partials
+    size_t cvt_off[2], cvt_bytes[2];  // bf16 -> fp32 staging of the two inputs
+    size_t total;
+};
+
+inline Plan make_plan(int op, const Problem &pb)
+{
+    Plan pl = {};
+    pl.op = op;
+    const int RS = pb.R * pb.S;
+    if (op == kOpFwd) { pl.M = pb.K; pl.Kg = pb.C * RS; }
+    else if (op == kOpBwdData) { pl.M = pb.C; pl.Kg = pb.K * RS; }
+    else { pl.M = pb.K; pl.Kg = pb.C * RS; }
+    pl.tile = pick_tile(pl.M);
+    pl.Mpad = round_up(pl.M, pl.tile.bm());
+    pl.Kgpad = round_up(pl.Kg, kChunk);
+    pl.tab_len = round_up(pl.Kg, kTapTablePad);
+    pl.nsplit = 1;
+    pl.chunks_per_split = 0;
+    size_t off = 0;
+    pl.tab_off = off; pl.tab_bytes = (size_t)pl.tab_len * 16; off += round_up64(pl.tab_bytes, 256);
+    if (op == kOpBwdFilter) {
+        const int64_t J = (int64_t)pb.N * pb.P * pb.Q;
+        const int jchunks = (int)((J + kChunk - 1) / kChunk);
+        const int tiles = (pl.Mpad / pl.tile.bm()) * ceil_div(pl.Kg, pl.tile.bn());
+        int want = ceil_div(kTargetGroups, tiles);
+        int most = jchunks / 8 > 0 ? jchunks / 8 : 1;     // at least 8 chunks of work per split
+        int nsplit = want < most ? want : most;
+        if (nsplit < 1) nsplit = 1;
+        pl.chunks_per_split = ceil_div(jchunks, nsplit);
+        pl.nsplit = ceil_div(jchunks, pl.chunks_per_split);
+        pl.part_off = off;
+        pl.part_bytes = pl.nsplit > 1 ? (size_t)pl.nsplit * pb.K * pb.C * RS * 4 : 0;
+        off += round_up64(pl.part_bytes, 256);
+    } else {
+        pl.wt_off = off;
+        pl.wt_bytes = (size_t)pl.Mpad * pl.Kgpad * 4;
+        off += round_up64(pl.wt_bytes, 256);
+    }
+    if (pb.dtype == kDtypeBf16) {
+        // inputs are widened to fp32 once, then the fp32 kernels run on the copies
+        const int64_t x_e = (int64_t)pb.N * pb.x_bs, y_e = (int64_t)pb.N * pb.y_bs;
+        const int64_t w_e = (int64_t)pb.K * pb.C * RS;
+        int64_t a = op == kOpFwd ? x_e : (op == kOpBwdData ? y_e : x_e);
+        int64_t b = op == kOpBwdFilter ? y_e : w_e;
+        pl.cvt_off[0] = off; pl.cvt_bytes[0] = (size_t)a * 4; off += round_up64(pl.cvt_bytes[0], 256);
+        pl.cvt_off[1] = off; pl.cvt_bytes[1] = (size_t)b * 4; off += round_up64(pl.cvt_bytes[1], 256);
+    }
+    pl.total = off;
+    return pl;
+}
+
+}  // namespace convnet
+#endif

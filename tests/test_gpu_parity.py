@@ -1,0 +1,290 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Error measure (for every floating-point comparison here): normalised max error
+    err = max_i |gpu_i - ref_i| / max_i |ref_i|
+over the compared elements, ref = fp64 oracle.  Bars: 1e-4 for fp32 arithmetic,
+2e-2 for bf16 inputs with fp32 accumulation (the oracle is fed the same
+bf16-rounded values, so only accumulation order and width differ).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1312_5853_amd import binding as hp
+from paper_1312_5853_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def norm_err(got, ref):
+    got = np.asarray(got, dtype=np.float64).ravel()
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    denom = np.abs(ref).max()
+    return np.abs(got - ref).max() / (denom if denom > 0 else 1.0)
+
+
+def dev(a, dtype="f32"):
+    t = torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def nan_like(shape):
+    return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+
+
+def prepared(x, w, dy, dtype):
+    """For bf16 the values are first rounded onto the bf16 grid; both sides then read them exactly."""
+    if dtype == "bf16":
+        return synth.to_bf16_grid(x), synth.to_bf16_grid(w), synth.to_bf16_grid(dy)
+    return x, w, dy
+
+
+def run_three(x, w, dy, st, pad, dtype="f32"):
+    N, C, H, W = x.shape
+    K, _, R, S = w.shape
+    P, Q = dy.shape[2:]
+    xd, wd, dyd = dev(x, dtype), dev(w, dtype), dev(dy, dtype)
+    y = hp.conv_fwd(xd, wd, st, pad, y=nan_like((N, K, P, Q)))
+    dx = hp.conv_bwd_data(dyd, wd, H, W, st, pad, dx=nan_like((N, C, H, W)))
+    dw = hp.conv_bwd_filter(xd, dyd, R, S, st, pad, dw=nan_like((K, C, R, S)))
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), dx.cpu().numpy(), dw.cpu().numpy()
+
+
+def check_full(x, w, dy, st, pad, dtype="f32"):
+    x, w, dy = prepared(x, w, dy, dtype)
+    N, C, H, W = x.shape
+    R, S = w.shape[2:]
+    y, dx, dw = run_three(x, w, dy, st, pad, dtype)
+    errs = (norm_err(y, oracle.conv_fwd(x, w, st, pad)),
+            norm_err(dx, oracle.conv_bwd_data(dy, w, H, W, st, pad)),
+            norm_err(dw, oracle.conv_bwd_filter(x, dy, R, S, st, pad)))
+    for name, e in zip(("fwd", "dgrad", "wgrad"), errs):
+        assert np.isfinite(e) and e <= TOL[dtype], "%s err %.3e" % (name, e)
+    return errs
+
+
+# ----------------------------------------------------------- tiny config ---
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_config_full_compare(dtype):
+    L = synth.LAYERS["tiny"]
+    x, w, dy = synth.layer_tensors("tiny", 4)
+    check_full(x, w, dy, L["stride"], L["pad"], dtype)
+
+
+# ------------------------------------------------------ odd small shapes ---
+ODD_SHAPES = [
+    # N, C, H, W, K, R, S, stride, pad
+    (1, 1, 5, 5, 1, 1, 1, 1, 0),
+    (1, 3, 7, 9, 17, 3, 3, 1, 1),
+    (3, 17, 9, 7, 3, 3, 2, 1, 1),
+    (2, 3, 12, 11, 5, 5, 5, 2, 2),
+    (3, 1, 23, 25, 48, 11, 11, 4, 2),
+    (1, 48, 6, 6, 17, 3, 3, 1, 0),
+    (2, 5, 8, 10, 130, 3, 3, 1, 5),        # pad beyond the filter, K past one row tile
+    (1, 2, 9, 9, 2, 9, 9, 1, 0),           # filter as large as the input: 1x1 output
+    (3, 4, 10, 10, 100, 2, 3, 3, 1),       # K = 100: ragged 96/128 row tile
+    (5, 33, 13, 13, 65, 3, 3, 1, 1),       # columns 5*169 = 845: ragged last column tile
+    (2, 2, 40, 3, 3, 4, 1, 4, 0),          # stride 4 along a thin plane
+]
+
+
+@pytest.mark.parametrize("shape", ODD_SHAPES)
+def test_odd_shapes_full_compare(shape):
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+    x = synth.gaussian((N, C, H, W), 101)
+    w = synth.gaussian((K, C, R, S), 102, 0.1)
+    dy = synth.gaussian((N, K, P, Q), 103)
+    check_full(x, w, dy, st, pad)
+
+
+def test_small_integers_are_exact():
+    """Integer-valued inputs with small sums are exact in fp32: bit-for-bit equality."""
+    N, C, H, W, K, R, S, st, pad = 2, 6, 11, 12, 40, 3, 3, 2, 1
+    P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+    x = synth.small_integers((N, C, H, W), 111)
+    w = synth.small_integers((K, C, R, S), 112)
+    dy = synth.small_integers((N, K, P, Q), 113)
+    y, dx, dw = run_three(x, w, dy, st, pad)
+    np.testing.assert_array_equal(y, oracle.conv_fwd(x, w, st, pad))
+    np.testing.assert_array_equal(dx, oracle.conv_bwd_data(dy, w, H, W, st, pad))
+    np.testing.assert_array_equal(dw, oracle.conv_bwd_filter(x, dy, R, S, st, pad))
+
+
+# ---------------------------------------- guard bands and full overwrite ---
+def test_guard_bands_untouched():
+    N, C, H, W, K, R, S, st, pad = 3, 7, 13, 13, 70, 3, 3, 1, 1
+    P, Q = H, W
+    x, w, dy = (synth.gaussian(s, i) for i, s in enumerate([(N, C, H, W), (K, C, R, S), (N, K, P, Q)], 121))
+    xd, wd, dyd = dev(x), dev(w), dev(dy)
+    G = 4096
+
+    def guarded(numel):
+        buf = torch.full((numel + 2 * G,), float("nan"), dtype=torch.float32, device="cuda")
+        return buf, buf[G:G + numel]
+
+    for op in ("fwd", "dgrad", "wgrad"):
+        if op == "fwd":
+            buf, out = guarded(N * K * P * Q)
+            hp.conv_fwd(xd, wd, st, pad, y=out.view(N, K, P, Q))
+        elif op == "dgrad":
+            buf, out = guarded(N * C * H * W)
+            hp.conv_bwd_data(dyd, wd, H, W, st, pad, dx=out.view(N, C, H, W))
+        else:
+            buf, out = guarded(K * C * R * S)
+            hp.conv_bwd_filter(xd, dyd, R, S, st, pad, dw=out.view(K, C, R, S))
+        torch.cuda.synchronize()
+        assert torch.isnan(buf[:G]).all() and torch.isnan(buf[-G:]).all(), op
+        assert not torch.isnan(out).any(), op
+
+
+def test_dgrad_rows_no_window_touches_are_zero():
+    # H = 226 with an 11x11 stride-4 filter: the last input rows/cols lie beyond every window
+    N, C, H, W, K, R, S, st, pad = 1, 2, 30, 30, 3, 11, 11, 4, 0
+    P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+    assert (P - 1) * st + R < H
+    w = synth.gaussian((K, C, R, S), 131)
+    dy = synth.gaussian((N, K, P, Q), 132)
+    dx = hp.conv_bwd_data(dev(dy), dev(w), H, W, st, pad, dx=nan_like((N, C, H, W))).cpu().numpy()
+    assert (dx[:, :, (P - 1) * st + R:, :] == 0).all() and (dx[:, :, :, (Q - 1) * st + S:] == 0).all()
+    assert norm_err(dx, oracle.conv_bwd_data(dy, w, H, W, st, pad)) <= TOL["f32"]
+
+
+def test_bitwise_determinism():
+    x, w, dy = synth.layer_tensors("conv2", 8)
+    L = synth.LAYERS["conv2"]
+    a = run_three(x, w, dy, L["stride"], L["pad"])
+    b = run_three(x, w, dy, L["stride"], L["pad"])
+    for u, v in zip(a, b):
+        assert np.array_equal(u.view(np.uint32), v.view(np.uint32))
+
+
+# ------------------------------ decompositions of the two parallel schemes ---
+def test_batch_shards_and_filter_halves_on_one_gpu():
+    L = synth.LAYERS["conv2"]
+    x, w, dy = synth.layer_tensors("conv2", 6)
+    st, pad, H, W, R, S = L["stride"], L["pad"], L["H"], L["W"], L["R"], L["S"]
+    y, dx, dw = run_three(x, w, dy, st, pad)
+    ya, dxa, dwa = run_three(x[:2], w, dy[:2], st, pad)
+    yb, dxb, dwb = run_three(x[2:], w, dy[2:], st, pad)
+    assert np.array_equal(np.concatenate([ya, yb]), y)            # per-sample results do not depend on the shard
+    assert np.array_equal(np.concatenate([dxa, dxb]), dx)
+    assert norm_err(dwa + dwb, dw) <= 1e-5                        # filter gradients add over shards
+    K = w.shape[0]
+    yh, dxh, dwh = run_three(x, w[:K // 2], dy[:, :K // 2], st, pad)
+    yg, dxg, dwg = run_three(x, w[K // 2:], dy[:, K // 2:], st, pad)
+    assert norm_err(np.concatenate([yh, yg], axis=1), y) <= 1e-6  # filter halves concatenate
+    assert norm_err(dxh + dxg, dx) <= 1e-5                        # and their input gradients add
+    assert norm_err(np.concatenate([dwh, dwg]), dw) <= 1e-6
+
+
+def test_channel_slices_of_wider_tensors():
+    """One column reads channels 48..95 of a 96-channel tensor and writes filters 128..255 of a 256-channel one."""
+    L = synth.LAYERS["conv2"]
+    N, st, pad = 5, L["stride"], L["pad"]
+    xw = synth.gaussian((N, 96, 27, 27), 141)
+    w = synth.gaussian((128, 48, 5, 5), 142, 0.01)
+    dyw = synth.gaussian((N, 256, 27, 27), 143)
+    xwd, wd, dywd = dev(xw), dev(w), dev(dyw)
+    ywd = nan_like((N, 256, 27, 27))
+    dxwd = nan_like((N, 96, 27, 27))
+    hp.conv_fwd(xwd[:, 48:], wd, st, pad, y=ywd[:, 128:])
+    hp.conv_bwd_data(dywd[:, 128:], wd, 27, 27, st, pad, dx=dxwd[:, 48:])
+    dw = hp.conv_bwd_filter(xwd[:, 48:], dywd[:, 128:], 5, 5, st, pad)
+    torch.cuda.synchronize()
+    assert torch.isnan(ywd[:, :128]).all() and torch.isnan(dxwd[:, :48]).all()
+    xs, dys = xw[:, 48:], dyw[:, 128:]
+    assert norm_err(ywd[:, 128:].cpu().numpy(), oracle.conv_fwd(xs, w, st, pad)) <= TOL["f32"]
+    assert norm_err(dxwd[:, 48:].cpu().numpy(), oracle.conv_bwd_data(dys, w, 27, 27, st, pad)) <= TOL["f32"]
+    assert norm_err(dw.cpu().numpy(), oracle.conv_bwd_filter(xs, dys, 5, 5, st, pad)) <= TOL["f32"]
+
+
+# ------------------------------- full-size layers, sampled against oracle ---
+FULL = [
+    # layer, N, passes, dtypes
+    ("conv1", 128, ("fwd", "wgrad"), ("f32",)),
+    ("conv2", 128, ("fwd", "dgrad", "wgrad"), ("f32",)),
+    ("conv3", 256, ("fwd", "dgrad", "wgrad"), ("f32", "bf16")),
+    ("conv4", 256, ("fwd", "dgrad", "wgrad"), ("f32", "bf16")),
+    ("conv5", 256, ("fwd", "dgrad", "wgrad"), ("f32", "bf16")),
+]
+
+
+def edge_indices(shape):
+    """Flat indices of the corners of every axis combination (first/last along each axis)."""
+    idx = []
+    for corner in np.ndindex(*(2,) * len(shape)):
+        pos = tuple((s - 1) if c else 0 for c, s in zip(corner, shape))
+        idx.append(np.ravel_multi_index(pos, shape))
+    return np.array(idx, dtype=np.int64)
+
+
+@pytest.mark.parametrize("layer,N,passes,dtypes", FULL)
+def test_full_size_layers_sampled(layer, N, passes, dtypes):
+    L = synth.LAYERS[layer]
+    st, pad, H, W, R, S, C, K, P, Q = (L[k] for k in ("stride", "pad", "H", "W", "R", "S", "C", "K", "P", "Q"))
+    x0, w0, dy0 = synth.layer_tensors(layer, N)
+    for dtype in dtypes:
+        x, w, dy = prepared(x0, w0, dy0, dtype)
+        xd, wd, dyd = dev(x, dtype), dev(w, dtype), dev(dy, dtype)
+        x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+        sums = {}
+        if "fwd" in passes:
+            y = hp.conv_fwd(xd, wd, st, pad, y=nan_like((N, K, P, Q)))
+            assert not torch.isnan(y).any()
+            sums["fwd"] = float((y.double() * dyd.double()).sum())
+            abs_sum = float((y.double().abs() * dyd.double().abs()).sum())
+            idx = np.unique(np.concatenate([synth.sample_indices(y.numel(), 20000, 7), edge_indices(y.shape)]))
+            ref = oracle.conv_fwd_at(x64, w64, st, pad, idx)
+            e = norm_err(y.view(-1)[torch.from_numpy(idx).cuda()].cpu().numpy(), ref)
+            assert e <= TOL[dtype], "%s fwd %s err %.3e" % (layer, dtype, e)
+        if "dgrad" in passes:
+            dx = hp.conv_bwd_data(dyd, wd, H, W, st, pad, dx=nan_like((N, C, H, W)))
+            assert not torch.isnan(dx).any()
+            sums["dgrad"] = float((dx.double() * xd.double()).sum())
+            idx = np.unique(np.concatenate([synth.sample_indices(dx.numel(), 1500, 8), edge_indices(dx.shape)]))
+            ref = oracle.conv_bwd_data_at(dy64, w64, H, W, st, pad, idx)
+            e = norm_err(dx.view(-1)[torch.from_numpy(idx).cuda()].cpu().numpy(), ref)
+            assert e <= TOL[dtype], "%s dgrad %s err %.3e" % (layer, dtype, e)
+        if "wgrad" in passes:
+            dw = hp.conv_bwd_filter(xd, dyd, R, S, st, pad, dw=nan_like((K, C, R, S)))
+            assert not torch.isnan(dw).any()
+            sums["wgrad"] = float((dw.double() * wd.double()).sum())
+            idx = np.unique(np.concatenate([synth.sample_indices(dw.numel(), 1500, 9), edge_indices(dw.shape)]))
+            ref = oracle.conv_bwd_filter_at(x64, dy64, R, S, st, pad, idx)
+            e = norm_err(dw.view(-1)[torch.from_numpy(idx).cuda()].cpu().numpy(), ref)
+            assert e <= TOL[dtype], "%s wgrad %s err %.3e" % (layer, dtype, e)
+        # property over ALL elements: <conv(x,w),dy> = <x,dgrad(dy,w)> = <w,wgrad(x,dy)>
+        # (the three sums differ only by rounding: bound them by 1e-5 of the sum of |terms|)
+        vals = list(sums.values())
+        for v in vals[1:]:
+            assert abs(v - vals[0]) <= 1e-5 * abs_sum, (layer, dtype, sums, abs_sum)
+
+
+# -------------------------------------------------------------------- glue ---
+def test_relu_and_pool_match_oracle():
+    for (N, C, H, W) in [(3, 5, 55, 55), (2, 7, 27, 27), (4, 3, 13, 13), (1, 1, 3, 3), (2, 2, 8, 5)]:
+        x = synth.gaussian((N, C, H, W), 151)
+        x[0, 0, :3, :3] = 0.0                                  # an all-tie window
+        xd = dev(x)
+        r = hp.relu_fwd(xd)
+        assert np.array_equal(r.cpu().numpy(), oracle.relu_fwd(x).astype(np.float32))
+        y = hp.maxpool3x3s2_fwd(xd)
+        yo = oracle.maxpool3x3s2_fwd(x)
+        assert np.array_equal(y.cpu().numpy(), yo.astype(np.float32))
+        g = synth.gaussian(yo.shape, 152)
+        gd = dev(g)
+        dxp = hp.maxpool3x3s2_bwd(xd, gd, dx=nan_like(x.shape))
+        assert norm_err(dxp.cpu().numpy(), oracle.maxpool3x3s2_bwd(x, g)) <= 1e-6
+        g2 = synth.gaussian(x.shape, 153)
+        drelu = hp.relu_bwd(xd, dev(g2))
+        assert np.array_equal(drelu.cpu().numpy(), oracle.relu_bwd(x, g2).astype(np.float32))
+    # post-ReLU planes: many all-zero windows, ties resolved to the first element on both sides
+    x = np.maximum(synth.gaussian((2, 3, 13, 13), 154), 0)
+    g = synth.gaussian((2, 3, 6, 6), 155)
+    got = hp.maxpool3x3s2_bwd(dev(x), dev(g)).cpu().numpy()
+    assert norm_err(got, oracle.maxpool3x3s2_bwd(x, g)) <= 1e-6
