@@ -1,0 +1,152 @@
+#!/usr/bin/env python3
+"""Benchmark of the convolution hot path on one MI355X.
+
+A step is one forward+backward pass of the five-convolution stack (conv1..conv5
+with ReLU / max-pool glue) over one synthetic mini-batch shard of N samples,
+N = 128 by default: the per-GPU share of the paper's two-GPU data-parallel run.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch N]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3      # MI355X dense fp32 matrix peak (published)
+
+
+def cpu_baseline(threads_hint=None, budget_images=None):
+    """Time the CPU oracle, as it stands, on a bounded sample of the same stack:
+    every conv pass of the step at the real layer shapes, on a few images."""
+    import numpy as np
+    import oracle
+    from paper_1312_5853_amd import synth
+    from paper_1312_5853_amd.stack import conv_flops
+
+    threads = oracle.num_threads()
+    n = budget_images or max(1, min(4 * threads, 64))      # about 10-30 s of oracle time
+    Ls = synth.LAYERS
+    flops = 0.0
+    t0 = time.perf_counter()
+    for name, passes, reps in (("conv1", ("f", "w"), 1), ("conv2", ("f", "d", "w"), 2),
+                               ("conv3", ("f", "d", "w"), 1), ("conv4", ("f", "d", "w"), 1),
+                               ("conv5", ("f", "d", "w"), 1)):
+        L = Ls[name]
+        x, w, dy = synth.layer_tensors(name, n)
+        x, w, dy = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
+        for _ in range(reps):
+            if "f" in passes:
+                oracle.conv_fwd(x, w, L["stride"], L["pad"])
+            if "d" in passes:
+                oracle.conv_bwd_data(dy, w, L["H"], L["W"], L["stride"], L["pad"])
+            if "w" in passes:
+                oracle.conv_bwd_filter(x, dy, L["R"], L["S"], L["stride"], L["pad"])
+            flops += len(passes) * conv_flops(n, L)
+    dt = time.perf_counter() - t0
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+        "sample": "all 16 conv passes of one stack step at the real layer shapes on %d images "
+                  "(%.1f GFLOP, %.1f s, input generation included)" % (n, flops / 1e9, dt),
+        "seconds": dt,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=128)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build targets one GPU (one data-parallel shard / one model-parallel "
+                 "column per call); --gpus %d is not supported, run with --gpus 1" % args.gpus)
+
+    import torch
+    from paper_1312_5853_amd import binding as hp
+    from paper_1312_5853_amd import build as hp_build
+    from paper_1312_5853_amd.stack import ConvStack, stack_flops, conv_flops
+    from paper_1312_5853_amd import synth
+
+    if not os.path.exists(hp.LIB_PATH):
+        hp_build.build()
+    hp.lib()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+
+    N = args.batch
+    stack = ConvStack(N)
+    flops = stack_flops(N)
+
+    for _ in range(args.warmup):
+        stack.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        stack.step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # second timed region: HIP events (on the launch stream) around every conv call
+    stack.timers = {}
+    acc = {}
+    reps = max(3, min(args.steps, 10))
+    for _ in range(reps):
+        stack.step()
+        torch.cuda.synchronize()
+        for key, (s, e) in stack.timers.items():
+            acc[key] = acc.get(key, 0.0) + s.elapsed_time(e)
+    stack.timers = None
+    per_pass = {}
+    conv_ms = 0.0
+    for (layer, p), tot in sorted(acc.items()):
+        L = synth.LAYERS[layer.rstrip("ab")]
+        ms = tot / reps
+        f = conv_flops(N, L)
+        conv_ms += ms
+        per_pass["%s.%s" % (layer, p)] = {"ms": round(ms, 4), "tflops": round(f / ms / 1e9, 2),
+                                           "frac_peak": round(f / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)}
+
+    # dominant kernel: the 128x128-tile implicit-GEMM kernel that runs forward and
+    # backward-data of conv2..conv5 (12 launches per step)
+    dom_keys = [k for k in acc if k[1] in ("fwd", "dgrad") and k[0] != "conv1"]
+    dom_keys = [k for k in dom_keys if not (k[0].startswith("conv2") and k[1] == "dgrad")]
+    dom_flops = sum(conv_flops(N, synth.LAYERS[k[0].rstrip("ab")]) for k in dom_keys)
+    dom_ms = sum(acc[k] for k in dom_keys) / reps
+    achieved = dom_flops / dom_ms / 1e9
+    roofline = {
+        "bound": "mfma", "kernel": "colgemm_kernel<2,2,2,2,direct> (fwd of conv2-5, dgrad of conv3-5)",
+        "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
+        "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None,
+        "launches_per_step": len(dom_keys), "avg_launch_ms": round(dom_ms / len(dom_keys), 4),
+        "flops_per_launch": dom_flops / len(dom_keys),
+    }
+
+    value = flops / ms_per_step / 1e9
+    out = {
+        "metric": "conv-stack TFLOP/s at N=%d (conv1-5 fwd+dgrad+wgrad, fp32 MFMA, ReLU/pool glue in the step)" % N,
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "5-conv AlexNet stack fwd+bwd, N=%d, fp32 (conv2 as two model-parallel columns)" % N,
+                   "batch": N, "conv_gflop_per_step": round(flops / 1e9, 2)},
+        "frac_fp32_mfma_peak": round(value / PEAK_FP32_MFMA_TFLOPS, 4),
+        "conv_only_ms": round(conv_ms, 4),
+        "conv_only_frac_peak": round(flops / conv_ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
+        "per_pass": per_pass,
+        "roofline": roofline,
+        "context": "paper: 10.5 days per 100 epochs on one NVIDIA TITAN at batch 256 (whole network, not this path)",
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,143 @@
+"""The five-convolution stack of the network the paper trains, as a sequence of
+C-ABI calls: forward through conv1..conv5 with ReLU and 3x3/stride-2 max
+pooling after conv1, conv2 and conv5, then back-propagation from a gradient on
+the last pooling output down to the first layer's filter gradient.
+
+Second layer: two model-parallel columns (channels 0..47 -> filters 0..127,
+channels 48..95 -> filters 128..255), each run in place on channel slices of
+the shared NCHW tensors -- the two-column layout of the paper's
+model-parallelism paragraph.  Layers three to five run at full width.  The
+first layer computes no input gradient (nothing lies below it).
+
+This module only owns buffers and the order of calls; all arithmetic happens
+in the library.
+"""
+import torch
+
+from . import binding as hp
+from . import synth
+
+CONV_ORDER = ("conv1", "conv2a", "conv2b", "conv3", "conv4", "conv5")
+
+
+def conv_flops(N, L):
+    """Nominal FLOPs of one pass of a layer: 2*N*K*P*Q*C*R*S (padding taps counted)."""
+    return 2.0 * N * L["K"] * L["P"] * L["Q"] * L["C"] * L["R"] * L["S"]
+
+
+def stack_flops(N):
+    """Nominal conv FLOPs of one forward+backward step of the stack."""
+    Ls = synth.LAYERS
+    total = 2 * conv_flops(N, Ls["conv1"])                    # fwd + wgrad
+    total += 2 * 3 * conv_flops(N, Ls["conv2"])               # two columns, three passes
+    for name in ("conv3", "conv4", "conv5"):
+        total += 3 * conv_flops(N, Ls[name])
+    return total
+
+
+class ConvStack:
+    def __init__(self, N, seed=synth.SEED_BASE + 64, device="cuda"):
+        self.N = N
+        Ls = synth.LAYERS
+        f32 = dict(dtype=torch.float32, device=device)
+
+        def t(a):
+            return torch.from_numpy(a).to(device)
+
+        self.x0 = t(synth.gaussian((N, 3, 224, 224), seed + 0))
+        self.w = {
+            "conv1": t(synth.gaussian((96, 3, 11, 11), seed + 1, synth.STD_FILTER)),
+            "conv2a": t(synth.gaussian((128, 48, 5, 5), seed + 2, synth.STD_FILTER)),
+            "conv2b": t(synth.gaussian((128, 48, 5, 5), seed + 3, synth.STD_FILTER)),
+            "conv3": t(synth.gaussian((384, 256, 3, 3), seed + 4, synth.STD_FILTER)),
+            "conv4": t(synth.gaussian((384, 384, 3, 3), seed + 5, synth.STD_FILTER)),
+            "conv5": t(synth.gaussian((256, 384, 3, 3), seed + 6, synth.STD_FILTER)),
+        }
+        self.g5 = t(synth.gaussian((N, 256, 6, 6), seed + 7))
+        self.dw = {k: torch.empty_like(v) for k, v in self.w.items()}
+        # activations (ReLU runs in place on the conv output)
+        self.y1 = torch.empty((N, 96, 55, 55), **f32)
+        self.a1 = torch.empty((N, 96, 27, 27), **f32)
+        self.y2 = torch.empty((N, 256, 27, 27), **f32)
+        self.a2 = torch.empty((N, 256, 13, 13), **f32)
+        self.y3 = torch.empty((N, 384, 13, 13), **f32)
+        self.y4 = torch.empty((N, 384, 13, 13), **f32)
+        self.y5 = torch.empty((N, 256, 13, 13), **f32)
+        self.a5 = torch.empty((N, 256, 6, 6), **f32)
+        # gradients
+        self.dy5 = torch.empty_like(self.y5)
+        self.dy4 = torch.empty_like(self.y4)
+        self.dy3 = torch.empty_like(self.y3)
+        self.da2 = torch.empty_like(self.a2)
+        self.dy2 = torch.empty_like(self.y2)
+        self.da1 = torch.empty_like(self.a1)
+        self.dy1 = torch.empty_like(self.y1)
+        self.ws = hp.Workspace(device)
+        self.timers = None          # optional dict name -> (start, stop) events per conv call
+
+    # -- helpers ------------------------------------------------------------
+    def _timed(self, key, fn):
+        if self.timers is None:
+            return fn()
+        s, e = self.timers.setdefault(key, (torch.cuda.Event(enable_timing=True),
+                                            torch.cuda.Event(enable_timing=True)))
+        s.record()
+        out = fn()
+        e.record()
+        return out
+
+    def forward(self):
+        w, ws = self.w, self.ws
+        self._timed(("conv1", "fwd"), lambda: hp.conv_fwd(self.x0, w["conv1"], 4, 2, y=self.y1, ws=ws))
+        hp.relu_fwd(self.y1, self.y1)
+        hp.maxpool3x3s2_fwd(self.y1, self.a1)
+        self._timed(("conv2a", "fwd"),
+                    lambda: hp.conv_fwd(self.a1[:, :48], w["conv2a"], 1, 2, y=self.y2[:, :128], ws=ws))
+        self._timed(("conv2b", "fwd"),
+                    lambda: hp.conv_fwd(self.a1[:, 48:], w["conv2b"], 1, 2, y=self.y2[:, 128:], ws=ws))
+        hp.relu_fwd(self.y2, self.y2)
+        hp.maxpool3x3s2_fwd(self.y2, self.a2)
+        self._timed(("conv3", "fwd"), lambda: hp.conv_fwd(self.a2, w["conv3"], 1, 1, y=self.y3, ws=ws))
+        hp.relu_fwd(self.y3, self.y3)
+        self._timed(("conv4", "fwd"), lambda: hp.conv_fwd(self.y3, w["conv4"], 1, 1, y=self.y4, ws=ws))
+        hp.relu_fwd(self.y4, self.y4)
+        self._timed(("conv5", "fwd"), lambda: hp.conv_fwd(self.y4, w["conv5"], 1, 1, y=self.y5, ws=ws))
+        hp.relu_fwd(self.y5, self.y5)
+        hp.maxpool3x3s2_fwd(self.y5, self.a5)
+        return self.a5
+
+    def backward(self):
+        w, dw, ws = self.w, self.dw, self.ws
+        hp.maxpool3x3s2_bwd(self.y5, self.g5, self.dy5)
+        hp.relu_bwd(self.y5, self.dy5, self.dy5)
+        self._timed(("conv5", "wgrad"),
+                    lambda: hp.conv_bwd_filter(self.y4, self.dy5, 3, 3, 1, 1, dw=dw["conv5"], ws=ws))
+        self._timed(("conv5", "dgrad"),
+                    lambda: hp.conv_bwd_data(self.dy5, w["conv5"], 13, 13, 1, 1, dx=self.dy4, ws=ws))
+        hp.relu_bwd(self.y4, self.dy4, self.dy4)
+        self._timed(("conv4", "wgrad"),
+                    lambda: hp.conv_bwd_filter(self.y3, self.dy4, 3, 3, 1, 1, dw=dw["conv4"], ws=ws))
+        self._timed(("conv4", "dgrad"),
+                    lambda: hp.conv_bwd_data(self.dy4, w["conv4"], 13, 13, 1, 1, dx=self.dy3, ws=ws))
+        hp.relu_bwd(self.y3, self.dy3, self.dy3)
+        self._timed(("conv3", "wgrad"),
+                    lambda: hp.conv_bwd_filter(self.a2, self.dy3, 3, 3, 1, 1, dw=dw["conv3"], ws=ws))
+        self._timed(("conv3", "dgrad"),
+                    lambda: hp.conv_bwd_data(self.dy3, w["conv3"], 13, 13, 1, 1, dx=self.da2, ws=ws))
+        hp.maxpool3x3s2_bwd(self.y2, self.da2, self.dy2)
+        hp.relu_bwd(self.y2, self.dy2, self.dy2)
+        for col, (c0, k0) in (("conv2a", (0, 0)), ("conv2b", (48, 128))):
+            xs, gs = self.a1[:, c0:c0 + 48], self.dy2[:, k0:k0 + 128]
+            self._timed((col, "wgrad"),
+                        lambda: hp.conv_bwd_filter(xs, gs, 5, 5, 1, 2, dw=dw[col], ws=ws))
+            self._timed((col, "dgrad"),
+                        lambda: hp.conv_bwd_data(gs, w[col], 27, 27, 1, 2, dx=self.da1[:, c0:c0 + 48], ws=ws))
+        hp.maxpool3x3s2_bwd(self.y1, self.da1, self.dy1)
+        hp.relu_bwd(self.y1, self.dy1, self.dy1)
+        self._timed(("conv1", "wgrad"),
+                    lambda: hp.conv_bwd_filter(self.x0, self.dy1, 11, 11, 4, 2, dw=dw["conv1"], ws=ws))
+        return dw
+
+    def step(self):
+        self.forward()
+        return self.backward()
