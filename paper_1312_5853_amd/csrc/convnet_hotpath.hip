@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include "../../include/convnet_hotpath.h"
@@ -154,6 +155,10 @@ struct ColGemmArgs {
 
 enum { kGatherDirect = 0, kGatherStridedBwd = 1 };
 
+#ifdef CONVNET_PHASE_PROBE
+__device__ long long *g_probe = nullptr;
+#endif
+
 template <int TM, int TN, int WM, int WN, int GATHER>
 __global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
 {
@@ -266,17 +271,44 @@ __global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
+#ifdef CONVNET_PHASE_PROBE
+    long long pr_t0 = __builtin_readcyclecounter(), pr_a = 0, pr_b = 0, pr_c = 0, pr_d = 0;
+#endif
     load_step(0);
     store_step(0);
     __syncthreads();
     for (int chunk = 0; chunk < p.nchunks; ++chunk) {
         const int buf = chunk & 1;
         const bool more = chunk + 1 < p.nchunks;
+#ifdef CONVNET_PHASE_PROBE
+        long long t0 = __builtin_readcyclecounter();
+#endif
         if (more) load_step(chunk + 1);
+#ifdef CONVNET_PHASE_PROBE
+        long long t1 = __builtin_readcyclecounter();
+#endif
         mma_step<TM, TN>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
+#ifdef CONVNET_PHASE_PROBE
+        long long t2 = __builtin_readcyclecounter();
+#endif
         if (more) store_step(buf ^ 1);
+#ifdef CONVNET_PHASE_PROBE
+        long long t3 = __builtin_readcyclecounter();
+#endif
         __syncthreads();
+#ifdef CONVNET_PHASE_PROBE
+        long long t4 = __builtin_readcyclecounter();
+        pr_a += t1 - t0; pr_b += t2 - t1; pr_c += t3 - t2; pr_d += t4 - t3;
+#endif
     }
+#ifdef CONVNET_PHASE_PROBE
+    if (tid == 0 && g_probe) {
+        long long *o = g_probe + (size_t)bid * 8;
+        o[0] = pr_t0; o[1] = __builtin_readcyclecounter(); o[2] = pr_a; o[3] = pr_b; o[4] = pr_c; o[5] = pr_d;
+        o[6] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));    // HW_ID
+        o[7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));   // XCC_ID
+    }
+#endif
 
     // --- epilogue.  Accumulator register v of lane l holds row
     // 8*(v/4) + 4*(l/32) + v%4 and column l%32 of its 32 x 32 tile.
@@ -299,6 +331,171 @@ __global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Forward / stride-1 backward-data when the reduction channel count is a
+// multiple of 16: each 16-deep step is one filter tap (r, s) and 16 consecutive
+// channels, so the padding test and the address of a thread's column are
+// computed once per step and its taps differ only by the channel stride.
+// Steps run channel-block-major, taps inside ((cb, r, s) order) so the nine or
+// twenty-five shifted reads of a channel block hit the same cache lines.
+// ---------------------------------------------------------------------------
+struct ColGemmFastArgs {
+    const float *At;      // filters as [cb][r][s][Mpad][16 channels]
+    const float *src;
+    float *dst;
+    int M, Mpad;
+    int cblocks, R, S;    // reduction: cblocks * R * S steps of 16 channels
+    int sign;             // +1 forward (reads hb + r), -1 backward-data (reads hb - r)
+    int plane_bytes;      // LH*LW*4: channel stride of the gathered tensor
+    int OH, OW, LH, LW;
+    int ncols, src_bs, dst_bs, mul, add;
+    int mtiles, ntiles;
+    FastDiv div_plane, div_ow;
+};
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFastArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int EPT = BN / 16;
+    constexpr int A4 = BM * 4;
+    constexpr int A4T = (A4 + kThreads - 1) / kThreads;
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
+
+    const int bid = blockIdx.x;
+    const int xcd = bid & 7, loc = bid >> 3;
+    const int mt = loc % p.mtiles;
+    const int nt = (loc / p.mtiles) * 8 + xcd;
+    if (nt >= p.ntiles) return;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int jc = tid % BN;
+    const int grp = uniform(tid / BN);
+    int hb, wb, base;
+    {
+        const int j = n0 + jc;
+        const bool colok = j < p.ncols;
+        const int jj = colok ? j : 0;
+        const int n = (int)fastdiv((uint32_t)jj, p.div_plane);
+        const int rem = jj - n * (p.OH * p.OW);
+        const int oh = (int)fastdiv((uint32_t)rem, p.div_ow);
+        const int ow = rem - oh * p.OW;
+        hb = oh * p.mul + p.add;
+        wb = ow * p.mul + p.add;
+        base = 4 * (n * p.src_bs + hb * p.LW + wb) + grp * EPT * p.plane_bytes;
+        if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
+    }
+    const char *src_bytes = reinterpret_cast<const char *>(p.src);
+    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * kChunk) + tid;
+    const size_t a_step = (size_t)p.Mpad * (kChunk / 4);      // f32x4 per step
+
+    f32x4 areg[A4T];
+    float breg[EPT];
+    bool bok;
+    int r = 0, s = 0, cboff = 0;     // next step to load: tap (r, s), channel-block byte offset
+
+    auto load_step = [&]() {
+#pragma unroll
+        for (int i = 0; i < A4T; ++i)
+            if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
+        a_ptr += a_step;
+        const int dr = p.sign * r, ds = p.sign * s;
+        const int hh = hb + dr, ww = wb + ds;
+        bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+        const int a0 = bok ? base + cboff + 4 * (dr * p.LW + ds) : 0;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
+        // advance (scalar): taps inside a channel block, then the next block
+        if (++s == p.S) { s = 0; if (++r == p.R) { r = 0; cboff += kChunk * p.plane_bytes; } }
+    };
+
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < A4T; ++i) {
+            int idx = tid + i * kThreads;
+            if (A4 % kThreads == 0 || idx < A4)
+                *reinterpret_cast<f32x4 *>(&As[buf][(idx >> 2) * kPitch + (idx & 3) * 4]) = areg[i];
+        }
+        float *brow = &Bs[buf][jc * kPitch + grp * EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; e += 4) {
+            f32x4 v = {bok ? breg[e] : 0.f, bok ? breg[e + 1] : 0.f, bok ? breg[e + 2] : 0.f,
+                       bok ? breg[e + 3] : 0.f};
+            *reinterpret_cast<f32x4 *>(brow + e) = v;
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int nsteps = p.cblocks * p.R * p.S;
+    load_step();
+    store_step(0);
+    __syncthreads();
+    for (int step = 0; step < nsteps - 1; ++step) {
+        const int buf = step & 1;
+        load_step();
+        mma_step<TM, TN>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
+        store_step(buf ^ 1);
+        __syncthreads();
+    }
+    mma_step<TM, TN>(As[(nsteps - 1) & 1], Bs[(nsteps - 1) & 1], wm * TM * 32, wn * TN * 32, lane, acc);
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int plane = p.OH * p.OW;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+        const int n = (int)fastdiv((uint32_t)col, p.div_plane);
+        const int rem = col - n * plane;
+        float *out = p.dst + (size_t)n * p.dst_bs + rem;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.M) out[(size_t)row * plane] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// Filters for colgemm_fast_kernel: wt[((cb*R + r)*S + s)][Mpad][16], element e = channel cb*16+e.
+//   transposed = 0: row m = filter k, channel = input channel c   (forward)
+//   transposed = 1: row m = input channel c, channel = filter k   (backward-data)
+__global__ void relayout_filters_cblk(const float *__restrict__ w, float *__restrict__ wt, int M, int Mpad,
+                                      int cblocks, int RS, int C, int transposed)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)cblocks * RS * Mpad * kChunk;
+    if (i >= total) return;
+    int e = (int)(i % kChunk);
+    int64_t t = i / kChunk;
+    int m = (int)(t % Mpad);
+    t /= Mpad;
+    int rs = (int)(t % RS);
+    int cb = (int)(t / RS);
+    int ch = cb * kChunk + e;
+    float v = 0.f;
+    if (m < M) v = transposed ? w[((int64_t)ch * C + m) * RS + rs] : w[((int64_t)m * C + ch) * RS + rs];
+    wt[i] = v;
 }
 
 // ---------------------------------------------------------------------------
@@ -538,13 +735,22 @@ int check_launch()
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+static int dbg_dyn_lds() { static int v = -1; if (v < 0) { const char *e = getenv("CONVNET_DYN_LDS"); v = e ? atoi(e) : 0; } return v; }
 template <int GATHER>
 void launch_colgemm(const TileShape &t, const ColGemmArgs &a, int grid, hipStream_t st)
 {
-    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_kernel<2, 2, 2, 2, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_kernel<2, 2, 2, 2, GATHER>), dim3(grid), dim3(kThreads), dbg_dyn_lds(), st, a);
     else if (t.TM == 3) hipLaunchKernelGGL((colgemm_kernel<3, 1, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
     else if (t.TM == 2) hipLaunchKernelGGL((colgemm_kernel<2, 1, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
     else hipLaunchKernelGGL((colgemm_kernel<1, 2, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
+}
+
+void launch_colgemm_fast(const TileShape &t, const ColGemmFastArgs &a, int grid, hipStream_t st)
+{
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_fast_kernel<2, 2, 2, 2>), dim3(grid), dim3(kThreads), dbg_dyn_lds(), st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((colgemm_fast_kernel<3, 1, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
+    else if (t.TM == 2) hipLaunchKernelGGL((colgemm_fast_kernel<2, 1, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
+    else hipLaunchKernelGGL((colgemm_fast_kernel<1, 2, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
 }
 
 void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
@@ -595,6 +801,29 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
     const float *actf = as_f32(act, act_elems, pb.dtype, wsb, pl, 0, st);
     const float *wf = as_f32(w, (int64_t)pb.K * pb.C * RS, pb.dtype, wsb, pl, 1, st);
 
+    const int Cr = fwd ? pb.C : pb.K;          // channels of the gathered tensor
+    if (Cr % kChunk == 0 && (fwd || pb.stride == 1)) {
+        hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d((int64_t)pl.Mpad * pl.Kgpad, 256)), dim3(256), 0, st,
+                           wf, wt, pl.M, pl.Mpad, Cr / kChunk, RS, pb.C, fwd ? 0 : 1);
+        ColGemmFastArgs a;
+        a.At = wt; a.src = actf; a.dst = static_cast<float *>(out);
+        a.M = pl.M; a.Mpad = pl.Mpad; a.cblocks = Cr / kChunk; a.R = pb.R; a.S = pb.S;
+        if (fwd) {
+            a.sign = 1; a.OH = pb.P; a.OW = pb.Q; a.LH = pb.H; a.LW = pb.W;
+            a.src_bs = (int)pb.x_bs; a.dst_bs = (int)pb.y_bs; a.mul = pb.stride; a.add = -pb.pad;
+        } else {
+            a.sign = -1; a.OH = pb.H; a.OW = pb.W; a.LH = pb.P; a.LW = pb.Q;
+            a.src_bs = (int)pb.y_bs; a.dst_bs = (int)pb.x_bs; a.mul = 1; a.add = pb.pad;
+        }
+        a.plane_bytes = a.LH * a.LW * 4;
+        a.ncols = pb.N * a.OH * a.OW;
+        a.mtiles = pl.Mpad / pl.tile.bm();
+        a.ntiles = ceil_div(a.ncols, pl.tile.bn());
+        a.div_plane = make_fastdiv((uint32_t)(a.OH * a.OW));
+        a.div_ow = make_fastdiv((uint32_t)a.OW);
+        launch_colgemm_fast(pl.tile, a, a.mtiles * round_up(a.ntiles, 8), st);
+        return check_launch();
+    }
     if (fwd)
         hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len,
                            pl.Kg, RS, pb.S, pb.H * pb.W, pb.W, 1, 1);
@@ -663,6 +892,14 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &pb, const 
 }
 
 }  // namespace
+
+#ifdef CONVNET_PHASE_PROBE
+extern "C" int conv_debug_set_probe(void *buf)
+{
+    long long *p = static_cast<long long *>(buf);
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_probe), &p, sizeof(p));
+}
+#endif
 
 extern "C" {
 
