@@ -149,7 +149,7 @@ struct ColGemmArgs {
     int ncols;            // N*OH*OW
     int src_bs, dst_bs;   // batch strides in elements
     int mul, add;         // window origin: hb = oh*mul + add, wb = ow*mul + add
-    int mtiles, ntiles;
+    int mtiles, ntiles, tiles_per_xcd;
     FastDiv div_plane, div_ow, div_stride;
 };
 
@@ -172,14 +172,15 @@ __global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
     __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
 
-    // Work-groups are dealt round-robin to the 8 XCDs; give each XCD whole
-    // column tiles (all row tiles of a column tile share its gathered slice
-    // through that XCD's L2).
+    // Work-groups are dealt round-robin to the 8 XCDs.  Each XCD takes one
+    // contiguous eighth of the tile list (row tiles fastest), so the row tiles
+    // of a column tile share its gathered slice through one L2 and no XCD
+    // holds more than ceil(tiles / 8) tiles.
     const int bid = blockIdx.x;
-    const int xcd = bid & 7, loc = bid >> 3;
-    const int mt = loc % p.mtiles;
-    const int nt = (loc / p.mtiles) * 8 + xcd;
-    if (nt >= p.ntiles) return;
+    const int idx = bid >> 3;
+    const int tile = (bid & 7) * p.tiles_per_xcd + idx;
+    if (idx >= p.tiles_per_xcd || tile >= p.mtiles * p.ntiles) return;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -351,7 +352,7 @@ struct ColGemmFastArgs {
     int plane_bytes;      // LH*LW*4: channel stride of the gathered tensor
     int OH, OW, LH, LW;
     int ncols, src_bs, dst_bs, mul, add;
-    int mtiles, ntiles;
+    int mtiles, ntiles, tiles_per_xcd;
     FastDiv div_plane, div_ow;
 };
 
@@ -368,10 +369,10 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
 
     const int bid = blockIdx.x;
-    const int xcd = bid & 7, loc = bid >> 3;
-    const int mt = loc % p.mtiles;
-    const int nt = (loc / p.mtiles) * 8 + xcd;
-    if (nt >= p.ntiles) return;
+    const int idx = bid >> 3;
+    const int tile = (bid & 7) * p.tiles_per_xcd + idx;
+    if (idx >= p.tiles_per_xcd || tile >= p.mtiles * p.ntiles) return;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -401,22 +402,39 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
     f32x4 areg[A4T];
     float breg[EPT];
     bool bok;
+    int a0 = 0;
     int r = 0, s = 0, cboff = 0;     // next step to load: tap (r, s), channel-block byte offset
 
-    auto load_step = [&]() {
+    // The next step's loads are cut into slots that the main loop drops between
+    // consecutive matrix instructions, so their issue cost hides behind the
+    // 64-cycle MFMAs of the current step.
+    auto slot_tap = [&]() {          // padding test and column address of tap (r, s)
+        const int dr = p.sign * r, ds = p.sign * s;
+        const int hh = hb + dr, ww = wb + ds;
+        bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+        a0 = bok ? base + cboff + 4 * (dr * p.LW + ds) : 0;
+        s += 1;
+        const bool ws = s == p.S;
+        s = ws ? 0 : s;
+        r += ws ? 1 : 0;
+        const bool wr = r == p.R;
+        r = wr ? 0 : r;
+        cboff += wr ? kChunk * p.plane_bytes : 0;
+    };
+    auto slot_a = [&]() {            // filter slice: contiguous block
 #pragma unroll
         for (int i = 0; i < A4T; ++i)
             if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
         a_ptr += a_step;
-        const int dr = p.sign * r, ds = p.sign * s;
-        const int hh = hb + dr, ww = wb + ds;
-        bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
-        const int a0 = bok ? base + cboff + 4 * (dr * p.LW + ds) : 0;
+    };
+    auto slot_b = [&](int e) {       // one channel of the gathered column
+        breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
+    };
+    auto load_step = [&]() {
+        slot_tap();
+        slot_a();
 #pragma unroll
-        for (int e = 0; e < EPT; ++e)
-            breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
-        // advance (scalar): taps inside a channel block, then the next block
-        if (++s == p.S) { s = 0; if (++r == p.R) { r = 0; cboff += kChunk * p.plane_bytes; } }
+        for (int e = 0; e < EPT; ++e) slot_b(e);
     };
 
     auto store_step = [&](int buf) {
@@ -444,16 +462,74 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
     const int nsteps = p.cblocks * p.R * p.S;
+    const int l32_ = lane & 31, half_ = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32_) * kPitch + half_ * 8;
+    const int b_frag = (wn * TN * 32 + l32_) * kPitch + half_ * 8;
+    constexpr int NMMA = 8 * TM * TN;
+    constexpr int NSLOT = EPT + 2;                              // tap, filter slice, EPT channels
+    constexpr int SPM = (NSLOT + NMMA - 5) / (NMMA - 4);        // slots issued after each matrix instruction
+
+#ifdef CONVNET_PHASE_PROBE
+    long long pr_t0 = __builtin_readcyclecounter(), pr_a = 0, pr_b = 0, pr_c = 0, pr_d = 0;
+    long long pr_rt0 = wall_clock64();
+#endif
     load_step();
     store_step(0);
     __syncthreads();
     for (int step = 0; step < nsteps - 1; ++step) {
         const int buf = step & 1;
-        load_step();
-        mma_step<TM, TN>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
+#ifdef CONVNET_PHASE_PROBE
+        long long t0 = __builtin_readcyclecounter();
+#endif
+        f32x4 fa[TM][2], fb[TN][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[buf][a_frag + i * 32 * kPitch]);
+            fa[i][0] = q[0]; fa[i][1] = q[1];
+        }
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[buf][b_frag + jn * 32 * kPitch]);
+            fb[jn][0] = q[0]; fb[jn][1] = q[1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                              acc[i][jn], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                if (q == 0) slot_tap();
+                else if (q == 1) slot_a();
+                else slot_b(q - 2);
+            }
+            if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+        }
+#ifdef CONVNET_PHASE_PROBE
+        long long t2 = __builtin_readcyclecounter();
+        __builtin_amdgcn_sched_barrier(0);
+#endif
         store_step(buf ^ 1);
+#ifdef CONVNET_PHASE_PROBE
+        __builtin_amdgcn_sched_barrier(0);
+        long long t3 = __builtin_readcyclecounter();
+#endif
         __syncthreads();
+#ifdef CONVNET_PHASE_PROBE
+        long long t4 = __builtin_readcyclecounter();
+        pr_b += t2 - t0; pr_c += t3 - t2; pr_d += t4 - t3;
+#endif
     }
+#ifdef CONVNET_PHASE_PROBE
+    if (tid == 0 && g_probe) {
+        long long *o = g_probe + (size_t)bid * 8;
+        o[0] = pr_t0; o[1] = __builtin_readcyclecounter(); o[2] = pr_rt0 + pr_a; o[3] = wall_clock64(); o[4] = pr_c; o[5] = pr_d;
+        o[6] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
+        o[7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));
+    }
+#endif
     mma_step<TM, TN>(As[(nsteps - 1) & 1], Bs[(nsteps - 1) & 1], wm * TM * 32, wn * TN * 32, lane, acc);
 
     const int l32 = lane & 31, half = lane >> 5;
@@ -735,22 +811,47 @@ int check_launch()
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
-static int dbg_dyn_lds() { static int v = -1; if (v < 0) { const char *e = getenv("CONVNET_DYN_LDS"); v = e ? atoi(e) : 0; } return v; }
-template <int GATHER>
-void launch_colgemm(const TileShape &t, const ColGemmArgs &a, int grid, hipStream_t st)
+static int dbg_env(const char *name, int dflt) { const char *e = getenv(name); return e ? atoi(e) : dflt; }
+
+// Tiles are spread evenly over the 8 XCDs (32 CUs each).  When that gives at
+// most `cap` <= 3 work-groups per CU, extra dynamic LDS is requested so that no
+// CU can hold more than `cap`: the dispatcher is then forced to balance, and
+// the launch ends when the evenly loaded CUs end instead of waiting for a CU
+// that was handed one work-group more.
+struct GridPlan { int tiles_per_xcd, grid, dyn_lds; };
+
+GridPlan plan_grid(int tiles, const TileShape &t)
 {
-    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_kernel<2, 2, 2, 2, GATHER>), dim3(grid), dim3(kThreads), dbg_dyn_lds(), st, a);
-    else if (t.TM == 3) hipLaunchKernelGGL((colgemm_kernel<3, 1, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
-    else if (t.TM == 2) hipLaunchKernelGGL((colgemm_kernel<2, 1, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((colgemm_kernel<1, 2, 1, 4, GATHER>), dim3(grid), dim3(kThreads), 0, st, a);
+    GridPlan g;
+    g.tiles_per_xcd = ceil_div(tiles, 8);
+    g.grid = 8 * g.tiles_per_xcd;
+    int cap = ceil_div(g.tiles_per_xcd, 32);
+    cap = dbg_env("CONVNET_CAP", cap);
+    const int static_lds = 2 * (t.bm() + t.bn()) * kPitch * 4;
+    int total = static_lds;
+    if (cap == 3) total = 52 * 1024;
+    else if (cap <= 2) total = 64 * 1024;
+    g.dyn_lds = total > static_lds ? total - static_lds : 0;
+    return g;
 }
 
-void launch_colgemm_fast(const TileShape &t, const ColGemmFastArgs &a, int grid, hipStream_t st)
+template <int GATHER>
+void launch_colgemm(const TileShape &t, const ColGemmArgs &a, const GridPlan &g, hipStream_t st)
 {
-    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_fast_kernel<2, 2, 2, 2>), dim3(grid), dim3(kThreads), dbg_dyn_lds(), st, a);
-    else if (t.TM == 3) hipLaunchKernelGGL((colgemm_fast_kernel<3, 1, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
-    else if (t.TM == 2) hipLaunchKernelGGL((colgemm_fast_kernel<2, 1, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((colgemm_fast_kernel<1, 2, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
+    const dim3 grid(g.grid), block(kThreads);
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_kernel<2, 2, 2, 2, GATHER>), grid, block, g.dyn_lds, st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((colgemm_kernel<3, 1, 1, 4, GATHER>), grid, block, g.dyn_lds, st, a);
+    else if (t.TM == 2) hipLaunchKernelGGL((colgemm_kernel<2, 1, 1, 4, GATHER>), grid, block, g.dyn_lds, st, a);
+    else hipLaunchKernelGGL((colgemm_kernel<1, 2, 1, 4, GATHER>), grid, block, g.dyn_lds, st, a);
+}
+
+void launch_colgemm_fast(const TileShape &t, const ColGemmFastArgs &a, const GridPlan &g, hipStream_t st)
+{
+    const dim3 grid(g.grid), block(kThreads);
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_fast_kernel<2, 2, 2, 2>), grid, block, g.dyn_lds, st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((colgemm_fast_kernel<3, 1, 1, 4>), grid, block, g.dyn_lds, st, a);
+    else if (t.TM == 2) hipLaunchKernelGGL((colgemm_fast_kernel<2, 1, 1, 4>), grid, block, g.dyn_lds, st, a);
+    else hipLaunchKernelGGL((colgemm_fast_kernel<1, 2, 1, 4>), grid, block, g.dyn_lds, st, a);
 }
 
 void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
@@ -821,7 +922,9 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
         a.ntiles = ceil_div(a.ncols, pl.tile.bn());
         a.div_plane = make_fastdiv((uint32_t)(a.OH * a.OW));
         a.div_ow = make_fastdiv((uint32_t)a.OW);
-        launch_colgemm_fast(pl.tile, a, a.mtiles * round_up(a.ntiles, 8), st);
+        const GridPlan g = plan_grid(a.mtiles * a.ntiles, pl.tile);
+        a.tiles_per_xcd = g.tiles_per_xcd;
+        launch_colgemm_fast(pl.tile, a, g, st);
         return check_launch();
     }
     if (fwd)
@@ -852,9 +955,10 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
     a.div_plane = make_fastdiv((uint32_t)(a.OH * a.OW));
     a.div_ow = make_fastdiv((uint32_t)a.OW);
     a.div_stride = make_fastdiv((uint32_t)pb.stride);
-    const int grid = a.mtiles * round_up(a.ntiles, 8);
-    if (!fwd && pb.stride > 1) launch_colgemm<kGatherStridedBwd>(pl.tile, a, grid, st);
-    else launch_colgemm<kGatherDirect>(pl.tile, a, grid, st);
+    const GridPlan g = plan_grid(a.mtiles * a.ntiles, pl.tile);
+    a.tiles_per_xcd = g.tiles_per_xcd;
+    if (!fwd && pb.stride > 1) launch_colgemm<kGatherStridedBwd>(pl.tile, a, g, st);
+    else launch_colgemm<kGatherDirect>(pl.tile, a, g, st);
     return check_launch();
 }
 

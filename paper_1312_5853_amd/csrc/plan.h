@@ -7,6 +7,7 @@
 
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "fastdiv.h"
 
@@ -130,6 +131,10 @@ inline Plan make_plan(int op, const Problem &pb)
     else if (op == kOpBwdData) { pl.M = pb.C; pl.Kg = pb.K * RS; }
     else { pl.M = pb.K; pl.Kg = pb.C * RS; }
     pl.tile = pick_tile(pl.M);
+    if (const char *e = getenv("CONVNET_FORCE_TILE")) {
+        const TileShape cand[4] = {kTile128x128, kTile96x128, kTile64x128, kTile32x256};
+        pl.tile = cand[atoi(e) & 3];
+    }
     pl.Mpad = round_up(pl.M, pl.tile.bm());
     pl.Kgpad = round_up(pl.Kg, kChunk);
     pl.tab_len = round_up(pl.Kg, kTapTablePad);
