@@ -708,6 +708,203 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
     }
 }
 
+// ---------------------------------------------------------------------------
+// Backward-filter when C is a multiple of 16.  The GEMM columns are taken in
+// (r, s, c) order, c fastest, so the rows a thread stages (a block of BN/16
+// consecutive columns) are consecutive channels of ONE filter tap: one padding
+// test and one base address per step, channel stride between its loads -- the
+// same economy as colgemm_fast_kernel.  Partial sums land in the workspace as
+// [split][K][R*S*C]; finish_wgrad adds the splits in order and writes KCRS.
+// ---------------------------------------------------------------------------
+struct WgradFastArgs {
+    const float *dy;
+    const float *x;
+    float *part;          // [nsplit][K][ncols], columns in (r, s, c) order
+    int K, C, S, ncols;   // ncols = R*S*C
+    int P, Q, H, W, stride, pad;
+    int dy_bs, x_bs;
+    int J, chunks_per_split;
+    int mtiles, ntiles, nunits, units_per_xcd;
+    int x_plane_bytes, y_plane_bytes;
+    FastDiv div_plane, div_q, div_c;
+};
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int RA = BM / 16, RB = BN / 16;
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.units_per_xcd + idx;
+    if (idx >= p.units_per_xcd || unit >= p.nunits) return;
+    const int tiles = p.mtiles * p.ntiles;
+    const int split = unit / tiles;
+    const int tile = unit - split * tiles;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int jj = tid & 15, g = tid >> 4;
+    const int PQ = p.P * p.Q;
+
+    // A rows (filters k): a block of RA consecutive rows; rows past K are clamped
+    // for the address and zeroed by a_rows
+    const int arow0 = m0 + g * RA;
+    const int a_rows = min(max(p.K - arow0, 0), RA);
+    int a_off[RA];
+#pragma unroll
+    for (int i = 0; i < RA; ++i) a_off[i] = min(arow0 + i, p.K - 1) * p.y_plane_bytes;
+
+    // B rows (columns of dw): RB consecutive channels of one tap
+    const int col0 = n0 + g * RB;
+    const bool col_ok = col0 < p.ncols;
+    int tap_r, tap_s, b_off;
+    {
+        const int cc = col_ok ? col0 : 0;
+        const int rs = (int)fastdiv((uint32_t)cc, p.div_c);
+        const int c0 = cc - rs * p.C;
+        tap_r = rs / p.S;
+        tap_s = rs - tap_r * p.S;
+        b_off = c0 * p.x_plane_bytes + 4 * (tap_r * p.W + tap_s);
+    }
+
+    const int jbeg = split * p.chunks_per_split * kChunk;
+    const int jend = min(jbeg + p.chunks_per_split * kChunk, p.J);
+    const int nsteps = (jend - jbeg + kChunk - 1) / kChunk;
+
+    const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
+    const char *x_bytes = reinterpret_cast<const char *>(p.x);
+    float areg[RA], breg[RB];
+    int a_lim = 0, abase = 0, bbase = 0, jnext = jbeg + jj;
+    bool bok = false;
+
+    auto slot_pos = [&]() {          // where this thread's reduction position sits
+        const bool jok = jnext < jend;
+        const int js = jok ? jnext : jbeg;
+        const int n = (int)fastdiv((uint32_t)js, p.div_plane);
+        const int pq = js - n * PQ;
+        const int pp = (int)fastdiv((uint32_t)pq, p.div_q);
+        const int qq = pq - pp * p.Q;
+        const int hb = pp * p.stride - p.pad, wb = qq * p.stride - p.pad;
+        a_lim = jok ? a_rows : 0;
+        abase = 4 * (n * p.dy_bs + pq);
+        bok = jok & col_ok & ((unsigned)(hb + tap_r) < (unsigned)p.H) & ((unsigned)(wb + tap_s) < (unsigned)p.W);
+        bbase = bok ? 4 * (n * p.x_bs + hb * p.W + wb) + b_off : 0;
+        jnext += kChunk;
+    };
+    auto slot_a = [&](int i) {
+        areg[i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(abase + a_off[i]));
+    };
+    auto slot_b = [&](int i) {
+        breg[i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(bbase + i * p.x_plane_bytes));
+    };
+    auto load_step = [&]() {
+        slot_pos();
+#pragma unroll
+        for (int i = 0; i < RA; ++i) slot_a(i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) slot_b(i);
+    };
+    auto store_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < RA; ++i) As[buf][(g * RA + i) * kPitch + jj] = i < a_lim ? areg[i] : 0.f;
+#pragma unroll
+        for (int i = 0; i < RB; ++i) Bs[buf][(g * RB + i) * kPitch + jj] = bok ? breg[i] : 0.f;
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * kPitch + half * 8;
+    const int b_frag = (wn * TN * 32 + l32) * kPitch + half * 8;
+    constexpr int NMMA = 8 * TM * TN;
+    constexpr int NSLOT = 1 + RA + RB;
+    constexpr int SPM = (NSLOT + NMMA - 5) / (NMMA - 4);
+
+    if (nsteps > 0) {
+        load_step();
+        store_step(0);
+    }
+    __syncthreads();
+    for (int step = 0; step < nsteps - 1; ++step) {
+        const int buf = step & 1;
+        f32x4 fa[TM][2], fb[TN][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[buf][a_frag + i * 32 * kPitch]);
+            fa[i][0] = q[0]; fa[i][1] = q[1];
+        }
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[buf][b_frag + jn * 32 * kPitch]);
+            fb[jn][0] = q[0]; fb[jn][1] = q[1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                              acc[i][jn], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                if (q == 0) slot_pos();
+                else if (q - 1 < RA) slot_a(q - 1);
+                else slot_b(q - 1 - RA);
+            }
+            if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+        }
+        store_step(buf ^ 1);
+        __syncthreads();
+    }
+    if (nsteps > 0)
+        mma_step<TM, TN>(As[(nsteps - 1) & 1], Bs[(nsteps - 1) & 1], wm * TM * 32, wn * TN * 32, lane, acc);
+
+    float *out = p.part + (size_t)split * p.K * p.ncols;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.ncols + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// dw[k][c][rs] = part[0][k][rs*C + c] + part[1][k][rs*C + c] + ...  (fixed order)
+__global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int RS,
+                             int nsplit)
+{
+    const int ncols = RS * C;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= K * ncols) return;
+    const int k = i / ncols, col = i - k * ncols;
+    const int rs = col / C, c = col - rs * C;
+    float s = part[i];
+    for (int t = 1; t < nsplit; ++t) s += part[(size_t)t * K * ncols + i];
+    dw[((size_t)k * C + c) * RS + rs] = s;
+}
+
 // Fixed-order sum of the split partials: dw[i] = part[0][i] + part[1][i] + ...
 __global__ void reduce_partials(const float *__restrict__ part, float *__restrict__ dw, int count, int nsplit)
 {
@@ -862,6 +1059,15 @@ void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t 
     else hipLaunchKernelGGL((wgrad_kernel<1, 2, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
 }
 
+void launch_wgrad_fast(const TileShape &t, const WgradFastArgs &a, const GridPlan &g, hipStream_t st)
+{
+    const dim3 grid(g.grid), block(kThreads);
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((wgrad_fast_kernel<2, 2, 2, 2>), grid, block, g.dyn_lds, st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((wgrad_fast_kernel<3, 1, 1, 4>), grid, block, g.dyn_lds, st, a);
+    else if (t.TM == 2) hipLaunchKernelGGL((wgrad_fast_kernel<2, 1, 1, 4>), grid, block, g.dyn_lds, st, a);
+    else hipLaunchKernelGGL((wgrad_fast_kernel<1, 2, 1, 4>), grid, block, g.dyn_lds, st, a);
+}
+
 int grid1d(int64_t n, int block) { return (int)((n + block - 1) / block); }
 
 // Common front end of the three passes: checks, plan, workspace carving.
@@ -969,6 +1175,32 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &pb, const 
     const int RS = pb.R * pb.S;
     const float *xf = as_f32(x, (int64_t)pb.N * pb.x_bs, pb.dtype, wsb, pl, 0, st);
     const float *dyf = as_f32(dy, (int64_t)pb.N * pb.y_bs, pb.dtype, wsb, pl, 1, st);
+    if (pb.C % kChunk == 0) {
+        WgradFastArgs a;
+        a.dy = dyf; a.x = xf; a.part = reinterpret_cast<float *>(wsb + pl.part_off);
+        a.K = pb.K; a.C = pb.C; a.S = pb.S; a.ncols = pl.Kg;
+        a.P = pb.P; a.Q = pb.Q; a.H = pb.H; a.W = pb.W; a.stride = pb.stride; a.pad = pb.pad;
+        a.dy_bs = (int)pb.y_bs; a.x_bs = (int)pb.x_bs;
+        a.J = pb.N * pb.P * pb.Q;
+        a.chunks_per_split = pl.chunks_per_split;
+        a.mtiles = pl.Mpad / pl.tile.bm();
+        a.ntiles = ceil_div(pl.Kg, pl.tile.bn());
+        a.nunits = a.mtiles * a.ntiles * pl.nsplit;
+        const GridPlan g = plan_grid(a.nunits, pl.tile);
+        a.units_per_xcd = g.tiles_per_xcd;
+        a.x_plane_bytes = pb.H * pb.W * 4;
+        a.y_plane_bytes = pb.P * pb.Q * 4;
+        a.div_plane = make_fastdiv((uint32_t)(pb.P * pb.Q));
+        a.div_q = make_fastdiv((uint32_t)pb.Q);
+        a.div_c = make_fastdiv((uint32_t)pb.C);
+        launch_wgrad_fast(pl.tile, a, g, st);
+        int rc = check_launch();
+        if (rc != kStatusOk) return rc;
+        const int count = pb.K * pl.Kg;
+        hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
+                           pb.K, pb.C, RS, pl.nsplit);
+        return check_launch();
+    }
     hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len, pl.Kg, RS,
                        pb.S, pb.H * pb.W, pb.W, 1, 1);
     WgradArgs a;

@@ -27,7 +27,7 @@ constexpr int kDtypeF32 = 0, kDtypeBf16 = 1;
 constexpr int kChunk = 16;            // reduction elements staged in LDS per step
 constexpr int kTapTablePad = 256;     // tap table length is rounded up to this
 constexpr int64_t kMaxSpanBytes = (int64_t)1 << 31;
-constexpr int kTargetGroups = 768;    // work-groups wanted in flight: 3 per CU on 256 CUs
+constexpr int kTargetGroups = 512;    // work-groups wanted in flight: 2 per CU on 256 CUs
 
 struct Problem {
     int N, C, H, W, K, R, S, stride, pad;
@@ -146,14 +146,16 @@ inline Plan make_plan(int op, const Problem &pb)
         const int64_t J = (int64_t)pb.N * pb.P * pb.Q;
         const int jchunks = (int)((J + kChunk - 1) / kChunk);
         const int tiles = (pl.Mpad / pl.tile.bm()) * ceil_div(pl.Kg, pl.tile.bn());
-        int want = ceil_div(kTargetGroups, tiles);
+        // as many splits as fill two work-groups per CU without exceeding them
+        int want = kTargetGroups / tiles;
         int most = jchunks / 8 > 0 ? jchunks / 8 : 1;     // at least 8 chunks of work per split
         int nsplit = want < most ? want : most;
         if (nsplit < 1) nsplit = 1;
         pl.chunks_per_split = ceil_div(jchunks, nsplit);
         pl.nsplit = ceil_div(jchunks, pl.chunks_per_split);
         pl.part_off = off;
-        pl.part_bytes = pl.nsplit > 1 ? (size_t)pl.nsplit * pb.K * pb.C * RS * 4 : 0;
+        const bool staged = pb.C % kChunk == 0;          // fast path always goes through the partials
+        pl.part_bytes = (pl.nsplit > 1 || staged) ? (size_t)pl.nsplit * pb.K * pb.C * RS * 4 : 0;
         off += round_up64(pl.part_bytes, 256);
     } else {
         pl.wt_off = off;
