@@ -159,6 +159,18 @@ int relu_bwd(const void *x, const void *dy, void *dx, int64_t count, void *strea
 int maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream);
 int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream);
 
+/*
+ * ReLU followed by the pooling above, fused (the conv1/conv2/conv5 tail of the
+ * stack), so that the activation never makes a pass of its own over HBM.
+ *   relu_maxpool3x3s2_fwd: y = maxpool3x3s2(relu(x)); x is the convolution
+ *       output and is left untouched.
+ *   relu_maxpool3x3s2_bwd: dx = relu_bwd(x, maxpool3x3s2_bwd(relu(x), dy)), the
+ *       gradient with respect to the convolution output x, from x itself.
+ * Both give exactly what the separate calls give.
+ */
+int relu_maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream);
+int relu_maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,6 +24,7 @@ EXPORTS = (
     "conv_fwd_ex", "conv_bwd_data_ex", "conv_bwd_filter_ex",
     "conv_workspace_bytes", "conv_status_string", "conv_last_hip_error",
     "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
+    "relu_maxpool3x3s2_fwd", "relu_maxpool3x3s2_bwd",
 )
 
 _lib = None
@@ -67,7 +68,10 @@ def lib():
     L.relu_bwd.argtypes = [vp, vp, vp, i64, vp]
     L.maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, vp]
     L.maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, vp]
-    for name in ("relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd"):
+    L.relu_maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, vp]
+    L.relu_maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, vp]
+    for name in ("relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd", "relu_maxpool3x3s2_fwd",
+                 "relu_maxpool3x3s2_bwd"):
         getattr(L, name).restype = i
     _lib = L
     return L
@@ -224,4 +228,22 @@ def maxpool3x3s2_bwd(x, dy, dx=None, stream=None):
         dx = torch.empty_like(x)
     _check(lib().maxpool3x3s2_bwd(_ptr(x), _ptr(dy), _ptr(dx), N * C, H, W, _stream_handle(stream)),
            "maxpool3x3s2_bwd")
+    return dx
+
+
+def relu_maxpool3x3s2_fwd(x, y=None, stream=None):
+    N, C, H, W = x.shape
+    if y is None:
+        y = torch.empty((N, C, (H - 3) // 2 + 1, (W - 3) // 2 + 1), dtype=x.dtype, device=x.device)
+    _check(lib().relu_maxpool3x3s2_fwd(_ptr(x), _ptr(y), N * C, H, W, _stream_handle(stream)),
+           "relu_maxpool3x3s2_fwd")
+    return y
+
+
+def relu_maxpool3x3s2_bwd(x, dy, dx=None, stream=None):
+    N, C, H, W = x.shape
+    if dx is None:
+        dx = torch.empty_like(x)
+    _check(lib().relu_maxpool3x3s2_bwd(_ptr(x), _ptr(dy), _ptr(dx), N * C, H, W, _stream_handle(stream)),
+           "relu_maxpool3x3s2_bwd")
     return dx

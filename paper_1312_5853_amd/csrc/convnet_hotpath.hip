@@ -918,17 +918,44 @@ __global__ void reduce_partials(const float *__restrict__ part, float *__restric
 // ---------------------------------------------------------------------------
 // Glue layers
 // ---------------------------------------------------------------------------
-__global__ void relu_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int64_t n)
+// four elements per thread where the pointers allow it, scalar tail otherwise
+__global__ void relu_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int64_t n, int vec)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) { float v = x[i]; y[i] = v > 0.f ? v : 0.f; }
+    if (vec) {
+        const int64_t n4 = n >> 2;
+        if (i < n4) {
+            f32x4 v = reinterpret_cast<const f32x4 *>(x)[i];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = v[k] > 0.f ? v[k] : 0.f;
+            reinterpret_cast<f32x4 *>(y)[i] = v;
+        }
+        const int64_t t = n4 * 4 + i;
+        if (i < (n & 3)) { float v = x[t]; y[t] = v > 0.f ? v : 0.f; }
+    } else if (i < n) {
+        float v = x[i];
+        y[i] = v > 0.f ? v : 0.f;
+    }
 }
 
 __global__ void relu_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
-                                float *__restrict__ dx, int64_t n)
+                                float *__restrict__ dx, int64_t n, int vec)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) dx[i] = x[i] > 0.f ? dy[i] : 0.f;
+    if (vec) {
+        const int64_t n4 = n >> 2;
+        if (i < n4) {
+            const f32x4 a = reinterpret_cast<const f32x4 *>(x)[i];
+            f32x4 g = reinterpret_cast<const f32x4 *>(dy)[i];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) g[k] = a[k] > 0.f ? g[k] : 0.f;
+            reinterpret_cast<f32x4 *>(dx)[i] = g;
+        }
+        const int64_t t = n4 * 4 + i;
+        if (i < (n & 3)) dx[t] = x[t] > 0.f ? dy[t] : 0.f;
+    } else if (i < n) {
+        dx[i] = x[i] > 0.f ? dy[i] : 0.f;
+    }
 }
 
 // index (within the plane) of the first maximum of the 3x3 window at (2i, 2j)
@@ -947,6 +974,7 @@ __device__ __forceinline__ int pool_argmax(const float *__restrict__ xp, int W, 
     return best;
 }
 
+template <bool RELU>
 __global__ void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int64_t total,
                                    int H, int W, int PH, int PW)
 {
@@ -958,12 +986,60 @@ __global__ void maxpool_fwd_kernel(const float *__restrict__ x, float *__restric
     int64_t pl = u / PH;
     float m;
     pool_argmax(x + pl * H * W, W, i, j, m);
-    y[t] = m;
+    y[t] = RELU ? (m > 0.f ? m : 0.f) : m;
 }
 
-// One thread per input element: it visits the (at most four) windows that
-// contain it, in row-major window order, and adds the gradient of each window
-// whose first maximum it is.  No atomics, fixed order.
+// Backward of the pooling (optionally of ReLU followed by pooling).  A
+// work-group stages a group of whole planes in LDS, finds every window's first
+// maximum once, then each input element adds the gradients of the (at most four)
+// windows that selected it, in row-major window order.  No atomics.
+// With RELU the input x is the pre-activation: the window maximum of relu(x)
+// sits where the maximum of x sits whenever it is positive, and a non-positive
+// maximum passes no gradient, so dx = [x > 0] * (pooled gradient routed by x).
+template <bool RELU>
+__global__ __launch_bounds__(256) void maxpool_bwd_tiled(const float *__restrict__ x, const float *__restrict__ dy,
+                                                          float *__restrict__ dx, int64_t planes, int H, int W,
+                                                          int PH, int PW, int group)
+{
+    extern __shared__ float pool_lds[];
+    const int HW = H * W, PP = PH * PW;
+    float *sx = pool_lds;                                   // group * HW values
+    int *sarg = reinterpret_cast<int *>(pool_lds + group * HW);   // group * PP window choices
+    for (int64_t pl0 = (int64_t)blockIdx.x * group; pl0 < planes; pl0 += (int64_t)gridDim.x * group) {
+        const int np = (int)min((int64_t)group, planes - pl0);
+        const float *xg = x + pl0 * HW;
+        const float *gg = dy + pl0 * PP;
+        float *og = dx + pl0 * HW;
+        for (int e = threadIdx.x; e < np * HW; e += 256) sx[e] = xg[e];
+        __syncthreads();
+        for (int o = threadIdx.x; o < np * PP; o += 256) {
+            const int pl = o / PP, rem = o - pl * PP;
+            const int i = rem / PW, j = rem - i * PW;
+            float m;
+            sarg[o] = pool_argmax(sx + pl * HW, W, i, j, m);
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < np * HW; e += 256) {
+            const int pl = e / HW, self = e - pl * HW;
+            const int h = self / W, w = self - h * W;
+            int i_lo = h >= 2 ? (h - 1) / 2 : 0, i_hi = min(h / 2, PH - 1);
+            int j_lo = w >= 2 ? (w - 1) / 2 : 0, j_hi = min(w / 2, PW - 1);
+            float sum = 0.f;
+            for (int i = i_lo; i <= i_hi; ++i)
+                for (int j = j_lo; j <= j_hi; ++j) {
+                    const int o = pl * PP + i * PW + j;
+                    if (sarg[o] == self) sum += gg[o];
+                }
+            if (RELU && !(sx[e] > 0.f)) sum = 0.f;
+            og[e] = sum;
+        }
+        __syncthreads();
+    }
+}
+
+// Fallback for planes too large to stage: one thread per input element
+// recomputes the windows that contain it.
+template <bool RELU>
 __global__ void maxpool_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
                                    float *__restrict__ dx, int64_t total, int H, int W, int PH, int PW)
 {
@@ -986,6 +1062,7 @@ __global__ void maxpool_bwd_kernel(const float *__restrict__ x, const float *__r
             float m;
             if (pool_argmax(xp, W, i, j, m) == self) s += gp[i * PW + j];
         }
+    if (RELU && !(xp[self] > 0.f)) s = 0.f;
     dx[t] = s;
 }
 
@@ -1227,6 +1304,57 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &pb, const 
     return rc;
 }
 
+int pool_checks(int64_t planes, int H, int W, int &PH, int &PW)
+{
+    if (planes <= 0 || H < 3 || W < 3) return kErrInvalidArg;
+    PH = (H - 3) / 2 + 1;
+    PW = (W - 3) / 2 + 1;
+    if ((double)planes * H * W * 4.0 >= (double)((int64_t)1 << 40) || (int64_t)H * W >= (1 << 30)) return kErrTooLarge;
+    return kStatusOk;
+}
+
+template <bool RELU>
+int pool_fwd_impl(const void *x, void *y, int64_t planes, int H, int W, void *stream)
+{
+    if (!x || !y) return kErrInvalidArg;
+    int PH, PW;
+    int rc = pool_checks(planes, H, W, PH, PW);
+    if (rc != kStatusOk) return rc;
+    if (!aligned(x, 4) || !aligned(y, 4)) return kErrMisaligned;
+    const int64_t total = planes * PH * PW;
+    hipLaunchKernelGGL(maxpool_fwd_kernel<RELU>, dim3(grid1d(total, 256)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const float *>(x), static_cast<float *>(y), total,
+                       H, W, PH, PW);
+    return check_launch();
+}
+
+template <bool RELU>
+int pool_bwd_impl(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream)
+{
+    if (!x || !dy || !dx) return kErrInvalidArg;
+    int PH, PW;
+    int rc = pool_checks(planes, H, W, PH, PW);
+    if (rc != kStatusOk) return rc;
+    if (!aligned(x, 4) || !aligned(dy, 4) || !aligned(dx, 4)) return kErrMisaligned;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int per_plane = H * W + PH * PW;                 // LDS words per staged plane
+    if (per_plane <= 12 * 1024) {
+        int group = 4096 / per_plane;                      // about 16 KB of planes per work-group
+        if (group < 1) group = 1;
+        int64_t blocks = (planes + group - 1) / group;
+        if (blocks > 256 * 16) blocks = 256 * 16;
+        hipLaunchKernelGGL(maxpool_bwd_tiled<RELU>, dim3((int)blocks), dim3(256), (size_t)group * per_plane * 4, st,
+                           static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx),
+                           planes, H, W, PH, PW, group);
+    } else {
+        const int64_t total = planes * H * W;
+        hipLaunchKernelGGL(maxpool_bwd_kernel<RELU>, dim3(grid1d(total, 256)), dim3(256), 0, st,
+                           static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx),
+                           total, H, W, PH, PW);
+    }
+    return check_launch();
+}
+
 }  // namespace
 
 #ifdef CONVNET_PHASE_PROBE
@@ -1319,8 +1447,10 @@ int relu_fwd(const void *x, void *y, int64_t count, void *stream)
     if (!x || !y || count < 0) return kErrInvalidArg;
     if (count == 0) return kStatusOk;
     if (!aligned(x, 4) || !aligned(y, 4)) return kErrMisaligned;
-    hipLaunchKernelGGL(relu_fwd_kernel, dim3(grid1d(count, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const float *>(x), static_cast<float *>(y), count);
+    const int vec = aligned(x, 16) && aligned(y, 16);
+    const int64_t threads = vec ? (count >> 2) + 4 : count;
+    hipLaunchKernelGGL(relu_fwd_kernel, dim3(grid1d(threads, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float *>(x), static_cast<float *>(y), count, vec);
     return check_launch();
 }
 
@@ -1329,45 +1459,32 @@ int relu_bwd(const void *x, const void *dy, void *dx, int64_t count, void *strea
     if (!x || !dy || !dx || count < 0) return kErrInvalidArg;
     if (count == 0) return kStatusOk;
     if (!aligned(x, 4) || !aligned(dy, 4) || !aligned(dx, 4)) return kErrMisaligned;
-    hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid1d(count, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx), count);
+    const int vec = aligned(x, 16) && aligned(dy, 16) && aligned(dx, 16);
+    const int64_t threads = vec ? (count >> 2) + 4 : count;
+    hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid1d(threads, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx), count,
+                       vec);
     return check_launch();
-}
-
-static int pool_checks(int64_t planes, int H, int W, int &PH, int &PW)
-{
-    if (planes <= 0 || H < 3 || W < 3) return kErrInvalidArg;
-    PH = (H - 3) / 2 + 1;
-    PW = (W - 3) / 2 + 1;
-    if ((double)planes * H * W * 4.0 >= (double)((int64_t)1 << 40)) return kErrTooLarge;
-    return kStatusOk;
 }
 
 int maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream)
 {
-    if (!x || !y) return kErrInvalidArg;
-    int PH, PW;
-    int rc = pool_checks(planes, H, W, PH, PW);
-    if (rc != kStatusOk) return rc;
-    if (!aligned(x, 4) || !aligned(y, 4)) return kErrMisaligned;
-    const int64_t total = planes * PH * PW;
-    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(grid1d(total, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const float *>(x), static_cast<float *>(y), total, H, W, PH, PW);
-    return check_launch();
+    return pool_fwd_impl<false>(x, y, planes, H, W, stream);
 }
 
 int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream)
 {
-    if (!x || !dy || !dx) return kErrInvalidArg;
-    int PH, PW;
-    int rc = pool_checks(planes, H, W, PH, PW);
-    if (rc != kStatusOk) return rc;
-    if (!aligned(x, 4) || !aligned(dy, 4) || !aligned(dx, 4)) return kErrMisaligned;
-    const int64_t total = planes * H * W;
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(grid1d(total, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx), total,
-                       H, W, PH, PW);
-    return check_launch();
+    return pool_bwd_impl<false>(x, dy, dx, planes, H, W, stream);
+}
+
+int relu_maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream)
+{
+    return pool_fwd_impl<true>(x, y, planes, H, W, stream);
+}
+
+int relu_maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream)
+{
+    return pool_bwd_impl<true>(x, dy, dx, planes, H, W, stream);
 }
 
 }  // extern "C"

@@ -55,7 +55,8 @@ class ConvStack:
         }
         self.g5 = t(synth.gaussian((N, 256, 6, 6), seed + 7))
         self.dw = {k: torch.empty_like(v) for k, v in self.w.items()}
-        # activations (ReLU runs in place on the conv output)
+        # activations (ReLU runs in place on y3, y4; y1, y2, y5 keep the pre-activation: their ReLU is fused
+        # into the pooling calls)
         self.y1 = torch.empty((N, 96, 55, 55), **f32)
         self.a1 = torch.empty((N, 96, 27, 27), **f32)
         self.y2 = torch.empty((N, 256, 27, 27), **f32)
@@ -89,27 +90,23 @@ class ConvStack:
     def forward(self):
         w, ws = self.w, self.ws
         self._timed(("conv1", "fwd"), lambda: hp.conv_fwd(self.x0, w["conv1"], 4, 2, y=self.y1, ws=ws))
-        hp.relu_fwd(self.y1, self.y1)
-        hp.maxpool3x3s2_fwd(self.y1, self.a1)
+        hp.relu_maxpool3x3s2_fwd(self.y1, self.a1)
         self._timed(("conv2a", "fwd"),
                     lambda: hp.conv_fwd(self.a1[:, :48], w["conv2a"], 1, 2, y=self.y2[:, :128], ws=ws))
         self._timed(("conv2b", "fwd"),
                     lambda: hp.conv_fwd(self.a1[:, 48:], w["conv2b"], 1, 2, y=self.y2[:, 128:], ws=ws))
-        hp.relu_fwd(self.y2, self.y2)
-        hp.maxpool3x3s2_fwd(self.y2, self.a2)
+        hp.relu_maxpool3x3s2_fwd(self.y2, self.a2)
         self._timed(("conv3", "fwd"), lambda: hp.conv_fwd(self.a2, w["conv3"], 1, 1, y=self.y3, ws=ws))
         hp.relu_fwd(self.y3, self.y3)
         self._timed(("conv4", "fwd"), lambda: hp.conv_fwd(self.y3, w["conv4"], 1, 1, y=self.y4, ws=ws))
         hp.relu_fwd(self.y4, self.y4)
         self._timed(("conv5", "fwd"), lambda: hp.conv_fwd(self.y4, w["conv5"], 1, 1, y=self.y5, ws=ws))
-        hp.relu_fwd(self.y5, self.y5)
-        hp.maxpool3x3s2_fwd(self.y5, self.a5)
+        hp.relu_maxpool3x3s2_fwd(self.y5, self.a5)
         return self.a5
 
     def backward(self):
         w, dw, ws = self.w, self.dw, self.ws
-        hp.maxpool3x3s2_bwd(self.y5, self.g5, self.dy5)
-        hp.relu_bwd(self.y5, self.dy5, self.dy5)
+        hp.relu_maxpool3x3s2_bwd(self.y5, self.g5, self.dy5)
         self._timed(("conv5", "wgrad"),
                     lambda: hp.conv_bwd_filter(self.y4, self.dy5, 3, 3, 1, 1, dw=dw["conv5"], ws=ws))
         self._timed(("conv5", "dgrad"),
@@ -124,16 +121,14 @@ class ConvStack:
                     lambda: hp.conv_bwd_filter(self.a2, self.dy3, 3, 3, 1, 1, dw=dw["conv3"], ws=ws))
         self._timed(("conv3", "dgrad"),
                     lambda: hp.conv_bwd_data(self.dy3, w["conv3"], 13, 13, 1, 1, dx=self.da2, ws=ws))
-        hp.maxpool3x3s2_bwd(self.y2, self.da2, self.dy2)
-        hp.relu_bwd(self.y2, self.dy2, self.dy2)
+        hp.relu_maxpool3x3s2_bwd(self.y2, self.da2, self.dy2)
         for col, (c0, k0) in (("conv2a", (0, 0)), ("conv2b", (48, 128))):
             xs, gs = self.a1[:, c0:c0 + 48], self.dy2[:, k0:k0 + 128]
             self._timed((col, "wgrad"),
                         lambda: hp.conv_bwd_filter(xs, gs, 5, 5, 1, 2, dw=dw[col], ws=ws))
             self._timed((col, "dgrad"),
                         lambda: hp.conv_bwd_data(gs, w[col], 27, 27, 1, 2, dx=self.da1[:, c0:c0 + 48], ws=ws))
-        hp.maxpool3x3s2_bwd(self.y1, self.da1, self.dy1)
-        hp.relu_bwd(self.y1, self.dy1, self.dy1)
+        hp.relu_maxpool3x3s2_bwd(self.y1, self.da1, self.dy1)
         self._timed(("conv1", "wgrad"),
                     lambda: hp.conv_bwd_filter(self.x0, self.dy1, 11, 11, 4, 2, dw=dw["conv1"], ws=ws))
         return dw

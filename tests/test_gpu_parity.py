@@ -288,3 +288,80 @@ def test_relu_and_pool_match_oracle():
     g = synth.gaussian((2, 3, 6, 6), 155)
     got = hp.maxpool3x3s2_bwd(dev(x), dev(g)).cpu().numpy()
     assert norm_err(got, oracle.maxpool3x3s2_bwd(x, g)) <= 1e-6
+
+
+def test_fused_relu_pool_matches_separate_oracle_calls():
+    """relu_maxpool3x3s2_fwd/bwd take the pre-activation and must equal ReLU then pooling (and back)."""
+    for (N, C, H, W) in [(3, 5, 55, 55), (2, 7, 27, 27), (9, 33, 13, 13), (1, 1, 3, 3), (2, 2, 8, 5), (1, 2, 120, 115)]:
+        x = synth.gaussian((N, C, H, W), 161)
+        x[0, 0, :3, :3] = -1.0                                  # a window with no positive entry
+        x[0, 0, 0, 0] = -0.5
+        xd = dev(x)
+        y = hp.relu_maxpool3x3s2_fwd(xd)
+        r = oracle.relu_fwd(x)
+        yo = oracle.maxpool3x3s2_fwd(r)
+        assert np.array_equal(y.cpu().numpy(), yo.astype(np.float32))
+        g = synth.gaussian(yo.shape, 162)
+        dx = hp.relu_maxpool3x3s2_bwd(xd, dev(g), dx=nan_like(x.shape))
+        want = oracle.relu_bwd(x, oracle.maxpool3x3s2_bwd(r, g))
+        assert norm_err(dx.cpu().numpy(), want) <= 1e-6
+        # the unfused entry points on the same planes (tiled kernel and large-plane fallback)
+        dxp = hp.maxpool3x3s2_bwd(xd, dev(g), dx=nan_like(x.shape))
+        assert norm_err(dxp.cpu().numpy(), oracle.maxpool3x3s2_bwd(x, g)) <= 1e-6
+
+
+def test_relu_vector_and_tail_paths():
+    for n in (1, 3, 4, 5, 1023, 4099):
+        x = synth.gaussian((n + 1,), 171)
+        g = synth.gaussian((n + 1,), 172)
+        for off in (0, 1):                                      # off = 1 breaks the 16-byte alignment
+            xd, gd = dev(x)[off:off + n], dev(g)[off:off + n]
+            y = torch.full((n + 2,), float("nan"), device="cuda")
+            hp.lib().relu_fwd(hp._ptr(xd), y[1:].data_ptr(), n, None)
+            hp.lib().relu_bwd(hp._ptr(xd), hp._ptr(gd), y[1:].data_ptr(), 0, None)
+            torch.cuda.synchronize()
+            assert torch.isnan(y[0]) and torch.isnan(y[n + 1])
+            assert np.array_equal(y[1:n + 1].cpu().numpy(), oracle.relu_fwd(x[off:off + n]).astype(np.float32))
+            d = hp.relu_bwd(xd.contiguous(), gd.contiguous())
+            assert np.array_equal(d.cpu().numpy(), oracle.relu_bwd(x[off:off + n], g[off:off + n]).astype(np.float32))
+
+
+def test_stack_step_layer_by_layer():
+    """One forward+backward step of the five-layer stack at a small batch: every conv call is checked against the
+    oracle applied to that call's own GPU inputs (so errors do not compound), the glue against the oracle too."""
+    from paper_1312_5853_amd.stack import ConvStack
+    N = 2
+    st = ConvStack(N)
+    st.step()
+    torch.cuda.synchronize()
+    c = lambda t: t.cpu().numpy()
+    x0, w = c(st.x0), {k: c(v) for k, v in st.w.items()}
+    y1, a1, y2, a2, y3, y4, y5, a5 = map(c, (st.y1, st.a1, st.y2, st.a2, st.y3, st.y4, st.y5, st.a5))
+    tol = TOL["f32"]
+    assert norm_err(y1, oracle.conv_fwd(x0, w["conv1"], 4, 2)) <= tol
+    assert np.array_equal(a1, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y1)).astype(np.float32))
+    assert norm_err(y2[:, :128], oracle.conv_fwd(a1[:, :48], w["conv2a"], 1, 2)) <= tol
+    assert norm_err(y2[:, 128:], oracle.conv_fwd(a1[:, 48:], w["conv2b"], 1, 2)) <= tol
+    assert np.array_equal(a2, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y2)).astype(np.float32))
+    # y3, y4 hold relu(conv) (in place): compare with relu of the oracle's conv
+    assert norm_err(y3, oracle.relu_fwd(oracle.conv_fwd(a2, w["conv3"], 1, 1))) <= tol
+    assert norm_err(y4, oracle.relu_fwd(oracle.conv_fwd(y3, w["conv4"], 1, 1))) <= tol
+    assert norm_err(y5, oracle.conv_fwd(y4, w["conv5"], 1, 1)) <= tol
+    assert np.array_equal(a5, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y5)).astype(np.float32))
+    g5, dy5, dy4, dy3, da2, dy2, da1, dy1 = map(c, (st.g5, st.dy5, st.dy4, st.dy3, st.da2, st.dy2, st.da1, st.dy1))
+    dw = {k: c(v) for k, v in st.dw.items()}
+    assert norm_err(dy5, oracle.relu_bwd(y5, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y5), g5))) <= 1e-6
+    assert norm_err(dw["conv5"], oracle.conv_bwd_filter(y4, dy5, 3, 3, 1, 1)) <= tol
+    # dy4 = relu_bwd(y4, dgrad(dy5)) in place
+    assert norm_err(dy4, oracle.relu_bwd(y4, oracle.conv_bwd_data(dy5, w["conv5"], 13, 13, 1, 1))) <= tol
+    assert norm_err(dw["conv4"], oracle.conv_bwd_filter(y3, dy4, 3, 3, 1, 1)) <= tol
+    assert norm_err(dy3, oracle.relu_bwd(y3, oracle.conv_bwd_data(dy4, w["conv4"], 13, 13, 1, 1))) <= tol
+    assert norm_err(dw["conv3"], oracle.conv_bwd_filter(a2, dy3, 3, 3, 1, 1)) <= tol
+    assert norm_err(da2, oracle.conv_bwd_data(dy3, w["conv3"], 13, 13, 1, 1)) <= tol
+    assert norm_err(dy2, oracle.relu_bwd(y2, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y2), da2))) <= 1e-6
+    assert norm_err(dw["conv2a"], oracle.conv_bwd_filter(a1[:, :48], dy2[:, :128], 5, 5, 1, 2)) <= tol
+    assert norm_err(dw["conv2b"], oracle.conv_bwd_filter(a1[:, 48:], dy2[:, 128:], 5, 5, 1, 2)) <= tol
+    assert norm_err(da1[:, :48], oracle.conv_bwd_data(dy2[:, :128], w["conv2a"], 27, 27, 1, 2)) <= tol
+    assert norm_err(da1[:, 48:], oracle.conv_bwd_data(dy2[:, 128:], w["conv2b"], 27, 27, 1, 2)) <= tol
+    assert norm_err(dy1, oracle.relu_bwd(y1, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y1), da1))) <= 1e-6
+    assert norm_err(dw["conv1"], oracle.conv_bwd_filter(x0, dy1, 11, 11, 4, 2)) <= tol
