@@ -10,6 +10,8 @@ import sys
 _HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(_HERE, "csrc", "convnet_hotpath.hip")
 LIB = os.path.join(_HERE, "libconvnet_hotpath.so")
+CEILING_SRC = os.path.join(_HERE, "csrc", "mfma_ceiling.hip")
+CEILING_EXE = os.path.join(_HERE, "mfma_ceiling")
 DEPS = [SRC, os.path.join(_HERE, "csrc", "plan.h"), os.path.join(_HERE, "csrc", "fastdiv.h"),
         os.path.join(os.path.dirname(_HERE), "include", "convnet_hotpath.h")]
 
@@ -42,6 +44,11 @@ def build(keep_temps_dir=None, verbose=False):
         sys.stderr.write(err + "\n")
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
+    # the stand-alone MFMA ceiling probe (no inputs, prints TFLOP/s)
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-o", CEILING_EXE, CEILING_SRC],
+                         capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stderr)
     return LIB
 
 

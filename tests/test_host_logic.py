@@ -1,0 +1,147 @@
+"""CPU-only checks of the boundary: the library loads, exports every symbol the
+header declares, rejects bad arguments before touching the GPU, and its host
+planning code (magic division, tile choice, workspace plan) is self-consistent."""
+import ctypes
+import os
+import re
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "convnet_hotpath.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_1312_5853_amd import binding, build
+    if build.is_stale():
+        build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", " ".join(l for l in text.splitlines() if not l.startswith("#")))))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_1312_5853_amd import binding
+    names = declared_functions()
+    assert {"conv_fwd", "conv_bwd_data", "conv_bwd_filter", "conv_workspace_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(0, -7, -1):
+        s = lib.conv_status_string(code).decode()
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 7
+    assert lib.conv_status_string(-99).decode() == "unknown status"
+    assert lib.conv_last_hip_error().decode() == ""
+
+
+GOOD = dict(N=2, C=16, H=13, W=13, K=32, R=3, S=3, stride=1, pad=1)
+PTR = 0x10000          # never dereferenced: every call below fails a host-side check first
+
+
+def call(lib, fn, ws=PTR, ws_bytes=1 << 30, a=PTR, b=PTR, out=PTR, dtype=0, **over):
+    d = dict(GOOD, **over)
+    return getattr(lib, fn)(a, b, out, d["N"], d["C"], d["H"], d["W"], d["K"], d["R"], d["S"], d["stride"], d["pad"],
+                            dtype, ws, ws_bytes, None)
+
+
+@pytest.mark.parametrize("fn", ["conv_fwd", "conv_bwd_data", "conv_bwd_filter"])
+def test_argument_checks_run_before_any_gpu_call(lib, fn):
+    from paper_1312_5853_amd import binding as b
+    assert call(lib, fn, a=None) == b.ERR_INVALID_ARG
+    assert call(lib, fn, b=None) == b.ERR_INVALID_ARG
+    assert call(lib, fn, out=None) == b.ERR_INVALID_ARG
+    for key in ("N", "C", "H", "W", "K", "R", "S", "stride"):
+        assert call(lib, fn, **{key: 0}) == b.ERR_INVALID_ARG, key
+        assert call(lib, fn, **{key: -3}) == b.ERR_INVALID_ARG, key
+    assert call(lib, fn, pad=-1) == b.ERR_INVALID_ARG
+    assert call(lib, fn, R=16, pad=1) == b.ERR_INVALID_ARG          # empty output (P <= 0)
+    assert call(lib, fn, dtype=2) == b.ERR_BAD_DTYPE
+    assert call(lib, fn, N=2048, C=64, H=64, W=64) == b.ERR_TOO_LARGE
+    assert call(lib, fn, a=PTR + 4) == b.ERR_MISALIGNED
+    assert call(lib, fn, out=PTR + 8) == b.ERR_MISALIGNED
+    assert call(lib, fn, ws=PTR + 16) == b.ERR_MISALIGNED
+    need = lib.conv_workspace_bytes({"conv_fwd": 0, "conv_bwd_data": 1, "conv_bwd_filter": 2}[fn],
+                                    *[GOOD[k] for k in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad")], 0)
+    assert need > 0
+    assert call(lib, fn, ws=None, ws_bytes=0) == b.ERR_WORKSPACE
+    assert call(lib, fn, ws_bytes=need - 1) == b.ERR_WORKSPACE
+
+
+def test_batch_stride_checks(lib):
+    from paper_1312_5853_amd import binding as b
+    d = GOOD
+    args = [PTR, PTR, PTR] + [d[k] for k in ("N", "C", "H", "W", "K", "R", "S", "stride", "pad")]
+    sample_x, sample_y = 16 * 169, 32 * 169
+    assert lib.conv_fwd_ex(*args, sample_x - 1, 0, 0, PTR, 1 << 30, None) == b.ERR_INVALID_ARG
+    assert lib.conv_fwd_ex(*args, 0, sample_y - 1, 0, PTR, 1 << 30, None) == b.ERR_INVALID_ARG
+    assert lib.conv_fwd_ex(*args, 1 << 40, 0, 0, PTR, 1 << 30, None) == b.ERR_TOO_LARGE
+
+
+def test_workspace_bytes(lib):
+    dims = [128, 256, 13, 13, 384, 3, 3, 1, 1]
+    a = lib.conv_workspace_bytes(0, *dims, 0)
+    assert a == lib.conv_workspace_bytes(0, *dims, 0) and a >= 384 * 2304 * 4
+    assert lib.conv_workspace_bytes(2, *dims, 0) >= 384 * 2304 * 4
+    assert lib.conv_workspace_bytes(1, *dims, 1) > lib.conv_workspace_bytes(1, *dims, 0)     # bf16 staging
+    assert lib.conv_workspace_bytes(3, *dims, 0) == 0
+    assert lib.conv_workspace_bytes(0, 0, 256, 13, 13, 384, 3, 3, 1, 1, 0) == 0
+
+
+def test_glue_argument_checks(lib):
+    from paper_1312_5853_amd import binding as b
+    assert lib.relu_fwd(None, PTR, 4, None) == b.ERR_INVALID_ARG
+    assert lib.relu_fwd(PTR, PTR, -1, None) == b.ERR_INVALID_ARG
+    assert lib.relu_fwd(PTR, PTR, 0, None) == b.OK
+    assert lib.relu_bwd(PTR, PTR + 2, PTR, 4, None) == b.ERR_MISALIGNED
+    for fn in (lib.maxpool3x3s2_fwd, lib.relu_maxpool3x3s2_fwd):
+        assert fn(PTR, PTR, 4, 2, 5, None) == b.ERR_INVALID_ARG         # plane smaller than the window
+        assert fn(PTR, PTR, 0, 5, 5, None) == b.ERR_INVALID_ARG
+        assert fn(None, PTR, 1, 5, 5, None) == b.ERR_INVALID_ARG
+    for fn in (lib.maxpool3x3s2_bwd, lib.relu_maxpool3x3s2_bwd):
+        assert fn(PTR, None, PTR, 1, 5, 5, None) == b.ERR_INVALID_ARG
+        assert fn(PTR, PTR, PTR + 1, 1, 5, 5, None) == b.ERR_MISALIGNED
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path):
+    import sys
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_1312_5853_amd import binding\n"
+            "binding.LIB_PATH = %r\n"
+            "try:\n    binding.lib()\nexcept RuntimeError as e:\n    print('raised'); sys.exit(0)\nsys.exit(1)\n"
+            % (ROOT, str(tmp_path / "missing.so")))
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True)
+    assert out.returncode == 0 and "raised" in out.stdout
+
+
+def test_product_never_imports_the_oracle():
+    import sys
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "import paper_1312_5853_amd.binding, paper_1312_5853_amd.stack, paper_1312_5853_amd.synth\n"
+            "sys.exit(1 if any(m == 'oracle' or m.startswith('oracle.') for m in sys.modules) else 0)\n" % ROOT)
+    assert subprocess.run([sys.executable, "-c", code]).returncode == 0
+    for name in ("binding.py", "stack.py", "synth.py", "build.py", "__init__.py"):
+        text = open(os.path.join(ROOT, "paper_1312_5853_amd", name)).read()
+        assert "import oracle" not in text and "from oracle" not in text
+    for name in os.listdir(os.path.join(ROOT, "paper_1312_5853_amd", "csrc")):
+        assert "oracle" not in open(os.path.join(ROOT, "paper_1312_5853_amd", "csrc", name)).read().lower()
+
+
+def test_host_planning_selftest(tmp_path):
+    exe = str(tmp_path / "host_selftest")
+    src = os.path.join(ROOT, "tests", "host_selftest.cpp")
+    subprocess.run(["g++", "-O2", "-std=c++17", "-o", exe, src], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout
+    assert "0 failures" in out.stdout
