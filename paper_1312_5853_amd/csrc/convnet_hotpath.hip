@@ -353,7 +353,9 @@ struct ColGemmFastArgs {
     int OH, OW, LH, LW;
     int ncols, src_bs, dst_bs, mul, add;
     int mtiles, ntiles, tiles_per_xcd;
-    FastDiv div_plane, div_ow;
+    int ksplit, steps_per_split;   // the reduction steps are cut into ksplit ranges (1 = whole)
+    float *part;                   // ksplit > 1: partial outputs [ksplit][N][M][OH*OW], summed by reduce_split_outputs
+    FastDiv div_plane, div_ow, div_rs, div_s;
 };
 
 template <int TM, int TN, int WM, int WN>
@@ -370,8 +372,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
 
     const int bid = blockIdx.x;
     const int idx = bid >> 3;
-    const int tile = (bid & 7) * p.tiles_per_xcd + idx;
-    if (idx >= p.tiles_per_xcd || tile >= p.mtiles * p.ntiles) return;
+    const int unit = (bid & 7) * p.tiles_per_xcd + idx;
+    const int ntile = p.mtiles * p.ntiles;
+    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit) return;
+    const int ks = unit / ntile;
+    const int tile = unit - ks * ntile;
     const int mt = tile % p.mtiles, nt = tile / p.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
 
@@ -396,14 +401,24 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
     }
     const char *src_bytes = reinterpret_cast<const char *>(p.src);
-    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * kChunk) + tid;
     const size_t a_step = (size_t)p.Mpad * (kChunk / 4);      // f32x4 per step
+    const int step_begin = ks * p.steps_per_split;
+    const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
+    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * kChunk) + tid + step_begin * a_step;
 
     f32x4 areg[A4T];
     float breg[EPT];
     bool bok;
     int a0 = 0;
-    int r = 0, s = 0, cboff = 0;     // next step to load: tap (r, s), channel-block byte offset
+    // next step to load: tap (r, s), channel-block byte offset
+    int r, s, cboff;
+    {
+        const int cb = (int)fastdiv((uint32_t)step_begin, p.div_rs);
+        const int rs = step_begin - cb * (p.R * p.S);
+        r = (int)fastdiv((uint32_t)rs, p.div_s);
+        s = rs - r * p.S;
+        cboff = cb * kChunk * p.plane_bytes;
+    }
 
     // The next step's loads are cut into slots that the main loop drops between
     // consecutive matrix instructions, so their issue cost hides behind the
@@ -461,7 +476,6 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
-    const int nsteps = p.cblocks * p.R * p.S;
     const int l32_ = lane & 31, half_ = lane >> 5;
     const int a_frag = (wm * TM * 32 + l32_) * kPitch + half_ * 8;
     const int b_frag = (wn * TN * 32 + l32_) * kPitch + half_ * 8;
@@ -540,7 +554,8 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         if (col >= p.ncols) continue;
         const int n = (int)fastdiv((uint32_t)col, p.div_plane);
         const int rem = col - n * plane;
-        float *out = p.dst + (size_t)n * p.dst_bs + rem;
+        float *out = p.ksplit > 1 ? p.part + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
+                                  : p.dst + (size_t)n * p.dst_bs + rem;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
@@ -550,6 +565,19 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
                 if (row < p.M) out[(size_t)row * plane] = acc[i][jn][v];
             }
         }
+    }
+}
+
+// out[n][i] = part[0][n][i] + part[1][n][i] + ...  (fixed order), i over one sample's M*OH*OW outputs
+__global__ void reduce_split_outputs(const float *__restrict__ part, float *__restrict__ dst, int nsplit,
+                                     int per_sample, int N, int dst_bs, FastDiv div_sample)
+{
+    const int total = N * per_sample;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+        float v = part[i];
+        for (int k = 1; k < nsplit; ++k) v += part[(size_t)k * total + i];
+        const int n = (int)fastdiv((uint32_t)i, div_sample);
+        dst[(size_t)n * dst_bs + (i - n * per_sample)] = v;
     }
 }
 
@@ -1205,9 +1233,19 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
         a.ntiles = ceil_div(a.ncols, pl.tile.bn());
         a.div_plane = make_fastdiv((uint32_t)(a.OH * a.OW));
         a.div_ow = make_fastdiv((uint32_t)a.OW);
-        const GridPlan g = plan_grid(a.mtiles * a.ntiles, pl.tile);
+        a.div_rs = make_fastdiv((uint32_t)RS);
+        a.div_s = make_fastdiv((uint32_t)pb.S);
+        a.ksplit = pl.nsplit;
+        a.steps_per_split = pl.chunks_per_split;
+        a.part = reinterpret_cast<float *>(wsb + pl.part_off);
+        const GridPlan g = plan_grid(a.mtiles * a.ntiles * a.ksplit, pl.tile);
         a.tiles_per_xcd = g.tiles_per_xcd;
         launch_colgemm_fast(pl.tile, a, g, st);
+        int rc = check_launch();
+        if (rc != kStatusOk || a.ksplit == 1) return rc;
+        const int per_sample = a.M * a.OH * a.OW;
+        hipLaunchKernelGGL(reduce_split_outputs, dim3(2048), dim3(256), 0, st, a.part, a.dst, a.ksplit, per_sample,
+                           pb.N, a.dst_bs, make_fastdiv((uint32_t)per_sample));
         return check_launch();
     }
     if (fwd)

@@ -161,6 +161,37 @@ inline Plan make_plan(int op, const Problem &pb)
         pl.wt_off = off;
         pl.wt_bytes = (size_t)pl.Mpad * pl.Kgpad * 4;
         off += round_up64(pl.wt_bytes, 256);
+        // Fast path (channel count of the gathered tensor a multiple of 16, unit-stride gather rows):
+        // the reduction may be cut into ranges when that balances the CUs better.  Model: a CU
+        // holding c work-groups runs them at eff(c) of its MFMA rate; the launch lasts as long
+        // as its fullest CU; the partial outputs cost one extra pass over memory per range.
+        const int Cr = op == kOpFwd ? pb.C : pb.K;
+        const int OH = op == kOpFwd ? pb.P : pb.H, OW = op == kOpFwd ? pb.Q : pb.W;
+        if (Cr % kChunk == 0 && (op == kOpFwd || pb.stride == 1)) {
+            const int steps = (Cr / kChunk) * RS;
+            const int64_t ncols = (int64_t)pb.N * OH * OW;
+            const int tiles = (pl.Mpad / pl.tile.bm()) * (int)((ncols + pl.tile.bn() - 1) / pl.tile.bn());
+            const double eff[5] = {1.0, 0.71, 0.83, 0.87, 0.88};
+            const double step_us = pl.tile.bm() * pl.tile.bn() * 2.0 * kChunk / 64.0 / 4.0 / 2100.0;   // MFMA time
+            const double out_mb = (double)ncols * pl.M * 4.0 / 1e6;
+            double best = 1e30;
+            for (int ks = 1; ks <= 4; ++ks) {
+                if (steps / ks < 16) break;
+                const int sps = ceil_div(steps, ks);
+                const int units = tiles * ceil_div(steps, sps);
+                const int per_cu = ceil_div(ceil_div(units, 8), 32);
+                const int resident = per_cu < 4 ? per_cu : 4;
+                double us = per_cu * sps * step_us / eff[resident];
+                if (ks > 1) us += 5.0 + (ks + 1) * out_mb / 4.5;      // launch + partial traffic at ~4.5 MB/us
+                if (us < best * 0.97) { best = us; pl.nsplit = ceil_div(steps, sps); pl.chunks_per_split = sps; }
+            }
+            if (pl.nsplit > 1) {
+                pl.part_off = off;
+                pl.part_bytes = (size_t)pl.nsplit * ncols * pl.M * 4;
+                off += round_up64(pl.part_bytes, 256);
+            }
+        }
+        if (pl.chunks_per_split == 0) pl.chunks_per_split = pl.Kgpad / kChunk;
     }
     if (pb.dtype == kDtypeBf16) {
         // inputs are widened to fp32 once, then the fp32 kernels run on the copies
