@@ -209,43 +209,45 @@ __global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
     f32x4 areg[A4T];
     float breg[EPT];
     bool bok[EPT];
+    int4 tap[EPT];            // table entries of the step that is loaded next (wave-uniform, scalar registers)
     const char *src_bytes = reinterpret_cast<const char *>(p.src);
 
-    auto load_step = [&](int chunk) {
+    // The table is padded by two steps, so fetching one step past the end is harmless.
+    auto fetch_taps = [&](int chunk) {
+        const int4 *t = p.tab + chunk * kChunk + grp * EPT;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) tap[e] = t[e];
+    };
+    auto slot_a = [&](int chunk) {
         const f32x4 *ablk = reinterpret_cast<const f32x4 *>(p.At + ((size_t)chunk * p.Mpad + m0) * kChunk);
 #pragma unroll
         for (int i = 0; i < A4T; ++i) {
             int idx = tid + i * kThreads;
             if (A4 % kThreads == 0 || idx < A4) areg[i] = ablk[idx];
         }
-        const int4 *t = p.tab + chunk * kChunk + grp * EPT;
-        int4 tap[EPT];
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) tap[e] = t[e];      // wave-uniform: scalar loads
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) {
-            bool ok;
-            int off;
-            if (GATHER == kGatherDirect) {
-                const int hh = hb + tap[e].y, ww = wb + tap[e].z;
-                ok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
-                off = base + tap[e].x;
-            } else {
-                // backward-data with stride > 1: output row h receives tap r only
-                // from the window row (h + pad - r)/stride, when that divides
-                const int th = hb + tap[e].y, tw = wb + tap[e].z;
-                ok = (th >= 0) & (tw >= 0);
-                const int ph = (int)fastdiv((uint32_t)(ok ? th : 0), p.div_stride);
-                const int qw = (int)fastdiv((uint32_t)(ok ? tw : 0), p.div_stride);
-                ok = ok & (ph * (int)p.div_stride.d == th) & (qw * (int)p.div_stride.d == tw) &
-                     (ph < p.LH) & (qw < p.LW);
-                off = base + tap[e].x + 4 * (ph * p.LW + qw);
-            }
-            // the load is always issued (address 0 when the tap is padding); the
-            // zero is substituted when the value is consumed, after the MFMAs
-            breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(ok ? off : 0));
-            bok[e] = ok;
+    };
+    auto slot_b = [&](int e) {
+        bool ok;
+        int off;
+        if (GATHER == kGatherDirect) {
+            const int hh = hb + tap[e].y, ww = wb + tap[e].z;
+            ok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+            off = base + tap[e].x;
+        } else {
+            // backward-data with stride > 1: output row h receives tap r only
+            // from the window row (h + pad - r)/stride, when that divides
+            const int th = hb + tap[e].y, tw = wb + tap[e].z;
+            ok = (th >= 0) & (tw >= 0);
+            const int ph = (int)fastdiv((uint32_t)(ok ? th : 0), p.div_stride);
+            const int qw = (int)fastdiv((uint32_t)(ok ? tw : 0), p.div_stride);
+            ok = ok & (ph * (int)p.div_stride.d == th) & (qw * (int)p.div_stride.d == tw) &
+                 (ph < p.LH) & (qw < p.LW);
+            off = base + tap[e].x + 4 * (ph * p.LW + qw);
         }
+        // the load is always issued (address 0 when the tap is padding); the
+        // zero is substituted when the value is staged, after the MFMAs
+        breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(ok ? off : 0));
+        bok[e] = ok;
     };
 
     auto store_step = [&](int buf) {
@@ -272,44 +274,53 @@ __global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
-#ifdef CONVNET_PHASE_PROBE
-    long long pr_t0 = __builtin_readcyclecounter(), pr_a = 0, pr_b = 0, pr_c = 0, pr_d = 0;
-#endif
-    load_step(0);
+    const int l32_ = lane & 31, half_ = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32_) * kPitch + half_ * 8;
+    const int b_frag = (wn * TN * 32 + l32_) * kPitch + half_ * 8;
+    constexpr int NMMA = 8 * TM * TN;
+    constexpr int NSLOT = EPT + 2;                              // filter slice, EPT taps, table prefetch
+    constexpr int SPM = (NSLOT + NMMA - 5) / (NMMA - 4);
+
+    fetch_taps(0);
+    slot_a(0);
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) slot_b(e);
     store_step(0);
+    fetch_taps(1);
     __syncthreads();
-    for (int chunk = 0; chunk < p.nchunks; ++chunk) {
+    for (int chunk = 0; chunk < p.nchunks - 1; ++chunk) {
         const int buf = chunk & 1;
-        const bool more = chunk + 1 < p.nchunks;
-#ifdef CONVNET_PHASE_PROBE
-        long long t0 = __builtin_readcyclecounter();
-#endif
-        if (more) load_step(chunk + 1);
-#ifdef CONVNET_PHASE_PROBE
-        long long t1 = __builtin_readcyclecounter();
-#endif
-        mma_step<TM, TN>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
-#ifdef CONVNET_PHASE_PROBE
-        long long t2 = __builtin_readcyclecounter();
-#endif
-        if (more) store_step(buf ^ 1);
-#ifdef CONVNET_PHASE_PROBE
-        long long t3 = __builtin_readcyclecounter();
-#endif
+        f32x4 fa[TM][2], fb[TN][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[buf][a_frag + i * 32 * kPitch]);
+            fa[i][0] = q[0]; fa[i][1] = q[1];
+        }
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[buf][b_frag + jn * 32 * kPitch]);
+            fb[jn][0] = q[0]; fb[jn][1] = q[1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // the next step's loads issue in the shadow of this step's matrix instructions
+#pragma unroll
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                              acc[i][jn], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                if (q == 0) slot_a(chunk + 1);
+                else if (q - 1 < EPT) slot_b(q - 1);
+                else fetch_taps(chunk + 2);
+            }
+            if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+        }
+        store_step(buf ^ 1);
         __syncthreads();
-#ifdef CONVNET_PHASE_PROBE
-        long long t4 = __builtin_readcyclecounter();
-        pr_a += t1 - t0; pr_b += t2 - t1; pr_c += t3 - t2; pr_d += t4 - t3;
-#endif
     }
-#ifdef CONVNET_PHASE_PROBE
-    if (tid == 0 && g_probe) {
-        long long *o = g_probe + (size_t)bid * 8;
-        o[0] = pr_t0; o[1] = __builtin_readcyclecounter(); o[2] = pr_a; o[3] = pr_b; o[4] = pr_c; o[5] = pr_d;
-        o[6] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));    // HW_ID
-        o[7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));   // XCC_ID
-    }
-#endif
+    mma_step<TM, TN>(As[(p.nchunks - 1) & 1], Bs[(p.nchunks - 1) & 1], wm * TM * 32, wn * TN * 32, lane, acc);
 
     // --- epilogue.  Accumulator register v of lane l holds row
     // 8*(v/4) + 4*(l/32) + v%4 and column l%32 of its 32 x 32 tile.
@@ -659,36 +670,42 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
     bool aok[RA], bok[RB];
     const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
     const char *x_bytes = reinterpret_cast<const char *>(p.x);
+    int abase = 0, bbase = 0, hb = 0, wb = 0, jnext = jbeg + jj;
+    bool jok = false;
 
-    auto load_step = [&](int step) {
-        const int j = jbeg + step * kChunk + jj;
-        const bool jok = j < jend;
-        const int js = jok ? j : jbeg;
+    auto slot_pos = [&]() {          // where this thread's reduction position sits
+        jok = jnext < jend;
+        const int js = jok ? jnext : jbeg;
         const int n = (int)fastdiv((uint32_t)js, p.div_plane);
         const int pq = js - n * PQ;
         const int pp = (int)fastdiv((uint32_t)pq, p.div_q);
         const int qq = pq - pp * p.Q;
         const int hb0 = pp * p.stride - p.pad;
-        const int wb = qq * p.stride - p.pad;
-        const int abase = 4 * (n * p.dy_bs + pq);                  // bytes
-        const int bbase = 4 * (n * p.x_bs + hb0 * p.W + wb);
-        const int hb = jok ? hb0 : kInvalidTap;
-#pragma unroll
-        for (int i = 0; i < RA; ++i) {
-            const int k = m0 + g + 16 * i;
-            const bool ok = jok & (k < p.K);
-            areg[i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(ok ? abase + 4 * k * PQ : 0));
-            aok[i] = ok;
-        }
-#pragma unroll
-        for (int i = 0; i < RB; ++i) {
-            const int hh = hb + bdr[i], ww = wb + bds[i];
-            const bool ok = ((unsigned)hh < (unsigned)p.H) & ((unsigned)ww < (unsigned)p.W);
-            breg[i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0));
-            bok[i] = ok;
-        }
+        wb = qq * p.stride - p.pad;
+        abase = 4 * (n * p.dy_bs + pq);                  // bytes
+        bbase = 4 * (n * p.x_bs + hb0 * p.W + wb);
+        hb = jok ? hb0 : kInvalidTap;
+        jnext += kChunk;
     };
-
+    auto slot_a = [&](int i) {
+        const int k = m0 + g + 16 * i;
+        const bool ok = jok & (k < p.K);
+        areg[i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(ok ? abase + 4 * k * PQ : 0));
+        aok[i] = ok;
+    };
+    auto slot_b = [&](int i) {
+        const int hh = hb + bdr[i], ww = wb + bds[i];
+        const bool ok = ((unsigned)hh < (unsigned)p.H) & ((unsigned)ww < (unsigned)p.W);
+        breg[i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0));
+        bok[i] = ok;
+    };
+    auto load_step = [&]() {
+        slot_pos();
+#pragma unroll
+        for (int i = 0; i < RA; ++i) slot_a(i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) slot_b(i);
+    };
     auto store_step = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < RA; ++i) As[buf][(g + 16 * i) * kPitch + jj] = aok[i] ? areg[i] : 0.f;
@@ -704,19 +721,51 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
+    const int l32_ = lane & 31, half_ = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32_) * kPitch + half_ * 8;
+    const int b_frag = (wn * TN * 32 + l32_) * kPitch + half_ * 8;
+    constexpr int NMMA = 8 * TM * TN;
+    constexpr int NSLOT = 1 + RA + RB;
+    constexpr int SPM = (NSLOT + NMMA - 5) / (NMMA - 4);
+
     if (nsteps > 0) {
-        load_step(0);
+        load_step();
         store_step(0);
     }
     __syncthreads();
-    for (int step = 0; step < nsteps; ++step) {
+    for (int step = 0; step < nsteps - 1; ++step) {
         const int buf = step & 1;
-        const bool more = step + 1 < nsteps;
-        if (more) load_step(step + 1);
-        mma_step<TM, TN>(As[buf], Bs[buf], wm * TM * 32, wn * TN * 32, lane, acc);
-        if (more) store_step(buf ^ 1);
+        f32x4 fa[TM][2], fb[TN][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[buf][a_frag + i * 32 * kPitch]);
+            fa[i][0] = q[0]; fa[i][1] = q[1];
+        }
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[buf][b_frag + jn * 32 * kPitch]);
+            fb[jn][0] = q[0]; fb[jn][1] = q[1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                              acc[i][jn], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                if (q == 0) slot_pos();
+                else if (q - 1 < RA) slot_a(q - 1);
+                else slot_b(q - 1 - RA);
+            }
+            if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+        }
+        store_step(buf ^ 1);
         __syncthreads();
     }
+    if (nsteps > 0)
+        mma_step<TM, TN>(As[(nsteps - 1) & 1], Bs[(nsteps - 1) & 1], wm * TM * 32, wn * TN * 32, lane, acc);
 
     const int l32 = lane & 31, half = lane >> 5;
     float *out = p.out + (size_t)split * p.K * p.CRS;

@@ -137,7 +137,7 @@ inline Plan make_plan(int op, const Problem &pb)
     }
     pl.Mpad = round_up(pl.M, pl.tile.bm());
     pl.Kgpad = round_up(pl.Kg, kChunk);
-    pl.tab_len = round_up(pl.Kg, kTapTablePad);
+    pl.tab_len = round_up(pl.Kg + 2 * kChunk, kTapTablePad);   // two steps of slack for the prefetch
     pl.nsplit = 1;
     pl.chunks_per_split = 0;
     size_t off = 0;
