@@ -354,11 +354,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
 // twenty-five shifted reads of a channel block hit the same cache lines.
 // ---------------------------------------------------------------------------
 struct ColGemmFastArgs {
-    const float *At;      // filters as [cb][r][s][Mpad][16 channels]
+    const float *At;      // filters as [cb][r][s][Mpad][KC channels]
     const float *src;
     float *dst;
     int M, Mpad;
-    int cblocks, R, S;    // reduction: cblocks * R * S steps of 16 channels
+    int cblocks, R, S;    // reduction: cblocks * R * S steps of KC channels
     int sign;             // +1 forward (reads hb + r), -1 backward-data (reads hb - r)
     int plane_bytes;      // LH*LW*4: channel stride of the gathered tensor
     int OH, OW, LH, LW;
@@ -369,17 +369,24 @@ struct ColGemmFastArgs {
     FastDiv div_plane, div_ow, div_rs, div_s;
 };
 
-template <int TM, int TN, int WM, int WN>
+// KC = reduction depth of one step (16 or 32 channels of one tap).  LDS is
+// dynamic: 2 * (BM + BN) * (KC + 4) floats.
+template <int TM, int TN, int WM, int WN, int KC>
 __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFastArgs p)
 {
     constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
-    constexpr int EPT = BN / 16;
-    constexpr int A4 = BM * 4;
+    constexpr int PITCH = KC + 4;            // 16 lanes x b128 still cover all banks once (20 and 36 both do)
+    constexpr int HALFK = KC / 2;            // reduction elements each half-wave feeds
+    constexpr int NF = HALFK / 4;            // b128 reads per 32-row fragment
+    constexpr int EPT = BN * KC / kThreads;  // gathered channels per thread per step
+    constexpr int A4 = BM * KC / 4;
     constexpr int A4T = (A4 + kThreads - 1) / kThreads;
     static_assert(WM * WN == 4, "four waves per work-group");
+    static_assert(KC == 16 || KC == 32, "step depth");
 
-    __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    float *const As0 = lds_fast;
+    float *const Bs0 = lds_fast + 2 * BM * PITCH;
 
     const int bid = blockIdx.x;
     const int idx = bid >> 3;
@@ -412,10 +419,10 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
     }
     const char *src_bytes = reinterpret_cast<const char *>(p.src);
-    const size_t a_step = (size_t)p.Mpad * (kChunk / 4);      // f32x4 per step
+    const size_t a_step = (size_t)p.Mpad * (KC / 4);          // f32x4 per step
     const int step_begin = ks * p.steps_per_split;
     const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
-    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * kChunk) + tid + step_begin * a_step;
+    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * KC) + tid + step_begin * a_step;
 
     f32x4 areg[A4T];
     float breg[EPT];
@@ -428,7 +435,7 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         const int rs = step_begin - cb * (p.R * p.S);
         r = (int)fastdiv((uint32_t)rs, p.div_s);
         s = rs - r * p.S;
-        cboff = cb * kChunk * p.plane_bytes;
+        cboff = cb * KC * p.plane_bytes;
     }
 
     // The next step's loads are cut into slots that the main loop drops between
@@ -445,32 +452,32 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         r += ws ? 1 : 0;
         const bool wr = r == p.R;
         r = wr ? 0 : r;
-        cboff += wr ? kChunk * p.plane_bytes : 0;
+        cboff += wr ? KC * p.plane_bytes : 0;
     };
-    auto slot_a = [&]() {            // filter slice: contiguous block
-#pragma unroll
-        for (int i = 0; i < A4T; ++i)
-            if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
-        a_ptr += a_step;
+    auto slot_a = [&](int i) {       // filter slice: contiguous block
+        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
+        if (i == A4T - 1) a_ptr += a_step;
     };
     auto slot_b = [&](int e) {       // one channel of the gathered column
         breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
     };
     auto load_step = [&]() {
         slot_tap();
-        slot_a();
+#pragma unroll
+        for (int i = 0; i < A4T; ++i) slot_a(i);
 #pragma unroll
         for (int e = 0; e < EPT; ++e) slot_b(e);
     };
 
     auto store_step = [&](int buf) {
+        float *As = As0 + buf * BM * PITCH, *Bs = Bs0 + buf * BN * PITCH;
 #pragma unroll
         for (int i = 0; i < A4T; ++i) {
-            int idx = tid + i * kThreads;
-            if (A4 % kThreads == 0 || idx < A4)
-                *reinterpret_cast<f32x4 *>(&As[buf][(idx >> 2) * kPitch + (idx & 3) * 4]) = areg[i];
+            int q = tid + i * kThreads;
+            if (A4 % kThreads == 0 || q < A4)
+                *reinterpret_cast<f32x4 *>(&As[(q / (KC / 4)) * PITCH + (q % (KC / 4)) * 4]) = areg[i];
         }
-        float *brow = &Bs[buf][jc * kPitch + grp * EPT];
+        float *brow = &Bs[jc * PITCH + grp * EPT];
 #pragma unroll
         for (int e = 0; e < EPT; e += 4) {
             f32x4 v = {bok ? breg[e] : 0.f, bok ? breg[e + 1] : 0.f, bok ? breg[e + 2] : 0.f,
@@ -487,77 +494,92 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
-    const int l32_ = lane & 31, half_ = lane >> 5;
-    const int a_frag = (wm * TM * 32 + l32_) * kPitch + half_ * 8;
-    const int b_frag = (wn * TN * 32 + l32_) * kPitch + half_ * 8;
-    constexpr int NMMA = 8 * TM * TN;
-    constexpr int NSLOT = EPT + 2;                              // tap, filter slice, EPT channels
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * PITCH + half * HALFK;
+    const int b_frag = (wn * TN * 32 + l32) * PITCH + half * HALFK;
+    constexpr int NMMA = HALFK * TM * TN;
+    constexpr int NSLOT = 1 + A4T + EPT;                        // tap, filter slice, EPT channels
     constexpr int SPM = (NSLOT + NMMA - 5) / (NMMA - 4);        // slots issued after each matrix instruction
 
 #ifdef CONVNET_PHASE_PROBE
-    long long pr_t0 = __builtin_readcyclecounter(), pr_a = 0, pr_b = 0, pr_c = 0, pr_d = 0;
+    long long pr_t0 = __builtin_readcyclecounter(), pr_b = 0, pr_c = 0, pr_d = 0;
     long long pr_rt0 = wall_clock64();
 #endif
     load_step();
     store_step(0);
     __syncthreads();
-    for (int step = 0; step < nsteps - 1; ++step) {
+#ifdef CONVNET_PHASE_PROBE
+    const long long pr_rt1 = wall_clock64();
+#endif
+    for (int step = 0; step < nsteps; ++step) {
         const int buf = step & 1;
+        const bool last = step == nsteps - 1;       // uniform; the last step has nothing left to load
 #ifdef CONVNET_PHASE_PROBE
         long long t0 = __builtin_readcyclecounter();
 #endif
-        f32x4 fa[TM][2], fb[TN][2];
+        const float *As = As0 + buf * BM * PITCH, *Bs = Bs0 + buf * BN * PITCH;
+        f32x4 fa[TM][NF], fb[TN][NF];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[buf][a_frag + i * 32 * kPitch]);
-            fa[i][0] = q[0]; fa[i][1] = q[1];
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[a_frag + i * 32 * PITCH]);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) fa[i][f] = q[f];
         }
 #pragma unroll
         for (int jn = 0; jn < TN; ++jn) {
-            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[buf][b_frag + jn * 32 * kPitch]);
-            fb[jn][0] = q[0]; fb[jn][1] = q[1];
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[b_frag + jn * 32 * PITCH]);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) fb[jn][f] = q[f];
         }
         __builtin_amdgcn_sched_barrier(0);
+        if (!last) {
 #pragma unroll
-        for (int m = 0; m < NMMA; ++m) {
-            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
-                                                              acc[i][jn], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                                  acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
-                if (q == 0) slot_tap();
-                else if (q == 1) slot_a();
-                else slot_b(q - 2);
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                    if (q == 0) slot_tap();
+                    else if (q - 1 < A4T) slot_a(q - 1);
+                    else slot_b(q - 1 - A4T);
+                }
+                if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
             }
-            if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+#ifdef CONVNET_PHASE_PROBE
+            long long t2 = __builtin_readcyclecounter();
+            __builtin_amdgcn_sched_barrier(0);
+#endif
+            store_step(buf ^ 1);
+#ifdef CONVNET_PHASE_PROBE
+            __builtin_amdgcn_sched_barrier(0);
+            long long t3 = __builtin_readcyclecounter();
+#endif
+            __syncthreads();
+#ifdef CONVNET_PHASE_PROBE
+            long long t4 = __builtin_readcyclecounter();
+            pr_b += t2 - t0; pr_c += t3 - t2; pr_d += t4 - t3;
+#endif
+        } else {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                                  acc[i][jn], 0, 0, 0);
+            }
         }
-#ifdef CONVNET_PHASE_PROBE
-        long long t2 = __builtin_readcyclecounter();
-        __builtin_amdgcn_sched_barrier(0);
-#endif
-        store_step(buf ^ 1);
-#ifdef CONVNET_PHASE_PROBE
-        __builtin_amdgcn_sched_barrier(0);
-        long long t3 = __builtin_readcyclecounter();
-#endif
-        __syncthreads();
-#ifdef CONVNET_PHASE_PROBE
-        long long t4 = __builtin_readcyclecounter();
-        pr_b += t2 - t0; pr_c += t3 - t2; pr_d += t4 - t3;
-#endif
     }
 #ifdef CONVNET_PHASE_PROBE
     if (tid == 0 && g_probe) {
         long long *o = g_probe + (size_t)bid * 8;
-        o[0] = pr_t0; o[1] = __builtin_readcyclecounter(); o[2] = pr_rt0 + pr_a; o[3] = wall_clock64(); o[4] = pr_c; o[5] = pr_d;
+        o[0] = pr_t0; o[1] = __builtin_readcyclecounter(); o[2] = pr_rt0; o[3] = wall_clock64(); o[5] = pr_rt1;
         o[6] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
         o[7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));
+        (void)pr_b;
     }
 #endif
-    mma_step<TM, TN>(As[(nsteps - 1) & 1], Bs[(nsteps - 1) & 1], wm * TM * 32, wn * TN * 32, lane, acc);
 
-    const int l32 = lane & 31, half = lane >> 5;
     const int plane = p.OH * p.OW;
 #pragma unroll
     for (int jn = 0; jn < TN; ++jn) {
@@ -577,6 +599,10 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
             }
         }
     }
+#ifdef CONVNET_PHASE_PROBE
+    __builtin_amdgcn_s_waitcnt(0);
+    if (tid == 0 && g_probe) g_probe[(size_t)bid * 8 + 4] = wall_clock64();
+#endif
 }
 
 // out[n][i] = part[0][n][i] + part[1][n][i] + ...  (fixed order), i over one sample's M*OH*OW outputs
@@ -592,22 +618,22 @@ __global__ void reduce_split_outputs(const float *__restrict__ part, float *__re
     }
 }
 
-// Filters for colgemm_fast_kernel: wt[((cb*R + r)*S + s)][Mpad][16], element e = channel cb*16+e.
+// Filters for colgemm_fast_kernel: wt[((cb*R + r)*S + s)][Mpad][kc], element e = channel cb*kc+e.
 //   transposed = 0: row m = filter k, channel = input channel c   (forward)
 //   transposed = 1: row m = input channel c, channel = filter k   (backward-data)
 __global__ void relayout_filters_cblk(const float *__restrict__ w, float *__restrict__ wt, int M, int Mpad,
-                                      int cblocks, int RS, int C, int transposed)
+                                      int cblocks, int RS, int C, int transposed, int kc)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)cblocks * RS * Mpad * kChunk;
+    int64_t total = (int64_t)cblocks * RS * Mpad * kc;
     if (i >= total) return;
-    int e = (int)(i % kChunk);
-    int64_t t = i / kChunk;
+    int e = (int)(i % kc);
+    int64_t t = i / kc;
     int m = (int)(t % Mpad);
     t /= Mpad;
     int rs = (int)(t % RS);
     int cb = (int)(t / RS);
-    int ch = cb * kChunk + e;
+    int ch = cb * kc + e;
     float v = 0.f;
     if (m < M) v = transposed ? w[((int64_t)ch * C + m) * RS + rs] : w[((int64_t)m * C + ch) * RS + rs];
     wt[i] = v;
@@ -1171,14 +1197,14 @@ static int dbg_env(const char *name, int dflt) { const char *e = getenv(name); r
 // that was handed one work-group more.
 struct GridPlan { int tiles_per_xcd, grid, dyn_lds; };
 
-GridPlan plan_grid(int tiles, const TileShape &t)
+GridPlan plan_grid(int tiles, const TileShape &t, int kc = kChunk)
 {
     GridPlan g;
     g.tiles_per_xcd = ceil_div(tiles, 8);
     g.grid = 8 * g.tiles_per_xcd;
     int cap = ceil_div(g.tiles_per_xcd, 32);
     cap = dbg_env("CONVNET_CAP", cap);
-    const int static_lds = 2 * (t.bm() + t.bn()) * kPitch * 4;
+    const int static_lds = 2 * (t.bm() + t.bn()) * (kc + 4) * 4;
     int total = static_lds;
     if (cap == 3) total = 52 * 1024;
     else if (cap <= 2) total = 64 * 1024;
@@ -1196,13 +1222,29 @@ void launch_colgemm(const TileShape &t, const ColGemmArgs &a, const GridPlan &g,
     else hipLaunchKernelGGL((colgemm_kernel<1, 2, 1, 4, GATHER>), grid, block, g.dyn_lds, st, a);
 }
 
-void launch_colgemm_fast(const TileShape &t, const ColGemmFastArgs &a, const GridPlan &g, hipStream_t st)
+template <typename Kern>
+void launch_dyn(Kern kern, const ColGemmFastArgs &a, int grid, int lds, hipStream_t st)
 {
-    const dim3 grid(g.grid), block(kThreads);
-    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((colgemm_fast_kernel<2, 2, 2, 2>), grid, block, g.dyn_lds, st, a);
-    else if (t.TM == 3) hipLaunchKernelGGL((colgemm_fast_kernel<3, 1, 1, 4>), grid, block, g.dyn_lds, st, a);
-    else if (t.TM == 2) hipLaunchKernelGGL((colgemm_fast_kernel<2, 1, 1, 4>), grid, block, g.dyn_lds, st, a);
-    else hipLaunchKernelGGL((colgemm_fast_kernel<1, 2, 1, 4>), grid, block, g.dyn_lds, st, a);
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    if (lds > 64 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      160 * 1024);
+            raised = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, st, a);
+}
+
+void launch_colgemm_fast(const TileShape &t, int kc, const ColGemmFastArgs &a, const GridPlan &g, hipStream_t st)
+{
+    const int need = 2 * (t.bm() + t.bn()) * (kc + 4) * 4;
+    const int lds = need + g.dyn_lds;
+    if (t.TM == 2 && t.TN == 2) launch_dyn(colgemm_fast_kernel<2, 2, 2, 2, 16>, a, g.grid, lds, st);
+    else if (t.TM == 3) launch_dyn(colgemm_fast_kernel<3, 1, 1, 4, 16>, a, g.grid, lds, st);
+    else if (t.TM == 2) launch_dyn(colgemm_fast_kernel<2, 1, 1, 4, 16>, a, g.grid, lds, st);
+    else launch_dyn(colgemm_fast_kernel<1, 2, 1, 4, 16>, a, g.grid, lds, st);
 }
 
 void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
@@ -1264,11 +1306,12 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
 
     const int Cr = fwd ? pb.C : pb.K;          // channels of the gathered tensor
     if (Cr % kChunk == 0 && (fwd || pb.stride == 1)) {
+        const int kc = pl.kc;
         hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d((int64_t)pl.Mpad * pl.Kgpad, 256)), dim3(256), 0, st,
-                           wf, wt, pl.M, pl.Mpad, Cr / kChunk, RS, pb.C, fwd ? 0 : 1);
+                           wf, wt, pl.M, pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc);
         ColGemmFastArgs a;
         a.At = wt; a.src = actf; a.dst = static_cast<float *>(out);
-        a.M = pl.M; a.Mpad = pl.Mpad; a.cblocks = Cr / kChunk; a.R = pb.R; a.S = pb.S;
+        a.M = pl.M; a.Mpad = pl.Mpad; a.cblocks = Cr / kc; a.R = pb.R; a.S = pb.S;
         if (fwd) {
             a.sign = 1; a.OH = pb.P; a.OW = pb.Q; a.LH = pb.H; a.LW = pb.W;
             a.src_bs = (int)pb.x_bs; a.dst_bs = (int)pb.y_bs; a.mul = pb.stride; a.add = -pb.pad;
@@ -1287,9 +1330,9 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
         a.ksplit = pl.nsplit;
         a.steps_per_split = pl.chunks_per_split;
         a.part = reinterpret_cast<float *>(wsb + pl.part_off);
-        const GridPlan g = plan_grid(a.mtiles * a.ntiles * a.ksplit, pl.tile);
+        const GridPlan g = plan_grid(a.mtiles * a.ntiles * a.ksplit, pl.tile, kc);
         a.tiles_per_xcd = g.tiles_per_xcd;
-        launch_colgemm_fast(pl.tile, a, g, st);
+        launch_colgemm_fast(pl.tile, kc, a, g, st);
         int rc = check_launch();
         if (rc != kStatusOk || a.ksplit == 1) return rc;
         const int per_sample = a.M * a.OH * a.OW;

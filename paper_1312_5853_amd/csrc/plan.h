@@ -113,6 +113,7 @@ struct Plan {
     int Kg;           // fwd: C*R*S, dgrad: K*R*S, wgrad: C*R*S (columns of dw)
     int Kgpad;        // Kg rounded up to kChunk
     int tab_len;      // tap table entries
+    int kc;           // reduction depth of one step (16, or 32 where the fast path allows)
     int nsplit;       // wgrad: partial sums over the (n, p, q) reduction
     int chunks_per_split;
     size_t tab_off, tab_bytes;
@@ -138,6 +139,7 @@ inline Plan make_plan(int op, const Problem &pb)
     pl.Mpad = round_up(pl.M, pl.tile.bm());
     pl.Kgpad = round_up(pl.Kg, kChunk);
     pl.tab_len = round_up(pl.Kg + 2 * kChunk, kTapTablePad);   // two steps of slack for the prefetch
+    pl.kc = kChunk;
     pl.nsplit = 1;
     pl.chunks_per_split = 0;
     size_t off = 0;
@@ -168,22 +170,28 @@ inline Plan make_plan(int op, const Problem &pb)
         const int Cr = op == kOpFwd ? pb.C : pb.K;
         const int OH = op == kOpFwd ? pb.P : pb.H, OW = op == kOpFwd ? pb.Q : pb.W;
         if (Cr % kChunk == 0 && (op == kOpFwd || pb.stride == 1)) {
-            const int steps = (Cr / kChunk) * RS;
             const int64_t ncols = (int64_t)pb.N * OH * OW;
             const int tiles = (pl.Mpad / pl.tile.bm()) * (int)((ncols + pl.tile.bn() - 1) / pl.tile.bn());
-            const double eff[5] = {1.0, 0.71, 0.83, 0.87, 0.88};
-            const double step_us = pl.tile.bm() * pl.tile.bn() * 2.0 * kChunk / 64.0 / 4.0 / 2100.0;   // MFMA time
             const double out_mb = (double)ncols * pl.M * 4.0 / 1e6;
+            // measured fraction of the MFMA rate a CU reaches with c resident work-groups
+            const double eff16[5] = {1.0, 0.71, 0.83, 0.87, 0.88};
+            // (32-deep steps were measured too: no faster at two work-groups per CU, so steps stay 16 deep)
             double best = 1e30;
-            for (int ks = 1; ks <= 4; ++ks) {
-                if (steps / ks < 16) break;
-                const int sps = ceil_div(steps, ks);
-                const int units = tiles * ceil_div(steps, sps);
-                const int per_cu = ceil_div(ceil_div(units, 8), 32);
-                const int resident = per_cu < 4 ? per_cu : 4;
-                double us = per_cu * sps * step_us / eff[resident];
-                if (ks > 1) us += 5.0 + (ks + 1) * out_mb / 4.5;      // launch + partial traffic at ~4.5 MB/us
-                if (us < best * 0.97) { best = us; pl.nsplit = ceil_div(steps, sps); pl.chunks_per_split = sps; }
+            for (int kc = kChunk; kc <= kChunk; kc *= 2) {
+                const int steps = (Cr / kc) * RS;
+                const double step_us = pl.tile.bm() * pl.tile.bn() * 2.0 * kc / 64.0 / 4.0 / 2100.0;   // MFMA time
+                for (int ks = 1; ks <= 4; ++ks) {
+                    if (steps * kc / ks < 256) break;
+                    const int sps = ceil_div(steps, ks);
+                    const int units = tiles * ceil_div(steps, sps);
+                    const int per_cu = ceil_div(ceil_div(units, 8), 32);
+                    const int resident = per_cu < 4 ? per_cu : 4;
+                    double us = per_cu * sps * step_us / eff16[resident];
+                    if (ks > 1) us += 5.0 + (ks + 1) * out_mb / 4.5;      // launch + partial traffic at ~4.5 MB/us
+                    if (us < best * 0.97) {
+                        best = us; pl.kc = kc; pl.nsplit = ceil_div(steps, sps); pl.chunks_per_split = sps;
+                    }
+                }
             }
             if (pl.nsplit > 1) {
                 pl.part_off = off;
