@@ -605,6 +605,235 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
 #endif
 }
 
+// ---------------------------------------------------------------------------
+// bf16 inputs, fp32 accumulation: the same walk as colgemm_fast_kernel (one
+// filter tap x KC consecutive channels per step, one padding test and one base
+// address per thread and step) on v_mfma_f32_32x32x16_bf16.  A lane feeds 8
+// consecutive channels of its row per instruction, so the LDS tiles are
+// [row][KC bf16] with 16 bytes of padding per row and every fragment read is one
+// b128.  Gathered activations arrive as 2-byte loads (NCHW: a column's channels
+// are a plane apart) and are packed in pairs when they are staged.
+// ---------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int TM, int TN, int WM, int WN, int KC>
+__global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFastArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int PITCHB = KC * 2 + 16;      // bytes per LDS row
+    constexpr int NK = KC / 16;              // matrix instructions per 32x32 tile and step
+    constexpr int EPT = BN * KC / kThreads;  // gathered channels per thread per step
+    constexpr int A4 = BM * KC / 8;          // 16-byte vectors of the filter slice per step
+    constexpr int A4T = (A4 + kThreads - 1) / kThreads;
+    static_assert(WM * WN == 4, "four waves per work-group");
+    static_assert(KC == 16 || KC == 64, "step depth");
+    static_assert(EPT % 8 == 0, "a thread stages whole 16-byte groups");
+
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    char *const As0 = reinterpret_cast<char *>(lds_fast);
+    char *const Bs0 = As0 + 2 * BM * PITCHB;
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.tiles_per_xcd + idx;
+    const int ntile = p.mtiles * p.ntiles;
+    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit) return;
+    const int ks = unit / ntile;
+    const int tile = unit - ks * ntile;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int jc = tid % BN;
+    const int grp = uniform(tid / BN);
+    int hb, wb, base;                        // base: byte offset of this column at tap (0, 0), first channel of its group
+    {
+        const int j = n0 + jc;
+        const bool colok = j < p.ncols;
+        const int jj = colok ? j : 0;
+        const int n = (int)fastdiv((uint32_t)jj, p.div_plane);
+        const int rem = jj - n * (p.OH * p.OW);
+        const int oh = (int)fastdiv((uint32_t)rem, p.div_ow);
+        const int ow = rem - oh * p.OW;
+        hb = oh * p.mul + p.add;
+        wb = ow * p.mul + p.add;
+        base = 2 * (n * p.src_bs + hb * p.LW + wb) + grp * EPT * p.plane_bytes;
+        if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
+    }
+    const char *src_bytes = reinterpret_cast<const char *>(p.src);
+    const size_t a_step = (size_t)p.Mpad * (KC / 8);          // 16-byte vectors per step
+    const int step_begin = ks * p.steps_per_split;
+    const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
+    const u32x4 *a_ptr = reinterpret_cast<const u32x4 *>(p.At) + (size_t)m0 * (KC / 8) + tid + step_begin * a_step;
+
+    u32x4 areg[A4T];
+    unsigned short breg[EPT];
+    bool bok;
+    int a0 = 0;
+    int r, s, cboff;
+    {
+        const int cb = (int)fastdiv((uint32_t)step_begin, p.div_rs);
+        const int rs = step_begin - cb * (p.R * p.S);
+        r = (int)fastdiv((uint32_t)rs, p.div_s);
+        s = rs - r * p.S;
+        cboff = cb * KC * p.plane_bytes;
+    }
+
+    auto slot_tap = [&]() {
+        const int dr = p.sign * r, ds = p.sign * s;
+        const int hh = hb + dr, ww = wb + ds;
+        bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+        a0 = bok ? base + cboff + 2 * (dr * p.LW + ds) : 0;
+        s += 1;
+        const bool ws = s == p.S;
+        s = ws ? 0 : s;
+        r += ws ? 1 : 0;
+        const bool wr = r == p.R;
+        r = wr ? 0 : r;
+        cboff += wr ? KC * p.plane_bytes : 0;
+    };
+    auto slot_a = [&](int i) {
+        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
+        if (i == A4T - 1) a_ptr += a_step;
+    };
+    auto slot_b = [&](int e) {
+        breg[e] = *reinterpret_cast<const unsigned short *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
+    };
+    auto load_step = [&]() {
+        slot_tap();
+#pragma unroll
+        for (int i = 0; i < A4T; ++i) slot_a(i);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) slot_b(e);
+    };
+    auto store_step = [&](int buf) {
+        char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+#pragma unroll
+        for (int i = 0; i < A4T; ++i) {
+            int q = tid + i * kThreads;
+            if (A4 % kThreads == 0 || q < A4)
+                *reinterpret_cast<u32x4 *>(As + (q / (KC / 8)) * PITCHB + (q % (KC / 8)) * 16) = areg[i];
+        }
+        char *brow = Bs + jc * PITCHB + grp * EPT * 2;
+#pragma unroll
+        for (int e = 0; e < EPT; e += 8) {
+            u32x4 v;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const unsigned pair = (unsigned)breg[e + 2 * k] | ((unsigned)breg[e + 2 * k + 1] << 16);
+                v[k] = bok ? pair : 0u;
+            }
+            *reinterpret_cast<u32x4 *>(brow + e * 2) = v;
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
+    const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
+    constexpr int NMMA = NK * TM * TN;
+    constexpr int NSLOT = 1 + A4T + EPT;
+    constexpr int SPM = (NSLOT + (NMMA > 2 ? NMMA - 2 : 1) - 1) / (NMMA > 2 ? NMMA - 2 : 1);
+
+    load_step();
+    store_step(0);
+    __syncthreads();
+    for (int step = 0; step < nsteps; ++step) {
+        const int buf = step & 1;
+        const bool last = step == nsteps - 1;
+        const char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+        u32x4 fa[TM][NK], fb[TN][NK];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fa[i][t] = *reinterpret_cast<const u32x4 *>(As + a_frag + i * 32 * PITCHB + t * 32);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fb[jn][t] = *reinterpret_cast<const u32x4 *>(Bs + b_frag + jn * 32 * PITCHB + t * 32);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!last) {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                     acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                    if (q == 0) slot_tap();
+                    else if (q - 1 < A4T) slot_a(q - 1);
+                    else slot_b(q - 1 - A4T);
+                }
+                if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+            }
+            store_step(buf ^ 1);
+            __syncthreads();
+        } else {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                     acc[i][jn], 0, 0, 0);
+            }
+        }
+    }
+
+    const int plane = p.OH * p.OW;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+        const int n = (int)fastdiv((uint32_t)col, p.div_plane);
+        const int rem = col - n * plane;
+        float *out = p.ksplit > 1 ? p.part + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
+                                  : p.dst + (size_t)n * p.dst_bs + rem;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.M) out[(size_t)row * plane] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// bf16 filters for colgemm_bf16_kernel: wt[((cb*R + r)*S + s)][Mpad][kc]
+__global__ void relayout_filters_cblk_bf16(const unsigned short *__restrict__ w, unsigned short *__restrict__ wt,
+                                           int M, int Mpad, int cblocks, int RS, int C, int transposed, int kc)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t total = (int64_t)cblocks * RS * Mpad * kc;
+    if (i >= total) return;
+    int e = (int)(i % kc);
+    int64_t t = i / kc;
+    int m = (int)(t % Mpad);
+    t /= Mpad;
+    int rs = (int)(t % RS);
+    int cb = (int)(t / RS);
+    int ch = cb * kc + e;
+    unsigned short v = 0;
+    if (m < M) v = transposed ? w[((int64_t)ch * C + m) * RS + rs] : w[((int64_t)m * C + ch) * RS + rs];
+    wt[i] = v;
+}
+
 // out[n][i] = part[0][n][i] + part[1][n][i] + ...  (fixed order), i over one sample's M*OH*OW outputs
 __global__ void reduce_split_outputs(const float *__restrict__ part, float *__restrict__ dst, int nsplit,
                                      int per_sample, int N, int dst_bs, FastDiv div_sample)
@@ -1197,14 +1426,13 @@ static int dbg_env(const char *name, int dflt) { const char *e = getenv(name); r
 // that was handed one work-group more.
 struct GridPlan { int tiles_per_xcd, grid, dyn_lds; };
 
-GridPlan plan_grid(int tiles, const TileShape &t, int kc = kChunk)
+GridPlan plan_grid(int tiles, int static_lds)
 {
     GridPlan g;
     g.tiles_per_xcd = ceil_div(tiles, 8);
     g.grid = 8 * g.tiles_per_xcd;
     int cap = ceil_div(g.tiles_per_xcd, 32);
     cap = dbg_env("CONVNET_CAP", cap);
-    const int static_lds = 2 * (t.bm() + t.bn()) * (kc + 4) * 4;
     int total = static_lds;
     if (cap == 3) total = 52 * 1024;
     else if (cap <= 2) total = 64 * 1024;
@@ -1225,15 +1453,10 @@ void launch_colgemm(const TileShape &t, const ColGemmArgs &a, const GridPlan &g,
 template <typename Kern>
 void launch_dyn(Kern kern, const ColGemmFastArgs &a, int grid, int lds, hipStream_t st)
 {
-    // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    if (lds > 64 * 1024) {
-        static bool raised = false;
-        if (!raised) {
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      160 * 1024);
-            raised = true;
-        }
-    }
+    // more than 64 KB of dynamic LDS has to be allowed per kernel
+    if (lds > 64 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, st, a);
 }
 
@@ -1245,6 +1468,20 @@ void launch_colgemm_fast(const TileShape &t, int kc, const ColGemmFastArgs &a, c
     else if (t.TM == 3) launch_dyn(colgemm_fast_kernel<3, 1, 1, 4, 16>, a, g.grid, lds, st);
     else if (t.TM == 2) launch_dyn(colgemm_fast_kernel<2, 1, 1, 4, 16>, a, g.grid, lds, st);
     else launch_dyn(colgemm_fast_kernel<1, 2, 1, 4, 16>, a, g.grid, lds, st);
+}
+
+void launch_colgemm_bf16(const TileShape &t, int kc, const ColGemmFastArgs &a, const GridPlan &g, hipStream_t st)
+{
+    const int need = 2 * (t.bm() + t.bn()) * (kc * 2 + 16);
+    const int lds = need + g.dyn_lds;
+    if (t.TM == 2 && t.TN == 2 && kc == 64) launch_dyn(colgemm_bf16_kernel<2, 2, 2, 2, 64>, a, g.grid, lds, st);
+    else if (t.TM == 2 && t.TN == 2) launch_dyn(colgemm_bf16_kernel<2, 2, 2, 2, 16>, a, g.grid, lds, st);
+    else if (t.TM == 3 && kc == 64) launch_dyn(colgemm_bf16_kernel<3, 1, 1, 4, 64>, a, g.grid, lds, st);
+    else if (t.TM == 3) launch_dyn(colgemm_bf16_kernel<3, 1, 1, 4, 16>, a, g.grid, lds, st);
+    else if (t.TM == 2 && kc == 64) launch_dyn(colgemm_bf16_kernel<2, 1, 1, 4, 64>, a, g.grid, lds, st);
+    else if (t.TM == 2) launch_dyn(colgemm_bf16_kernel<2, 1, 1, 4, 16>, a, g.grid, lds, st);
+    else if (kc == 64) launch_dyn(colgemm_bf16_kernel<1, 2, 1, 4, 64>, a, g.grid, lds, st);
+    else launch_dyn(colgemm_bf16_kernel<1, 2, 1, 4, 16>, a, g.grid, lds, st);
 }
 
 void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
@@ -1301,16 +1538,24 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
     const int RS = pb.R * pb.S;
     const bool fwd = op == kOpFwd;
     const int64_t act_elems = (int64_t)pb.N * (fwd ? pb.x_bs : pb.y_bs);
-    const float *actf = as_f32(act, act_elems, pb.dtype, wsb, pl, 0, st);
-    const float *wf = as_f32(w, (int64_t)pb.K * pb.C * RS, pb.dtype, wsb, pl, 1, st);
-
     const int Cr = fwd ? pb.C : pb.K;          // channels of the gathered tensor
-    if (Cr % kChunk == 0 && (fwd || pb.stride == 1)) {
-        const int kc = pl.kc;
-        hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d((int64_t)pl.Mpad * pl.Kgpad, 256)), dim3(256), 0, st,
-                           wf, wt, pl.M, pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc);
+    const bool fast = Cr % kChunk == 0 && (fwd || pb.stride == 1);
+    const bool bf = pb.dtype == kDtypeBf16 && fast;     // bf16 MFMA kernel reads the caller's tensors directly
+    const float *actf = bf ? nullptr : as_f32(act, act_elems, pb.dtype, wsb, pl, 0, st);
+    const float *wf = bf ? nullptr : as_f32(w, (int64_t)pb.K * pb.C * RS, pb.dtype, wsb, pl, 1, st);
+
+    if (fast) {
+        const int kc = bf ? (Cr % 64 == 0 ? 64 : 16) : pl.kc;
+        const int64_t wt_elems = (int64_t)pl.Mpad * Cr * RS;
+        if (bf)
+            hipLaunchKernelGGL(relayout_filters_cblk_bf16, dim3(grid1d(wt_elems, 256)), dim3(256), 0, st,
+                               static_cast<const unsigned short *>(w), reinterpret_cast<unsigned short *>(wt), pl.M,
+                               pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc);
+        else
+            hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d(wt_elems, 256)), dim3(256), 0, st, wf, wt, pl.M,
+                               pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc);
         ColGemmFastArgs a;
-        a.At = wt; a.src = actf; a.dst = static_cast<float *>(out);
+        a.At = wt; a.src = bf ? static_cast<const float *>(act) : actf; a.dst = static_cast<float *>(out);
         a.M = pl.M; a.Mpad = pl.Mpad; a.cblocks = Cr / kc; a.R = pb.R; a.S = pb.S;
         if (fwd) {
             a.sign = 1; a.OH = pb.P; a.OW = pb.Q; a.LH = pb.H; a.LW = pb.W;
@@ -1319,7 +1564,7 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
             a.sign = -1; a.OH = pb.H; a.OW = pb.W; a.LH = pb.P; a.LW = pb.Q;
             a.src_bs = (int)pb.y_bs; a.dst_bs = (int)pb.x_bs; a.mul = 1; a.add = pb.pad;
         }
-        a.plane_bytes = a.LH * a.LW * 4;
+        a.plane_bytes = a.LH * a.LW * (bf ? 2 : 4);
         a.ncols = pb.N * a.OH * a.OW;
         a.mtiles = pl.Mpad / pl.tile.bm();
         a.ntiles = ceil_div(a.ncols, pl.tile.bn());
@@ -1328,11 +1573,13 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
         a.div_rs = make_fastdiv((uint32_t)RS);
         a.div_s = make_fastdiv((uint32_t)pb.S);
         a.ksplit = pl.nsplit;
-        a.steps_per_split = pl.chunks_per_split;
+        a.steps_per_split = ceil_div(a.cblocks * RS, pl.nsplit);      // same ranges as planned, in steps of kc
         a.part = reinterpret_cast<float *>(wsb + pl.part_off);
-        const GridPlan g = plan_grid(a.mtiles * a.ntiles * a.ksplit, pl.tile, kc);
+        const int need_lds = 2 * (pl.tile.bm() + pl.tile.bn()) * (bf ? kc * 2 + 16 : (kc + 4) * 4);
+        const GridPlan g = plan_grid(a.mtiles * a.ntiles * a.ksplit, need_lds);
         a.tiles_per_xcd = g.tiles_per_xcd;
-        launch_colgemm_fast(pl.tile, kc, a, g, st);
+        if (bf) launch_colgemm_bf16(pl.tile, kc, a, g, st);
+        else launch_colgemm_fast(pl.tile, kc, a, g, st);
         int rc = check_launch();
         if (rc != kStatusOk || a.ksplit == 1) return rc;
         const int per_sample = a.M * a.OH * a.OW;
@@ -1368,7 +1615,7 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
     a.div_plane = make_fastdiv((uint32_t)(a.OH * a.OW));
     a.div_ow = make_fastdiv((uint32_t)a.OW);
     a.div_stride = make_fastdiv((uint32_t)pb.stride);
-    const GridPlan g = plan_grid(a.mtiles * a.ntiles, pl.tile);
+    const GridPlan g = plan_grid(a.mtiles * a.ntiles, 2 * (pl.tile.bm() + pl.tile.bn()) * kPitch * 4);
     a.tiles_per_xcd = g.tiles_per_xcd;
     if (!fwd && pb.stride > 1) launch_colgemm<kGatherStridedBwd>(pl.tile, a, g, st);
     else launch_colgemm<kGatherDirect>(pl.tile, a, g, st);
@@ -1393,7 +1640,7 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &pb, const 
         a.mtiles = pl.Mpad / pl.tile.bm();
         a.ntiles = ceil_div(pl.Kg, pl.tile.bn());
         a.nunits = a.mtiles * a.ntiles * pl.nsplit;
-        const GridPlan g = plan_grid(a.nunits, pl.tile);
+        const GridPlan g = plan_grid(a.nunits, 2 * (pl.tile.bm() + pl.tile.bn()) * kPitch * 4);
         a.units_per_xcd = g.tiles_per_xcd;
         a.x_plane_bytes = pb.H * pb.W * 4;
         a.y_plane_bytes = pb.P * pb.Q * 4;
