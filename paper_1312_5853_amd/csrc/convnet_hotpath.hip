@@ -13,6 +13,7 @@
 #include <hip/hip_runtime.h>
 
 #include <stdio.h>
+#include <algorithm>
 #include <stdlib.h>
 #include <string.h>
 
@@ -869,6 +870,192 @@ __global__ void relayout_filters_cblk(const float *__restrict__ w, float *__rest
 }
 
 // ---------------------------------------------------------------------------
+// Forward pass for layers with few input channels (the 11x11 stride-4 first
+// layer: C = 3).  A work-group owns 128 consecutive output positions of ONE
+// image and stages every input row those positions read -- zero padding
+// included -- in LDS once, with coalesced row loads.  The im2col operand is then
+// read from that patch: element (g = (c, r, s), position (p, q)) sits at
+//   patch[(c*NR + (p - p0)*stride + r) * WP + q*stride + s],
+// i.e. a per-lane position offset plus a per-g offset from a small LDS table.
+// No gathers from global memory, no padding tests in the loop.  Filters stream
+// through LDS 16 deep as in the other kernels.  One wave = TM x 1 tiles of 32x32.
+// ---------------------------------------------------------------------------
+struct PatchArgs {
+    const float *At;      // filters [chunk][Mpad][16], g in (c, r, s) order, zero padded
+    const float *x;
+    float *y;
+    int M, Mpad, nchunks;
+    int C, H, W, R, S, stride, pad;
+    int P, Q, PQ;
+    int NR, WP;           // staged rows per channel, LDS row pitch (W + 2*pad rounded up)
+    int Kg, Kgpad;
+    int x_bs, y_bs;
+    int mtiles, jtiles;   // row tiles, position tiles per image
+    int ntiles, tiles_per_xcd;
+    FastDiv div_q, div_rs, div_s, div_mj, div_m, div_wp, div_nr;
+};
+
+template <int TM>
+__global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs p)
+{
+    constexpr int BM = TM * 32, BN = 128;
+    constexpr int A4 = BM * 4;
+    constexpr int A4T = (A4 + kThreads - 1) / kThreads;
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    float *const As0 = lds_fast;                               // 2 x BM x kPitch
+    int *const koff = reinterpret_cast<int *>(lds_fast + 2 * BM * kPitch);   // Kgpad
+    float *const patch = lds_fast + 2 * BM * kPitch + p.Kgpad; // C x NR x WP
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int tile = (bid & 7) * p.tiles_per_xcd + idx;
+    if (idx >= p.tiles_per_xcd || tile >= p.ntiles) return;
+    // tile -> (image n, position tile jt, row tile mt), row tiles fastest
+    const int n = (int)fastdiv((uint32_t)tile, p.div_mj);
+    const int rem = tile - n * (p.mtiles * p.jtiles);
+    const int jt = (int)fastdiv((uint32_t)rem, p.div_m);
+    const int mt = rem - jt * p.mtiles;
+    const int m0 = mt * BM, j0 = jt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+
+    const int p0 = (int)fastdiv((uint32_t)j0, p.div_q);
+    const int h0 = p0 * p.stride - p.pad;                      // image row of staged row 0
+
+    // --- stage the patch: row (c, i) <- x[n][c][h0 + i][:], zero outside the image
+    {
+        // 32 independent loads in flight per thread and batch (the first layer's patch is ~60 values per thread)
+        const float *xn = p.x + (size_t)n * p.x_bs;
+        const int total = p.C * p.NR * p.WP;
+        for (int e0 = tid; e0 < total; e0 += kThreads * 32) {
+            float tmp[32];
+#pragma unroll
+            for (int u = 0; u < 32; ++u) {
+                const int e = e0 + u * kThreads;
+                const int ee = e < total ? e : 0;
+                const int row = (int)fastdiv((uint32_t)ee, p.div_wp);
+                const int v = ee - row * p.WP;
+                const int c = (int)fastdiv((uint32_t)row, p.div_nr);
+                const int h = h0 + row - c * p.NR, w = v - p.pad;
+                const bool ok = ((unsigned)h < (unsigned)p.H) & ((unsigned)w < (unsigned)p.W);
+                const float val = xn[ok ? (c * p.H + h) * p.W + w : 0];
+                tmp[u] = ok ? val : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 32; ++u) {
+                const int e = e0 + u * kThreads;
+                if (e < total) patch[e] = tmp[u];
+            }
+        }
+        // per-g offset table; padded g (zero filter) may point anywhere inside the patch
+        for (int g = tid; g < p.Kgpad; g += kThreads) {
+            int off = 0;
+            if (g < p.Kg) {
+                const int c = (int)fastdiv((uint32_t)g, p.div_rs);
+                const int rs = g - c * (p.R * p.S);
+                const int r = (int)fastdiv((uint32_t)rs, p.div_s);
+                off = (c * p.NR + r) * p.WP + (rs - r * p.S);
+            }
+            koff[g] = off;
+        }
+    }
+
+    // this lane's output position and its offset into the patch
+    const int j = j0 + wave * 32 + l32;
+    const bool jok = j < p.PQ;
+    int colbase;
+    {
+        const int jj = jok ? j : j0;
+        const int pp = (int)fastdiv((uint32_t)jj, p.div_q);
+        const int qq = jj - pp * p.Q;
+        colbase = (pp - p0) * p.stride * p.WP + qq * p.stride;
+    }
+
+    f32x4 areg[A4T];
+    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * kChunk) + tid;
+    const size_t a_step = (size_t)p.Mpad * (kChunk / 4);
+    auto slot_a = [&](int i) {
+        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
+        if (i == A4T - 1) a_ptr += a_step;
+    };
+    auto store_a = [&](int buf) {
+        float *As = As0 + buf * BM * kPitch;
+#pragma unroll
+        for (int i = 0; i < A4T; ++i) {
+            int q = tid + i * kThreads;
+            if (A4 % kThreads == 0 || q < A4) *reinterpret_cast<f32x4 *>(&As[(q >> 2) * kPitch + (q & 3) * 4]) = areg[i];
+        }
+    };
+
+    f32x16 acc[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+#pragma unroll
+    for (int i = 0; i < A4T; ++i) slot_a(i);
+    store_a(0);
+    __syncthreads();
+    const int a_frag = l32 * kPitch + half * 8;
+    // The im2col values do not depend on the filter staging, so those of step+1 are
+    // read from the patch while step's matrix instructions run.
+    float bv[8];
+    auto read_b = [&](int step) {
+        const int4 k0 = *reinterpret_cast<const int4 *>(&koff[step * kChunk + half * 8]);
+        const int4 k1 = *reinterpret_cast<const int4 *>(&koff[step * kChunk + half * 8 + 4]);
+        bv[0] = patch[colbase + k0.x]; bv[1] = patch[colbase + k0.y];
+        bv[2] = patch[colbase + k0.z]; bv[3] = patch[colbase + k0.w];
+        bv[4] = patch[colbase + k1.x]; bv[5] = patch[colbase + k1.y];
+        bv[6] = patch[colbase + k1.z]; bv[7] = patch[colbase + k1.w];
+    };
+    read_b(0);
+    for (int step = 0; step < p.nchunks; ++step) {
+        const int buf = step & 1;
+        const bool last = step == p.nchunks - 1;
+        const float *As = As0 + buf * BM * kPitch;
+        f32x4 fa[TM][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[a_frag + i * 32 * kPitch]);
+            fa[i][0] = q[0]; fa[i][1] = q[1];
+        }
+        float bc[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) bc[t] = bv[t];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], bc[t], acc[i], 0, 0, 0);
+            if (!last && (t < A4T || t == 3)) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (t < A4T) slot_a(t);
+                if (t == 3) read_b(step + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (!last) store_a(buf ^ 1);
+        __syncthreads();
+    }
+
+    if (!jok) return;
+    float *out = p.y + (size_t)n * p.y_bs + j;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int row0 = m0 + i * 32 + half * 4;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = row0 + (v >> 2) * 8 + (v & 3);
+            if (row < p.M) out[(size_t)row * p.PQ] = acc[i][v];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Backward-filter: dw[k][g] = sum_j dy[k][j] * im2col(x)[g][j],  j = (n, p, q)
 // ---------------------------------------------------------------------------
 struct WgradArgs {
@@ -1470,6 +1657,17 @@ void launch_colgemm_fast(const TileShape &t, int kc, const ColGemmFastArgs &a, c
     else launch_dyn(colgemm_fast_kernel<1, 2, 1, 4, 16>, a, g.grid, lds, st);
 }
 
+void launch_patch(int tm, const PatchArgs &a, int grid, int lds, hipStream_t st)
+{
+    const void *k = tm == 1 ? (const void *)colgemm_patch_kernel<1> : tm == 2 ? (const void *)colgemm_patch_kernel<2>
+                  : tm == 3 ? (const void *)colgemm_patch_kernel<3> : (const void *)colgemm_patch_kernel<4>;
+    if (lds > 64 * 1024) (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (tm == 1) hipLaunchKernelGGL(colgemm_patch_kernel<1>, dim3(grid), dim3(kThreads), lds, st, a);
+    else if (tm == 2) hipLaunchKernelGGL(colgemm_patch_kernel<2>, dim3(grid), dim3(kThreads), lds, st, a);
+    else if (tm == 3) hipLaunchKernelGGL(colgemm_patch_kernel<3>, dim3(grid), dim3(kThreads), lds, st, a);
+    else hipLaunchKernelGGL(colgemm_patch_kernel<4>, dim3(grid), dim3(kThreads), lds, st, a);
+}
+
 void launch_colgemm_bf16(const TileShape &t, int kc, const ColGemmFastArgs &a, const GridPlan &g, hipStream_t st)
 {
     const int need = 2 * (t.bm() + t.bn()) * (kc * 2 + 16);
@@ -1586,6 +1784,39 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
         hipLaunchKernelGGL(reduce_split_outputs, dim3(2048), dim3(256), 0, st, a.part, a.dst, a.ksplit, per_sample,
                            pb.N, a.dst_bs, make_fastdiv((uint32_t)per_sample));
         return check_launch();
+    }
+    // forward with few channels: stage the input rows once per work-group when they fit in LDS
+    if (fwd) {
+        const int tm = pl.M <= 32 ? 1 : pl.M <= 64 ? 2 : pl.M <= 96 ? 3 : 4;
+        const int bm = tm * 32, mpad = round_up(pl.M, bm);
+        const int PQ = pb.P * pb.Q;
+        int span = (pb.Q + 126) / pb.Q;                 // output rows a 128-position tile can straddle, minus one
+        if (span > pb.P - 1) span = pb.P - 1;
+        const int NR = span * pb.stride + pb.R;
+        const int WP = round_up(std::max(pb.W + 2 * pb.pad, (pb.Q - 1) * pb.stride + pb.S), 4);
+        const int64_t lds64 = ((int64_t)2 * bm * kPitch + pl.Kgpad + (int64_t)pb.C * NR * WP) * 4;
+        if (lds64 <= 80 * 1024 && (int64_t)mpad * pl.Kgpad * 4 <= (int64_t)pl.wt_bytes) {
+            hipLaunchKernelGGL(relayout_filters, dim3(grid1d((int64_t)mpad * pl.Kgpad, 256)), dim3(256), 0, st, wf, wt,
+                               pl.M, mpad, pl.Kg, pl.Kgpad, pb.C, RS, 0);
+            PatchArgs a;
+            a.At = wt; a.x = actf; a.y = static_cast<float *>(out);
+            a.M = pl.M; a.Mpad = mpad; a.nchunks = pl.Kgpad / kChunk;
+            a.C = pb.C; a.H = pb.H; a.W = pb.W; a.R = pb.R; a.S = pb.S; a.stride = pb.stride; a.pad = pb.pad;
+            a.P = pb.P; a.Q = pb.Q; a.PQ = PQ; a.NR = NR; a.WP = WP; a.Kg = pl.Kg; a.Kgpad = pl.Kgpad;
+            a.x_bs = (int)pb.x_bs; a.y_bs = (int)pb.y_bs;
+            a.mtiles = mpad / bm; a.jtiles = ceil_div(PQ, 128);
+            a.ntiles = pb.N * a.mtiles * a.jtiles;
+            a.tiles_per_xcd = ceil_div(a.ntiles, 8);
+            a.div_q = make_fastdiv((uint32_t)pb.Q);
+            a.div_rs = make_fastdiv((uint32_t)RS);
+            a.div_s = make_fastdiv((uint32_t)pb.S);
+            a.div_mj = make_fastdiv((uint32_t)(a.mtiles * a.jtiles));
+            a.div_m = make_fastdiv((uint32_t)a.mtiles);
+            a.div_wp = make_fastdiv((uint32_t)WP);
+            a.div_nr = make_fastdiv((uint32_t)NR);
+            launch_patch(tm, a, 8 * a.tiles_per_xcd, (int)lds64, st);
+            return check_launch();
+        }
     }
     if (fwd)
         hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len,
