@@ -1410,6 +1410,206 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArg
     }
 }
 
+// ---------------------------------------------------------------------------
+// Backward-filter with bf16 inputs on v_mfma_f32_32x32x16_bf16.  Same column
+// order and split scheme as wgrad_fast_kernel; a step covers 64 reduction
+// positions.  A thread stages a PAIR of adjacent positions for 16 rows of dy and
+// 16 channels of one tap of x (2-byte loads, lanes along positions), packs each
+// pair into one dword and writes it to the [row][64 positions] LDS tiles, from
+// which every MFMA operand (8 consecutive positions of a row) is one b128 read.
+// ---------------------------------------------------------------------------
+template <int TM, int TN, int WM, int WN, int KJ>
+__global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(const WgradFastArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int GROUPS = 2 * kThreads / KJ;   // row groups: a thread stages BM/GROUPS + BN/GROUPS rows of one position pair
+    constexpr int PITCHB = KJ * 2 + 16;
+    constexpr int NK = KJ / 16;
+    constexpr int RA = BM / GROUPS, RB = BN / GROUPS;
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    char *const As0 = reinterpret_cast<char *>(lds_fast);
+    char *const Bs0 = As0 + 2 * BM * PITCHB;
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.units_per_xcd + idx;
+    if (idx >= p.units_per_xcd || unit >= p.nunits) return;
+    const int tiles = p.mtiles * p.ntiles;
+    const int split = unit / tiles;
+    const int tile = unit - split * tiles;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int jp = tid % (KJ / 2), g = tid / (KJ / 2);
+    const int PQ = p.P * p.Q;
+
+    const int arow0 = m0 + g * RA;
+    const int a_rows = min(max(p.K - arow0, 0), RA);
+    int a_off[RA];
+#pragma unroll
+    for (int i = 0; i < RA; ++i) a_off[i] = min(arow0 + i, p.K - 1) * p.y_plane_bytes;
+
+    const int col0 = n0 + g * RB;
+    const bool col_ok = col0 < p.ncols;
+    int tap_r, tap_s, b_off;
+    {
+        const int cc = col_ok ? col0 : 0;
+        const int rs = (int)fastdiv((uint32_t)cc, p.div_c);
+        const int c0 = cc - rs * p.C;
+        tap_r = rs / p.S;
+        tap_s = rs - tap_r * p.S;
+        b_off = c0 * p.x_plane_bytes + 2 * (tap_r * p.W + tap_s);
+    }
+
+    // chunks_per_split counts 16-position chunks; steps here are KJ positions
+    const int steps_per_split = (p.chunks_per_split * 16 + KJ - 1) / KJ;
+    const int jbeg = split * steps_per_split * KJ;
+    const int jend = min(jbeg + steps_per_split * KJ, p.J);
+    const int nsteps = jend > jbeg ? (jend - jbeg + KJ - 1) / KJ : 0;
+
+    const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
+    const char *x_bytes = reinterpret_cast<const char *>(p.x);
+    unsigned short areg[2][RA], breg[2][RB];
+    int a_lim[2] = {0, 0}, abase[2] = {0, 0}, bbase[2] = {0, 0};
+    bool bok[2] = {false, false};
+    int jnext = jbeg + 2 * jp;
+
+    auto slot_pos = [&]() {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int j = jnext + h;
+            const bool jok = j < jend;
+            const int js = jok ? j : jbeg;
+            const int n = (int)fastdiv((uint32_t)js, p.div_plane);
+            const int pq = js - n * PQ;
+            const int pp = (int)fastdiv((uint32_t)pq, p.div_q);
+            const int qq = pq - pp * p.Q;
+            const int hb = pp * p.stride - p.pad, wb = qq * p.stride - p.pad;
+            a_lim[h] = jok ? a_rows : 0;
+            abase[h] = 2 * (n * p.dy_bs + pq);
+            bok[h] = jok & col_ok & ((unsigned)(hb + tap_r) < (unsigned)p.H) & ((unsigned)(wb + tap_s) < (unsigned)p.W);
+            bbase[h] = bok[h] ? 2 * (n * p.x_bs + hb * p.W + wb) + b_off : 0;
+        }
+        jnext += KJ;
+    };
+    auto slot_a = [&](int q) {       // q = 2*i + h
+        const int i = q >> 1, h = q & 1;
+        areg[h][i] = *reinterpret_cast<const unsigned short *>(dy_bytes + (uint32_t)(abase[h] + a_off[i]));
+    };
+    auto slot_b = [&](int q) {
+        const int i = q >> 1, h = q & 1;
+        breg[h][i] = *reinterpret_cast<const unsigned short *>(x_bytes + (uint32_t)(bbase[h] + i * p.x_plane_bytes));
+    };
+    auto load_step = [&]() {
+        slot_pos();
+#pragma unroll
+        for (int q = 0; q < 2 * RA; ++q) slot_a(q);
+#pragma unroll
+        for (int q = 0; q < 2 * RB; ++q) slot_b(q);
+    };
+    auto store_step = [&](int buf) {
+        char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+#pragma unroll
+        for (int i = 0; i < RA; ++i) {
+            const unsigned lo = i < a_lim[0] ? (unsigned)areg[0][i] : 0u;
+            const unsigned hi = i < a_lim[1] ? (unsigned)areg[1][i] : 0u;
+            *reinterpret_cast<unsigned *>(As + (g * RA + i) * PITCHB + jp * 4) = lo | (hi << 16);
+        }
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            const unsigned lo = bok[0] ? (unsigned)breg[0][i] : 0u;
+            const unsigned hi = bok[1] ? (unsigned)breg[1][i] : 0u;
+            *reinterpret_cast<unsigned *>(Bs + (g * RB + i) * PITCHB + jp * 4) = lo | (hi << 16);
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
+    const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
+    constexpr int NMMA = NK * TM * TN;
+    constexpr int NSLOT = 1 + 2 * RA + 2 * RB;
+    constexpr int SPM = (NSLOT + (NMMA > 2 ? NMMA - 2 : 1) - 1) / (NMMA > 2 ? NMMA - 2 : 1);
+
+    if (nsteps > 0) {
+        load_step();
+        store_step(0);
+    }
+    __syncthreads();
+    for (int step = 0; step < nsteps; ++step) {
+        const int buf = step & 1;
+        const bool last = step == nsteps - 1;
+        const char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+        u32x4 fa[TM][NK], fb[TN][NK];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fa[i][t] = *reinterpret_cast<const u32x4 *>(As + a_frag + i * 32 * PITCHB + t * 32);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fb[jn][t] = *reinterpret_cast<const u32x4 *>(Bs + b_frag + jn * 32 * PITCHB + t * 32);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!last) {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                     acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                    if (q == 0) slot_pos();
+                    else if (q - 1 < 2 * RA) slot_a(q - 1);
+                    else slot_b(q - 1 - 2 * RA);
+                }
+                if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+            }
+            store_step(buf ^ 1);
+            __syncthreads();
+        } else {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                     acc[i][jn], 0, 0, 0);
+            }
+        }
+    }
+
+    float *out = p.part + (size_t)split * p.K * p.ncols;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.ncols + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
 // dw[k][c][rs] = part[0][k][rs*C + c] + part[1][k][rs*C + c] + ...  (fixed order)
 __global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int RS,
                              int nsplit)
@@ -1690,6 +1890,21 @@ void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t 
     else hipLaunchKernelGGL((wgrad_kernel<1, 2, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
 }
 
+constexpr int kWgradBf16Depth = 32;     // reduction positions per step of the bf16 backward-filter kernel
+
+void launch_wgrad_bf16(const TileShape &t, const WgradFastArgs &a, int grid, int lds, hipStream_t st)
+{
+    constexpr int KJ = kWgradBf16Depth;
+    const void *k = (t.TM == 2 && t.TN == 2) ? (const void *)wgrad_bf16_kernel<2, 2, 2, 2, KJ>
+                  : t.TM == 3 ? (const void *)wgrad_bf16_kernel<3, 1, 1, 4, KJ>
+                              : (const void *)wgrad_bf16_kernel<2, 1, 1, 4, KJ>;
+    if (lds > 64 * 1024) (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    const dim3 g(grid), b(kThreads);
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((wgrad_bf16_kernel<2, 2, 2, 2, KJ>), g, b, lds, st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((wgrad_bf16_kernel<3, 1, 1, 4, KJ>), g, b, lds, st, a);
+    else hipLaunchKernelGGL((wgrad_bf16_kernel<2, 1, 1, 4, KJ>), g, b, lds, st, a);
+}
+
 void launch_wgrad_fast(const TileShape &t, const WgradFastArgs &a, const GridPlan &g, hipStream_t st)
 {
     const dim3 grid(g.grid), block(kThreads);
@@ -1858,8 +2073,11 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &pb, const 
     char *wsb = static_cast<char *>(ws);
     int4 *tab = reinterpret_cast<int4 *>(wsb + pl.tab_off);
     const int RS = pb.R * pb.S;
-    const float *xf = as_f32(x, (int64_t)pb.N * pb.x_bs, pb.dtype, wsb, pl, 0, st);
-    const float *dyf = as_f32(dy, (int64_t)pb.N * pb.y_bs, pb.dtype, wsb, pl, 1, st);
+    // bf16 MFMA kernel: reads the caller's bf16 tensors directly (128-column tiles only)
+    const bool bf = pb.dtype == kDtypeBf16 && pb.C % kChunk == 0 && pl.tile.bn() == 128;
+    const float *xf = bf ? static_cast<const float *>(x) : as_f32(x, (int64_t)pb.N * pb.x_bs, pb.dtype, wsb, pl, 0, st);
+    const float *dyf = bf ? static_cast<const float *>(dy)
+                          : as_f32(dy, (int64_t)pb.N * pb.y_bs, pb.dtype, wsb, pl, 1, st);
     if (pb.C % kChunk == 0) {
         WgradFastArgs a;
         a.dy = dyf; a.x = xf; a.part = reinterpret_cast<float *>(wsb + pl.part_off);
@@ -1871,14 +2089,16 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &pb, const 
         a.mtiles = pl.Mpad / pl.tile.bm();
         a.ntiles = ceil_div(pl.Kg, pl.tile.bn());
         a.nunits = a.mtiles * a.ntiles * pl.nsplit;
-        const GridPlan g = plan_grid(a.nunits, 2 * (pl.tile.bm() + pl.tile.bn()) * kPitch * 4);
+        const int need_lds = 2 * (pl.tile.bm() + pl.tile.bn()) * (bf ? kWgradBf16Depth * 2 + 16 : kPitch * 4);
+        const GridPlan g = plan_grid(a.nunits, need_lds);
         a.units_per_xcd = g.tiles_per_xcd;
-        a.x_plane_bytes = pb.H * pb.W * 4;
-        a.y_plane_bytes = pb.P * pb.Q * 4;
+        a.x_plane_bytes = pb.H * pb.W * (bf ? 2 : 4);
+        a.y_plane_bytes = pb.P * pb.Q * (bf ? 2 : 4);
         a.div_plane = make_fastdiv((uint32_t)(pb.P * pb.Q));
         a.div_q = make_fastdiv((uint32_t)pb.Q);
         a.div_c = make_fastdiv((uint32_t)pb.C);
-        launch_wgrad_fast(pl.tile, a, g, st);
+        if (bf) launch_wgrad_bf16(pl.tile, a, g.grid, need_lds + g.dyn_lds, st);
+        else launch_wgrad_fast(pl.tile, a, g, st);
         int rc = check_launch();
         if (rc != kStatusOk) return rc;
         const int count = pb.K * pl.Kg;
