@@ -166,6 +166,19 @@ def main():
     }
 
     bf16 = bf16_layers(N, hp, synth, conv_flops, torch)
+    # the same step with bf16 convolution inputs (fp32 accumulation and outputs, fp32 glue, conversions included)
+    del stack
+    bstack = ConvStack(N, dtype="bf16")
+    for _ in range(3):
+        bstack.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        bstack.step()
+    torch.cuda.synchronize()
+    bf16_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    bf16["stack_ms_per_step"] = round(bf16_ms, 4)
+    bf16["stack_tflops"] = round(flops / bf16_ms / 1e9, 2)
 
     value = flops / ms_per_step / 1e9
     out = {

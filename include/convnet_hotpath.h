@@ -171,6 +171,13 @@ int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, in
 int relu_maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream);
 int relu_maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream);
 
+/*
+ * fp32 -> bfloat16 with round-to-nearest-even, for callers that chain
+ * CONV_DTYPE_BF16 layers (the passes produce fp32; the next layer's bf16 input
+ * is this rounding of it).  dst holds `count` 2-byte values; device pointers.
+ */
+int convert_f32_to_bf16(const void *src, void *dst, int64_t count, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = (
     "conv_fwd_ex", "conv_bwd_data_ex", "conv_bwd_filter_ex",
     "conv_workspace_bytes", "conv_status_string", "conv_last_hip_error",
     "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
-    "relu_maxpool3x3s2_fwd", "relu_maxpool3x3s2_bwd",
+    "relu_maxpool3x3s2_fwd", "relu_maxpool3x3s2_bwd", "convert_f32_to_bf16",
 )
 
 _lib = None
@@ -68,6 +68,8 @@ def lib():
     L.relu_bwd.argtypes = [vp, vp, vp, i64, vp]
     L.maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, vp]
     L.maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, vp]
+    L.convert_f32_to_bf16.argtypes = [vp, vp, i64, vp]
+    L.convert_f32_to_bf16.restype = i
     L.relu_maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, vp]
     L.relu_maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, vp]
     for name in ("relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd", "relu_maxpool3x3s2_fwd",
@@ -247,3 +249,13 @@ def relu_maxpool3x3s2_bwd(x, dy, dx=None, stream=None):
     _check(lib().relu_maxpool3x3s2_bwd(_ptr(x), _ptr(dy), _ptr(dx), N * C, H, W, _stream_handle(stream)),
            "relu_maxpool3x3s2_bwd")
     return dx
+
+
+def convert_f32_to_bf16(src, dst=None, stream=None):
+    """Round an fp32 tensor to bfloat16 (nearest even) into `dst` (same shape, contiguous)."""
+    if dst is None:
+        dst = torch.empty(src.shape, dtype=torch.bfloat16, device=src.device)
+    if not src.is_contiguous() or not dst.is_contiguous():
+        raise ValueError("convert_f32_to_bf16 needs contiguous tensors")
+    _check(lib().convert_f32_to_bf16(_ptr(src), _ptr(dst), src.numel(), _stream_handle(stream)), "convert_f32_to_bf16")
+    return dst

@@ -93,10 +93,25 @@ __global__ void relayout_filters(const float *__restrict__ w, float *__restrict_
     wt[i] = v;
 }
 
-__global__ void widen_bf16(const unsigned short *__restrict__ src, float *__restrict__ dst, int64_t n)
+// fp32 -> bf16, round to nearest even (NaN stays NaN)
+__global__ void narrow_to_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, int64_t n)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) dst[i] = __uint_as_float((unsigned)src[i] << 16);
+    if (i >= n) return;
+    const unsigned u = __float_as_uint(src[i]);
+    unsigned r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) r = (u >> 16) | 0x40u;
+    dst[i] = (unsigned short)r;
+}
+
+// dst: dense [batch][sample]; src: samples `src_bs` elements apart
+__global__ void widen_bf16(const unsigned short *__restrict__ src, float *__restrict__ dst, int64_t n,
+                           int64_t sample, int64_t src_bs)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int64_t b = i / sample;
+    dst[i] = __uint_as_float((unsigned)src[b * src_bs + (i - b * sample)] << 16);
 }
 
 // ---------------------------------------------------------------------------
@@ -1804,7 +1819,6 @@ int check_launch()
 
 bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
-static int dbg_env(const char *name, int dflt) { const char *e = getenv(name); return e ? atoi(e) : dflt; }
 
 // Tiles are spread evenly over the 8 XCDs (32 CUs each).  When that gives at
 // most `cap` <= 3 work-groups per CU, extra dynamic LDS is requested so that no
@@ -1819,7 +1833,6 @@ GridPlan plan_grid(int tiles, int static_lds)
     g.tiles_per_xcd = ceil_div(tiles, 8);
     g.grid = 8 * g.tiles_per_xcd;
     int cap = ceil_div(g.tiles_per_xcd, 32);
-    cap = dbg_env("CONVNET_CAP", cap);
     int total = static_lds;
     if (cap == 3) total = 52 * 1024;
     else if (cap <= 2) total = 64 * 1024;
@@ -1933,29 +1946,36 @@ int prepare(int op, const void *a, const void *b, void *out, int N, int C, int H
     return kStatusOk;
 }
 
-const float *as_f32(const void *src, int64_t count, int dtype, char *ws, const Plan &pl, int slot, hipStream_t st)
+// fp32 view of an input: the caller's tensor, or (plan says widen) a dense fp32 copy of `batch` samples of
+// `sample` elements that lie `*bs` elements apart; *bs becomes the copy's stride.
+const float *as_f32(const void *src, int batch, int64_t sample, int64_t *bs, char *ws, const Plan &pl, int slot,
+                    hipStream_t st)
 {
-    if (dtype == kDtypeF32) return static_cast<const float *>(src);
+    if (!pl.widen) return static_cast<const float *>(src);
     float *dst = reinterpret_cast<float *>(ws + pl.cvt_off[slot]);
+    const int64_t count = batch * sample;
     hipLaunchKernelGGL(widen_bf16, dim3(grid1d(count, 256)), dim3(256), 0, st,
-                       static_cast<const unsigned short *>(src), dst, count);
+                       static_cast<const unsigned short *>(src), dst, count, sample, *bs);
+    *bs = sample;
     return dst;
 }
 
-int run_colgemm(int op, const void *act, const void *w, void *out, const Problem &pb, const Plan &pl,
+int run_colgemm(int op, const void *act, const void *w, void *out, const Problem &caller_pb, const Plan &pl,
                 void *ws, hipStream_t st)
 {
+    Problem pb = caller_pb;                     // batch stride of a widened input changes below
     char *wsb = static_cast<char *>(ws);
     int4 *tab = reinterpret_cast<int4 *>(wsb + pl.tab_off);
     float *wt = reinterpret_cast<float *>(wsb + pl.wt_off);
     const int RS = pb.R * pb.S;
     const bool fwd = op == kOpFwd;
-    const int64_t act_elems = (int64_t)pb.N * (fwd ? pb.x_bs : pb.y_bs);
     const int Cr = fwd ? pb.C : pb.K;          // channels of the gathered tensor
     const bool fast = Cr % kChunk == 0 && (fwd || pb.stride == 1);
-    const bool bf = pb.dtype == kDtypeBf16 && fast;     // bf16 MFMA kernel reads the caller's tensors directly
-    const float *actf = bf ? nullptr : as_f32(act, act_elems, pb.dtype, wsb, pl, 0, st);
-    const float *wf = bf ? nullptr : as_f32(w, (int64_t)pb.K * pb.C * RS, pb.dtype, wsb, pl, 1, st);
+    const bool bf = pb.dtype == kDtypeBf16 && !pl.widen;     // bf16 MFMA kernel reads the caller's tensors directly
+    int64_t w_bs = (int64_t)pb.K * pb.C * RS;
+    const float *actf = fwd ? as_f32(act, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st)
+                            : as_f32(act, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 0, st);
+    const float *wf = as_f32(w, 1, w_bs, &w_bs, wsb, pl, 1, st);
 
     if (fast) {
         const int kc = bf ? (Cr % 64 == 0 ? 64 : 16) : pl.kc;
@@ -2068,16 +2088,17 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
     return check_launch();
 }
 
-int run_wgrad(const void *x, const void *dy, void *dw, const Problem &pb, const Plan &pl, void *ws, hipStream_t st)
+int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb, const Plan &pl, void *ws,
+              hipStream_t st)
 {
+    Problem pb = caller_pb;                     // batch strides of widened inputs change below
     char *wsb = static_cast<char *>(ws);
     int4 *tab = reinterpret_cast<int4 *>(wsb + pl.tab_off);
     const int RS = pb.R * pb.S;
     // bf16 MFMA kernel: reads the caller's bf16 tensors directly (128-column tiles only)
-    const bool bf = pb.dtype == kDtypeBf16 && pb.C % kChunk == 0 && pl.tile.bn() == 128;
-    const float *xf = bf ? static_cast<const float *>(x) : as_f32(x, (int64_t)pb.N * pb.x_bs, pb.dtype, wsb, pl, 0, st);
-    const float *dyf = bf ? static_cast<const float *>(dy)
-                          : as_f32(dy, (int64_t)pb.N * pb.y_bs, pb.dtype, wsb, pl, 1, st);
+    const bool bf = pb.dtype == kDtypeBf16 && !pl.widen;
+    const float *xf = as_f32(x, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st);
+    const float *dyf = as_f32(dy, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 1, st);
     if (pb.C % kChunk == 0) {
         WgradFastArgs a;
         a.dy = dyf; a.x = xf; a.part = reinterpret_cast<float *>(wsb + pl.part_off);
@@ -2269,6 +2290,16 @@ const char *conv_status_string(int status)
 }
 
 const char *conv_last_hip_error(void) { return g_hip_error; }
+
+int convert_f32_to_bf16(const void *src, void *dst, int64_t count, void *stream)
+{
+    if (!src || !dst || count < 0) return kErrInvalidArg;
+    if (count == 0) return kStatusOk;
+    if (!aligned(src, 4) || !aligned(dst, 2)) return kErrMisaligned;
+    hipLaunchKernelGGL(narrow_to_bf16, dim3(grid1d(count, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const float *>(src), static_cast<unsigned short *>(dst), count);
+    return check_launch();
+}
 
 int relu_fwd(const void *x, void *y, int64_t count, void *stream)
 {

@@ -119,6 +119,7 @@ struct Plan {
     size_t tab_off, tab_bytes;
     size_t wt_off, wt_bytes;          // re-laid-out filters (fwd, dgrad)
     size_t part_off, part_bytes;      // wgrad partials
+    bool widen;                       // bf16 inputs are widened to dense fp32 copies first (no bf16 kernel for the shape)
     size_t cvt_off[2], cvt_bytes[2];  // bf16 -> fp32 staging of the two inputs
     size_t total;
 };
@@ -132,10 +133,6 @@ inline Plan make_plan(int op, const Problem &pb)
     else if (op == kOpBwdData) { pl.M = pb.C; pl.Kg = pb.K * RS; }
     else { pl.M = pb.K; pl.Kg = pb.C * RS; }
     pl.tile = pick_tile(pl.M);
-    if (const char *e = getenv("CONVNET_FORCE_TILE")) {
-        const TileShape cand[4] = {kTile128x128, kTile96x128, kTile64x128, kTile32x256};
-        pl.tile = cand[atoi(e) & 3];
-    }
     pl.Mpad = round_up(pl.M, pl.tile.bm());
     pl.Kgpad = round_up(pl.Kg, kChunk);
     pl.tab_len = round_up(pl.Kg + 2 * kChunk, kTapTablePad);   // two steps of slack for the prefetch
@@ -201,9 +198,15 @@ inline Plan make_plan(int op, const Problem &pb)
         }
         if (pl.chunks_per_split == 0) pl.chunks_per_split = pl.Kgpad / kChunk;
     }
-    if (pb.dtype == kDtypeBf16) {
-        // inputs are widened to fp32 once, then the fp32 kernels run on the copies
-        const int64_t x_e = (int64_t)pb.N * pb.x_bs, y_e = (int64_t)pb.N * pb.y_bs;
+    // bf16 inputs go straight to the bf16 MFMA kernels where the gathered channel count is a multiple of 16
+    // (backward-filter: 128-column tiles only); other shapes are widened to dense fp32 copies, batch strides
+    // dropped, and take the fp32 kernels
+    const int Cr = op == kOpBwdData ? pb.K : pb.C;
+    const bool bf16_kernel = Cr % kChunk == 0 &&
+        (op == kOpFwd || (op == kOpBwdData && pb.stride == 1) || (op == kOpBwdFilter && pl.tile.bn() == 128));
+    pl.widen = pb.dtype == kDtypeBf16 && !bf16_kernel;
+    if (pl.widen) {
+        const int64_t x_e = (int64_t)pb.N * pb.C * pb.H * pb.W, y_e = (int64_t)pb.N * pb.K * pb.P * pb.Q;
         const int64_t w_e = (int64_t)pb.K * pb.C * RS;
         int64_t a = op == kOpFwd ? x_e : (op == kOpBwdData ? y_e : x_e);
         int64_t b = op == kOpBwdFilter ? y_e : w_e;

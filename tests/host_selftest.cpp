@@ -59,6 +59,19 @@ int main()
     CHECK(pl.M == 384 && pl.Kg == 2304 && pl.Kgpad == 2304 && pl.wt_bytes == (size_t)384 * 2304 * 4);
     pl = make_plan(kOpBwdData, pb);
     CHECK(pl.M == 256 && pl.Kg == 3456);
+    // the workspace need does not depend on the batch strides, for either dtype and for widened shapes too
+    for (int dt = 0; dt < 2; ++dt)
+        for (int op = kOpFwd; op <= kOpBwdFilter; ++op) {
+            Problem dense, wide;
+            CHECK(make_problem(dense, 5, 21, 27, 27, 33, 5, 5, 1, 2, 0, 0, dt) == kStatusOk);
+            CHECK(make_problem(wide, 5, 21, 27, 27, 33, 5, 5, 1, 2, 96 * 729, 256 * 729, dt) == kStatusOk);
+            CHECK(make_plan(op, dense).total == make_plan(op, wide).total);
+            CHECK(make_plan(op, dense).widen == (dt == 1));
+            CHECK(make_problem(dense, 5, 48, 27, 27, 128, 5, 5, 1, 2, 0, 0, dt) == kStatusOk);
+            CHECK(make_problem(wide, 5, 48, 27, 27, 128, 5, 5, 1, 2, 96 * 729, 256 * 729, dt) == kStatusOk);
+            CHECK(make_plan(op, dense).total == make_plan(op, wide).total);
+            CHECK(!make_plan(op, dense).widen);
+        }
     std::printf("%llu divisions checked, %d failures\n", checked, fails);
     return fails ? 1 : 0;
 }

@@ -203,6 +203,28 @@ def test_channel_slices_of_wider_tensors():
     assert norm_err(dw.cpu().numpy(), oracle.conv_bwd_filter(xs, dys, 5, 5, st, pad)) <= TOL["f32"]
 
 
+@pytest.mark.parametrize("c0,c1,k0,k1", [(48, 96, 128, 256),      # channel counts the bf16 kernels take
+                                         (8, 29, 8, 41)])          # widened to dense fp32 copies first
+def test_bf16_channel_slices_of_wider_tensors(c0, c1, k0, k1):
+    N, st, pad = 3, 1, 2
+    xw = synth.to_bf16_grid(synth.gaussian((N, 96, 27, 27), 151))
+    w = synth.to_bf16_grid(synth.gaussian((k1 - k0, c1 - c0, 5, 5), 152, 0.01))
+    dyw = synth.to_bf16_grid(synth.gaussian((N, 256, 27, 27), 153))
+    xwd, wd, dywd = (dev(a).to(torch.bfloat16) for a in (xw, w, dyw))
+    ywd = nan_like((N, 256, 27, 27))
+    dxwd = nan_like((N, 96, 27, 27))
+    hp.conv_fwd(xwd[:, c0:c1], wd, st, pad, y=ywd[:, k0:k1])
+    hp.conv_bwd_data(dywd[:, k0:k1], wd, 27, 27, st, pad, dx=dxwd[:, c0:c1])
+    dw = hp.conv_bwd_filter(xwd[:, c0:c1], dywd[:, k0:k1], 5, 5, st, pad)
+    torch.cuda.synchronize()
+    assert torch.isnan(ywd[:, :k0]).all() and torch.isnan(ywd[:, k1:]).all()
+    assert torch.isnan(dxwd[:, :c0]).all() and torch.isnan(dxwd[:, c1:]).all()
+    xs, dys = xw[:, c0:c1], dyw[:, k0:k1]
+    assert norm_err(ywd[:, k0:k1].cpu().numpy(), oracle.conv_fwd(xs, w, st, pad)) <= TOL["bf16"]
+    assert norm_err(dxwd[:, c0:c1].cpu().numpy(), oracle.conv_bwd_data(dys, w, 27, 27, st, pad)) <= TOL["bf16"]
+    assert norm_err(dw.cpu().numpy(), oracle.conv_bwd_filter(xs, dys, 5, 5, st, pad)) <= TOL["bf16"]
+
+
 # ------------------------------- full-size layers, sampled against oracle ---
 FULL = [
     # layer, N, passes, dtypes
@@ -365,3 +387,40 @@ def test_stack_step_layer_by_layer():
     assert norm_err(da1[:, 48:], oracle.conv_bwd_data(dy2[:, 128:], w["conv2b"], 27, 27, 1, 2)) <= tol
     assert norm_err(dy1, oracle.relu_bwd(y1, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y1), da1))) <= 1e-6
     assert norm_err(dw["conv1"], oracle.conv_bwd_filter(x0, dy1, 11, 11, 4, 2)) <= tol
+
+
+def test_convert_f32_to_bf16_is_round_to_nearest_even():
+    x = synth.gaussian((100003,), 181)
+    x[:6] = [0.0, -0.0, 1.0, 1.00390625, 1.01171875, -3.3895314e38]      # exact, tie to even (down / up), large
+    got = hp.convert_f32_to_bf16(dev(x))
+    want = synth.bf16_bits(synth.to_bf16_grid(x))
+    assert np.array_equal(got.view(torch.int16).cpu().numpy().view(np.uint16), want)
+
+
+def test_bf16_stack_step_layer_by_layer():
+    """bf16 mode of the stack: every convolution against the oracle applied to the bf16 tensors it actually read."""
+    from paper_1312_5853_amd.stack import ConvStack
+    st = ConvStack(2, dtype="bf16")
+    st.step()
+    torch.cuda.synchronize()
+    f = lambda t: t.float().cpu().numpy()
+    b, wb, dw = {k: f(v) for k, v in st.b.items()}, {k: f(v) for k, v in st.wb.items()}, {k: f(v) for k, v in st.dw.items()}
+    y1, y2, y3, y4, y5, da2, da1 = map(f, (st.y1, st.y2, st.y3, st.y4, st.y5, st.da2, st.da1))
+    tol = TOL["bf16"]
+    assert norm_err(y1, oracle.conv_fwd(b["x0"], wb["conv1"], 4, 2)) <= tol
+    assert norm_err(y2[:, :128], oracle.conv_fwd(b["a1"][:, :48], wb["conv2a"], 1, 2)) <= tol
+    assert norm_err(y2[:, 128:], oracle.conv_fwd(b["a1"][:, 48:], wb["conv2b"], 1, 2)) <= tol
+    assert norm_err(y3, oracle.relu_fwd(oracle.conv_fwd(b["a2"], wb["conv3"], 1, 1))) <= tol
+    assert norm_err(y4, oracle.relu_fwd(oracle.conv_fwd(b["y3"], wb["conv4"], 1, 1))) <= tol
+    assert norm_err(y5, oracle.conv_fwd(b["y4"], wb["conv5"], 1, 1)) <= tol
+    # the bf16 images are the roundings of what the fp32 glue produced
+    assert np.array_equal(b["y4"], synth.to_bf16_grid(y4)) and np.array_equal(b["a1"], synth.to_bf16_grid(f(st.a1)))
+    assert norm_err(dw["conv5"], oracle.conv_bwd_filter(b["y4"], b["dy5"], 3, 3, 1, 1)) <= tol
+    assert norm_err(dw["conv4"], oracle.conv_bwd_filter(b["y3"], b["dy4"], 3, 3, 1, 1)) <= tol
+    assert norm_err(dw["conv3"], oracle.conv_bwd_filter(b["a2"], b["dy3"], 3, 3, 1, 1)) <= tol
+    assert norm_err(da2, oracle.conv_bwd_data(b["dy3"], wb["conv3"], 13, 13, 1, 1)) <= tol
+    assert norm_err(dw["conv2a"], oracle.conv_bwd_filter(b["a1"][:, :48], b["dy2"][:, :128], 5, 5, 1, 2)) <= tol
+    assert norm_err(dw["conv2b"], oracle.conv_bwd_filter(b["a1"][:, 48:], b["dy2"][:, 128:], 5, 5, 1, 2)) <= tol
+    assert norm_err(da1[:, :48], oracle.conv_bwd_data(b["dy2"][:, :128], wb["conv2a"], 27, 27, 1, 2)) <= tol
+    assert norm_err(da1[:, 48:], oracle.conv_bwd_data(b["dy2"][:, 128:], wb["conv2b"], 27, 27, 1, 2)) <= tol
+    assert norm_err(dw["conv1"], oracle.conv_bwd_filter(b["x0"], b["dy1"], 11, 11, 4, 2)) <= tol

@@ -94,7 +94,10 @@ def test_workspace_bytes(lib):
     a = lib.conv_workspace_bytes(0, *dims, 0)
     assert a == lib.conv_workspace_bytes(0, *dims, 0) and a >= 384 * 2304 * 4
     assert lib.conv_workspace_bytes(2, *dims, 0) >= 384 * 2304 * 4
-    assert lib.conv_workspace_bytes(1, *dims, 1) > lib.conv_workspace_bytes(1, *dims, 0)     # bf16 staging
+    assert lib.conv_workspace_bytes(1, *dims, 1) <= lib.conv_workspace_bytes(1, *dims, 0)    # bf16 kernel, no staging
+    odd = [4, 3, 32, 32, 20, 5, 5, 2, 1]                                                     # widened to fp32 copies
+    for op in (0, 1, 2):
+        assert lib.conv_workspace_bytes(op, *odd, 1) > lib.conv_workspace_bytes(op, *odd, 0)
     assert lib.conv_workspace_bytes(3, *dims, 0) == 0
     assert lib.conv_workspace_bytes(0, 0, 256, 13, 13, 384, 3, 3, 1, 1, 0) == 0
 
@@ -145,3 +148,13 @@ def test_host_planning_selftest(tmp_path):
     out = subprocess.run([exe], capture_output=True, text=True)
     assert out.returncode == 0, out.stdout
     assert "0 failures" in out.stdout
+
+
+def test_convert_argument_checks(lib):
+    from paper_1312_5853_amd import binding as b
+    assert lib.convert_f32_to_bf16(None, PTR, 8, None) == b.ERR_INVALID_ARG
+    assert lib.convert_f32_to_bf16(PTR, None, 8, None) == b.ERR_INVALID_ARG
+    assert lib.convert_f32_to_bf16(PTR, PTR, -1, None) == b.ERR_INVALID_ARG
+    assert lib.convert_f32_to_bf16(PTR + 2, PTR, 8, None) == b.ERR_MISALIGNED
+    assert lib.convert_f32_to_bf16(PTR, PTR + 1, 8, None) == b.ERR_MISALIGNED
+    assert lib.convert_f32_to_bf16(PTR, PTR, 0, None) == b.OK
