@@ -1730,42 +1730,90 @@ __global__ void maxpool_fwd_kernel(const float *__restrict__ x, float *__restric
 // With RELU the input x is the pre-activation: the window maximum of relu(x)
 // sits where the maximum of x sits whenever it is positive, and a non-positive
 // maximum passes no gradient, so dx = [x > 0] * (pooled gradient routed by x).
-template <bool RELU>
+//
+// The pass is HBM-bound (read x and dy, write dx once each), so the loop is
+// built to keep loads in flight: a thread holds NR elements of the next group
+// of planes (and its NR/4 gradients) in registers, fetched while the current
+// group is being worked on in LDS; index arithmetic uses multiply-shift division.
+// group * H*W <= 256 * NR; windows are fewer than a quarter of the elements.
+template <bool RELU, int NR>
 __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const float *__restrict__ x, const float *__restrict__ dy,
                                                           float *__restrict__ dx, int64_t planes, int H, int W,
-                                                          int PH, int PW, int group)
+                                                          int PH, int PW, int group, FastDiv dHW, FastDiv dW,
+                                                          FastDiv dPP, FastDiv dPW)
 {
+    constexpr int NG = NR / 4;
     extern __shared__ float pool_lds[];
     const int HW = H * W, PP = PH * PW;
-    float *sx = pool_lds;                                   // group * HW values
-    int *sarg = reinterpret_cast<int *>(pool_lds + group * HW);   // group * PP window choices
-    for (int64_t pl0 = (int64_t)blockIdx.x * group; pl0 < planes; pl0 += (int64_t)gridDim.x * group) {
+    float *sx = pool_lds;                                                      // group * HW values
+    float2 *swin = reinterpret_cast<float2 *>(pool_lds + ((group * HW + 1) & ~1));   // {chosen element, gradient}
+    const int tid = threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * group;
+    float xr[NR], gr[NG];
+
+    auto fetch = [&](int64_t pl0) {
         const int np = (int)min((int64_t)group, planes - pl0);
         const float *xg = x + pl0 * HW;
         const float *gg = dy + pl0 * PP;
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            const int e = tid + 256 * k;
+            xr[k] = e < np * HW ? xg[e] : 0.f;
+        }
+#pragma unroll
+        for (int k = 0; k < NG; ++k) {
+            const int o = tid + 256 * k;
+            gr[k] = o < np * PP ? gg[o] : 0.f;
+        }
+    };
+
+    int64_t pl0 = (int64_t)blockIdx.x * group;
+    if (pl0 < planes) fetch(pl0);
+    for (; pl0 < planes; pl0 += stride) {
+        const int np = (int)min((int64_t)group, planes - pl0);
         float *og = dx + pl0 * HW;
-        for (int e = threadIdx.x; e < np * HW; e += 256) sx[e] = xg[e];
-        __syncthreads();
-        for (int o = threadIdx.x; o < np * PP; o += 256) {
-            const int pl = o / PP, rem = o - pl * PP;
-            const int i = rem / PW, j = rem - i * PW;
-            float m;
-            sarg[o] = pool_argmax(sx + pl * HW, W, i, j, m);
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            const int e = tid + 256 * k;
+            if (e < np * HW) sx[e] = xr[k];
         }
         __syncthreads();
-        for (int e = threadIdx.x; e < np * HW; e += 256) {
-            const int pl = e / HW, self = e - pl * HW;
-            const int h = self / W, w = self - h * W;
-            int i_lo = h >= 2 ? (h - 1) / 2 : 0, i_hi = min(h / 2, PH - 1);
-            int j_lo = w >= 2 ? (w - 1) / 2 : 0, j_hi = min(w / 2, PW - 1);
-            float sum = 0.f;
-            for (int i = i_lo; i <= i_hi; ++i)
-                for (int j = j_lo; j <= j_hi; ++j) {
-                    const int o = pl * PP + i * PW + j;
-                    if (sarg[o] == self) sum += gg[o];
-                }
-            if (RELU && !(sx[e] > 0.f)) sum = 0.f;
-            og[e] = sum;
+#pragma unroll
+        for (int k = 0; k < NG; ++k) {
+            const int o = tid + 256 * k;
+            if (o < np * PP) {
+                const int pl = (int)fastdiv((uint32_t)o, dPP), rem = o - pl * PP;
+                const int i = (int)fastdiv((uint32_t)rem, dPW), j = rem - i * PW;
+                float m;
+                const int best = pool_argmax(sx + pl * HW, W, i, j, m);
+                swin[o] = make_float2(__int_as_float(best), gr[k]);
+            }
+        }
+        if (pl0 + stride < planes) fetch(pl0 + stride);
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < NR; ++k) {
+            const int e = tid + 256 * k;
+            if (e < np * HW) {
+                const int pl = (int)fastdiv((uint32_t)e, dHW), self = e - pl * HW;
+                const int h = (int)fastdiv((uint32_t)self, dW), w = self - h * W;
+                // windows over row h: i1 = h/2, and i0 = h/2 - 1 when h is even (same for columns)
+                const int i1 = h >> 1, i0 = i1 - 1, j1 = w >> 1, j0 = j1 - 1;
+                const bool vi0 = ((h & 1) == 0) & (i0 >= 0) & (i0 < PH), vi1 = i1 < PH;
+                const bool vj0 = ((w & 1) == 0) & (j0 >= 0) & (j0 < PW), vj1 = j1 < PW;
+                const float2 *wp = swin + pl * PP;
+                float sum = 0.f;
+                auto take = [&](bool ok, int i, int j) {
+                    const float2 c = wp[ok ? i * PW + j : 0];
+                    sum += (ok & (__float_as_int(c.x) == self)) ? c.y : 0.f;
+                };
+                take(vi0 & vj0, i0, j0);
+                take(vi0 & vj1, i0, j1);
+                take(vi1 & vj0, i1, j0);
+                take(vi1 & vj1, i1, j1);
+                if (RELU && !(sx[e] > 0.f)) sum = 0.f;
+                og[e] = sum;
+            }
         }
         __syncthreads();
     }
@@ -2186,15 +2234,23 @@ int pool_bwd_impl(const void *x, const void *dy, void *dx, int64_t planes, int H
     if (rc != kStatusOk) return rc;
     if (!aligned(x, 4) || !aligned(dy, 4) || !aligned(dx, 4)) return kErrMisaligned;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int per_plane = H * W + PH * PW;                 // LDS words per staged plane
-    if (per_plane <= 12 * 1024) {
-        int group = 4096 / per_plane;                      // about 16 KB of planes per work-group
-        if (group < 1) group = 1;
+    const int HW = H * W, PP = PH * PW;
+    if (HW <= 256 * 40) {
+        // planes staged whole: up to 16 elements per thread (several small planes), else one plane of up to 40
+        const bool small = HW <= 256 * 16;
+        const int group = small ? (256 * 16) / HW : 1;
         int64_t blocks = (planes + group - 1) / group;
-        if (blocks > 256 * 16) blocks = 256 * 16;
-        hipLaunchKernelGGL(maxpool_bwd_tiled<RELU>, dim3((int)blocks), dim3(256), (size_t)group * per_plane * 4, st,
-                           static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx),
-                           planes, H, W, PH, PW, group);
+        if (blocks > 256 * 6) blocks = 256 * 6;
+        const size_t lds = (size_t)((group * HW + 1) & ~1) * 4 + (size_t)group * PP * 8;
+        const FastDiv dHW = make_fastdiv(HW), dW = make_fastdiv(W), dPP = make_fastdiv(PP), dPW = make_fastdiv(PW);
+        const float *xp = static_cast<const float *>(x), *gp = static_cast<const float *>(dy);
+        float *op = static_cast<float *>(dx);
+        if (small)
+            hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 16>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
+                               planes, H, W, PH, PW, group, dHW, dW, dPP, dPW);
+        else
+            hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 40>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
+                               planes, H, W, PH, PW, group, dHW, dW, dPP, dPW);
     } else {
         const int64_t total = planes * H * W;
         hipLaunchKernelGGL(maxpool_bwd_kernel<RELU>, dim3(grid1d(total, 256)), dim3(256), 0, st,

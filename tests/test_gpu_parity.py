@@ -314,7 +314,10 @@ def test_relu_and_pool_match_oracle():
 
 def test_fused_relu_pool_matches_separate_oracle_calls():
     """relu_maxpool3x3s2_fwd/bwd take the pre-activation and must equal ReLU then pooling (and back)."""
-    for (N, C, H, W) in [(3, 5, 55, 55), (2, 7, 27, 27), (9, 33, 13, 13), (1, 1, 3, 3), (2, 2, 8, 5), (1, 2, 120, 115)]:
+    # the last four: one large plane per work-group, the large-plane fallback, and plane counts beyond one
+    # round of the persistent grid (one plane per group, several planes per group)
+    for (N, C, H, W) in [(3, 5, 55, 55), (2, 7, 27, 27), (9, 33, 13, 13), (1, 1, 3, 3), (2, 2, 8, 5), (1, 3, 90, 100),
+                         (1, 2, 120, 115), (20, 83, 55, 55), (32, 251, 27, 27)]:
         x = synth.gaussian((N, C, H, W), 161)
         x[0, 0, :3, :3] = -1.0                                  # a window with no positive entry
         x[0, 0, 0, 0] = -0.5
