@@ -627,8 +627,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
 // address per thread and step) on v_mfma_f32_32x32x16_bf16.  A lane feeds 8
 // consecutive channels of its row per instruction, so the LDS tiles are
 // [row][KC bf16] with 16 bytes of padding per row and every fragment read is one
-// b128.  Gathered activations arrive as 2-byte loads (NCHW: a column's channels
-// are a plane apart) and are packed in pairs when they are staged.
+// b128.  In NCHW a column's channels lie a plane apart, which would make every
+// gathered element its own 2-byte load; block_channels_bf16 therefore first
+// copies the gathered tensor into [n][channel block of 16][h][w][16 channels],
+// so that 8 channels of one position are one 16-byte load that goes to LDS as it
+// is.  KC (channels per step) is 16, 32, 48 or 64.
 // ---------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -640,10 +643,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
     constexpr int PITCHB = KC * 2 + 16;      // bytes per LDS row
     constexpr int NK = KC / 16;              // matrix instructions per 32x32 tile and step
     constexpr int EPT = BN * KC / kThreads;  // gathered channels per thread per step
+    constexpr int NV = EPT / 8;              // ... as 16-byte vectors
     constexpr int A4 = BM * KC / 8;          // 16-byte vectors of the filter slice per step
     constexpr int A4T = (A4 + kThreads - 1) / kThreads;
     static_assert(WM * WN == 4, "four waves per work-group");
-    static_assert(KC == 16 || KC == 64, "step depth");
+    static_assert(KC % 16 == 0 && KC <= 64, "step depth");
     static_assert(EPT % 8 == 0, "a thread stages whole 16-byte groups");
 
     extern __shared__ __attribute__((aligned(16))) float lds_fast[];
@@ -666,7 +670,7 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
 
     const int jc = tid % BN;
     const int grp = uniform(tid / BN);
-    int hb, wb, base;                        // base: byte offset of this column at tap (0, 0), first channel of its group
+    int hb, wb, base;                        // base: byte offset of this column at tap (0, 0) in channel block 0
     {
         const int j = n0 + jc;
         const bool colok = j < p.ncols;
@@ -677,8 +681,14 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
         const int ow = rem - oh * p.OW;
         hb = oh * p.mul + p.add;
         wb = ow * p.mul + p.add;
-        base = 2 * (n * p.src_bs + hb * p.LW + wb) + grp * EPT * p.plane_bytes;
+        base = 32 * (n * p.src_bs + hb * p.LW + wb);          // src_bs: 32-byte position blocks per sample
         if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
+    }
+    int voff[NV];                            // this thread's vectors inside a step: channels grp*EPT + 8v ..+7
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const int c = grp * EPT + 8 * v;
+        voff[v] = (c >> 4) * p.plane_bytes + (c & 15) * 2;
     }
     const char *src_bytes = reinterpret_cast<const char *>(p.src);
     const size_t a_step = (size_t)p.Mpad * (KC / 8);          // 16-byte vectors per step
@@ -687,7 +697,7 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
     const u32x4 *a_ptr = reinterpret_cast<const u32x4 *>(p.At) + (size_t)m0 * (KC / 8) + tid + step_begin * a_step;
 
     u32x4 areg[A4T];
-    unsigned short breg[EPT];
+    u32x4 breg[NV];
     bool bok;
     int a0 = 0;
     int r, s, cboff;
@@ -696,35 +706,35 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
         const int rs = step_begin - cb * (p.R * p.S);
         r = (int)fastdiv((uint32_t)rs, p.div_s);
         s = rs - r * p.S;
-        cboff = cb * KC * p.plane_bytes;
+        cboff = cb * (KC / 16) * p.plane_bytes;
     }
 
     auto slot_tap = [&]() {
         const int dr = p.sign * r, ds = p.sign * s;
         const int hh = hb + dr, ww = wb + ds;
         bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
-        a0 = bok ? base + cboff + 2 * (dr * p.LW + ds) : 0;
+        a0 = bok ? base + cboff + 32 * (dr * p.LW + ds) : 0;
         s += 1;
         const bool ws = s == p.S;
         s = ws ? 0 : s;
         r += ws ? 1 : 0;
         const bool wr = r == p.R;
         r = wr ? 0 : r;
-        cboff += wr ? KC * p.plane_bytes : 0;
+        cboff += wr ? (KC / 16) * p.plane_bytes : 0;
     };
     auto slot_a = [&](int i) {
         if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
         if (i == A4T - 1) a_ptr += a_step;
     };
-    auto slot_b = [&](int e) {
-        breg[e] = *reinterpret_cast<const unsigned short *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
+    auto slot_b = [&](int v) {
+        breg[v] = *reinterpret_cast<const u32x4 *>(src_bytes + (uint32_t)(a0 + voff[v]));
     };
     auto load_step = [&]() {
         slot_tap();
 #pragma unroll
         for (int i = 0; i < A4T; ++i) slot_a(i);
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) slot_b(e);
+        for (int v = 0; v < NV; ++v) slot_b(v);
     };
     auto store_step = [&](int buf) {
         char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
@@ -736,14 +746,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
         }
         char *brow = Bs + jc * PITCHB + grp * EPT * 2;
 #pragma unroll
-        for (int e = 0; e < EPT; e += 8) {
-            u32x4 v;
+        for (int v = 0; v < NV; ++v) {
+            u32x4 q;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const unsigned pair = (unsigned)breg[e + 2 * k] | ((unsigned)breg[e + 2 * k + 1] << 16);
-                v[k] = bok ? pair : 0u;
-            }
-            *reinterpret_cast<u32x4 *>(brow + e * 2) = v;
+            for (int k = 0; k < 4; ++k) q[k] = bok ? breg[v][k] : 0u;
+            *reinterpret_cast<u32x4 *>(brow + v * 16) = q;
         }
     };
 
@@ -759,7 +766,7 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
     const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
     const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
     constexpr int NMMA = NK * TM * TN;
-    constexpr int NSLOT = 1 + A4T + EPT;
+    constexpr int NSLOT = 1 + A4T + NV;
     constexpr int SPM = (NSLOT + (NMMA > 2 ? NMMA - 2 : 1) - 1) / (NMMA > 2 ? NMMA - 2 : 1);
 
     load_step();
@@ -829,6 +836,31 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
             }
         }
     }
+}
+
+// NCHW bf16 (samples src_bs elements apart) -> dst[n][c / 16][h*w][16]: the 16 channels of a block at one
+// position become 32 contiguous bytes.  One thread per (n, block, position); lanes run along positions.
+__global__ void block_channels_bf16(const unsigned short *__restrict__ src, u32x4 *__restrict__ dst, int N, int C,
+                                    int HW, int64_t src_bs, FastDiv div_hw)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)N * (C / 16) * HW;
+    if (i >= total) return;
+    const uint32_t nb = fastdiv((uint32_t)i, div_hw);           // n * (C/16) + block
+    const int pos = (int)((uint32_t)i - nb * (uint32_t)HW);
+    const uint32_t n = nb / (uint32_t)(C / 16), cb = nb - n * (uint32_t)(C / 16);
+    const unsigned short *s = src + n * src_bs + (int64_t)cb * 16 * HW + pos;
+    unsigned short v[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) v[k] = s[(int64_t)k * HW];
+    u32x4 lo, hi;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        lo[k] = (unsigned)v[2 * k] | ((unsigned)v[2 * k + 1] << 16);
+        hi[k] = (unsigned)v[8 + 2 * k] | ((unsigned)v[8 + 2 * k + 1] << 16);
+    }
+    dst[2 * i] = lo;
+    dst[2 * i + 1] = hi;
 }
 
 // bf16 filters for colgemm_bf16_kernel: wt[((cb*R + r)*S + s)][Mpad][kc]
@@ -1929,18 +1961,28 @@ void launch_patch(int tm, const PatchArgs &a, int grid, int lds, hipStream_t st)
     else hipLaunchKernelGGL(colgemm_patch_kernel<4>, dim3(grid), dim3(kThreads), lds, st, a);
 }
 
+template <int KC>
+void launch_colgemm_bf16_kc(const TileShape &t, const ColGemmFastArgs &a, const GridPlan &g, hipStream_t st)
+{
+    const int lds = 2 * (t.bm() + t.bn()) * (KC * 2 + 16) + g.dyn_lds;
+    if (t.TM == 2 && t.TN == 2) launch_dyn(colgemm_bf16_kernel<2, 2, 2, 2, KC>, a, g.grid, lds, st);
+    else if (t.TM == 3) launch_dyn(colgemm_bf16_kernel<3, 1, 1, 4, KC>, a, g.grid, lds, st);
+    else if (t.TM == 2) launch_dyn(colgemm_bf16_kernel<2, 1, 1, 4, KC>, a, g.grid, lds, st);
+    else launch_dyn(colgemm_bf16_kernel<1, 2, 1, 4, KC>, a, g.grid, lds, st);
+}
+
+// channels per step of the bf16 kernel: the largest of 64, 48, 32, 16 that divides the channel count
+int bf16_step_channels(int channels)
+{
+    return channels % 64 == 0 ? 64 : channels % 48 == 0 ? 48 : channels % 32 == 0 ? 32 : 16;
+}
+
 void launch_colgemm_bf16(const TileShape &t, int kc, const ColGemmFastArgs &a, const GridPlan &g, hipStream_t st)
 {
-    const int need = 2 * (t.bm() + t.bn()) * (kc * 2 + 16);
-    const int lds = need + g.dyn_lds;
-    if (t.TM == 2 && t.TN == 2 && kc == 64) launch_dyn(colgemm_bf16_kernel<2, 2, 2, 2, 64>, a, g.grid, lds, st);
-    else if (t.TM == 2 && t.TN == 2) launch_dyn(colgemm_bf16_kernel<2, 2, 2, 2, 16>, a, g.grid, lds, st);
-    else if (t.TM == 3 && kc == 64) launch_dyn(colgemm_bf16_kernel<3, 1, 1, 4, 64>, a, g.grid, lds, st);
-    else if (t.TM == 3) launch_dyn(colgemm_bf16_kernel<3, 1, 1, 4, 16>, a, g.grid, lds, st);
-    else if (t.TM == 2 && kc == 64) launch_dyn(colgemm_bf16_kernel<2, 1, 1, 4, 64>, a, g.grid, lds, st);
-    else if (t.TM == 2) launch_dyn(colgemm_bf16_kernel<2, 1, 1, 4, 16>, a, g.grid, lds, st);
-    else if (kc == 64) launch_dyn(colgemm_bf16_kernel<1, 2, 1, 4, 64>, a, g.grid, lds, st);
-    else launch_dyn(colgemm_bf16_kernel<1, 2, 1, 4, 16>, a, g.grid, lds, st);
+    if (kc == 64) launch_colgemm_bf16_kc<64>(t, a, g, st);
+    else if (kc == 48) launch_colgemm_bf16_kc<48>(t, a, g, st);
+    else if (kc == 32) launch_colgemm_bf16_kc<32>(t, a, g, st);
+    else launch_colgemm_bf16_kc<16>(t, a, g, st);
 }
 
 void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
@@ -2026,7 +2068,7 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
     const float *wf = as_f32(w, 1, w_bs, &w_bs, wsb, pl, 1, st);
 
     if (fast) {
-        const int kc = bf ? (Cr % 64 == 0 ? 64 : 16) : pl.kc;
+        const int kc = bf ? bf16_step_channels(Cr) : pl.kc;
         const int64_t wt_elems = (int64_t)pl.Mpad * Cr * RS;
         if (bf)
             hipLaunchKernelGGL(relayout_filters_cblk_bf16, dim3(grid1d(wt_elems, 256)), dim3(256), 0, st,
@@ -2036,7 +2078,7 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
             hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d(wt_elems, 256)), dim3(256), 0, st, wf, wt, pl.M,
                                pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc);
         ColGemmFastArgs a;
-        a.At = wt; a.src = bf ? static_cast<const float *>(act) : actf; a.dst = static_cast<float *>(out);
+        a.At = wt; a.src = actf; a.dst = static_cast<float *>(out);
         a.M = pl.M; a.Mpad = pl.Mpad; a.cblocks = Cr / kc; a.R = pb.R; a.S = pb.S;
         if (fwd) {
             a.sign = 1; a.OH = pb.P; a.OW = pb.Q; a.LH = pb.H; a.LW = pb.W;
@@ -2045,7 +2087,19 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
             a.sign = -1; a.OH = pb.H; a.OW = pb.W; a.LH = pb.P; a.LW = pb.Q;
             a.src_bs = (int)pb.y_bs; a.dst_bs = (int)pb.x_bs; a.mul = 1; a.add = pb.pad;
         }
-        a.plane_bytes = a.LH * a.LW * (bf ? 2 : 4);
+        a.plane_bytes = a.LH * a.LW * 4;
+        if (bf) {
+            // channel-blocked copy of the gathered tensor: 32 bytes per position and block of 16 channels
+            const int LHW = a.LH * a.LW;
+            const int64_t vecs = (int64_t)pb.N * (Cr / 16) * LHW;
+            u32x4 *blk = reinterpret_cast<u32x4 *>(wsb + pl.blk_off);
+            hipLaunchKernelGGL(block_channels_bf16, dim3(grid1d(vecs, 256)), dim3(256), 0, st,
+                               static_cast<const unsigned short *>(act), blk, pb.N, Cr, LHW, (int64_t)a.src_bs,
+                               make_fastdiv((uint32_t)LHW));
+            a.src = reinterpret_cast<const float *>(blk);
+            a.src_bs = (Cr / 16) * LHW;
+            a.plane_bytes = LHW * 32;
+        }
         a.ncols = pb.N * a.OH * a.OW;
         a.mtiles = pl.Mpad / pl.tile.bm();
         a.ntiles = ceil_div(a.ncols, pl.tile.bn());

@@ -121,6 +121,7 @@ struct Plan {
     size_t part_off, part_bytes;      // wgrad partials
     bool widen;                       // bf16 inputs are widened to dense fp32 copies first (no bf16 kernel for the shape)
     size_t cvt_off[2], cvt_bytes[2];  // bf16 -> fp32 staging of the two inputs
+    size_t blk_off, blk_bytes;        // channel-blocked copy of the gathered bf16 tensor (forward, backward-data)
     size_t total;
 };
 
@@ -205,6 +206,11 @@ inline Plan make_plan(int op, const Problem &pb)
     const bool bf16_kernel = Cr % kChunk == 0 &&
         (op == kOpFwd || (op == kOpBwdData && pb.stride == 1) || (op == kOpBwdFilter && pl.tile.bn() == 128));
     pl.widen = pb.dtype == kDtypeBf16 && !bf16_kernel;
+    if (pb.dtype == kDtypeBf16 && bf16_kernel && op != kOpBwdFilter) {
+        pl.blk_off = off;
+        pl.blk_bytes = (size_t)pb.N * Cr * (op == kOpFwd ? pb.H * pb.W : pb.P * pb.Q) * 2;
+        off += round_up64(pl.blk_bytes, 256);
+    }
     if (pl.widen) {
         const int64_t x_e = (int64_t)pb.N * pb.C * pb.H * pb.W, y_e = (int64_t)pb.N * pb.K * pb.P * pb.Q;
         const int64_t w_e = (int64_t)pb.K * pb.C * RS;

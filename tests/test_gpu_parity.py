@@ -102,6 +102,41 @@ def test_odd_shapes_full_compare(shape):
     check_full(x, w, dy, st, pad)
 
 
+BF16_SHAPES = [
+    # channel counts that select 16, 32, 48 and 64 channels per step of the bf16 kernels, every tile shape,
+    # ragged column tiles, a strided forward; passes whose channel count is not a multiple of 16 are widened
+    (3, 16, 9, 11, 24, 3, 3, 1, 1),
+    (2, 32, 13, 13, 160, 3, 3, 1, 1),
+    (5, 48, 10, 7, 96, 5, 5, 1, 2),
+    (2, 64, 12, 12, 48, 3, 3, 2, 1),
+    (4, 128, 13, 13, 20, 3, 3, 1, 1),
+    (3, 80, 7, 7, 64, 1, 1, 1, 0),
+    (7, 192, 6, 5, 256, 3, 2, 1, 1),
+]
+
+
+@pytest.mark.parametrize("shape", BF16_SHAPES)
+def test_bf16_shapes_full_compare(shape):
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+    x = synth.gaussian((N, C, H, W), 104)
+    w = synth.gaussian((K, C, R, S), 105, 0.1)
+    dy = synth.gaussian((N, K, P, Q), 106)
+    check_full(x, w, dy, st, pad, "bf16")
+
+
+def test_bf16_small_integers_are_exact():
+    """Small integers are exact in bf16 and their sums in fp32: the bf16 kernels must return them bit for bit."""
+    N, C, H, W, K, R, S, st, pad = 3, 32, 9, 10, 48, 3, 3, 1, 1
+    x = synth.small_integers((N, C, H, W), 114)
+    w = synth.small_integers((K, C, R, S), 115)
+    dy = synth.small_integers((N, K, H, W), 116)
+    y, dx, dw = run_three(x, w, dy, st, pad, "bf16")
+    np.testing.assert_array_equal(y, oracle.conv_fwd(x, w, st, pad))
+    np.testing.assert_array_equal(dx, oracle.conv_bwd_data(dy, w, H, W, st, pad))
+    np.testing.assert_array_equal(dw, oracle.conv_bwd_filter(x, dy, R, S, st, pad))
+
+
 def test_small_integers_are_exact():
     """Integer-valued inputs with small sums are exact in fp32: bit-for-bit equality."""
     N, C, H, W, K, R, S, st, pad = 2, 6, 11, 12, 40, 3, 3, 2, 1
