@@ -1657,6 +1657,234 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(const WgradFastArg
     }
 }
 
+// ---------------------------------------------------------------------------
+// Backward-filter with bf16 inputs for stride-1 layers whose output has the
+// input's extent (R - 1 = S - 1 = 2 * pad): every MFMA operand (8 consecutive
+// reduction positions of a row) is ONE 16-byte global load.
+//
+// Two packing passes lay the tensors out for that.  With row pitch Wq = W + pad,
+//   dyp[k][n][Jy]: dy(n, k, p, q) at j = p*Wq + q, zeros in the pad columns and in
+//                  the tail up to Jy (a multiple of 8); rows zero-filled up to a
+//                  whole number of 64-position steps;
+//   xp[c][n][Jx]:  x(n, c, h, w) at (h + pad)*Wq + (w + pad), zeros elsewhere.
+// The input element that dy position j meets under tap (r, s) then sits at
+// j + r*Wq + s of the same image: a column that would wrap lands in the pad
+// columns of the neighbouring row (one gap serves as right pad of a row and left
+// pad of the next), a row out of range in the zero rows above and below.  No
+// masks and no per-element addresses are left; positions where dy is zero cost
+// (Jy / (P*Q) - 1) extra matrix work, 9 % at 13x13.
+// The x loads are 2-byte aligned only (the tap shift is arbitrary).
+// Columns in (r, s, c) order, partials [split][K][R*S*C] as in wgrad_fast_kernel.
+// ---------------------------------------------------------------------------
+struct WgradLinArgs {
+    const unsigned short *dyp;
+    const unsigned short *xp;
+    float *part;
+    int K, C, ncols;
+    int S, Wq;
+    int N, G, Jx;             // G = Jy / 8 groups of 8 positions per image
+    int row_a_bytes;          // bytes per dyp row
+    int row_x_bytes;          // bytes per xp row (N * Jx * 2)
+    int steps, steps_per_split;
+    int mtiles, ntiles, nunits, units_per_xcd;
+    FastDiv div_c, div_s, div_g;
+};
+
+typedef u32x4 u32x4_align2 __attribute__((aligned(2)));
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(kThreads) void wgrad_bf16_lin_kernel(const WgradLinArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int KJ = 64, NK = KJ / 16;
+    constexpr int PITCHB = KJ * 2 + 16;
+    constexpr int RA = BM / 32, RB = BN / 32;      // 16-byte vectors per thread and step
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    char *const As0 = reinterpret_cast<char *>(lds_fast);
+    char *const Bs0 = As0 + 2 * BM * PITCHB;
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.units_per_xcd + idx;
+    if (idx >= p.units_per_xcd || unit >= p.nunits) return;
+    const int ntile = p.mtiles * p.ntiles;
+    const int split = unit / ntile;
+    const int tile = unit - split * ntile;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int jg = tid & 7, r8 = tid >> 3;         // this thread's group of 8 positions in a step; its row inside 32
+
+    const int step_begin = split * p.steps_per_split;
+    const int nsteps = min(p.steps - step_begin, p.steps_per_split);
+
+    uint32_t abase[RA], bbase[RB];
+#pragma unroll
+    for (int i = 0; i < RA; ++i) abase[i] = (uint32_t)min(m0 + r8 + 32 * i, p.K - 1) * (uint32_t)p.row_a_bytes;
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        int col = n0 + r8 + 32 * i;
+        col = col < p.ncols ? col : 0;
+        const int rs = (int)fastdiv((uint32_t)col, p.div_c), c = col - rs * p.C;
+        const int r = (int)fastdiv((uint32_t)rs, p.div_s), sx = rs - r * p.S;
+        bbase[i] = (uint32_t)c * (uint32_t)p.row_x_bytes + 2u * (uint32_t)(r * p.Wq + sx);
+    }
+    // position of this thread's group: g = step*8 + jg = n*G + gg
+    int n, gg;
+    {
+        const int g = step_begin * 8 + jg;
+        n = (int)fastdiv((uint32_t)g, p.div_g);
+        gg = g - n * p.G;
+    }
+    uint32_t aoff = (uint32_t)(step_begin * 8 + jg) * 16u, boff = 0;
+    const char *ap = reinterpret_cast<const char *>(p.dyp), *xp = reinterpret_cast<const char *>(p.xp);
+
+    u32x4 areg[RA], breg[RB];
+    auto slot_pos = [&]() {
+        boff = 2u * (uint32_t)(min(n, p.N - 1) * p.Jx + gg * 8);
+        gg += 8;
+        const bool wrap = gg >= p.G;
+        gg -= wrap ? p.G : 0;
+        n += wrap ? 1 : 0;
+    };
+    auto slot_a = [&](int i) {
+        areg[i] = *reinterpret_cast<const u32x4 *>(ap + (abase[i] + aoff));
+        if (i == RA - 1) aoff += 128u;
+    };
+    auto slot_b = [&](int i) { breg[i] = *reinterpret_cast<const u32x4_align2 *>(xp + (bbase[i] + boff)); };
+    auto load_step = [&]() {
+        slot_pos();
+#pragma unroll
+        for (int i = 0; i < RA; ++i) slot_a(i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) slot_b(i);
+    };
+    auto store_step = [&](int buf) {
+        char *As = As0 + buf * BM * PITCHB + r8 * PITCHB + jg * 16;
+        char *Bs = Bs0 + buf * BN * PITCHB + r8 * PITCHB + jg * 16;
+#pragma unroll
+        for (int i = 0; i < RA; ++i) *reinterpret_cast<u32x4 *>(As + i * 32 * PITCHB) = areg[i];
+#pragma unroll
+        for (int i = 0; i < RB; ++i) *reinterpret_cast<u32x4 *>(Bs + i * 32 * PITCHB) = breg[i];
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
+    const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
+    constexpr int NMMA = NK * TM * TN;
+    constexpr int NSLOT = 1 + RA + RB;
+    constexpr int SPM = (NSLOT + NMMA - 3) / (NMMA - 2);
+
+    if (nsteps > 0) {
+        load_step();
+        store_step(0);
+    }
+    __syncthreads();
+    for (int step = 0; step < nsteps; ++step) {
+        const int buf = step & 1;
+        const bool last = step == nsteps - 1;
+        const char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+        u32x4 fa[TM][NK], fb[TN][NK];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fa[i][t] = *reinterpret_cast<const u32x4 *>(As + a_frag + i * 32 * PITCHB + t * 32);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fb[jn][t] = *reinterpret_cast<const u32x4 *>(Bs + b_frag + jn * 32 * PITCHB + t * 32);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!last) {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                     acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                    if (q == 0) slot_pos();
+                    else if (q - 1 < RA) slot_a(q - 1);
+                    else slot_b(q - 1 - RA);
+                }
+                if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+            }
+            store_step(buf ^ 1);
+            __syncthreads();
+        } else {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                     acc[i][jn], 0, 0, 0);
+            }
+        }
+    }
+
+    float *out = p.part + (size_t)split * p.K * p.ncols;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.ncols + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// dyp[k][e], e < row_elems: image n = e / Jy, j = e % Jy = p*Wq + q; dy(n, k, p, q) where p < P and q < Q, else 0
+__global__ void pack_dy_lin(const unsigned short *__restrict__ dy, unsigned short *__restrict__ dyp, int N, int K,
+                            int P, int Q, int Wq, int Jy, int row_elems, int64_t dy_bs, FastDiv div_row,
+                            FastDiv div_jy, FastDiv div_wq)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)K * row_elems) return;
+    const uint32_t k = fastdiv((uint32_t)i, div_row), e = (uint32_t)i - k * (uint32_t)row_elems;
+    const uint32_t n = fastdiv(e, div_jy), j = e - n * (uint32_t)Jy;
+    const uint32_t pp = fastdiv(j, div_wq), q = j - pp * (uint32_t)Wq;
+    unsigned short v = 0;
+    if (n < (uint32_t)N && pp < (uint32_t)P && q < (uint32_t)Q) v = dy[n * dy_bs + ((int64_t)k * P + pp) * Q + q];
+    dyp[i] = v;
+}
+
+// xp[c][n][e], e < Jx: padded row hh = e / Wq, column ww = e % Wq; x(n, c, hh - pad, ww - pad) where inside, else 0
+__global__ void pack_x_lin(const unsigned short *__restrict__ x, unsigned short *__restrict__ xp, int N, int C, int H,
+                           int W, int pad, int Wq, int Jx, int64_t x_bs, FastDiv div_jx, FastDiv div_wq)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)C * N * Jx) return;
+    const uint32_t cn = fastdiv((uint32_t)i, div_jx), e = (uint32_t)i - cn * (uint32_t)Jx;
+    const uint32_t c = cn / (uint32_t)N, n = cn - c * (uint32_t)N;
+    const uint32_t hh = fastdiv(e, div_wq), ww = e - hh * (uint32_t)Wq;
+    const int h = (int)hh - pad, w = (int)ww - pad;
+    unsigned short v = 0;
+    if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) v = x[n * x_bs + ((int64_t)c * H + h) * W + w];
+    xp[i] = v;
+}
+
 // dw[k][c][rs] = part[0][k][rs*C + c] + part[1][k][rs*C + c] + ...  (fixed order)
 __global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int RS,
                              int nsplit)
@@ -2008,6 +2236,18 @@ void launch_wgrad_bf16(const TileShape &t, const WgradFastArgs &a, int grid, int
     else hipLaunchKernelGGL((wgrad_bf16_kernel<2, 1, 1, 4, KJ>), g, b, lds, st, a);
 }
 
+void launch_wgrad_bf16_lin(const TileShape &t, const WgradLinArgs &a, int grid, int lds, hipStream_t st)
+{
+    const void *k = (t.TM == 2 && t.TN == 2) ? (const void *)wgrad_bf16_lin_kernel<2, 2, 2, 2>
+                  : t.TM == 3 ? (const void *)wgrad_bf16_lin_kernel<3, 1, 1, 4>
+                              : (const void *)wgrad_bf16_lin_kernel<2, 1, 1, 4>;
+    if (lds > 64 * 1024) (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    const dim3 g(grid), b(kThreads);
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((wgrad_bf16_lin_kernel<2, 2, 2, 2>), g, b, lds, st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((wgrad_bf16_lin_kernel<3, 1, 1, 4>), g, b, lds, st, a);
+    else hipLaunchKernelGGL((wgrad_bf16_lin_kernel<2, 1, 1, 4>), g, b, lds, st, a);
+}
+
 void launch_wgrad_fast(const TileShape &t, const WgradFastArgs &a, const GridPlan &g, hipStream_t st)
 {
     const dim3 grid(g.grid), block(kThreads);
@@ -2199,6 +2439,41 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
     const int RS = pb.R * pb.S;
     // bf16 MFMA kernel: reads the caller's bf16 tensors directly (128-column tiles only)
     const bool bf = pb.dtype == kDtypeBf16 && !pl.widen;
+    if (pl.lin) {
+        // same-extent stride-1 layer: pack both tensors, then every operand is a 16-byte load
+        unsigned short *dyp = reinterpret_cast<unsigned short *>(wsb + pl.lin_dy_off);
+        unsigned short *xp = reinterpret_cast<unsigned short *>(wsb + pl.lin_x_off);
+        const int row_elems = pl.lin_steps * 64;
+        hipLaunchKernelGGL(pack_dy_lin, dim3(grid1d((int64_t)pb.K * row_elems, 256)), dim3(256), 0, st,
+                           static_cast<const unsigned short *>(dy), dyp, pb.N, pb.K, pb.P, pb.Q, pl.lin_wq, pl.lin_jy,
+                           row_elems, pb.y_bs, make_fastdiv((uint32_t)row_elems), make_fastdiv((uint32_t)pl.lin_jy),
+                           make_fastdiv((uint32_t)pl.lin_wq));
+        hipLaunchKernelGGL(pack_x_lin, dim3(grid1d((int64_t)pb.C * pb.N * pl.lin_jx, 256)), dim3(256), 0, st,
+                           static_cast<const unsigned short *>(x), xp, pb.N, pb.C, pb.H, pb.W, pb.pad, pl.lin_wq,
+                           pl.lin_jx, pb.x_bs, make_fastdiv((uint32_t)pl.lin_jx), make_fastdiv((uint32_t)pl.lin_wq));
+        WgradLinArgs a;
+        a.dyp = dyp; a.xp = xp; a.part = reinterpret_cast<float *>(wsb + pl.part_off);
+        a.K = pb.K; a.C = pb.C; a.ncols = pl.Kg; a.S = pb.S; a.Wq = pl.lin_wq;
+        a.N = pb.N; a.G = pl.lin_jy / 8; a.Jx = pl.lin_jx;
+        a.row_a_bytes = row_elems * 2; a.row_x_bytes = pb.N * pl.lin_jx * 2;
+        a.steps = pl.lin_steps; a.steps_per_split = pl.chunks_per_split;
+        a.mtiles = pl.Mpad / pl.tile.bm();
+        a.ntiles = ceil_div(pl.Kg, pl.tile.bn());
+        a.nunits = a.mtiles * a.ntiles * pl.nsplit;
+        const int need_lds = 2 * (pl.tile.bm() + pl.tile.bn()) * (64 * 2 + 16);
+        const GridPlan g = plan_grid(a.nunits, need_lds);
+        a.units_per_xcd = g.tiles_per_xcd;
+        a.div_c = make_fastdiv((uint32_t)pb.C);
+        a.div_s = make_fastdiv((uint32_t)pb.S);
+        a.div_g = make_fastdiv((uint32_t)a.G);
+        launch_wgrad_bf16_lin(pl.tile, a, g.grid, need_lds + g.dyn_lds, st);
+        int rc = check_launch();
+        if (rc != kStatusOk) return rc;
+        const int count = pb.K * pl.Kg;
+        hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
+                           pb.K, pb.C, RS, pl.nsplit);
+        return check_launch();
+    }
     const float *xf = as_f32(x, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st);
     const float *dyf = as_f32(dy, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 1, st);
     if (pb.C % kChunk == 0) {

@@ -122,6 +122,11 @@ struct Plan {
     bool widen;                       // bf16 inputs are widened to dense fp32 copies first (no bf16 kernel for the shape)
     size_t cvt_off[2], cvt_bytes[2];  // bf16 -> fp32 staging of the two inputs
     size_t blk_off, blk_bytes;        // channel-blocked copy of the gathered bf16 tensor (forward, backward-data)
+    // bf16 backward-filter of a stride-1 layer whose output has the input's extent: packed copies in which a
+    // filter tap is a linear shift (row pitch lin_wq, lin_jy / lin_jx elements per image), 64 positions per step
+    bool lin;
+    int lin_wq, lin_jy, lin_jx, lin_steps;
+    size_t lin_dy_off, lin_dy_bytes, lin_x_off, lin_x_bytes;
     size_t total;
 };
 
@@ -153,6 +158,24 @@ inline Plan make_plan(int op, const Problem &pb)
         if (nsplit < 1) nsplit = 1;
         pl.chunks_per_split = ceil_div(jchunks, nsplit);
         pl.nsplit = ceil_div(jchunks, pl.chunks_per_split);
+        if (pb.dtype == kDtypeBf16 && pb.C % kChunk == 0 && pl.tile.bn() == 128 && pb.stride == 1 &&
+            pb.P == pb.H && pb.Q == pb.W && pb.R - 1 == 2 * pb.pad && pb.S - 1 == 2 * pb.pad) {
+            const int wq = pb.W + pb.pad;
+            const int jy = round_up(pb.P * wq, 8);
+            const int jx = round_up(jy + (pb.R - 1) * wq + pb.S, 8);
+            const int64_t steps = ((int64_t)pb.N * jy + 63) / 64;
+            const int64_t dy_bytes = (int64_t)pb.K * steps * 64 * 2, x_bytes = (int64_t)pb.C * pb.N * jx * 2;
+            if (jy >= 64 && dy_bytes < kMaxSpanBytes && x_bytes < kMaxSpanBytes) {
+                pl.lin = true;
+                pl.lin_wq = wq; pl.lin_jy = jy; pl.lin_jx = jx; pl.lin_steps = (int)steps;
+                int ns = want < (int)(steps / 4) ? want : (int)(steps / 4);     // at least 4 steps per split
+                if (ns < 1) ns = 1;
+                pl.chunks_per_split = ceil_div((int)steps, ns);
+                pl.nsplit = ceil_div((int)steps, pl.chunks_per_split);
+                pl.lin_dy_off = off; pl.lin_dy_bytes = (size_t)dy_bytes; off += round_up64(pl.lin_dy_bytes, 256);
+                pl.lin_x_off = off; pl.lin_x_bytes = (size_t)x_bytes; off += round_up64(pl.lin_x_bytes, 256);
+            }
+        }
         pl.part_off = off;
         const bool staged = pb.C % kChunk == 0;          // fast path always goes through the partials
         pl.part_bytes = (pl.nsplit > 1 || staged) ? (size_t)pl.nsplit * pb.K * pb.C * RS * 4 : 0;

@@ -112,6 +112,12 @@ BF16_SHAPES = [
     (4, 128, 13, 13, 20, 3, 3, 1, 1),
     (3, 80, 7, 7, 64, 1, 1, 1, 0),
     (7, 192, 6, 5, 256, 3, 2, 1, 1),
+    # backward-filter on packed copies (stride 1, output extent = input extent): 64-, 96- and 128-row tiles,
+    # a reduction that ends inside a 64-position step, and a plane too small for it (falls back)
+    (3, 64, 13, 13, 64, 3, 3, 1, 1),
+    (2, 32, 27, 27, 128, 5, 5, 1, 2),
+    (9, 16, 12, 9, 96, 1, 1, 1, 0),
+    (4, 16, 5, 5, 128, 3, 3, 1, 1),
 ]
 
 
