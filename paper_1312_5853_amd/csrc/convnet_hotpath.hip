@@ -622,6 +622,177 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
 }
 
 // ---------------------------------------------------------------------------
+// The same walk as colgemm_fast_kernel for GEMM views of 33..48 rows (backward-
+// data of a 48-channel column): 32-row matrix tiles would pad 48 rows to 64, so
+// this kernel works in 16 x 16 blocks on v_mfma_f32_16x16x4_f32.  A work-group
+// covers 48 rows x 256 columns, a wave 48 x 64 (3 x 4 blocks).  Per lane the
+// instruction takes A[row = lane%16][k = lane/16] and B[k = lane/16][col =
+// lane%16] and returns D[row = 4*(lane/16) + v][col = lane%16], v = 0..3.  A lane
+// reads the four consecutive reduction elements 4*(lane/16).. of its row with one
+// b128 and feeds element t to the t-th instruction, so the 16 elements of a step
+// are consumed in the order (t, 4+t, 8+t, 12+t) on both operands.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmFastArgs p)
+{
+    constexpr int BM = 48, BN = 256, KC = 16, PITCH = KC + 4;
+    constexpr int TM = 3, TN = 4;            // 16 x 16 blocks per wave
+    constexpr int EPT = KC;                  // a thread gathers all 16 channels of its column
+    constexpr int A4 = BM * KC / 4;          // 192 vectors of the filter slice per step
+
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    float *const As0 = lds_fast;
+    float *const Bs0 = lds_fast + 2 * BM * PITCH;
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.tiles_per_xcd + idx;
+    const int ntile = p.mtiles * p.ntiles;
+    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit) return;
+    const int ks = unit / ntile;
+    const int tile = unit - ks * ntile;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wn = uniform(tid >> 6);
+    const int jc = tid;
+    int hb, wb, base;
+    {
+        const int j = n0 + jc;
+        const bool colok = j < p.ncols;
+        const int jj = colok ? j : 0;
+        const int n = (int)fastdiv((uint32_t)jj, p.div_plane);
+        const int rem = jj - n * (p.OH * p.OW);
+        const int oh = (int)fastdiv((uint32_t)rem, p.div_ow);
+        const int ow = rem - oh * p.OW;
+        hb = oh * p.mul + p.add;
+        wb = ow * p.mul + p.add;
+        base = 4 * (n * p.src_bs + hb * p.LW + wb);
+        if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
+    }
+    const char *src_bytes = reinterpret_cast<const char *>(p.src);
+    const size_t a_step = (size_t)p.Mpad * (KC / 4);
+    const int step_begin = ks * p.steps_per_split;
+    const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
+    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * KC) + tid + step_begin * a_step;
+
+    f32x4 areg = {0.f, 0.f, 0.f, 0.f};
+    float breg[EPT];
+    bool bok;
+    int a0 = 0;
+    int r, s, cboff;
+    {
+        const int cb = (int)fastdiv((uint32_t)step_begin, p.div_rs);
+        const int rs = step_begin - cb * (p.R * p.S);
+        r = (int)fastdiv((uint32_t)rs, p.div_s);
+        s = rs - r * p.S;
+        cboff = cb * KC * p.plane_bytes;
+    }
+    auto slot_tap = [&]() {
+        const int dr = p.sign * r, ds = p.sign * s;
+        const int hh = hb + dr, ww = wb + ds;
+        bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+        a0 = bok ? base + cboff + 4 * (dr * p.LW + ds) : 0;
+        s += 1;
+        const bool ws = s == p.S;
+        s = ws ? 0 : s;
+        r += ws ? 1 : 0;
+        const bool wr = r == p.R;
+        r = wr ? 0 : r;
+        cboff += wr ? KC * p.plane_bytes : 0;
+    };
+    auto slot_a = [&]() {
+        if (tid < A4) areg = a_ptr[0];
+        a_ptr += a_step;
+    };
+    auto slot_b = [&](int e) {
+        breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
+    };
+    auto load_step = [&]() {
+        slot_tap();
+        slot_a();
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) slot_b(e);
+    };
+    auto store_step = [&](int buf) {
+        float *As = As0 + buf * BM * PITCH, *Bs = Bs0 + buf * BN * PITCH;
+        if (tid < A4) *reinterpret_cast<f32x4 *>(&As[(tid >> 2) * PITCH + (tid & 3) * 4]) = areg;
+        float *brow = &Bs[jc * PITCH];
+#pragma unroll
+        for (int e = 0; e < EPT; e += 4) {
+            f32x4 v = {bok ? breg[e] : 0.f, bok ? breg[e + 1] : 0.f, bok ? breg[e + 2] : 0.f,
+                       bok ? breg[e + 3] : 0.f};
+            *reinterpret_cast<f32x4 *>(brow + e) = v;
+        }
+    };
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) acc[i][jn] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int l16 = lane & 15, kq = lane >> 4;
+    const int a_frag = l16 * PITCH + kq * 4;
+    const int b_frag = (wn * TN * 16 + l16) * PITCH + kq * 4;
+    constexpr int NMMA = 4 * TM * TN;
+    constexpr int NSLOT = 2 + EPT;
+
+    load_step();
+    store_step(0);
+    __syncthreads();
+    for (int step = 0; step < nsteps; ++step) {
+        const int buf = step & 1;
+        const bool last = step == nsteps - 1;
+        const float *As = As0 + buf * BM * PITCH, *Bs = Bs0 + buf * BN * PITCH;
+        f32x4 fa[TM], fb[TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const f32x4 *>(&As[a_frag + i * 16 * PITCH]);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) fb[jn] = *reinterpret_cast<const f32x4 *>(&Bs[b_frag + jn * 16 * PITCH]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!last) {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[i][t], fb[jn][t], acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (m == 0) slot_tap();
+                else if (m == 1) slot_a();
+                else if (m < NSLOT) slot_b(m - 2);
+                if (m < NSLOT) __builtin_amdgcn_sched_barrier(0);
+            }
+            store_step(buf ^ 1);
+            __syncthreads();
+        } else {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[i][t], fb[jn][t], acc[i][jn], 0, 0, 0);
+            }
+        }
+    }
+
+    const int plane = p.OH * p.OW;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 16 + l16;
+        if (col >= p.ncols) continue;
+        const int n = (int)fastdiv((uint32_t)col, p.div_plane);
+        const int rem = col - n * plane;
+        float *out = p.ksplit > 1 ? p.part + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
+                                  : p.dst + (size_t)n * p.dst_bs + rem;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int row = m0 + i * 16 + kq * 4 + v;
+                if (row < p.M) out[(size_t)row * plane] = acc[i][jn][v];
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // bf16 inputs, fp32 accumulation: the same walk as colgemm_fast_kernel (one
 // filter tap x KC consecutive channels per step, one padding test and one base
 // address per thread and step) on v_mfma_f32_32x32x16_bf16.  A lane feeds 8
@@ -2172,7 +2343,8 @@ void launch_colgemm_fast(const TileShape &t, int kc, const ColGemmFastArgs &a, c
 {
     const int need = 2 * (t.bm() + t.bn()) * (kc + 4) * 4;
     const int lds = need + g.dyn_lds;
-    if (t.TM == 2 && t.TN == 2) launch_dyn(colgemm_fast_kernel<2, 2, 2, 2, 16>, a, g.grid, lds, st);
+    if (t.mfma == 16) launch_dyn(colgemm_rows48_kernel, a, g.grid, lds, st);
+    else if (t.TM == 2 && t.TN == 2) launch_dyn(colgemm_fast_kernel<2, 2, 2, 2, 16>, a, g.grid, lds, st);
     else if (t.TM == 3) launch_dyn(colgemm_fast_kernel<3, 1, 1, 4, 16>, a, g.grid, lds, st);
     else if (t.TM == 2) launch_dyn(colgemm_fast_kernel<2, 1, 1, 4, 16>, a, g.grid, lds, st);
     else launch_dyn(colgemm_fast_kernel<1, 2, 1, 4, 16>, a, g.grid, lds, st);

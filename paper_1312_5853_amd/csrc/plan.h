@@ -40,14 +40,16 @@ struct Problem {
 // 32 x 32; waves are laid out WM x WN.
 struct TileShape {
     int TM, TN, WM, WN;
-    int bm() const { return TM * WM * 32; }
-    int bn() const { return TN * WN * 32; }
+    int mfma;                          // edge of the square matrix-instruction block: 32, or 16 for the 48-row tile
+    int bm() const { return TM * WM * mfma; }
+    int bn() const { return TN * WN * mfma; }
 };
 
-constexpr TileShape kTile128x128 = {2, 2, 2, 2};
-constexpr TileShape kTile96x128 = {3, 1, 1, 4};
-constexpr TileShape kTile64x128 = {2, 1, 1, 4};
-constexpr TileShape kTile32x256 = {1, 2, 1, 4};
+constexpr TileShape kTile128x128 = {2, 2, 2, 2, 32};
+constexpr TileShape kTile96x128 = {3, 1, 1, 4, 32};
+constexpr TileShape kTile64x128 = {2, 1, 1, 4, 32};
+constexpr TileShape kTile32x256 = {1, 2, 1, 4, 32};
+constexpr TileShape kTile48x256 = {3, 4, 1, 4, 16};   // fp32 forward / backward-data fast path only
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -139,6 +141,13 @@ inline Plan make_plan(int op, const Problem &pb)
     else if (op == kOpBwdData) { pl.M = pb.C; pl.Kg = pb.K * RS; }
     else { pl.M = pb.K; pl.Kg = pb.C * RS; }
     pl.tile = pick_tile(pl.M);
+    {
+        // 33..48 rows on the fp32 fast path: 16 x 16 matrix blocks instead of padding to 64 rows
+        const int Cg = op == kOpFwd ? pb.C : pb.K;
+        if (pb.dtype == kDtypeF32 && pl.M > 32 && pl.M <= 48 && Cg % kChunk == 0 &&
+            (op == kOpFwd || (op == kOpBwdData && pb.stride == 1)))
+            pl.tile = kTile48x256;
+    }
     pl.Mpad = round_up(pl.M, pl.tile.bm());
     pl.Kgpad = round_up(pl.Kg, kChunk);
     pl.tab_len = round_up(pl.Kg + 2 * kChunk, kTapTablePad);   // two steps of slack for the prefetch

@@ -89,6 +89,9 @@ ODD_SHAPES = [
     (3, 4, 10, 10, 100, 2, 3, 3, 1),       # K = 100: ragged 96/128 row tile
     (5, 33, 13, 13, 65, 3, 3, 1, 1),       # columns 5*169 = 845: ragged last column tile
     (2, 2, 40, 3, 3, 4, 1, 4, 0),          # stride 4 along a thin plane
+    (3, 48, 9, 9, 40, 3, 3, 1, 1),         # forward with 40 rows: the 48-row tile of 16x16 blocks
+    (2, 40, 11, 7, 32, 3, 3, 1, 1),        # backward-data with 40 rows, ragged 256-column tile
+    (7, 48, 14, 14, 64, 5, 5, 1, 2),       # backward-data with 48 rows, several column tiles
 ]
 
 
