@@ -29,6 +29,11 @@
  *           CONV_DTYPE_BF16 = x, w, dy hold bfloat16 (2 bytes, already rounded
  *           by the caller); products accumulate in fp32; outputs (y, dx, dw)
  *           are fp32.
+ *           CONV_DTYPE_BF16_OUT_BF16 = as CONV_DTYPE_BF16, but conv_fwd writes y
+ *           and conv_bwd_data writes dx as bfloat16, each fp32 sum rounded once
+ *           to nearest even, so that activations and gradients chain from layer
+ *           to layer without a conversion call.  conv_bwd_filter treats it as
+ *           CONV_DTYPE_BF16: dw is always fp32.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Work is enqueued; returning does not imply completion.  Calls on one
  *    stream that share a workspace are ordered by the stream; calls on
@@ -62,7 +67,7 @@ typedef enum conv_status {
     CONV_ERR_HIP = -6                  /* the HIP runtime refused a launch; hipGetLastError() text via conv_last_hip_error() */
 } conv_status;
 
-enum { CONV_DTYPE_F32 = 0, CONV_DTYPE_BF16 = 1 };
+enum { CONV_DTYPE_F32 = 0, CONV_DTYPE_BF16 = 1, CONV_DTYPE_BF16_OUT_BF16 = 2 };
 enum { CONV_OP_FWD = 0, CONV_OP_BWD_DATA = 1, CONV_OP_BWD_FILTER = 2 };
 
 /*

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libconvnet_hotpath.so")
 
 OK = 0
 ERR_INVALID_ARG, ERR_TOO_LARGE, ERR_BAD_DTYPE, ERR_WORKSPACE, ERR_MISALIGNED, ERR_HIP = -1, -2, -3, -4, -5, -6
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_BF16_OUT_BF16 = 0, 1, 2
 OP_FWD, OP_BWD_DATA, OP_BWD_FILTER = 0, 1, 2
 
 EXPORTS = (
@@ -159,31 +159,43 @@ def _batch_stride(t):
     return 0 if (n == 1 or t.stride(0) == c * h * w) else t.stride(0)
 
 
-def conv_fwd(x, w, stride, pad, y=None, ws=None, stream=None):
-    """x [N,C,H,W], w [K,C,R,S] -> y [N,K,P,Q] fp32.  x and y may be channel
-    slices of wider NCHW tensors (their batch strides are passed on)."""
+def _io_dtype(src, out):
+    """dtype code of a forward / backward-data call from its input and output tensors."""
+    d = _dtype_of(src)
+    if out.dtype == torch.bfloat16:
+        if d != DTYPE_BF16:
+            raise TypeError("a bfloat16 output needs bfloat16 inputs")
+        return DTYPE_BF16_OUT_BF16
+    if out.dtype != torch.float32:
+        raise TypeError("unsupported output dtype %s" % out.dtype)
+    return d
+
+
+def conv_fwd(x, w, stride, pad, y=None, ws=None, stream=None, out_bf16=False):
+    """x [N,C,H,W], w [K,C,R,S] -> y [N,K,P,Q], fp32 (or bfloat16: pass a bfloat16 y, or out_bf16=True, with
+    bfloat16 inputs).  x and y may be channel slices of wider NCHW tensors (their batch strides are passed on)."""
     N, C, H, W = x.shape
     K, Cw, R, S = w.shape
     if C != Cw or not w.is_contiguous():
         raise ValueError("filter tensor does not match the input")
     P, Q = out_extent(H, R, stride, pad), out_extent(W, S, stride, pad)
     if y is None:
-        y = torch.empty((N, K, P, Q), dtype=torch.float32, device=x.device)
+        y = torch.empty((N, K, P, Q), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=x.device)
     dims = (N, C, H, W, K, R, S, stride, pad)
-    return _run("conv_fwd", OP_FWD, x, w, y, dims, _batch_stride(x), _batch_stride(y), _dtype_of(x), ws, stream)
+    return _run("conv_fwd", OP_FWD, x, w, y, dims, _batch_stride(x), _batch_stride(y), _io_dtype(x, y), ws, stream)
 
 
-def conv_bwd_data(dy, w, H, W, stride, pad, dx=None, ws=None, stream=None):
-    """dy [N,K,P,Q], w [K,C,R,S] -> dx [N,C,H,W] fp32 (H, W: the layer's input extent)."""
+def conv_bwd_data(dy, w, H, W, stride, pad, dx=None, ws=None, stream=None, out_bf16=False):
+    """dy [N,K,P,Q], w [K,C,R,S] -> dx [N,C,H,W] fp32 or bfloat16 (H, W: the layer's input extent)."""
     N = dy.shape[0]
     K, C, R, S = w.shape
     if dy.shape[1] != K or not w.is_contiguous():
         raise ValueError("filter tensor does not match the output gradient")
     if dx is None:
-        dx = torch.empty((N, C, H, W), dtype=torch.float32, device=dy.device)
+        dx = torch.empty((N, C, H, W), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=dy.device)
     dims = (N, C, H, W, K, R, S, stride, pad)
-    return _run("conv_bwd_data", OP_BWD_DATA, dy, w, dx, dims, _batch_stride(dx), _batch_stride(dy), _dtype_of(dy),
-                ws, stream)
+    return _run("conv_bwd_data", OP_BWD_DATA, dy, w, dx, dims, _batch_stride(dx), _batch_stride(dy),
+                _io_dtype(dy, dx), ws, stream)
 
 
 def conv_bwd_filter(x, dy, R, S, stride, pad, dw=None, ws=None, stream=None):

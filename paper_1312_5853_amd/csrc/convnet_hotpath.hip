@@ -104,6 +104,19 @@ __global__ void narrow_to_bf16(const float *__restrict__ src, unsigned short *__
     dst[i] = (unsigned short)r;
 }
 
+// src: dense [batch][sample] fp32; dst: bf16 samples `dst_bs` elements apart (round to nearest even)
+__global__ void narrow_to_bf16_strided(const float *__restrict__ src, unsigned short *__restrict__ dst, int64_t n,
+                                       int64_t sample, int64_t dst_bs)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int64_t b = i / sample;
+    const unsigned u = __float_as_uint(src[i]);
+    unsigned r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) r = (u >> 16) | 0x40u;      // NaN stays NaN (quiet)
+    dst[b * dst_bs + (i - b * sample)] = (unsigned short)r;
+}
+
 // dst: dense [batch][sample]; src: samples `src_bs` elements apart
 __global__ void widen_bf16(const unsigned short *__restrict__ src, float *__restrict__ dst, int64_t n,
                            int64_t sample, int64_t src_bs)
@@ -2462,8 +2475,30 @@ const float *as_f32(const void *src, int batch, int64_t sample, int64_t *bs, cha
     return dst;
 }
 
-int run_colgemm(int op, const void *act, const void *w, void *out, const Problem &caller_pb, const Plan &pl,
-                void *ws, hipStream_t st)
+int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const Problem &caller_pb, const Plan &pl,
+                       void *ws, hipStream_t st);
+
+// Forward / backward-data.  A bf16 destination is produced from a dense fp32 result in the workspace.
+int run_colgemm(int op, const void *act, const void *w, void *out, const Problem &pb, const Plan &pl, void *ws,
+                hipStream_t st)
+{
+    if (!pb.out_bf16) return run_colgemm_f32out(op, act, w, out, pb, pl, ws, st);
+    Problem q = pb;
+    const int64_t sample = op == kOpFwd ? (int64_t)pb.K * pb.P * pb.Q : (int64_t)pb.C * pb.H * pb.W;
+    int64_t &out_bs = op == kOpFwd ? q.y_bs : q.x_bs;
+    const int64_t caller_bs = out_bs;
+    out_bs = sample;
+    float *stage = reinterpret_cast<float *>(static_cast<char *>(ws) + pl.stage_off);
+    int rc = run_colgemm_f32out(op, act, w, stage, q, pl, ws, st);
+    if (rc != kStatusOk) return rc;
+    const int64_t count = pb.N * sample;
+    hipLaunchKernelGGL(narrow_to_bf16_strided, dim3(grid1d(count, 256)), dim3(256), 0, st, stage,
+                       static_cast<unsigned short *>(out), count, sample, caller_bs);
+    return check_launch();
+}
+
+int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const Problem &caller_pb, const Plan &pl,
+                       void *ws, hipStream_t st)
 {
     Problem pb = caller_pb;                     // batch stride of a widened input changes below
     char *wsb = static_cast<char *>(ws);

@@ -22,7 +22,7 @@ constexpr int kErrMisaligned = -5;
 constexpr int kErrHip = -6;
 
 constexpr int kOpFwd = 0, kOpBwdData = 1, kOpBwdFilter = 2;
-constexpr int kDtypeF32 = 0, kDtypeBf16 = 1;
+constexpr int kDtypeF32 = 0, kDtypeBf16 = 1, kDtypeBf16OutBf16 = 2;
 
 constexpr int kChunk = 16;            // reduction elements staged in LDS per step
 constexpr int kTapTablePad = 256;     // tap table length is rounded up to this
@@ -33,7 +33,8 @@ struct Problem {
     int N, C, H, W, K, R, S, stride, pad;
     int P, Q;
     int64_t x_bs, y_bs;               // batch strides in elements
-    int dtype;
+    int dtype;                        // of the inputs: kDtypeF32 or kDtypeBf16
+    bool out_bf16;                    // forward / backward-data write bf16 (caller passed kDtypeBf16OutBf16)
 };
 
 // Tile shape of one work-group (4 waves): each wave owns TM x TN MFMA tiles of
@@ -81,7 +82,9 @@ inline int make_problem(Problem &pb, int N, int C, int H, int W, int K, int R, i
 {
     if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || K <= 0 || R <= 0 || S <= 0) return kErrInvalidArg;
     if (stride <= 0 || pad < 0) return kErrInvalidArg;
-    if (dtype != kDtypeF32 && dtype != kDtypeBf16) return kErrBadDtype;
+    if (dtype != kDtypeF32 && dtype != kDtypeBf16 && dtype != kDtypeBf16OutBf16) return kErrBadDtype;
+    pb.out_bf16 = dtype == kDtypeBf16OutBf16;
+    if (pb.out_bf16) dtype = kDtypeBf16;
     // keep every intermediate below 2^31 before multiplying extents together
     if (pad > (1 << 20) || stride > (1 << 20)) return kErrTooLarge;
     if ((int64_t)H + 2 * (int64_t)pad < R || (int64_t)W + 2 * (int64_t)pad < S) return kErrInvalidArg;
@@ -124,6 +127,7 @@ struct Plan {
     bool widen;                       // bf16 inputs are widened to dense fp32 copies first (no bf16 kernel for the shape)
     size_t cvt_off[2], cvt_bytes[2];  // bf16 -> fp32 staging of the two inputs
     size_t blk_off, blk_bytes;        // channel-blocked copy of the gathered bf16 tensor (forward, backward-data)
+    size_t stage_off, stage_bytes;    // dense fp32 result of forward / backward-data before it is rounded to bf16
     // bf16 backward-filter of a stride-1 layer whose output has the input's extent: packed copies in which a
     // filter tap is a linear shift (row pitch lin_wq, lin_jy / lin_jx elements per image), 64 positions per step
     bool lin;
@@ -242,6 +246,11 @@ inline Plan make_plan(int op, const Problem &pb)
         pl.blk_off = off;
         pl.blk_bytes = (size_t)pb.N * Cr * (op == kOpFwd ? pb.H * pb.W : pb.P * pb.Q) * 2;
         off += round_up64(pl.blk_bytes, 256);
+    }
+    if (pb.out_bf16 && op != kOpBwdFilter) {
+        pl.stage_off = off;
+        pl.stage_bytes = (size_t)pb.N * (op == kOpFwd ? (size_t)pb.K * pb.P * pb.Q : (size_t)pb.C * pb.H * pb.W) * 4;
+        off += round_up64(pl.stage_bytes, 256);
     }
     if (pl.widen) {
         const int64_t x_e = (int64_t)pb.N * pb.C * pb.H * pb.W, y_e = (int64_t)pb.N * pb.K * pb.P * pb.Q;

@@ -146,6 +146,35 @@ def test_bf16_small_integers_are_exact():
     np.testing.assert_array_equal(dw, oracle.conv_bwd_filter(x, dy, R, S, st, pad))
 
 
+@pytest.mark.parametrize("shape", [(5, 64, 13, 13, 96, 3, 3, 1, 1),      # bf16 kernels
+                                   (3, 3, 20, 21, 24, 5, 5, 2, 2),       # widened inputs, fp32 kernels
+                                   (4, 48, 9, 9, 40, 3, 3, 1, 1)])
+def test_bf16_outputs_are_the_rounded_fp32_results(shape):
+    """dtype 2: y and dx come back as bfloat16 = the fp32 results of dtype 1 rounded to nearest even, written
+    through batch strides; within the bf16 tolerance of the oracle."""
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+    x, w, dy = prepared(synth.gaussian((N, C, H, W), 107), synth.gaussian((K, C, R, S), 108, 0.1),
+                        synth.gaussian((N, K, P, Q), 109), "bf16")
+    xd, wd, dyd = dev(x, "bf16"), dev(w, "bf16"), dev(dy, "bf16")
+    y32 = hp.conv_fwd(xd, wd, st, pad)
+    dx32 = hp.conv_bwd_data(dyd, wd, H, W, st, pad)
+    # outputs land in channel slices of wider bf16 tensors pre-filled with a marker
+    ywide = torch.full((N, K + 8, P, Q), 7.0, dtype=torch.bfloat16, device="cuda")
+    dxwide = torch.full((N, C + 8, H, W), 7.0, dtype=torch.bfloat16, device="cuda")
+    hp.conv_fwd(xd, wd, st, pad, y=ywide[:, 8:])
+    hp.conv_bwd_data(dyd, wd, H, W, st, pad, dx=dxwide[:, 8:])
+    y16 = hp.conv_fwd(xd, wd, st, pad, out_bf16=True)
+    torch.cuda.synchronize()
+    assert y16.dtype == torch.bfloat16 and torch.equal(y16, ywide[:, 8:])
+    assert (ywide[:, :8] == 7.0).all() and (dxwide[:, :8] == 7.0).all()
+    bits = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(bits(ywide[:, 8:]), synth.bf16_bits(synth.to_bf16_grid(y32.cpu().numpy())))
+    assert np.array_equal(bits(dxwide[:, 8:]), synth.bf16_bits(synth.to_bf16_grid(dx32.cpu().numpy())))
+    assert norm_err(ywide[:, 8:].float().cpu().numpy(), oracle.conv_fwd(x, w, st, pad)) <= TOL["bf16"]
+    assert norm_err(dxwide[:, 8:].float().cpu().numpy(), oracle.conv_bwd_data(dy, w, H, W, st, pad)) <= TOL["bf16"]
+
+
 def test_small_integers_are_exact():
     """Integer-valued inputs with small sums are exact in fp32: bit-for-bit equality."""
     N, C, H, W, K, R, S, st, pad = 2, 6, 11, 12, 40, 3, 3, 2, 1

@@ -67,7 +67,7 @@ def test_argument_checks_run_before_any_gpu_call(lib, fn):
         assert call(lib, fn, **{key: -3}) == b.ERR_INVALID_ARG, key
     assert call(lib, fn, pad=-1) == b.ERR_INVALID_ARG
     assert call(lib, fn, R=16, pad=1) == b.ERR_INVALID_ARG          # empty output (P <= 0)
-    assert call(lib, fn, dtype=2) == b.ERR_BAD_DTYPE
+    assert call(lib, fn, dtype=3) == b.ERR_BAD_DTYPE and call(lib, fn, dtype=-1) == b.ERR_BAD_DTYPE
     assert call(lib, fn, N=2048, C=64, H=64, W=64) == b.ERR_TOO_LARGE
     assert call(lib, fn, a=PTR + 4) == b.ERR_MISALIGNED
     assert call(lib, fn, out=PTR + 8) == b.ERR_MISALIGNED
@@ -97,6 +97,10 @@ def test_workspace_bytes(lib):
     # bf16 kernel: the only addition is the channel-blocked bf16 copy of the output gradient
     extra = lib.conv_workspace_bytes(1, *dims, 1) - lib.conv_workspace_bytes(1, *dims, 0)
     assert 0 < extra <= 128 * 384 * 169 * 2 + 256
+    # bf16 outputs add a dense fp32 staging copy of the result (forward, backward-data), nothing for backward-filter
+    assert lib.conv_workspace_bytes(0, *dims, 2) - lib.conv_workspace_bytes(0, *dims, 1) == 128 * 384 * 169 * 4
+    assert lib.conv_workspace_bytes(1, *dims, 2) - lib.conv_workspace_bytes(1, *dims, 1) == 128 * 256 * 169 * 4
+    assert lib.conv_workspace_bytes(2, *dims, 2) == lib.conv_workspace_bytes(2, *dims, 1)
     odd = [4, 3, 32, 32, 20, 5, 5, 2, 1]                                                     # widened to fp32 copies
     for op in (0, 1, 2):
         assert lib.conv_workspace_bytes(op, *odd, 1) > lib.conv_workspace_bytes(op, *odd, 0)
