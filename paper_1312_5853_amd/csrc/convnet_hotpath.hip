@@ -2083,14 +2083,20 @@ __global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__
     dw[((size_t)k * C + c) * RS + rs] = s;
 }
 
-// Fixed-order sum of the split partials: dw[i] = part[0][i] + part[1][i] + ...
-__global__ void reduce_partials(const float *__restrict__ part, float *__restrict__ dw, int count, int nsplit)
+// Sum of the split partials in a fixed order: 64 outputs per work-group; lane group g of four adds the
+// splits g, g + 4, g + 8, ... in ascending order, then the four sums are added in group order.
+__global__ __launch_bounds__(256) void reduce_partials(const float *__restrict__ part, float *__restrict__ dw,
+                                                        int count, int nsplit)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= count) return;
-    float s = part[i];
-    for (int k = 1; k < nsplit; ++k) s += part[(size_t)k * count + i];
-    dw[i] = s;
+    __shared__ float sums[4][64];
+    const int o = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + o;
+    float s = 0.f;
+    if (i < count)
+        for (int k = g; k < nsplit; k += 4) s += part[(size_t)k * count + i];
+    sums[g][o] = s;
+    __syncthreads();
+    if (g == 0 && i < count) dw[i] = ((sums[0][o] + sums[1][o]) + sums[2][o]) + sums[3][o];
 }
 
 // ---------------------------------------------------------------------------
@@ -2730,7 +2736,7 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
     if (rc != kStatusOk) return rc;
     if (pl.nsplit > 1) {
         const int count = pb.K * pl.Kg;
-        hipLaunchKernelGGL(reduce_partials, dim3(grid1d(count, 256)), dim3(256), 0, st, a.out,
+        hipLaunchKernelGGL(reduce_partials, dim3(grid1d(count, 64)), dim3(256), 0, st, a.out,
                            static_cast<float *>(dw), count, pl.nsplit);
         rc = check_launch();
     }
