@@ -148,8 +148,12 @@ const char *conv_last_hip_error(void);
 /*
  * Glue layers between the convolutions of the five-layer stack (they belong to
  * the Krizhevsky architecture the paper trains; the paper's text does not
- * spell them out).  fp32 tensors, device pointers, 4-byte aligned, fully
- * overwritten outputs, same stream and error conventions as above.
+ * spell them out).  Device pointers, fully overwritten outputs, same stream and
+ * error conventions as above.  `dtype` names the element type of ALL tensors of
+ * the call: CONV_DTYPE_F32 = fp32 (4-byte aligned); CONV_DTYPE_BF16 or
+ * CONV_DTYPE_BF16_OUT_BF16 = bfloat16 (2-byte aligned): values are read exactly,
+ * arithmetic is fp32, and a result that is not itself an input value (the sum of
+ * up to four gradients in the pooling backward) is rounded once to nearest even.
  *
  *   relu_fwd:  y[i]  = x[i] > 0 ? x[i] : 0                     (y may alias x)
  *   relu_bwd:  dx[i] = x[i] > 0 ? dy[i] : 0   (x = forward input or output; dx may alias dy)
@@ -159,10 +163,10 @@ const char *conv_last_hip_error(void);
  *                     forward pass selected (first maximum in row-major window order);
  *                     overlapping windows accumulate in a fixed order.
  */
-int relu_fwd(const void *x, void *y, int64_t count, void *stream);
-int relu_bwd(const void *x, const void *dy, void *dx, int64_t count, void *stream);
-int maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream);
-int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream);
+int relu_fwd(const void *x, void *y, int64_t count, int dtype, void *stream);
+int relu_bwd(const void *x, const void *dy, void *dx, int64_t count, int dtype, void *stream);
+int maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, int dtype, void *stream);
+int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, int dtype, void *stream);
 
 /*
  * ReLU followed by the pooling above, fused (the conv1/conv2/conv5 tail of the
@@ -173,13 +177,14 @@ int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, in
  *       gradient with respect to the convolution output x, from x itself.
  * Both give exactly what the separate calls give.
  */
-int relu_maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream);
-int relu_maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream);
+int relu_maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, int dtype, void *stream);
+int relu_maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, int dtype,
+                          void *stream);
 
 /*
- * fp32 -> bfloat16 with round-to-nearest-even, for callers that chain
- * CONV_DTYPE_BF16 layers (the passes produce fp32; the next layer's bf16 input
- * is this rounding of it).  dst holds `count` 2-byte values; device pointers.
+ * fp32 -> bfloat16 with round-to-nearest-even, for callers that hold fp32 data
+ * (network input, filters after an fp32 update, fp32 results of CONV_DTYPE_BF16
+ * passes) and feed bf16 layers.  dst holds `count` 2-byte values; device pointers.
  */
 int convert_f32_to_bf16(const void *src, void *dst, int64_t count, void *stream);
 

@@ -64,14 +64,14 @@ def lib():
     L.conv_status_string.restype = ctypes.c_char_p
     L.conv_last_hip_error.argtypes = []
     L.conv_last_hip_error.restype = ctypes.c_char_p
-    L.relu_fwd.argtypes = [vp, vp, i64, vp]
-    L.relu_bwd.argtypes = [vp, vp, vp, i64, vp]
-    L.maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, vp]
-    L.maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, vp]
+    L.relu_fwd.argtypes = [vp, vp, i64, i, vp]
+    L.relu_bwd.argtypes = [vp, vp, vp, i64, i, vp]
+    L.maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, i, vp]
+    L.maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, i, vp]
     L.convert_f32_to_bf16.argtypes = [vp, vp, i64, vp]
     L.convert_f32_to_bf16.restype = i
-    L.relu_maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, vp]
-    L.relu_maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, vp]
+    L.relu_maxpool3x3s2_fwd.argtypes = [vp, vp, i64, i, i, i, vp]
+    L.relu_maxpool3x3s2_bwd.argtypes = [vp, vp, vp, i64, i, i, i, vp]
     for name in ("relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd", "relu_maxpool3x3s2_fwd",
                  "relu_maxpool3x3s2_bwd"):
         getattr(L, name).restype = i
@@ -214,53 +214,61 @@ def _check(rc, where):
         raise ConvError(rc, where)
 
 
+def _glue_dtype(*tensors):
+    """All tensors of a glue call share one element type (fp32 or bfloat16)."""
+    d = _dtype_of(tensors[0])
+    for t in tensors[1:]:
+        if t.dtype != tensors[0].dtype:
+            raise TypeError("the tensors of a glue call must have one dtype")
+    return d
+
+
 def relu_fwd(x, y=None, stream=None):
     if y is None:
         y = torch.empty_like(x)
-    _check(lib().relu_fwd(_ptr(x), _ptr(y), x.numel(), _stream_handle(stream)), "relu_fwd")
+    _check(lib().relu_fwd(_ptr(x), _ptr(y), x.numel(), _glue_dtype(x, y), _stream_handle(stream)), "relu_fwd")
     return y
 
 
 def relu_bwd(x, dy, dx=None, stream=None):
     if dx is None:
         dx = torch.empty_like(dy)
-    _check(lib().relu_bwd(_ptr(x), _ptr(dy), _ptr(dx), x.numel(), _stream_handle(stream)), "relu_bwd")
+    _check(lib().relu_bwd(_ptr(x), _ptr(dy), _ptr(dx), x.numel(), _glue_dtype(x, dy, dx), _stream_handle(stream)),
+           "relu_bwd")
+    return dx
+
+
+def _pool_fwd(name, x, y, stream):
+    N, C, H, W = x.shape
+    if y is None:
+        y = torch.empty((N, C, (H - 3) // 2 + 1, (W - 3) // 2 + 1), dtype=x.dtype, device=x.device)
+    _check(getattr(lib(), name)(_ptr(x), _ptr(y), N * C, H, W, _glue_dtype(x, y), _stream_handle(stream)), name)
+    return y
+
+
+def _pool_bwd(name, x, dy, dx, stream):
+    N, C, H, W = x.shape
+    if dx is None:
+        dx = torch.empty_like(x)
+    _check(getattr(lib(), name)(_ptr(x), _ptr(dy), _ptr(dx), N * C, H, W, _glue_dtype(x, dy, dx),
+                                _stream_handle(stream)), name)
     return dx
 
 
 def maxpool3x3s2_fwd(x, y=None, stream=None):
-    N, C, H, W = x.shape
-    if y is None:
-        y = torch.empty((N, C, (H - 3) // 2 + 1, (W - 3) // 2 + 1), dtype=x.dtype, device=x.device)
-    _check(lib().maxpool3x3s2_fwd(_ptr(x), _ptr(y), N * C, H, W, _stream_handle(stream)), "maxpool3x3s2_fwd")
-    return y
+    return _pool_fwd("maxpool3x3s2_fwd", x, y, stream)
 
 
 def maxpool3x3s2_bwd(x, dy, dx=None, stream=None):
-    N, C, H, W = x.shape
-    if dx is None:
-        dx = torch.empty_like(x)
-    _check(lib().maxpool3x3s2_bwd(_ptr(x), _ptr(dy), _ptr(dx), N * C, H, W, _stream_handle(stream)),
-           "maxpool3x3s2_bwd")
-    return dx
+    return _pool_bwd("maxpool3x3s2_bwd", x, dy, dx, stream)
 
 
 def relu_maxpool3x3s2_fwd(x, y=None, stream=None):
-    N, C, H, W = x.shape
-    if y is None:
-        y = torch.empty((N, C, (H - 3) // 2 + 1, (W - 3) // 2 + 1), dtype=x.dtype, device=x.device)
-    _check(lib().relu_maxpool3x3s2_fwd(_ptr(x), _ptr(y), N * C, H, W, _stream_handle(stream)),
-           "relu_maxpool3x3s2_fwd")
-    return y
+    return _pool_fwd("relu_maxpool3x3s2_fwd", x, y, stream)
 
 
 def relu_maxpool3x3s2_bwd(x, dy, dx=None, stream=None):
-    N, C, H, W = x.shape
-    if dx is None:
-        dx = torch.empty_like(x)
-    _check(lib().relu_maxpool3x3s2_bwd(_ptr(x), _ptr(dy), _ptr(dx), N * C, H, W, _stream_handle(stream)),
-           "relu_maxpool3x3s2_bwd")
-    return dx
+    return _pool_bwd("relu_maxpool3x3s2_bwd", x, dy, dx, stream)
 
 
 def convert_f32_to_bf16(src, dst=None, stream=None):

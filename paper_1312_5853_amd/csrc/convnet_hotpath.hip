@@ -94,14 +94,29 @@ __global__ void relayout_filters(const float *__restrict__ w, float *__restrict_
 }
 
 // fp32 -> bf16, round to nearest even (NaN stays NaN)
+// fp32 -> bfloat16 bits, round to nearest even; NaN stays a (quiet) NaN
+__device__ __forceinline__ unsigned short bf16_round(float f)
+{
+    const unsigned u = __float_as_uint(f);
+    unsigned r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) r = (u >> 16) | 0x40u;
+    return (unsigned short)r;
+}
+
+// element access of the glue kernels: fp32 tensors, or bfloat16 tensors read exactly and written rounded
+__device__ __forceinline__ float ld_elem(const float *p, int64_t i) { return p[i]; }
+__device__ __forceinline__ float ld_elem(const unsigned short *p, int64_t i)
+{
+    return __uint_as_float((unsigned)p[i] << 16);
+}
+__device__ __forceinline__ void st_elem(float *p, int64_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void st_elem(unsigned short *p, int64_t i, float v) { p[i] = bf16_round(v); }
+
 __global__ void narrow_to_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, int64_t n)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const unsigned u = __float_as_uint(src[i]);
-    unsigned r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) r = (u >> 16) | 0x40u;
-    dst[i] = (unsigned short)r;
+    dst[i] = bf16_round(src[i]);
 }
 
 // src: dense [batch][sample] fp32; dst: bf16 samples `dst_bs` elements apart (round to nearest even)
@@ -111,10 +126,7 @@ __global__ void narrow_to_bf16_strided(const float *__restrict__ src, unsigned s
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int64_t b = i / sample;
-    const unsigned u = __float_as_uint(src[i]);
-    unsigned r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) r = (u >> 16) | 0x40u;      // NaN stays NaN (quiet)
-    dst[b * dst_bs + (i - b * sample)] = (unsigned short)r;
+    dst[b * dst_bs + (i - b * sample)] = bf16_round(src[i]);
 }
 
 // dst: dense [batch][sample]; src: samples `src_bs` elements apart
@@ -395,6 +407,7 @@ struct ColGemmFastArgs {
     int mtiles, ntiles, tiles_per_xcd;
     int ksplit, steps_per_split;   // the reduction steps are cut into ksplit ranges (1 = whole)
     float *part;                   // ksplit > 1: partial outputs [ksplit][N][M][OH*OW], summed by reduce_split_outputs
+    int out_bf16;                  // bf16 kernel only: dst holds bfloat16 (each sum rounded to nearest even)
     FastDiv div_plane, div_ow, div_rs, div_s;
 };
 
@@ -1008,6 +1021,19 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
         if (col >= p.ncols) continue;
         const int n = (int)fastdiv((uint32_t)col, p.div_plane);
         const int rem = col - n * plane;
+        if (p.ksplit == 1 && p.out_bf16) {
+            unsigned short *out = reinterpret_cast<unsigned short *>(p.dst) + (size_t)n * p.dst_bs + rem;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + (v >> 2) * 8 + (v & 3);
+                    if (row < p.M) out[(size_t)row * plane] = bf16_round(acc[i][jn][v]);
+                }
+            }
+            continue;
+        }
         float *out = p.ksplit > 1 ? p.part + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
                                   : p.dst + (size_t)n * p.dst_bs + rem;
 #pragma unroll
@@ -1067,7 +1093,8 @@ __global__ void relayout_filters_cblk_bf16(const unsigned short *__restrict__ w,
 }
 
 // out[n][i] = part[0][n][i] + part[1][n][i] + ...  (fixed order), i over one sample's M*OH*OW outputs
-__global__ void reduce_split_outputs(const float *__restrict__ part, float *__restrict__ dst, int nsplit,
+template <typename T>
+__global__ void reduce_split_outputs(const float *__restrict__ part, T *__restrict__ dst, int nsplit,
                                      int per_sample, int N, int dst_bs, FastDiv div_sample)
 {
     const int total = N * per_sample;
@@ -1075,7 +1102,7 @@ __global__ void reduce_split_outputs(const float *__restrict__ part, float *__re
         float v = part[i];
         for (int k = 1; k < nsplit; ++k) v += part[(size_t)k * total + i];
         const int n = (int)fastdiv((uint32_t)i, div_sample);
-        dst[(size_t)n * dst_bs + (i - n * per_sample)] = v;
+        st_elem(dst, (int64_t)n * dst_bs + (i - n * per_sample), v);
     }
 }
 
@@ -2103,63 +2130,100 @@ __global__ __launch_bounds__(256) void reduce_partials(const float *__restrict__
 // Glue layers
 // ---------------------------------------------------------------------------
 // four elements per thread where the pointers allow it, scalar tail otherwise
-__global__ void relu_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int64_t n, int vec)
+// 16-byte groups of the element-wise kernels: 4 floats, or 8 bfloat16 widened to float
+__device__ __forceinline__ void ld_vec16(const float *p, int64_t g, float (&v)[4])
 {
+    const f32x4 q = reinterpret_cast<const f32x4 *>(p)[g];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = q[k];
+}
+__device__ __forceinline__ void ld_vec16(const unsigned short *p, int64_t g, float (&v)[8])
+{
+    const u32x4 q = reinterpret_cast<const u32x4 *>(p)[g];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        v[2 * k] = __uint_as_float(q[k] << 16);
+        v[2 * k + 1] = __uint_as_float(q[k] & 0xFFFF0000u);
+    }
+}
+__device__ __forceinline__ void st_vec16(float *p, int64_t g, const float (&v)[4])
+{
+    reinterpret_cast<f32x4 *>(p)[g] = f32x4{v[0], v[1], v[2], v[3]};
+}
+__device__ __forceinline__ void st_vec16(unsigned short *p, int64_t g, const float (&v)[8])
+{
+    u32x4 q;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) q[k] = (unsigned)bf16_round(v[2 * k]) | ((unsigned)bf16_round(v[2 * k + 1]) << 16);
+    reinterpret_cast<u32x4 *>(p)[g] = q;
+}
+
+// One thread handles a 16-byte group (4 floats or 8 bfloat16) when `vec` (pointers 16-byte aligned), else one
+// element; the last few threads of the vector form take the tail elements one each.
+template <typename T>
+__global__ void relu_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int64_t n, int vec)
+{
+    constexpr int V = 16 / (int)sizeof(T);
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (vec) {
-        const int64_t n4 = n >> 2;
-        if (i < n4) {
-            f32x4 v = reinterpret_cast<const f32x4 *>(x)[i];
+        const int64_t nv = n / V;
+        if (i < nv) {
+            float v[V];
+            ld_vec16(x, i, v);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) v[k] = v[k] > 0.f ? v[k] : 0.f;
-            reinterpret_cast<f32x4 *>(y)[i] = v;
+            for (int k = 0; k < V; ++k) v[k] = v[k] > 0.f ? v[k] : 0.f;
+            st_vec16(y, i, v);
         }
-        const int64_t t = n4 * 4 + i;
-        if (i < (n & 3)) { float v = x[t]; y[t] = v > 0.f ? v : 0.f; }
+        const int64_t t = nv * V + i;
+        if (i < n - nv * V) { const float v = ld_elem(x, t); st_elem(y, t, v > 0.f ? v : 0.f); }
     } else if (i < n) {
-        float v = x[i];
-        y[i] = v > 0.f ? v : 0.f;
+        const float v = ld_elem(x, i);
+        st_elem(y, i, v > 0.f ? v : 0.f);
     }
 }
 
-__global__ void relu_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
-                                float *__restrict__ dx, int64_t n, int vec)
+template <typename T>
+__global__ void relu_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy, T *__restrict__ dx, int64_t n,
+                                int vec)
 {
+    constexpr int V = 16 / (int)sizeof(T);
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (vec) {
-        const int64_t n4 = n >> 2;
-        if (i < n4) {
-            const f32x4 a = reinterpret_cast<const f32x4 *>(x)[i];
-            f32x4 g = reinterpret_cast<const f32x4 *>(dy)[i];
+        const int64_t nv = n / V;
+        if (i < nv) {
+            float a[V], g[V];
+            ld_vec16(x, i, a);
+            ld_vec16(dy, i, g);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) g[k] = a[k] > 0.f ? g[k] : 0.f;
-            reinterpret_cast<f32x4 *>(dx)[i] = g;
+            for (int k = 0; k < V; ++k) g[k] = a[k] > 0.f ? g[k] : 0.f;
+            st_vec16(dx, i, g);
         }
-        const int64_t t = n4 * 4 + i;
-        if (i < (n & 3)) dx[t] = x[t] > 0.f ? dy[t] : 0.f;
+        const int64_t t = nv * V + i;
+        if (i < n - nv * V) st_elem(dx, t, ld_elem(x, t) > 0.f ? ld_elem(dy, t) : 0.f);
     } else if (i < n) {
-        dx[i] = x[i] > 0.f ? dy[i] : 0.f;
+        st_elem(dx, i, ld_elem(x, i) > 0.f ? ld_elem(dy, i) : 0.f);
     }
 }
 
 // index (within the plane) of the first maximum of the 3x3 window at (2i, 2j)
-__device__ __forceinline__ int pool_argmax(const float *__restrict__ xp, int W, int i, int j, float &m)
+template <typename T>
+__device__ __forceinline__ int pool_argmax(const T *__restrict__ xp, int W, int i, int j, float &m)
 {
     int best = (2 * i) * W + 2 * j;
-    m = xp[best];
+    m = ld_elem(xp, best);
 #pragma unroll
     for (int r = 0; r < 3; ++r)
 #pragma unroll
         for (int s = 0; s < 3; ++s) {
             int at = (2 * i + r) * W + (2 * j + s);
-            float v = xp[at];
+            float v = ld_elem(xp, at);
             if (v > m) { m = v; best = at; }
         }
     return best;
 }
 
-template <bool RELU>
-__global__ void maxpool_fwd_kernel(const float *__restrict__ x, float *__restrict__ y, int64_t total,
+template <bool RELU, typename T>
+__global__ void maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int64_t total,
                                    int H, int W, int PH, int PW)
 {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -2170,7 +2234,7 @@ __global__ void maxpool_fwd_kernel(const float *__restrict__ x, float *__restric
     int64_t pl = u / PH;
     float m;
     pool_argmax(x + pl * H * W, W, i, j, m);
-    y[t] = RELU ? (m > 0.f ? m : 0.f) : m;
+    st_elem(y, t, RELU ? (m > 0.f ? m : 0.f) : m);
 }
 
 // Backward of the pooling (optionally of ReLU followed by pooling).  A
@@ -2186,84 +2250,119 @@ __global__ void maxpool_fwd_kernel(const float *__restrict__ x, float *__restric
 // of planes (and its NR/4 gradients) in registers, fetched while the current
 // group is being worked on in LDS; index arithmetic uses multiply-shift division.
 // group * H*W <= 256 * NR; windows are fewer than a quarter of the elements.
-template <bool RELU, int NR>
-__global__ __launch_bounds__(256) void maxpool_bwd_tiled(const float *__restrict__ x, const float *__restrict__ dy,
-                                                          float *__restrict__ dx, int64_t planes, int H, int W,
+// A thread's unit of global access in the tiled pooling backward: one float, or two adjacent bfloat16 as
+// one 32-bit access (2-byte aligned: planes of odd size start anywhere).  e < limit selects what exists.
+typedef unsigned int u32_align2 __attribute__((aligned(2)));
+__device__ __forceinline__ void ld_group(const float *p, int e, int limit, float (&v)[1])
+{
+    v[0] = e < limit ? p[e] : 0.f;
+}
+__device__ __forceinline__ void ld_group(const unsigned short *p, int e, int limit, float (&v)[2])
+{
+    if (e + 1 < limit) {
+        const unsigned u = *reinterpret_cast<const u32_align2 *>(p + e);
+        v[0] = __uint_as_float(u << 16);
+        v[1] = __uint_as_float(u & 0xFFFF0000u);
+    } else {
+        v[0] = e < limit ? ld_elem(p, e) : 0.f;
+        v[1] = 0.f;
+    }
+}
+__device__ __forceinline__ void st_group(float *p, int e, int limit, const float (&v)[1])
+{
+    if (e < limit) p[e] = v[0];
+}
+__device__ __forceinline__ void st_group(unsigned short *p, int e, int limit, const float (&v)[2])
+{
+    if (e + 1 < limit)
+        *reinterpret_cast<u32_align2 *>(p + e) = (unsigned)bf16_round(v[0]) | ((unsigned)bf16_round(v[1]) << 16);
+    else if (e < limit)
+        p[e] = bf16_round(v[0]);
+}
+
+template <bool RELU, int NR, typename T>
+__global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x, const T *__restrict__ dy,
+                                                          T *__restrict__ dx, int64_t planes, int H, int W,
                                                           int PH, int PW, int group, FastDiv dHW, FastDiv dW,
                                                           FastDiv dPP, FastDiv dPW)
 {
     constexpr int NG = NR / 4;
+    constexpr int EV = 4 / (int)sizeof(T);          // adjacent elements per access: 1 float or 2 bfloat16
+    static_assert(NR % EV == 0 && NG % EV == 0, "whole access groups per thread");
     extern __shared__ float pool_lds[];
     const int HW = H * W, PP = PH * PW;
     float *sx = pool_lds;                                                      // group * HW values
     float2 *swin = reinterpret_cast<float2 *>(pool_lds + ((group * HW + 1) & ~1));   // {chosen element, gradient}
     const int tid = threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * group;
-    float xr[NR], gr[NG];
+    float xr[NR / EV][EV], gr[NG / EV][EV];
 
     auto fetch = [&](int64_t pl0) {
         const int np = (int)min((int64_t)group, planes - pl0);
-        const float *xg = x + pl0 * HW;
-        const float *gg = dy + pl0 * PP;
+        const T *xg = x + pl0 * HW;
+        const T *gg = dy + pl0 * PP;
 #pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const int e = tid + 256 * k;
-            xr[k] = e < np * HW ? xg[e] : 0.f;
-        }
+        for (int k = 0; k < NR / EV; ++k) ld_group(xg, EV * (tid + 256 * k), np * HW, xr[k]);
 #pragma unroll
-        for (int k = 0; k < NG; ++k) {
-            const int o = tid + 256 * k;
-            gr[k] = o < np * PP ? gg[o] : 0.f;
-        }
+        for (int k = 0; k < NG / EV; ++k) ld_group(gg, EV * (tid + 256 * k), np * PP, gr[k]);
     };
 
     int64_t pl0 = (int64_t)blockIdx.x * group;
     if (pl0 < planes) fetch(pl0);
     for (; pl0 < planes; pl0 += stride) {
         const int np = (int)min((int64_t)group, planes - pl0);
-        float *og = dx + pl0 * HW;
+        T *og = dx + pl0 * HW;
 #pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const int e = tid + 256 * k;
-            if (e < np * HW) sx[e] = xr[k];
-        }
+        for (int k = 0; k < NR / EV; ++k)
+#pragma unroll
+            for (int u = 0; u < EV; ++u) {
+                const int e = EV * (tid + 256 * k) + u;
+                if (e < np * HW) sx[e] = xr[k][u];
+            }
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < NG; ++k) {
-            const int o = tid + 256 * k;
-            if (o < np * PP) {
-                const int pl = (int)fastdiv((uint32_t)o, dPP), rem = o - pl * PP;
-                const int i = (int)fastdiv((uint32_t)rem, dPW), j = rem - i * PW;
-                float m;
-                const int best = pool_argmax(sx + pl * HW, W, i, j, m);
-                swin[o] = make_float2(__int_as_float(best), gr[k]);
+        for (int k = 0; k < NG / EV; ++k)
+#pragma unroll
+            for (int u = 0; u < EV; ++u) {
+                const int o = EV * (tid + 256 * k) + u;
+                if (o < np * PP) {
+                    const int pl = (int)fastdiv((uint32_t)o, dPP), rem = o - pl * PP;
+                    const int i = (int)fastdiv((uint32_t)rem, dPW), j = rem - i * PW;
+                    float m;
+                    const int best = pool_argmax(sx + pl * HW, W, i, j, m);
+                    swin[o] = make_float2(__int_as_float(best), gr[k][u]);
+                }
             }
-        }
         if (pl0 + stride < planes) fetch(pl0 + stride);
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < NR; ++k) {
-            const int e = tid + 256 * k;
-            if (e < np * HW) {
-                const int pl = (int)fastdiv((uint32_t)e, dHW), self = e - pl * HW;
-                const int h = (int)fastdiv((uint32_t)self, dW), w = self - h * W;
-                // windows over row h: i1 = h/2, and i0 = h/2 - 1 when h is even (same for columns)
-                const int i1 = h >> 1, i0 = i1 - 1, j1 = w >> 1, j0 = j1 - 1;
-                const bool vi0 = ((h & 1) == 0) & (i0 >= 0) & (i0 < PH), vi1 = i1 < PH;
-                const bool vj0 = ((w & 1) == 0) & (j0 >= 0) & (j0 < PW), vj1 = j1 < PW;
-                const float2 *wp = swin + pl * PP;
+        for (int k = 0; k < NR / EV; ++k) {
+            float res[EV];
+#pragma unroll
+            for (int u = 0; u < EV; ++u) {
+                const int e = EV * (tid + 256 * k) + u;
                 float sum = 0.f;
-                auto take = [&](bool ok, int i, int j) {
-                    const float2 c = wp[ok ? i * PW + j : 0];
-                    sum += (ok & (__float_as_int(c.x) == self)) ? c.y : 0.f;
-                };
-                take(vi0 & vj0, i0, j0);
-                take(vi0 & vj1, i0, j1);
-                take(vi1 & vj0, i1, j0);
-                take(vi1 & vj1, i1, j1);
-                if (RELU && !(sx[e] > 0.f)) sum = 0.f;
-                og[e] = sum;
+                if (e < np * HW) {
+                    const int pl = (int)fastdiv((uint32_t)e, dHW), self = e - pl * HW;
+                    const int h = (int)fastdiv((uint32_t)self, dW), w = self - h * W;
+                    // windows over row h: i1 = h/2, and i0 = h/2 - 1 when h is even (same for columns)
+                    const int i1 = h >> 1, i0 = i1 - 1, j1 = w >> 1, j0 = j1 - 1;
+                    const bool vi0 = ((h & 1) == 0) & (i0 >= 0) & (i0 < PH), vi1 = i1 < PH;
+                    const bool vj0 = ((w & 1) == 0) & (j0 >= 0) & (j0 < PW), vj1 = j1 < PW;
+                    const float2 *wp = swin + pl * PP;
+                    auto take = [&](bool ok, int i, int j) {
+                        const float2 c = wp[ok ? i * PW + j : 0];
+                        sum += (ok & (__float_as_int(c.x) == self)) ? c.y : 0.f;
+                    };
+                    take(vi0 & vj0, i0, j0);
+                    take(vi0 & vj1, i0, j1);
+                    take(vi1 & vj0, i1, j0);
+                    take(vi1 & vj1, i1, j1);
+                    if (RELU && !(sx[e] > 0.f)) sum = 0.f;
+                }
+                res[u] = sum;
             }
+            st_group(og, EV * (tid + 256 * k), np * HW, res);
         }
         __syncthreads();
     }
@@ -2271,9 +2370,9 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const float *__restrict
 
 // Fallback for planes too large to stage: one thread per input element
 // recomputes the windows that contain it.
-template <bool RELU>
-__global__ void maxpool_bwd_kernel(const float *__restrict__ x, const float *__restrict__ dy,
-                                   float *__restrict__ dx, int64_t total, int H, int W, int PH, int PW)
+template <bool RELU, typename T>
+__global__ void maxpool_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy,
+                                   T *__restrict__ dx, int64_t total, int H, int W, int PH, int PW)
 {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= total) return;
@@ -2281,8 +2380,8 @@ __global__ void maxpool_bwd_kernel(const float *__restrict__ x, const float *__r
     int64_t u = t / W;
     int h = (int)(u % H);
     int64_t pl = u / H;
-    const float *xp = x + pl * H * W;
-    const float *gp = dy + pl * PH * PW;
+    const T *xp = x + pl * H * W;
+    const T *gp = dy + pl * PH * PW;
     const int self = h * W + w;
     int i_lo = h >= 2 ? (h - 1) / 2 : 0, i_hi = h / 2;
     int j_lo = w >= 2 ? (w - 1) / 2 : 0, j_hi = w / 2;
@@ -2292,10 +2391,10 @@ __global__ void maxpool_bwd_kernel(const float *__restrict__ x, const float *__r
     for (int i = i_lo; i <= i_hi; ++i)
         for (int j = j_lo; j <= j_hi; ++j) {
             float m;
-            if (pool_argmax(xp, W, i, j, m) == self) s += gp[i * PW + j];
+            if (pool_argmax(xp, W, i, j, m) == self) s += ld_elem(gp, i * PW + j);
         }
-    if (RELU && !(xp[self] > 0.f)) s = 0.f;
-    dx[t] = s;
+    if (RELU && !(ld_elem(xp, self) > 0.f)) s = 0.f;
+    st_elem(dx, t, s);
 }
 
 // ---------------------------------------------------------------------------
@@ -2484,12 +2583,14 @@ const float *as_f32(const void *src, int batch, int64_t sample, int64_t *bs, cha
 int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const Problem &caller_pb, const Plan &pl,
                        void *ws, hipStream_t st);
 
-// Forward / backward-data.  A bf16 destination is produced from a dense fp32 result in the workspace.
+// Forward / backward-data.  The bf16 kernels write a bf16 destination themselves; for the other paths it is
+// produced from a dense fp32 result in the workspace.
 int run_colgemm(int op, const void *act, const void *w, void *out, const Problem &pb, const Plan &pl, void *ws,
                 hipStream_t st)
 {
-    if (!pb.out_bf16) return run_colgemm_f32out(op, act, w, out, pb, pl, ws, st);
+    if (!pb.out_bf16 || pl.stage_bytes == 0) return run_colgemm_f32out(op, act, w, out, pb, pl, ws, st);
     Problem q = pb;
+    q.out_bf16 = false;
     const int64_t sample = op == kOpFwd ? (int64_t)pb.K * pb.P * pb.Q : (int64_t)pb.C * pb.H * pb.W;
     int64_t &out_bs = op == kOpFwd ? q.y_bs : q.x_bs;
     const int64_t caller_bs = out_bs;
@@ -2561,6 +2662,7 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         a.div_rs = make_fastdiv((uint32_t)RS);
         a.div_s = make_fastdiv((uint32_t)pb.S);
         a.ksplit = pl.nsplit;
+        a.out_bf16 = bf && pb.out_bf16;
         a.steps_per_split = ceil_div(a.cblocks * RS, pl.nsplit);      // same ranges as planned, in steps of kc
         a.part = reinterpret_cast<float *>(wsb + pl.part_off);
         const int need_lds = 2 * (pl.tile.bm() + pl.tile.bn()) * (bf ? kc * 2 + 16 : (kc + 4) * 4);
@@ -2571,8 +2673,13 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         int rc = check_launch();
         if (rc != kStatusOk || a.ksplit == 1) return rc;
         const int per_sample = a.M * a.OH * a.OW;
-        hipLaunchKernelGGL(reduce_split_outputs, dim3(2048), dim3(256), 0, st, a.part, a.dst, a.ksplit, per_sample,
-                           pb.N, a.dst_bs, make_fastdiv((uint32_t)per_sample));
+        if (a.out_bf16)
+            hipLaunchKernelGGL(reduce_split_outputs<unsigned short>, dim3(2048), dim3(256), 0, st, a.part,
+                               reinterpret_cast<unsigned short *>(a.dst), a.ksplit, per_sample, pb.N, a.dst_bs,
+                               make_fastdiv((uint32_t)per_sample));
+        else
+            hipLaunchKernelGGL(reduce_split_outputs<float>, dim3(2048), dim3(256), 0, st, a.part, a.dst, a.ksplit,
+                               per_sample, pb.N, a.dst_bs, make_fastdiv((uint32_t)per_sample));
         return check_launch();
     }
     // forward with few channels: stage the input rows once per work-group when they fit in LDS
@@ -2752,31 +2859,45 @@ int pool_checks(int64_t planes, int H, int W, int &PH, int &PW)
     return kStatusOk;
 }
 
+// element type of the glue tensors: fp32 for kDtypeF32, bfloat16 for the two bf16 codes
+int glue_elem_bytes(int dtype)
+{
+    if (dtype == kDtypeF32) return 4;
+    if (dtype == kDtypeBf16 || dtype == kDtypeBf16OutBf16) return 2;
+    return 0;
+}
+
+template <bool RELU, typename T>
+int pool_fwd_typed(const void *x, void *y, int64_t planes, int H, int W, int PH, int PW, hipStream_t st)
+{
+    const int64_t total = planes * PH * PW;
+    hipLaunchKernelGGL((maxpool_fwd_kernel<RELU, T>), dim3(grid1d(total, 256)), dim3(256), 0, st,
+                       static_cast<const T *>(x), static_cast<T *>(y), total, H, W, PH, PW);
+    return check_launch();
+}
+
 template <bool RELU>
-int pool_fwd_impl(const void *x, void *y, int64_t planes, int H, int W, void *stream)
+int pool_fwd_impl(const void *x, void *y, int64_t planes, int H, int W, int dtype, void *stream)
 {
     if (!x || !y) return kErrInvalidArg;
     int PH, PW;
     int rc = pool_checks(planes, H, W, PH, PW);
     if (rc != kStatusOk) return rc;
-    if (!aligned(x, 4) || !aligned(y, 4)) return kErrMisaligned;
-    const int64_t total = planes * PH * PW;
-    hipLaunchKernelGGL(maxpool_fwd_kernel<RELU>, dim3(grid1d(total, 256)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), static_cast<const float *>(x), static_cast<float *>(y), total,
-                       H, W, PH, PW);
-    return check_launch();
+    const int eb = glue_elem_bytes(dtype);
+    if (!eb) return kErrBadDtype;
+    if (!aligned(x, eb) || !aligned(y, eb)) return kErrMisaligned;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return eb == 4 ? pool_fwd_typed<RELU, float>(x, y, planes, H, W, PH, PW, st)
+                   : pool_fwd_typed<RELU, unsigned short>(x, y, planes, H, W, PH, PW, st);
 }
 
-template <bool RELU>
-int pool_bwd_impl(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream)
+template <bool RELU, typename T>
+int pool_bwd_typed(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, int PH, int PW,
+                   hipStream_t st)
 {
-    if (!x || !dy || !dx) return kErrInvalidArg;
-    int PH, PW;
-    int rc = pool_checks(planes, H, W, PH, PW);
-    if (rc != kStatusOk) return rc;
-    if (!aligned(x, 4) || !aligned(dy, 4) || !aligned(dx, 4)) return kErrMisaligned;
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const int HW = H * W, PP = PH * PW;
+    const T *xp = static_cast<const T *>(x), *gp = static_cast<const T *>(dy);
+    T *op = static_cast<T *>(dx);
     if (HW <= 256 * 40) {
         // planes staged whole: up to 16 elements per thread (several small planes), else one plane of up to 40
         const bool small = HW <= 256 * 16;
@@ -2785,20 +2906,54 @@ int pool_bwd_impl(const void *x, const void *dy, void *dx, int64_t planes, int H
         if (blocks > 256 * 6) blocks = 256 * 6;
         const size_t lds = (size_t)((group * HW + 1) & ~1) * 4 + (size_t)group * PP * 8;
         const FastDiv dHW = make_fastdiv(HW), dW = make_fastdiv(W), dPP = make_fastdiv(PP), dPW = make_fastdiv(PW);
-        const float *xp = static_cast<const float *>(x), *gp = static_cast<const float *>(dy);
-        float *op = static_cast<float *>(dx);
         if (small)
-            hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 16>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
+            hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 16, T>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
                                planes, H, W, PH, PW, group, dHW, dW, dPP, dPW);
         else
-            hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 40>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
+            hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 40, T>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
                                planes, H, W, PH, PW, group, dHW, dW, dPP, dPW);
     } else {
         const int64_t total = planes * H * W;
-        hipLaunchKernelGGL(maxpool_bwd_kernel<RELU>, dim3(grid1d(total, 256)), dim3(256), 0, st,
-                           static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx),
+        hipLaunchKernelGGL((maxpool_bwd_kernel<RELU, T>), dim3(grid1d(total, 256)), dim3(256), 0, st, xp, gp, op,
                            total, H, W, PH, PW);
     }
+    return check_launch();
+}
+
+template <bool RELU>
+int pool_bwd_impl(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, int dtype, void *stream)
+{
+    if (!x || !dy || !dx) return kErrInvalidArg;
+    int PH, PW;
+    int rc = pool_checks(planes, H, W, PH, PW);
+    if (rc != kStatusOk) return rc;
+    const int eb = glue_elem_bytes(dtype);
+    if (!eb) return kErrBadDtype;
+    if (!aligned(x, eb) || !aligned(dy, eb) || !aligned(dx, eb)) return kErrMisaligned;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return eb == 4 ? pool_bwd_typed<RELU, float>(x, dy, dx, planes, H, W, PH, PW, st)
+                   : pool_bwd_typed<RELU, unsigned short>(x, dy, dx, planes, H, W, PH, PW, st);
+}
+
+template <typename T>
+int relu_fwd_typed(const void *x, void *y, int64_t count, hipStream_t st)
+{
+    constexpr int V = 16 / (int)sizeof(T);
+    const int vec = aligned(x, 16) && aligned(y, 16);
+    const int64_t threads = vec ? count / V + V : count;
+    hipLaunchKernelGGL(relu_fwd_kernel<T>, dim3(grid1d(threads, 256)), dim3(256), 0, st, static_cast<const T *>(x),
+                       static_cast<T *>(y), count, vec);
+    return check_launch();
+}
+
+template <typename T>
+int relu_bwd_typed(const void *x, const void *dy, void *dx, int64_t count, hipStream_t st)
+{
+    constexpr int V = 16 / (int)sizeof(T);
+    const int vec = aligned(x, 16) && aligned(dy, 16) && aligned(dx, 16);
+    const int64_t threads = vec ? count / V + V : count;
+    hipLaunchKernelGGL(relu_bwd_kernel<T>, dim3(grid1d(threads, 256)), dim3(256), 0, st, static_cast<const T *>(x),
+                       static_cast<const T *>(dy), static_cast<T *>(dx), count, vec);
     return check_launch();
 }
 
@@ -2899,49 +3054,48 @@ int convert_f32_to_bf16(const void *src, void *dst, int64_t count, void *stream)
     return check_launch();
 }
 
-int relu_fwd(const void *x, void *y, int64_t count, void *stream)
+int relu_fwd(const void *x, void *y, int64_t count, int dtype, void *stream)
 {
     if (!x || !y || count < 0) return kErrInvalidArg;
+    const int eb = glue_elem_bytes(dtype);
+    if (!eb) return kErrBadDtype;
     if (count == 0) return kStatusOk;
-    if (!aligned(x, 4) || !aligned(y, 4)) return kErrMisaligned;
-    const int vec = aligned(x, 16) && aligned(y, 16);
-    const int64_t threads = vec ? (count >> 2) + 4 : count;
-    hipLaunchKernelGGL(relu_fwd_kernel, dim3(grid1d(threads, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const float *>(x), static_cast<float *>(y), count, vec);
-    return check_launch();
+    if (!aligned(x, eb) || !aligned(y, eb)) return kErrMisaligned;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return eb == 4 ? relu_fwd_typed<float>(x, y, count, st) : relu_fwd_typed<unsigned short>(x, y, count, st);
 }
 
-int relu_bwd(const void *x, const void *dy, void *dx, int64_t count, void *stream)
+int relu_bwd(const void *x, const void *dy, void *dx, int64_t count, int dtype, void *stream)
 {
     if (!x || !dy || !dx || count < 0) return kErrInvalidArg;
+    const int eb = glue_elem_bytes(dtype);
+    if (!eb) return kErrBadDtype;
     if (count == 0) return kStatusOk;
-    if (!aligned(x, 4) || !aligned(dy, 4) || !aligned(dx, 4)) return kErrMisaligned;
-    const int vec = aligned(x, 16) && aligned(dy, 16) && aligned(dx, 16);
-    const int64_t threads = vec ? (count >> 2) + 4 : count;
-    hipLaunchKernelGGL(relu_bwd_kernel, dim3(grid1d(threads, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const float *>(x), static_cast<const float *>(dy), static_cast<float *>(dx), count,
-                       vec);
-    return check_launch();
+    if (!aligned(x, eb) || !aligned(dy, eb) || !aligned(dx, eb)) return kErrMisaligned;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return eb == 4 ? relu_bwd_typed<float>(x, dy, dx, count, st)
+                   : relu_bwd_typed<unsigned short>(x, dy, dx, count, st);
 }
 
-int maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream)
+int maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, int dtype, void *stream)
 {
-    return pool_fwd_impl<false>(x, y, planes, H, W, stream);
+    return pool_fwd_impl<false>(x, y, planes, H, W, dtype, stream);
 }
 
-int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream)
+int maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, int dtype, void *stream)
 {
-    return pool_bwd_impl<false>(x, dy, dx, planes, H, W, stream);
+    return pool_bwd_impl<false>(x, dy, dx, planes, H, W, dtype, stream);
 }
 
-int relu_maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, void *stream)
+int relu_maxpool3x3s2_fwd(const void *x, void *y, int64_t planes, int H, int W, int dtype, void *stream)
 {
-    return pool_fwd_impl<true>(x, y, planes, H, W, stream);
+    return pool_fwd_impl<true>(x, y, planes, H, W, dtype, stream);
 }
 
-int relu_maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, void *stream)
+int relu_maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, int dtype,
+                          void *stream)
 {
-    return pool_bwd_impl<true>(x, dy, dx, planes, H, W, stream);
+    return pool_bwd_impl<true>(x, dy, dx, planes, H, W, dtype, stream);
 }
 
 }  // extern "C"

@@ -247,7 +247,7 @@ inline Plan make_plan(int op, const Problem &pb)
         pl.blk_bytes = (size_t)pb.N * Cr * (op == kOpFwd ? pb.H * pb.W : pb.P * pb.Q) * 2;
         off += round_up64(pl.blk_bytes, 256);
     }
-    if (pb.out_bf16 && op != kOpBwdFilter) {
+    if (pb.out_bf16 && op != kOpBwdFilter && !bf16_kernel) {
         pl.stage_off = off;
         pl.stage_bytes = (size_t)pb.N * (op == kOpFwd ? (size_t)pb.K * pb.P * pb.Q : (size_t)pb.C * pb.H * pb.W) * 4;
         off += round_up64(pl.stage_bytes, 256);

@@ -9,10 +9,10 @@ the shared NCHW tensors -- the two-column layout of the paper's
 model-parallelism paragraph.  Layers three to five run at full width.  The
 first layer computes no input gradient (nothing lies below it).
 
-With dtype="bf16" every convolution reads bfloat16 inputs (activations,
-gradients and filters rounded to nearest even by the library's conversion call
-right after they are produced) and accumulates and writes fp32; the glue
-layers stay fp32.
+With dtype="bf16" the input, the filters and every activation and gradient
+tensor are bfloat16: convolutions accumulate in fp32 and round each output once
+(forward and backward-data write bfloat16, backward-filter writes fp32 filter
+gradients), the glue layers work on bfloat16 tensors.
 
 This module only owns buffers and the order of calls; all arithmetic happens
 in the library.
@@ -44,11 +44,12 @@ class ConvStack:
     def __init__(self, N, seed=synth.SEED_BASE + 64, device="cuda", dtype="f32"):
         self.N = N
         self.bf16 = dtype == "bf16"
-        Ls = synth.LAYERS
-        f32 = dict(dtype=torch.float32, device=device)
+        act = dict(dtype=torch.bfloat16 if self.bf16 else torch.float32, device=device)
 
         def t(a):
-            return torch.from_numpy(a).to(device)
+            """Seeded host tensor on the device, in the stack's storage type."""
+            v = torch.from_numpy(a).to(device)
+            return hp.convert_f32_to_bf16(v) if self.bf16 else v
 
         self.x0 = t(synth.gaussian((N, 3, 224, 224), seed + 0))
         self.w = {
@@ -60,17 +61,17 @@ class ConvStack:
             "conv5": t(synth.gaussian((256, 384, 3, 3), seed + 6, synth.STD_FILTER)),
         }
         self.g5 = t(synth.gaussian((N, 256, 6, 6), seed + 7))
-        self.dw = {k: torch.empty_like(v) for k, v in self.w.items()}
+        self.dw = {k: torch.empty(v.shape, dtype=torch.float32, device=device) for k, v in self.w.items()}
         # activations (ReLU runs in place on y3, y4; y1, y2, y5 keep the pre-activation: their ReLU is fused
         # into the pooling calls)
-        self.y1 = torch.empty((N, 96, 55, 55), **f32)
-        self.a1 = torch.empty((N, 96, 27, 27), **f32)
-        self.y2 = torch.empty((N, 256, 27, 27), **f32)
-        self.a2 = torch.empty((N, 256, 13, 13), **f32)
-        self.y3 = torch.empty((N, 384, 13, 13), **f32)
-        self.y4 = torch.empty((N, 384, 13, 13), **f32)
-        self.y5 = torch.empty((N, 256, 13, 13), **f32)
-        self.a5 = torch.empty((N, 256, 6, 6), **f32)
+        self.y1 = torch.empty((N, 96, 55, 55), **act)
+        self.a1 = torch.empty((N, 96, 27, 27), **act)
+        self.y2 = torch.empty((N, 256, 27, 27), **act)
+        self.a2 = torch.empty((N, 256, 13, 13), **act)
+        self.y3 = torch.empty((N, 384, 13, 13), **act)
+        self.y4 = torch.empty((N, 384, 13, 13), **act)
+        self.y5 = torch.empty((N, 256, 13, 13), **act)
+        self.a5 = torch.empty((N, 256, 6, 6), **act)
         # gradients
         self.dy5 = torch.empty_like(self.y5)
         self.dy4 = torch.empty_like(self.y4)
@@ -81,24 +82,6 @@ class ConvStack:
         self.dy1 = torch.empty_like(self.y1)
         self.ws = hp.Workspace(device)
         self.timers = None          # optional dict name -> (start, stop) events per conv call
-        if self.bf16:
-            # bf16 images of every tensor a convolution reads
-            self.b = {name: torch.empty(getattr(self, name).shape, dtype=torch.bfloat16, device=device)
-                      for name in ("x0", "a1", "a2", "y3", "y4", "dy5", "dy4", "dy3", "dy2", "dy1")}
-            self.wb = {k: hp.convert_f32_to_bf16(v) for k, v in self.w.items()}
-            hp.convert_f32_to_bf16(self.x0, self.b["x0"])
-
-    def _in(self, name):
-        """The tensor `name` as the convolutions read it (rounded to bf16 first in bf16 mode)."""
-        t = getattr(self, name)
-        if not self.bf16:
-            return t
-        if name != "x0":
-            hp.convert_f32_to_bf16(t, self.b[name])
-        return self.b[name]
-
-    def _w(self, name):
-        return self.wb[name] if self.bf16 else self.w[name]
 
     # -- helpers ------------------------------------------------------------
     def _timed(self, key, fn):
@@ -112,61 +95,49 @@ class ConvStack:
         return out
 
     def forward(self):
-        w, ws = self._w, self.ws
-        x0 = self._in("x0")
-        self._timed(("conv1", "fwd"), lambda: hp.conv_fwd(x0, w("conv1"), 4, 2, y=self.y1, ws=ws))
+        w, ws = self.w, self.ws
+        self._timed(("conv1", "fwd"), lambda: hp.conv_fwd(self.x0, w["conv1"], 4, 2, y=self.y1, ws=ws))
         hp.relu_maxpool3x3s2_fwd(self.y1, self.a1)
-        a1 = self._in("a1")
         self._timed(("conv2a", "fwd"),
-                    lambda: hp.conv_fwd(a1[:, :48], w("conv2a"), 1, 2, y=self.y2[:, :128], ws=ws))
+                    lambda: hp.conv_fwd(self.a1[:, :48], w["conv2a"], 1, 2, y=self.y2[:, :128], ws=ws))
         self._timed(("conv2b", "fwd"),
-                    lambda: hp.conv_fwd(a1[:, 48:], w("conv2b"), 1, 2, y=self.y2[:, 128:], ws=ws))
+                    lambda: hp.conv_fwd(self.a1[:, 48:], w["conv2b"], 1, 2, y=self.y2[:, 128:], ws=ws))
         hp.relu_maxpool3x3s2_fwd(self.y2, self.a2)
-        a2 = self._in("a2")
-        self._timed(("conv3", "fwd"), lambda: hp.conv_fwd(a2, w("conv3"), 1, 1, y=self.y3, ws=ws))
+        self._timed(("conv3", "fwd"), lambda: hp.conv_fwd(self.a2, w["conv3"], 1, 1, y=self.y3, ws=ws))
         hp.relu_fwd(self.y3, self.y3)
-        y3 = self._in("y3")
-        self._timed(("conv4", "fwd"), lambda: hp.conv_fwd(y3, w("conv4"), 1, 1, y=self.y4, ws=ws))
+        self._timed(("conv4", "fwd"), lambda: hp.conv_fwd(self.y3, w["conv4"], 1, 1, y=self.y4, ws=ws))
         hp.relu_fwd(self.y4, self.y4)
-        y4 = self._in("y4")
-        self._timed(("conv5", "fwd"), lambda: hp.conv_fwd(y4, w("conv5"), 1, 1, y=self.y5, ws=ws))
+        self._timed(("conv5", "fwd"), lambda: hp.conv_fwd(self.y4, w["conv5"], 1, 1, y=self.y5, ws=ws))
         hp.relu_maxpool3x3s2_fwd(self.y5, self.a5)
         return self.a5
 
     def backward(self):
-        w, dw, ws = self._w, self.dw, self.ws
-        # activations as the forward pass left them (bf16 images are still current)
-        rd = (lambda n: self.b[n]) if self.bf16 else (lambda n: getattr(self, n))
+        w, dw, ws = self.w, self.dw, self.ws
         hp.relu_maxpool3x3s2_bwd(self.y5, self.g5, self.dy5)
-        dy5 = self._in("dy5")
         self._timed(("conv5", "wgrad"),
-                    lambda: hp.conv_bwd_filter(rd("y4"), dy5, 3, 3, 1, 1, dw=dw["conv5"], ws=ws))
+                    lambda: hp.conv_bwd_filter(self.y4, self.dy5, 3, 3, 1, 1, dw=dw["conv5"], ws=ws))
         self._timed(("conv5", "dgrad"),
-                    lambda: hp.conv_bwd_data(dy5, w("conv5"), 13, 13, 1, 1, dx=self.dy4, ws=ws))
+                    lambda: hp.conv_bwd_data(self.dy5, w["conv5"], 13, 13, 1, 1, dx=self.dy4, ws=ws))
         hp.relu_bwd(self.y4, self.dy4, self.dy4)
-        dy4 = self._in("dy4")
         self._timed(("conv4", "wgrad"),
-                    lambda: hp.conv_bwd_filter(rd("y3"), dy4, 3, 3, 1, 1, dw=dw["conv4"], ws=ws))
+                    lambda: hp.conv_bwd_filter(self.y3, self.dy4, 3, 3, 1, 1, dw=dw["conv4"], ws=ws))
         self._timed(("conv4", "dgrad"),
-                    lambda: hp.conv_bwd_data(dy4, w("conv4"), 13, 13, 1, 1, dx=self.dy3, ws=ws))
+                    lambda: hp.conv_bwd_data(self.dy4, w["conv4"], 13, 13, 1, 1, dx=self.dy3, ws=ws))
         hp.relu_bwd(self.y3, self.dy3, self.dy3)
-        dy3 = self._in("dy3")
         self._timed(("conv3", "wgrad"),
-                    lambda: hp.conv_bwd_filter(rd("a2"), dy3, 3, 3, 1, 1, dw=dw["conv3"], ws=ws))
+                    lambda: hp.conv_bwd_filter(self.a2, self.dy3, 3, 3, 1, 1, dw=dw["conv3"], ws=ws))
         self._timed(("conv3", "dgrad"),
-                    lambda: hp.conv_bwd_data(dy3, w("conv3"), 13, 13, 1, 1, dx=self.da2, ws=ws))
+                    lambda: hp.conv_bwd_data(self.dy3, w["conv3"], 13, 13, 1, 1, dx=self.da2, ws=ws))
         hp.relu_maxpool3x3s2_bwd(self.y2, self.da2, self.dy2)
-        dy2, a1 = self._in("dy2"), rd("a1")
         for col, (c0, k0) in (("conv2a", (0, 0)), ("conv2b", (48, 128))):
-            xs, gs = a1[:, c0:c0 + 48], dy2[:, k0:k0 + 128]
+            xs, gs = self.a1[:, c0:c0 + 48], self.dy2[:, k0:k0 + 128]
             self._timed((col, "wgrad"),
                         lambda: hp.conv_bwd_filter(xs, gs, 5, 5, 1, 2, dw=dw[col], ws=ws))
             self._timed((col, "dgrad"),
-                        lambda: hp.conv_bwd_data(gs, w(col), 27, 27, 1, 2, dx=self.da1[:, c0:c0 + 48], ws=ws))
+                        lambda: hp.conv_bwd_data(gs, w[col], 27, 27, 1, 2, dx=self.da1[:, c0:c0 + 48], ws=ws))
         hp.relu_maxpool3x3s2_bwd(self.y1, self.da1, self.dy1)
-        dy1 = self._in("dy1")
         self._timed(("conv1", "wgrad"),
-                    lambda: hp.conv_bwd_filter(rd("x0"), dy1, 11, 11, 4, 2, dw=dw["conv1"], ws=ws))
+                    lambda: hp.conv_bwd_filter(self.x0, self.dy1, 11, 11, 4, 2, dw=dw["conv1"], ws=ws))
         return dw
 
     def step(self):

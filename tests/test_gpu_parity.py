@@ -415,8 +415,8 @@ def test_relu_vector_and_tail_paths():
         for off in (0, 1):                                      # off = 1 breaks the 16-byte alignment
             xd, gd = dev(x)[off:off + n], dev(g)[off:off + n]
             y = torch.full((n + 2,), float("nan"), device="cuda")
-            hp.lib().relu_fwd(hp._ptr(xd), y[1:].data_ptr(), n, None)
-            hp.lib().relu_bwd(hp._ptr(xd), hp._ptr(gd), y[1:].data_ptr(), 0, None)
+            hp.lib().relu_fwd(hp._ptr(xd), y[1:].data_ptr(), n, hp.DTYPE_F32, None)
+            hp.lib().relu_bwd(hp._ptr(xd), hp._ptr(gd), y[1:].data_ptr(), 0, hp.DTYPE_F32, None)
             torch.cuda.synchronize()
             assert torch.isnan(y[0]) and torch.isnan(y[n + 1])
             assert np.array_equal(y[1:n + 1].cpu().numpy(), oracle.relu_fwd(x[off:off + n]).astype(np.float32))
@@ -474,29 +474,84 @@ def test_convert_f32_to_bf16_is_round_to_nearest_even():
 
 
 def test_bf16_stack_step_layer_by_layer():
-    """bf16 mode of the stack: every convolution against the oracle applied to the bf16 tensors it actually read."""
+    """bf16 mode of the stack (bf16 activations and gradients, fp32 filter gradients): every call against the
+    oracle applied to the bf16 tensors that call read.  Convolution outputs are rounded once to bf16, so they are
+    within the bf16 tolerance; ReLU and pooling forward are exact; pooling backward rounds a sum of up to four."""
     from paper_1312_5853_amd.stack import ConvStack
     st = ConvStack(2, dtype="bf16")
-    st.step()
+    a5d = st.forward()
     torch.cuda.synchronize()
     f = lambda t: t.float().cpu().numpy()
-    b, wb, dw = {k: f(v) for k, v in st.b.items()}, {k: f(v) for k, v in st.wb.items()}, {k: f(v) for k, v in st.dw.items()}
-    y1, y2, y3, y4, y5, da2, da1 = map(f, (st.y1, st.y2, st.y3, st.y4, st.y5, st.da2, st.da1))
+    x0, w = f(st.x0), {k: f(v) for k, v in st.w.items()}
+    y1, a1, y2, a2, y3, y4, y5, a5 = map(f, (st.y1, st.a1, st.y2, st.a2, st.y3, st.y4, st.y5, a5d))
     tol = TOL["bf16"]
-    assert norm_err(y1, oracle.conv_fwd(b["x0"], wb["conv1"], 4, 2)) <= tol
-    assert norm_err(y2[:, :128], oracle.conv_fwd(b["a1"][:, :48], wb["conv2a"], 1, 2)) <= tol
-    assert norm_err(y2[:, 128:], oracle.conv_fwd(b["a1"][:, 48:], wb["conv2b"], 1, 2)) <= tol
-    assert norm_err(y3, oracle.relu_fwd(oracle.conv_fwd(b["a2"], wb["conv3"], 1, 1))) <= tol
-    assert norm_err(y4, oracle.relu_fwd(oracle.conv_fwd(b["y3"], wb["conv4"], 1, 1))) <= tol
-    assert norm_err(y5, oracle.conv_fwd(b["y4"], wb["conv5"], 1, 1)) <= tol
-    # the bf16 images are the roundings of what the fp32 glue produced
-    assert np.array_equal(b["y4"], synth.to_bf16_grid(y4)) and np.array_equal(b["a1"], synth.to_bf16_grid(f(st.a1)))
-    assert norm_err(dw["conv5"], oracle.conv_bwd_filter(b["y4"], b["dy5"], 3, 3, 1, 1)) <= tol
-    assert norm_err(dw["conv4"], oracle.conv_bwd_filter(b["y3"], b["dy4"], 3, 3, 1, 1)) <= tol
-    assert norm_err(dw["conv3"], oracle.conv_bwd_filter(b["a2"], b["dy3"], 3, 3, 1, 1)) <= tol
-    assert norm_err(da2, oracle.conv_bwd_data(b["dy3"], wb["conv3"], 13, 13, 1, 1)) <= tol
-    assert norm_err(dw["conv2a"], oracle.conv_bwd_filter(b["a1"][:, :48], b["dy2"][:, :128], 5, 5, 1, 2)) <= tol
-    assert norm_err(dw["conv2b"], oracle.conv_bwd_filter(b["a1"][:, 48:], b["dy2"][:, 128:], 5, 5, 1, 2)) <= tol
-    assert norm_err(da1[:, :48], oracle.conv_bwd_data(b["dy2"][:, :128], wb["conv2a"], 27, 27, 1, 2)) <= tol
-    assert norm_err(da1[:, 48:], oracle.conv_bwd_data(b["dy2"][:, 128:], wb["conv2b"], 27, 27, 1, 2)) <= tol
-    assert norm_err(dw["conv1"], oracle.conv_bwd_filter(b["x0"], b["dy1"], 11, 11, 4, 2)) <= tol
+    assert st.y1.dtype == torch.bfloat16 and st.dy1.dtype == torch.bfloat16 and st.dw["conv1"].dtype == torch.float32
+    assert norm_err(y1, oracle.conv_fwd(x0, w["conv1"], 4, 2)) <= tol
+    assert np.array_equal(a1, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y1)).astype(np.float32))
+    assert norm_err(y2[:, :128], oracle.conv_fwd(a1[:, :48], w["conv2a"], 1, 2)) <= tol
+    assert norm_err(y2[:, 128:], oracle.conv_fwd(a1[:, 48:], w["conv2b"], 1, 2)) <= tol
+    assert np.array_equal(a2, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y2)).astype(np.float32))
+    # y3, y4 hold the activation (ReLU applied in place to the rounded convolution output)
+    assert norm_err(y3, oracle.relu_fwd(oracle.conv_fwd(a2, w["conv3"], 1, 1))) <= tol
+    assert norm_err(y4, oracle.relu_fwd(oracle.conv_fwd(y3, w["conv4"], 1, 1))) <= tol
+    assert (y3 >= 0).all() and (y4 >= 0).all()
+    assert norm_err(y5, oracle.conv_fwd(y4, w["conv5"], 1, 1)) <= tol
+    assert np.array_equal(a5, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y5)).astype(np.float32))
+
+    st.backward()
+    torch.cuda.synchronize()
+    g5, dy5, dy4, dy3, da2, dy2, da1, dy1 = map(f, (st.g5, st.dy5, st.dy4, st.dy3, st.da2, st.dy2, st.da1, st.dy1))
+    dw = {k: f(v) for k, v in st.dw.items()}
+    rnd = 2.0 ** -8                                            # one rounding to bf16, relative to the largest value
+    assert norm_err(dy5, oracle.relu_bwd(y5, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y5), g5))) <= rnd
+    assert norm_err(dw["conv5"], oracle.conv_bwd_filter(y4, dy5, 3, 3, 1, 1)) <= tol
+    # dy4 and dy3 hold the gradient after the in-place ReLU backward
+    assert norm_err(dy4, oracle.relu_bwd(y4, oracle.conv_bwd_data(dy5, w["conv5"], 13, 13, 1, 1))) <= tol
+    assert norm_err(dw["conv4"], oracle.conv_bwd_filter(y3, dy4, 3, 3, 1, 1)) <= tol
+    assert norm_err(dy3, oracle.relu_bwd(y3, oracle.conv_bwd_data(dy4, w["conv4"], 13, 13, 1, 1))) <= tol
+    assert norm_err(dw["conv3"], oracle.conv_bwd_filter(a2, dy3, 3, 3, 1, 1)) <= tol
+    assert norm_err(da2, oracle.conv_bwd_data(dy3, w["conv3"], 13, 13, 1, 1)) <= tol
+    assert norm_err(dy2, oracle.relu_bwd(y2, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y2), da2))) <= rnd
+    assert norm_err(dw["conv2a"], oracle.conv_bwd_filter(a1[:, :48], dy2[:, :128], 5, 5, 1, 2)) <= tol
+    assert norm_err(dw["conv2b"], oracle.conv_bwd_filter(a1[:, 48:], dy2[:, 128:], 5, 5, 1, 2)) <= tol
+    assert norm_err(da1[:, :48], oracle.conv_bwd_data(dy2[:, :128], w["conv2a"], 27, 27, 1, 2)) <= tol
+    assert norm_err(da1[:, 48:], oracle.conv_bwd_data(dy2[:, 128:], w["conv2b"], 27, 27, 1, 2)) <= tol
+    assert norm_err(dy1, oracle.relu_bwd(y1, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y1), da1))) <= rnd
+    assert norm_err(dw["conv1"], oracle.conv_bwd_filter(x0, dy1, 11, 11, 4, 2)) <= tol
+
+
+def test_bf16_glue_matches_oracle():
+    """Glue on bfloat16 tensors: ReLU and pooling forward return input values (exact); pooling backward adds up to
+    four bf16 gradients in fp32 and rounds once."""
+    for (N, C, H, W) in [(3, 5, 55, 55), (2, 7, 27, 27), (9, 33, 13, 13), (1, 1, 3, 3), (2, 2, 8, 5), (1, 3, 90, 100),
+                         (1, 2, 120, 115), (1, 1, 7, 1003)]:
+        x = synth.to_bf16_grid(synth.gaussian((N, C, H, W), 171))
+        x[0, 0, :3, :3] = 0.0
+        xd = dev(x, "bf16")
+        f = lambda t: t.float().cpu().numpy()
+        assert np.array_equal(f(hp.relu_fwd(xd)), oracle.relu_fwd(x).astype(np.float32))
+        y = hp.maxpool3x3s2_fwd(xd)
+        yo = oracle.maxpool3x3s2_fwd(x)
+        assert y.dtype == torch.bfloat16 and np.array_equal(f(y), yo.astype(np.float32))
+        assert np.array_equal(f(hp.relu_maxpool3x3s2_fwd(xd)), oracle.maxpool3x3s2_fwd(oracle.relu_fwd(x)).astype(np.float32))
+        g = synth.to_bf16_grid(synth.gaussian(yo.shape, 172))
+        gd = dev(g, "bf16")
+        marker = torch.full(x.shape, 7.0, dtype=torch.bfloat16, device="cuda")
+        dxp = hp.maxpool3x3s2_bwd(xd, gd, dx=marker)
+        want = oracle.maxpool3x3s2_bwd(x, g)
+        assert norm_err(f(dxp), want) <= 2.0 ** -8
+        # where a single window contributes the result is that gradient, exactly; where none does, zero
+        single = np.isin(want, g) | (want == 0)
+        assert np.array_equal(f(dxp)[single], want[single].astype(np.float32))
+        dxr = hp.relu_maxpool3x3s2_bwd(xd, gd)
+        assert norm_err(f(dxr), oracle.relu_bwd(x, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(x), g))) <= 2.0 ** -8
+        g2 = synth.to_bf16_grid(synth.gaussian(x.shape, 173))
+        assert np.array_equal(f(hp.relu_bwd(xd, dev(g2, "bf16"))), oracle.relu_bwd(x, g2).astype(np.float32))
+    # odd counts and unaligned bases: the vector body, the tail and the scalar form of the ReLU kernels
+    for count, off in [(1, 0), (7, 0), (8, 0), (1029, 0), (1029, 1), (4099, 3)]:
+        x = synth.to_bf16_grid(synth.gaussian((count + off,), 174))
+        g = synth.to_bf16_grid(synth.gaussian((count + off,), 175))
+        xd, gd = dev(x, "bf16")[off:], dev(g, "bf16")[off:]
+        f = lambda t: t.float().cpu().numpy()
+        assert np.array_equal(f(hp.relu_fwd(xd)), oracle.relu_fwd(x[off:]).astype(np.float32))
+        assert np.array_equal(f(hp.relu_bwd(xd, gd)), oracle.relu_bwd(x[off:], g[off:]).astype(np.float32))

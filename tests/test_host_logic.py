@@ -97,30 +97,39 @@ def test_workspace_bytes(lib):
     # bf16 kernel: the only addition is the channel-blocked bf16 copy of the output gradient
     extra = lib.conv_workspace_bytes(1, *dims, 1) - lib.conv_workspace_bytes(1, *dims, 0)
     assert 0 < extra <= 128 * 384 * 169 * 2 + 256
-    # bf16 outputs add a dense fp32 staging copy of the result (forward, backward-data), nothing for backward-filter
-    assert lib.conv_workspace_bytes(0, *dims, 2) - lib.conv_workspace_bytes(0, *dims, 1) == 128 * 384 * 169 * 4
-    assert lib.conv_workspace_bytes(1, *dims, 2) - lib.conv_workspace_bytes(1, *dims, 1) == 128 * 256 * 169 * 4
-    assert lib.conv_workspace_bytes(2, *dims, 2) == lib.conv_workspace_bytes(2, *dims, 1)
+    # bf16 outputs: written by the bf16 kernels themselves, nothing extra
+    for op in (0, 1, 2):
+        assert lib.conv_workspace_bytes(op, *dims, 2) == lib.conv_workspace_bytes(op, *dims, 1)
     odd = [4, 3, 32, 32, 20, 5, 5, 2, 1]                                                     # widened to fp32 copies
     for op in (0, 1, 2):
         assert lib.conv_workspace_bytes(op, *odd, 1) > lib.conv_workspace_bytes(op, *odd, 0)
+    # ... and with bf16 outputs their fp32 result is staged (P = Q = 15): forward 4*20*15*15, backward-data 4*3*32*32
+    up = lambda v: -(-v // 256) * 256                                       # regions are 256-byte aligned
+    assert lib.conv_workspace_bytes(0, *odd, 2) - lib.conv_workspace_bytes(0, *odd, 1) == up(4 * 20 * 15 * 15 * 4)
+    assert lib.conv_workspace_bytes(1, *odd, 2) - lib.conv_workspace_bytes(1, *odd, 1) == up(4 * 3 * 32 * 32 * 4)
+    assert lib.conv_workspace_bytes(2, *odd, 2) == lib.conv_workspace_bytes(2, *odd, 1)
     assert lib.conv_workspace_bytes(3, *dims, 0) == 0
     assert lib.conv_workspace_bytes(0, 0, 256, 13, 13, 384, 3, 3, 1, 1, 0) == 0
 
 
 def test_glue_argument_checks(lib):
     from paper_1312_5853_amd import binding as b
-    assert lib.relu_fwd(None, PTR, 4, None) == b.ERR_INVALID_ARG
-    assert lib.relu_fwd(PTR, PTR, -1, None) == b.ERR_INVALID_ARG
-    assert lib.relu_fwd(PTR, PTR, 0, None) == b.OK
-    assert lib.relu_bwd(PTR, PTR + 2, PTR, 4, None) == b.ERR_MISALIGNED
+    assert lib.relu_fwd(None, PTR, 4, 0, None) == b.ERR_INVALID_ARG
+    assert lib.relu_fwd(PTR, PTR, -1, 0, None) == b.ERR_INVALID_ARG
+    assert lib.relu_fwd(PTR, PTR, 0, 0, None) == b.OK
+    assert lib.relu_fwd(PTR, PTR, 4, 3, None) == b.ERR_BAD_DTYPE
+    assert lib.relu_bwd(PTR, PTR + 2, PTR, 4, 0, None) == b.ERR_MISALIGNED      # fp32 needs 4-byte alignment
+    assert lib.relu_bwd(PTR, PTR + 1, PTR, 4, 1, None) == b.ERR_MISALIGNED      # bf16 needs 2-byte alignment
     for fn in (lib.maxpool3x3s2_fwd, lib.relu_maxpool3x3s2_fwd):
-        assert fn(PTR, PTR, 4, 2, 5, None) == b.ERR_INVALID_ARG         # plane smaller than the window
-        assert fn(PTR, PTR, 0, 5, 5, None) == b.ERR_INVALID_ARG
-        assert fn(None, PTR, 1, 5, 5, None) == b.ERR_INVALID_ARG
+        assert fn(PTR, PTR, 4, 2, 5, 0, None) == b.ERR_INVALID_ARG         # plane smaller than the window
+        assert fn(PTR, PTR, 0, 5, 5, 0, None) == b.ERR_INVALID_ARG
+        assert fn(None, PTR, 1, 5, 5, 0, None) == b.ERR_INVALID_ARG
+        assert fn(PTR, PTR, 1, 5, 5, 7, None) == b.ERR_BAD_DTYPE
     for fn in (lib.maxpool3x3s2_bwd, lib.relu_maxpool3x3s2_bwd):
-        assert fn(PTR, None, PTR, 1, 5, 5, None) == b.ERR_INVALID_ARG
-        assert fn(PTR, PTR, PTR + 1, 1, 5, 5, None) == b.ERR_MISALIGNED
+        assert fn(PTR, None, PTR, 1, 5, 5, 0, None) == b.ERR_INVALID_ARG
+        assert fn(PTR, PTR, PTR + 1, 1, 5, 5, 0, None) == b.ERR_MISALIGNED
+        assert fn(PTR, PTR, PTR + 1, 1, 5, 5, 2, None) == b.ERR_MISALIGNED
+        assert fn(PTR, PTR, PTR, 1, 5, 5, -1, None) == b.ERR_BAD_DTYPE
 
 
 def test_binding_fails_loudly_without_the_library(tmp_path):
