@@ -2251,21 +2251,26 @@ __global__ void maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, i
 // group is being worked on in LDS; index arithmetic uses multiply-shift division.
 // group * H*W <= 256 * NR; windows are fewer than a quarter of the elements.
 // A thread's unit of global access in the tiled pooling backward: one float, or two adjacent bfloat16 as
-// one 32-bit access (2-byte aligned: planes of odd size start anywhere).  e < limit selects what exists.
-typedef unsigned int u32_align2 __attribute__((aligned(2)));
+// one aligned 32-bit access.  Indices outside [0, limit) do not exist (the pair grid is shifted by
+// align_shift() so that pairs are 4-byte aligned even where a plane group starts on an odd element).
+__device__ __forceinline__ int align_shift(const float *) { return 0; }
+__device__ __forceinline__ int align_shift(const unsigned short *p)
+{
+    return (int)((reinterpret_cast<uintptr_t>(p) >> 1) & 1);
+}
 __device__ __forceinline__ void ld_group(const float *p, int e, int limit, float (&v)[1])
 {
     v[0] = e < limit ? p[e] : 0.f;
 }
 __device__ __forceinline__ void ld_group(const unsigned short *p, int e, int limit, float (&v)[2])
 {
-    if (e + 1 < limit) {
-        const unsigned u = *reinterpret_cast<const u32_align2 *>(p + e);
+    if (e >= 0 && e + 1 < limit) {
+        const unsigned u = *reinterpret_cast<const unsigned *>(p + e);
         v[0] = __uint_as_float(u << 16);
         v[1] = __uint_as_float(u & 0xFFFF0000u);
     } else {
-        v[0] = e < limit ? ld_elem(p, e) : 0.f;
-        v[1] = 0.f;
+        v[0] = (e >= 0 && e < limit) ? ld_elem(p, e) : 0.f;
+        v[1] = (e + 1 >= 0 && e + 1 < limit) ? ld_elem(p, e + 1) : 0.f;
     }
 }
 __device__ __forceinline__ void st_group(float *p, int e, int limit, const float (&v)[1])
@@ -2274,10 +2279,12 @@ __device__ __forceinline__ void st_group(float *p, int e, int limit, const float
 }
 __device__ __forceinline__ void st_group(unsigned short *p, int e, int limit, const float (&v)[2])
 {
-    if (e + 1 < limit)
-        *reinterpret_cast<u32_align2 *>(p + e) = (unsigned)bf16_round(v[0]) | ((unsigned)bf16_round(v[1]) << 16);
-    else if (e < limit)
-        p[e] = bf16_round(v[0]);
+    if (e >= 0 && e + 1 < limit) {
+        *reinterpret_cast<unsigned *>(p + e) = (unsigned)bf16_round(v[0]) | ((unsigned)bf16_round(v[1]) << 16);
+    } else {
+        if (e >= 0 && e < limit) p[e] = bf16_round(v[0]);
+        if (e + 1 >= 0 && e + 1 < limit) p[e + 1] = bf16_round(v[1]);
+    }
 }
 
 template <bool RELU, int NR, typename T>
@@ -2289,22 +2296,27 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
     constexpr int NG = NR / 4;
     constexpr int EV = 4 / (int)sizeof(T);          // adjacent elements per access: 1 float or 2 bfloat16
     static_assert(NR % EV == 0 && NG % EV == 0, "whole access groups per thread");
+    // groups per thread; with pairs one more, since the pair grid may start one element early
+    constexpr int KX = NR / EV + (EV > 1), KG = NG / EV + (EV > 1);
     extern __shared__ float pool_lds[];
     const int HW = H * W, PP = PH * PW;
     float *sx = pool_lds;                                                      // group * HW values
     float2 *swin = reinterpret_cast<float2 *>(pool_lds + ((group * HW + 1) & ~1));   // {chosen element, gradient}
     const int tid = threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * group;
-    float xr[NR / EV][EV], gr[NG / EV][EV];
+    float xr[KX][EV], gr[KG][EV];
+    int xs = 0, gs = 0;                              // shifts of the pair grids of the fetched x and dy groups
 
     auto fetch = [&](int64_t pl0) {
         const int np = (int)min((int64_t)group, planes - pl0);
         const T *xg = x + pl0 * HW;
         const T *gg = dy + pl0 * PP;
+        xs = align_shift(xg);
+        gs = align_shift(gg);
 #pragma unroll
-        for (int k = 0; k < NR / EV; ++k) ld_group(xg, EV * (tid + 256 * k), np * HW, xr[k]);
+        for (int k = 0; k < KX; ++k) ld_group(xg, EV * (tid + 256 * k) - xs, np * HW, xr[k]);
 #pragma unroll
-        for (int k = 0; k < NG / EV; ++k) ld_group(gg, EV * (tid + 256 * k), np * PP, gr[k]);
+        for (int k = 0; k < KG; ++k) ld_group(gg, EV * (tid + 256 * k) - gs, np * PP, gr[k]);
     };
 
     int64_t pl0 = (int64_t)blockIdx.x * group;
@@ -2312,20 +2324,21 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
     for (; pl0 < planes; pl0 += stride) {
         const int np = (int)min((int64_t)group, planes - pl0);
         T *og = dx + pl0 * HW;
+        const int os = align_shift(og);
 #pragma unroll
-        for (int k = 0; k < NR / EV; ++k)
+        for (int k = 0; k < KX; ++k)
 #pragma unroll
             for (int u = 0; u < EV; ++u) {
-                const int e = EV * (tid + 256 * k) + u;
-                if (e < np * HW) sx[e] = xr[k][u];
+                const int e = EV * (tid + 256 * k) - xs + u;
+                if (e >= 0 && e < np * HW) sx[e] = xr[k][u];
             }
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < NG / EV; ++k)
+        for (int k = 0; k < KG; ++k)
 #pragma unroll
             for (int u = 0; u < EV; ++u) {
-                const int o = EV * (tid + 256 * k) + u;
-                if (o < np * PP) {
+                const int o = EV * (tid + 256 * k) - gs + u;
+                if (o >= 0 && o < np * PP) {
                     const int pl = (int)fastdiv((uint32_t)o, dPP), rem = o - pl * PP;
                     const int i = (int)fastdiv((uint32_t)rem, dPW), j = rem - i * PW;
                     float m;
@@ -2336,13 +2349,13 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
         if (pl0 + stride < planes) fetch(pl0 + stride);
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < NR / EV; ++k) {
+        for (int k = 0; k < KX; ++k) {
             float res[EV];
 #pragma unroll
             for (int u = 0; u < EV; ++u) {
-                const int e = EV * (tid + 256 * k) + u;
+                const int e = EV * (tid + 256 * k) - os + u;
                 float sum = 0.f;
-                if (e < np * HW) {
+                if (e >= 0 && e < np * HW) {
                     const int pl = (int)fastdiv((uint32_t)e, dHW), self = e - pl * HW;
                     const int h = (int)fastdiv((uint32_t)self, dW), w = self - h * W;
                     // windows over row h: i1 = h/2, and i0 = h/2 - 1 when h is even (same for columns)
@@ -2362,7 +2375,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
                 }
                 res[u] = sum;
             }
-            st_group(og, EV * (tid + 256 * k), np * HW, res);
+            st_group(og, EV * (tid + 256 * k) - os, np * HW, res);
         }
         __syncthreads();
     }
