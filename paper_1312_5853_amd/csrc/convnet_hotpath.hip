@@ -14,6 +14,7 @@
 
 #include <stdio.h>
 #include <algorithm>
+#include <type_traits>
 #include <stdlib.h>
 #include <string.h>
 
@@ -466,9 +467,14 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
     const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
     const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * KC) + tid + step_begin * a_step;
 
-    f32x4 areg[A4T];
-    float breg[EPT];
-    bool bok;
+    // Data of step t lives in register set t & 1 and LDS buffer t & 1.  While step s is multiplied out of
+    // buffer s & 1, the loads of step s + 2 are issued into set s & 1 (free since its contents went to LDS
+    // during step s - 1) and the values of step s + 1, loaded a whole step earlier, are written from the other
+    // set into the other buffer -- all of it in slots between the matrix instructions, so that between two
+    // steps only the barrier and the first fragment reads remain.
+    f32x4 areg[2][A4T];
+    float breg[2][EPT];
+    bool bok[2];
     int a0 = 0;
     // next step to load: tap (r, s), channel-block byte offset
     int r, s, cboff;
@@ -480,14 +486,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         cboff = cb * KC * p.plane_bytes;
     }
 
-    // The next step's loads are cut into slots that the main loop drops between
-    // consecutive matrix instructions, so their issue cost hides behind the
-    // 64-cycle MFMAs of the current step.
-    auto slot_tap = [&]() {          // padding test and column address of tap (r, s)
+    auto slot_tap = [&](int set) {   // padding test and column address of tap (r, s)
         const int dr = p.sign * r, ds = p.sign * s;
         const int hh = hb + dr, ww = wb + ds;
-        bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
-        a0 = bok ? base + cboff + 4 * (dr * p.LW + ds) : 0;
+        bok[set] = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+        a0 = bok[set] ? base + cboff + 4 * (dr * p.LW + ds) : 0;
         s += 1;
         const bool ws = s == p.S;
         s = ws ? 0 : s;
@@ -496,36 +499,38 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         r = wr ? 0 : r;
         cboff += wr ? KC * p.plane_bytes : 0;
     };
-    auto slot_a = [&](int i) {       // filter slice: contiguous block
-        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
+    auto slot_a = [&](int set, int i) {       // filter slice: contiguous block
+        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[set][i] = a_ptr[i * kThreads];
         if (i == A4T - 1) a_ptr += a_step;
     };
-    auto slot_b = [&](int e) {       // one channel of the gathered column
-        breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
+    auto slot_b = [&](int set, int e) {       // one channel of the gathered column
+        breg[set][e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
     };
-    auto load_step = [&]() {
-        slot_tap();
+    auto load_step = [&](int set) {
+        slot_tap(set);
 #pragma unroll
-        for (int i = 0; i < A4T; ++i) slot_a(i);
+        for (int i = 0; i < A4T; ++i) slot_a(set, i);
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) slot_b(e);
+        for (int e = 0; e < EPT; ++e) slot_b(set, e);
     };
-
-    auto store_step = [&](int buf) {
-        float *As = As0 + buf * BM * PITCH, *Bs = Bs0 + buf * BN * PITCH;
+    auto store_a = [&](int set, int i) {      // one 16-byte piece of the filter slice into LDS buffer `set`
+        float *As = As0 + set * BM * PITCH;
+        const int q = tid + i * kThreads;
+        if (A4 % kThreads == 0 || q < A4)
+            *reinterpret_cast<f32x4 *>(&As[(q / (KC / 4)) * PITCH + (q % (KC / 4)) * 4]) = areg[set][i];
+    };
+    auto store_b = [&](int set, int g) {      // four gathered channels into LDS buffer `set`, zeros for a padding tap
+        float *brow = Bs0 + set * BN * PITCH + jc * PITCH + grp * EPT;
+        const int e = 4 * g;
+        f32x4 v = {bok[set] ? breg[set][e] : 0.f, bok[set] ? breg[set][e + 1] : 0.f,
+                   bok[set] ? breg[set][e + 2] : 0.f, bok[set] ? breg[set][e + 3] : 0.f};
+        *reinterpret_cast<f32x4 *>(brow + e) = v;
+    };
+    auto store_step = [&](int set) {
 #pragma unroll
-        for (int i = 0; i < A4T; ++i) {
-            int q = tid + i * kThreads;
-            if (A4 % kThreads == 0 || q < A4)
-                *reinterpret_cast<f32x4 *>(&As[(q / (KC / 4)) * PITCH + (q % (KC / 4)) * 4]) = areg[i];
-        }
-        float *brow = &Bs[jc * PITCH + grp * EPT];
+        for (int i = 0; i < A4T; ++i) store_a(set, i);
 #pragma unroll
-        for (int e = 0; e < EPT; e += 4) {
-            f32x4 v = {bok ? breg[e] : 0.f, bok ? breg[e + 1] : 0.f, bok ? breg[e + 2] : 0.f,
-                       bok ? breg[e + 3] : 0.f};
-            *reinterpret_cast<f32x4 *>(brow + e) = v;
-        }
+        for (int g = 0; g < EPT / 4; ++g) store_b(set, g);
     };
 
     f32x16 acc[TM][TN];
@@ -540,26 +545,27 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
     const int a_frag = (wm * TM * 32 + l32) * PITCH + half * HALFK;
     const int b_frag = (wn * TN * 32 + l32) * PITCH + half * HALFK;
     constexpr int NMMA = HALFK * TM * TN;
-    constexpr int NSLOT = 1 + A4T + EPT;                        // tap, filter slice, EPT channels
-    constexpr int SPM = (NSLOT + NMMA - 5) / (NMMA - 4);        // slots issued after each matrix instruction
+    constexpr int NLOAD = 1 + A4T + EPT;                        // load slots: tap, filter slice, EPT channels
+    constexpr int NSTORE = A4T + EPT / 4;                       // store slots
+    constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);   // slots after each matrix instruction
 
 #ifdef CONVNET_PHASE_PROBE
-    long long pr_t0 = __builtin_readcyclecounter(), pr_b = 0, pr_c = 0, pr_d = 0;
-    long long pr_rt0 = wall_clock64();
+    const long long pr_t0 = __builtin_readcyclecounter();
+    const long long pr_rt0 = wall_clock64();
 #endif
-    load_step();
+    load_step(0);
     store_step(0);
+    if (nsteps > 1) load_step(1);
     __syncthreads();
 #ifdef CONVNET_PHASE_PROBE
     const long long pr_rt1 = wall_clock64();
 #endif
-    for (int step = 0; step < nsteps; ++step) {
-        const int buf = step & 1;
-        const bool last = step == nsteps - 1;       // uniform; the last step has nothing left to load
-#ifdef CONVNET_PHASE_PROBE
-        long long t0 = __builtin_readcyclecounter();
-#endif
-        const float *As = As0 + buf * BM * PITCH, *Bs = Bs0 + buf * BN * PITCH;
+    // One step out of LDS buffer `par`.  par and mode are compile-time constants: the register sets stay in
+    // registers and the slot stream has no branches, so the waits before the LDS writes count only the loads
+    // issued a step earlier.  mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither.
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
+        const float *As = As0 + par * BM * PITCH, *Bs = Bs0 + par * BN * PITCH;
         f32x4 fa[TM][NF], fb[TN][NF];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -574,43 +580,50 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
             for (int f = 0; f < NF; ++f) fb[jn][f] = q[f];
         }
         __builtin_amdgcn_sched_barrier(0);
-        if (!last) {
 #pragma unroll
-            for (int m = 0; m < NMMA; ++m) {
-                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
-                                                                  acc[i][jn], 0, 0, 0);
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                              acc[i][jn], 0, 0, 0);
+            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
-                    if (q == 0) slot_tap();
-                    else if (q - 1 < A4T) slot_a(q - 1);
-                    else slot_b(q - 1 - A4T);
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
+                    if (q < NLOAD) {
+                        if (mode == 2) {
+                            if (q == 0) slot_tap(par);
+                            else if (q - 1 < A4T) slot_a(par, q - 1);
+                            else slot_b(par, q - 1 - A4T);
+                        }
+                    } else {
+                        const int w = q - NLOAD;
+                        if (w < A4T) store_a(par ^ 1, w);
+                        else store_b(par ^ 1, w - A4T);
+                    }
                 }
-                if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
-            }
-#ifdef CONVNET_PHASE_PROBE
-            long long t2 = __builtin_readcyclecounter();
-            __builtin_amdgcn_sched_barrier(0);
-#endif
-            store_step(buf ^ 1);
-#ifdef CONVNET_PHASE_PROBE
-            __builtin_amdgcn_sched_barrier(0);
-            long long t3 = __builtin_readcyclecounter();
-#endif
-            __syncthreads();
-#ifdef CONVNET_PHASE_PROBE
-            long long t4 = __builtin_readcyclecounter();
-            pr_b += t2 - t0; pr_c += t3 - t2; pr_d += t4 - t3;
-#endif
-        } else {
-#pragma unroll
-            for (int m = 0; m < NMMA; ++m) {
-                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
-                                                                  acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
+    }
+    const int rest = nsteps - step;                 // 1, 2 or 3 steps left, the first in buffer 0
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
     }
 #ifdef CONVNET_PHASE_PROBE
     if (tid == 0 && g_probe) {
@@ -618,7 +631,6 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         o[0] = pr_t0; o[1] = __builtin_readcyclecounter(); o[2] = pr_rt0; o[3] = wall_clock64(); o[5] = pr_rt1;
         o[6] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
         o[7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));
-        (void)pr_b;
     }
 #endif
 
