@@ -1571,11 +1571,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArg
 
     const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
     const char *x_bytes = reinterpret_cast<const char *>(p.x);
-    float areg[RA], breg[RB];
-    int a_lim = 0, abase = 0, bbase = 0, jnext = jbeg + jj;
-    bool bok = false;
+    // Register set t & 1 and LDS buffer t & 1 hold step t; loads run two steps ahead and the LDS writes of the
+    // next step sit between the matrix instructions of the current one (see colgemm_fast_kernel).
+    float areg[2][RA], breg[2][RB];
+    int a_lim[2] = {0, 0}, abase = 0, bbase = 0, jnext = jbeg + jj;
+    bool bok[2] = {false, false};
 
-    auto slot_pos = [&]() {          // where this thread's reduction position sits
+    auto slot_pos = [&](int set) {   // where this thread's reduction position sits
         const bool jok = jnext < jend;
         const int js = jok ? jnext : jbeg;
         const int n = (int)fastdiv((uint32_t)js, p.div_plane);
@@ -1583,30 +1585,36 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArg
         const int pp = (int)fastdiv((uint32_t)pq, p.div_q);
         const int qq = pq - pp * p.Q;
         const int hb = pp * p.stride - p.pad, wb = qq * p.stride - p.pad;
-        a_lim = jok ? a_rows : 0;
+        a_lim[set] = jok ? a_rows : 0;
         abase = 4 * (n * p.dy_bs + pq);
-        bok = jok & col_ok & ((unsigned)(hb + tap_r) < (unsigned)p.H) & ((unsigned)(wb + tap_s) < (unsigned)p.W);
-        bbase = bok ? 4 * (n * p.x_bs + hb * p.W + wb) + b_off : 0;
+        bok[set] = jok & col_ok & ((unsigned)(hb + tap_r) < (unsigned)p.H) & ((unsigned)(wb + tap_s) < (unsigned)p.W);
+        bbase = bok[set] ? 4 * (n * p.x_bs + hb * p.W + wb) + b_off : 0;
         jnext += kChunk;
     };
-    auto slot_a = [&](int i) {
-        areg[i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(abase + a_off[i]));
+    auto slot_a = [&](int set, int i) {
+        areg[set][i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(abase + a_off[i]));
     };
-    auto slot_b = [&](int i) {
-        breg[i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(bbase + i * p.x_plane_bytes));
+    auto slot_b = [&](int set, int i) {
+        breg[set][i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(bbase + i * p.x_plane_bytes));
     };
-    auto load_step = [&]() {
-        slot_pos();
+    auto load_step = [&](int set) {
+        slot_pos(set);
 #pragma unroll
-        for (int i = 0; i < RA; ++i) slot_a(i);
+        for (int i = 0; i < RA; ++i) slot_a(set, i);
 #pragma unroll
-        for (int i = 0; i < RB; ++i) slot_b(i);
+        for (int i = 0; i < RB; ++i) slot_b(set, i);
     };
-    auto store_step = [&](int buf) {
+    auto store_a = [&](int set, int i) {
+        As[set][(g * RA + i) * kPitch + jj] = i < a_lim[set] ? areg[set][i] : 0.f;
+    };
+    auto store_b = [&](int set, int i) {
+        Bs[set][(g * RB + i) * kPitch + jj] = bok[set] ? breg[set][i] : 0.f;
+    };
+    auto store_step = [&](int set) {
 #pragma unroll
-        for (int i = 0; i < RA; ++i) As[buf][(g * RA + i) * kPitch + jj] = i < a_lim ? areg[i] : 0.f;
+        for (int i = 0; i < RA; ++i) store_a(set, i);
 #pragma unroll
-        for (int i = 0; i < RB; ++i) Bs[buf][(g * RB + i) * kPitch + jj] = bok ? breg[i] : 0.f;
+        for (int i = 0; i < RB; ++i) store_b(set, i);
     };
 
     f32x16 acc[TM][TN];
@@ -1621,25 +1629,27 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArg
     const int a_frag = (wm * TM * 32 + l32) * kPitch + half * 8;
     const int b_frag = (wn * TN * 32 + l32) * kPitch + half * 8;
     constexpr int NMMA = 8 * TM * TN;
-    constexpr int NSLOT = 1 + RA + RB;
-    constexpr int SPM = (NSLOT + NMMA - 5) / (NMMA - 4);
+    constexpr int NLOAD = 1 + RA + RB, NSTORE = RA + RB;
+    constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);
 
     if (nsteps > 0) {
-        load_step();
+        load_step(0);
         store_step(0);
+        if (nsteps > 1) load_step(1);
     }
     __syncthreads();
-    for (int step = 0; step < nsteps - 1; ++step) {
-        const int buf = step & 1;
+    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
         f32x4 fa[TM][2], fb[TN][2];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[buf][a_frag + i * 32 * kPitch]);
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[par][a_frag + i * 32 * kPitch]);
             fa[i][0] = q[0]; fa[i][1] = q[1];
         }
 #pragma unroll
         for (int jn = 0; jn < TN; ++jn) {
-            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[buf][b_frag + jn * 32 * kPitch]);
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[par][b_frag + jn * 32 * kPitch]);
             fb[jn][0] = q[0]; fb[jn][1] = q[1];
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -1648,20 +1658,46 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArg
             const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
             acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
                                                               acc[i][jn], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
-                if (q == 0) slot_pos();
-                else if (q - 1 < RA) slot_a(q - 1);
-                else slot_b(q - 1 - RA);
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
+                    if (q < NLOAD) {
+                        if (mode == 2) {
+                            if (q == 0) slot_pos(par);
+                            else if (q - 1 < RA) slot_a(par, q - 1);
+                            else slot_b(par, q - 1 - RA);
+                        }
+                    } else {
+                        const int w = q - NLOAD;
+                        if (w < RA) store_a(par ^ 1, w);
+                        else store_b(par ^ 1, w - RA);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
         }
-        store_step(buf ^ 1);
-        __syncthreads();
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
     }
-    if (nsteps > 0)
-        mma_step<TM, TN>(As[(nsteps - 1) & 1], Bs[(nsteps - 1) & 1], wm * TM * 32, wn * TN * 32, lane, acc);
+    const int rest = nsteps - step;                 // up to 3 steps left, the first in buffer 0
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
+    }
 
     float *out = p.part + (size_t)split * p.K * p.ncols;
 #pragma unroll
