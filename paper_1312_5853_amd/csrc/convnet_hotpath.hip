@@ -714,9 +714,10 @@ __global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmF
     const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
     const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * KC) + tid + step_begin * a_step;
 
-    f32x4 areg = {0.f, 0.f, 0.f, 0.f};
-    float breg[EPT];
-    bool bok;
+    // register set t & 1 and LDS buffer t & 1 hold step t (two-set pipeline of colgemm_fast_kernel)
+    f32x4 areg[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+    float breg[2][EPT];
+    bool bok[2];
     int a0 = 0;
     int r, s, cboff;
     {
@@ -726,11 +727,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmF
         s = rs - r * p.S;
         cboff = cb * KC * p.plane_bytes;
     }
-    auto slot_tap = [&]() {
+    auto slot_tap = [&](int set) {
         const int dr = p.sign * r, ds = p.sign * s;
         const int hh = hb + dr, ww = wb + ds;
-        bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
-        a0 = bok ? base + cboff + 4 * (dr * p.LW + ds) : 0;
+        bok[set] = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+        a0 = bok[set] ? base + cboff + 4 * (dr * p.LW + ds) : 0;
         s += 1;
         const bool ws = s == p.S;
         s = ws ? 0 : s;
@@ -739,29 +740,34 @@ __global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmF
         r = wr ? 0 : r;
         cboff += wr ? KC * p.plane_bytes : 0;
     };
-    auto slot_a = [&]() {
-        if (tid < A4) areg = a_ptr[0];
+    auto slot_a = [&](int set) {
+        if (tid < A4) areg[set] = a_ptr[0];
         a_ptr += a_step;
     };
-    auto slot_b = [&](int e) {
-        breg[e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
+    auto slot_b = [&](int set, int e) {
+        breg[set][e] = *reinterpret_cast<const float *>(src_bytes + (uint32_t)(a0 + e * p.plane_bytes));
     };
-    auto load_step = [&]() {
-        slot_tap();
-        slot_a();
+    auto load_step = [&](int set) {
+        slot_tap(set);
+        slot_a(set);
 #pragma unroll
-        for (int e = 0; e < EPT; ++e) slot_b(e);
+        for (int e = 0; e < EPT; ++e) slot_b(set, e);
     };
-    auto store_step = [&](int buf) {
-        float *As = As0 + buf * BM * PITCH, *Bs = Bs0 + buf * BN * PITCH;
-        if (tid < A4) *reinterpret_cast<f32x4 *>(&As[(tid >> 2) * PITCH + (tid & 3) * 4]) = areg;
-        float *brow = &Bs[jc * PITCH];
+    auto store_a = [&](int set) {
+        float *As = As0 + set * BM * PITCH;
+        if (tid < A4) *reinterpret_cast<f32x4 *>(&As[(tid >> 2) * PITCH + (tid & 3) * 4]) = areg[set];
+    };
+    auto store_b = [&](int set, int g) {
+        float *brow = Bs0 + set * BN * PITCH + jc * PITCH;
+        const int e = 4 * g;
+        f32x4 v = {bok[set] ? breg[set][e] : 0.f, bok[set] ? breg[set][e + 1] : 0.f,
+                   bok[set] ? breg[set][e + 2] : 0.f, bok[set] ? breg[set][e + 3] : 0.f};
+        *reinterpret_cast<f32x4 *>(brow + e) = v;
+    };
+    auto store_step = [&](int set) {
+        store_a(set);
 #pragma unroll
-        for (int e = 0; e < EPT; e += 4) {
-            f32x4 v = {bok ? breg[e] : 0.f, bok ? breg[e + 1] : 0.f, bok ? breg[e + 2] : 0.f,
-                       bok ? breg[e + 3] : 0.f};
-            *reinterpret_cast<f32x4 *>(brow + e) = v;
-        }
+        for (int g = 0; g < EPT / 4; ++g) store_b(set, g);
     };
 
     f32x4 acc[TM][TN];
@@ -774,41 +780,61 @@ __global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmF
     const int a_frag = l16 * PITCH + kq * 4;
     const int b_frag = (wn * TN * 16 + l16) * PITCH + kq * 4;
     constexpr int NMMA = 4 * TM * TN;
-    constexpr int NSLOT = 2 + EPT;
+    constexpr int NLOAD = 2 + EPT, NSTORE = 1 + EPT / 4;
 
-    load_step();
+    load_step(0);
     store_step(0);
+    if (nsteps > 1) load_step(1);
     __syncthreads();
-    for (int step = 0; step < nsteps; ++step) {
-        const int buf = step & 1;
-        const bool last = step == nsteps - 1;
-        const float *As = As0 + buf * BM * PITCH, *Bs = Bs0 + buf * BN * PITCH;
+    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
+        const float *As = As0 + par * BM * PITCH, *Bs = Bs0 + par * BN * PITCH;
         f32x4 fa[TM], fb[TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const f32x4 *>(&As[a_frag + i * 16 * PITCH]);
 #pragma unroll
         for (int jn = 0; jn < TN; ++jn) fb[jn] = *reinterpret_cast<const f32x4 *>(&Bs[b_frag + jn * 16 * PITCH]);
         __builtin_amdgcn_sched_barrier(0);
-        if (!last) {
 #pragma unroll
-            for (int m = 0; m < NMMA; ++m) {
-                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-                acc[i][jn] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[i][t], fb[jn][t], acc[i][jn], 0, 0, 0);
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[i][t], fb[jn][t], acc[i][jn], 0, 0, 0);
+            if (mode > 0 && m < NLOAD + NSTORE) {
                 __builtin_amdgcn_sched_barrier(0);
-                if (m == 0) slot_tap();
-                else if (m == 1) slot_a();
-                else if (m < NSLOT) slot_b(m - 2);
-                if (m < NSLOT) __builtin_amdgcn_sched_barrier(0);
-            }
-            store_step(buf ^ 1);
-            __syncthreads();
-        } else {
-#pragma unroll
-            for (int m = 0; m < NMMA; ++m) {
-                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-                acc[i][jn] = __builtin_amdgcn_mfma_f32_16x16x4f32(fa[i][t], fb[jn][t], acc[i][jn], 0, 0, 0);
+                if (m < NLOAD) {
+                    if (mode == 2) {
+                        if (m == 0) slot_tap(par);
+                        else if (m == 1) slot_a(par);
+                        else slot_b(par, m - 2);
+                    }
+                } else {
+                    if (m == NLOAD) store_a(par ^ 1);
+                    else store_b(par ^ 1, m - NLOAD - 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
+    }
+    const int rest = nsteps - step;
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
     }
 
     const int plane = p.OH * p.OW;
@@ -846,7 +872,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <int TM, int TN, int WM, int WN, int KC>
-__global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFastArgs p)
+__global__ __launch_bounds__(kThreads, 2) void colgemm_bf16_kernel(const ColGemmFastArgs p)
 {
     constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
     constexpr int PITCHB = KC * 2 + 16;      // bytes per LDS row
@@ -905,9 +931,10 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
     const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
     const u32x4 *a_ptr = reinterpret_cast<const u32x4 *>(p.At) + (size_t)m0 * (KC / 8) + tid + step_begin * a_step;
 
-    u32x4 areg[A4T];
-    u32x4 breg[NV];
-    bool bok;
+    // register set t & 1 and LDS buffer t & 1 hold step t (two-set pipeline of colgemm_fast_kernel)
+    u32x4 areg[2][A4T];
+    u32x4 breg[2][NV];
+    bool bok[2];
     int a0 = 0;
     int r, s, cboff;
     {
@@ -918,11 +945,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
         cboff = cb * (KC / 16) * p.plane_bytes;
     }
 
-    auto slot_tap = [&]() {
+    auto slot_tap = [&](int set) {
         const int dr = p.sign * r, ds = p.sign * s;
         const int hh = hb + dr, ww = wb + ds;
-        bok = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
-        a0 = bok ? base + cboff + 32 * (dr * p.LW + ds) : 0;
+        bok[set] = ((unsigned)hh < (unsigned)p.LH) & ((unsigned)ww < (unsigned)p.LW);
+        a0 = bok[set] ? base + cboff + 32 * (dr * p.LW + ds) : 0;
         s += 1;
         const bool ws = s == p.S;
         s = ws ? 0 : s;
@@ -931,36 +958,38 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
         r = wr ? 0 : r;
         cboff += wr ? (KC / 16) * p.plane_bytes : 0;
     };
-    auto slot_a = [&](int i) {
-        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
+    auto slot_a = [&](int set, int i) {
+        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[set][i] = a_ptr[i * kThreads];
         if (i == A4T - 1) a_ptr += a_step;
     };
-    auto slot_b = [&](int v) {
-        breg[v] = *reinterpret_cast<const u32x4 *>(src_bytes + (uint32_t)(a0 + voff[v]));
+    auto slot_b = [&](int set, int v) {
+        breg[set][v] = *reinterpret_cast<const u32x4 *>(src_bytes + (uint32_t)(a0 + voff[v]));
     };
-    auto load_step = [&]() {
-        slot_tap();
+    auto load_step = [&](int set) {
+        slot_tap(set);
 #pragma unroll
-        for (int i = 0; i < A4T; ++i) slot_a(i);
+        for (int i = 0; i < A4T; ++i) slot_a(set, i);
 #pragma unroll
-        for (int v = 0; v < NV; ++v) slot_b(v);
+        for (int v = 0; v < NV; ++v) slot_b(set, v);
     };
-    auto store_step = [&](int buf) {
-        char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+    auto store_a = [&](int set, int i) {
+        char *As = As0 + set * BM * PITCHB;
+        const int q = tid + i * kThreads;
+        if (A4 % kThreads == 0 || q < A4)
+            *reinterpret_cast<u32x4 *>(As + (q / (KC / 8)) * PITCHB + (q % (KC / 8)) * 16) = areg[set][i];
+    };
+    auto store_b = [&](int set, int v) {
+        char *brow = Bs0 + set * BN * PITCHB + jc * PITCHB + grp * EPT * 2;
+        u32x4 q;
 #pragma unroll
-        for (int i = 0; i < A4T; ++i) {
-            int q = tid + i * kThreads;
-            if (A4 % kThreads == 0 || q < A4)
-                *reinterpret_cast<u32x4 *>(As + (q / (KC / 8)) * PITCHB + (q % (KC / 8)) * 16) = areg[i];
-        }
-        char *brow = Bs + jc * PITCHB + grp * EPT * 2;
+        for (int k = 0; k < 4; ++k) q[k] = bok[set] ? breg[set][v][k] : 0u;
+        *reinterpret_cast<u32x4 *>(brow + v * 16) = q;
+    };
+    auto store_step = [&](int set) {
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            u32x4 q;
+        for (int i = 0; i < A4T; ++i) store_a(set, i);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) q[k] = bok ? breg[v][k] : 0u;
-            *reinterpret_cast<u32x4 *>(brow + v * 16) = q;
-        }
+        for (int v = 0; v < NV; ++v) store_b(set, v);
     };
 
     f32x16 acc[TM][TN];
@@ -975,16 +1004,17 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
     const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
     const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
     constexpr int NMMA = NK * TM * TN;
-    constexpr int NSLOT = 1 + A4T + NV;
-    constexpr int SPM = (NSLOT + (NMMA > 2 ? NMMA - 2 : 1) - 1) / (NMMA > 2 ? NMMA - 2 : 1);
+    constexpr int NLOAD = 1 + A4T + NV, NSTORE = A4T + NV;
+    constexpr int SPM = (NLOAD + NSTORE + (NMMA > 2 ? NMMA - 2 : 1) - 1) / (NMMA > 2 ? NMMA - 2 : 1);
 
-    load_step();
+    load_step(0);
     store_step(0);
+    if (nsteps > 1) load_step(1);
     __syncthreads();
-    for (int step = 0; step < nsteps; ++step) {
-        const int buf = step & 1;
-        const bool last = step == nsteps - 1;
-        const char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
+        const char *As = As0 + par * BM * PITCHB, *Bs = Bs0 + par * BN * PITCHB;
         u32x4 fa[TM][NK], fb[TN][NK];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -997,33 +1027,51 @@ __global__ __launch_bounds__(kThreads) void colgemm_bf16_kernel(const ColGemmFas
             for (int t = 0; t < NK; ++t)
                 fb[jn][t] = *reinterpret_cast<const u32x4 *>(Bs + b_frag + jn * 32 * PITCHB + t * 32);
         __builtin_amdgcn_sched_barrier(0);
-        if (!last) {
 #pragma unroll
-            for (int m = 0; m < NMMA; ++m) {
-                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
-                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
-                                                                     acc[i][jn], 0, 0, 0);
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                 __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                 acc[i][jn], 0, 0, 0);
+            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
-                    if (q == 0) slot_tap();
-                    else if (q - 1 < A4T) slot_a(q - 1);
-                    else slot_b(q - 1 - A4T);
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
+                    if (q < NLOAD) {
+                        if (mode == 2) {
+                            if (q == 0) slot_tap(par);
+                            else if (q - 1 < A4T) slot_a(par, q - 1);
+                            else slot_b(par, q - 1 - A4T);
+                        }
+                    } else {
+                        const int w = q - NLOAD;
+                        if (w < A4T) store_a(par ^ 1, w);
+                        else store_b(par ^ 1, w - A4T);
+                    }
                 }
-                if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
-            }
-            store_step(buf ^ 1);
-            __syncthreads();
-        } else {
-#pragma unroll
-            for (int m = 0; m < NMMA; ++m) {
-                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
-                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
-                                                                     acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
+    }
+    const int rest = nsteps - step;
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
     }
 
     const int plane = p.OH * p.OW;
@@ -1952,7 +2000,7 @@ struct WgradLinArgs {
 typedef u32x4 u32x4_align2 __attribute__((aligned(2)));
 
 template <int TM, int TN, int WM, int WN>
-__global__ __launch_bounds__(kThreads) void wgrad_bf16_lin_kernel(const WgradLinArgs p)
+__global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const WgradLinArgs p)
 {
     constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
     constexpr int KJ = 64, NK = KJ / 16;
@@ -2003,7 +2051,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_lin_kernel(const WgradLin
     uint32_t aoff = (uint32_t)(step_begin * 8 + jg) * 16u, boff = 0;
     const char *ap = reinterpret_cast<const char *>(p.dyp), *xp = reinterpret_cast<const char *>(p.xp);
 
-    u32x4 areg[RA], breg[RB];
+    // register set t & 1 and LDS buffer t & 1 hold step t (two-set pipeline of colgemm_fast_kernel)
+    u32x4 areg[2][RA], breg[2][RB];
     auto slot_pos = [&]() {
         boff = 2u * (uint32_t)(min(n, p.N - 1) * p.Jx + gg * 8);
         gg += 8;
@@ -2011,25 +2060,31 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_lin_kernel(const WgradLin
         gg -= wrap ? p.G : 0;
         n += wrap ? 1 : 0;
     };
-    auto slot_a = [&](int i) {
-        areg[i] = *reinterpret_cast<const u32x4 *>(ap + (abase[i] + aoff));
+    auto slot_a = [&](int set, int i) {
+        areg[set][i] = *reinterpret_cast<const u32x4 *>(ap + (abase[i] + aoff));
         if (i == RA - 1) aoff += 128u;
     };
-    auto slot_b = [&](int i) { breg[i] = *reinterpret_cast<const u32x4_align2 *>(xp + (bbase[i] + boff)); };
-    auto load_step = [&]() {
+    auto slot_b = [&](int set, int i) {
+        breg[set][i] = *reinterpret_cast<const u32x4_align2 *>(xp + (bbase[i] + boff));
+    };
+    auto load_step = [&](int set) {
         slot_pos();
 #pragma unroll
-        for (int i = 0; i < RA; ++i) slot_a(i);
+        for (int i = 0; i < RA; ++i) slot_a(set, i);
 #pragma unroll
-        for (int i = 0; i < RB; ++i) slot_b(i);
+        for (int i = 0; i < RB; ++i) slot_b(set, i);
     };
-    auto store_step = [&](int buf) {
-        char *As = As0 + buf * BM * PITCHB + r8 * PITCHB + jg * 16;
-        char *Bs = Bs0 + buf * BN * PITCHB + r8 * PITCHB + jg * 16;
+    auto store_a = [&](int set, int i) {
+        *reinterpret_cast<u32x4 *>(As0 + set * BM * PITCHB + (r8 + i * 32) * PITCHB + jg * 16) = areg[set][i];
+    };
+    auto store_b = [&](int set, int i) {
+        *reinterpret_cast<u32x4 *>(Bs0 + set * BN * PITCHB + (r8 + i * 32) * PITCHB + jg * 16) = breg[set][i];
+    };
+    auto store_step = [&](int set) {
 #pragma unroll
-        for (int i = 0; i < RA; ++i) *reinterpret_cast<u32x4 *>(As + i * 32 * PITCHB) = areg[i];
+        for (int i = 0; i < RA; ++i) store_a(set, i);
 #pragma unroll
-        for (int i = 0; i < RB; ++i) *reinterpret_cast<u32x4 *>(Bs + i * 32 * PITCHB) = breg[i];
+        for (int i = 0; i < RB; ++i) store_b(set, i);
     };
 
     f32x16 acc[TM][TN];
@@ -2044,18 +2099,19 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_lin_kernel(const WgradLin
     const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
     const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
     constexpr int NMMA = NK * TM * TN;
-    constexpr int NSLOT = 1 + RA + RB;
-    constexpr int SPM = (NSLOT + NMMA - 3) / (NMMA - 2);
+    constexpr int NLOAD = 1 + RA + RB, NSTORE = RA + RB;
+    constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);
 
     if (nsteps > 0) {
-        load_step();
+        load_step(0);
         store_step(0);
+        if (nsteps > 1) load_step(1);
     }
     __syncthreads();
-    for (int step = 0; step < nsteps; ++step) {
-        const int buf = step & 1;
-        const bool last = step == nsteps - 1;
-        const char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
+        const char *As = As0 + par * BM * PITCHB, *Bs = Bs0 + par * BN * PITCHB;
         u32x4 fa[TM][NK], fb[TN][NK];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -2068,33 +2124,51 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_lin_kernel(const WgradLin
             for (int t = 0; t < NK; ++t)
                 fb[jn][t] = *reinterpret_cast<const u32x4 *>(Bs + b_frag + jn * 32 * PITCHB + t * 32);
         __builtin_amdgcn_sched_barrier(0);
-        if (!last) {
 #pragma unroll
-            for (int m = 0; m < NMMA; ++m) {
-                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
-                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
-                                                                     acc[i][jn], 0, 0, 0);
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                 __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                 acc[i][jn], 0, 0, 0);
+            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
-                    if (q == 0) slot_pos();
-                    else if (q - 1 < RA) slot_a(q - 1);
-                    else slot_b(q - 1 - RA);
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
+                    if (q < NLOAD) {
+                        if (mode == 2) {
+                            if (q == 0) slot_pos();
+                            else if (q - 1 < RA) slot_a(par, q - 1);
+                            else slot_b(par, q - 1 - RA);
+                        }
+                    } else {
+                        const int w = q - NLOAD;
+                        if (w < RA) store_a(par ^ 1, w);
+                        else store_b(par ^ 1, w - RA);
+                    }
                 }
-                if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
-            }
-            store_step(buf ^ 1);
-            __syncthreads();
-        } else {
-#pragma unroll
-            for (int m = 0; m < NMMA; ++m) {
-                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
-                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
-                                                                     acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
+    }
+    const int rest = nsteps - step;
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
     }
 
     float *out = p.part + (size_t)split * p.K * p.ncols;
