@@ -1291,20 +1291,19 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
         colbase = (pp - p0) * p.stride * p.WP + qq * p.stride;
     }
 
-    f32x4 areg[A4T];
+    // filter slices: register set t & 1 and LDS buffer t & 1 hold step t; loads run two steps ahead and the LDS
+    // writes of the next step sit between the matrix instructions (see colgemm_fast_kernel)
+    f32x4 areg[2][A4T];
     const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * kChunk) + tid;
     const size_t a_step = (size_t)p.Mpad * (kChunk / 4);
-    auto slot_a = [&](int i) {
-        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[i] = a_ptr[i * kThreads];
+    auto slot_a = [&](int set, int i) {
+        if (A4 % kThreads == 0 || tid + i * kThreads < A4) areg[set][i] = a_ptr[i * kThreads];
         if (i == A4T - 1) a_ptr += a_step;
     };
-    auto store_a = [&](int buf) {
-        float *As = As0 + buf * BM * kPitch;
-#pragma unroll
-        for (int i = 0; i < A4T; ++i) {
-            int q = tid + i * kThreads;
-            if (A4 % kThreads == 0 || q < A4) *reinterpret_cast<f32x4 *>(&As[(q >> 2) * kPitch + (q & 3) * 4]) = areg[i];
-        }
+    auto store_a = [&](int set, int i) {
+        float *As = As0 + set * BM * kPitch;
+        const int q = tid + i * kThreads;
+        if (A4 % kThreads == 0 || q < A4) *reinterpret_cast<f32x4 *>(&As[(q >> 2) * kPitch + (q & 3) * 4]) = areg[set][i];
     };
 
     f32x16 acc[TM];
@@ -1314,8 +1313,13 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
 #pragma unroll
-    for (int i = 0; i < A4T; ++i) slot_a(i);
-    store_a(0);
+    for (int i = 0; i < A4T; ++i) slot_a(0, i);
+#pragma unroll
+    for (int i = 0; i < A4T; ++i) store_a(0, i);
+    if (p.nchunks > 1) {
+#pragma unroll
+        for (int i = 0; i < A4T; ++i) slot_a(1, i);
+    }
     __syncthreads();
     const int a_frag = l32 * kPitch + half * 8;
     // The im2col values do not depend on the filter staging, so those of step+1 are
@@ -1330,10 +1334,10 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
         bv[6] = patch[colbase + k1.z]; bv[7] = patch[colbase + k1.w];
     };
     read_b(0);
-    for (int step = 0; step < p.nchunks; ++step) {
-        const int buf = step & 1;
-        const bool last = step == p.nchunks - 1;
-        const float *As = As0 + buf * BM * kPitch;
+    // mode 2: filter loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c, int step) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
+        const float *As = As0 + par * BM * kPitch;
         f32x4 fa[TM][2];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
@@ -1349,15 +1353,35 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
 #pragma unroll
             for (int i = 0; i < TM; ++i)
                 acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], bc[t], acc[i], 0, 0, 0);
-            if (!last && (t < A4T || t == 3)) {
+            if (mode > 0) {
                 __builtin_amdgcn_sched_barrier(0);
-                if (t < A4T) slot_a(t);
+                if (mode == 2 && t < A4T) slot_a(par, t);
                 if (t == 3) read_b(step + 1);
+                if (t >= 4 && t - 4 < A4T) store_a(par ^ 1, t - 4);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (!last) store_a(buf ^ 1);
-        __syncthreads();
+        if (mode > 0) __syncthreads();
+    };
+    static_assert(A4T <= 4, "filter slots fit the eight reduction pairs of a step");
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < p.nchunks; step += 2) {
+        do_step(P0{}, M2{}, step);
+        do_step(P1{}, M2{}, step + 1);
+    }
+    const int rest = p.nchunks - step;
+    if (rest == 3) {
+        do_step(P0{}, M2{}, step);
+        do_step(P1{}, P1{}, step + 1);
+        do_step(P0{}, P0{}, step + 2);
+    } else if (rest == 2) {
+        do_step(P0{}, P1{}, step);
+        do_step(P1{}, P0{}, step + 1);
+    } else if (rest == 1) {
+        do_step(P0{}, P0{}, step);
     }
 
     if (!jok) return;
@@ -1426,8 +1450,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
     if (jend > p.J) jend = p.J;
     const int nsteps = (jend - jbeg + kChunk - 1) / kChunk;
 
-    float areg[RA], breg[RB];
-    bool aok[RA], bok[RB];
+    // register set t & 1 and LDS buffer t & 1 hold step t; loads run two steps ahead and the LDS writes of the
+    // next step sit between the matrix instructions of the current one (see colgemm_fast_kernel)
+    float areg[2][RA], breg[2][RB];
+    bool aok[2][RA], bok[2][RB];
     const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
     const char *x_bytes = reinterpret_cast<const char *>(p.x);
     int abase = 0, bbase = 0, hb = 0, wb = 0, jnext = jbeg + jj;
@@ -1447,30 +1473,36 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
         hb = jok ? hb0 : kInvalidTap;
         jnext += kChunk;
     };
-    auto slot_a = [&](int i) {
+    auto slot_a = [&](int set, int i) {
         const int k = m0 + g + 16 * i;
         const bool ok = jok & (k < p.K);
-        areg[i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(ok ? abase + 4 * k * PQ : 0));
-        aok[i] = ok;
+        areg[set][i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(ok ? abase + 4 * k * PQ : 0));
+        aok[set][i] = ok;
     };
-    auto slot_b = [&](int i) {
+    auto slot_b = [&](int set, int i) {
         const int hh = hb + bdr[i], ww = wb + bds[i];
         const bool ok = ((unsigned)hh < (unsigned)p.H) & ((unsigned)ww < (unsigned)p.W);
-        breg[i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0));
-        bok[i] = ok;
+        breg[set][i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0));
+        bok[set][i] = ok;
     };
-    auto load_step = [&]() {
+    auto load_step = [&](int set) {
         slot_pos();
 #pragma unroll
-        for (int i = 0; i < RA; ++i) slot_a(i);
+        for (int i = 0; i < RA; ++i) slot_a(set, i);
 #pragma unroll
-        for (int i = 0; i < RB; ++i) slot_b(i);
+        for (int i = 0; i < RB; ++i) slot_b(set, i);
     };
-    auto store_step = [&](int buf) {
+    auto store_a = [&](int set, int i) {
+        As[set][(g + 16 * i) * kPitch + jj] = aok[set][i] ? areg[set][i] : 0.f;
+    };
+    auto store_b = [&](int set, int i) {
+        Bs[set][(g + 16 * i) * kPitch + jj] = bok[set][i] ? breg[set][i] : 0.f;
+    };
+    auto store_step = [&](int set) {
 #pragma unroll
-        for (int i = 0; i < RA; ++i) As[buf][(g + 16 * i) * kPitch + jj] = aok[i] ? areg[i] : 0.f;
+        for (int i = 0; i < RA; ++i) store_a(set, i);
 #pragma unroll
-        for (int i = 0; i < RB; ++i) Bs[buf][(g + 16 * i) * kPitch + jj] = bok[i] ? breg[i] : 0.f;
+        for (int i = 0; i < RB; ++i) store_b(set, i);
     };
 
     f32x16 acc[TM][TN];
@@ -1481,29 +1513,31 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
 
-    const int l32_ = lane & 31, half_ = lane >> 5;
-    const int a_frag = (wm * TM * 32 + l32_) * kPitch + half_ * 8;
-    const int b_frag = (wn * TN * 32 + l32_) * kPitch + half_ * 8;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * kPitch + half * 8;
+    const int b_frag = (wn * TN * 32 + l32) * kPitch + half * 8;
     constexpr int NMMA = 8 * TM * TN;
-    constexpr int NSLOT = 1 + RA + RB;
-    constexpr int SPM = (NSLOT + NMMA - 5) / (NMMA - 4);
+    constexpr int NLOAD = 1 + RA + RB, NSTORE = RA + RB;
+    constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);
 
     if (nsteps > 0) {
-        load_step();
+        load_step(0);
         store_step(0);
+        if (nsteps > 1) load_step(1);
     }
     __syncthreads();
-    for (int step = 0; step < nsteps - 1; ++step) {
-        const int buf = step & 1;
+    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
         f32x4 fa[TM][2], fb[TN][2];
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[buf][a_frag + i * 32 * kPitch]);
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[par][a_frag + i * 32 * kPitch]);
             fa[i][0] = q[0]; fa[i][1] = q[1];
         }
 #pragma unroll
         for (int jn = 0; jn < TN; ++jn) {
-            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[buf][b_frag + jn * 32 * kPitch]);
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[par][b_frag + jn * 32 * kPitch]);
             fb[jn][0] = q[0]; fb[jn][1] = q[1];
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -1512,22 +1546,47 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
             const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
             acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
                                                               acc[i][jn], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
-                if (q == 0) slot_pos();
-                else if (q - 1 < RA) slot_a(q - 1);
-                else slot_b(q - 1 - RA);
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
+                    if (q < NLOAD) {
+                        if (mode == 2) {
+                            if (q == 0) slot_pos();
+                            else if (q - 1 < RA) slot_a(par, q - 1);
+                            else slot_b(par, q - 1 - RA);
+                        }
+                    } else {
+                        const int w = q - NLOAD;
+                        if (w < RA) store_a(par ^ 1, w);
+                        else store_b(par ^ 1, w - RA);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
         }
-        store_step(buf ^ 1);
-        __syncthreads();
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
     }
-    if (nsteps > 0)
-        mma_step<TM, TN>(As[(nsteps - 1) & 1], Bs[(nsteps - 1) & 1], wm * TM * 32, wn * TN * 32, lane, acc);
+    const int rest = nsteps - step;
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
+    }
 
-    const int l32 = lane & 31, half = lane >> 5;
     float *out = p.out + (size_t)split * p.K * p.CRS;
 #pragma unroll
     for (int jn = 0; jn < TN; ++jn) {
