@@ -301,8 +301,8 @@ def test_bf16_channel_slices_of_wider_tensors(c0, c1, k0, k1):
 # ------------------------------- full-size layers, sampled against oracle ---
 FULL = [
     # layer, N, passes, dtypes
-    ("conv1", 128, ("fwd", "wgrad"), ("f32",)),
-    ("conv2", 128, ("fwd", "dgrad", "wgrad"), ("f32",)),
+    ("conv1", 128, ("fwd", "wgrad"), ("f32", "bf16")),
+    ("conv2", 128, ("fwd", "dgrad", "wgrad"), ("f32", "bf16")),
     ("conv3", 256, ("fwd", "dgrad", "wgrad"), ("f32", "bf16")),
     ("conv4", 256, ("fwd", "dgrad", "wgrad"), ("f32", "bf16")),
     ("conv5", 256, ("fwd", "dgrad", "wgrad"), ("f32", "bf16")),
