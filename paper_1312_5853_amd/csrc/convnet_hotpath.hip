@@ -2419,9 +2419,11 @@ __global__ void maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, i
 }
 
 // Backward of the pooling (optionally of ReLU followed by pooling).  A
-// work-group stages a group of whole planes in LDS, finds every window's first
-// maximum once, then each input element adds the gradients of the (at most four)
-// windows that selected it, in row-major window order.  No atomics.
+// work-group stages a group of whole planes in LDS and finds every window's first
+// maximum once.  The gradients are then added into an LDS plane in four phases,
+// one per parity class (i % 2, j % 2) of the windows: windows of one class do not
+// overlap, so a phase needs no atomics, and an element always receives its (at
+// most four) gradients in the same order.
 // With RELU the input x is the pre-activation: the window maximum of relu(x)
 // sits where the maximum of x sits whenever it is positive, and a non-positive
 // maximum passes no gradient, so dx = [x > 0] * (pooled gradient routed by x).
@@ -2429,7 +2431,7 @@ __global__ void maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, i
 // The pass is HBM-bound (read x and dy, write dx once each), so the loop is
 // built to keep loads in flight: a thread holds NR elements of the next group
 // of planes (and its NR/4 gradients) in registers, fetched while the current
-// group is being worked on in LDS; index arithmetic uses multiply-shift division.
+// group is being worked on in LDS.
 // group * H*W <= 256 * NR; windows are fewer than a quarter of the elements.
 // A thread's unit of global access in the tiled pooling backward: one float, or two adjacent bfloat16 as
 // one aligned 32-bit access.  Indices outside [0, limit) do not exist (the pair grid is shifted by
@@ -2471,8 +2473,7 @@ __device__ __forceinline__ void st_group(unsigned short *p, int e, int limit, co
 template <bool RELU, int NR, typename T>
 __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x, const T *__restrict__ dy,
                                                           T *__restrict__ dx, int64_t planes, int H, int W,
-                                                          int PH, int PW, int group, FastDiv dHW, FastDiv dW,
-                                                          FastDiv dPP, FastDiv dPW)
+                                                          int PH, int PW, int group, FastDiv dPP, FastDiv dPW)
 {
     constexpr int NG = NR / 4;
     constexpr int EV = 4 / (int)sizeof(T);          // adjacent elements per access: 1 float or 2 bfloat16
@@ -2481,8 +2482,8 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
     constexpr int KX = NR / EV + (EV > 1), KG = NG / EV + (EV > 1);
     extern __shared__ float pool_lds[];
     const int HW = H * W, PP = PH * PW;
-    float *sx = pool_lds;                                                      // group * HW values
-    float2 *swin = reinterpret_cast<float2 *>(pool_lds + ((group * HW + 1) & ~1));   // {chosen element, gradient}
+    float *sx = pool_lds;                            // group * HW inputs
+    float *sacc = pool_lds + group * HW;             // group * HW routed gradients
     const int tid = threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * group;
     float xr[KX][EV], gr[KG][EV];
@@ -2511,24 +2512,38 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
 #pragma unroll
             for (int u = 0; u < EV; ++u) {
                 const int e = EV * (tid + 256 * k) - xs + u;
-                if (e >= 0 && e < np * HW) sx[e] = xr[k][u];
+                if (e >= 0 && e < np * HW) { sx[e] = xr[k][u]; sacc[e] = 0.f; }
             }
         __syncthreads();
+        // every window's first maximum, once; cls = parity class (i % 2, j % 2) of the window, -1 = no window
+        int best[KG][EV], cls[KG][EV];
+        float g[KG][EV];
 #pragma unroll
         for (int k = 0; k < KG; ++k)
 #pragma unroll
             for (int u = 0; u < EV; ++u) {
                 const int o = EV * (tid + 256 * k) - gs + u;
+                best[k][u] = 0; cls[k][u] = -1; g[k][u] = gr[k][u];
                 if (o >= 0 && o < np * PP) {
                     const int pl = (int)fastdiv((uint32_t)o, dPP), rem = o - pl * PP;
                     const int i = (int)fastdiv((uint32_t)rem, dPW), j = rem - i * PW;
                     float m;
-                    const int best = pool_argmax(sx + pl * HW, W, i, j, m);
-                    swin[o] = make_float2(__int_as_float(best), gr[k][u]);
+                    best[k][u] = pl * HW + pool_argmax(sx + pl * HW, W, i, j, m);
+                    cls[k][u] = (i & 1) * 2 + (j & 1);
                 }
             }
         if (pl0 + stride < planes) fetch(pl0 + stride);
-        __syncthreads();
+        // windows of one parity class are disjoint (stride 2, extent 3), so within a phase every accumulator has at
+        // most one writer; an element receives its up to four gradients in phase order
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+#pragma unroll
+            for (int k = 0; k < KG; ++k)
+#pragma unroll
+                for (int u = 0; u < EV; ++u)
+                    if (cls[k][u] == c) sacc[best[k][u]] += g[k][u];
+            __syncthreads();
+        }
 #pragma unroll
         for (int k = 0; k < KX; ++k) {
             float res[EV];
@@ -2537,21 +2552,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
                 const int e = EV * (tid + 256 * k) - os + u;
                 float sum = 0.f;
                 if (e >= 0 && e < np * HW) {
-                    const int pl = (int)fastdiv((uint32_t)e, dHW), self = e - pl * HW;
-                    const int h = (int)fastdiv((uint32_t)self, dW), w = self - h * W;
-                    // windows over row h: i1 = h/2, and i0 = h/2 - 1 when h is even (same for columns)
-                    const int i1 = h >> 1, i0 = i1 - 1, j1 = w >> 1, j0 = j1 - 1;
-                    const bool vi0 = ((h & 1) == 0) & (i0 >= 0) & (i0 < PH), vi1 = i1 < PH;
-                    const bool vj0 = ((w & 1) == 0) & (j0 >= 0) & (j0 < PW), vj1 = j1 < PW;
-                    const float2 *wp = swin + pl * PP;
-                    auto take = [&](bool ok, int i, int j) {
-                        const float2 c = wp[ok ? i * PW + j : 0];
-                        sum += (ok & (__float_as_int(c.x) == self)) ? c.y : 0.f;
-                    };
-                    take(vi0 & vj0, i0, j0);
-                    take(vi0 & vj1, i0, j1);
-                    take(vi1 & vj0, i1, j0);
-                    take(vi1 & vj1, i1, j1);
+                    sum = sacc[e];
                     if (RELU && !(sx[e] > 0.f)) sum = 0.f;
                 }
                 res[u] = sum;
@@ -3098,14 +3099,18 @@ int pool_bwd_typed(const void *x, const void *dy, void *dx, int64_t planes, int 
         const int group = small ? (256 * 16) / HW : 1;
         int64_t blocks = (planes + group - 1) / group;
         if (blocks > 256 * 6) blocks = 256 * 6;
-        const size_t lds = (size_t)((group * HW + 1) & ~1) * 4 + (size_t)group * PP * 8;
-        const FastDiv dHW = make_fastdiv(HW), dW = make_fastdiv(W), dPP = make_fastdiv(PP), dPW = make_fastdiv(PW);
-        if (small)
+        const size_t lds = (size_t)group * HW * 8;        // inputs + accumulators
+        const FastDiv dPP = make_fastdiv(PP), dPW = make_fastdiv(PW);
+        if (small) {
             hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 16, T>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
-                               planes, H, W, PH, PW, group, dHW, dW, dPP, dPW);
-        else
+                               planes, H, W, PH, PW, group, dPP, dPW);
+        } else {
+            if (lds > 64 * 1024)
+                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(maxpool_bwd_tiled<RELU, 40, T>),
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
             hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 40, T>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
-                               planes, H, W, PH, PW, group, dHW, dW, dPP, dPW);
+                               planes, H, W, PH, PW, group, dPP, dPW);
+        }
     } else {
         const int64_t total = planes * H * W;
         hipLaunchKernelGGL((maxpool_bwd_kernel<RELU, T>), dim3(grid1d(total, 256)), dim3(256), 0, st, xp, gp, op,
