@@ -19,6 +19,9 @@ from .oracle import (  # noqa: F401
     conv_fwd_at,
     conv_bwd_data_at,
     conv_bwd_filter_at,
+    conv_fwd_grouped,
+    conv_bwd_data_grouped,
+    conv_bwd_filter_grouped,
     relu_fwd,
     relu_bwd,
     maxpool3x3s2_fwd,

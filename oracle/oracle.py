@@ -120,6 +120,42 @@ def conv_bwd_filter(x, dy, R, S, stride, pad):
     return dw
 
 
+# Grouped (multi-column) layers: the two-column architecture of the paper's
+# model-parallelism paragraph splits a layer's filters into `groups` columns, and
+# where the columns are not cross-connected the filters of column g read only
+# the input channels of column g.  x [N, C, H, W] with C = groups * Cg, w
+# [K, Cg, R, S] with K = groups * Kg (filters g*Kg .. (g+1)*Kg-1 form column g):
+# every column is an ordinary layer on its channel slice, written out as such.
+def _column(t, g, groups, axis):
+    size = t.shape[axis] // groups
+    sl = [slice(None)] * t.ndim
+    sl[axis] = slice(g * size, (g + 1) * size)
+    return t[tuple(sl)]
+
+
+def _check_groups(C, K, Cw, groups):
+    assert groups >= 1 and C % groups == 0 and K % groups == 0 and Cw == C // groups
+
+
+def conv_fwd_grouped(x, w, stride, pad, groups):
+    _check_groups(x.shape[1], w.shape[0], w.shape[1], groups)
+    return np.concatenate([conv_fwd(_column(x, g, groups, 1), _column(w, g, groups, 0), stride, pad)
+                           for g in range(groups)], axis=1)
+
+
+def conv_bwd_data_grouped(dy, w, H, W, stride, pad, groups):
+    _check_groups(w.shape[1] * groups, w.shape[0], w.shape[1], groups)
+    assert dy.shape[1] == w.shape[0]
+    return np.concatenate([conv_bwd_data(_column(dy, g, groups, 1), _column(w, g, groups, 0), H, W, stride, pad)
+                           for g in range(groups)], axis=1)
+
+
+def conv_bwd_filter_grouped(x, dy, R, S, stride, pad, groups):
+    assert x.shape[1] % groups == 0 and dy.shape[1] % groups == 0
+    return np.concatenate([conv_bwd_filter(_column(x, g, groups, 1), _column(dy, g, groups, 1), R, S, stride, pad)
+                           for g in range(groups)], axis=0)
+
+
 def _idx(idx):
     return np.ascontiguousarray(np.asarray(idx, dtype=np.int64).ravel())
 

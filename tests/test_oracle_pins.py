@@ -395,3 +395,49 @@ def test_oracle_does_not_import_the_product():
             "sys.exit(1 if bad else 0)")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     assert subprocess.run([sys.executable, "-c", code], cwd=root).returncode == 0
+
+
+# ---------------------------------------------------------------- grouped layers ---
+def _block_diagonal(w, groups):
+    """Filters of a grouped layer as filters of an ordinary layer over all channels: zero outside the own column."""
+    K, Cg, R, S = w.shape
+    Kg = K // groups
+    full = np.zeros((K, Cg * groups, R, S), dtype=w.dtype)
+    for g in range(groups):
+        full[g * Kg:(g + 1) * Kg, g * Cg:(g + 1) * Cg] = w[g * Kg:(g + 1) * Kg]
+    return full
+
+
+@pytest.mark.parametrize("groups,st,pad", [(2, 1, 1), (3, 2, 0), (1, 1, 2)])
+def test_grouped_layer_is_the_block_diagonal_layer(groups, st, pad):
+    """A multi-column layer without cross-connections equals the full layer whose filters are zero outside their
+    column -- forward, backward-data, and (restricted to the column blocks) backward-filter.  Small integers: exact."""
+    rng = np.random.default_rng(7)
+    N, Cg, Kg, H, W, R, S = 2, 3, 4, 7, 6, 3, 3
+    x = rng.integers(-3, 4, (N, Cg * groups, H, W)).astype(np.float64)
+    w = rng.integers(-3, 4, (Kg * groups, Cg, R, S)).astype(np.float64)
+    full = _block_diagonal(w, groups)
+    y = oracle.conv_fwd_grouped(x, w, st, pad, groups)
+    assert np.array_equal(y, oracle.conv_fwd(x, full, st, pad))
+    dy = rng.integers(-3, 4, y.shape).astype(np.float64)
+    assert np.array_equal(oracle.conv_bwd_data_grouped(dy, w, H, W, st, pad, groups),
+                          oracle.conv_bwd_data(dy, full, H, W, st, pad))
+    dw_full = oracle.conv_bwd_filter(x, dy, R, S, st, pad)          # [K, C, R, S]: the column blocks are the grouped dw
+    dw = oracle.conv_bwd_filter_grouped(x, dy, R, S, st, pad, groups)
+    for g in range(groups):
+        assert np.array_equal(dw[g * Kg:(g + 1) * Kg], dw_full[g * Kg:(g + 1) * Kg, g * Cg:(g + 1) * Cg])
+
+
+def test_grouped_adjoint_identities():
+    """<conv_g(x, w), g> = <x, dgrad_g(g, w)> = <w, wgrad_g(x, g)> for the grouped layer as well."""
+    rng = np.random.default_rng(8)
+    groups, N, Cg, Kg, H, W, R, S, st, pad = 2, 3, 5, 3, 9, 8, 5, 5, 1, 2
+    x = rng.standard_normal((N, Cg * groups, H, W))
+    w = rng.standard_normal((Kg * groups, Cg, R, S))
+    y = oracle.conv_fwd_grouped(x, w, st, pad, groups)
+    g = rng.standard_normal(y.shape)
+    a = np.sum(y * g)
+    b = np.sum(x * oracle.conv_bwd_data_grouped(g, w, H, W, st, pad, groups))
+    c = np.sum(w * oracle.conv_bwd_filter_grouped(x, g, R, S, st, pad, groups))
+    scale = np.sum(np.abs(y * g))
+    assert abs(a - b) <= 1e-12 * scale and abs(a - c) <= 1e-12 * scale
