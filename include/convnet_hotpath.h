@@ -132,6 +132,32 @@ int conv_bwd_filter_ex(const void *x, const void *dy, void *dw,
                        int dtype, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Grouped (multi-column) layers: the two-column architecture of the
+ * model-parallelism paragraph, where a column's filters read only the
+ * column's own input channels (no cross-connection).  C and K are the TOTAL
+ * channel and filter counts, both multiples of `groups`; column g owns input
+ * channels g*C/groups .. and filters g*K/groups ..:
+ *   x, dx  [N][C][H][W]      w, dw  [K][C/groups][R][S]      y, dy  [N][K][P][Q]
+ * Each column is the corresponding ordinary pass on its channel slice; all
+ * conventions above apply (dense tensors here).  With fp32 tensors and channel
+ * counts per column that are multiples of 16 the columns share one launch;
+ * otherwise they run one after the other on the stream (then every column's
+ * slice must itself start 16-byte aligned: CONV_ERR_MISALIGNED if not).
+ * groups = 1 is the ordinary layer.
+ */
+int conv_fwd_grouped(const void *x, const void *w, void *y,
+                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int groups,
+                     int dtype, void *ws, size_t ws_bytes, void *stream);
+int conv_bwd_data_grouped(const void *dy, const void *w, void *dx,
+                          int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int groups,
+                          int dtype, void *ws, size_t ws_bytes, void *stream);
+int conv_bwd_filter_grouped(const void *x, const void *dy, void *dw,
+                            int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int groups,
+                            int dtype, void *ws, size_t ws_bytes, void *stream);
+size_t conv_workspace_bytes_grouped(int op, int N, int C, int H, int W, int K, int R, int S,
+                                    int stride, int pad, int groups, int dtype);
+
+/*
  * Scratch bytes the given pass needs for these extents (op = CONV_OP_*).
  * Pure host arithmetic; returns 0 for invalid arguments.  The figure depends
  * only on the arguments, never on the device or on earlier calls.

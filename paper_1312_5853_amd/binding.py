@@ -22,6 +22,7 @@ OP_FWD, OP_BWD_DATA, OP_BWD_FILTER = 0, 1, 2
 EXPORTS = (
     "conv_fwd", "conv_bwd_data", "conv_bwd_filter",
     "conv_fwd_ex", "conv_bwd_data_ex", "conv_bwd_filter_ex",
+    "conv_fwd_grouped", "conv_bwd_data_grouped", "conv_bwd_filter_grouped", "conv_workspace_bytes_grouped",
     "conv_workspace_bytes", "conv_status_string", "conv_last_hip_error",
     "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
     "relu_maxpool3x3s2_fwd", "relu_maxpool3x3s2_bwd", "convert_f32_to_bf16",
@@ -58,6 +59,11 @@ def lib():
         f = getattr(L, name + "_ex")
         f.argtypes = [vp, vp, vp] + dims + [i64, i64, i, vp, sz, vp]
         f.restype = i
+        f = getattr(L, name + "_grouped")
+        f.argtypes = [vp, vp, vp] + dims + [i, i, vp, sz, vp]
+        f.restype = i
+    L.conv_workspace_bytes_grouped.argtypes = [i] + dims + [i, i]
+    L.conv_workspace_bytes_grouped.restype = sz
     L.conv_workspace_bytes.argtypes = [i] + dims + [i]
     L.conv_workspace_bytes.restype = sz
     L.conv_status_string.argtypes = [i]
@@ -207,6 +213,55 @@ def conv_bwd_filter(x, dy, R, S, stride, pad, dw=None, ws=None, stream=None):
     dims = (N, C, H, W, K, R, S, stride, pad)
     return _run("conv_bwd_filter", OP_BWD_FILTER, x, dy, dw, dims, _batch_stride(x), _batch_stride(dy),
                 _dtype_of(x), ws, stream)
+
+
+def _run_grouped(name, op, a, b, out, dims, groups, dtype, ws, stream):
+    for t in (a, b, out):
+        if not t.is_contiguous():
+            raise ValueError("grouped calls take dense tensors")
+    need = int(lib().conv_workspace_bytes_grouped(op, *dims, groups, dtype))
+    buf, nbytes = _ws(ws).get(need)
+    wsp = ctypes.c_void_p(buf.data_ptr()) if buf is not None else ctypes.c_void_p(0)
+    rc = getattr(lib(), name)(_ptr(a), _ptr(b), _ptr(out), *dims, groups, dtype, wsp, nbytes, _stream_handle(stream))
+    if rc != OK:
+        raise ConvError(rc, name)
+    return out
+
+
+def conv_fwd_grouped(x, w, stride, pad, groups, y=None, ws=None, stream=None, out_bf16=False):
+    """x [N,C,H,W], w [K,C/groups,R,S] -> y [N,K,P,Q]: column g's filters read column g's channels only."""
+    N, C, H, W = x.shape
+    K, Cg, R, S = w.shape
+    if Cg * groups != C or K % groups:
+        raise ValueError("filter tensor does not match the input and the group count")
+    P, Q = out_extent(H, R, stride, pad), out_extent(W, S, stride, pad)
+    if y is None:
+        y = torch.empty((N, K, P, Q), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=x.device)
+    return _run_grouped("conv_fwd_grouped", OP_FWD, x, w, y, (N, C, H, W, K, R, S, stride, pad), groups,
+                        _io_dtype(x, y), ws, stream)
+
+
+def conv_bwd_data_grouped(dy, w, H, W, stride, pad, groups, dx=None, ws=None, stream=None, out_bf16=False):
+    N = dy.shape[0]
+    K, Cg, R, S = w.shape
+    C = Cg * groups
+    if dy.shape[1] != K or K % groups:
+        raise ValueError("filter tensor does not match the output gradient and the group count")
+    if dx is None:
+        dx = torch.empty((N, C, H, W), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=dy.device)
+    return _run_grouped("conv_bwd_data_grouped", OP_BWD_DATA, dy, w, dx, (N, C, H, W, K, R, S, stride, pad), groups,
+                        _io_dtype(dy, dx), ws, stream)
+
+
+def conv_bwd_filter_grouped(x, dy, R, S, stride, pad, groups, dw=None, ws=None, stream=None):
+    N, C, H, W = x.shape
+    K = dy.shape[1]
+    if C % groups or K % groups:
+        raise ValueError("channel counts are not multiples of the group count")
+    if dw is None:
+        dw = torch.empty((K, C // groups, R, S), dtype=torch.float32, device=x.device)
+    return _run_grouped("conv_bwd_filter_grouped", OP_BWD_FILTER, x, dy, dw, (N, C, H, W, K, R, S, stride, pad),
+                        groups, _dtype_of(x), ws, stream)
 
 
 def _check(rc, where):

@@ -409,6 +409,10 @@ struct ColGemmFastArgs {
     int ksplit, steps_per_split;   // the reduction steps are cut into ksplit ranges (1 = whole)
     float *part;                   // ksplit > 1: partial outputs [ksplit][N][M][OH*OW], summed by reduce_split_outputs
     int out_bf16;                  // bf16 kernel only: dst holds bfloat16 (each sum rounded to nearest even)
+    // columns of a grouped layer in one launch (fp32 kernels): column g reads src + g * src_gs, the filter copy
+    // At + g * at_gs, writes dst + g * dst_gs and the partials part + g * part_gs (all in floats)
+    int groups;
+    int64_t src_gs, dst_gs, at_gs, part_gs;
     FastDiv div_plane, div_ow, div_rs, div_s;
 };
 
@@ -435,9 +439,15 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
     const int idx = bid >> 3;
     const int unit = (bid & 7) * p.tiles_per_xcd + idx;
     const int ntile = p.mtiles * p.ntiles;
-    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit) return;
-    const int ks = unit / ntile;
-    const int tile = unit - ks * ntile;
+    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit * p.groups) return;
+    const int grp_col = unit / (ntile * p.ksplit);              // column of a grouped layer
+    const int unit_c = unit - grp_col * (ntile * p.ksplit);
+    const int ks = unit_c / ntile;
+    const int tile = unit_c - ks * ntile;
+    const float *const At_c = p.At + (size_t)grp_col * p.at_gs;
+    const float *const src_c = p.src + (size_t)grp_col * p.src_gs;
+    float *const dst_c = p.dst + (size_t)grp_col * p.dst_gs;
+    float *const part_c = p.part + (size_t)grp_col * p.part_gs;
     const int mt = tile % p.mtiles, nt = tile / p.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
 
@@ -461,11 +471,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         base = 4 * (n * p.src_bs + hb * p.LW + wb) + grp * EPT * p.plane_bytes;
         if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
     }
-    const char *src_bytes = reinterpret_cast<const char *>(p.src);
+    const char *src_bytes = reinterpret_cast<const char *>(src_c);
     const size_t a_step = (size_t)p.Mpad * (KC / 4);          // f32x4 per step
     const int step_begin = ks * p.steps_per_split;
     const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
-    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * KC) + tid + step_begin * a_step;
+    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(At_c + (size_t)m0 * KC) + tid + step_begin * a_step;
 
     // Data of step t lives in register set t & 1 and LDS buffer t & 1.  While step s is multiplied out of
     // buffer s & 1, the loads of step s + 2 are issued into set s & 1 (free since its contents went to LDS
@@ -641,8 +651,8 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         if (col >= p.ncols) continue;
         const int n = (int)fastdiv((uint32_t)col, p.div_plane);
         const int rem = col - n * plane;
-        float *out = p.ksplit > 1 ? p.part + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
-                                  : p.dst + (size_t)n * p.dst_bs + rem;
+        float *out = p.ksplit > 1 ? part_c + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
+                                  : dst_c + (size_t)n * p.dst_bs + rem;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
@@ -685,9 +695,15 @@ __global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmF
     const int idx = bid >> 3;
     const int unit = (bid & 7) * p.tiles_per_xcd + idx;
     const int ntile = p.mtiles * p.ntiles;
-    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit) return;
-    const int ks = unit / ntile;
-    const int tile = unit - ks * ntile;
+    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit * p.groups) return;
+    const int grp_col = unit / (ntile * p.ksplit);              // column of a grouped layer
+    const int unit_c = unit - grp_col * (ntile * p.ksplit);
+    const int ks = unit_c / ntile;
+    const int tile = unit_c - ks * ntile;
+    const float *const At_c = p.At + (size_t)grp_col * p.at_gs;
+    const float *const src_c = p.src + (size_t)grp_col * p.src_gs;
+    float *const dst_c = p.dst + (size_t)grp_col * p.dst_gs;
+    float *const part_c = p.part + (size_t)grp_col * p.part_gs;
     const int mt = tile % p.mtiles, nt = tile / p.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
 
@@ -708,11 +724,11 @@ __global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmF
         base = 4 * (n * p.src_bs + hb * p.LW + wb);
         if (!colok) { hb = kInvalidTap; wb = kInvalidTap; }
     }
-    const char *src_bytes = reinterpret_cast<const char *>(p.src);
+    const char *src_bytes = reinterpret_cast<const char *>(src_c);
     const size_t a_step = (size_t)p.Mpad * (KC / 4);
     const int step_begin = ks * p.steps_per_split;
     const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
-    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(p.At + (size_t)m0 * KC) + tid + step_begin * a_step;
+    const f32x4 *a_ptr = reinterpret_cast<const f32x4 *>(At_c + (size_t)m0 * KC) + tid + step_begin * a_step;
 
     // register set t & 1 and LDS buffer t & 1 hold step t (two-set pipeline of colgemm_fast_kernel)
     f32x4 areg[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
@@ -844,8 +860,8 @@ __global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmF
         if (col >= p.ncols) continue;
         const int n = (int)fastdiv((uint32_t)col, p.div_plane);
         const int rem = col - n * plane;
-        float *out = p.ksplit > 1 ? p.part + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
-                                  : p.dst + (size_t)n * p.dst_bs + rem;
+        float *out = p.ksplit > 1 ? part_c + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
+                                  : dst_c + (size_t)n * p.dst_bs + rem;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -1169,12 +1185,17 @@ __global__ void reduce_split_outputs(const float *__restrict__ part, T *__restri
 // Filters for colgemm_fast_kernel: wt[((cb*R + r)*S + s)][Mpad][kc], element e = channel cb*kc+e.
 //   transposed = 0: row m = filter k, channel = input channel c   (forward)
 //   transposed = 1: row m = input channel c, channel = filter k   (backward-data)
+//   groups > 1: the filters of column g start w_gs floats after those of column g - 1; the copies are consecutive
 __global__ void relayout_filters_cblk(const float *__restrict__ w, float *__restrict__ wt, int M, int Mpad,
-                                      int cblocks, int RS, int C, int transposed, int kc)
+                                      int cblocks, int RS, int C, int transposed, int kc, int groups, int64_t w_gs)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)cblocks * RS * Mpad * kc;
-    if (i >= total) return;
+    const int64_t per = (int64_t)cblocks * RS * Mpad * kc;
+    if (i >= per * groups) return;
+    const int64_t gcol = i / per;
+    w += gcol * w_gs;
+    wt += gcol * per;
+    i -= gcol * per;
     int e = (int)(i % kc);
     int64_t t = i / kc;
     int m = (int)(t % Mpad);
@@ -1622,6 +1643,10 @@ struct WgradFastArgs {
     int J, chunks_per_split;
     int mtiles, ntiles, nunits, units_per_xcd;
     int x_plane_bytes, y_plane_bytes;
+    // columns of a grouped layer in one launch (fp32 kernel): nunits = tiles * nsplit * groups; column g reads
+    // dy + g * dy_gs and x + g * x_gs and writes part + g * part_gs (floats)
+    int nsplit, groups;
+    int64_t dy_gs, x_gs, part_gs;
     FastDiv div_plane, div_q, div_c;
 };
 
@@ -1640,8 +1665,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArg
     const int unit = (bid & 7) * p.units_per_xcd + idx;
     if (idx >= p.units_per_xcd || unit >= p.nunits) return;
     const int tiles = p.mtiles * p.ntiles;
-    const int split = unit / tiles;
-    const int tile = unit - split * tiles;
+    const int grp_col = unit / (tiles * p.nsplit);              // column of a grouped layer
+    const int unit_c = unit - grp_col * (tiles * p.nsplit);
+    const int split = unit_c / tiles;
+    const int tile = unit_c - split * tiles;
     const int mt = tile % p.mtiles, nt = tile / p.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
 
@@ -1676,8 +1703,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArg
     const int jend = min(jbeg + p.chunks_per_split * kChunk, p.J);
     const int nsteps = (jend - jbeg + kChunk - 1) / kChunk;
 
-    const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
-    const char *x_bytes = reinterpret_cast<const char *>(p.x);
+    const char *dy_bytes = reinterpret_cast<const char *>(p.dy + (size_t)grp_col * p.dy_gs);
+    const char *x_bytes = reinterpret_cast<const char *>(p.x + (size_t)grp_col * p.x_gs);
     // Register set t & 1 and LDS buffer t & 1 hold step t; loads run two steps ahead and the LDS writes of the
     // next step sit between the matrix instructions of the current one (see colgemm_fast_kernel).
     float areg[2][RA], breg[2][RB];
@@ -1806,7 +1833,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArg
         do_step(P0{}, P0{});
     }
 
-    float *out = p.part + (size_t)split * p.K * p.ncols;
+    float *out = p.part + (size_t)grp_col * p.part_gs + (size_t)split * p.K * p.ncols;
 #pragma unroll
     for (int jn = 0; jn < TN; ++jn) {
         const int col = n0 + (wn * TN + jn) * 32 + l32;
@@ -2278,12 +2305,18 @@ __global__ void pack_x_lin(const unsigned short *__restrict__ x, unsigned short 
 }
 
 // dw[k][c][rs] = part[0][k][rs*C + c] + part[1][k][rs*C + c] + ...  (fixed order)
+// groups > 1: K filters per column; the partials of column g follow those of column g - 1, dw holds the columns'
+// filters one after the other
 __global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int RS,
-                             int nsplit)
+                             int nsplit, int groups)
 {
     const int ncols = RS * C;
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= K * ncols) return;
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= groups * K * ncols) return;
+    const int gcol = i / (K * ncols);
+    i -= gcol * (K * ncols);
+    part += (size_t)gcol * nsplit * K * ncols;
+    dw += (size_t)gcol * K * ncols;
     const int k = i / ncols, col = i - k * ncols;
     const int rs = col / C, c = col - rs * C;
     float s = part[i];
@@ -2819,13 +2852,14 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
     if (fast) {
         const int kc = bf ? bf16_step_channels(Cr) : pl.kc;
         const int64_t wt_elems = (int64_t)pl.Mpad * Cr * RS;
+        const int GF = pl.fused_groups ? pb.groups : 1;      // columns of a grouped layer run in this one launch
         if (bf)
             hipLaunchKernelGGL(relayout_filters_cblk_bf16, dim3(grid1d(wt_elems, 256)), dim3(256), 0, st,
                                static_cast<const unsigned short *>(w), reinterpret_cast<unsigned short *>(wt), pl.M,
                                pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc);
         else
-            hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d(wt_elems, 256)), dim3(256), 0, st, wf, wt, pl.M,
-                               pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc);
+            hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d(wt_elems * GF, 256)), dim3(256), 0, st, wf, wt, pl.M,
+                               pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc, GF, pb.w_gs);
         ColGemmFastArgs a;
         a.At = wt; a.src = actf; a.dst = static_cast<float *>(out);
         a.M = pl.M; a.Mpad = pl.Mpad; a.cblocks = Cr / kc; a.R = pb.R; a.S = pb.S;
@@ -2860,8 +2894,13 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         a.out_bf16 = bf && pb.out_bf16;
         a.steps_per_split = ceil_div(a.cblocks * RS, pl.nsplit);      // same ranges as planned, in steps of kc
         a.part = reinterpret_cast<float *>(wsb + pl.part_off);
+        a.groups = GF;
+        a.src_gs = fwd ? pb.x_gs : pb.y_gs;
+        a.dst_gs = fwd ? pb.y_gs : pb.x_gs;
+        a.at_gs = wt_elems;
+        a.part_gs = (int64_t)(pl.part_bytes / 4);
         const int need_lds = 2 * (pl.tile.bm() + pl.tile.bn()) * (bf ? kc * 2 + 16 : (kc + 4) * 4);
-        const GridPlan g = plan_grid(a.mtiles * a.ntiles * a.ksplit, need_lds);
+        const GridPlan g = plan_grid(a.mtiles * a.ntiles * a.ksplit * GF, need_lds);
         a.tiles_per_xcd = g.tiles_per_xcd;
         if (bf) launch_colgemm_bf16(pl.tile, kc, a, g, st);
         else launch_colgemm_fast(pl.tile, kc, a, g, st);
@@ -2873,8 +2912,10 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
                                reinterpret_cast<unsigned short *>(a.dst), a.ksplit, per_sample, pb.N, a.dst_bs,
                                make_fastdiv((uint32_t)per_sample));
         else
-            hipLaunchKernelGGL(reduce_split_outputs<float>, dim3(2048), dim3(256), 0, st, a.part, a.dst, a.ksplit,
-                               per_sample, pb.N, a.dst_bs, make_fastdiv((uint32_t)per_sample));
+            for (int gc = 0; gc < GF; ++gc)
+                hipLaunchKernelGGL(reduce_split_outputs<float>, dim3(2048), dim3(256), 0, st, a.part + gc * a.part_gs,
+                                   a.dst + gc * a.dst_gs, a.ksplit, per_sample, pb.N, a.dst_bs,
+                                   make_fastdiv((uint32_t)per_sample));
         return check_launch();
     }
     // forward with few channels: stage the input rows once per work-group when they fit in LDS
@@ -2986,7 +3027,7 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         if (rc != kStatusOk) return rc;
         const int count = pb.K * pl.Kg;
         hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
-                           pb.K, pb.C, RS, pl.nsplit);
+                           pb.K, pb.C, RS, pl.nsplit, 1);
         return check_launch();
     }
     const float *xf = as_f32(x, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st);
@@ -3001,7 +3042,10 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         a.chunks_per_split = pl.chunks_per_split;
         a.mtiles = pl.Mpad / pl.tile.bm();
         a.ntiles = ceil_div(pl.Kg, pl.tile.bn());
-        a.nunits = a.mtiles * a.ntiles * pl.nsplit;
+        const int GF = pl.fused_groups ? pb.groups : 1;      // columns of a grouped layer run in this one launch
+        a.nsplit = pl.nsplit; a.groups = GF;
+        a.dy_gs = pb.y_gs; a.x_gs = pb.x_gs; a.part_gs = (int64_t)(pl.part_bytes / 4);
+        a.nunits = a.mtiles * a.ntiles * pl.nsplit * GF;
         const int need_lds = 2 * (pl.tile.bm() + pl.tile.bn()) * (bf ? kWgradBf16Depth * 2 + 16 : kPitch * 4);
         const GridPlan g = plan_grid(a.nunits, need_lds);
         a.units_per_xcd = g.tiles_per_xcd;
@@ -3014,9 +3058,9 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         else launch_wgrad_fast(pl.tile, a, g, st);
         int rc = check_launch();
         if (rc != kStatusOk) return rc;
-        const int count = pb.K * pl.Kg;
+        const int count = pb.K * pl.Kg * GF;
         hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
-                           pb.K, pb.C, RS, pl.nsplit);
+                           pb.K, pb.C, RS, pl.nsplit, GF);
         return check_launch();
     }
     hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len, pl.Kg, RS,
@@ -3199,6 +3243,93 @@ int conv_bwd_filter_ex(const void *x, const void *dy, void *dw, int N, int C, in
                      dtype, ws, ws_bytes, pb, pl);
     if (rc != kStatusOk) return rc;
     return run_wgrad(x, dy, dw, pb, pl, ws, static_cast<hipStream_t>(stream));
+}
+
+// Grouped layers.  The per-column problem carries the full tensors' batch strides and the column strides; columns
+// run in one launch where the plan says so, else one after the other on offset pointers.
+static int grouped_problem(Problem &pb, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                           int groups, int dtype)
+{
+    if (groups < 1 || C <= 0 || K <= 0 || C % groups != 0 || K % groups != 0) return kErrInvalidArg;
+    const int Cg = C / groups, Kg = K / groups;
+    int rc = make_problem(pb, N, Cg, H, W, Kg, R, S, stride, pad, 0, 0, dtype);
+    if (rc != kStatusOk) return rc;
+    // the same checks on the full tensors' spans (the kernels index them with 32-bit byte offsets)
+    Problem full;
+    rc = make_problem(full, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype);
+    if (rc != kStatusOk && rc != kErrTooLarge) return rc;
+    if ((int64_t)N * C * H * W * 4 >= kMaxSpanBytes || (int64_t)N * K * pb.P * pb.Q * 4 >= kMaxSpanBytes)
+        return kErrTooLarge;
+    pb.x_bs = (int64_t)C * H * W;
+    pb.y_bs = (int64_t)K * pb.P * pb.Q;
+    pb.groups = groups;
+    pb.x_gs = (int64_t)Cg * H * W;
+    pb.y_gs = (int64_t)Kg * pb.P * pb.Q;
+    pb.w_gs = (int64_t)Kg * Cg * R * S;
+    return kStatusOk;
+}
+
+static int run_grouped(int op, const void *a, const void *b, void *out, int N, int C, int H, int W, int K, int R,
+                       int S, int stride, int pad, int groups, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!a || !b || !out) return kErrInvalidArg;
+    Problem pb;
+    int rc = grouped_problem(pb, N, C, H, W, K, R, S, stride, pad, groups, dtype);
+    if (rc != kStatusOk) return rc;
+    if (!aligned(a, 16) || !aligned(b, 16) || !aligned(out, 16)) return kErrMisaligned;
+    const Plan pl = make_plan(op, pb);
+    if (pl.total > 0) {
+        if (!ws || ws_bytes < pl.total) return kErrWorkspace;
+        if (!aligned(ws, 256)) return kErrMisaligned;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (groups == 1 || pl.fused_groups)
+        return op == kOpBwdFilter ? run_wgrad(a, b, out, pb, pl, ws, st) : run_colgemm(op, a, b, out, pb, pl, ws, st);
+    // one column after the other: element sizes of the three tensors of this pass
+    const int in_b = pb.dtype == kDtypeBf16 ? 2 : 4;
+    const int out_b = (pb.out_bf16 && op != kOpBwdFilter) ? 2 : 4;
+    Problem one = pb;
+    one.groups = 1;
+    for (int g = 0; g < groups; ++g) {
+        const char *pa = static_cast<const char *>(a), *pbp = static_cast<const char *>(b);
+        char *po = static_cast<char *>(out);
+        if (op == kOpFwd) { pa += g * pb.x_gs * in_b; pbp += g * pb.w_gs * in_b; po += g * pb.y_gs * out_b; }
+        else if (op == kOpBwdData) { pa += g * pb.y_gs * in_b; pbp += g * pb.w_gs * in_b; po += g * pb.x_gs * out_b; }
+        else { pa += g * pb.x_gs * in_b; pbp += g * pb.y_gs * in_b; po += g * pb.w_gs * 4; }
+        // column bases must keep the alignment the kernels rely on
+        if (!aligned(pa, 16) || !aligned(pbp, 16) || !aligned(po, 16)) return kErrMisaligned;
+        rc = op == kOpBwdFilter ? run_wgrad(pa, pbp, po, one, pl, ws, st) : run_colgemm(op, pa, pbp, po, one, pl, ws, st);
+        if (rc != kStatusOk) return rc;
+    }
+    return kStatusOk;
+}
+
+int conv_fwd_grouped(const void *x, const void *w, void *y, int N, int C, int H, int W, int K, int R, int S,
+                     int stride, int pad, int groups, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    return run_grouped(kOpFwd, x, w, y, N, C, H, W, K, R, S, stride, pad, groups, dtype, ws, ws_bytes, stream);
+}
+
+int conv_bwd_data_grouped(const void *dy, const void *w, void *dx, int N, int C, int H, int W, int K, int R, int S,
+                          int stride, int pad, int groups, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    return run_grouped(kOpBwdData, dy, w, dx, N, C, H, W, K, R, S, stride, pad, groups, dtype, ws, ws_bytes, stream);
+}
+
+int conv_bwd_filter_grouped(const void *x, const void *dy, void *dw, int N, int C, int H, int W, int K, int R, int S,
+                            int stride, int pad, int groups, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    return run_grouped(kOpBwdFilter, x, dy, dw, N, C, H, W, K, R, S, stride, pad, groups, dtype, ws, ws_bytes,
+                       stream);
+}
+
+size_t conv_workspace_bytes_grouped(int op, int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                                    int groups, int dtype)
+{
+    if (op != kOpFwd && op != kOpBwdData && op != kOpBwdFilter) return 0;
+    Problem pb;
+    if (grouped_problem(pb, N, C, H, W, K, R, S, stride, pad, groups, dtype) != kStatusOk) return 0;
+    return make_plan(op, pb).total;
 }
 
 int conv_fwd(const void *x, const void *w, void *y, int N, int C, int H, int W, int K, int R, int S, int stride,

@@ -35,6 +35,10 @@ struct Problem {
     int64_t x_bs, y_bs;               // batch strides in elements
     int dtype;                        // of the inputs: kDtypeF32 or kDtypeBf16
     bool out_bf16;                    // forward / backward-data write bf16 (caller passed kDtypeBf16OutBf16)
+    // Grouped (multi-column) layer: C and K above are the PER-COLUMN counts, the batch strides those of the
+    // full tensors; column g starts g * x_gs / y_gs / w_gs elements into x / y / the filters.
+    int groups;
+    int64_t x_gs, y_gs, w_gs;
 };
 
 // Tile shape of one work-group (4 waves): each wave owns TM x TN MFMA tiles of
@@ -90,6 +94,7 @@ inline int make_problem(Problem &pb, int N, int C, int H, int W, int K, int R, i
     if ((int64_t)H + 2 * (int64_t)pad < R || (int64_t)W + 2 * (int64_t)pad < S) return kErrInvalidArg;
     pb.N = N; pb.C = C; pb.H = H; pb.W = W; pb.K = K; pb.R = R; pb.S = S;
     pb.stride = stride; pb.pad = pad; pb.dtype = dtype;
+    pb.groups = 1; pb.x_gs = 0; pb.y_gs = 0; pb.w_gs = 0;
     pb.P = out_extent(H, R, stride, pad);
     pb.Q = out_extent(W, S, stride, pad);
     if (pb.P <= 0 || pb.Q <= 0) return kErrInvalidArg;
@@ -133,6 +138,9 @@ struct Plan {
     bool lin;
     int lin_wq, lin_jy, lin_jx, lin_steps;
     size_t lin_dy_off, lin_dy_bytes, lin_x_off, lin_x_bytes;
+    // columns of a grouped layer run in ONE launch (fp32 kernels of the fast paths): the filter and partial-sum
+    // regions then hold `groups` consecutive copies; otherwise the host runs the columns one after the other
+    bool fused_groups;
     size_t total;
 };
 
@@ -140,6 +148,7 @@ inline Plan make_plan(int op, const Problem &pb)
 {
     Plan pl = {};
     pl.op = op;
+    const int G = pb.groups > 1 ? pb.groups : 1;
     const int RS = pb.R * pb.S;
     if (op == kOpFwd) { pl.M = pb.K; pl.Kg = pb.C * RS; }
     else if (op == kOpBwdData) { pl.M = pb.C; pl.Kg = pb.K * RS; }
@@ -163,7 +172,8 @@ inline Plan make_plan(int op, const Problem &pb)
     if (op == kOpBwdFilter) {
         const int64_t J = (int64_t)pb.N * pb.P * pb.Q;
         const int jchunks = (int)((J + kChunk - 1) / kChunk);
-        const int tiles = (pl.Mpad / pl.tile.bm()) * ceil_div(pl.Kg, pl.tile.bn());
+        pl.fused_groups = G > 1 && pb.dtype == kDtypeF32 && pb.C % kChunk == 0;
+        const int tiles = (pl.Mpad / pl.tile.bm()) * ceil_div(pl.Kg, pl.tile.bn()) * (pl.fused_groups ? G : 1);
         // as many splits as fill two work-groups per CU without exceeding them
         int want = kTargetGroups / tiles;
         int most = jchunks / 8 > 0 ? jchunks / 8 : 1;     // at least 8 chunks of work per split
@@ -192,11 +202,14 @@ inline Plan make_plan(int op, const Problem &pb)
         pl.part_off = off;
         const bool staged = pb.C % kChunk == 0;          // fast path always goes through the partials
         pl.part_bytes = (pl.nsplit > 1 || staged) ? (size_t)pl.nsplit * pb.K * pb.C * RS * 4 : 0;
-        off += round_up64(pl.part_bytes, 256);
+        off += round_up64(pl.part_bytes * (pl.fused_groups ? G : 1), 256);
     } else {
+        const int Cr_ = op == kOpFwd ? pb.C : pb.K;
+        pl.fused_groups = G > 1 && pb.dtype == kDtypeF32 && Cr_ % kChunk == 0 && (op == kOpFwd || pb.stride == 1);
+        const int GF = pl.fused_groups ? G : 1;
         pl.wt_off = off;
         pl.wt_bytes = (size_t)pl.Mpad * pl.Kgpad * 4;
-        off += round_up64(pl.wt_bytes, 256);
+        off += round_up64(pl.wt_bytes * GF, 256);
         // Fast path (channel count of the gathered tensor a multiple of 16, unit-stride gather rows):
         // the reduction may be cut into ranges when that balances the CUs better.  Model: a CU
         // holding c work-groups runs them at eff(c) of its MFMA rate; the launch lasts as long
@@ -205,8 +218,8 @@ inline Plan make_plan(int op, const Problem &pb)
         const int OH = op == kOpFwd ? pb.P : pb.H, OW = op == kOpFwd ? pb.Q : pb.W;
         if (Cr % kChunk == 0 && (op == kOpFwd || pb.stride == 1)) {
             const int64_t ncols = (int64_t)pb.N * OH * OW;
-            const int tiles = (pl.Mpad / pl.tile.bm()) * (int)((ncols + pl.tile.bn() - 1) / pl.tile.bn());
-            const double out_mb = (double)ncols * pl.M * 4.0 / 1e6;
+            const int tiles = (pl.Mpad / pl.tile.bm()) * (int)((ncols + pl.tile.bn() - 1) / pl.tile.bn()) * GF;
+            const double out_mb = (double)ncols * pl.M * 4.0 * GF / 1e6;
             // measured fraction of the MFMA rate a CU reaches with c resident work-groups
             const double eff16[5] = {1.0, 0.71, 0.83, 0.87, 0.88};
             // (32-deep steps were measured too: no faster at two work-groups per CU, so steps stay 16 deep)
@@ -230,7 +243,7 @@ inline Plan make_plan(int op, const Problem &pb)
             if (pl.nsplit > 1) {
                 pl.part_off = off;
                 pl.part_bytes = (size_t)pl.nsplit * ncols * pl.M * 4;
-                off += round_up64(pl.part_bytes, 256);
+                off += round_up64(pl.part_bytes * GF, 256);
             }
         }
         if (pl.chunks_per_split == 0) pl.chunks_per_split = pl.Kgpad / kChunk;

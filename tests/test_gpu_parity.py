@@ -298,6 +298,44 @@ def test_bf16_channel_slices_of_wider_tensors(c0, c1, k0, k1):
     assert norm_err(dw.cpu().numpy(), oracle.conv_bwd_filter(xs, dys, 5, 5, st, pad)) <= TOL["bf16"]
 
 
+# ------------------------------------------------------------ grouped layers ---
+GROUPED = [
+    # N, C, H, W, K, R, S, stride, pad, groups, dtype
+    (3, 96, 27, 27, 256, 5, 5, 1, 2, 2, "f32"),       # the second layer's two columns: one launch, 48-row backward-data
+    (2, 64, 13, 13, 96, 3, 3, 1, 1, 2, "f32"),        # 32 -> 48 per column
+    (5, 48, 9, 9, 192, 3, 3, 1, 1, 3, "f32"),         # three columns of 16 -> 64, ragged column tiles
+    (2, 32, 12, 12, 64, 3, 3, 2, 1, 2, "f32"),        # strided: forward / backward-filter fused, backward-data in turn
+    (2, 6, 10, 10, 16, 3, 3, 1, 1, 2, "f32"),         # few channels: columns one after the other (16-byte aligned slices)
+    (3, 96, 27, 27, 256, 5, 5, 1, 2, 2, "bf16"),      # bf16 kernels, columns in turn
+    (4, 64, 13, 13, 64, 3, 3, 1, 1, 1, "f32"),        # one group = the ordinary layer
+]
+
+
+@pytest.mark.parametrize("shape", GROUPED)
+def test_grouped_layers_full_compare(shape):
+    N, C, H, W, K, R, S, st, pad, groups, dtype = shape
+    P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+    x, w, dy = prepared(synth.gaussian((N, C, H, W), 131), synth.gaussian((K, C // groups, R, S), 132, 0.1),
+                        synth.gaussian((N, K, P, Q), 133), dtype)
+    xd, wd, dyd = dev(x, dtype), dev(w, dtype), dev(dy, dtype)
+    y = hp.conv_fwd_grouped(xd, wd, st, pad, groups, y=nan_like((N, K, P, Q)))
+    dx = hp.conv_bwd_data_grouped(dyd, wd, H, W, st, pad, groups, dx=nan_like((N, C, H, W)))
+    dw = hp.conv_bwd_filter_grouped(xd, dyd, R, S, st, pad, groups, dw=nan_like((K, C // groups, R, S)))
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert norm_err(y.cpu().numpy(), oracle.conv_fwd_grouped(x, w, st, pad, groups)) <= tol
+    assert norm_err(dx.cpu().numpy(), oracle.conv_bwd_data_grouped(dy, w, H, W, st, pad, groups)) <= tol
+    assert norm_err(dw.cpu().numpy(), oracle.conv_bwd_filter_grouped(x, dy, R, S, st, pad, groups)) <= tol
+    if groups > 1 and dtype == "f32":
+        # the columns in one launch give bit for bit what the same columns give as separate calls on channel slices
+        Cg, Kg = C // groups, K // groups
+        for g in range(groups):
+            yg = hp.conv_fwd(xd[:, g * Cg:(g + 1) * Cg], wd[g * Kg:(g + 1) * Kg].contiguous(), st, pad)
+            assert torch.equal(yg, y[:, g * Kg:(g + 1) * Kg])
+            dwg = hp.conv_bwd_filter(xd[:, g * Cg:(g + 1) * Cg], dyd[:, g * Kg:(g + 1) * Kg], R, S, st, pad)
+            assert torch.equal(dwg, dw[g * Kg:(g + 1) * Kg])
+
+
 # ------------------------------- full-size layers, sampled against oracle ---
 FULL = [
     # layer, N, passes, dtypes

@@ -173,3 +173,22 @@ def test_convert_argument_checks(lib):
     assert lib.convert_f32_to_bf16(PTR + 2, PTR, 8, None) == b.ERR_MISALIGNED
     assert lib.convert_f32_to_bf16(PTR, PTR + 1, 8, None) == b.ERR_MISALIGNED
     assert lib.convert_f32_to_bf16(PTR, PTR, 0, None) == b.OK
+
+
+def test_grouped_argument_checks(lib):
+    from paper_1312_5853_amd import binding as b
+    dims = [4, 96, 27, 27, 256, 5, 5, 1, 2]
+    for fn in (lib.conv_fwd_grouped, lib.conv_bwd_data_grouped, lib.conv_bwd_filter_grouped):
+        assert fn(PTR, PTR, PTR, *dims, 0, 0, PTR, 1 << 30, None) == b.ERR_INVALID_ARG        # no groups
+        assert fn(PTR, PTR, PTR, *dims, 5, 0, PTR, 1 << 30, None) == b.ERR_INVALID_ARG        # 96 % 5
+        assert fn(PTR, PTR, PTR, *dims, 3, 0, PTR, 1 << 30, None) == b.ERR_INVALID_ARG        # 256 % 3
+        assert fn(None, PTR, PTR, *dims, 2, 0, PTR, 1 << 30, None) == b.ERR_INVALID_ARG
+        assert fn(PTR, PTR, PTR, *dims, 2, 9, PTR, 1 << 30, None) == b.ERR_BAD_DTYPE
+        assert fn(PTR, PTR, PTR, *dims, 2, 0, None, 0, None) == b.ERR_WORKSPACE
+        assert fn(PTR, PTR + 4, PTR, *dims, 2, 0, PTR, 1 << 30, None) == b.ERR_MISALIGNED
+    # columns in one launch hold one filter copy / one set of partial sums per column
+    for op in (0, 1, 2):
+        two = lib.conv_workspace_bytes_grouped(op, *dims, 2, 0)
+        one = lib.conv_workspace_bytes(op, 4, 48, 27, 27, 128, 5, 5, 1, 2, 0)
+        assert two > one and lib.conv_workspace_bytes_grouped(op, *dims, 1, 0) == lib.conv_workspace_bytes(op, *dims, 0)
+    assert lib.conv_workspace_bytes_grouped(0, *dims, 7, 0) == 0
