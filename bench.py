@@ -139,19 +139,22 @@ def main():
     stack.timers = None
     per_pass = {}
     conv_ms = 0.0
+    def pass_flops(layer):
+        """Nominal FLOPs of one pass of a stack layer (conv2 = both model-parallel columns in one grouped call)."""
+        return conv_flops(N, synth.LAYERS[layer]) * (2 if layer == "conv2" else 1)
+
     for (layer, p), tot in sorted(acc.items()):
-        L = synth.LAYERS[layer.rstrip("ab")]
         ms = tot / reps
-        f = conv_flops(N, L)
+        f = pass_flops(layer)
         conv_ms += ms
         per_pass["%s.%s" % (layer, p)] = {"ms": round(ms, 4), "tflops": round(f / ms / 1e9, 2),
                                            "frac_peak": round(f / ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4)}
 
-    # dominant kernel: the 128x128-tile implicit-GEMM kernel that runs forward of
-    # conv2a/2b/3/4/5 and backward-data of conv3/4/5 (8 launches per step)
+    # dominant kernel: the 128x128-tile implicit-GEMM kernel that runs forward of conv2 (both columns in one
+    # launch), conv3, conv4, conv5 and backward-data of conv3, conv4, conv5 (7 launches per step)
     dom_keys = [k for k in acc if k[1] in ("fwd", "dgrad") and k[0] != "conv1"]
-    dom_keys = [k for k in dom_keys if not (k[0].startswith("conv2") and k[1] == "dgrad")]
-    dom_flops = sum(conv_flops(N, synth.LAYERS[k[0].rstrip("ab")]) for k in dom_keys)
+    dom_keys = [k for k in dom_keys if not (k[0] == "conv2" and k[1] == "dgrad")]
+    dom_flops = sum(pass_flops(k[0]) for k in dom_keys)
     dom_ms = sum(acc[k] for k in dom_keys) / reps
     achieved = dom_flops / dom_ms / 1e9
     roofline = {
@@ -160,7 +163,7 @@ def main():
         "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
         # HBM bytes per launch of this kernel from rocprofv3 FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00), factors from a
         # 256 MiB copy; collected offline (profiles/stack_n128_fp32_hbm_traffic.txt), valid for the default N = 128
-        "traffic": 107.5e6 if N == 128 else None,
+        "traffic": 122.9e6 if N == 128 else None,
         "launches_per_step": len(dom_keys), "avg_launch_ms": round(dom_ms / len(dom_keys), 4),
         "flops_per_launch": dom_flops / len(dom_keys),
     }

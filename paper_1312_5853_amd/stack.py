@@ -4,9 +4,9 @@ pooling after conv1, conv2 and conv5, then back-propagation from a gradient on
 the last pooling output down to the first layer's filter gradient.
 
 Second layer: two model-parallel columns (channels 0..47 -> filters 0..127,
-channels 48..95 -> filters 128..255), each run in place on channel slices of
-the shared NCHW tensors -- the two-column layout of the paper's
-model-parallelism paragraph.  Layers three to five run at full width.  The
+channels 48..95 -> filters 128..255) -- the two-column layout of the paper's
+model-parallelism paragraph -- run as one grouped call per pass on the shared
+NCHW tensors (filters of both columns in one [256, 48, 5, 5] tensor).  Layers three to five run at full width.  The
 first layer computes no input gradient (nothing lies below it).
 
 With dtype="bf16" the input, the filters and every activation and gradient
@@ -17,12 +17,13 @@ gradients), the glue layers work on bfloat16 tensors.
 This module only owns buffers and the order of calls; all arithmetic happens
 in the library.
 """
+import numpy as np
 import torch
 
 from . import binding as hp
 from . import synth
 
-CONV_ORDER = ("conv1", "conv2a", "conv2b", "conv3", "conv4", "conv5")
+CONV_ORDER = ("conv1", "conv2", "conv3", "conv4", "conv5")
 
 
 def conv_flops(N, L):
@@ -54,8 +55,9 @@ class ConvStack:
         self.x0 = t(synth.gaussian((N, 3, 224, 224), seed + 0))
         self.w = {
             "conv1": t(synth.gaussian((96, 3, 11, 11), seed + 1, synth.STD_FILTER)),
-            "conv2a": t(synth.gaussian((128, 48, 5, 5), seed + 2, synth.STD_FILTER)),
-            "conv2b": t(synth.gaussian((128, 48, 5, 5), seed + 3, synth.STD_FILTER)),
+            # the two columns' filters, column a first
+            "conv2": t(np.concatenate([synth.gaussian((128, 48, 5, 5), seed + 2, synth.STD_FILTER),
+                                       synth.gaussian((128, 48, 5, 5), seed + 3, synth.STD_FILTER)])),
             "conv3": t(synth.gaussian((384, 256, 3, 3), seed + 4, synth.STD_FILTER)),
             "conv4": t(synth.gaussian((384, 384, 3, 3), seed + 5, synth.STD_FILTER)),
             "conv5": t(synth.gaussian((256, 384, 3, 3), seed + 6, synth.STD_FILTER)),
@@ -98,10 +100,7 @@ class ConvStack:
         w, ws = self.w, self.ws
         self._timed(("conv1", "fwd"), lambda: hp.conv_fwd(self.x0, w["conv1"], 4, 2, y=self.y1, ws=ws))
         hp.relu_maxpool3x3s2_fwd(self.y1, self.a1)
-        self._timed(("conv2a", "fwd"),
-                    lambda: hp.conv_fwd(self.a1[:, :48], w["conv2a"], 1, 2, y=self.y2[:, :128], ws=ws))
-        self._timed(("conv2b", "fwd"),
-                    lambda: hp.conv_fwd(self.a1[:, 48:], w["conv2b"], 1, 2, y=self.y2[:, 128:], ws=ws))
+        self._timed(("conv2", "fwd"), lambda: hp.conv_fwd_grouped(self.a1, w["conv2"], 1, 2, 2, y=self.y2, ws=ws))
         hp.relu_maxpool3x3s2_fwd(self.y2, self.a2)
         self._timed(("conv3", "fwd"), lambda: hp.conv_fwd(self.a2, w["conv3"], 1, 1, y=self.y3, ws=ws))
         hp.relu_fwd(self.y3, self.y3)
@@ -129,12 +128,10 @@ class ConvStack:
         self._timed(("conv3", "dgrad"),
                     lambda: hp.conv_bwd_data(self.dy3, w["conv3"], 13, 13, 1, 1, dx=self.da2, ws=ws))
         hp.relu_maxpool3x3s2_bwd(self.y2, self.da2, self.dy2)
-        for col, (c0, k0) in (("conv2a", (0, 0)), ("conv2b", (48, 128))):
-            xs, gs = self.a1[:, c0:c0 + 48], self.dy2[:, k0:k0 + 128]
-            self._timed((col, "wgrad"),
-                        lambda: hp.conv_bwd_filter(xs, gs, 5, 5, 1, 2, dw=dw[col], ws=ws))
-            self._timed((col, "dgrad"),
-                        lambda: hp.conv_bwd_data(gs, w[col], 27, 27, 1, 2, dx=self.da1[:, c0:c0 + 48], ws=ws))
+        self._timed(("conv2", "wgrad"),
+                    lambda: hp.conv_bwd_filter_grouped(self.a1, self.dy2, 5, 5, 1, 2, 2, dw=dw["conv2"], ws=ws))
+        self._timed(("conv2", "dgrad"),
+                    lambda: hp.conv_bwd_data_grouped(self.dy2, w["conv2"], 27, 27, 1, 2, 2, dx=self.da1, ws=ws))
         hp.relu_maxpool3x3s2_bwd(self.y1, self.da1, self.dy1)
         self._timed(("conv1", "wgrad"),
                     lambda: hp.conv_bwd_filter(self.x0, self.dy1, 11, 11, 4, 2, dw=dw["conv1"], ws=ws))

@@ -476,8 +476,7 @@ def test_stack_step_layer_by_layer():
     tol = TOL["f32"]
     assert norm_err(y1, oracle.conv_fwd(x0, w["conv1"], 4, 2)) <= tol
     assert np.array_equal(a1, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y1)).astype(np.float32))
-    assert norm_err(y2[:, :128], oracle.conv_fwd(a1[:, :48], w["conv2a"], 1, 2)) <= tol
-    assert norm_err(y2[:, 128:], oracle.conv_fwd(a1[:, 48:], w["conv2b"], 1, 2)) <= tol
+    assert norm_err(y2, oracle.conv_fwd_grouped(a1, w["conv2"], 1, 2, 2)) <= tol
     assert np.array_equal(a2, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y2)).astype(np.float32))
     # y3, y4 hold relu(conv) (in place): compare with relu of the oracle's conv
     assert norm_err(y3, oracle.relu_fwd(oracle.conv_fwd(a2, w["conv3"], 1, 1))) <= tol
@@ -495,10 +494,8 @@ def test_stack_step_layer_by_layer():
     assert norm_err(dw["conv3"], oracle.conv_bwd_filter(a2, dy3, 3, 3, 1, 1)) <= tol
     assert norm_err(da2, oracle.conv_bwd_data(dy3, w["conv3"], 13, 13, 1, 1)) <= tol
     assert norm_err(dy2, oracle.relu_bwd(y2, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y2), da2))) <= 1e-6
-    assert norm_err(dw["conv2a"], oracle.conv_bwd_filter(a1[:, :48], dy2[:, :128], 5, 5, 1, 2)) <= tol
-    assert norm_err(dw["conv2b"], oracle.conv_bwd_filter(a1[:, 48:], dy2[:, 128:], 5, 5, 1, 2)) <= tol
-    assert norm_err(da1[:, :48], oracle.conv_bwd_data(dy2[:, :128], w["conv2a"], 27, 27, 1, 2)) <= tol
-    assert norm_err(da1[:, 48:], oracle.conv_bwd_data(dy2[:, 128:], w["conv2b"], 27, 27, 1, 2)) <= tol
+    assert norm_err(dw["conv2"], oracle.conv_bwd_filter_grouped(a1, dy2, 5, 5, 1, 2, 2)) <= tol
+    assert norm_err(da1, oracle.conv_bwd_data_grouped(dy2, w["conv2"], 27, 27, 1, 2, 2)) <= tol
     assert norm_err(dy1, oracle.relu_bwd(y1, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y1), da1))) <= 1e-6
     assert norm_err(dw["conv1"], oracle.conv_bwd_filter(x0, dy1, 11, 11, 4, 2)) <= tol
 
@@ -526,8 +523,7 @@ def test_bf16_stack_step_layer_by_layer():
     assert st.y1.dtype == torch.bfloat16 and st.dy1.dtype == torch.bfloat16 and st.dw["conv1"].dtype == torch.float32
     assert norm_err(y1, oracle.conv_fwd(x0, w["conv1"], 4, 2)) <= tol
     assert np.array_equal(a1, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y1)).astype(np.float32))
-    assert norm_err(y2[:, :128], oracle.conv_fwd(a1[:, :48], w["conv2a"], 1, 2)) <= tol
-    assert norm_err(y2[:, 128:], oracle.conv_fwd(a1[:, 48:], w["conv2b"], 1, 2)) <= tol
+    assert norm_err(y2, oracle.conv_fwd_grouped(a1, w["conv2"], 1, 2, 2)) <= tol
     assert np.array_equal(a2, oracle.maxpool3x3s2_fwd(oracle.relu_fwd(y2)).astype(np.float32))
     # y3, y4 hold the activation (ReLU applied in place to the rounded convolution output)
     assert norm_err(y3, oracle.relu_fwd(oracle.conv_fwd(a2, w["conv3"], 1, 1))) <= tol
@@ -550,10 +546,8 @@ def test_bf16_stack_step_layer_by_layer():
     assert norm_err(dw["conv3"], oracle.conv_bwd_filter(a2, dy3, 3, 3, 1, 1)) <= tol
     assert norm_err(da2, oracle.conv_bwd_data(dy3, w["conv3"], 13, 13, 1, 1)) <= tol
     assert norm_err(dy2, oracle.relu_bwd(y2, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y2), da2))) <= rnd
-    assert norm_err(dw["conv2a"], oracle.conv_bwd_filter(a1[:, :48], dy2[:, :128], 5, 5, 1, 2)) <= tol
-    assert norm_err(dw["conv2b"], oracle.conv_bwd_filter(a1[:, 48:], dy2[:, 128:], 5, 5, 1, 2)) <= tol
-    assert norm_err(da1[:, :48], oracle.conv_bwd_data(dy2[:, :128], w["conv2a"], 27, 27, 1, 2)) <= tol
-    assert norm_err(da1[:, 48:], oracle.conv_bwd_data(dy2[:, 128:], w["conv2b"], 27, 27, 1, 2)) <= tol
+    assert norm_err(dw["conv2"], oracle.conv_bwd_filter_grouped(a1, dy2, 5, 5, 1, 2, 2)) <= tol
+    assert norm_err(da1, oracle.conv_bwd_data_grouped(dy2, w["conv2"], 27, 27, 1, 2, 2)) <= tol
     assert norm_err(dy1, oracle.relu_bwd(y1, oracle.maxpool3x3s2_bwd(oracle.relu_fwd(y1), da1))) <= rnd
     assert norm_err(dw["conv1"], oracle.conv_bwd_filter(x0, dy1, 11, 11, 4, 2)) <= tol
 
