@@ -26,6 +26,8 @@ from .oracle import (  # noqa: F401
     relu_bwd,
     maxpool3x3s2_fwd,
     maxpool3x3s2_bwd,
+    bias_fwd,
+    bias_bwd,
     num_threads,
     set_num_threads,
 )

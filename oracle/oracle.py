@@ -223,3 +223,23 @@ def maxpool3x3s2_bwd(x, dy):
     dx = np.empty_like(x)
     _load().oracle_maxpool3x3s2_bwd(_p(x), _p(dy), _p(dx), N * C, H, W)
     return dx
+
+
+# Bias of a convolutional layer (one value per filter, the same at every
+# output position): forward adds it, its gradient is the sum of the output
+# gradient over samples and positions.
+def bias_fwd(y, b):
+    y, b = _f64(y), _f64(b)
+    assert y.ndim == 4 and b.shape == (y.shape[1],)
+    out = np.empty_like(y)
+    for k in range(y.shape[1]):
+        out[:, k] = y[:, k] + b[k]
+    return out
+
+
+def bias_bwd(dy):
+    dy = _f64(dy)
+    db = np.zeros(dy.shape[1], dtype=np.float64)
+    for k in range(dy.shape[1]):
+        db[k] = np.sum(dy[:, k])
+    return db

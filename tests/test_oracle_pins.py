@@ -441,3 +441,29 @@ def test_grouped_adjoint_identities():
     c = np.sum(w * oracle.conv_bwd_filter_grouped(x, g, R, S, st, pad, groups))
     scale = np.sum(np.abs(y * g))
     assert abs(a - b) <= 1e-12 * scale and abs(a - c) <= 1e-12 * scale
+
+
+# ------------------------------------------------------------------------- bias ---
+def test_bias_closed_forms_and_adjoint():
+    rng = np.random.default_rng(9)
+    N, K, P, Q = 3, 5, 4, 6
+    y = rng.standard_normal((N, K, P, Q))
+    b = rng.standard_normal(K)
+    out = oracle.bias_fwd(y, b)
+    # element by element against the definition, and exact on integers
+    for n, k, p, q in [(0, 0, 0, 0), (2, 4, 3, 5), (1, 2, 1, 3)]:
+        assert out[n, k, p, q] == y[n, k, p, q] + b[k]
+    yi = rng.integers(-5, 6, (N, K, P, Q)).astype(np.float64)
+    bi = rng.integers(-5, 6, K).astype(np.float64)
+    assert np.array_equal(oracle.bias_fwd(yi, bi) - yi, np.broadcast_to(bi[None, :, None, None], yi.shape))
+    # gradient: all-ones closed form, a single non-zero entry, integers against a brute-force loop
+    assert np.array_equal(oracle.bias_bwd(np.ones((N, K, P, Q))), np.full(K, N * P * Q, dtype=np.float64))
+    d = np.zeros((N, K, P, Q)); d[1, 3, 2, 4] = 2.5
+    assert np.array_equal(oracle.bias_bwd(d), np.array([0, 0, 0, 2.5, 0]))
+    gi = rng.integers(-5, 6, (N, K, P, Q)).astype(np.float64)
+    brute = [sum(gi[n, k, p, q] for n in range(N) for p in range(P) for q in range(Q)) for k in range(K)]
+    assert np.array_equal(oracle.bias_bwd(gi), np.array(brute))
+    # adjoint of the forward's dependence on b: <bias_fwd(0, b), g> = <b, bias_bwd(g)>
+    g = rng.standard_normal((N, K, P, Q))
+    lhs = np.sum(oracle.bias_fwd(np.zeros_like(g), b) * g)
+    assert abs(lhs - np.dot(b, oracle.bias_bwd(g))) <= 1e-12 * np.sum(np.abs(g))
