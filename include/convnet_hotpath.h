@@ -208,6 +208,18 @@ int relu_maxpool3x3s2_bwd(const void *x, const void *dy, void *dx, int64_t plane
                           void *stream);
 
 /*
+ * Bias of a convolutional layer: one fp32 value per filter.
+ *   bias_fwd: y[n][k][:] += b[k], in place on y [N][K][PQ] (dtype = element type
+ *             of y as for the glue layers; b is always fp32).
+ *   bias_bwd: db[k] = sum over n and positions of dy[n][k][:], fp32, summed in a
+ *             fixed order; needs bias_bwd_workspace_bytes(N, K) bytes of scratch
+ *             (256-byte aligned).  N*K*PQ must stay below 2^31.
+ */
+int bias_fwd(void *y, const void *b, int N, int K, int PQ, int dtype, void *stream);
+int bias_bwd(const void *dy, void *db, int N, int K, int PQ, int dtype, void *ws, size_t ws_bytes, void *stream);
+size_t bias_bwd_workspace_bytes(int N, int K);
+
+/*
  * fp32 -> bfloat16 with round-to-nearest-even, for callers that hold fp32 data
  * (network input, filters after an fp32 update, fp32 results of CONV_DTYPE_BF16
  * passes) and feed bf16 layers.  dst holds `count` 2-byte values; device pointers.

@@ -26,6 +26,7 @@ EXPORTS = (
     "conv_workspace_bytes", "conv_status_string", "conv_last_hip_error",
     "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
     "relu_maxpool3x3s2_fwd", "relu_maxpool3x3s2_bwd", "convert_f32_to_bf16",
+    "bias_fwd", "bias_bwd", "bias_bwd_workspace_bytes",
 )
 
 _lib = None
@@ -66,6 +67,12 @@ def lib():
     L.conv_workspace_bytes_grouped.restype = sz
     L.conv_workspace_bytes.argtypes = [i] + dims + [i]
     L.conv_workspace_bytes.restype = sz
+    L.bias_fwd.argtypes = [vp, vp, i, i, i, i, vp]
+    L.bias_fwd.restype = i
+    L.bias_bwd.argtypes = [vp, vp, i, i, i, i, vp, sz, vp]
+    L.bias_bwd.restype = i
+    L.bias_bwd_workspace_bytes.argtypes = [i, i]
+    L.bias_bwd_workspace_bytes.restype = sz
     L.conv_status_string.argtypes = [i]
     L.conv_status_string.restype = ctypes.c_char_p
     L.conv_last_hip_error.argtypes = []
@@ -324,6 +331,28 @@ def relu_maxpool3x3s2_fwd(x, y=None, stream=None):
 
 def relu_maxpool3x3s2_bwd(x, dy, dx=None, stream=None):
     return _pool_bwd("relu_maxpool3x3s2_bwd", x, dy, dx, stream)
+
+
+def bias_fwd(y, b, stream=None):
+    """y [N,K,P,Q] += b[k] in place (b fp32)."""
+    N, K, P, Q = y.shape
+    if not y.is_contiguous() or b.dtype != torch.float32 or b.numel() != K:
+        raise ValueError("bias_fwd takes a dense y and one fp32 value per filter")
+    _check(lib().bias_fwd(_ptr(y), _ptr(b), N, K, P * Q, _dtype_of(y), _stream_handle(stream)), "bias_fwd")
+    return y
+
+
+def bias_bwd(dy, db=None, ws=None, stream=None):
+    """db[k] = sum of dy [N,K,P,Q] over samples and positions, fp32."""
+    N, K, P, Q = dy.shape
+    if not dy.is_contiguous():
+        raise ValueError("bias_bwd takes a dense dy")
+    if db is None:
+        db = torch.empty((K,), dtype=torch.float32, device=dy.device)
+    buf, nbytes = _ws(ws).get(int(lib().bias_bwd_workspace_bytes(N, K)))
+    _check(lib().bias_bwd(_ptr(dy), _ptr(db), N, K, P * Q, _dtype_of(dy), ctypes.c_void_p(buf.data_ptr()), nbytes,
+                          _stream_handle(stream)), "bias_bwd")
+    return db
 
 
 def convert_f32_to_bf16(src, dst=None, stream=None):

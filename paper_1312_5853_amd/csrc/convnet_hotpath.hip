@@ -2419,6 +2419,50 @@ __global__ void relu_bwd_kernel(const T *__restrict__ x, const T *__restrict__ d
     }
 }
 
+// y[n][k][:] += b[k], in place; one thread per element (bf16 tensors: fp32 add, result rounded once)
+template <typename T>
+__global__ void bias_fwd_kernel(T *__restrict__ y, const float *__restrict__ b, int64_t total, int K, FastDiv div_pq,
+                                FastDiv div_k)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const uint32_t plane = fastdiv((uint32_t)i, div_pq);             // n * K + k
+    const uint32_t k = plane - fastdiv(plane, div_k) * (uint32_t)K;
+    st_elem(y, i, ld_elem(y, i) + b[k]);
+}
+
+// Bias gradient, first stage: work-group (k, s) adds dy[n][k][:] over the samples n = s, s + nsplit, ... in a
+// fixed order (thread t takes positions t, t + 256, ...; then a tree over the 256 thread sums) -> part[k][s]
+template <typename T>
+__global__ __launch_bounds__(256) void bias_bwd_partial(const T *__restrict__ dy, float *__restrict__ part, int N,
+                                                         int K, int PQ, int nsplit)
+{
+    __shared__ float red[256];
+    const int k = blockIdx.x, sidx = blockIdx.y, tid = threadIdx.x;
+    float acc = 0.f;
+    for (int n = sidx; n < N; n += nsplit) {
+        const T *row = dy + ((int64_t)n * K + k) * PQ;
+        for (int e = tid; e < PQ; e += 256) acc += ld_elem(row, e);
+    }
+    red[tid] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (tid < w) red[tid] += red[tid + w];
+        __syncthreads();
+    }
+    if (tid == 0) part[k * nsplit + sidx] = red[0];
+}
+
+// second stage: db[k] = part[k][0] + part[k][1] + ...
+__global__ void bias_bwd_finish(const float *__restrict__ part, float *__restrict__ db, int K, int nsplit)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    float s = 0.f;
+    for (int t = 0; t < nsplit; ++t) s += part[k * nsplit + t];
+    db[k] = s;
+}
+
 // index (within the plane) of the first maximum of the 3x3 window at (2i, 2j)
 template <typename T>
 __device__ __forceinline__ int pool_argmax(const T *__restrict__ xp, int W, int i, int j, float &m)
@@ -3381,6 +3425,62 @@ int convert_f32_to_bf16(const void *src, void *dst, int64_t count, void *stream)
     if (!aligned(src, 4) || !aligned(dst, 2)) return kErrMisaligned;
     hipLaunchKernelGGL(narrow_to_bf16, dim3(grid1d(count, 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const float *>(src), static_cast<unsigned short *>(dst), count);
+    return check_launch();
+}
+
+// samples per filter are spread over this many work-groups in the bias gradient (about 2048 work-groups)
+static int bias_splits(int N, int K)
+{
+    int s = 2048 / K;
+    if (s < 1) s = 1;
+    return s < N ? s : N;
+}
+
+size_t bias_bwd_workspace_bytes(int N, int K)
+{
+    if (N <= 0 || K <= 0) return 0;
+    return (size_t)K * bias_splits(N, K) * 4;
+}
+
+int bias_fwd(void *y, const void *b, int N, int K, int PQ, int dtype, void *stream)
+{
+    if (!y || !b || N <= 0 || K <= 0 || PQ <= 0) return kErrInvalidArg;
+    const int eb = glue_elem_bytes(dtype);
+    if (!eb) return kErrBadDtype;
+    const int64_t total = (int64_t)N * K * PQ;
+    if (total >= ((int64_t)1 << 31)) return kErrTooLarge;
+    if (!aligned(y, eb) || !aligned(b, 4)) return kErrMisaligned;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const FastDiv dpq = make_fastdiv((uint32_t)PQ), dk = make_fastdiv((uint32_t)K);
+    if (eb == 4)
+        hipLaunchKernelGGL(bias_fwd_kernel<float>, dim3(grid1d(total, 256)), dim3(256), 0, st, static_cast<float *>(y),
+                           static_cast<const float *>(b), total, K, dpq, dk);
+    else
+        hipLaunchKernelGGL(bias_fwd_kernel<unsigned short>, dim3(grid1d(total, 256)), dim3(256), 0, st,
+                           static_cast<unsigned short *>(y), static_cast<const float *>(b), total, K, dpq, dk);
+    return check_launch();
+}
+
+int bias_bwd(const void *dy, void *db, int N, int K, int PQ, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!dy || !db || N <= 0 || K <= 0 || PQ <= 0) return kErrInvalidArg;
+    const int eb = glue_elem_bytes(dtype);
+    if (!eb) return kErrBadDtype;
+    if ((int64_t)N * K * PQ >= ((int64_t)1 << 31)) return kErrTooLarge;
+    if (!aligned(dy, eb) || !aligned(db, 4)) return kErrMisaligned;
+    if (!ws || ws_bytes < bias_bwd_workspace_bytes(N, K)) return kErrWorkspace;
+    if (!aligned(ws, 256)) return kErrMisaligned;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int nsplit = bias_splits(N, K);
+    float *part = static_cast<float *>(ws);
+    if (eb == 4)
+        hipLaunchKernelGGL(bias_bwd_partial<float>, dim3(K, nsplit), dim3(256), 0, st, static_cast<const float *>(dy),
+                           part, N, K, PQ, nsplit);
+    else
+        hipLaunchKernelGGL(bias_bwd_partial<unsigned short>, dim3(K, nsplit), dim3(256), 0, st,
+                           static_cast<const unsigned short *>(dy), part, N, K, PQ, nsplit);
+    hipLaunchKernelGGL(bias_bwd_finish, dim3(grid1d(K, 256)), dim3(256), 0, st, part, static_cast<float *>(db), K,
+                       nsplit);
     return check_launch();
 }
 

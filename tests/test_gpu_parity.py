@@ -587,3 +587,26 @@ def test_bf16_glue_matches_oracle():
         f = lambda t: t.float().cpu().numpy()
         assert np.array_equal(f(hp.relu_fwd(xd)), oracle.relu_fwd(x[off:]).astype(np.float32))
         assert np.array_equal(f(hp.relu_bwd(xd, gd)), oracle.relu_bwd(x[off:], g[off:]).astype(np.float32))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_bias_forward_and_gradient(dtype):
+    for (N, K, P, Q) in [(3, 5, 7, 9), (128, 96, 55, 55), (2, 300, 1, 1), (1, 1, 3, 3), (9, 2500, 2, 3)]:
+        y = synth.gaussian((N, K, P, Q), 181)
+        b = synth.gaussian((K,), 182)
+        if dtype == "bf16":
+            y = synth.to_bf16_grid(y)
+        got = hp.bias_fwd(dev(y, dtype), dev(b))
+        want = oracle.bias_fwd(y, b)
+        if dtype == "f32":
+            assert np.array_equal(got.cpu().numpy(), (y + b[None, :, None, None]).astype(np.float32))   # one fp32 add
+            assert norm_err(got.cpu().numpy(), want) <= 1e-6
+        else:
+            assert norm_err(got.float().cpu().numpy(), want) <= 2.0 ** -8                                 # one rounding
+        db = hp.bias_bwd(dev(y, dtype))
+        ref = oracle.bias_bwd(y)
+        scale = np.abs(y.astype(np.float64)).sum(axis=(0, 2, 3)).max()
+        assert np.abs(db.cpu().numpy() - ref).max() <= 1e-6 * scale
+        assert torch.equal(db, hp.bias_bwd(dev(y, dtype)))                                               # fixed order
+    yi = synth.small_integers((4, 6, 5, 5), 183)
+    assert np.array_equal(hp.bias_bwd(dev(yi, dtype)).cpu().numpy(), oracle.bias_bwd(yi))

@@ -192,3 +192,18 @@ def test_grouped_argument_checks(lib):
         one = lib.conv_workspace_bytes(op, 4, 48, 27, 27, 128, 5, 5, 1, 2, 0)
         assert two > one and lib.conv_workspace_bytes_grouped(op, *dims, 1, 0) == lib.conv_workspace_bytes(op, *dims, 0)
     assert lib.conv_workspace_bytes_grouped(0, *dims, 7, 0) == 0
+
+
+def test_bias_argument_checks(lib):
+    from paper_1312_5853_amd import binding as b
+    assert lib.bias_fwd(None, PTR, 2, 3, 4, 0, None) == b.ERR_INVALID_ARG
+    assert lib.bias_fwd(PTR, PTR, 0, 3, 4, 0, None) == b.ERR_INVALID_ARG
+    assert lib.bias_fwd(PTR, PTR, 2, 3, 4, 5, None) == b.ERR_BAD_DTYPE
+    assert lib.bias_fwd(PTR + 2, PTR, 2, 3, 4, 0, None) == b.ERR_MISALIGNED
+    assert lib.bias_fwd(PTR, PTR, 1 << 15, 1 << 10, 1 << 7, 0, None) == b.ERR_TOO_LARGE
+    need = lib.bias_bwd_workspace_bytes(128, 96)
+    assert need == 96 * 21 * 4 and lib.bias_bwd_workspace_bytes(0, 96) == 0
+    assert lib.bias_bwd(PTR, PTR, 128, 96, 3025, 0, PTR, need - 1, None) == b.ERR_WORKSPACE
+    assert lib.bias_bwd(PTR, PTR, 128, 96, 3025, 0, None, need, None) == b.ERR_WORKSPACE
+    assert lib.bias_bwd(PTR, None, 128, 96, 3025, 0, PTR, need, None) == b.ERR_INVALID_ARG
+    assert lib.bias_bwd(PTR, PTR, 128, 96, 3025, 0, PTR + 16, need, None) == b.ERR_MISALIGNED
