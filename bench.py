@@ -90,6 +90,36 @@ def bf16_layers(N, hp, synth, conv_flops, torch, reps=10):
     return out
 
 
+def two_column_layers(N, hp, synth, conv_flops, torch, reps=10):
+    """conv4 / conv5 as the paper's two model-parallel columns without cross-connection (groups = 2: 192 -> 192 and
+    192 -> 128 per column), fp32, per-pass timings of the grouped calls (HIP events)."""
+    out = {}
+    for layer in ("conv4", "conv5"):
+        L = synth.LAYERS[layer]
+        x, w, dy = (torch.from_numpy(a).cuda() for a in synth.layer_tensors(layer, N))
+        w = w[:, :L["C"] // 2].contiguous()                      # [K, C/2, R, S]: each filter reads its column only
+        y, dx, dw = torch.empty_like(dy), torch.empty_like(x), torch.empty_like(w)
+        calls = {
+            "fwd": lambda: hp.conv_fwd_grouped(x, w, L["stride"], L["pad"], 2, y=y),
+            "dgrad": lambda: hp.conv_bwd_data_grouped(dy, w, L["H"], L["W"], L["stride"], L["pad"], 2, dx=dx),
+            "wgrad": lambda: hp.conv_bwd_filter_grouped(x, dy, L["R"], L["S"], L["stride"], L["pad"], 2, dw=dw),
+        }
+        for name, fn in calls.items():
+            for _ in range(3):
+                fn()
+            s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            s.record()
+            for _ in range(reps):
+                fn()
+            e.record()
+            torch.cuda.synchronize()
+            ms = s.elapsed_time(e) / reps
+            tf = conv_flops(N, L) / 2 / ms / 1e9                 # half the multiply-adds of the full-width layer
+            out["%s.%s" % (layer, name)] = {"ms": round(ms, 4), "tflops": round(tf, 1),
+                                            "frac_peak": round(tf / PEAK_FP32_MFMA_TFLOPS, 4)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -168,6 +198,7 @@ def main():
         "flops_per_launch": dom_flops / len(dom_keys),
     }
 
+    columns = two_column_layers(N, hp, synth, conv_flops, torch)
     bf16 = bf16_layers(N, hp, synth, conv_flops, torch)
     # the same step with bf16 convolution inputs (fp32 accumulation and outputs, fp32 glue, conversions included)
     del stack
@@ -196,6 +227,7 @@ def main():
         "conv_only_frac_peak": round(flops / conv_ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
         "per_pass": per_pass,
         "roofline": roofline,
+        "two_column_conv4_conv5_fp32": columns,
         "bf16_in_fp32_acc": bf16,
         "context": "paper: 10.5 days per 100 epochs on one NVIDIA TITAN at batch 256 (whole network, not this path)",
     }
