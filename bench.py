@@ -127,6 +127,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stack-only", action="store_true",
+                    help="only the fp32 stack step (no two-column, bf16 or CPU blocks): the run the profiles are taken on")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build targets one GPU (one data-parallel shard / one model-parallel "
@@ -193,26 +195,28 @@ def main():
         "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
         # HBM bytes per launch of this kernel from rocprofv3 FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00), factors from a
         # 256 MiB copy; collected offline (profiles/stack_n128_fp32_hbm_traffic.txt), valid for the default N = 128
-        "traffic": 122.9e6 if N == 128 else None,
+        "traffic": 123.7e6 if N == 128 else None,
         "launches_per_step": len(dom_keys), "avg_launch_ms": round(dom_ms / len(dom_keys), 4),
         "flops_per_launch": dom_flops / len(dom_keys),
     }
 
-    columns = two_column_layers(N, hp, synth, conv_flops, torch)
-    bf16 = bf16_layers(N, hp, synth, conv_flops, torch)
-    # the same step with bf16 convolution inputs (fp32 accumulation and outputs, fp32 glue, conversions included)
-    del stack
-    bstack = ConvStack(N, dtype="bf16")
-    for _ in range(3):
-        bstack.step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        bstack.step()
-    torch.cuda.synchronize()
-    bf16_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    bf16["stack_ms_per_step"] = round(bf16_ms, 4)
-    bf16["stack_tflops"] = round(flops / bf16_ms / 1e9, 2)
+    columns, bf16 = None, None
+    if not args.stack_only:
+        columns = two_column_layers(N, hp, synth, conv_flops, torch)
+        bf16 = bf16_layers(N, hp, synth, conv_flops, torch)
+        # the same step with bf16 tensors end to end (fp32 accumulation, fp32 filter gradients)
+        del stack
+        bstack = ConvStack(N, dtype="bf16")
+        for _ in range(3):
+            bstack.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            bstack.step()
+        torch.cuda.synchronize()
+        bf16_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        bf16["stack_ms_per_step"] = round(bf16_ms, 4)
+        bf16["stack_tflops"] = round(flops / bf16_ms / 1e9, 2)
 
     value = flops / ms_per_step / 1e9
     out = {
@@ -231,7 +235,7 @@ def main():
         "bf16_in_fp32_acc": bf16,
         "context": "paper: 10.5 days per 100 epochs on one NVIDIA TITAN at batch 256 (whole network, not this path)",
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.stack_only:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
 
