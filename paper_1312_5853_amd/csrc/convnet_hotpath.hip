@@ -1221,8 +1221,8 @@ __global__ void relayout_filters_cblk(const float *__restrict__ w, float *__rest
 // ---------------------------------------------------------------------------
 struct PatchArgs {
     const float *At;      // filters [chunk][Mpad][16], g in (c, r, s) order, zero padded
-    const float *x;
-    float *y;
+    const void *x;        // fp32 or bfloat16 (the kernel's TI)
+    void *y;              // fp32 or bfloat16 (the kernel's TO)
     int M, Mpad, nchunks;
     int C, H, W, R, S, stride, pad;
     int P, Q, PQ;
@@ -1234,7 +1234,7 @@ struct PatchArgs {
     FastDiv div_q, div_rs, div_s, div_mj, div_m, div_wp, div_nr;
 };
 
-template <int TM>
+template <int TM, typename TI, typename TO>
 __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs p)
 {
     constexpr int BM = TM * 32, BN = 128;
@@ -1266,7 +1266,7 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
     // --- stage the patch: row (c, i) <- x[n][c][h0 + i][:], zero outside the image
     {
         // 32 independent loads in flight per thread and batch (the first layer's patch is ~60 values per thread)
-        const float *xn = p.x + (size_t)n * p.x_bs;
+        const TI *xn = static_cast<const TI *>(p.x) + (size_t)n * p.x_bs;
         const int total = p.C * p.NR * p.WP;
         for (int e0 = tid; e0 < total; e0 += kThreads * 32) {
             float tmp[32];
@@ -1279,7 +1279,7 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
                 const int c = (int)fastdiv((uint32_t)row, p.div_nr);
                 const int h = h0 + row - c * p.NR, w = v - p.pad;
                 const bool ok = ((unsigned)h < (unsigned)p.H) & ((unsigned)w < (unsigned)p.W);
-                const float val = xn[ok ? (c * p.H + h) * p.W + w : 0];
+                const float val = ld_elem(xn, ok ? (c * p.H + h) * p.W + w : 0);
                 tmp[u] = ok ? val : 0.f;
             }
 #pragma unroll
@@ -1406,14 +1406,14 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
     }
 
     if (!jok) return;
-    float *out = p.y + (size_t)n * p.y_bs + j;
+    TO *out = static_cast<TO *>(p.y) + (size_t)n * p.y_bs + j;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row0 = m0 + i * 32 + half * 4;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = row0 + (v >> 2) * 8 + (v & 3);
-            if (row < p.M) out[(size_t)row * p.PQ] = acc[i][v];
+            if (row < p.M) st_elem(out, (int64_t)row * p.PQ, acc[i][v]);
         }
     }
 }
@@ -1422,8 +1422,8 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
 // Backward-filter: dw[k][g] = sum_j dy[k][j] * im2col(x)[g][j],  j = (n, p, q)
 // ---------------------------------------------------------------------------
 struct WgradArgs {
-    const float *dy;
-    const float *x;
+    const void *dy;       // fp32 or bfloat16 (the kernel's TI), both inputs alike
+    const void *x;
     const int4 *tab;      // forward-style tap table over g = (c, r, s)
     float *out;           // dw, or partial sums [split][K][CRS]
     int K, CRS;
@@ -1435,11 +1435,12 @@ struct WgradArgs {
     FastDiv div_plane, div_q;
 };
 
-template <int TM, int TN, int WM, int WN>
+template <int TM, int TN, int WM, int WN, typename TI>
 __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
 {
     constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
     constexpr int RA = BM / 16, RB = BN / 16;    // rows per thread per step
+    constexpr int EB = (int)sizeof(TI);          // bytes per input element
     static_assert(WM * WN == 4, "four waves per work-group");
 
     __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
@@ -1463,7 +1464,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
         const int4 tap = p.tab[n0 + g + 16 * i];     // table is padded past CRS with failing taps
-        boff[i] = tap.x; bdr[i] = tap.y; bds[i] = tap.z;
+        boff[i] = tap.x / 4 * EB; bdr[i] = tap.y; bds[i] = tap.z;     // the table holds byte offsets of fp32 elements
     }
 
     const int jbeg = split * p.chunks_per_split * kChunk;
@@ -1489,21 +1490,21 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
         const int qq = pq - pp * p.Q;
         const int hb0 = pp * p.stride - p.pad;
         wb = qq * p.stride - p.pad;
-        abase = 4 * (n * p.dy_bs + pq);                  // bytes
-        bbase = 4 * (n * p.x_bs + hb0 * p.W + wb);
+        abase = EB * (n * p.dy_bs + pq);                 // bytes
+        bbase = EB * (n * p.x_bs + hb0 * p.W + wb);
         hb = jok ? hb0 : kInvalidTap;
         jnext += kChunk;
     };
     auto slot_a = [&](int set, int i) {
         const int k = m0 + g + 16 * i;
         const bool ok = jok & (k < p.K);
-        areg[set][i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(ok ? abase + 4 * k * PQ : 0));
+        areg[set][i] = ld_elem(reinterpret_cast<const TI *>(dy_bytes + (uint32_t)(ok ? abase + EB * k * PQ : 0)), 0);
         aok[set][i] = ok;
     };
     auto slot_b = [&](int set, int i) {
         const int hh = hb + bdr[i], ww = wb + bds[i];
         const bool ok = ((unsigned)hh < (unsigned)p.H) & ((unsigned)ww < (unsigned)p.W);
-        breg[set][i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0));
+        breg[set][i] = ld_elem(reinterpret_cast<const TI *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0)), 0);
         bok[set][i] = ok;
     };
     auto load_step = [&](int set) {
@@ -2740,15 +2741,26 @@ void launch_colgemm_fast(const TileShape &t, int kc, const ColGemmFastArgs &a, c
     else launch_dyn(colgemm_fast_kernel<1, 2, 1, 4, 16>, a, g.grid, lds, st);
 }
 
-void launch_patch(int tm, const PatchArgs &a, int grid, int lds, hipStream_t st)
+template <typename TI, typename TO>
+void launch_patch_typed(int tm, const PatchArgs &a, int grid, int lds, hipStream_t st)
 {
-    const void *k = tm == 1 ? (const void *)colgemm_patch_kernel<1> : tm == 2 ? (const void *)colgemm_patch_kernel<2>
-                  : tm == 3 ? (const void *)colgemm_patch_kernel<3> : (const void *)colgemm_patch_kernel<4>;
+    const void *k = tm == 1 ? (const void *)colgemm_patch_kernel<1, TI, TO>
+                  : tm == 2 ? (const void *)colgemm_patch_kernel<2, TI, TO>
+                  : tm == 3 ? (const void *)colgemm_patch_kernel<3, TI, TO>
+                            : (const void *)colgemm_patch_kernel<4, TI, TO>;
     if (lds > 64 * 1024) (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (tm == 1) hipLaunchKernelGGL(colgemm_patch_kernel<1>, dim3(grid), dim3(kThreads), lds, st, a);
-    else if (tm == 2) hipLaunchKernelGGL(colgemm_patch_kernel<2>, dim3(grid), dim3(kThreads), lds, st, a);
-    else if (tm == 3) hipLaunchKernelGGL(colgemm_patch_kernel<3>, dim3(grid), dim3(kThreads), lds, st, a);
-    else hipLaunchKernelGGL(colgemm_patch_kernel<4>, dim3(grid), dim3(kThreads), lds, st, a);
+    if (tm == 1) hipLaunchKernelGGL((colgemm_patch_kernel<1, TI, TO>), dim3(grid), dim3(kThreads), lds, st, a);
+    else if (tm == 2) hipLaunchKernelGGL((colgemm_patch_kernel<2, TI, TO>), dim3(grid), dim3(kThreads), lds, st, a);
+    else if (tm == 3) hipLaunchKernelGGL((colgemm_patch_kernel<3, TI, TO>), dim3(grid), dim3(kThreads), lds, st, a);
+    else hipLaunchKernelGGL((colgemm_patch_kernel<4, TI, TO>), dim3(grid), dim3(kThreads), lds, st, a);
+}
+
+// in_bf16 / out_bf16: element types of x and y
+void launch_patch(int tm, const PatchArgs &a, int grid, int lds, bool in_bf16, bool out_bf16, hipStream_t st)
+{
+    if (!in_bf16) launch_patch_typed<float, float>(tm, a, grid, lds, st);
+    else if (!out_bf16) launch_patch_typed<unsigned short, float>(tm, a, grid, lds, st);
+    else launch_patch_typed<unsigned short, unsigned short>(tm, a, grid, lds, st);
 }
 
 template <int KC>
@@ -2775,12 +2787,20 @@ void launch_colgemm_bf16(const TileShape &t, int kc, const ColGemmFastArgs &a, c
     else launch_colgemm_bf16_kc<16>(t, a, g, st);
 }
 
-void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
+template <typename TI>
+void launch_wgrad_typed(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
 {
-    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((wgrad_kernel<2, 2, 2, 2>), dim3(grid), dim3(kThreads), 0, st, a);
-    else if (t.TM == 3) hipLaunchKernelGGL((wgrad_kernel<3, 1, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
-    else if (t.TM == 2) hipLaunchKernelGGL((wgrad_kernel<2, 1, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
-    else hipLaunchKernelGGL((wgrad_kernel<1, 2, 1, 4>), dim3(grid), dim3(kThreads), 0, st, a);
+    const dim3 g(grid), b(kThreads);
+    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((wgrad_kernel<2, 2, 2, 2, TI>), g, b, 0, st, a);
+    else if (t.TM == 3) hipLaunchKernelGGL((wgrad_kernel<3, 1, 1, 4, TI>), g, b, 0, st, a);
+    else if (t.TM == 2) hipLaunchKernelGGL((wgrad_kernel<2, 1, 1, 4, TI>), g, b, 0, st, a);
+    else hipLaunchKernelGGL((wgrad_kernel<1, 2, 1, 4, TI>), g, b, 0, st, a);
+}
+
+void launch_wgrad(const TileShape &t, const WgradArgs &a, int grid, bool in_bf16, hipStream_t st)
+{
+    if (in_bf16) launch_wgrad_typed<unsigned short>(t, a, grid, st);
+    else launch_wgrad_typed<float>(t, a, grid, st);
 }
 
 constexpr int kWgradBf16Depth = 32;     // reduction positions per step of the bf16 backward-filter kernel
@@ -2838,12 +2858,12 @@ int prepare(int op, const void *a, const void *b, void *out, int N, int C, int H
     return kStatusOk;
 }
 
-// fp32 view of an input: the caller's tensor, or (plan says widen) a dense fp32 copy of `batch` samples of
+// fp32 view of an input: the caller's tensor, or (widen, as the plan decided) a dense fp32 copy of `batch` samples of
 // `sample` elements that lie `*bs` elements apart; *bs becomes the copy's stride.
-const float *as_f32(const void *src, int batch, int64_t sample, int64_t *bs, char *ws, const Plan &pl, int slot,
-                    hipStream_t st)
+const float *as_f32(bool widen, const void *src, int batch, int64_t sample, int64_t *bs, char *ws, const Plan &pl,
+                    int slot, hipStream_t st)
 {
-    if (!pl.widen) return static_cast<const float *>(src);
+    if (!widen) return static_cast<const float *>(src);
     float *dst = reinterpret_cast<float *>(ws + pl.cvt_off[slot]);
     const int64_t count = batch * sample;
     hipLaunchKernelGGL(widen_bf16, dim3(grid1d(count, 256)), dim3(256), 0, st,
@@ -2887,11 +2907,11 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
     const bool fwd = op == kOpFwd;
     const int Cr = fwd ? pb.C : pb.K;          // channels of the gathered tensor
     const bool fast = Cr % kChunk == 0 && (fwd || pb.stride == 1);
-    const bool bf = pb.dtype == kDtypeBf16 && !pl.widen;     // bf16 MFMA kernel reads the caller's tensors directly
+    const bool bf = pb.dtype == kDtypeBf16 && !pl.widen_w;   // bf16 MFMA kernel reads the caller's tensors directly
     int64_t w_bs = (int64_t)pb.K * pb.C * RS;
-    const float *actf = fwd ? as_f32(act, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st)
-                            : as_f32(act, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 0, st);
-    const float *wf = as_f32(w, 1, w_bs, &w_bs, wsb, pl, 1, st);
+    const float *actf = fwd ? as_f32(pl.widen, act, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st)
+                            : as_f32(pl.widen, act, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 0, st);
+    const float *wf = as_f32(pl.widen_w, w, 1, w_bs, &w_bs, wsb, pl, 1, st);
 
     if (fast) {
         const int kc = bf ? bf16_step_channels(Cr) : pl.kc;
@@ -2962,38 +2982,31 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
                                    make_fastdiv((uint32_t)per_sample));
         return check_launch();
     }
-    // forward with few channels: stage the input rows once per work-group when they fit in LDS
-    if (fwd) {
-        const int tm = pl.M <= 32 ? 1 : pl.M <= 64 ? 2 : pl.M <= 96 ? 3 : 4;
-        const int bm = tm * 32, mpad = round_up(pl.M, bm);
+    // forward with few channels: the input rows of a tile are staged once in LDS (reads fp32 or bf16 itself and
+    // writes the caller's output type)
+    if (pl.patch) {
+        const int tm = pl.patch_tm, bm = tm * 32, mpad = round_up(pl.M, bm);
         const int PQ = pb.P * pb.Q;
-        int span = (pb.Q + 126) / pb.Q;                 // output rows a 128-position tile can straddle, minus one
-        if (span > pb.P - 1) span = pb.P - 1;
-        const int NR = span * pb.stride + pb.R;
-        const int WP = round_up(std::max(pb.W + 2 * pb.pad, (pb.Q - 1) * pb.stride + pb.S), 4);
-        const int64_t lds64 = ((int64_t)2 * bm * kPitch + pl.Kgpad + (int64_t)pb.C * NR * WP) * 4;
-        if (lds64 <= 80 * 1024 && (int64_t)mpad * pl.Kgpad * 4 <= (int64_t)pl.wt_bytes) {
-            hipLaunchKernelGGL(relayout_filters, dim3(grid1d((int64_t)mpad * pl.Kgpad, 256)), dim3(256), 0, st, wf, wt,
-                               pl.M, mpad, pl.Kg, pl.Kgpad, pb.C, RS, 0);
-            PatchArgs a;
-            a.At = wt; a.x = actf; a.y = static_cast<float *>(out);
-            a.M = pl.M; a.Mpad = mpad; a.nchunks = pl.Kgpad / kChunk;
-            a.C = pb.C; a.H = pb.H; a.W = pb.W; a.R = pb.R; a.S = pb.S; a.stride = pb.stride; a.pad = pb.pad;
-            a.P = pb.P; a.Q = pb.Q; a.PQ = PQ; a.NR = NR; a.WP = WP; a.Kg = pl.Kg; a.Kgpad = pl.Kgpad;
-            a.x_bs = (int)pb.x_bs; a.y_bs = (int)pb.y_bs;
-            a.mtiles = mpad / bm; a.jtiles = ceil_div(PQ, 128);
-            a.ntiles = pb.N * a.mtiles * a.jtiles;
-            a.tiles_per_xcd = ceil_div(a.ntiles, 8);
-            a.div_q = make_fastdiv((uint32_t)pb.Q);
-            a.div_rs = make_fastdiv((uint32_t)RS);
-            a.div_s = make_fastdiv((uint32_t)pb.S);
-            a.div_mj = make_fastdiv((uint32_t)(a.mtiles * a.jtiles));
-            a.div_m = make_fastdiv((uint32_t)a.mtiles);
-            a.div_wp = make_fastdiv((uint32_t)WP);
-            a.div_nr = make_fastdiv((uint32_t)NR);
-            launch_patch(tm, a, 8 * a.tiles_per_xcd, (int)lds64, st);
-            return check_launch();
-        }
+        hipLaunchKernelGGL(relayout_filters, dim3(grid1d((int64_t)mpad * pl.Kgpad, 256)), dim3(256), 0, st, wf, wt,
+                           pl.M, mpad, pl.Kg, pl.Kgpad, pb.C, RS, 0);
+        PatchArgs a;
+        a.At = wt; a.x = act; a.y = out;
+        a.M = pl.M; a.Mpad = mpad; a.nchunks = pl.Kgpad / kChunk;
+        a.C = pb.C; a.H = pb.H; a.W = pb.W; a.R = pb.R; a.S = pb.S; a.stride = pb.stride; a.pad = pb.pad;
+        a.P = pb.P; a.Q = pb.Q; a.PQ = PQ; a.NR = pl.patch_nr; a.WP = pl.patch_wp; a.Kg = pl.Kg; a.Kgpad = pl.Kgpad;
+        a.x_bs = (int)pb.x_bs; a.y_bs = (int)pb.y_bs;
+        a.mtiles = mpad / bm; a.jtiles = ceil_div(PQ, 128);
+        a.ntiles = pb.N * a.mtiles * a.jtiles;
+        a.tiles_per_xcd = ceil_div(a.ntiles, 8);
+        a.div_q = make_fastdiv((uint32_t)pb.Q);
+        a.div_rs = make_fastdiv((uint32_t)RS);
+        a.div_s = make_fastdiv((uint32_t)pb.S);
+        a.div_mj = make_fastdiv((uint32_t)(a.mtiles * a.jtiles));
+        a.div_m = make_fastdiv((uint32_t)a.mtiles);
+        a.div_wp = make_fastdiv((uint32_t)pl.patch_wp);
+        a.div_nr = make_fastdiv((uint32_t)pl.patch_nr);
+        launch_patch(tm, a, 8 * a.tiles_per_xcd, pl.patch_lds, pb.dtype == kDtypeBf16, pb.out_bf16, st);
+        return check_launch();
     }
     if (fwd)
         hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len,
@@ -3038,7 +3051,7 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
     int4 *tab = reinterpret_cast<int4 *>(wsb + pl.tab_off);
     const int RS = pb.R * pb.S;
     // bf16 MFMA kernel: reads the caller's bf16 tensors directly (128-column tiles only)
-    const bool bf = pb.dtype == kDtypeBf16 && !pl.widen;
+    const bool bf = pb.dtype == kDtypeBf16 && !pl.widen && pb.C % kChunk == 0;     // bf16 MFMA kernel
     if (pl.lin) {
         // same-extent stride-1 layer: pack both tensors, then every operand is a 16-byte load
         unsigned short *dyp = reinterpret_cast<unsigned short *>(wsb + pl.lin_dy_off);
@@ -3074,8 +3087,8 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
                            pb.K, pb.C, RS, pl.nsplit, 1);
         return check_launch();
     }
-    const float *xf = as_f32(x, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st);
-    const float *dyf = as_f32(dy, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 1, st);
+    const float *xf = as_f32(pl.widen, x, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st);
+    const float *dyf = as_f32(pl.widen, dy, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 1, st);
     if (pb.C % kChunk == 0) {
         WgradFastArgs a;
         a.dy = dyf; a.x = xf; a.part = reinterpret_cast<float *>(wsb + pl.part_off);
@@ -3121,7 +3134,8 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
     a.ntiles = ceil_div(pl.Kg, pl.tile.bn());
     a.div_plane = make_fastdiv((uint32_t)(pb.P * pb.Q));
     a.div_q = make_fastdiv((uint32_t)pb.Q);
-    launch_wgrad(pl.tile, a, a.mtiles * a.ntiles * pl.nsplit, st);
+    // the table kernel reads fp32 or bf16 inputs itself
+    launch_wgrad(pl.tile, a, a.mtiles * a.ntiles * pl.nsplit, pb.dtype == kDtypeBf16, st);
     int rc = check_launch();
     if (rc != kStatusOk) return rc;
     if (pl.nsplit > 1) {

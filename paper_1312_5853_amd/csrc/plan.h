@@ -129,7 +129,12 @@ struct Plan {
     size_t tab_off, tab_bytes;
     size_t wt_off, wt_bytes;          // re-laid-out filters (fwd, dgrad)
     size_t part_off, part_bytes;      // wgrad partials
-    bool widen;                       // bf16 inputs are widened to dense fp32 copies first (no bf16 kernel for the shape)
+    bool widen;                       // bf16 activation-side inputs are widened to dense fp32 copies first
+    bool widen_w;                     // bf16 filters are widened to fp32 first (forward, backward-data)
+    // forward with few channels: the input rows of a 128-position tile are staged once in LDS (patch kernel),
+    // row tile of patch_tm * 32 filters, patch_nr rows of pitch patch_wp per channel, patch_lds bytes of LDS
+    bool patch;
+    int patch_tm, patch_nr, patch_wp, patch_lds;
     size_t cvt_off[2], cvt_bytes[2];  // bf16 -> fp32 staging of the two inputs
     size_t blk_off, blk_bytes;        // channel-blocked copy of the gathered bf16 tensor (forward, backward-data)
     size_t stage_off, stage_bytes;    // dense fp32 result of forward / backward-data before it is rounded to bf16
@@ -249,29 +254,50 @@ inline Plan make_plan(int op, const Problem &pb)
         if (pl.chunks_per_split == 0) pl.chunks_per_split = pl.Kgpad / kChunk;
     }
     // bf16 inputs go straight to the bf16 MFMA kernels where the gathered channel count is a multiple of 16
-    // (backward-filter: 128-column tiles only); other shapes are widened to dense fp32 copies, batch strides
-    // dropped, and take the fp32 kernels
+    // (backward-filter: 128-column tiles only).  The few-channel kernels (patch forward, table backward-filter)
+    // read bf16 tensors themselves and only want fp32 filters; every other shape is widened to dense fp32
+    // copies, batch strides dropped, and takes the fp32 kernels.
     const int Cr = op == kOpBwdData ? pb.K : pb.C;
     const bool bf16_kernel = Cr % kChunk == 0 &&
         (op == kOpFwd || (op == kOpBwdData && pb.stride == 1) || (op == kOpBwdFilter && pl.tile.bn() == 128));
-    pl.widen = pb.dtype == kDtypeBf16 && !bf16_kernel;
+    if (op == kOpFwd && !(pb.C % kChunk == 0)) {
+        const int tm = pl.M <= 32 ? 1 : pl.M <= 64 ? 2 : pl.M <= 96 ? 3 : 4;
+        const int bm = tm * 32, mpad = round_up(pl.M, bm);
+        int span = (pb.Q + 126) / pb.Q;                 // output rows a 128-position tile can straddle, minus one
+        if (span > pb.P - 1) span = pb.P - 1;
+        const int nr = span * pb.stride + pb.R;
+        const int need_w = pb.W + 2 * pb.pad > (pb.Q - 1) * pb.stride + pb.S ? pb.W + 2 * pb.pad
+                                                                              : (pb.Q - 1) * pb.stride + pb.S;
+        const int wp = round_up(need_w, 4);
+        const int64_t lds64 = ((int64_t)2 * bm * 20 + pl.Kgpad + (int64_t)pb.C * nr * wp) * 4;
+        if (lds64 <= 80 * 1024 && (int64_t)mpad * pl.Kgpad * 4 <= (int64_t)pl.wt_bytes) {
+            pl.patch = true;
+            pl.patch_tm = tm; pl.patch_nr = nr; pl.patch_wp = wp; pl.patch_lds = (int)lds64;
+        }
+    }
+    const bool bf16_in = pb.dtype == kDtypeBf16;
+    const bool direct = pl.patch || (op == kOpBwdFilter && pb.C % kChunk != 0);   // kernels that read bf16 themselves
+    pl.widen = bf16_in && !bf16_kernel && !direct;
+    pl.widen_w = bf16_in && !bf16_kernel && op != kOpBwdFilter;
     if (pb.dtype == kDtypeBf16 && bf16_kernel && op != kOpBwdFilter) {
         pl.blk_off = off;
         pl.blk_bytes = (size_t)pb.N * Cr * (op == kOpFwd ? pb.H * pb.W : pb.P * pb.Q) * 2;
         off += round_up64(pl.blk_bytes, 256);
     }
-    if (pb.out_bf16 && op != kOpBwdFilter && !bf16_kernel) {
+    if (pb.out_bf16 && op != kOpBwdFilter && !bf16_kernel && !pl.patch) {
         pl.stage_off = off;
         pl.stage_bytes = (size_t)pb.N * (op == kOpFwd ? (size_t)pb.K * pb.P * pb.Q : (size_t)pb.C * pb.H * pb.W) * 4;
         off += round_up64(pl.stage_bytes, 256);
     }
-    if (pl.widen) {
+    if (pl.widen || pl.widen_w) {
         const int64_t x_e = (int64_t)pb.N * pb.C * pb.H * pb.W, y_e = (int64_t)pb.N * pb.K * pb.P * pb.Q;
         const int64_t w_e = (int64_t)pb.K * pb.C * RS;
-        int64_t a = op == kOpFwd ? x_e : (op == kOpBwdData ? y_e : x_e);
-        int64_t b = op == kOpBwdFilter ? y_e : w_e;
-        pl.cvt_off[0] = off; pl.cvt_bytes[0] = (size_t)a * 4; off += round_up64(pl.cvt_bytes[0], 256);
-        pl.cvt_off[1] = off; pl.cvt_bytes[1] = (size_t)b * 4; off += round_up64(pl.cvt_bytes[1], 256);
+        // slot 0: the activation-side input; slot 1: the filters (forward, backward-data) or dy (backward-filter)
+        const int64_t a = op == kOpBwdData ? y_e : x_e;
+        const int64_t b = op == kOpBwdFilter ? y_e : w_e;
+        const bool need0 = pl.widen, need1 = op == kOpBwdFilter ? pl.widen : pl.widen_w;
+        pl.cvt_off[0] = off; pl.cvt_bytes[0] = need0 ? (size_t)a * 4 : 0; off += round_up64(pl.cvt_bytes[0], 256);
+        pl.cvt_off[1] = off; pl.cvt_bytes[1] = need1 ? (size_t)b * 4 : 0; off += round_up64(pl.cvt_bytes[1], 256);
     }
     pl.total = off;
     return pl;

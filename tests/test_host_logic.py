@@ -100,14 +100,16 @@ def test_workspace_bytes(lib):
     # bf16 outputs: written by the bf16 kernels themselves, nothing extra
     for op in (0, 1, 2):
         assert lib.conv_workspace_bytes(op, *dims, 2) == lib.conv_workspace_bytes(op, *dims, 1)
-    odd = [4, 3, 32, 32, 20, 5, 5, 2, 1]                                                     # widened to fp32 copies
-    for op in (0, 1, 2):
-        assert lib.conv_workspace_bytes(op, *odd, 1) > lib.conv_workspace_bytes(op, *odd, 0)
-    # ... and with bf16 outputs their fp32 result is staged (P = Q = 15): forward 4*20*15*15, backward-data 4*3*32*32
+    odd = [4, 3, 32, 32, 20, 5, 5, 2, 1]            # 3 -> 20 channels: no bf16 kernel
     up = lambda v: -(-v // 256) * 256                                       # regions are 256-byte aligned
-    assert lib.conv_workspace_bytes(0, *odd, 2) - lib.conv_workspace_bytes(0, *odd, 1) == up(4 * 20 * 15 * 15 * 4)
-    assert lib.conv_workspace_bytes(1, *odd, 2) - lib.conv_workspace_bytes(1, *odd, 1) == up(4 * 3 * 32 * 32 * 4)
-    assert lib.conv_workspace_bytes(2, *odd, 2) == lib.conv_workspace_bytes(2, *odd, 1)
+    ws = lambda op, dt: lib.conv_workspace_bytes(op, *odd, dt)
+    # forward (few-channel kernel reads bf16 itself): only the filters are widened; bf16 output written directly
+    assert ws(0, 1) - ws(0, 0) == up(20 * 3 * 25 * 4) and ws(0, 2) == ws(0, 1)
+    # backward-data: both inputs widened to fp32 copies, a bf16 output staged in fp32 first
+    assert ws(1, 1) - ws(1, 0) == up(4 * 20 * 15 * 15 * 4) + up(20 * 3 * 25 * 4)
+    assert ws(1, 2) - ws(1, 1) == up(4 * 3 * 32 * 32 * 4)
+    # backward-filter (tap-table kernel reads bf16 itself): nothing extra; its output is fp32 in every mode
+    assert ws(2, 1) == ws(2, 0) == ws(2, 2)
     assert lib.conv_workspace_bytes(3, *dims, 0) == 0
     assert lib.conv_workspace_bytes(0, 0, 256, 13, 13, 384, 3, 3, 1, 1, 0) == 0
 
