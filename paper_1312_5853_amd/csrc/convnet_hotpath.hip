@@ -110,6 +110,8 @@ __device__ __forceinline__ float ld_elem(const unsigned short *p, int64_t i)
 {
     return __uint_as_float((unsigned)p[i] << 16);
 }
+__device__ __forceinline__ float widen_elem(float v) { return v; }
+__device__ __forceinline__ float widen_elem(unsigned short v) { return __uint_as_float((unsigned)v << 16); }
 __device__ __forceinline__ void st_elem(float *p, int64_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void st_elem(unsigned short *p, int64_t i, float v) { p[i] = bf16_round(v); }
 
@@ -1474,7 +1476,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
 
     // register set t & 1 and LDS buffer t & 1 hold step t; loads run two steps ahead and the LDS writes of the
     // next step sit between the matrix instructions of the current one (see colgemm_fast_kernel)
-    float areg[2][RA], breg[2][RB];
+    TI areg[2][RA], breg[2][RB];                 // as loaded; widened when they are written to LDS
     bool aok[2][RA], bok[2][RB];
     const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
     const char *x_bytes = reinterpret_cast<const char *>(p.x);
@@ -1498,13 +1500,13 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
     auto slot_a = [&](int set, int i) {
         const int k = m0 + g + 16 * i;
         const bool ok = jok & (k < p.K);
-        areg[set][i] = ld_elem(reinterpret_cast<const TI *>(dy_bytes + (uint32_t)(ok ? abase + EB * k * PQ : 0)), 0);
+        areg[set][i] = *reinterpret_cast<const TI *>(dy_bytes + (uint32_t)(ok ? abase + EB * k * PQ : 0));
         aok[set][i] = ok;
     };
     auto slot_b = [&](int set, int i) {
         const int hh = hb + bdr[i], ww = wb + bds[i];
         const bool ok = ((unsigned)hh < (unsigned)p.H) & ((unsigned)ww < (unsigned)p.W);
-        breg[set][i] = ld_elem(reinterpret_cast<const TI *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0)), 0);
+        breg[set][i] = *reinterpret_cast<const TI *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0));
         bok[set][i] = ok;
     };
     auto load_step = [&](int set) {
@@ -1515,10 +1517,10 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
         for (int i = 0; i < RB; ++i) slot_b(set, i);
     };
     auto store_a = [&](int set, int i) {
-        As[set][(g + 16 * i) * kPitch + jj] = aok[set][i] ? areg[set][i] : 0.f;
+        As[set][(g + 16 * i) * kPitch + jj] = aok[set][i] ? widen_elem(areg[set][i]) : 0.f;
     };
     auto store_b = [&](int set, int i) {
-        Bs[set][(g + 16 * i) * kPitch + jj] = bok[set][i] ? breg[set][i] : 0.f;
+        Bs[set][(g + 16 * i) * kPitch + jj] = bok[set][i] ? widen_elem(breg[set][i]) : 0.f;
     };
     auto store_step = [&](int set) {
 #pragma unroll
