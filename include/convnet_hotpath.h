@@ -158,6 +158,29 @@ size_t conv_workspace_bytes_grouped(int op, int N, int C, int H, int W, int K, i
                                     int stride, int pad, int groups, int dtype);
 
 /*
+ * Convolution passes with the element-wise layer that follows them applied
+ * where the sums are stored, so that the activation layer makes no pass of its
+ * own over HBM (conv3 and conv4 of the stack are followed by a ReLU without
+ * pooling; bias and ReLU belong to the Krizhevsky architecture the paper
+ * trains).  Dense tensors, one column; workspace as for conv_fwd /
+ * conv_bwd_data with the same extents.
+ *   conv_fwd_bias_relu: y = f(conv_fwd(x, w) + bias[k]), f = max(., 0) if relu = 1,
+ *       identity if relu = 0; bias is fp32 [K] on the device or NULL (no bias).
+ *       The bias is added to the fp32 sum before any rounding to bfloat16.
+ *   conv_bwd_data_relu: dx = conv_bwd_data(dy, w) where act > 0, else 0: the
+ *       gradient with respect to the INPUT of the ReLU whose output (or input)
+ *       act [N][C][H][W] is; act has the element type of dx and is only read.
+ * Both give exactly what the separate calls give for fp32 outputs; for bfloat16
+ * outputs the fused result is rounded once, after the bias.
+ */
+int conv_fwd_bias_relu(const void *x, const void *w, const void *bias, void *y,
+                       int N, int C, int H, int W, int K, int R, int S, int stride, int pad, int relu,
+                       int dtype, void *ws, size_t ws_bytes, void *stream);
+int conv_bwd_data_relu(const void *dy, const void *w, const void *act, void *dx,
+                       int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                       int dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Scratch bytes the given pass needs for these extents (op = CONV_OP_*).
  * Pure host arithmetic; returns 0 for invalid arguments.  The figure depends
  * only on the arguments, never on the device or on earlier calls.

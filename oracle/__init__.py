@@ -28,6 +28,8 @@ from .oracle import (  # noqa: F401
     maxpool3x3s2_bwd,
     bias_fwd,
     bias_bwd,
+    conv_fwd_bias_relu,
+    conv_bwd_data_relu,
     num_threads,
     set_num_threads,
 )

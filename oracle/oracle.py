@@ -243,3 +243,20 @@ def bias_bwd(dy):
     for k in range(dy.shape[1]):
         db[k] = np.sum(dy[:, k])
     return db
+
+
+# A convolutional layer with the element-wise layers that follow it, as the
+# chain of their definitions: bias, then ReLU (forward); the gradient through
+# a ReLU, then nothing else (backward-data: the ReLU in question is the one
+# that FEEDS the layer, so its mask multiplies the layer's input gradient).
+def conv_fwd_bias_relu(x, w, b, stride, pad, relu=True):
+    y = conv_fwd(x, w, stride, pad)
+    if b is not None:
+        y = bias_fwd(y, b)
+    return relu_fwd(y) if relu else y
+
+
+def conv_bwd_data_relu(dy, w, act, stride, pad):
+    act = _f64(act)
+    H, W = act.shape[2], act.shape[3]
+    return relu_bwd(act, conv_bwd_data(dy, w, H, W, stride, pad))

@@ -21,7 +21,7 @@ OP_FWD, OP_BWD_DATA, OP_BWD_FILTER = 0, 1, 2
 
 EXPORTS = (
     "conv_fwd", "conv_bwd_data", "conv_bwd_filter",
-    "conv_fwd_ex", "conv_bwd_data_ex", "conv_bwd_filter_ex",
+    "conv_fwd_ex", "conv_bwd_data_ex", "conv_bwd_filter_ex", "conv_fwd_bias_relu", "conv_bwd_data_relu",
     "conv_fwd_grouped", "conv_bwd_data_grouped", "conv_bwd_filter_grouped", "conv_workspace_bytes_grouped",
     "conv_workspace_bytes", "conv_status_string", "conv_last_hip_error",
     "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
@@ -63,6 +63,10 @@ def lib():
         f = getattr(L, name + "_grouped")
         f.argtypes = [vp, vp, vp] + dims + [i, i, vp, sz, vp]
         f.restype = i
+    L.conv_fwd_bias_relu.argtypes = [vp, vp, vp, vp] + dims + [i, i, vp, sz, vp]
+    L.conv_fwd_bias_relu.restype = i
+    L.conv_bwd_data_relu.argtypes = [vp, vp, vp, vp] + dims + [i, vp, sz, vp]
+    L.conv_bwd_data_relu.restype = i
     L.conv_workspace_bytes_grouped.argtypes = [i] + dims + [i, i]
     L.conv_workspace_bytes_grouped.restype = sz
     L.conv_workspace_bytes.argtypes = [i] + dims + [i]
@@ -209,6 +213,59 @@ def conv_bwd_data(dy, w, H, W, stride, pad, dx=None, ws=None, stream=None, out_b
     dims = (N, C, H, W, K, R, S, stride, pad)
     return _run("conv_bwd_data", OP_BWD_DATA, dy, w, dx, dims, _batch_stride(dx), _batch_stride(dy),
                 _io_dtype(dy, dx), ws, stream)
+
+
+def _dense(*ts):
+    for t in ts:
+        if t is not None and not t.is_contiguous():
+            raise ValueError("this call takes dense tensors")
+
+
+def conv_fwd_bias_relu(x, w, bias, stride, pad, relu=True, y=None, ws=None, stream=None, out_bf16=False):
+    """y = relu(conv_fwd(x, w) + bias[k]) in one call (bias: fp32 [K] or None; relu=False leaves the sum as it is)."""
+    N, C, H, W = x.shape
+    K, Cw, R, S = w.shape
+    if C != Cw:
+        raise ValueError("filter tensor does not match the input")
+    if bias is not None and (bias.dtype != torch.float32 or bias.numel() != K):
+        raise ValueError("bias must hold one fp32 value per filter")
+    P, Q = out_extent(H, R, stride, pad), out_extent(W, S, stride, pad)
+    if y is None:
+        y = torch.empty((N, K, P, Q), dtype=torch.bfloat16 if out_bf16 else torch.float32, device=x.device)
+    _dense(x, w, bias, y)
+    dims = (N, C, H, W, K, R, S, stride, pad)
+    dtype = _io_dtype(x, y)
+    buf, nbytes = _ws(ws).get(workspace_bytes(OP_FWD, *dims, dtype))
+    wsp = ctypes.c_void_p(buf.data_ptr()) if buf is not None else ctypes.c_void_p(0)
+    bp = _ptr(bias) if bias is not None else ctypes.c_void_p(0)
+    rc = lib().conv_fwd_bias_relu(_ptr(x), _ptr(w), bp, _ptr(y), *dims, 1 if relu else 0, dtype, wsp, nbytes,
+                                  _stream_handle(stream))
+    if rc != OK:
+        raise ConvError(rc, "conv_fwd_bias_relu")
+    return y
+
+
+def conv_bwd_data_relu(dy, w, act, stride, pad, dx=None, ws=None, stream=None):
+    """dx = conv_bwd_data(dy, w) where act > 0, else 0 (act [N,C,H,W]: output or input of the ReLU that feeds this
+    layer, element type of dx)."""
+    N, C, H, W = act.shape
+    K, Cw, R, S = w.shape
+    if dy.shape[1] != K or Cw != C:
+        raise ValueError("filter tensor does not match the tensors")
+    if dx is None:
+        dx = torch.empty_like(act)
+    if dx.dtype != act.dtype or dx.shape != act.shape:
+        raise ValueError("act must have the shape and element type of dx")
+    _dense(dy, w, act, dx)
+    dims = (N, C, H, W, K, R, S, stride, pad)
+    dtype = _io_dtype(dy, dx)
+    buf, nbytes = _ws(ws).get(workspace_bytes(OP_BWD_DATA, *dims, dtype))
+    wsp = ctypes.c_void_p(buf.data_ptr()) if buf is not None else ctypes.c_void_p(0)
+    rc = lib().conv_bwd_data_relu(_ptr(dy), _ptr(w), _ptr(act), _ptr(dx), *dims, dtype, wsp, nbytes,
+                                  _stream_handle(stream))
+    if rc != OK:
+        raise ConvError(rc, "conv_bwd_data_relu")
+    return dx
 
 
 def conv_bwd_filter(x, dy, R, S, stride, pad, dw=None, ws=None, stream=None):

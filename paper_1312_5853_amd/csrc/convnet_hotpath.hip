@@ -115,6 +115,45 @@ __device__ __forceinline__ float widen_elem(unsigned short v) { return __uint_as
 __device__ __forceinline__ void st_elem(float *p, int64_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void st_elem(unsigned short *p, int64_t i, float v) { p[i] = bf16_round(v); }
 
+// What a forward / backward-data kernel may apply to each sum before it is stored (in this order):
+//   bias: v += bias[row]        (row = output channel)
+//   relu: v  = max(v, 0)
+//   mask: v  = mask[n][row][pos] > 0 ? v : 0    (mask laid out like the output, samples mask_bs elements apart)
+struct Epilogue {
+    const float *bias;
+    const void *mask;
+    int64_t mask_bs;
+    int relu;
+    int mask_bf16;      // element type of mask: 0 = fp32, 1 = bfloat16
+};
+
+__device__ __forceinline__ float epi_apply(const Epilogue &e, float v, int row, int64_t mask_idx)
+{
+    if (e.bias) v += e.bias[row];
+    if (e.relu) v = v > 0.f ? v : 0.f;
+    if (e.mask) {
+        const float m = e.mask_bf16 ? ld_elem(static_cast<const unsigned short *>(e.mask), mask_idx)
+                                    : ld_elem(static_cast<const float *>(e.mask), mask_idx);
+        v = m > 0.f ? v : 0.f;
+    }
+    return v;
+}
+
+// The same epilogue as a pass of its own over out[n][row][pos] (samples out_bs elements apart), for the kernels
+// that do not apply it themselves.
+template <typename T>
+__global__ void epilogue_inplace(T *__restrict__ out, int64_t out_bs, Epilogue e, int64_t total, int per_sample,
+                                 FastDiv div_sample, FastDiv div_plane)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int n = (int)fastdiv((uint32_t)i, div_sample);
+    const int r = (int)(i - (int64_t)n * per_sample);
+    const int row = (int)fastdiv((uint32_t)r, div_plane);
+    const int64_t o = (int64_t)n * out_bs + r;
+    st_elem(out, o, epi_apply(e, ld_elem(out, o), row, (int64_t)n * e.mask_bs + r));
+}
+
 __global__ void narrow_to_bf16(const float *__restrict__ src, unsigned short *__restrict__ dst, int64_t n)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -415,6 +454,9 @@ struct ColGemmFastArgs {
     // At + g * at_gs, writes dst + g * dst_gs and the partials part + g * part_gs (all in floats)
     int groups;
     int64_t src_gs, dst_gs, at_gs, part_gs;
+    // applied where the final sums are stored (this kernel when ksplit == 1 and epi_on, else the split-sum kernel)
+    int epi_on;
+    Epilogue epi;
     FastDiv div_plane, div_ow, div_rs, div_s;
 };
 
@@ -655,6 +697,20 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         const int rem = col - n * plane;
         float *out = p.ksplit > 1 ? part_c + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
                                   : dst_c + (size_t)n * p.dst_bs + rem;
+        if (p.epi_on && p.ksplit == 1) {          // one column only; split sums get it in reduce_split_outputs
+            const int64_t mbase = (int64_t)n * p.epi.mask_bs + rem;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + (v >> 2) * 8 + (v & 3);
+                    if (row < p.M)
+                        out[(size_t)row * plane] = epi_apply(p.epi, acc[i][jn][v], row, mbase + (int64_t)row * plane);
+                }
+            }
+            continue;
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
@@ -1099,6 +1155,18 @@ __global__ __launch_bounds__(kThreads, 2) void colgemm_bf16_kernel(const ColGemm
         if (col >= p.ncols) continue;
         const int n = (int)fastdiv((uint32_t)col, p.div_plane);
         const int rem = col - n * plane;
+        if (p.epi_on && p.ksplit == 1) {          // split sums get it in reduce_split_outputs
+            const int64_t mbase = (int64_t)n * p.epi.mask_bs + rem;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + (v >> 2) * 8 + (v & 3);
+                    if (row < p.M) acc[i][jn][v] = epi_apply(p.epi, acc[i][jn][v], row, mbase + (int64_t)row * plane);
+                }
+            }
+        }
         if (p.ksplit == 1 && p.out_bf16) {
             unsigned short *out = reinterpret_cast<unsigned short *>(p.dst) + (size_t)n * p.dst_bs + rem;
 #pragma unroll
@@ -1171,16 +1239,20 @@ __global__ void relayout_filters_cblk_bf16(const unsigned short *__restrict__ w,
 }
 
 // out[n][i] = part[0][n][i] + part[1][n][i] + ...  (fixed order), i over one sample's M*OH*OW outputs
+// and the epilogue applied to the sum when epi_on
 template <typename T>
 __global__ void reduce_split_outputs(const float *__restrict__ part, T *__restrict__ dst, int nsplit,
-                                     int per_sample, int N, int dst_bs, FastDiv div_sample)
+                                     int per_sample, int N, int dst_bs, FastDiv div_sample, int epi_on, Epilogue epi,
+                                     FastDiv div_plane)
 {
     const int total = N * per_sample;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
         float v = part[i];
         for (int k = 1; k < nsplit; ++k) v += part[(size_t)k * total + i];
         const int n = (int)fastdiv((uint32_t)i, div_sample);
-        st_elem(dst, (int64_t)n * dst_bs + (i - n * per_sample), v);
+        const int r = i - n * per_sample;
+        if (epi_on) v = epi_apply(epi, v, (int)fastdiv((uint32_t)r, div_plane), (int64_t)n * epi.mask_bs + r);
+        st_elem(dst, (int64_t)n * dst_bs + r, v);
     }
 }
 
@@ -2875,14 +2947,38 @@ const float *as_f32(bool widen, const void *src, int batch, int64_t sample, int6
 }
 
 int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const Problem &caller_pb, const Plan &pl,
-                       void *ws, hipStream_t st);
+                       void *ws, hipStream_t st, const Epilogue *ep, bool *ep_applied);
+
+// The epilogue as a pass of its own over out[N][rows][plane] (element type fp32 or bf16)
+int run_epilogue_pass(void *out, bool out_bf16, int64_t out_bs, const Epilogue &e, int N, int rows, int plane,
+                      hipStream_t st)
+{
+    const int per_sample = rows * plane;
+    const int64_t total = (int64_t)N * per_sample;
+    const FastDiv ds = make_fastdiv((uint32_t)per_sample), dp = make_fastdiv((uint32_t)plane);
+    if (out_bf16)
+        hipLaunchKernelGGL(epilogue_inplace<unsigned short>, dim3(grid1d(total, 256)), dim3(256), 0, st,
+                           static_cast<unsigned short *>(out), out_bs, e, total, per_sample, ds, dp);
+    else
+        hipLaunchKernelGGL(epilogue_inplace<float>, dim3(grid1d(total, 256)), dim3(256), 0, st,
+                           static_cast<float *>(out), out_bs, e, total, per_sample, ds, dp);
+    return check_launch();
+}
 
 // Forward / backward-data.  The bf16 kernels write a bf16 destination themselves; for the other paths it is
-// produced from a dense fp32 result in the workspace.
+// produced from a dense fp32 result in the workspace.  An epilogue (ep != null) is applied by the kernel that stores
+// the final sums where that kernel can, else by a pass over the fp32 result.
 int run_colgemm(int op, const void *act, const void *w, void *out, const Problem &pb, const Plan &pl, void *ws,
-                hipStream_t st)
+                hipStream_t st, const Epilogue *ep = nullptr)
 {
-    if (!pb.out_bf16 || pl.stage_bytes == 0) return run_colgemm_f32out(op, act, w, out, pb, pl, ws, st);
+    const int rows = op == kOpFwd ? pb.K : pb.C;
+    const int plane = op == kOpFwd ? pb.P * pb.Q : pb.H * pb.W;
+    bool applied = false;
+    if (!pb.out_bf16 || pl.stage_bytes == 0) {
+        int rc = run_colgemm_f32out(op, act, w, out, pb, pl, ws, st, ep, &applied);
+        if (rc != kStatusOk || !ep || applied) return rc;
+        return run_epilogue_pass(out, pb.out_bf16, op == kOpFwd ? pb.y_bs : pb.x_bs, *ep, pb.N, rows, plane, st);
+    }
     Problem q = pb;
     q.out_bf16 = false;
     const int64_t sample = op == kOpFwd ? (int64_t)pb.K * pb.P * pb.Q : (int64_t)pb.C * pb.H * pb.W;
@@ -2890,8 +2986,12 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
     const int64_t caller_bs = out_bs;
     out_bs = sample;
     float *stage = reinterpret_cast<float *>(static_cast<char *>(ws) + pl.stage_off);
-    int rc = run_colgemm_f32out(op, act, w, stage, q, pl, ws, st);
+    int rc = run_colgemm_f32out(op, act, w, stage, q, pl, ws, st, ep, &applied);
     if (rc != kStatusOk) return rc;
+    if (ep && !applied) {
+        rc = run_epilogue_pass(stage, false, sample, *ep, pb.N, rows, plane, st);
+        if (rc != kStatusOk) return rc;
+    }
     const int64_t count = pb.N * sample;
     hipLaunchKernelGGL(narrow_to_bf16_strided, dim3(grid1d(count, 256)), dim3(256), 0, st, stage,
                        static_cast<unsigned short *>(out), count, sample, caller_bs);
@@ -2899,7 +2999,7 @@ int run_colgemm(int op, const void *act, const void *w, void *out, const Problem
 }
 
 int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const Problem &caller_pb, const Plan &pl,
-                       void *ws, hipStream_t st)
+                       void *ws, hipStream_t st, const Epilogue *ep, bool *ep_applied)
 {
     Problem pb = caller_pb;                     // batch stride of a widened input changes below
     char *wsb = static_cast<char *>(ws);
@@ -2965,6 +3065,10 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         a.dst_gs = fwd ? pb.y_gs : pb.x_gs;
         a.at_gs = wt_elems;
         a.part_gs = (int64_t)(pl.part_bytes / 4);
+        // the 32 x 32 tile kernels and the split-sum kernel apply an epilogue themselves (one column only)
+        a.epi_on = ep && GF == 1 && pb.groups == 1 && (bf || pl.tile.mfma != 16 || a.ksplit > 1);
+        a.epi = ep ? *ep : Epilogue{};
+        *ep_applied = a.epi_on;
         const int need_lds = 2 * (pl.tile.bm() + pl.tile.bn()) * (bf ? kc * 2 + 16 : (kc + 4) * 4);
         const GridPlan g = plan_grid(a.mtiles * a.ntiles * a.ksplit * GF, need_lds);
         a.tiles_per_xcd = g.tiles_per_xcd;
@@ -2976,12 +3080,12 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         if (a.out_bf16)
             hipLaunchKernelGGL(reduce_split_outputs<unsigned short>, dim3(2048), dim3(256), 0, st, a.part,
                                reinterpret_cast<unsigned short *>(a.dst), a.ksplit, per_sample, pb.N, a.dst_bs,
-                               make_fastdiv((uint32_t)per_sample));
+                               make_fastdiv((uint32_t)per_sample), a.epi_on, a.epi, a.div_plane);
         else
             for (int gc = 0; gc < GF; ++gc)
                 hipLaunchKernelGGL(reduce_split_outputs<float>, dim3(2048), dim3(256), 0, st, a.part + gc * a.part_gs,
                                    a.dst + gc * a.dst_gs, a.ksplit, per_sample, pb.N, a.dst_bs,
-                                   make_fastdiv((uint32_t)per_sample));
+                                   make_fastdiv((uint32_t)per_sample), a.epi_on, a.epi, a.div_plane);
         return check_launch();
     }
     // forward with few channels: the input rows of a tile are staged once in LDS (reads fp32 or bf16 itself and
@@ -3292,6 +3396,36 @@ int conv_bwd_data_ex(const void *dy, const void *w, void *dx, int N, int C, int 
                      ws, ws_bytes, pb, pl);
     if (rc != kStatusOk) return rc;
     return run_colgemm(kOpBwdData, dy, w, dx, pb, pl, ws, static_cast<hipStream_t>(stream));
+}
+
+int conv_fwd_bias_relu(const void *x, const void *w, const void *bias, void *y, int N, int C, int H, int W, int K,
+                       int R, int S, int stride, int pad, int relu, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    if (relu != 0 && relu != 1) return kErrInvalidArg;
+    if (bias && !aligned(bias, 4)) return kErrMisaligned;
+    Problem pb; Plan pl;
+    int rc = prepare(kOpFwd, x, w, y, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype, ws, ws_bytes, pb, pl);
+    if (rc != kStatusOk) return rc;
+    Epilogue e{};
+    e.bias = static_cast<const float *>(bias);
+    e.relu = relu;
+    const bool any = bias || relu;
+    return run_colgemm(kOpFwd, x, w, y, pb, pl, ws, static_cast<hipStream_t>(stream), any ? &e : nullptr);
+}
+
+int conv_bwd_data_relu(const void *dy, const void *w, const void *act, void *dx, int N, int C, int H, int W, int K,
+                       int R, int S, int stride, int pad, int dtype, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!act) return kErrInvalidArg;
+    if (!aligned(act, 4)) return kErrMisaligned;
+    Problem pb; Plan pl;
+    int rc = prepare(kOpBwdData, dy, w, dx, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype, ws, ws_bytes, pb, pl);
+    if (rc != kStatusOk) return rc;
+    Epilogue e{};
+    e.mask = act;
+    e.mask_bs = pb.x_bs;
+    e.mask_bf16 = pb.out_bf16;
+    return run_colgemm(kOpBwdData, dy, w, dx, pb, pl, ws, static_cast<hipStream_t>(stream), &e);
 }
 
 int conv_bwd_filter_ex(const void *x, const void *dy, void *dw, int N, int C, int H, int W, int K, int R, int S,

@@ -64,8 +64,9 @@ class ConvStack:
         }
         self.g5 = t(synth.gaussian((N, 256, 6, 6), seed + 7))
         self.dw = {k: torch.empty(v.shape, dtype=torch.float32, device=device) for k, v in self.w.items()}
-        # activations (ReLU runs in place on y3, y4; y1, y2, y5 keep the pre-activation: their ReLU is fused
-        # into the pooling calls)
+        # activations (y3, y4 hold relu(conv): the ReLU is applied where the convolution stores its sums, and its
+        # backward where the next layer's backward-data stores; y1, y2, y5 keep the pre-activation: their ReLU is
+        # fused into the pooling calls)
         self.y1 = torch.empty((N, 96, 55, 55), **act)
         self.a1 = torch.empty((N, 96, 27, 27), **act)
         self.y2 = torch.empty((N, 256, 27, 27), **act)
@@ -102,10 +103,10 @@ class ConvStack:
         hp.relu_maxpool3x3s2_fwd(self.y1, self.a1)
         self._timed(("conv2", "fwd"), lambda: hp.conv_fwd_grouped(self.a1, w["conv2"], 1, 2, 2, y=self.y2, ws=ws))
         hp.relu_maxpool3x3s2_fwd(self.y2, self.a2)
-        self._timed(("conv3", "fwd"), lambda: hp.conv_fwd(self.a2, w["conv3"], 1, 1, y=self.y3, ws=ws))
-        hp.relu_fwd(self.y3, self.y3)
-        self._timed(("conv4", "fwd"), lambda: hp.conv_fwd(self.y3, w["conv4"], 1, 1, y=self.y4, ws=ws))
-        hp.relu_fwd(self.y4, self.y4)
+        self._timed(("conv3", "fwd"),
+                    lambda: hp.conv_fwd_bias_relu(self.a2, w["conv3"], None, 1, 1, y=self.y3, ws=ws))
+        self._timed(("conv4", "fwd"),
+                    lambda: hp.conv_fwd_bias_relu(self.y3, w["conv4"], None, 1, 1, y=self.y4, ws=ws))
         self._timed(("conv5", "fwd"), lambda: hp.conv_fwd(self.y4, w["conv5"], 1, 1, y=self.y5, ws=ws))
         hp.relu_maxpool3x3s2_fwd(self.y5, self.a5)
         return self.a5
@@ -116,13 +117,11 @@ class ConvStack:
         self._timed(("conv5", "wgrad"),
                     lambda: hp.conv_bwd_filter(self.y4, self.dy5, 3, 3, 1, 1, dw=dw["conv5"], ws=ws))
         self._timed(("conv5", "dgrad"),
-                    lambda: hp.conv_bwd_data(self.dy5, w["conv5"], 13, 13, 1, 1, dx=self.dy4, ws=ws))
-        hp.relu_bwd(self.y4, self.dy4, self.dy4)
+                    lambda: hp.conv_bwd_data_relu(self.dy5, w["conv5"], self.y4, 1, 1, dx=self.dy4, ws=ws))
         self._timed(("conv4", "wgrad"),
                     lambda: hp.conv_bwd_filter(self.y3, self.dy4, 3, 3, 1, 1, dw=dw["conv4"], ws=ws))
         self._timed(("conv4", "dgrad"),
-                    lambda: hp.conv_bwd_data(self.dy4, w["conv4"], 13, 13, 1, 1, dx=self.dy3, ws=ws))
-        hp.relu_bwd(self.y3, self.dy3, self.dy3)
+                    lambda: hp.conv_bwd_data_relu(self.dy4, w["conv4"], self.y3, 1, 1, dx=self.dy3, ws=ws))
         self._timed(("conv3", "wgrad"),
                     lambda: hp.conv_bwd_filter(self.a2, self.dy3, 3, 3, 1, 1, dw=dw["conv3"], ws=ws))
         self._timed(("conv3", "dgrad"),

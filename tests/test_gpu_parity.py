@@ -610,3 +610,76 @@ def test_bias_forward_and_gradient(dtype):
         assert torch.equal(db, hp.bias_bwd(dev(y, dtype)))                                               # fixed order
     yi = synth.small_integers((4, 6, 5, 5), 183)
     assert np.array_equal(hp.bias_bwd(dev(yi, dtype)).cpu().numpy(), oracle.bias_bwd(yi))
+
+
+# --------------------------------------------- convolution with its bias / ReLU applied at the store ---
+EPILOGUE_SHAPES = [
+    (128, 64, 13, 13, 256, 3, 3, 1, 1),    # 32 x 32 tile kernels, enough tiles for a whole-reduction launch
+    (4, 64, 13, 13, 96, 3, 3, 1, 1),       # few tiles: reduction split, epilogue in the split-sum kernel
+    (7, 48, 14, 14, 64, 5, 5, 1, 2),       # backward-data in the 48-row kernel: epilogue as a pass of its own
+    (3, 3, 23, 25, 48, 11, 11, 4, 2),      # few-channel forward (patch kernel), strided backward-data (tap table)
+    (2, 5, 8, 10, 130, 3, 3, 1, 5),        # tap-table kernels both ways
+]
+
+
+@pytest.mark.parametrize("mode", ["f32", "bf16", "bf16out"])
+@pytest.mark.parametrize("shape", EPILOGUE_SHAPES)
+def test_conv_with_bias_relu_epilogues(shape, mode):
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+    dtype = "f32" if mode == "f32" else "bf16"
+    out_t = torch.bfloat16 if mode == "bf16out" else torch.float32
+    x, w, dy = prepared(synth.gaussian((N, C, H, W), 191), synth.gaussian((K, C, R, S), 192, 0.1),
+                        synth.gaussian((N, K, P, Q), 193), dtype)
+    b = synth.gaussian((K,), 194)
+    act = synth.gaussian((N, C, H, W), 195)
+    if mode == "bf16out":
+        act = synth.to_bf16_grid(act)
+    xd, wd, dyd, bd = dev(x, dtype), dev(w, dtype), dev(dy, dtype), dev(b)
+    actd = dev(act).to(out_t)
+    tol = TOL[dtype]
+
+    def fresh(shape_):
+        return torch.full(shape_, float("nan"), dtype=out_t, device="cuda")
+
+    for bias, relu in [(b, True), (None, True), (b, False)]:
+        got = hp.conv_fwd_bias_relu(xd, wd, bd if bias is not None else None, st, pad, relu=relu,
+                                    y=fresh((N, K, P, Q)))
+        want = oracle.conv_fwd_bias_relu(x, w, bias, st, pad, relu=relu)
+        e = norm_err(got.float().cpu().numpy(), want)
+        assert np.isfinite(e) and e <= tol, "fwd bias=%s relu=%s err %.3e" % (bias is not None, relu, e)
+        if relu:
+            assert float(got.float().min()) >= 0.0
+        if mode != "bf16out":
+            # the separate calls do the same fp32 operations in the same order
+            sep = hp.conv_fwd(xd, wd, st, pad, y=fresh((N, K, P, Q)))
+            if bias is not None:
+                hp.bias_fwd(sep, bd)
+            if relu:
+                hp.relu_fwd(sep, y=sep)
+            assert torch.equal(got, sep)
+    got = hp.conv_bwd_data_relu(dyd, wd, actd, st, pad, dx=fresh((N, C, H, W)))
+    want = oracle.conv_bwd_data_relu(dy, w, act, st, pad)
+    e = norm_err(got.float().cpu().numpy(), want)
+    assert np.isfinite(e) and e <= tol, "dgrad err %.3e" % e
+    assert np.array_equal(got.float().cpu().numpy()[act <= 0], np.zeros(np.count_nonzero(act <= 0), np.float32))
+    sep = hp.conv_bwd_data(dyd, wd, H, W, st, pad, dx=fresh((N, C, H, W)))
+    assert torch.equal(got, hp.relu_bwd(actd, sep))
+
+
+def test_epilogue_argument_checks():
+    x = torch.zeros((1, 16, 5, 5), device="cuda"); w = torch.zeros((16, 16, 3, 3), device="cuda")
+    y = torch.zeros((1, 16, 5, 5), device="cuda")
+    L = hp.lib()
+    import ctypes
+    p = lambda t: ctypes.c_void_p(t.data_ptr())
+    need = hp.workspace_bytes(hp.OP_FWD, 1, 16, 5, 5, 16, 3, 3, 1, 1)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    dims = (1, 16, 5, 5, 16, 3, 3, 1, 1)
+    assert L.conv_fwd_bias_relu(p(x), p(w), None, p(y), *dims, 2, 0, p(ws), ws.numel(), st) == hp.ERR_INVALID_ARG
+    assert L.conv_fwd_bias_relu(p(x), p(w), None, None, *dims, 1, 0, p(ws), ws.numel(), st) == hp.ERR_INVALID_ARG
+    assert L.conv_bwd_data_relu(p(y), p(w), None, p(x), *dims, 0, p(ws), ws.numel(), st) == hp.ERR_INVALID_ARG
+    assert L.conv_fwd_bias_relu(p(x), p(w), None, p(y), *dims, 1, 0, p(ws), 0, st) == (
+        hp.ERR_WORKSPACE if need else hp.OK)
+    torch.cuda.synchronize()

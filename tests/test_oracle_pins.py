@@ -467,3 +467,46 @@ def test_bias_closed_forms_and_adjoint():
     g = rng.standard_normal((N, K, P, Q))
     lhs = np.sum(oracle.bias_fwd(np.zeros_like(g), b) * g)
     assert abs(lhs - np.dot(b, oracle.bias_bwd(g))) <= 1e-12 * np.sum(np.abs(g))
+
+
+# ------------------------------------------------- convolution + bias + ReLU chains ---
+def test_fused_forward_closed_form_orders_bias_before_relu():
+    # x = 1, w = 1, 3x3 pad 1: the sum is C * (taps inside) = 18 inside, 12 on edges, 8 in corners.  A bias of -10
+    # leaves 8 / 2 / 0 after the ReLU (ReLU before the bias would give 8 / 2 / -2); filter 1 has bias +1.
+    C, H = 2, 5
+    x = np.ones((1, C, H, H)); w = np.ones((2, C, 3, 3)); b = np.array([-10.0, 1.0])
+    y = oracle.conv_fwd_bias_relu(x, w, b, 1, 1)
+    assert y[0, 0, 2, 2] == 8 and y[0, 0, 0, 2] == 2 and y[0, 0, 0, 0] == 0 and y[0, 0, 4, 4] == 0
+    assert y[0, 1, 2, 2] == 19 and y[0, 1, 0, 0] == 9
+    lin = oracle.conv_fwd_bias_relu(x, w, b, 1, 1, relu=False)
+    assert lin[0, 0, 0, 0] == -2 and lin[0, 0, 2, 2] == 8
+    nob = oracle.conv_fwd_bias_relu(-x, w, None, 1, 1)
+    assert np.array_equal(nob, np.zeros_like(nob))
+
+
+def test_fused_backward_data_is_the_derivative_through_the_relu():
+    # L(a) = <conv_fwd(relu(a), w), g> is piecewise linear in a: away from a = 0 a central difference is exact up to
+    # rounding, and it must equal conv_bwd_data_relu(g, w, a); where a <= 0 the gradient is exactly 0.
+    rng = np.random.default_rng(21)
+    N, C, H, W, K, R, S, st, pad = 2, 3, 7, 6, 4, 3, 3, 2, 1
+    a = rng.standard_normal((N, C, H, W))
+    a[np.abs(a) < 0.05] = 0.5
+    a[0, 1, 2, 3] = 0.0                                   # relu'(0) = 0
+    w = rng.standard_normal((K, C, R, S))
+    g = rng.standard_normal((N, K, oracle.out_extent(H, R, st, pad), oracle.out_extent(W, S, st, pad)))
+    da = oracle.conv_bwd_data_relu(g, w, a, st, pad)
+    assert da.shape == a.shape and da[0, 1, 2, 3] == 0.0
+    assert np.array_equal(da[a <= 0], np.zeros(np.count_nonzero(a <= 0)))
+
+    def loss(t):
+        return float(np.sum(oracle.conv_fwd(np.maximum(t, 0.0), w, st, pad) * g))
+
+    eps = 1e-3
+    for _ in range(12):
+        i = tuple(int(rng.integers(0, d)) for d in a.shape)
+        if a[i] == 0.0:
+            continue
+        ap, am = a.copy(), a.copy()
+        ap[i] += eps; am[i] -= eps
+        fd = (loss(ap) - loss(am)) / (2 * eps)
+        assert abs(fd - da[i]) <= 1e-8 * max(1.0, abs(da[i])), (i, fd, da[i])
