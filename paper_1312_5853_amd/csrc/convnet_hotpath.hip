@@ -139,6 +139,47 @@ __device__ __forceinline__ float epi_apply(const Epilogue &e, float v, int row, 
     return v;
 }
 
+// The epilogue on the accumulators of one 32-column block (index jn) of a wave's tile of 32 x 32 matrix blocks:
+// value v of block i belongs to row row_base + 32*i + 8*(v/4) + v%4 (the accumulator layout of
+// v_mfma_f32_32x32x2_f32 and v_mfma_f32_32x32x16_bf16).  The 16 loads of a block are issued before the first use,
+// so their latencies overlap; rows past M (padding of the last row tile) read row M-1 and are never stored.
+template <int TM, int TN>
+__device__ __forceinline__ void epi_tile(const Epilogue &e, f32x16 (&acc)[TM][TN], int jn, int row_base, int M,
+                                         int plane, int64_t mask_base)
+{
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        int row[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) row[v] = min(row_base + i * 32 + (v >> 2) * 8 + (v & 3), M - 1);
+        if (e.bias) {
+            float bv[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) bv[v] = e.bias[row[v]];
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] += bv[v];
+        }
+        if (e.relu) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = acc[i][jn][v] > 0.f ? acc[i][jn][v] : 0.f;
+        }
+        if (e.mask) {
+            float mv[16];
+            if (e.mask_bf16) {
+                const unsigned short *m = static_cast<const unsigned short *>(e.mask) + mask_base;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mv[v] = ld_elem(m, (int64_t)row[v] * plane);
+            } else {
+                const float *m = static_cast<const float *>(e.mask) + mask_base;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mv[v] = m[(int64_t)row[v] * plane];
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = mv[v] > 0.f ? acc[i][jn][v] : 0.f;
+        }
+    }
+}
+
 // The same epilogue as a pass of its own over out[n][row][pos] (samples out_bs elements apart), for the kernels
 // that do not apply it themselves.
 template <typename T>
@@ -463,7 +504,7 @@ struct ColGemmFastArgs {
 // KC = reduction depth of one step (16 or 32 channels of one tap).  LDS is
 // dynamic: 2 * (BM + BN) * (KC + 4) floats.
 template <int TM, int TN, int WM, int WN, int KC>
-__global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFastArgs p)
+__global__ __launch_bounds__(kThreads, 2) void colgemm_fast_kernel(const ColGemmFastArgs p)
 {
     constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
     constexpr int PITCH = KC + 4;            // 16 lanes x b128 still cover all banks once (20 and 36 both do)
@@ -697,20 +738,9 @@ __global__ __launch_bounds__(kThreads) void colgemm_fast_kernel(const ColGemmFas
         const int rem = col - n * plane;
         float *out = p.ksplit > 1 ? part_c + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
                                   : dst_c + (size_t)n * p.dst_bs + rem;
-        if (p.epi_on && p.ksplit == 1) {          // one column only; split sums get it in reduce_split_outputs
-            const int64_t mbase = (int64_t)n * p.epi.mask_bs + rem;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < p.M)
-                        out[(size_t)row * plane] = epi_apply(p.epi, acc[i][jn][v], row, mbase + (int64_t)row * plane);
-                }
-            }
-            continue;
-        }
+        if (p.epi_on && p.ksplit == 1)            // one column only; split sums get it in reduce_split_outputs
+            epi_tile<TM, TN>(p.epi, acc, jn, m0 + wm * TM * 32 + half * 4, p.M, plane,
+                             (int64_t)n * p.epi.mask_bs + rem);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
@@ -1155,18 +1185,9 @@ __global__ __launch_bounds__(kThreads, 2) void colgemm_bf16_kernel(const ColGemm
         if (col >= p.ncols) continue;
         const int n = (int)fastdiv((uint32_t)col, p.div_plane);
         const int rem = col - n * plane;
-        if (p.epi_on && p.ksplit == 1) {          // split sums get it in reduce_split_outputs
-            const int64_t mbase = (int64_t)n * p.epi.mask_bs + rem;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < p.M) acc[i][jn][v] = epi_apply(p.epi, acc[i][jn][v], row, mbase + (int64_t)row * plane);
-                }
-            }
-        }
+        if (p.epi_on && p.ksplit == 1)            // split sums get it in reduce_split_outputs
+            epi_tile<TM, TN>(p.epi, acc, jn, m0 + wm * TM * 32 + half * 4, p.M, plane,
+                             (int64_t)n * p.epi.mask_bs + rem);
         if (p.ksplit == 1 && p.out_bf16) {
             unsigned short *out = reinterpret_cast<unsigned short *>(p.dst) + (size_t)n * p.dst_bs + rem;
 #pragma unroll
