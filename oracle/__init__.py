@@ -30,6 +30,10 @@ from .oracle import (  # noqa: F401
     bias_bwd,
     conv_fwd_bias_relu,
     conv_bwd_data_relu,
+    fc_fwd,
+    fc_bwd_data,
+    fc_bwd_filter,
+    sgd_update,
     num_threads,
     set_num_threads,
 )

@@ -260,3 +260,39 @@ def conv_bwd_data_relu(dy, w, act, stride, pad):
     act = _f64(act)
     H, W = act.shape[2], act.shape[3]
     return relu_bwd(act, conv_bwd_data(dy, w, H, W, stride, pad))
+
+
+# ---------------------------------------------------------------------------
+# Fully connected layers (the top layers of the network; model-parallelism
+# paragraph) and the synchronous mini-batch SGD update (training-procedure
+# paragraph).  The paper names both without formulas; these are the textbook
+# definitions.  x [N, I] (a sample per row), w [O, I] (a neuron per row).
+# ---------------------------------------------------------------------------
+def fc_fwd(x, w, b=None, relu=False):
+    x, w = _f64(x), _f64(w)
+    assert x.ndim == 2 and w.ndim == 2 and x.shape[1] == w.shape[1]
+    y = np.matmul(x, w.T)                       # y[n, o] = sum_i x[n, i] * w[o, i]
+    if b is not None:
+        y = y + _f64(b)[None, :]
+    return np.where(y > 0, y, 0.0) if relu else y
+
+
+def fc_bwd_data(dy, w):
+    dy, w = _f64(dy), _f64(w)
+    assert dy.shape[1] == w.shape[0]
+    return np.matmul(dy, w)                     # dx[n, i] = sum_o dy[n, o] * w[o, i]
+
+
+def fc_bwd_filter(x, dy):
+    x, dy = _f64(x), _f64(dy)
+    assert x.shape[0] == dy.shape[0]
+    return np.matmul(dy.T, x)                   # dw[o, i] = sum_n dy[n, o] * x[n, i]
+
+
+def sgd_update(w, dw, v, lr, momentum=0.0, weight_decay=0.0, grad_scale=1.0):
+    """One step of mini-batch SGD with momentum and L2 weight decay:
+        v' = momentum * v - lr * (weight_decay * w + grad_scale * dw),   w' = w + v'
+    (grad_scale = 1 / mini-batch size turns a summed gradient into the mean).  Returns (w', v')."""
+    w, dw, v = _f64(w), _f64(dw), _f64(v)
+    v2 = momentum * v - lr * (weight_decay * w + grad_scale * dw)
+    return w + v2, v2

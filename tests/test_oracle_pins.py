@@ -510,3 +510,78 @@ def test_fused_backward_data_is_the_derivative_through_the_relu():
         ap[i] += eps; am[i] -= eps
         fd = (loss(ap) - loss(am)) / (2 * eps)
         assert abs(fd - da[i]) <= 1e-8 * max(1.0, abs(da[i])), (i, fd, da[i])
+
+
+# ------------------------------------------------- fully connected layers and SGD ---
+def test_fc_equals_brute_force_and_the_convolution_oracle():
+    rng = np.random.default_rng(31)
+    N, I, O = 3, 8, 5
+    x = rng.integers(-4, 5, (N, I)).astype(np.float64)
+    w = rng.integers(-4, 5, (O, I)).astype(np.float64)
+    g = rng.integers(-4, 5, (N, O)).astype(np.float64)
+    y = oracle.fc_fwd(x, w)
+    dx = oracle.fc_bwd_data(g, w)
+    dw = oracle.fc_bwd_filter(x, g)
+    for n in range(N):
+        for o in range(O):
+            assert y[n, o] == sum(x[n, i] * w[o, i] for i in range(I))
+        for i in range(I):
+            assert dx[n, i] == sum(g[n, o] * w[o, i] for o in range(O))
+    for o in range(O):
+        for i in range(I):
+            assert dw[o, i] == sum(g[n, o] * x[n, i] for n in range(N))
+    # a fully connected layer is a 1x1 convolution on 1x1 planes ...
+    x4, w4, g4 = x.reshape(N, I, 1, 1), w.reshape(O, I, 1, 1), g.reshape(N, O, 1, 1)
+    assert np.array_equal(y, oracle.conv_fwd(x4, w4, 1, 0).reshape(N, O))
+    assert np.array_equal(dx, oracle.conv_bwd_data(g4, w4, 1, 1, 1, 0).reshape(N, I))
+    assert np.array_equal(dw, oracle.conv_bwd_filter(x4, g4, 1, 1, 1, 0).reshape(O, I))
+    # ... and, on a flattened [C][H][W] sample, a convolution whose filter covers the whole plane
+    C, H, W = 2, 2, 2
+    xc, wc = x.reshape(N, C, H, W), w.reshape(O, C, H, W)
+    assert np.array_equal(y, oracle.conv_fwd(xc, wc, 1, 0).reshape(N, O))
+
+
+def test_fc_bias_relu_and_adjoints():
+    rng = np.random.default_rng(32)
+    N, I, O = 4, 7, 6
+    x, w, g = rng.standard_normal((N, I)), rng.standard_normal((O, I)), rng.standard_normal((N, O))
+    b = rng.standard_normal(O)
+    lin = oracle.fc_fwd(x, w)
+    assert np.array_equal(oracle.fc_fwd(x, w, b), lin + b[None, :])
+    yr = oracle.fc_fwd(x, w, b, relu=True)
+    assert np.array_equal(yr, np.maximum(lin + b[None, :], 0.0)) and (yr >= 0).all()
+    # x = 1, w = 1: every output is I; with bias -I-1 the ReLU leaves 0, with bias 1 it leaves I + 1
+    one = oracle.fc_fwd(np.ones((2, I)), np.ones((2, I)), np.array([-I - 1.0, 1.0]), relu=True)
+    assert np.array_equal(one, np.array([[0.0, I + 1.0]] * 2))
+    # <fc(x, w), g> = <x, bwd_data(g, w)> = <w, bwd_filter(x, g)>
+    lhs = np.sum(lin * g)
+    assert abs(lhs - np.sum(x * oracle.fc_bwd_data(g, w))) <= 1e-12 * abs(lhs) + 1e-12
+    assert abs(lhs - np.sum(w * oracle.fc_bwd_filter(x, g))) <= 1e-12 * abs(lhs) + 1e-12
+    # not symmetric in its arguments: a transposed operand must fail
+    assert oracle.fc_bwd_filter(x, g).shape == (O, I) and oracle.fc_bwd_data(g, w).shape == (N, I)
+
+
+def test_sgd_update_closed_forms():
+    w0 = np.array([1.0, -2.0, 0.5]); g = np.array([0.5, 0.25, -1.0]); z = np.zeros(3)
+    # plain SGD: w' = w - lr * dw, velocity is the step
+    w1, v1 = oracle.sgd_update(w0, g, z, lr=0.1)
+    assert np.allclose(w1, w0 - 0.1 * g, rtol=0, atol=1e-16) and np.allclose(v1, -0.1 * g, rtol=0, atol=1e-16)
+    # gradient of the mean: grad_scale = 1/B
+    w1, _ = oracle.sgd_update(w0, g, z, lr=0.1, grad_scale=0.25)
+    assert np.allclose(w1, w0 - 0.025 * g, rtol=0, atol=1e-16)
+    # weight decay alone contracts the weights: w_t = (1 - lr * wd)^t * w_0
+    w, v = w0.copy(), z.copy()
+    for _ in range(10):
+        w, v = oracle.sgd_update(w, z, v, lr=0.1, weight_decay=0.5)
+    assert np.allclose(w, (1 - 0.05) ** 10 * w0, rtol=1e-13)
+    # constant gradient with momentum: v_t = -lr * g * (1 - mu^t) / (1 - mu), w_t = w_0 + sum of the v
+    mu, lr, T = 0.9, 0.01, 25
+    w, v = w0.copy(), z.copy()
+    for _ in range(T):
+        w, v = oracle.sgd_update(w, g, v, lr=lr, momentum=mu)
+    assert np.allclose(v, -lr * g * (1 - mu ** T) / (1 - mu), rtol=1e-12)
+    total = -lr * g * (T - mu * (1 - mu ** T) / (1 - mu)) / (1 - mu)
+    assert np.allclose(w, w0 + total, rtol=1e-12)
+    # gradient descent on L = |w|^2 / 2 (dw = w) with lr = 1 lands on the minimum in one step
+    w1, _ = oracle.sgd_update(w0, w0, z, lr=1.0)
+    assert np.array_equal(w1, z)
