@@ -249,6 +249,45 @@ size_t bias_bwd_workspace_bytes(int N, int K);
  */
 int convert_f32_to_bf16(const void *src, void *dst, int64_t count, void *stream);
 
+/*
+ * Fully connected layers (the top layers of the network, where the columns of
+ * the model-parallel architecture are cross-connected; model-parallelism
+ * paragraph).  Row-major fp32 device tensors: x, dx [N][I] (a sample per row),
+ * w, dw [O][I] (an output neuron per row), y, dy [N][O].
+ *   fc_fwd:        y[n][o]  = f(sum_i x[n][i] * w[o][i] + bias[o]); bias fp32 [O] or
+ *                  NULL; f = max(., 0) if relu = 1, identity if relu = 0
+ *   fc_bwd_data:   dx[n][i] = sum_o dy[n][o] * w[o][i]
+ *   fc_bwd_filter: dw[o][i] = sum_n dy[n][o] * x[n][i]   (this shard's sum)
+ * Outputs are fully overwritten; sums accumulate in fp32 in a fixed order.
+ * I and O must be multiples of 4 (CONV_ERR_INVALID_ARG otherwise), every tensor
+ * below 2^31 elements, pointers 16-byte aligned, dtype CONV_DTYPE_F32
+ * (CONV_ERR_BAD_DTYPE otherwise).  Scratch: fc_workspace_bytes(op, ...) bytes
+ * (op = CONV_OP_*; 0 for invalid arguments), 256-byte aligned.  Stream, ownership
+ * and error conventions as for the convolution passes.
+ */
+int fc_fwd(const void *x, const void *w, const void *bias, void *y, int N, int I, int O, int relu,
+           int dtype, void *ws, size_t ws_bytes, void *stream);
+int fc_bwd_data(const void *dy, const void *w, void *dx, int N, int I, int O,
+                int dtype, void *ws, size_t ws_bytes, void *stream);
+int fc_bwd_filter(const void *x, const void *dy, void *dw, int N, int I, int O,
+                  int dtype, void *ws, size_t ws_bytes, void *stream);
+size_t fc_workspace_bytes(int op, int N, int I, int O, int dtype);
+
+/*
+ * One step of synchronous mini-batch stochastic gradient descent (training-
+ * procedure paragraph; the paper fixes no hyper-parameters beyond "the same
+ * set-up" as the network it trains, whose rule this is), in place on fp32
+ * device arrays of `count` parameters:
+ *   vel[i] = momentum * vel[i] - lr * (weight_decay * w[i] + grad_scale * dw[i])
+ *   w[i]  += vel[i]
+ * grad_scale = 1 / mini-batch size turns the summed gradients the backward-
+ * filter passes produce into the mean; momentum = weight_decay = 0 is plain
+ * SGD (vel then only receives the step).  dw is only read.  4-byte aligned
+ * pointers (16-byte aligned ones take the vector path); count = 0 is a no-op.
+ */
+int sgd_update(void *w, const void *dw, void *vel, int64_t count, float lr, float momentum,
+               float weight_decay, float grad_scale, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,6 +27,7 @@ EXPORTS = (
     "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
     "relu_maxpool3x3s2_fwd", "relu_maxpool3x3s2_bwd", "convert_f32_to_bf16",
     "bias_fwd", "bias_bwd", "bias_bwd_workspace_bytes",
+    "fc_fwd", "fc_bwd_data", "fc_bwd_filter", "fc_workspace_bytes", "sgd_update",
 )
 
 _lib = None
@@ -67,6 +68,15 @@ def lib():
     L.conv_fwd_bias_relu.restype = i
     L.conv_bwd_data_relu.argtypes = [vp, vp, vp, vp] + dims + [i, vp, sz, vp]
     L.conv_bwd_data_relu.restype = i
+    L.fc_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, vp, sz, vp]
+    L.fc_bwd_data.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.fc_bwd_filter.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp]
+    L.fc_workspace_bytes.argtypes = [i, i, i, i, i]
+    L.fc_workspace_bytes.restype = sz
+    f32 = ctypes.c_float
+    L.sgd_update.argtypes = [vp, vp, vp, i64, f32, f32, f32, f32, vp]
+    for name in ("fc_fwd", "fc_bwd_data", "fc_bwd_filter", "sgd_update"):
+        getattr(L, name).restype = i
     L.conv_workspace_bytes_grouped.argtypes = [i] + dims + [i, i]
     L.conv_workspace_bytes_grouped.restype = sz
     L.conv_workspace_bytes.argtypes = [i] + dims + [i]
@@ -420,3 +430,64 @@ def convert_f32_to_bf16(src, dst=None, stream=None):
         raise ValueError("convert_f32_to_bf16 needs contiguous tensors")
     _check(lib().convert_f32_to_bf16(_ptr(src), _ptr(dst), src.numel(), _stream_handle(stream)), "convert_f32_to_bf16")
     return dst
+
+
+def _fc_ws(op, N, I, O, ws):
+    buf, nbytes = _ws(ws).get(int(lib().fc_workspace_bytes(op, N, I, O, DTYPE_F32)))
+    return (ctypes.c_void_p(buf.data_ptr()) if buf is not None else ctypes.c_void_p(0)), nbytes
+
+
+def fc_fwd(x, w, bias=None, relu=False, y=None, ws=None, stream=None):
+    """x [N,I], w [O,I] (fp32) -> y [N,O] = f(x w^T + bias)."""
+    N, I = x.shape
+    O, Iw = w.shape
+    if I != Iw or (bias is not None and (bias.dtype != torch.float32 or bias.numel() != O)):
+        raise ValueError("operands do not match")
+    if y is None:
+        y = torch.empty((N, O), dtype=torch.float32, device=x.device)
+    _dense(x, w, bias, y)
+    wsp, nbytes = _fc_ws(OP_FWD, N, I, O, ws)
+    bp = _ptr(bias) if bias is not None else ctypes.c_void_p(0)
+    _check(lib().fc_fwd(_ptr(x), _ptr(w), bp, _ptr(y), N, I, O, 1 if relu else 0, _dtype_of(x), wsp, nbytes,
+                        _stream_handle(stream)), "fc_fwd")
+    return y
+
+
+def fc_bwd_data(dy, w, dx=None, ws=None, stream=None):
+    """dy [N,O], w [O,I] -> dx [N,I]."""
+    N, O = dy.shape
+    Ow, I = w.shape
+    if O != Ow:
+        raise ValueError("operands do not match")
+    if dx is None:
+        dx = torch.empty((N, I), dtype=torch.float32, device=dy.device)
+    _dense(dy, w, dx)
+    wsp, nbytes = _fc_ws(OP_BWD_DATA, N, I, O, ws)
+    _check(lib().fc_bwd_data(_ptr(dy), _ptr(w), _ptr(dx), N, I, O, _dtype_of(dy), wsp, nbytes,
+                             _stream_handle(stream)), "fc_bwd_data")
+    return dx
+
+
+def fc_bwd_filter(x, dy, dw=None, ws=None, stream=None):
+    """x [N,I], dy [N,O] -> dw [O,I]."""
+    N, I = x.shape
+    Ny, O = dy.shape
+    if N != Ny:
+        raise ValueError("operands do not match")
+    if dw is None:
+        dw = torch.empty((O, I), dtype=torch.float32, device=x.device)
+    _dense(x, dy, dw)
+    wsp, nbytes = _fc_ws(OP_BWD_FILTER, N, I, O, ws)
+    _check(lib().fc_bwd_filter(_ptr(x), _ptr(dy), _ptr(dw), N, I, O, _dtype_of(x), wsp, nbytes,
+                               _stream_handle(stream)), "fc_bwd_filter")
+    return dw
+
+
+def sgd_update(w, dw, vel, lr, momentum=0.0, weight_decay=0.0, grad_scale=1.0, stream=None):
+    """In place: vel = momentum*vel - lr*(weight_decay*w + grad_scale*dw); w += vel (fp32 tensors of one size)."""
+    if not (w.dtype == dw.dtype == vel.dtype == torch.float32) or not (w.numel() == dw.numel() == vel.numel()):
+        raise ValueError("sgd_update takes three fp32 tensors of one size")
+    _dense(w, dw, vel)
+    _check(lib().sgd_update(_ptr(w), _ptr(dw), _ptr(vel), w.numel(), lr, momentum, weight_decay, grad_scale,
+                            _stream_handle(stream)), "sgd_update")
+    return w

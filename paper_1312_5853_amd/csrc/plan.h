@@ -8,6 +8,7 @@
 #include <stddef.h>
 #include <stdint.h>
 #include <stdlib.h>
+#include <algorithm>
 
 #include "fastdiv.h"
 
@@ -301,6 +302,44 @@ inline Plan make_plan(int op, const Problem &pb)
     }
     pl.total = off;
     return pl;
+}
+
+// ---------------------------------------------------------------------------
+// Fully connected layers: x [N][I], w [O][I], y [N][O].  GEMM extents, operand
+// orientation and the split of the reduction for fc_gemm_kernel (128 x 128
+// tiles, 16 reduction elements per step).
+// ---------------------------------------------------------------------------
+struct FcPlan {
+    int M, Nc, K;                 // output rows, output columns, reduction length
+    int lda, ldb, ldd;
+    bool at, bt;                  // operand A / B has its rows (columns) contiguous rather than k
+    int mtiles, ntiles, ksplit, steps_per_split;
+    size_t part_bytes;            // ksplit > 1: partial sums [ksplit][M][Nc], the whole workspace
+};
+
+inline int make_fc_plan(FcPlan &pl, int op, int N, int I, int O, int dtype)
+{
+    if (N <= 0 || I <= 0 || O <= 0) return kErrInvalidArg;
+    if (op != kOpFwd && op != kOpBwdData && op != kOpBwdFilter) return kErrInvalidArg;
+    if (I % 4 != 0 || O % 4 != 0) return kErrInvalidArg;      // 16-byte pieces along I and O
+    if (dtype != kDtypeF32) return kErrBadDtype;
+    const int64_t lim = (int64_t)1 << 31;
+    if ((int64_t)N * I >= lim || (int64_t)N * O >= lim || (int64_t)O * I >= lim) return kErrTooLarge;
+    if (op == kOpFwd) { pl.M = N; pl.Nc = O; pl.K = I; pl.lda = I; pl.ldb = I; pl.ldd = O; pl.at = false; pl.bt = false; }
+    else if (op == kOpBwdData) { pl.M = N; pl.Nc = I; pl.K = O; pl.lda = O; pl.ldb = I; pl.ldd = I; pl.at = false; pl.bt = true; }
+    else { pl.M = O; pl.Nc = I; pl.K = N; pl.lda = O; pl.ldb = I; pl.ldd = I; pl.at = true; pl.bt = true; }
+    pl.mtiles = ceil_div(pl.M, 128);
+    pl.ntiles = ceil_div(pl.Nc, 128);
+    // aim at two work-groups per compute unit, with at least eight steps per range
+    const int64_t tiles = (int64_t)pl.mtiles * pl.ntiles;
+    const int steps = ceil_div(pl.K, kChunk);
+    int ks = (int)std::min<int64_t>(std::max<int64_t>(1, 512 / tiles), std::max(1, steps / 8));
+    ks = std::min(ks, 32);
+    pl.steps_per_split = ceil_div(steps, ks);
+    pl.ksplit = ceil_div(steps, pl.steps_per_split);
+    pl.part_bytes = pl.ksplit > 1 ? (size_t)pl.ksplit * pl.M * pl.Nc * 4 : 0;
+    if (tiles * pl.ksplit >= lim) return kErrTooLarge;
+    return kStatusOk;
 }
 
 }  // namespace convnet

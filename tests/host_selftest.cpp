@@ -76,6 +76,29 @@ int main()
             CHECK(make_plan(op, dense).total == make_plan(op, wide).total);
             CHECK(!make_plan(op, dense).widen && !make_plan(op, dense).widen_w && !make_plan(op, dense).patch);
         }
+    // fully connected plans: GEMM views, ranges that cover the reduction exactly, argument checks
+    FcPlan fp;
+    CHECK(make_fc_plan(fp, kOpFwd, 128, 9216, 4096, 0) == kStatusOk);
+    CHECK(fp.M == 128 && fp.Nc == 4096 && fp.K == 9216 && !fp.at && !fp.bt && fp.ldd == 4096);
+    CHECK(fp.ksplit == 16 && fp.steps_per_split == 36 && fp.part_bytes == (size_t)16 * 128 * 4096 * 4);
+    CHECK(make_fc_plan(fp, kOpBwdData, 128, 9216, 4096, 0) == kStatusOk);
+    CHECK(fp.M == 128 && fp.Nc == 9216 && fp.K == 4096 && !fp.at && fp.bt && fp.lda == 4096 && fp.ldb == 9216);
+    CHECK(fp.ksplit * fp.steps_per_split >= 256 && (fp.ksplit - 1) * fp.steps_per_split < 256);
+    CHECK(make_fc_plan(fp, kOpBwdFilter, 128, 9216, 4096, 0) == kStatusOk);
+    CHECK(fp.M == 4096 && fp.Nc == 9216 && fp.K == 128 && fp.at && fp.bt && fp.ksplit == 1 && fp.part_bytes == 0);
+    for (int K : {1, 15, 16, 17, 100, 1000, 4096, 9216})
+        for (int op : {kOpFwd, kOpBwdData, kOpBwdFilter}) {
+            const int N = op == kOpBwdFilter ? K : 8, I = op == kOpFwd ? 4 * K : 12, O = op == kOpBwdData ? 4 * K : 20;
+            CHECK(make_fc_plan(fp, op, N, I, O, 0) == kStatusOk);
+            const int steps = (fp.K + 15) / 16;
+            CHECK(fp.ksplit >= 1 && fp.ksplit * fp.steps_per_split >= steps && (fp.ksplit - 1) * fp.steps_per_split < steps);
+        }
+    CHECK(make_fc_plan(fp, kOpFwd, 0, 16, 16, 0) == kErrInvalidArg);
+    CHECK(make_fc_plan(fp, kOpFwd, 4, 18, 16, 0) == kErrInvalidArg);       // I not a multiple of 4
+    CHECK(make_fc_plan(fp, kOpFwd, 4, 16, 18, 0) == kErrInvalidArg);
+    CHECK(make_fc_plan(fp, 3, 4, 16, 16, 0) == kErrInvalidArg);
+    CHECK(make_fc_plan(fp, kOpFwd, 4, 16, 16, 1) == kErrBadDtype);
+    CHECK(make_fc_plan(fp, kOpFwd, 4, 1 << 16, 1 << 15, 0) == kErrTooLarge);
     std::printf("%llu divisions checked, %d failures\n", checked, fails);
     return fails ? 1 : 0;
 }

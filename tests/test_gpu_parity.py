@@ -683,3 +683,111 @@ def test_epilogue_argument_checks():
     assert L.conv_fwd_bias_relu(p(x), p(w), None, p(y), *dims, 1, 0, p(ws), 0, st) == (
         hp.ERR_WORKSPACE if need else hp.OK)
     torch.cuda.synchronize()
+
+
+# ----------------------------------------------------- fully connected layers, SGD update ---
+FC_SHAPES = [
+    # N, I, O
+    (1, 4, 4),
+    (3, 8, 12),
+    (5, 100, 36),            # reduction tails of 4 and of 5 samples
+    (130, 260, 132),         # two tiles each way, ragged
+    (257, 16, 1000),         # three row tiles, last output tile of 104
+    (64, 4096, 1000),        # fc8 at a shard of 64
+    (128, 9216, 4096),       # fc6 at a shard of 128 (reduction split 16 ways forward)
+]
+
+
+@pytest.mark.parametrize("shape", FC_SHAPES)
+def test_fc_layers_full_compare(shape):
+    N, I, O = shape
+    x = synth.gaussian((N, I), 201)
+    w = synth.gaussian((O, I), 202, 0.05)
+    dy = synth.gaussian((N, O), 203)
+    b = synth.gaussian((O,), 204)
+    xd, wd, dyd, bd = dev(x), dev(w), dev(dy), dev(b)
+    nan2 = lambda *s: torch.full(s, float("nan"), dtype=torch.float32, device="cuda")
+    tol = TOL["f32"]
+    y = hp.fc_fwd(xd, wd, y=nan2(N, O))
+    assert norm_err(y.cpu().numpy(), oracle.fc_fwd(x, w)) <= tol
+    yb = hp.fc_fwd(xd, wd, bias=bd, relu=True, y=nan2(N, O))
+    assert norm_err(yb.cpu().numpy(), oracle.fc_fwd(x, w, b, relu=True)) <= tol
+    assert float(yb.min()) >= 0.0
+    # bias and ReLU are applied to the same fp32 sums the plain call stores
+    assert torch.equal(yb, torch.clamp_min(y + bd[None, :], 0.0))
+    dx = hp.fc_bwd_data(dyd, wd, dx=nan2(N, I))
+    assert norm_err(dx.cpu().numpy(), oracle.fc_bwd_data(dy, w)) <= tol
+    dw = hp.fc_bwd_filter(xd, dyd, dw=nan2(O, I))
+    assert norm_err(dw.cpu().numpy(), oracle.fc_bwd_filter(x, dy)) <= tol
+    # fixed summation order
+    assert torch.equal(y, hp.fc_fwd(xd, wd)) and torch.equal(dx, hp.fc_bwd_data(dyd, wd))
+    assert torch.equal(dw, hp.fc_bwd_filter(xd, dyd))
+
+
+def test_fc_small_integers_are_exact_and_guards_untouched():
+    N, I, O = 37, 72, 140
+    x, w, dy = synth.small_integers((N, I), 211), synth.small_integers((O, I), 212), synth.small_integers((N, O), 213)
+    xd, wd, dyd = dev(x), dev(w), dev(dy)
+    assert np.array_equal(hp.fc_fwd(xd, wd).cpu().numpy(), oracle.fc_fwd(x, w))
+    assert np.array_equal(hp.fc_bwd_data(dyd, wd).cpu().numpy(), oracle.fc_bwd_data(dy, w))
+    assert np.array_equal(hp.fc_bwd_filter(xd, dyd).cpu().numpy(), oracle.fc_bwd_filter(x, dy))
+    # outputs inside a larger allocation: nothing outside [N][O] / [N][I] / [O][I] is written
+    for fn, shape in ((lambda out: hp.fc_fwd(xd, wd, y=out), (N, O)),
+                      (lambda out: hp.fc_bwd_data(dyd, wd, dx=out), (N, I)),
+                      (lambda out: hp.fc_bwd_filter(xd, dyd, dw=out), (O, I))):
+        n = shape[0] * shape[1]
+        buf = torch.full((n + 2048,), -7.0, dtype=torch.float32, device="cuda")
+        fn(buf[1024:1024 + n].view(shape))
+        torch.cuda.synchronize()
+        assert bool((buf[:1024] == -7.0).all()) and bool((buf[1024 + n:] == -7.0).all())
+        assert not bool(torch.isnan(buf).any())
+
+
+def test_fc_argument_checks():
+    import ctypes
+    L = hp.lib()
+    t = torch.zeros(4096, device="cuda")
+    p = lambda off=0: ctypes.c_void_p(t.data_ptr() + off)
+    st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    assert L.fc_fwd(p(), p(), None, p(), 4, 6, 8, 0, 0, None, 0, st) == hp.ERR_INVALID_ARG      # I % 4
+    assert L.fc_fwd(p(), p(), None, p(), 4, 8, 6, 0, 0, None, 0, st) == hp.ERR_INVALID_ARG      # O % 4
+    assert L.fc_fwd(p(), p(), None, None, 4, 8, 8, 0, 0, None, 0, st) == hp.ERR_INVALID_ARG
+    assert L.fc_fwd(p(), p(), None, p(), 4, 8, 8, 3, 0, None, 0, st) == hp.ERR_INVALID_ARG      # relu flag
+    assert L.fc_fwd(p(), p(), None, p(), 4, 8, 8, 0, 1, None, 0, st) == hp.ERR_BAD_DTYPE
+    assert L.fc_fwd(p(4), p(), None, p(), 4, 8, 8, 0, 0, None, 0, st) == hp.ERR_MISALIGNED
+    assert L.fc_bwd_data(p(), p(), p(), 0, 8, 8, 0, None, 0, st) == hp.ERR_INVALID_ARG
+    need = L.fc_workspace_bytes(hp.OP_FWD, 8, 4096, 8, 0)
+    assert need > 0 and L.fc_workspace_bytes(hp.OP_FWD, 8, 4095, 8, 0) == 0
+    big = torch.zeros(8 * 4096, device="cuda")
+    assert L.fc_fwd(ctypes.c_void_p(big.data_ptr()), ctypes.c_void_p(big.data_ptr()), None, p(), 8, 4096, 8, 0, 0,
+                    None, 0, st) == hp.ERR_WORKSPACE
+    assert L.sgd_update(None, p(), p(), 4, 0.1, 0.0, 0.0, 1.0, st) == hp.ERR_INVALID_ARG
+    assert L.sgd_update(p(), p(), p(), -1, 0.1, 0.0, 0.0, 1.0, st) == hp.ERR_INVALID_ARG
+    assert L.sgd_update(None, None, None, 0, 0.1, 0.0, 0.0, 1.0, st) == hp.OK
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("count", [1, 3, 4, 5, 1003, 1 << 20, 37748736 // 8 + 1])
+def test_sgd_update_matches_oracle(count):
+    w = synth.gaussian((count,), 221)
+    g = synth.gaussian((count,), 222)
+    v = synth.gaussian((count,), 223, 0.1)
+    for off in (0, 1):                       # off = 1: pointers 4 bytes past a 16-byte boundary (scalar path)
+        store = [torch.zeros(count + 4, device="cuda") for _ in range(3)]
+        wd, gd, vd = (s[off:off + count] for s in store)
+        wd.copy_(dev(w)); gd.copy_(dev(g)); vd.copy_(dev(v))
+        rw, rv = w.astype(np.float64), v.astype(np.float64)
+        for step in range(2):
+            hp.sgd_update(wd, gd, vd, lr=0.01, momentum=0.9, weight_decay=5e-4, grad_scale=1.0 / 128)
+            rw, rv = oracle.sgd_update(rw, g, rv, 0.01, 0.9, 5e-4, 1.0 / 128)
+            # the reference continues from the fp32 state the device holds, so each step is compared on its own
+            assert norm_err(vd.cpu().numpy(), rv) <= 1e-6 and norm_err(wd.cpu().numpy(), rw) <= 1e-6
+            rw, rv = wd.cpu().numpy().astype(np.float64), vd.cpu().numpy().astype(np.float64)
+        assert torch.equal(gd, dev(g))                                   # gradients only read
+        for s in store:                                                  # nothing outside the arrays touched
+            assert float(s[:off].abs().sum()) == 0.0 and float(s[off + count:].abs().sum()) == 0.0
+    # plain SGD is exactly w - lr * dw in fp32
+    wd, gd, vd = dev(w), dev(g), torch.zeros(count, device="cuda")
+    hp.sgd_update(wd, gd, vd, lr=0.5)
+    want = (w - (np.float32(0.5) * g).astype(np.float32)).astype(np.float32)
+    assert np.array_equal(wd.cpu().numpy(), want)
