@@ -120,6 +120,61 @@ def two_column_layers(N, hp, synth, conv_flops, torch, reps=10):
     return out
 
 
+PEAK_HBM_TBS = 8.0                 # MI355X HBM3E peak (published)
+
+
+def whole_network(N, hp, torch, steps):
+    """The fully connected layers (fp32 MFMA GEMMs), the SGD update, and one whole training step of the network on
+    one shard (conv stack + fc6-fc8 + update): per-call timings with HIP events and the step's wall time."""
+    from paper_1312_5853_amd.stack import FullNetwork, FC_LAYERS, fc_flops, stack_flops
+    net = FullNetwork(N)
+    out = {}
+
+    def timed(fn, reps=10):
+        for _ in range(3):
+            fn()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        for _ in range(reps):
+            fn()
+        e.record()
+        torch.cuda.synchronize()
+        return s.elapsed_time(e) / reps
+
+    net.forward()
+    for idx, (name, i, o) in enumerate(FC_LAYERS):
+        x = net.a5.view(N, -1) if idx == 0 else net.fc_y[FC_LAYERS[idx - 1][0]]
+        w, b, dy = net.fc_w[name], net.fc_b[name], torch.randn((N, o), device="cuda")
+        dx = torch.empty((N, i), device="cuda")
+        calls = {"fwd": lambda: hp.fc_fwd(x, w, b, relu=True, y=net.fc_y[name], ws=net.ws),
+                 "dgrad": lambda: hp.fc_bwd_data(dy, w, dx=dx, ws=net.ws),
+                 "wgrad": lambda: hp.fc_bwd_filter(x, dy, dw=net.fc_dw[name], ws=net.ws)}
+        for pname, fn in calls.items():
+            ms = timed(fn)
+            tf = 2.0 * N * i * o / ms / 1e9
+            out["%s.%s" % (name, pname)] = {"ms": round(ms, 4), "tflops": round(tf, 1),
+                                            "frac_peak": round(tf / PEAK_FP32_MFMA_TFLOPS, 4)}
+    nparam = sum(p.numel() for p, _ in net.params)
+    ms = timed(net.update)
+    out["sgd_update"] = {"ms": round(ms, 4), "params": nparam, "launches": len(net.params),
+                         "hbm_tb_per_s": round(nparam * 20 / ms / 1e9, 3),       # w, dw, v read; w, v written
+                         "frac_hbm_peak": round(nparam * 20 / ms / 1e9 / PEAK_HBM_TBS, 4)}
+    for _ in range(3):
+        net.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        net.step()
+    torch.cuda.synchronize()
+    step_ms = (time.perf_counter() - t0) * 1e3 / steps
+    gf = (stack_flops(N) + fc_flops(N)) / 1e9
+    out["step"] = {"ms": round(step_ms, 4), "images_per_s": round(N / step_ms * 1e3, 1), "gflop": round(gf, 2),
+                   "tflops": round(gf / step_ms, 2),
+                   "what": "conv1-5 + glue, fc6-fc8 with bias/ReLU, SGD update with momentum and weight decay; "
+                           "seeded gradient instead of a loss, no dropout / response normalisation"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,12 +255,13 @@ def main():
         "flops_per_launch": dom_flops / len(dom_keys),
     }
 
-    columns, bf16 = None, None
+    columns, bf16, network = None, None, None
     if not args.stack_only:
+        del stack
+        network = whole_network(N, hp, torch, args.steps)
         columns = two_column_layers(N, hp, synth, conv_flops, torch)
         bf16 = bf16_layers(N, hp, synth, conv_flops, torch)
         # the same step with bf16 tensors end to end (fp32 accumulation, fp32 filter gradients)
-        del stack
         bstack = ConvStack(N, dtype="bf16")
         for _ in range(3):
             bstack.step()
@@ -233,7 +289,9 @@ def main():
         "roofline": roofline,
         "two_column_conv4_conv5_fp32": columns,
         "bf16_in_fp32_acc": bf16,
-        "context": "paper: 10.5 days per 100 epochs on one NVIDIA TITAN at batch 256 (whole network, not this path)",
+        "whole_network_fp32": network,
+        "context": "paper: 10.5 days per 100 epochs on one NVIDIA TITAN at batch 256 (whole network with data "
+                   "loading: about 141 images/s; context for whole_network_fp32.step, not for value)",
     }
     if not args.no_cpu_baseline and not args.stack_only:
         out["cpu_baseline"] = cpu_baseline()

@@ -139,3 +139,69 @@ class ConvStack:
     def step(self):
         self.forward()
         return self.backward()
+
+
+FC_LAYERS = (("fc6", 256 * 6 * 6, 4096), ("fc7", 4096, 4096), ("fc8", 4096, 1000))
+
+
+def fc_flops(N):
+    """Nominal FLOPs of the three fully connected layers, forward + backward-data + backward-filter (the first one
+    included: its input gradient feeds the convolutional stack)."""
+    return sum(3 * 2.0 * N * i * o for _, i, o in FC_LAYERS)
+
+
+class FullNetwork(ConvStack):
+    """The convolutional stack with the three fully connected layers of the network on top (9216 -> 4096 -> 4096 ->
+    1000, bias and ReLU after the first two) and the SGD update of every parameter: one whole synchronous training
+    step on one GPU's shard, fp32.  The loss is replaced by a seeded gradient on the last layer's output; dropout,
+    response normalisation and the soft-max are not part of it."""
+
+    def __init__(self, N, seed=synth.SEED_BASE + 96, device="cuda", lr=0.01, momentum=0.9, weight_decay=5e-4):
+        super().__init__(N, seed=seed, device=device, dtype="f32")
+        self.lr, self.momentum, self.weight_decay = lr, momentum, weight_decay
+        f = dict(dtype=torch.float32, device=device)
+        self.fc_w, self.fc_b, self.fc_dw, self.fc_db, self.fc_y, self.fc_dy = {}, {}, {}, {}, {}, {}
+        for j, (name, i, o) in enumerate(FC_LAYERS):
+            self.fc_w[name] = torch.from_numpy(synth.gaussian((o, i), seed + 20 + 2 * j, synth.STD_FILTER)).to(device)
+            self.fc_b[name] = torch.from_numpy(synth.gaussian((o,), seed + 21 + 2 * j, 0.1)).to(device)
+            self.fc_dw[name] = torch.empty((o, i), **f)
+            self.fc_db[name] = torch.empty((o,), **f)
+            self.fc_y[name] = torch.empty((N, o), **f)
+            self.fc_dy[name] = torch.empty((N, o), **f)
+        self.g8 = torch.from_numpy(synth.gaussian((N, 1000), seed + 30)).to(device)
+        # one velocity per parameter tensor
+        self.params = ([(self.w[k], self.dw[k]) for k in CONV_ORDER]
+                       + [(self.fc_w[n], self.fc_dw[n]) for n, _, _ in FC_LAYERS]
+                       + [(self.fc_b[n], self.fc_db[n]) for n, _, _ in FC_LAYERS])
+        self.vel = [torch.zeros_like(p) for p, _ in self.params]
+
+    def forward(self):
+        a = super().forward().view(self.N, -1)
+        ws = self.ws
+        for name, _, _ in FC_LAYERS:
+            a = hp.fc_fwd(a, self.fc_w[name], self.fc_b[name], relu=name != "fc8", y=self.fc_y[name], ws=ws)
+        return a
+
+    def backward(self):
+        ws, N = self.ws, self.N
+        d = self.g8
+        for idx in range(len(FC_LAYERS) - 1, -1, -1):
+            name = FC_LAYERS[idx][0]
+            if name != "fc8":                   # through the ReLU that follows the layer
+                d = hp.relu_bwd(self.fc_y[name], d, self.fc_dy[name])
+            inp = self.fc_y[FC_LAYERS[idx - 1][0]] if idx > 0 else self.a5.view(N, -1)
+            hp.fc_bwd_filter(inp, d, dw=self.fc_dw[name], ws=ws)
+            hp.bias_bwd(d.view(N, -1, 1, 1), db=self.fc_db[name], ws=ws)
+            dx = self.fc_dy[FC_LAYERS[idx - 1][0]] if idx > 0 else self.g5.view(N, -1)
+            d = hp.fc_bwd_data(d, self.fc_w[name], dx=dx, ws=ws)
+        return super().backward()
+
+    def update(self):
+        """Mean gradient over this shard's N samples (a data-parallel job would first sum the shards' gradients)."""
+        for (p, g), v in zip(self.params, self.vel):
+            hp.sgd_update(p, g, v, self.lr, self.momentum, self.weight_decay, 1.0 / self.N)
+
+    def step(self):
+        self.forward()
+        self.backward()
+        self.update()

@@ -791,3 +791,46 @@ def test_sgd_update_matches_oracle(count):
     hp.sgd_update(wd, gd, vd, lr=0.5)
     want = (w - (np.float32(0.5) * g).astype(np.float32)).astype(np.float32)
     assert np.array_equal(wd.cpu().numpy(), want)
+
+
+def test_full_network_step_fc_part_and_update():
+    """One whole training step (conv stack, three fully connected layers, SGD update) at a small batch: the fully
+    connected part and the update are checked call by call against the oracle on the tensors each call read (the
+    convolutional part has its own test above)."""
+    from paper_1312_5853_amd.stack import FullNetwork, FC_LAYERS, CONV_ORDER
+    N = 2
+    net = FullNetwork(N)
+    c = lambda t: t.detach().cpu().numpy().copy()
+    before = [c(p) for p, _ in net.params]
+    net.forward()
+    net.backward()
+    torch.cuda.synchronize()
+    tol = TOL["f32"]
+    a = c(net.a5).reshape(N, -1)
+    acts = {}
+    for name, _, _ in FC_LAYERS:
+        want = oracle.fc_fwd(a, c(net.fc_w[name]), c(net.fc_b[name]), relu=name != "fc8")
+        got = c(net.fc_y[name])
+        assert norm_err(got, want) <= tol, name
+        acts[name] = a
+        a = got
+    d = c(net.g8)
+    for name, _, _ in reversed(FC_LAYERS):
+        if name != "fc8":
+            d_ref = oracle.relu_bwd(c(net.fc_y[name]), d)
+            d = c(net.fc_dy[name])                         # holds the gradient after the in-place ReLU backward
+            assert norm_err(d, d_ref) <= tol, name
+        assert norm_err(c(net.fc_dw[name]), oracle.fc_bwd_filter(acts[name], d)) <= tol, name
+        assert norm_err(c(net.fc_db[name]), d.astype(np.float64).sum(axis=0)) <= 1e-6, name
+        d_next = oracle.fc_bwd_data(d, c(net.fc_w[name]))
+        d = d_next                                         # compared one layer down, after that layer's ReLU
+    assert norm_err(c(net.g5).reshape(N, -1), d) <= tol
+    # the convolutional backward consumed g5: its last filter gradient is finite and non-zero
+    assert np.isfinite(c(net.dw["conv1"])).all() and np.abs(c(net.dw["conv1"])).max() > 0
+    grads = [c(g) for _, g in net.params]
+    net.update()
+    torch.cuda.synchronize()
+    assert len(net.params) == len(CONV_ORDER) + 2 * len(FC_LAYERS)
+    for (p, _), w0, g, v in zip(net.params, before, grads, net.vel):
+        w_ref, v_ref = oracle.sgd_update(w0, g, np.zeros_like(w0), net.lr, net.momentum, net.weight_decay, 1.0 / N)
+        assert norm_err(c(p), w_ref) <= 1e-6 and norm_err(c(v), v_ref) <= 1e-6
