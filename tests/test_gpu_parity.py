@@ -834,3 +834,63 @@ def test_full_network_step_fc_part_and_update():
     for (p, _), w0, g, v in zip(net.params, before, grads, net.vel):
         w_ref, v_ref = oracle.sgd_update(w0, g, np.zeros_like(w0), net.lr, net.momentum, net.weight_decay, 1.0 / N)
         assert norm_err(c(p), w_ref) <= 1e-6 and norm_err(c(v), v_ref) <= 1e-6
+
+
+def test_stack_step_full_batch_sampled():
+    """The benchmarked step itself (N = 128: grouped conv2 calls, conv3 / conv4 with the ReLU in the epilogue, the
+    backward-data passes with the ReLU mask, every tile shape and reduction split the bench times): each convolution
+    output is checked on sampled elements against the oracle's element-wise definitions applied to the tensors that
+    call read on the GPU."""
+    from paper_1312_5853_amd.stack import ConvStack
+    N = 128
+    st = ConvStack(N)
+    st.step()
+    torch.cuda.synchronize()
+    tol = TOL["f32"]
+    c64 = lambda t: t.cpu().numpy().astype(np.float64)
+
+    def sample(t, count, seed):
+        idx = np.unique(np.concatenate([synth.sample_indices(t.numel(), count, seed), edge_indices(t.shape)]))
+        return idx, t.reshape(-1)[torch.from_numpy(idx).cuda()].cpu().numpy()
+
+    def column(t, g, width):
+        return t[:, g * width:(g + 1) * width].contiguous()
+
+    w = {k: c64(v) for k, v in st.w.items()}
+    # forward
+    idx, got = sample(st.y1, 20000, 11)
+    assert norm_err(got, oracle.conv_fwd_at(c64(st.x0), w["conv1"], 4, 2, idx)) <= tol
+    a1, a2 = c64(st.a1), c64(st.a2)
+    for g in range(2):
+        idx, got = sample(column(st.y2, g, 128), 10000, 12 + g)
+        ref = oracle.conv_fwd_at(np.ascontiguousarray(a1[:, 48 * g:48 * g + 48]), w["conv2"][128 * g:128 * g + 128],
+                                 1, 2, idx)
+        assert norm_err(got, ref) <= tol
+    y3, y4 = c64(st.y3), c64(st.y4)
+    for out, inp, name, seed in ((st.y3, a2, "conv3", 14), (st.y4, y3, "conv4", 15)):
+        idx, got = sample(out, 20000, seed)
+        ref = np.maximum(oracle.conv_fwd_at(inp, w[name], 1, 1, idx), 0.0)          # ReLU in the epilogue
+        assert norm_err(got, ref) <= tol and got.min() >= 0.0
+    idx, got = sample(st.y5, 20000, 16)
+    assert norm_err(got, oracle.conv_fwd_at(y4, w["conv5"], 1, 1, idx)) <= tol
+    # backward
+    dy5, dy4, dy3, dy2, dy1 = (c64(t) for t in (st.dy5, st.dy4, st.dy3, st.dy2, st.dy1))
+    for dx_t, dy, act, name, seed in ((st.dy4, dy5, y4, "conv5", 17), (st.dy3, dy4, y3, "conv4", 18)):
+        idx, got = sample(dx_t, 1500, seed)
+        ref = oracle.conv_bwd_data_at(dy, w[name], 13, 13, 1, 1, idx)
+        ref = np.where(act.reshape(-1)[idx] > 0, ref, 0.0)                          # ReLU mask in the epilogue
+        assert norm_err(got, ref) <= tol
+    idx, got = sample(st.da2, 1500, 19)
+    assert norm_err(got, oracle.conv_bwd_data_at(dy3, w["conv3"], 13, 13, 1, 1, idx)) <= tol
+    for g in range(2):
+        dyg = np.ascontiguousarray(dy2[:, 128 * g:128 * g + 128])
+        idx, got = sample(column(st.da1, g, 48), 1500, 20 + g)
+        assert norm_err(got, oracle.conv_bwd_data_at(dyg, w["conv2"][128 * g:128 * g + 128], 27, 27, 1, 2, idx)) <= tol
+        idx, got = sample(st.dw["conv2"][128 * g:128 * g + 128], 1500, 22 + g)
+        ref = oracle.conv_bwd_filter_at(np.ascontiguousarray(a1[:, 48 * g:48 * g + 48]), dyg, 5, 5, 1, 2, idx)
+        assert norm_err(got, ref) <= tol
+    for name, inp, dy, seed in (("conv5", y4, dy5, 24), ("conv4", y3, dy4, 25), ("conv3", a2, dy3, 26)):
+        idx, got = sample(st.dw[name], 1500, seed)
+        assert norm_err(got, oracle.conv_bwd_filter_at(inp, dy, 3, 3, 1, 1, idx)) <= tol
+    idx, got = sample(st.dw["conv1"], 1500, 27)
+    assert norm_err(got, oracle.conv_bwd_filter_at(c64(st.x0), dy1, 11, 11, 4, 2, idx)) <= tol
