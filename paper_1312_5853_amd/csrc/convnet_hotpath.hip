@@ -1527,6 +1527,7 @@ struct WgradArgs {
     int J;                // N*P*Q
     int chunks_per_split;
     int mtiles, ntiles;
+    int units, units_per_xcd;   // units = tiles * splits; the grid is 8 * units_per_xcd
     FastDiv div_plane, div_q;
 };
 
@@ -1541,9 +1542,14 @@ __global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
     __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
     __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
 
+    // Work-groups are dealt round-robin to the 8 XCDs; each XCD takes a contiguous eighth of the (split, tile)
+    // list, so the tiles of one split -- which read the same range of dy and overlapping rows of x -- run on
+    // one XCD at the same time and share its L2.
     const int tiles = p.mtiles * p.ntiles;
-    const int split = blockIdx.x / tiles;
-    const int tile = blockIdx.x - split * tiles;
+    const int unit = (blockIdx.x & 7) * p.units_per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= p.units_per_xcd || unit >= p.units) return;
+    const int split = unit / tiles;
+    const int tile = unit - split * tiles;
     const int mt = tile % p.mtiles, nt = tile / p.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
 
@@ -3542,7 +3548,9 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
     a.div_plane = make_fastdiv((uint32_t)(pb.P * pb.Q));
     a.div_q = make_fastdiv((uint32_t)pb.Q);
     // the table kernel reads fp32 or bf16 inputs itself
-    launch_wgrad(pl.tile, a, a.mtiles * a.ntiles * pl.nsplit, pb.dtype == kDtypeBf16, st);
+    a.units = a.mtiles * a.ntiles * pl.nsplit;
+    a.units_per_xcd = ceil_div(a.units, 8);
+    launch_wgrad(pl.tile, a, 8 * a.units_per_xcd, pb.dtype == kDtypeBf16, st);
     int rc = check_launch();
     if (rc != kStatusOk) return rc;
     if (pl.nsplit > 1) {
