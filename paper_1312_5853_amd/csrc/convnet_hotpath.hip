@@ -768,7 +768,7 @@ __global__ __launch_bounds__(kThreads, 2) void colgemm_fast_kernel(const ColGemm
 // b128 and feeds element t to the t-th instruction, so the 16 elements of a step
 // are consumed in the order (t, 4+t, 8+t, 12+t) on both operands.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void colgemm_rows48_kernel(const ColGemmFastArgs p)
+__global__ __launch_bounds__(kThreads, 3) void colgemm_rows48_kernel(const ColGemmFastArgs p)
 {
     constexpr int BM = 48, BN = 256, KC = 16, PITCH = KC + 4;
     constexpr int TM = 3, TN = 4;            // 16 x 16 blocks per wave
