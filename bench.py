@@ -250,7 +250,7 @@ def main():
         "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
         # HBM bytes per launch of this kernel from rocprofv3 FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00), factors from a
         # 256 MiB copy; collected offline (profiles/stack_n128_fp32_hbm_traffic.txt), valid for the default N = 128
-        "traffic": 123.7e6 if N == 128 else None,
+        "traffic": 140.4e6 if N == 128 else None,
         "launches_per_step": len(dom_keys), "avg_launch_ms": round(dom_ms / len(dom_keys), 4),
         "flops_per_launch": dom_flops / len(dom_keys),
     }
