@@ -2835,6 +2835,19 @@ __global__ __launch_bounds__(256) void bias_bwd_partial(const T *__restrict__ dy
     if (tid == 0) part[k * nsplit + sidx] = red[0];
 }
 
+// Bias gradient of one-position planes (a fully connected layer's [N][K] output gradient): thread k adds column k
+// over the samples in order; neighbouring threads read neighbouring addresses.
+template <typename T>
+__global__ void bias_bwd_columns(const T *__restrict__ dy, float *__restrict__ db, int N, int K)
+{
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    float acc = 0.f;
+#pragma unroll 8
+    for (int n = 0; n < N; ++n) acc += ld_elem(dy, (int64_t)n * K + k);
+    db[k] = acc;
+}
+
 // second stage: db[k] = part[k][0] + part[k][1] + ...
 __global__ void bias_bwd_finish(const float *__restrict__ part, float *__restrict__ db, int K, int nsplit)
 {
@@ -3930,6 +3943,15 @@ int bias_bwd(const void *dy, void *db, int N, int K, int PQ, int dtype, void *ws
     if (!ws || ws_bytes < bias_bwd_workspace_bytes(N, K)) return kErrWorkspace;
     if (!aligned(ws, 256)) return kErrMisaligned;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (PQ == 1) {
+        if (eb == 4)
+            hipLaunchKernelGGL(bias_bwd_columns<float>, dim3(grid1d(K, 64)), dim3(64), 0, st,
+                               static_cast<const float *>(dy), static_cast<float *>(db), N, K);
+        else
+            hipLaunchKernelGGL(bias_bwd_columns<unsigned short>, dim3(grid1d(K, 64)), dim3(64), 0, st,
+                               static_cast<const unsigned short *>(dy), static_cast<float *>(db), N, K);
+        return check_launch();
+    }
     const int nsplit = bias_splits(N, K);
     float *part = static_cast<float *>(ws);
     if (eb == 4)
