@@ -92,6 +92,15 @@ ODD_SHAPES = [
     (3, 48, 9, 9, 40, 3, 3, 1, 1),         # forward with 40 rows: the 48-row tile of 16x16 blocks
     (2, 40, 11, 7, 32, 3, 3, 1, 1),        # backward-data with 40 rows, ragged 256-column tile
     (7, 48, 14, 14, 64, 5, 5, 1, 2),       # backward-data with 48 rows, several column tiles
+    # channel count 16 / 32 (fast kernels) on small planes: P*Q = 1, 2, 3 and 0 mod 4, dy tensors of 1 and 3
+    # elements, a stride-2 layer
+    (2, 16, 5, 5, 3, 3, 3, 1, 1),          # P*Q = 25
+    (2, 16, 4, 5, 5, 3, 3, 1, 0),          # P*Q = 6
+    (3, 32, 3, 9, 2, 3, 3, 1, 0),          # P*Q = 7
+    (2, 16, 6, 6, 130, 3, 3, 1, 0),        # P*Q = 16, K past one row tile
+    (1, 16, 3, 3, 1, 3, 3, 1, 0),          # dy has one element
+    (3, 16, 1, 1, 1, 1, 1, 1, 0),          # dy has three elements
+    (5, 16, 9, 11, 7, 3, 3, 2, 1),         # stride 2: P*Q = 5*6 = 30
 ]
 
 
