@@ -1,0 +1,931 @@
+// Backward-filter kernels (tap table, fast, bf16, bf16 linear) and the kernels that sum their partials.
+// Part of convnet_hotpath.hip: included there, inside its anonymous namespace, after the common
+// definitions (kThreads, kPitch, vector types); not a stand-alone header.
+// ---------------------------------------------------------------------------
+// Backward-filter: dw[k][g] = sum_j dy[k][j] * im2col(x)[g][j],  j = (n, p, q)
+// ---------------------------------------------------------------------------
+struct WgradArgs {
+    const void *dy;       // fp32 or bfloat16 (the kernel's TI), both inputs alike
+    const void *x;
+    const int4 *tab;      // forward-style tap table over g = (c, r, s)
+    float *out;           // dw, or partial sums [split][K][CRS]
+    int K, CRS;
+    int P, Q, H, W, stride, pad;
+    int dy_bs, x_bs;
+    int J;                // N*P*Q
+    int chunks_per_split;
+    int mtiles, ntiles;
+    int units, units_per_xcd;   // units = tiles * splits; the grid is 8 * units_per_xcd
+    FastDiv div_plane, div_q;
+};
+
+template <int TM, int TN, int WM, int WN, typename TI>
+__global__ __launch_bounds__(kThreads) void wgrad_kernel(const WgradArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int RA = BM / 16, RB = BN / 16;    // rows per thread per step
+    constexpr int EB = (int)sizeof(TI);          // bytes per input element
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
+
+    // Work-groups are dealt round-robin to the 8 XCDs; each XCD takes a contiguous eighth of the (split, tile)
+    // list, so the tiles of one split -- which read the same range of dy and overlapping rows of x -- run on
+    // one XCD at the same time and share its L2.
+    const int tiles = p.mtiles * p.ntiles;
+    const int unit = (blockIdx.x & 7) * p.units_per_xcd + (blockIdx.x >> 3);
+    if ((int)(blockIdx.x >> 3) >= p.units_per_xcd || unit >= p.units) return;
+    const int split = unit / tiles;
+    const int tile = unit - split * tiles;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // loader role: reduction position jj of the step, rows g, g+16, ...
+    const int jj = tid & 15, g = tid >> 4;
+    const int PQ = p.P * p.Q;
+
+    int boff[RB], bdr[RB], bds[RB];
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        const int4 tap = p.tab[n0 + g + 16 * i];     // table is padded past CRS with failing taps
+        boff[i] = tap.x / 4 * EB; bdr[i] = tap.y; bds[i] = tap.z;     // the table holds byte offsets of fp32 elements
+    }
+
+    const int jbeg = split * p.chunks_per_split * kChunk;
+    int jend = jbeg + p.chunks_per_split * kChunk;
+    if (jend > p.J) jend = p.J;
+    const int nsteps = (jend - jbeg + kChunk - 1) / kChunk;
+
+    // register set t & 1 and LDS buffer t & 1 hold step t; loads run two steps ahead and the LDS writes of the
+    // next step sit between the matrix instructions of the current one (see colgemm_fast_kernel)
+    TI areg[2][RA], breg[2][RB];                 // as loaded; widened when they are written to LDS
+    bool aok[2][RA], bok[2][RB];
+    const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
+    const char *x_bytes = reinterpret_cast<const char *>(p.x);
+    int abase = 0, bbase = 0, hb = 0, wb = 0, jnext = jbeg + jj;
+    bool jok = false;
+
+    auto slot_pos = [&]() {          // where this thread's reduction position sits
+        jok = jnext < jend;
+        const int js = jok ? jnext : jbeg;
+        const int n = (int)fastdiv((uint32_t)js, p.div_plane);
+        const int pq = js - n * PQ;
+        const int pp = (int)fastdiv((uint32_t)pq, p.div_q);
+        const int qq = pq - pp * p.Q;
+        const int hb0 = pp * p.stride - p.pad;
+        wb = qq * p.stride - p.pad;
+        abase = EB * (n * p.dy_bs + pq);                 // bytes
+        bbase = EB * (n * p.x_bs + hb0 * p.W + wb);
+        hb = jok ? hb0 : kInvalidTap;
+        jnext += kChunk;
+    };
+    auto slot_a = [&](int set, int i) {
+        const int k = m0 + g + 16 * i;
+        const bool ok = jok & (k < p.K);
+        areg[set][i] = *reinterpret_cast<const TI *>(dy_bytes + (uint32_t)(ok ? abase + EB * k * PQ : 0));
+        aok[set][i] = ok;
+    };
+    auto slot_b = [&](int set, int i) {
+        const int hh = hb + bdr[i], ww = wb + bds[i];
+        const bool ok = ((unsigned)hh < (unsigned)p.H) & ((unsigned)ww < (unsigned)p.W);
+        breg[set][i] = *reinterpret_cast<const TI *>(x_bytes + (uint32_t)(ok ? bbase + boff[i] : 0));
+        bok[set][i] = ok;
+    };
+    auto load_step = [&](int set) {
+        slot_pos();
+#pragma unroll
+        for (int i = 0; i < RA; ++i) slot_a(set, i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) slot_b(set, i);
+    };
+    auto store_a = [&](int set, int i) {
+        As[set][(g + 16 * i) * kPitch + jj] = aok[set][i] ? widen_elem(areg[set][i]) : 0.f;
+    };
+    auto store_b = [&](int set, int i) {
+        Bs[set][(g + 16 * i) * kPitch + jj] = bok[set][i] ? widen_elem(breg[set][i]) : 0.f;
+    };
+    auto store_step = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < RA; ++i) store_a(set, i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) store_b(set, i);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * kPitch + half * 8;
+    const int b_frag = (wn * TN * 32 + l32) * kPitch + half * 8;
+    constexpr int NMMA = 8 * TM * TN;
+    constexpr int NLOAD = 1 + RA + RB, NSTORE = RA + RB;
+    constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);
+
+    if (nsteps > 0) {
+        load_step(0);
+        store_step(0);
+        if (nsteps > 1) load_step(1);
+    }
+    __syncthreads();
+    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
+        f32x4 fa[TM][2], fb[TN][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[par][a_frag + i * 32 * kPitch]);
+            fa[i][0] = q[0]; fa[i][1] = q[1];
+        }
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[par][b_frag + jn * 32 * kPitch]);
+            fb[jn][0] = q[0]; fb[jn][1] = q[1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                              acc[i][jn], 0, 0, 0);
+            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
+                    if (q < NLOAD) {
+                        if (mode == 2) {
+                            if (q == 0) slot_pos();
+                            else if (q - 1 < RA) slot_a(par, q - 1);
+                            else slot_b(par, q - 1 - RA);
+                        }
+                    } else {
+                        const int w = q - NLOAD;
+                        if (w < RA) store_a(par ^ 1, w);
+                        else store_b(par ^ 1, w - RA);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
+    }
+    const int rest = nsteps - step;
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
+    }
+
+    float *out = p.out + (size_t)split * p.K * p.CRS;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.CRS) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.CRS + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Backward-filter when C is a multiple of 16.  The GEMM columns are taken in
+// (r, s, c) order, c fastest, so the rows a thread stages (a block of BN/16
+// consecutive columns) are consecutive channels of ONE filter tap: one padding
+// test and one base address per step, channel stride between its loads -- the
+// same economy as colgemm_fast_kernel.  Partial sums land in the workspace as
+// [split][K][R*S*C]; finish_wgrad adds the splits in order and writes KCRS.
+// ---------------------------------------------------------------------------
+struct WgradFastArgs {
+    const float *dy;
+    const float *x;
+    float *part;          // [nsplit][K][ncols], columns in (r, s, c) order
+    int K, C, S, ncols;   // ncols = R*S*C
+    int P, Q, H, W, stride, pad;
+    int dy_bs, x_bs;
+    int J, chunks_per_split;
+    int mtiles, ntiles, nunits, units_per_xcd;
+    int x_plane_bytes, y_plane_bytes;
+    // columns of a grouped layer in one launch (fp32 kernel): nunits = tiles * nsplit * groups; column g reads
+    // dy + g * dy_gs and x + g * x_gs and writes part + g * part_gs (floats)
+    int nsplit, groups;
+    int64_t dy_gs, x_gs, part_gs;
+    FastDiv div_plane, div_q, div_c;
+};
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(kThreads) void wgrad_fast_kernel(const WgradFastArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int RA = BM / 16, RB = BN / 16;
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    __shared__ __attribute__((aligned(16))) float As[2][BM * kPitch];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BN * kPitch];
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.units_per_xcd + idx;
+    if (idx >= p.units_per_xcd || unit >= p.nunits) return;
+    const int tiles = p.mtiles * p.ntiles;
+    const int grp_col = unit / (tiles * p.nsplit);              // column of a grouped layer
+    const int unit_c = unit - grp_col * (tiles * p.nsplit);
+    const int split = unit_c / tiles;
+    const int tile = unit_c - split * tiles;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int jj = tid & 15, g = tid >> 4;
+    const int PQ = p.P * p.Q;
+
+    // A rows (filters k): a block of RA consecutive rows; rows past K are clamped
+    // for the address and zeroed by a_rows
+    const int arow0 = m0 + g * RA;
+    const int a_rows = min(max(p.K - arow0, 0), RA);
+    int a_off[RA];
+#pragma unroll
+    for (int i = 0; i < RA; ++i) a_off[i] = min(arow0 + i, p.K - 1) * p.y_plane_bytes;
+
+    // B rows (columns of dw): RB consecutive channels of one tap
+    const int col0 = n0 + g * RB;
+    const bool col_ok = col0 < p.ncols;
+    int tap_r, tap_s, b_off;
+    {
+        const int cc = col_ok ? col0 : 0;
+        const int rs = (int)fastdiv((uint32_t)cc, p.div_c);
+        const int c0 = cc - rs * p.C;
+        tap_r = rs / p.S;
+        tap_s = rs - tap_r * p.S;
+        b_off = c0 * p.x_plane_bytes + 4 * (tap_r * p.W + tap_s);
+    }
+
+    const int jbeg = split * p.chunks_per_split * kChunk;
+    const int jend = min(jbeg + p.chunks_per_split * kChunk, p.J);
+    const int nsteps = (jend - jbeg + kChunk - 1) / kChunk;
+
+    const char *dy_bytes = reinterpret_cast<const char *>(p.dy + (size_t)grp_col * p.dy_gs);
+    const char *x_bytes = reinterpret_cast<const char *>(p.x + (size_t)grp_col * p.x_gs);
+    // Register set t & 1 and LDS buffer t & 1 hold step t; loads run two steps ahead and the LDS writes of the
+    // next step sit between the matrix instructions of the current one (see colgemm_fast_kernel).
+    float areg[2][RA], breg[2][RB];
+    int a_lim[2] = {0, 0}, abase = 0, bbase = 0, jnext = jbeg + jj;
+    bool bok[2] = {false, false};
+
+    auto slot_pos = [&](int set) {   // where this thread's reduction position sits
+        const bool jok = jnext < jend;
+        const int js = jok ? jnext : jbeg;
+        const int n = (int)fastdiv((uint32_t)js, p.div_plane);
+        const int pq = js - n * PQ;
+        const int pp = (int)fastdiv((uint32_t)pq, p.div_q);
+        const int qq = pq - pp * p.Q;
+        const int hb = pp * p.stride - p.pad, wb = qq * p.stride - p.pad;
+        a_lim[set] = jok ? a_rows : 0;
+        abase = 4 * (n * p.dy_bs + pq);
+        bok[set] = jok & col_ok & ((unsigned)(hb + tap_r) < (unsigned)p.H) & ((unsigned)(wb + tap_s) < (unsigned)p.W);
+        bbase = bok[set] ? 4 * (n * p.x_bs + hb * p.W + wb) + b_off : 0;
+        jnext += kChunk;
+    };
+    auto slot_a = [&](int set, int i) {
+        areg[set][i] = *reinterpret_cast<const float *>(dy_bytes + (uint32_t)(abase + a_off[i]));
+    };
+    auto slot_b = [&](int set, int i) {
+        breg[set][i] = *reinterpret_cast<const float *>(x_bytes + (uint32_t)(bbase + i * p.x_plane_bytes));
+    };
+    auto load_step = [&](int set) {
+        slot_pos(set);
+#pragma unroll
+        for (int i = 0; i < RA; ++i) slot_a(set, i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) slot_b(set, i);
+    };
+    auto store_a = [&](int set, int i) {
+        As[set][(g * RA + i) * kPitch + jj] = i < a_lim[set] ? areg[set][i] : 0.f;
+    };
+    auto store_b = [&](int set, int i) {
+        Bs[set][(g * RB + i) * kPitch + jj] = bok[set] ? breg[set][i] : 0.f;
+    };
+    auto store_step = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < RA; ++i) store_a(set, i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) store_b(set, i);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * kPitch + half * 8;
+    const int b_frag = (wn * TN * 32 + l32) * kPitch + half * 8;
+    constexpr int NMMA = 8 * TM * TN;
+    constexpr int NLOAD = 1 + RA + RB, NSTORE = RA + RB;
+    constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);
+
+    if (nsteps > 0) {
+        load_step(0);
+        store_step(0);
+        if (nsteps > 1) load_step(1);
+    }
+    __syncthreads();
+    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
+        f32x4 fa[TM][2], fb[TN][2];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&As[par][a_frag + i * 32 * kPitch]);
+            fa[i][0] = q[0]; fa[i][1] = q[1];
+        }
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) {
+            const f32x4 *q = reinterpret_cast<const f32x4 *>(&Bs[par][b_frag + jn * 32 * kPitch]);
+            fb[jn][0] = q[0]; fb[jn][1] = q[1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i][t >> 2][t & 3], fb[jn][t >> 2][t & 3],
+                                                              acc[i][jn], 0, 0, 0);
+            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
+                    if (q < NLOAD) {
+                        if (mode == 2) {
+                            if (q == 0) slot_pos(par);
+                            else if (q - 1 < RA) slot_a(par, q - 1);
+                            else slot_b(par, q - 1 - RA);
+                        }
+                    } else {
+                        const int w = q - NLOAD;
+                        if (w < RA) store_a(par ^ 1, w);
+                        else store_b(par ^ 1, w - RA);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
+    }
+    const int rest = nsteps - step;                 // up to 3 steps left, the first in buffer 0
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
+    }
+
+    float *out = p.part + (size_t)grp_col * p.part_gs + (size_t)split * p.K * p.ncols;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.ncols + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Backward-filter with bf16 inputs on v_mfma_f32_32x32x16_bf16.  Same column
+// order and split scheme as wgrad_fast_kernel; a step covers 64 reduction
+// positions.  A thread stages a PAIR of adjacent positions for 16 rows of dy and
+// 16 channels of one tap of x (2-byte loads, lanes along positions), packs each
+// pair into one dword and writes it to the [row][64 positions] LDS tiles, from
+// which every MFMA operand (8 consecutive positions of a row) is one b128 read.
+// ---------------------------------------------------------------------------
+template <int TM, int TN, int WM, int WN, int KJ>
+__global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(const WgradFastArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int GROUPS = 2 * kThreads / KJ;   // row groups: a thread stages BM/GROUPS + BN/GROUPS rows of one position pair
+    constexpr int PITCHB = KJ * 2 + 16;
+    constexpr int NK = KJ / 16;
+    constexpr int RA = BM / GROUPS, RB = BN / GROUPS;
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    char *const As0 = reinterpret_cast<char *>(lds_fast);
+    char *const Bs0 = As0 + 2 * BM * PITCHB;
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.units_per_xcd + idx;
+    if (idx >= p.units_per_xcd || unit >= p.nunits) return;
+    const int tiles = p.mtiles * p.ntiles;
+    const int split = unit / tiles;
+    const int tile = unit - split * tiles;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int jp = tid % (KJ / 2), g = tid / (KJ / 2);
+    const int PQ = p.P * p.Q;
+
+    const int arow0 = m0 + g * RA;
+    const int a_rows = min(max(p.K - arow0, 0), RA);
+    int a_off[RA];
+#pragma unroll
+    for (int i = 0; i < RA; ++i) a_off[i] = min(arow0 + i, p.K - 1) * p.y_plane_bytes;
+
+    const int col0 = n0 + g * RB;
+    const bool col_ok = col0 < p.ncols;
+    int tap_r, tap_s, b_off;
+    {
+        const int cc = col_ok ? col0 : 0;
+        const int rs = (int)fastdiv((uint32_t)cc, p.div_c);
+        const int c0 = cc - rs * p.C;
+        tap_r = rs / p.S;
+        tap_s = rs - tap_r * p.S;
+        b_off = c0 * p.x_plane_bytes + 2 * (tap_r * p.W + tap_s);
+    }
+
+    // chunks_per_split counts 16-position chunks; steps here are KJ positions
+    const int steps_per_split = (p.chunks_per_split * 16 + KJ - 1) / KJ;
+    const int jbeg = split * steps_per_split * KJ;
+    const int jend = min(jbeg + steps_per_split * KJ, p.J);
+    const int nsteps = jend > jbeg ? (jend - jbeg + KJ - 1) / KJ : 0;
+
+    const char *dy_bytes = reinterpret_cast<const char *>(p.dy);
+    const char *x_bytes = reinterpret_cast<const char *>(p.x);
+    unsigned short areg[2][RA], breg[2][RB];
+    int a_lim[2] = {0, 0}, abase[2] = {0, 0}, bbase[2] = {0, 0};
+    bool bok[2] = {false, false};
+    int jnext = jbeg + 2 * jp;
+
+    auto slot_pos = [&]() {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int j = jnext + h;
+            const bool jok = j < jend;
+            const int js = jok ? j : jbeg;
+            const int n = (int)fastdiv((uint32_t)js, p.div_plane);
+            const int pq = js - n * PQ;
+            const int pp = (int)fastdiv((uint32_t)pq, p.div_q);
+            const int qq = pq - pp * p.Q;
+            const int hb = pp * p.stride - p.pad, wb = qq * p.stride - p.pad;
+            a_lim[h] = jok ? a_rows : 0;
+            abase[h] = 2 * (n * p.dy_bs + pq);
+            bok[h] = jok & col_ok & ((unsigned)(hb + tap_r) < (unsigned)p.H) & ((unsigned)(wb + tap_s) < (unsigned)p.W);
+            bbase[h] = bok[h] ? 2 * (n * p.x_bs + hb * p.W + wb) + b_off : 0;
+        }
+        jnext += KJ;
+    };
+    auto slot_a = [&](int q) {       // q = 2*i + h
+        const int i = q >> 1, h = q & 1;
+        areg[h][i] = *reinterpret_cast<const unsigned short *>(dy_bytes + (uint32_t)(abase[h] + a_off[i]));
+    };
+    auto slot_b = [&](int q) {
+        const int i = q >> 1, h = q & 1;
+        breg[h][i] = *reinterpret_cast<const unsigned short *>(x_bytes + (uint32_t)(bbase[h] + i * p.x_plane_bytes));
+    };
+    auto load_step = [&]() {
+        slot_pos();
+#pragma unroll
+        for (int q = 0; q < 2 * RA; ++q) slot_a(q);
+#pragma unroll
+        for (int q = 0; q < 2 * RB; ++q) slot_b(q);
+    };
+    auto store_step = [&](int buf) {
+        char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+#pragma unroll
+        for (int i = 0; i < RA; ++i) {
+            const unsigned lo = i < a_lim[0] ? (unsigned)areg[0][i] : 0u;
+            const unsigned hi = i < a_lim[1] ? (unsigned)areg[1][i] : 0u;
+            *reinterpret_cast<unsigned *>(As + (g * RA + i) * PITCHB + jp * 4) = lo | (hi << 16);
+        }
+#pragma unroll
+        for (int i = 0; i < RB; ++i) {
+            const unsigned lo = bok[0] ? (unsigned)breg[0][i] : 0u;
+            const unsigned hi = bok[1] ? (unsigned)breg[1][i] : 0u;
+            *reinterpret_cast<unsigned *>(Bs + (g * RB + i) * PITCHB + jp * 4) = lo | (hi << 16);
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
+    const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
+    constexpr int NMMA = NK * TM * TN;
+    constexpr int NSLOT = 1 + 2 * RA + 2 * RB;
+    constexpr int SPM = (NSLOT + (NMMA > 2 ? NMMA - 2 : 1) - 1) / (NMMA > 2 ? NMMA - 2 : 1);
+
+    if (nsteps > 0) {
+        load_step();
+        store_step(0);
+    }
+    __syncthreads();
+    for (int step = 0; step < nsteps; ++step) {
+        const int buf = step & 1;
+        const bool last = step == nsteps - 1;
+        const char *As = As0 + buf * BM * PITCHB, *Bs = Bs0 + buf * BN * PITCHB;
+        u32x4 fa[TM][NK], fb[TN][NK];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fa[i][t] = *reinterpret_cast<const u32x4 *>(As + a_frag + i * 32 * PITCHB + t * 32);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fb[jn][t] = *reinterpret_cast<const u32x4 *>(Bs + b_frag + jn * 32 * PITCHB + t * 32);
+        __builtin_amdgcn_sched_barrier(0);
+        if (!last) {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                     acc[i][jn], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NSLOT; ++q) {
+                    if (q == 0) slot_pos();
+                    else if (q - 1 < 2 * RA) slot_a(q - 1);
+                    else slot_b(q - 1 - 2 * RA);
+                }
+                if (m * SPM < NSLOT) __builtin_amdgcn_sched_barrier(0);
+            }
+            store_step(buf ^ 1);
+            __syncthreads();
+        } else {
+#pragma unroll
+            for (int m = 0; m < NMMA; ++m) {
+                const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+                acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                     __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                     acc[i][jn], 0, 0, 0);
+            }
+        }
+    }
+
+    float *out = p.part + (size_t)split * p.K * p.ncols;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.ncols + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Backward-filter with bf16 inputs for stride-1 layers whose output has the
+// input's extent (R - 1 = S - 1 = 2 * pad): every MFMA operand (8 consecutive
+// reduction positions of a row) is ONE 16-byte global load.
+//
+// Two packing passes lay the tensors out for that.  With row pitch Wq = W + pad,
+//   dyp[k][n][Jy]: dy(n, k, p, q) at j = p*Wq + q, zeros in the pad columns and in
+//                  the tail up to Jy (a multiple of 8); rows zero-filled up to a
+//                  whole number of 64-position steps;
+//   xp[c][n][Jx]:  x(n, c, h, w) at (h + pad)*Wq + (w + pad), zeros elsewhere.
+// The input element that dy position j meets under tap (r, s) then sits at
+// j + r*Wq + s of the same image: a column that would wrap lands in the pad
+// columns of the neighbouring row (one gap serves as right pad of a row and left
+// pad of the next), a row out of range in the zero rows above and below.  No
+// masks and no per-element addresses are left; positions where dy is zero cost
+// (Jy / (P*Q) - 1) extra matrix work, 9 % at 13x13.
+// The x loads are 2-byte aligned only (the tap shift is arbitrary).
+// Columns in (r, s, c) order, partials [split][K][R*S*C] as in wgrad_fast_kernel.
+// ---------------------------------------------------------------------------
+struct WgradLinArgs {
+    const unsigned short *dyp;
+    const unsigned short *xp;
+    float *part;
+    int K, C, ncols;
+    int S, Wq;
+    int N, G, Jx;             // G = Jy / 8 groups of 8 positions per image
+    int row_a_bytes;          // bytes per dyp row
+    int row_x_bytes;          // bytes per xp row (N * Jx * 2)
+    int steps, steps_per_split;
+    int mtiles, ntiles, nunits, units_per_xcd;
+    FastDiv div_c, div_s, div_g;
+};
+
+typedef u32x4 u32x4_align2 __attribute__((aligned(2)));
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const WgradLinArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int KJ = 64, NK = KJ / 16;
+    constexpr int PITCHB = KJ * 2 + 16;
+    constexpr int RA = BM / 32, RB = BN / 32;      // 16-byte vectors per thread and step
+    static_assert(WM * WN == 4, "four waves per work-group");
+
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    char *const As0 = reinterpret_cast<char *>(lds_fast);
+    char *const Bs0 = As0 + 2 * BM * PITCHB;
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.units_per_xcd + idx;
+    if (idx >= p.units_per_xcd || unit >= p.nunits) return;
+    const int ntile = p.mtiles * p.ntiles;
+    const int split = unit / ntile;
+    const int tile = unit - split * ntile;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int jg = tid & 7, r8 = tid >> 3;         // this thread's group of 8 positions in a step; its row inside 32
+
+    const int step_begin = split * p.steps_per_split;
+    const int nsteps = min(p.steps - step_begin, p.steps_per_split);
+
+    uint32_t abase[RA], bbase[RB];
+#pragma unroll
+    for (int i = 0; i < RA; ++i) abase[i] = (uint32_t)min(m0 + r8 + 32 * i, p.K - 1) * (uint32_t)p.row_a_bytes;
+#pragma unroll
+    for (int i = 0; i < RB; ++i) {
+        int col = n0 + r8 + 32 * i;
+        col = col < p.ncols ? col : 0;
+        const int rs = (int)fastdiv((uint32_t)col, p.div_c), c = col - rs * p.C;
+        const int r = (int)fastdiv((uint32_t)rs, p.div_s), sx = rs - r * p.S;
+        bbase[i] = (uint32_t)c * (uint32_t)p.row_x_bytes + 2u * (uint32_t)(r * p.Wq + sx);
+    }
+    // position of this thread's group: g = step*8 + jg = n*G + gg
+    int n, gg;
+    {
+        const int g = step_begin * 8 + jg;
+        n = (int)fastdiv((uint32_t)g, p.div_g);
+        gg = g - n * p.G;
+    }
+    uint32_t aoff = (uint32_t)(step_begin * 8 + jg) * 16u, boff = 0;
+    const char *ap = reinterpret_cast<const char *>(p.dyp), *xp = reinterpret_cast<const char *>(p.xp);
+
+    // register set t & 1 and LDS buffer t & 1 hold step t (two-set pipeline of colgemm_fast_kernel)
+    u32x4 areg[2][RA], breg[2][RB];
+    auto slot_pos = [&]() {
+        boff = 2u * (uint32_t)(min(n, p.N - 1) * p.Jx + gg * 8);
+        gg += 8;
+        const bool wrap = gg >= p.G;
+        gg -= wrap ? p.G : 0;
+        n += wrap ? 1 : 0;
+    };
+    auto slot_a = [&](int set, int i) {
+        areg[set][i] = *reinterpret_cast<const u32x4 *>(ap + (abase[i] + aoff));
+        if (i == RA - 1) aoff += 128u;
+    };
+    auto slot_b = [&](int set, int i) {
+        breg[set][i] = *reinterpret_cast<const u32x4_align2 *>(xp + (bbase[i] + boff));
+    };
+    auto load_step = [&](int set) {
+        slot_pos();
+#pragma unroll
+        for (int i = 0; i < RA; ++i) slot_a(set, i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) slot_b(set, i);
+    };
+    auto store_a = [&](int set, int i) {
+        *reinterpret_cast<u32x4 *>(As0 + set * BM * PITCHB + (r8 + i * 32) * PITCHB + jg * 16) = areg[set][i];
+    };
+    auto store_b = [&](int set, int i) {
+        *reinterpret_cast<u32x4 *>(Bs0 + set * BN * PITCHB + (r8 + i * 32) * PITCHB + jg * 16) = breg[set][i];
+    };
+    auto store_step = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < RA; ++i) store_a(set, i);
+#pragma unroll
+        for (int i = 0; i < RB; ++i) store_b(set, i);
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
+    const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
+    constexpr int NMMA = NK * TM * TN;
+    constexpr int NLOAD = 1 + RA + RB, NSTORE = RA + RB;
+    constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);
+
+    if (nsteps > 0) {
+        load_step(0);
+        store_step(0);
+        if (nsteps > 1) load_step(1);
+    }
+    __syncthreads();
+    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
+    auto do_step = [&](auto par_c, auto mode_c) {
+        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
+        const char *As = As0 + par * BM * PITCHB, *Bs = Bs0 + par * BN * PITCHB;
+        u32x4 fa[TM][NK], fb[TN][NK];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fa[i][t] = *reinterpret_cast<const u32x4 *>(As + a_frag + i * 32 * PITCHB + t * 32);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int t = 0; t < NK; ++t)
+                fb[jn][t] = *reinterpret_cast<const u32x4 *>(Bs + b_frag + jn * 32 * PITCHB + t * 32);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int m = 0; m < NMMA; ++m) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
+            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
+                                                                 __builtin_bit_cast(bf16x8, fb[jn][t]),
+                                                                 acc[i][jn], 0, 0, 0);
+            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
+                    if (q < NLOAD) {
+                        if (mode == 2) {
+                            if (q == 0) slot_pos();
+                            else if (q - 1 < RA) slot_a(par, q - 1);
+                            else slot_b(par, q - 1 - RA);
+                        }
+                    } else {
+                        const int w = q - NLOAD;
+                        if (w < RA) store_a(par ^ 1, w);
+                        else store_b(par ^ 1, w - RA);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (mode > 0) __syncthreads();
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    using M2 = std::integral_constant<int, 2>;
+    int step = 0;
+    for (; step + 3 < nsteps; step += 2) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, M2{});
+    }
+    const int rest = nsteps - step;
+    if (rest == 3) {
+        do_step(P0{}, M2{});
+        do_step(P1{}, P1{});
+        do_step(P0{}, P0{});
+    } else if (rest == 2) {
+        do_step(P0{}, P1{});
+        do_step(P1{}, P0{});
+    } else if (rest == 1) {
+        do_step(P0{}, P0{});
+    }
+
+    float *out = p.part + (size_t)split * p.K * p.ncols;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.ncols + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// dyp[k][e], e < row_elems: image n = e / Jy, j = e % Jy = p*Wq + q; dy(n, k, p, q) where p < P and q < Q, else 0
+__global__ void pack_dy_lin(const unsigned short *__restrict__ dy, unsigned short *__restrict__ dyp, int N, int K,
+                            int P, int Q, int Wq, int Jy, int row_elems, int64_t dy_bs, FastDiv div_row,
+                            FastDiv div_jy, FastDiv div_wq)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)K * row_elems) return;
+    const uint32_t k = fastdiv((uint32_t)i, div_row), e = (uint32_t)i - k * (uint32_t)row_elems;
+    const uint32_t n = fastdiv(e, div_jy), j = e - n * (uint32_t)Jy;
+    const uint32_t pp = fastdiv(j, div_wq), q = j - pp * (uint32_t)Wq;
+    unsigned short v = 0;
+    if (n < (uint32_t)N && pp < (uint32_t)P && q < (uint32_t)Q) v = dy[n * dy_bs + ((int64_t)k * P + pp) * Q + q];
+    dyp[i] = v;
+}
+
+// xp[c][n][e], e < Jx: padded row hh = e / Wq, column ww = e % Wq; x(n, c, hh - pad, ww - pad) where inside, else 0
+__global__ void pack_x_lin(const unsigned short *__restrict__ x, unsigned short *__restrict__ xp, int N, int C, int H,
+                           int W, int pad, int Wq, int Jx, int64_t x_bs, FastDiv div_jx, FastDiv div_wq)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)C * N * Jx) return;
+    const uint32_t cn = fastdiv((uint32_t)i, div_jx), e = (uint32_t)i - cn * (uint32_t)Jx;
+    const uint32_t c = cn / (uint32_t)N, n = cn - c * (uint32_t)N;
+    const uint32_t hh = fastdiv(e, div_wq), ww = e - hh * (uint32_t)Wq;
+    const int h = (int)hh - pad, w = (int)ww - pad;
+    unsigned short v = 0;
+    if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) v = x[n * x_bs + ((int64_t)c * H + h) * W + w];
+    xp[i] = v;
+}
+
+// dw[k][c][rs] = part[0][k][rs*C + c] + part[1][k][rs*C + c] + ...  (fixed order)
+// groups > 1: K filters per column; the partials of column g follow those of column g - 1, dw holds the columns'
+// filters one after the other
+__global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int RS,
+                             int nsplit, int groups)
+{
+    const int ncols = RS * C;
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= groups * K * ncols) return;
+    const int gcol = i / (K * ncols);
+    i -= gcol * (K * ncols);
+    part += (size_t)gcol * nsplit * K * ncols;
+    dw += (size_t)gcol * K * ncols;
+    const int k = i / ncols, col = i - k * ncols;
+    const int rs = col / C, c = col - rs * C;
+    float s = part[i];
+    for (int t = 1; t < nsplit; ++t) s += part[(size_t)t * K * ncols + i];
+    dw[((size_t)k * C + c) * RS + rs] = s;
+}
+
+// Sum of the split partials in a fixed order: 64 outputs per work-group; lane group g of four adds the
+// splits g, g + 4, g + 8, ... in ascending order, then the four sums are added in group order.
+__global__ __launch_bounds__(256) void reduce_partials(const float *__restrict__ part, float *__restrict__ dw,
+                                                        int count, int nsplit)
+{
+    __shared__ float sums[4][64];
+    const int o = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + o;
+    float s = 0.f;
+    if (i < count)
+        for (int k = g; k < nsplit; k += 4) s += part[(size_t)k * count + i];
+    sums[g][o] = s;
+    __syncthreads();
+    if (g == 0 && i < count) dw[i] = ((sums[0][o] + sums[1][o]) + sums[2][o]) + sums[3][o];
+}
