@@ -209,3 +209,42 @@ def test_bias_argument_checks(lib):
     assert lib.bias_bwd(PTR, PTR, 128, 96, 3025, 0, None, need, None) == b.ERR_WORKSPACE
     assert lib.bias_bwd(PTR, None, 128, 96, 3025, 0, PTR, need, None) == b.ERR_INVALID_ARG
     assert lib.bias_bwd(PTR, PTR, 128, 96, 3025, 0, PTR + 16, need, None) == b.ERR_MISALIGNED
+
+
+def test_fused_epilogue_argument_checks(lib):
+    from paper_1312_5853_amd import binding as b
+    dims = (2, 16, 8, 8, 16, 3, 3, 1, 1)
+    need = lib.conv_workspace_bytes(b.OP_FWD, *dims, 0)
+    assert lib.conv_fwd_bias_relu(PTR, PTR, None, None, *dims, 1, 0, PTR, need, None) == b.ERR_INVALID_ARG
+    assert lib.conv_fwd_bias_relu(PTR, PTR, None, PTR, *dims, 2, 0, PTR, need, None) == b.ERR_INVALID_ARG   # relu flag
+    assert lib.conv_fwd_bias_relu(PTR, PTR, PTR + 2, PTR, *dims, 1, 0, PTR, need, None) == b.ERR_MISALIGNED  # bias
+    assert lib.conv_fwd_bias_relu(PTR, PTR, None, PTR, *dims, 1, 9, PTR, need, None) == b.ERR_BAD_DTYPE
+    assert lib.conv_fwd_bias_relu(PTR, PTR, None, PTR, *dims, 1, 0, None, 0, None) == b.ERR_WORKSPACE
+    need = lib.conv_workspace_bytes(b.OP_BWD_DATA, *dims, 0)
+    assert lib.conv_bwd_data_relu(PTR, PTR, None, PTR, *dims, 0, PTR, need, None) == b.ERR_INVALID_ARG      # no mask
+    assert lib.conv_bwd_data_relu(PTR, PTR, PTR + 2, PTR, *dims, 0, PTR, need, None) == b.ERR_MISALIGNED
+    assert lib.conv_bwd_data_relu(PTR, PTR, PTR, PTR, *dims, 0, None, 0, None) == b.ERR_WORKSPACE
+
+
+def test_fc_and_sgd_argument_checks(lib):
+    from paper_1312_5853_amd import binding as b
+    # workspace: the partial sums of a split reduction, nothing when the reduction is not split
+    assert lib.fc_workspace_bytes(b.OP_FWD, 128, 9216, 4096, 0) == 16 * 128 * 4096 * 4
+    assert lib.fc_workspace_bytes(b.OP_BWD_FILTER, 128, 9216, 4096, 0) == 0
+    assert lib.fc_workspace_bytes(b.OP_FWD, 128, 9214, 4096, 0) == 0                 # invalid: I % 4
+    assert lib.fc_workspace_bytes(7, 128, 9216, 4096, 0) == 0
+    assert lib.fc_fwd(PTR, PTR, None, PTR, 4, 6, 8, 0, 0, None, 0, None) == b.ERR_INVALID_ARG
+    assert lib.fc_fwd(PTR, PTR, None, PTR, 4, 8, 6, 0, 0, None, 0, None) == b.ERR_INVALID_ARG
+    assert lib.fc_fwd(None, PTR, None, PTR, 4, 8, 8, 0, 0, None, 0, None) == b.ERR_INVALID_ARG
+    assert lib.fc_fwd(PTR, PTR, None, PTR, 4, 8, 8, 2, 0, None, 0, None) == b.ERR_INVALID_ARG
+    assert lib.fc_fwd(PTR, PTR, None, PTR, 4, 8, 8, 0, 1, None, 0, None) == b.ERR_BAD_DTYPE
+    assert lib.fc_fwd(PTR + 4, PTR, None, PTR, 4, 8, 8, 0, 0, None, 0, None) == b.ERR_MISALIGNED
+    assert lib.fc_fwd(PTR, PTR, None, PTR, 1 << 16, 1 << 15, 8, 0, 0, None, 0, None) == b.ERR_TOO_LARGE
+    assert lib.fc_fwd(PTR, PTR, None, PTR, 128, 9216, 4096, 0, 0, None, 0, None) == b.ERR_WORKSPACE
+    assert lib.fc_bwd_data(PTR, PTR, PTR, 0, 8, 8, 0, None, 0, None) == b.ERR_INVALID_ARG
+    assert lib.fc_bwd_filter(PTR, None, PTR, 4, 8, 8, 0, None, 0, None) == b.ERR_INVALID_ARG
+    f = ctypes.c_float
+    assert lib.sgd_update(None, PTR, PTR, 4, f(0.1), f(0), f(0), f(1), None) == b.ERR_INVALID_ARG
+    assert lib.sgd_update(PTR, PTR, PTR, -1, f(0.1), f(0), f(0), f(1), None) == b.ERR_INVALID_ARG
+    assert lib.sgd_update(PTR, PTR + 2, PTR, 4, f(0.1), f(0), f(0), f(1), None) == b.ERR_MISALIGNED
+    assert lib.sgd_update(None, None, None, 0, f(0.1), f(0), f(0), f(1), None) == b.OK
