@@ -903,3 +903,55 @@ def test_stack_step_full_batch_sampled():
         assert norm_err(got, oracle.conv_bwd_filter_at(inp, dy, 3, 3, 1, 1, idx)) <= tol
     idx, got = sample(st.dw["conv1"], 1500, 27)
     assert norm_err(got, oracle.conv_bwd_filter_at(c64(st.x0), dy1, 11, 11, 4, 2, idx)) <= tol
+
+
+# ------------------------------------------------------------ seeded random small shapes ---
+def _random_shapes(count, seed):
+    rng = np.random.Generator(np.random.Philox(seed))
+    shapes = []
+    while len(shapes) < count:
+        N = int(rng.integers(1, 5))
+        C = int(rng.choice([1, 2, 3, 5, 8, 16, 17, 32, 33, 48, 64]))
+        K = int(rng.choice([1, 3, 16, 31, 32, 33, 47, 48, 64, 96, 100, 129]))
+        H, W = int(rng.integers(1, 15)), int(rng.integers(1, 15))
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        st, pad = int(rng.integers(1, 4)), int(rng.integers(0, 4))
+        if H + 2 * pad < R or W + 2 * pad < S:
+            continue
+        shapes.append((N, C, H, W, K, R, S, st, pad))
+    return shapes
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_small_shapes_full_compare(dtype):
+    """Sixty seeded random layer shapes per element type (channel counts on and off the multiples of 16 that select
+    the kernels, strides 1-3, padding up to 3, planes down to 1x1): all three passes against the oracle."""
+    for i, shape in enumerate(_random_shapes(60, 4242 if dtype == "f32" else 4343)):
+        N, C, H, W, K, R, S, st, pad = shape
+        P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+        x = synth.gaussian((N, C, H, W), 7000 + i)
+        w = synth.gaussian((K, C, R, S), 8000 + i, 0.1)
+        dy = synth.gaussian((N, K, P, Q), 9000 + i)
+        try:
+            check_full(x, w, dy, st, pad, dtype)
+        except AssertionError as e:
+            raise AssertionError("shape %r: %s" % (shape, e))
+
+
+def test_random_fc_shapes_full_compare():
+    """Forty seeded random fully connected shapes (batch up to 300, widths up to 600 in multiples of 4: one to
+    five tiles each way, reductions of one to 38 steps with ragged ends and split ranges)."""
+    rng = np.random.Generator(np.random.Philox(5151))
+    for i in range(40):
+        N = int(rng.integers(1, 301))
+        I, O = 4 * int(rng.integers(1, 151)), 4 * int(rng.integers(1, 151))
+        x = synth.gaussian((N, I), 11000 + i)
+        w = synth.gaussian((O, I), 12000 + i, 0.1)
+        dy = synth.gaussian((N, O), 13000 + i)
+        b = synth.gaussian((O,), 14000 + i)
+        xd, wd, dyd, bd = dev(x), dev(w), dev(dy), dev(b)
+        tag = "N=%d I=%d O=%d" % (N, I, O)
+        assert norm_err(hp.fc_fwd(xd, wd, bias=bd, relu=bool(i & 1)).cpu().numpy(),
+                        oracle.fc_fwd(x, w, b, relu=bool(i & 1))) <= TOL["f32"], tag
+        assert norm_err(hp.fc_bwd_data(dyd, wd).cpu().numpy(), oracle.fc_bwd_data(dy, w)) <= TOL["f32"], tag
+        assert norm_err(hp.fc_bwd_filter(xd, dyd).cpu().numpy(), oracle.fc_bwd_filter(x, dy)) <= TOL["f32"], tag
