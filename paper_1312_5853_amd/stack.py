@@ -140,6 +140,18 @@ class ConvStack:
         self.forward()
         return self.backward()
 
+    def capture(self):
+        """One step recorded into a HIP graph (torch's capture of the stream the binding launches on).  A step is
+        run first so that the workspace has its final size: nothing allocates while the graph is recorded, and the
+        library itself issues only kernel launches (no memsets, copies or synchronisation).  Replaying the graph
+        runs the step on the buffers this object owns."""
+        self.step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            self.step()
+        return graph
+
 
 FC_LAYERS = (("fc6", 256 * 6 * 6, 4096), ("fc7", 4096, 4096), ("fc8", 4096, 1000))
 

@@ -955,3 +955,31 @@ def test_random_fc_shapes_full_compare():
                         oracle.fc_fwd(x, w, b, relu=bool(i & 1))) <= TOL["f32"], tag
         assert norm_err(hp.fc_bwd_data(dyd, wd).cpu().numpy(), oracle.fc_bwd_data(dy, w)) <= TOL["f32"], tag
         assert norm_err(hp.fc_bwd_filter(xd, dyd).cpu().numpy(), oracle.fc_bwd_filter(x, dy)) <= TOL["f32"], tag
+
+
+def test_step_replayed_from_a_hip_graph_equals_the_eager_step():
+    """The stack step captured into a HIP graph: several replays, with eager steps and synchronisations between
+    them, each leave exactly the tensors the eager step leaves (the step is deterministic)."""
+    from paper_1312_5853_amd.stack import ConvStack
+    st = ConvStack(4)
+    st.step()
+    torch.cuda.synchronize()
+    names = ("y1", "a1", "y2", "a2", "y3", "y4", "y5", "a5", "dy5", "dy4", "dy3", "da2", "dy2", "da1", "dy1")
+    want = {n: getattr(st, n).clone() for n in names}
+    want_dw = {k: v.clone() for k, v in st.dw.items()}
+    graph = st.capture()
+    for rep in range(3):
+        for n in names:
+            getattr(st, n).fill_(float("nan"))
+        for v in st.dw.values():
+            v.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in names:
+            assert torch.equal(getattr(st, n), want[n]), (rep, n)
+        for k in want_dw:
+            assert torch.equal(st.dw[k], want_dw[k]), (rep, k)
+        st.step()                                  # eager work between the replays
+        torch.cuda.synchronize()
+        hp.relu_fwd(st.y3, st.y3)
+        torch.cuda.synchronize()
