@@ -864,34 +864,53 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const Wgrad
     }
 }
 
-// dyp[k][e], e < row_elems: image n = e / Jy, j = e % Jy = p*Wq + q; dy(n, k, p, q) where p < P and q < Q, else 0
+// dyp[k][e], e < row_elems: image n = e / Jy, j = e % Jy = p*Wq + q; dy(n, k, p, q) where p < P and q < Q, else 0.
+// One thread per 8 consecutive elements (Jy and row_elems are multiples of 8, so they share k and n): eight
+// 2-byte loads along a row of dy, one 16-byte store.
 __global__ void pack_dy_lin(const unsigned short *__restrict__ dy, unsigned short *__restrict__ dyp, int N, int K,
                             int P, int Q, int Wq, int Jy, int row_elems, int64_t dy_bs, FastDiv div_row,
                             FastDiv div_jy, FastDiv div_wq)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i8 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = i8 * 8;
     if (i >= (int64_t)K * row_elems) return;
     const uint32_t k = fastdiv((uint32_t)i, div_row), e = (uint32_t)i - k * (uint32_t)row_elems;
     const uint32_t n = fastdiv(e, div_jy), j = e - n * (uint32_t)Jy;
-    const uint32_t pp = fastdiv(j, div_wq), q = j - pp * (uint32_t)Wq;
-    unsigned short v = 0;
-    if (n < (uint32_t)N && pp < (uint32_t)P && q < (uint32_t)Q) v = dy[n * dy_bs + ((int64_t)k * P + pp) * Q + q];
-    dyp[i] = v;
+    uint32_t pp = fastdiv(j, div_wq), q = j - pp * (uint32_t)Wq;
+    const unsigned short *src = dy + n * dy_bs + (int64_t)k * P * Q;
+    unsigned short v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        v[t] = (n < (uint32_t)N && pp < (uint32_t)P && q < (uint32_t)Q) ? src[pp * Q + q] : (unsigned short)0;
+        if (++q == (uint32_t)Wq) { q = 0; ++pp; }
+    }
+    u32x4 o = {(uint32_t)v[0] | (uint32_t)v[1] << 16, (uint32_t)v[2] | (uint32_t)v[3] << 16,
+               (uint32_t)v[4] | (uint32_t)v[5] << 16, (uint32_t)v[6] | (uint32_t)v[7] << 16};
+    reinterpret_cast<u32x4 *>(dyp)[i8] = o;
 }
 
-// xp[c][n][e], e < Jx: padded row hh = e / Wq, column ww = e % Wq; x(n, c, hh - pad, ww - pad) where inside, else 0
+// xp[c][n][e], e < Jx: padded row hh = e / Wq, column ww = e % Wq; x(n, c, hh - pad, ww - pad) where inside, else 0.
+// One thread per 8 consecutive elements (Jx is a multiple of 8).
 __global__ void pack_x_lin(const unsigned short *__restrict__ x, unsigned short *__restrict__ xp, int N, int C, int H,
                            int W, int pad, int Wq, int Jx, int64_t x_bs, FastDiv div_jx, FastDiv div_wq)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i8 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t i = i8 * 8;
     if (i >= (int64_t)C * N * Jx) return;
     const uint32_t cn = fastdiv((uint32_t)i, div_jx), e = (uint32_t)i - cn * (uint32_t)Jx;
     const uint32_t c = cn / (uint32_t)N, n = cn - c * (uint32_t)N;
-    const uint32_t hh = fastdiv(e, div_wq), ww = e - hh * (uint32_t)Wq;
-    const int h = (int)hh - pad, w = (int)ww - pad;
-    unsigned short v = 0;
-    if ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) v = x[n * x_bs + ((int64_t)c * H + h) * W + w];
-    xp[i] = v;
+    uint32_t hh = fastdiv(e, div_wq), ww = e - hh * (uint32_t)Wq;
+    const unsigned short *src = x + n * x_bs + (int64_t)c * H * W;
+    unsigned short v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        const int h = (int)hh - pad, w = (int)ww - pad;
+        v[t] = ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) ? src[h * W + w] : (unsigned short)0;
+        if (++ww == (uint32_t)Wq) { ww = 0; ++hh; }
+    }
+    u32x4 o = {(uint32_t)v[0] | (uint32_t)v[1] << 16, (uint32_t)v[2] | (uint32_t)v[3] << 16,
+               (uint32_t)v[4] | (uint32_t)v[5] << 16, (uint32_t)v[6] | (uint32_t)v[7] << 16};
+    reinterpret_cast<u32x4 *>(xp)[i8] = o;
 }
 
 // dw[k][c][rs] = part[0][k][rs*C + c] + part[1][k][rs*C + c] + ...  (fixed order)

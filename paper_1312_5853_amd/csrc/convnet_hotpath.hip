@@ -459,11 +459,11 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         unsigned short *dyp = reinterpret_cast<unsigned short *>(wsb + pl.lin_dy_off);
         unsigned short *xp = reinterpret_cast<unsigned short *>(wsb + pl.lin_x_off);
         const int row_elems = pl.lin_steps * 64;
-        hipLaunchKernelGGL(pack_dy_lin, dim3(grid1d((int64_t)pb.K * row_elems, 256)), dim3(256), 0, st,
+        hipLaunchKernelGGL(pack_dy_lin, dim3(grid1d((int64_t)pb.K * row_elems / 8, 256)), dim3(256), 0, st,
                            static_cast<const unsigned short *>(dy), dyp, pb.N, pb.K, pb.P, pb.Q, pl.lin_wq, pl.lin_jy,
                            row_elems, pb.y_bs, make_fastdiv((uint32_t)row_elems), make_fastdiv((uint32_t)pl.lin_jy),
                            make_fastdiv((uint32_t)pl.lin_wq));
-        hipLaunchKernelGGL(pack_x_lin, dim3(grid1d((int64_t)pb.C * pb.N * pl.lin_jx, 256)), dim3(256), 0, st,
+        hipLaunchKernelGGL(pack_x_lin, dim3(grid1d((int64_t)pb.C * pb.N * pl.lin_jx / 8, 256)), dim3(256), 0, st,
                            static_cast<const unsigned short *>(x), xp, pb.N, pb.C, pb.H, pb.W, pb.pad, pl.lin_wq,
                            pl.lin_jx, pb.x_bs, make_fastdiv((uint32_t)pl.lin_jx), make_fastdiv((uint32_t)pl.lin_wq));
         WgradLinArgs a;
