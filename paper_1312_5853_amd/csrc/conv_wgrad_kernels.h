@@ -917,17 +917,17 @@ __global__ void pack_x_lin(const unsigned short *__restrict__ x, unsigned short 
 // groups > 1: K filters per column; the partials of column g follow those of column g - 1, dw holds the columns'
 // filters one after the other
 __global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int RS,
-                             int nsplit, int groups)
+                             int nsplit, int groups, FastDiv div_kcols, FastDiv div_cols, FastDiv div_c)
 {
     const int ncols = RS * C;
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= groups * K * ncols) return;
-    const int gcol = i / (K * ncols);
+    const int gcol = (int)fastdiv((uint32_t)i, div_kcols);
     i -= gcol * (K * ncols);
     part += (size_t)gcol * nsplit * K * ncols;
     dw += (size_t)gcol * K * ncols;
-    const int k = i / ncols, col = i - k * ncols;
-    const int rs = col / C, c = col - rs * C;
+    const int k = (int)fastdiv((uint32_t)i, div_cols), col = i - k * ncols;
+    const int rs = (int)fastdiv((uint32_t)col, div_c), c = col - rs * C;
     float s = part[i];
     for (int t = 1; t < nsplit; ++t) s += part[(size_t)t * K * ncols + i];
     dw[((size_t)k * C + c) * RS + rs] = s;

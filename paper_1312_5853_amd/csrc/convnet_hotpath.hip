@@ -486,7 +486,8 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         if (rc != kStatusOk) return rc;
         const int count = pb.K * pl.Kg;
         hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
-                           pb.K, pb.C, RS, pl.nsplit, 1);
+                           pb.K, pb.C, RS, pl.nsplit, 1, make_fastdiv((uint32_t)(pb.K * pl.Kg)),
+                           make_fastdiv((uint32_t)pl.Kg), make_fastdiv((uint32_t)pb.C));
         return check_launch();
     }
     const float *xf = as_f32(pl.widen, x, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st);
@@ -519,7 +520,8 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         if (rc != kStatusOk) return rc;
         const int count = pb.K * pl.Kg * GF;
         hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
-                           pb.K, pb.C, RS, pl.nsplit, GF);
+                           pb.K, pb.C, RS, pl.nsplit, GF, make_fastdiv((uint32_t)(pb.K * pl.Kg)),
+                           make_fastdiv((uint32_t)pl.Kg), make_fastdiv((uint32_t)pb.C));
         return check_launch();
     }
     hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len, pl.Kg, RS,
