@@ -983,3 +983,39 @@ def test_step_replayed_from_a_hip_graph_equals_the_eager_step():
         torch.cuda.synchronize()
         hp.relu_fwd(st.y3, st.y3)
         torch.cuda.synchronize()
+
+
+def test_largest_tensors_the_boundary_accepts():
+    """Tensors of 2047 x 64 x 64 x 64 fp32 elements: 1 MiB short of the 2^31-byte span the boundary allows, so byte
+    offsets inside the kernels run up to the top of their 32-bit range.  Inputs are drawn on the device (seeded);
+    sampled outputs, the last elements of every tensor among them, are checked against the oracle."""
+    N, C, H, W, K, R, S, st, pad = 2047, 64, 64, 64, 64, 3, 3, 1, 1
+    assert N * C * H * W * 4 < 2 ** 31 <= (N + 1) * C * H * W * 4
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.SEED_BASE + 4001)
+    xd = torch.randn((N, C, H, W), device="cuda", generator=gen)
+    dyd = torch.randn((N, K, H, W), device="cuda", generator=gen)
+    wd = torch.randn((K, C, R, S), device="cuda", generator=gen) * 0.05
+    x64, dy64, w64 = (t.cpu().numpy().astype(np.float64) for t in (xd, dyd, wd))
+
+    def sample(t, count, seed):
+        tail = np.arange(t.numel() - 64, t.numel(), dtype=np.int64)          # the highest addresses
+        idx = np.unique(np.concatenate([synth.sample_indices(t.numel(), count, seed), edge_indices(t.shape), tail]))
+        return idx, t.view(-1)[torch.from_numpy(idx).cuda()].cpu().numpy()
+
+    y = hp.conv_fwd(xd, wd, st, pad)
+    idx, got = sample(y, 4000, 31)
+    assert norm_err(got, oracle.conv_fwd_at(x64, w64, st, pad, idx)) <= TOL["f32"]
+    del y
+    dx = hp.conv_bwd_data(dyd, wd, H, W, st, pad)
+    idx, got = sample(dx, 2000, 32)
+    assert norm_err(got, oracle.conv_bwd_data_at(dy64, w64, H, W, st, pad, idx)) <= TOL["f32"]
+    del dx
+    dw = hp.conv_bwd_filter(xd, dyd, R, S, st, pad)
+    idx, got = sample(dw, 300, 33)
+    assert norm_err(got, oracle.conv_bwd_filter_at(x64, dy64, R, S, st, pad, idx)) <= TOL["f32"]
+    # one sample more is refused before anything is launched
+    big = torch.empty(((N + 1) * C * H * W,), device="cuda")
+    with pytest.raises(hp.ConvError) as e:
+        hp.conv_fwd(big.view(N + 1, C, H, W), wd, st, pad, y=big.view(N + 1, K, H, W))
+    assert e.value.status == hp.ERR_TOO_LARGE
