@@ -624,6 +624,7 @@ def test_bias_forward_and_gradient(dtype):
 # --------------------------------------------- convolution with its bias / ReLU applied at the store ---
 EPILOGUE_SHAPES = [
     (128, 64, 13, 13, 256, 3, 3, 1, 1),    # 32 x 32 tile kernels, enough tiles for a whole-reduction launch
+    (200, 64, 13, 13, 256, 3, 3, 1, 1),    # 530 tiles of 128 x 128: more than one round of work-groups, ragged end
     (4, 64, 13, 13, 96, 3, 3, 1, 1),       # few tiles: reduction split, epilogue in the split-sum kernel
     (7, 48, 14, 14, 64, 5, 5, 1, 2),       # backward-data in the 48-row kernel: epilogue as a pass of its own
     (3, 3, 23, 25, 48, 11, 11, 4, 2),      # few-channel forward (patch kernel), strided backward-data (tap table)
