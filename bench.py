@@ -215,16 +215,21 @@ def main():
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
     # the same step replayed from a HIP graph (no per-call host work): K replays
-    graph = stack.capture()
-    for _ in range(2):
-        graph.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        graph.replay()
-    torch.cuda.synchronize()
-    graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    del graph
+    graph_ms = None
+    try:
+        graph = stack.capture()
+        for _ in range(2):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        del graph
+    except RuntimeError as e:           # an extra figure only: the headline numbers do not depend on it
+        sys.stderr.write("bench.py: HIP graph replay skipped (%s)\n" % e)
+        torch.cuda.synchronize()
 
     # second timed region: HIP events (on the launch stream) around every conv call
     stack.timers = {}
@@ -295,7 +300,7 @@ def main():
         "config": {"workload": "5-conv AlexNet stack fwd+bwd, N=%d, fp32 (conv2 as two model-parallel columns)" % N,
                    "batch": N, "conv_gflop_per_step": round(flops / 1e9, 2)},
         "frac_fp32_mfma_peak": round(value / PEAK_FP32_MFMA_TFLOPS, 4),
-        "hip_graph_ms_per_step": round(graph_ms, 4),
+        "hip_graph_ms_per_step": None if graph_ms is None else round(graph_ms, 4),
         "conv_only_ms": round(conv_ms, 4),
         "conv_only_frac_peak": round(flops / conv_ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
         "per_pass": per_pass,
