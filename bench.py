@@ -272,12 +272,8 @@ def main():
         "flops_per_launch": dom_flops / len(dom_keys),
     }
 
-    columns, bf16, network = None, None, None
-    if not args.stack_only:
-        del stack
-        network = whole_network(N, hp, torch, args.steps)
-        columns = two_column_layers(N, hp, synth, conv_flops, torch)
-        bf16 = bf16_layers(N, hp, synth, conv_flops, torch)
+    def bf16_block():
+        out = bf16_layers(N, hp, synth, conv_flops, torch)
         # the same step with bf16 tensors end to end (fp32 accumulation, fp32 filter gradients)
         bstack = ConvStack(N, dtype="bf16")
         for _ in range(3):
@@ -288,8 +284,24 @@ def main():
             bstack.step()
         torch.cuda.synchronize()
         bf16_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        bf16["stack_ms_per_step"] = round(bf16_ms, 4)
-        bf16["stack_tflops"] = round(flops / bf16_ms / 1e9, 2)
+        out["stack_ms_per_step"] = round(bf16_ms, 4)
+        out["stack_tflops"] = round(flops / bf16_ms / 1e9, 2)
+        return out
+
+    def extra(fn):
+        """The blocks beside the headline step: a failure in one of them is reported in its place."""
+        try:
+            return fn()
+        except Exception as e:          # noqa: BLE001 - the headline figures above stand on their own
+            torch.cuda.synchronize()
+            return {"error": "%s: %s" % (type(e).__name__, e)}
+
+    columns, bf16, network = None, None, None
+    if not args.stack_only:
+        del stack
+        network = extra(lambda: whole_network(N, hp, torch, args.steps))
+        columns = extra(lambda: two_column_layers(N, hp, synth, conv_flops, torch))
+        bf16 = extra(bf16_block)
 
     value = flops / ms_per_step / 1e9
     out = {
@@ -312,7 +324,7 @@ def main():
                    "loading: about 141 images/s; context for whole_network_fp32.step, not for value)",
     }
     if not args.no_cpu_baseline and not args.stack_only:
-        out["cpu_baseline"] = cpu_baseline()
+        out["cpu_baseline"] = extra(cpu_baseline)
     print(json.dumps(out))
 
 
