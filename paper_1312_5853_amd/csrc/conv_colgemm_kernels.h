@@ -246,7 +246,7 @@ struct ColGemmFastArgs {
 // KC = reduction depth of one step (16 or 32 channels of one tap).  LDS is
 // dynamic: 2 * (BM + BN) * (KC + 4) floats.
 template <int TM, int TN, int WM, int WN, int KC>
-__global__ __launch_bounds__(kThreads, 2) void colgemm_fast_kernel(const ColGemmFastArgs p)
+__global__ __launch_bounds__(kThreads, (TM == 3 && TN == 1) ? 3 : 2) void colgemm_fast_kernel(const ColGemmFastArgs p)
 {
     constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
     constexpr int PITCH = KC + 4;            // 16 lanes x b128 still cover all banks once (20 and 36 both do)
