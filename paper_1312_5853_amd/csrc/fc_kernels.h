@@ -217,7 +217,11 @@ __global__ __launch_bounds__(kThreads, 2) void fc_gemm_kernel(const FcArgs p)
     for (int jn = 0; jn < TN; ++jn) {
         const int col = n0 + (wn * TN + jn) * 32 + l32;
         if (col >= p.Nc) continue;
-        const float bv = final_sums && p.bias ? p.bias[col] : 0.f;
+        // The wait for the bias load must sit here, once: left to the compiler it lands in front of every
+        // conditional store below, as a wait for ALL outstanding memory operations, the stores before it included,
+        // so that the 64 stores of a tile went out one round trip at a time.
+        float bv = final_sums && p.bias ? p.bias[col] : 0.f;
+        asm volatile("" : "+v"(bv));          // the loaded value is complete from here on
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
