@@ -34,6 +34,8 @@ from .oracle import (  # noqa: F401
     fc_bwd_data,
     fc_bwd_filter,
     sgd_update,
+    bf16_bits,
+    bf16_round,
     num_threads,
     set_num_threads,
 )

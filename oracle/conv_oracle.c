@@ -10,12 +10,13 @@
  * the benchmark's cpu_baseline leg may call it.
  *
  * The paper itself prints no formula: it speaks of a convolutional layer
- * whose filters "convolve the input" (model-parallelism paragraph, where a
- * layer with N filters is split into two halves) and of "standard supervised
- * back-propagation" with gradients "with respect to all model parameters"
- * (data-parallelism paragraph).  The definitions below are the standard ones
- * those words denote, in the NCHW / KCRS layout with one stride and one
- * symmetric zero padding for both axes:
+ * whose filters are applied to the layer input by convolution
+ * (model-parallelism paragraph, where a layer's filters are split into two
+ * halves) and of training by ordinary supervised back-propagation, each GPU
+ * computing the gradients of every model parameter on its samples
+ * (optimisation and data-parallelism paragraphs).  The definitions below are
+ * the standard ones those statements denote, in the NCHW / KCRS layout with
+ * one stride and one symmetric zero padding for both axes:
  *
  *   P = floor((H + 2*pad - R) / stride) + 1,   Q likewise from W and S
  *
@@ -37,6 +38,12 @@
  * hand-worked fixture.  The paper prints no worked numeric example, so
  * paper-value parity is unpinned; every function here is pinned by the
  * mathematics above.
+ *
+ * bfloat16 storage (the reduced-precision variant keeps tensors as the upper
+ * 16 bits of an IEEE binary32 value): oracle_round_bf16 rounds binary32 to the
+ * nearest such value, ties to the even 16-bit pattern.  Pinned by hand-written
+ * bit patterns (exact values, both tie directions, carry into the exponent,
+ * overflow to infinity, signed zeros, NaN) and against torch's CPU conversion.
  *
  * Glue layers of the five-layer stack (not in the paper's text; they come
  * with the Krizhevsky architecture it trains): ReLU and 3x3 stride-2 max
@@ -319,5 +326,35 @@ void oracle_maxpool3x3s2_bwd(const double *x, const double *dy, double *dx,
                     }
                 dxp[best] += dy[((size_t)pl * PH + i) * PW + j];
             }
+    }
+}
+
+/* ---- bfloat16 storage ------------------------------------------------------ */
+
+/*
+ * Round IEEE binary32 bit patterns to bfloat16 (sign, 8 exponent bits, 7
+ * fraction bits = the upper half of the binary32 pattern), nearest value, ties
+ * to the pattern whose last kept bit is 0.  For finite values the binary32
+ * patterns of one sign are ordered like the magnitudes they encode, so the two
+ * bfloat16 neighbours of a value are its upper half `keep` and `keep + 1`; the
+ * dropped half `rest` says which is nearer (0x8000 = exactly half way).  A
+ * carry out of the fraction moves into the exponent, and past the largest
+ * finite value into the pattern of infinity, as rounding to nearest requires.
+ * NaN stays NaN (quiet bit set so that a payload in the dropped half cannot
+ * turn it into infinity); infinities and zeros have rest == 0 and pass.
+ */
+void oracle_round_bf16(const uint32_t *bits, uint16_t *out, int64_t n)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        const uint32_t b = bits[i];
+        const uint32_t magnitude = b & 0x7FFFFFFFu;
+        uint32_t keep = b >> 16;
+        const uint32_t rest = b & 0xFFFFu;
+        if (magnitude > 0x7F800000u) {          /* NaN */
+            out[i] = (uint16_t)(keep | 0x0040u);
+            continue;
+        }
+        if (rest > 0x8000u || (rest == 0x8000u && (keep & 1u))) keep += 1;
+        out[i] = (uint16_t)keep;
     }
 }

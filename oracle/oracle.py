@@ -59,6 +59,9 @@ def _load():
         _lib.oracle_pool_extent.argtypes = [ctypes.c_int]
         _lib.oracle_pool_extent.restype = ctypes.c_int
         _lib.oracle_num_threads.restype = ctypes.c_int
+        _lib.oracle_round_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint16),
+                                           ctypes.c_int64]
+        _lib.oracle_round_bf16.restype = None
         _lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
     return _lib
 
@@ -296,3 +299,23 @@ def sgd_update(w, dw, v, lr, momentum=0.0, weight_decay=0.0, grad_scale=1.0):
     w, dw, v = _f64(w), _f64(dw), _f64(v)
     v2 = momentum * v - lr * (weight_decay * w + grad_scale * dw)
     return w + v2, v2
+
+
+# ---------------------------------------------------------------------------
+# bfloat16 storage of the reduced-precision variant: a value is kept as the
+# upper 16 bits of its IEEE binary32 pattern, rounded to nearest, ties to even.
+# ---------------------------------------------------------------------------
+def bf16_bits(a):
+    """uint16 bfloat16 patterns of a float32 array, round to nearest even (NaN stays NaN)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    bits = a.view(np.uint32).ravel()
+    out = np.empty(bits.shape, dtype=np.uint16)
+    _load().oracle_round_bf16(bits.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
+                              out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint16)), bits.size)
+    return out.reshape(a.shape)
+
+
+def bf16_round(a):
+    """The float32 array rounded onto the bfloat16 grid, returned as float32 (exactly representable)."""
+    b = bf16_bits(a)
+    return (b.astype(np.uint32) << 16).view(np.float32).reshape(b.shape)

@@ -585,3 +585,96 @@ def test_sgd_update_closed_forms():
     # gradient descent on L = |w|^2 / 2 (dw = w) with lr = 1 lands on the minimum in one step
     w1, _ = oracle.sgd_update(w0, w0, z, lr=1.0)
     assert np.array_equal(w1, z)
+
+
+# ----------------------------------------------------------- bfloat16 rounding ---
+# Hand-written (binary32 pattern -> bfloat16 pattern) pairs, worked from the format: 1 sign, 8 exponent and 7
+# fraction bits are kept; the dropped 16 bits decide, 0x8000 being exactly half way (then the even pattern wins).
+BF16_BIT_PINS = [
+    (0x3F800000, 0x3F80),        # 1.0, exact
+    (0x40490FDB, 0x4049),        # pi -> 3.140625 (dropped part 0x0FDB is below half)
+    (0x3F808000, 0x3F80),        # 1 + 2^-8: tie, kept pattern even -> down
+    (0x3F818000, 0x3F82),        # 1 + 3*2^-8: tie, kept pattern odd -> up
+    (0xBF818000, 0xBF82),        # the same tie, negative
+    (0x3F808001, 0x3F81),        # just above the tie -> up
+    (0x3F807FFF, 0x3F80),        # just below the tie -> down
+    (0x3FFFFFFF, 0x4000),        # 1.9999999: the carry runs through the fraction into the exponent -> 2.0
+    (0x7F7FFFFF, 0x7F80),        # largest finite binary32 -> +infinity
+    (0xFF7FFFFF, 0xFF80),        # ... and -infinity
+    (0x7F7F7FFF, 0x7F7F),        # largest value that still rounds to the largest finite bfloat16
+    (0x7F7F8000, 0x7F80),        # tie at the top, kept pattern odd -> infinity
+    (0x00000000, 0x0000),        # +0
+    (0x80000000, 0x8000),        # -0 keeps its sign
+    (0x7F800000, 0x7F80),        # infinity stays
+    (0x00000001, 0x0000),        # smallest subnormal -> 0
+    (0x00008000, 0x0000),        # subnormal tie, even -> 0
+    (0x00008001, 0x0001),        # just above -> smallest bfloat16 subnormal
+    (0x00018000, 0x0002),        # subnormal tie, odd -> up
+    (0x007FFFFF, 0x0080),        # largest subnormal -> smallest normal
+]
+
+
+def test_bf16_rounding_hand_written_bit_patterns():
+    bits = np.array([b for b, _ in BF16_BIT_PINS], dtype=np.uint32)
+    want = np.array([w for _, w in BF16_BIT_PINS], dtype=np.uint16)
+    got = oracle.bf16_bits(bits.view(np.float32))
+    assert np.array_equal(got, want), [(hex(b), hex(g), hex(w)) for b, g, w in zip(bits, got, want) if g != w]
+    # values, not only patterns
+    r = oracle.bf16_round(np.array([1.00390625, 1.01171875, 3.14159265, -0.0], dtype=np.float32))
+    assert np.array_equal(r[:3], np.array([1.0, 1.015625, 3.140625], dtype=np.float32))
+    assert np.signbit(r[3]) and r[3] == 0.0
+    # NaN stays NaN, also when its payload lies wholly in the dropped half (it must not turn into infinity)
+    nans = np.array([0x7FC00000, 0x7F800001, 0xFFC00001, 0x7FFFFFFF], dtype=np.uint32)
+    out = oracle.bf16_bits(nans.view(np.float32))
+    assert np.all((out & 0x7F80) == 0x7F80) and np.all((out & 0x007F) != 0)
+    assert np.array_equal(out >> 15, nans >> 31)
+
+
+def test_bf16_rounding_is_the_nearest_value_with_even_ties():
+    """Defining property, checked in exact arithmetic (float64 holds binary32 and bfloat16 values exactly): the
+    result is a bfloat16 value at least as close as both of its bfloat16 neighbours, and an exact tie goes to the
+    pattern with last bit 0."""
+    rng = np.random.default_rng(41)
+    bits = rng.integers(0, 1 << 32, size=200000, dtype=np.uint64).astype(np.uint32)
+    bits = bits[(bits & 0x7F800000) != 0x7F800000]                        # finite
+    bits = bits[(bits & 0x7FFFFFFF) < 0x7F7F0000]                         # neighbours stay finite
+    x = bits.view(np.float32)
+    out = oracle.bf16_bits(x)
+    val = lambda p: (p.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    r = val(out)
+    mag = out & 0x7FFF
+    # magnitudes one pattern up / down; stepping down from a zero crosses to the other sign's smallest value
+    up = val((out & 0x8000) | (mag + 1))
+    down_mag = np.where(mag > 0, mag - 1, 1)
+    down_sign = np.where(mag > 0, out & 0x8000, (out & 0x8000) ^ 0x8000)
+    down = val((down_sign | down_mag).astype(np.uint16))
+    x64 = x.astype(np.float64)
+    d = np.abs(x64 - r)
+    assert np.all(d <= np.abs(x64 - up)) and np.all(d <= np.abs(x64 - down))
+    tie = (d == np.abs(x64 - up)) | (d == np.abs(x64 - down))
+    assert np.all((out[tie] & 1) == 0)
+    # values already on the grid pass unchanged
+    assert np.array_equal(oracle.bf16_bits(oracle.bf16_round(x)), out)
+
+
+def test_bf16_rounding_matches_torch_cpu_conversion():
+    import torch
+    rng = np.random.default_rng(42)
+    bits = rng.integers(0, 1 << 32, size=1 << 20, dtype=np.uint64).astype(np.uint32)
+    bits = np.concatenate([bits, np.array([b for b, _ in BF16_BIT_PINS], dtype=np.uint32)])
+    notnan = (bits & 0x7FFFFFFF) <= 0x7F800000
+    x = bits[notnan].view(np.float32)
+    want = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(oracle.bf16_bits(x), want)
+    g = (rng.standard_normal(1 << 18) * 0.01).astype(np.float32)        # the filters' value range
+    want = torch.from_numpy(g).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(oracle.bf16_round(g), want)
+
+
+def test_seeded_bf16_inputs_lie_on_the_grid_the_oracle_defines():
+    """The input generator's own rounding (used to prepare tensors both sides read) agrees with the oracle's."""
+    from paper_1312_5853_amd import synth
+    for seed, std in ((1, 1.0), (2, 0.01), (3, 300.0)):
+        a = synth.gaussian((50000,), seed, std)
+        assert np.array_equal(synth.to_bf16_grid(a), oracle.bf16_round(a))
+        assert np.array_equal(synth.bf16_bits(synth.to_bf16_grid(a)), oracle.bf16_bits(a))
