@@ -188,6 +188,13 @@ int conv_bwd_data_relu(const void *dy, const void *w, const void *act, void *dx,
 size_t conv_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, int S,
                             int stride, int pad, int dtype);
 
+/*
+ * Output extent of one axis, floor((in + 2*pad - filt) / stride) + 1: the P (from H, R) and Q (from W, S) every
+ * entry point derives, for callers that size y / dy.  0 when no window fits or an argument is not positive
+ * (pad may be 0).
+ */
+int conv_output_extent(int in, int filt, int stride, int pad);
+
 /* Static, NUL-terminated description of a conv_status value. */
 const char *conv_status_string(int status);
 

@@ -23,7 +23,7 @@ EXPORTS = (
     "conv_fwd", "conv_bwd_data", "conv_bwd_filter",
     "conv_fwd_ex", "conv_bwd_data_ex", "conv_bwd_filter_ex", "conv_fwd_bias_relu", "conv_bwd_data_relu",
     "conv_fwd_grouped", "conv_bwd_data_grouped", "conv_bwd_filter_grouped", "conv_workspace_bytes_grouped",
-    "conv_workspace_bytes", "conv_status_string", "conv_last_hip_error",
+    "conv_workspace_bytes", "conv_output_extent", "conv_status_string", "conv_last_hip_error",
     "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
     "relu_maxpool3x3s2_fwd", "relu_maxpool3x3s2_bwd", "convert_f32_to_bf16",
     "bias_fwd", "bias_bwd", "bias_bwd_workspace_bytes",
@@ -87,6 +87,8 @@ def lib():
     L.bias_bwd.restype = i
     L.bias_bwd_workspace_bytes.argtypes = [i, i]
     L.bias_bwd_workspace_bytes.restype = sz
+    L.conv_output_extent.argtypes = [i, i, i, i]
+    L.conv_output_extent.restype = i
     L.conv_status_string.argtypes = [i]
     L.conv_status_string.restype = ctypes.c_char_p
     L.conv_last_hip_error.argtypes = []
@@ -133,7 +135,8 @@ def _dtype_of(t):
 
 
 def out_extent(size, filt, stride, pad):
-    return (size + 2 * pad - filt) // stride + 1
+    """P or Q of a layer, asked of the library (conv_output_extent)."""
+    return int(lib().conv_output_extent(size, filt, stride, pad))
 
 
 class Workspace:

@@ -30,16 +30,11 @@ def is_stale():
     return any(os.path.getmtime(d) > t for d in DEPS)
 
 
-def build(keep_temps_dir=None, verbose=False):
-    """Compile unconditionally.  keep_temps_dir: directory for the ISA listing."""
+def build(verbose=False):
+    """Compile unconditionally."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB, SRC]
-    cwd = None
-    if keep_temps_dir:
-        os.makedirs(keep_temps_dir, exist_ok=True)
-        cmd.insert(1, "-save-temps")
-        cwd = keep_temps_dir
-    res = subprocess.run(cmd, cwd=cwd, capture_output=True, text=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
     if verbose or res.returncode != 0:
         sys.stderr.write(err + "\n")
@@ -54,5 +49,5 @@ def build(keep_temps_dir=None, verbose=False):
 
 
 if __name__ == "__main__":
-    build(keep_temps_dir=os.environ.get("CONVNET_KEEP_TEMPS"), verbose=True)
+    build(verbose=True)
     print(LIB)

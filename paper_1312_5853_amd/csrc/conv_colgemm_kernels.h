@@ -21,9 +21,6 @@ struct ColGemmArgs {
 
 enum { kGatherDirect = 0, kGatherStridedBwd = 1 };
 
-#ifdef CONVNET_PHASE_PROBE
-__device__ long long *g_probe = nullptr;
-#endif
 
 template <int TM, int TN, int WM, int WN, int GATHER>
 __global__ __launch_bounds__(kThreads) void colgemm_kernel(const ColGemmArgs p)
@@ -386,17 +383,10 @@ __global__ __launch_bounds__(kThreads, (TM == 3 && TN == 1) ? 3 : 2) void colgem
     constexpr int NSTORE = A4T + EPT / 4;                       // store slots
     constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);   // slots after each matrix instruction
 
-#ifdef CONVNET_PHASE_PROBE
-    const long long pr_t0 = __builtin_readcyclecounter();
-    const long long pr_rt0 = wall_clock64();
-#endif
     load_step(0);
     store_step(0);
     if (nsteps > 1) load_step(1);
     __syncthreads();
-#ifdef CONVNET_PHASE_PROBE
-    const long long pr_rt1 = wall_clock64();
-#endif
     // One step out of LDS buffer `par`.  par and mode are compile-time constants: the register sets stay in
     // registers and the slot stream has no branches, so the waits before the LDS writes count only the loads
     // issued a step earlier.  mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither.
@@ -462,14 +452,6 @@ __global__ __launch_bounds__(kThreads, (TM == 3 && TN == 1) ? 3 : 2) void colgem
     } else if (rest == 1) {
         do_step(P0{}, P0{});
     }
-#ifdef CONVNET_PHASE_PROBE
-    if (tid == 0 && g_probe) {
-        long long *o = g_probe + (size_t)bid * 8;
-        o[0] = pr_t0; o[1] = __builtin_readcyclecounter(); o[2] = pr_rt0; o[3] = wall_clock64(); o[5] = pr_rt1;
-        o[6] = __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11));
-        o[7] = __builtin_amdgcn_s_getreg(20 | (0 << 6) | (31 << 11));
-    }
-#endif
 
     const int plane = p.OH * p.OW;
 #pragma unroll
@@ -493,10 +475,6 @@ __global__ __launch_bounds__(kThreads, (TM == 3 && TN == 1) ? 3 : 2) void colgem
             }
         }
     }
-#ifdef CONVNET_PHASE_PROBE
-    __builtin_amdgcn_s_waitcnt(0);
-    if (tid == 0 && g_probe) g_probe[(size_t)bid * 8 + 4] = wall_clock64();
-#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -1068,6 +1046,8 @@ struct PatchArgs {
     int x_bs, y_bs;
     int mtiles, jtiles;   // row tiles, position tiles per image
     int ntiles, tiles_per_xcd;
+    int epi_on;           // bias / ReLU applied to each fp32 sum before it is stored (and, for TO = bfloat16, rounded)
+    Epilogue epi;
     FastDiv div_q, div_rs, div_s, div_mj, div_m, div_wp, div_nr;
 };
 
@@ -1247,6 +1227,17 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int row0 = m0 + i * 32 + half * 4;
+        if (p.epi_on) {                                          // forward only: bias and ReLU, no mask
+            float bv16[16];
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                bv16[v] = p.epi.bias ? p.epi.bias[min(row0 + (v >> 2) * 8 + (v & 3), p.M - 1)] : 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const float t = acc[i][v] + bv16[v];
+                acc[i][v] = (p.epi.relu && !(t > 0.f)) ? 0.f : t;
+            }
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int row = row0 + (v >> 2) * 8 + (v & 3);

@@ -407,6 +407,10 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         a.div_m = make_fastdiv((uint32_t)a.mtiles);
         a.div_wp = make_fastdiv((uint32_t)pl.patch_wp);
         a.div_nr = make_fastdiv((uint32_t)pl.patch_nr);
+        // forward only, so an epilogue here is bias / ReLU: applied to the fp32 sums in the kernel's store
+        a.epi_on = ep != nullptr;
+        a.epi = ep ? *ep : Epilogue{};
+        *ep_applied = a.epi_on;
         launch_patch(tm, a, 8 * a.tiles_per_xcd, pl.patch_lds, pb.dtype == kDtypeBf16, pb.out_bf16, st);
         return check_launch();
     }
@@ -666,14 +670,6 @@ int relu_bwd_typed(const void *x, const void *dy, void *dx, int64_t count, hipSt
 
 }  // namespace
 
-#ifdef CONVNET_PHASE_PROBE
-extern "C" int conv_debug_set_probe(void *buf)
-{
-    long long *p = static_cast<long long *>(buf);
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_probe), &p, sizeof(p));
-}
-#endif
-
 extern "C" {
 
 int conv_fwd_ex(const void *x, const void *w, void *y, int N, int C, int H, int W, int K, int R, int S, int stride,
@@ -784,14 +780,18 @@ static int run_grouped(int op, const void *a, const void *b, void *out, int N, i
     const int out_b = (pb.out_bf16 && op != kOpBwdFilter) ? 2 : 4;
     Problem one = pb;
     one.groups = 1;
+    // byte distance between the columns' slices of the three tensors
+    int64_t sa, sb, so;
+    if (op == kOpFwd) { sa = pb.x_gs * in_b; sb = pb.w_gs * in_b; so = pb.y_gs * out_b; }
+    else if (op == kOpBwdData) { sa = pb.y_gs * in_b; sb = pb.w_gs * in_b; so = pb.x_gs * out_b; }
+    else { sa = pb.x_gs * in_b; sb = pb.y_gs * in_b; so = pb.w_gs * 4; }
+    // every column's base must keep the alignment the kernels rely on: checked for all columns before the first
+    // one is enqueued
+    for (int g = 1; g < groups; ++g)
+        if ((g * sa) % 16 != 0 || (g * sb) % 16 != 0 || (g * so) % 16 != 0) return kErrMisaligned;
     for (int g = 0; g < groups; ++g) {
-        const char *pa = static_cast<const char *>(a), *pbp = static_cast<const char *>(b);
-        char *po = static_cast<char *>(out);
-        if (op == kOpFwd) { pa += g * pb.x_gs * in_b; pbp += g * pb.w_gs * in_b; po += g * pb.y_gs * out_b; }
-        else if (op == kOpBwdData) { pa += g * pb.y_gs * in_b; pbp += g * pb.w_gs * in_b; po += g * pb.x_gs * out_b; }
-        else { pa += g * pb.x_gs * in_b; pbp += g * pb.y_gs * in_b; po += g * pb.w_gs * 4; }
-        // column bases must keep the alignment the kernels rely on
-        if (!aligned(pa, 16) || !aligned(pbp, 16) || !aligned(po, 16)) return kErrMisaligned;
+        const char *pa = static_cast<const char *>(a) + g * sa, *pbp = static_cast<const char *>(b) + g * sb;
+        char *po = static_cast<char *>(out) + g * so;
         rc = op == kOpBwdFilter ? run_wgrad(pa, pbp, po, one, pl, ws, st) : run_colgemm(op, pa, pbp, po, one, pl, ws, st);
         if (rc != kStatusOk) return rc;
     }
@@ -850,6 +850,12 @@ size_t conv_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, in
     Problem pb;
     if (make_problem(pb, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype) != kStatusOk) return 0;
     return make_plan(op, pb).total;
+}
+
+int conv_output_extent(int in, int filt, int stride, int pad)
+{
+    if (in <= 0 || filt <= 0 || stride <= 0 || pad < 0 || pad > (1 << 20)) return 0;
+    return out_extent(in, filt, stride, pad);
 }
 
 const char *conv_status_string(int status)

@@ -27,3 +27,22 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+# Normalised max errors the parity tests measured, printed once at the end of the run (also under -q).
+_PARITY = []
+
+
+@pytest.fixture
+def parity_record():
+    def record(tag, err, tol):
+        _PARITY.append((tag, float(err), float(tol)))
+    return record
+
+
+def pytest_terminal_summary(terminalreporter):
+    if not _PARITY:
+        return
+    terminalreporter.write_line("normalised max error vs the CPU oracle (whole tensors):")
+    for tag, err, tol in _PARITY:
+        terminalreporter.write_line("  %-44s %.3e  (bar %.1e)" % (tag, err, tol))

@@ -167,6 +167,36 @@ def test_host_planning_selftest(tmp_path):
     assert "0 failures" in out.stdout
 
 
+SAN_FLAGS = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"]
+# leak checking off (the OpenMP runtime keeps its thread pool); the link-order check is off because the test
+# harness may preload a library of its own ahead of the sanitizer runtime
+SAN_ENV = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:verify_asan_link_order=0:abort_on_error=0",
+               UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1", OMP_NUM_THREADS="4")
+
+
+def test_oracle_runs_clean_under_address_and_ub_sanitizers(tmp_path):
+    """The C oracle built with AddressSanitizer + UndefinedBehaviorSanitizer: all entry points on exactly-sized heap
+    tensors (padding beyond the filter, strides that leave rows unread, 1x1 outputs), checked by closed forms."""
+    exe = str(tmp_path / "oracle_san")
+    subprocess.run(["gcc", "-std=c99", "-fopenmp", "-Wall", "-Wextra"] + SAN_FLAGS +
+                   ["-o", exe, os.path.join(ROOT, "tests", "oracle_sanitizer_main.c"),
+                    os.path.join(ROOT, "oracle", "conv_oracle.c"), "-lm"], check=True)
+    out = subprocess.run([exe], capture_output=True, text=True, env=SAN_ENV)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert "0 failures" in out.stdout and "runtime error" not in out.stderr and "AddressSanitizer" not in out.stderr
+
+
+def test_host_planning_runs_clean_under_sanitizers(tmp_path):
+    """The host-side planning header (argument checks, extents, tile and split choice, workspace layout, magic
+    division) under the same sanitizers: signed overflow in the size arithmetic would stop the run."""
+    exe = str(tmp_path / "host_selftest_san")
+    subprocess.run(["g++", "-std=c++17"] + SAN_FLAGS + ["-o", exe, os.path.join(ROOT, "tests", "host_selftest.cpp")],
+                   check=True)
+    out = subprocess.run([exe], capture_output=True, text=True, env=SAN_ENV)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert "0 failures" in out.stdout and "runtime error" not in out.stderr
+
+
 def test_convert_argument_checks(lib):
     from paper_1312_5853_amd import binding as b
     assert lib.convert_f32_to_bf16(None, PTR, 8, None) == b.ERR_INVALID_ARG
