@@ -64,7 +64,8 @@ typedef enum conv_status {
     CONV_ERR_BAD_DTYPE = -3,
     CONV_ERR_WORKSPACE_TOO_SMALL = -4, /* ws is NULL or ws_bytes < conv_workspace_bytes() while scratch is needed */
     CONV_ERR_MISALIGNED = -5,          /* tensor base not 16-byte aligned, or ws not 256-byte aligned */
-    CONV_ERR_HIP = -6                  /* the HIP runtime refused a launch; hipGetLastError() text via conv_last_hip_error() */
+    CONV_ERR_HIP = -6,                 /* the HIP runtime refused a launch; hipGetLastError() text via conv_last_hip_error() */
+    CONV_ERR_SCRATCH_LIMIT = -7        /* conv_bwd_filter_noalloc: the pass needs more than CONV_NOALLOC_SCRATCH_BYTES */
 } conv_status;
 
 enum { CONV_DTYPE_F32 = 0, CONV_DTYPE_BF16 = 1, CONV_DTYPE_BF16_OUT_BF16 = 2 };
@@ -108,6 +109,32 @@ int conv_bwd_data(const void *dy, const void *w, void *dx,
 int conv_bwd_filter(const void *x, const void *dy, void *dw,
                     int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                     int dtype, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * conv_bwd_filter for callers that cannot allocate and have no workspace to
+ * pass: code under HIP graph capture, tight training or serving loops, harnesses
+ * that forbid hipMalloc.  Same arithmetic, kernels, layouts and results (bit for
+ * bit) as conv_bwd_filter with dense tensors; the scratch (tap table, partial
+ * sums of the split reduction, packed bf16 copies) lives in a static device
+ * array of CONV_NOALLOC_SCRATCH_BYTES inside the library, of which every GPU the
+ * library runs on holds one copy until the process ends.  The call allocates
+ * and frees nothing, on the device or through any library.
+ *   - A pass whose conv_workspace_bytes(CONV_OP_BWD_FILTER, ...) exceeds
+ *     CONV_NOALLOC_SCRATCH_BYTES returns CONV_ERR_SCRATCH_LIMIT before anything
+ *     is enqueued.  fp32: the partial sums do not grow with N, and all five
+ *     layers of the stack fit at any batch size.  bf16: the packed copies grow
+ *     with N (the third layer needs 31 MB at N = 16, 46 MB at N = 64).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time
+ *     on one GPU (different streams or threads) race.  Calls on one stream are
+ *     ordered.  The array keeps the previous call's contents; every call
+ *     overwrites what it reads, nothing has to start at zero.
+ *   - The first call on a device looks the array's address up
+ *     (hipGetSymbolAddress); make that call before a stream capture begins.
+ */
+#define CONV_NOALLOC_SCRATCH_BYTES (32u << 20)
+int conv_bwd_filter_noalloc(const void *x, const void *dy, void *dw,
+                            int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
+                            int dtype, void *stream);
 
 /*
  * Batch-strided variants: sample n of the activation tensor on the layer's

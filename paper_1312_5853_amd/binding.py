@@ -16,11 +16,13 @@ LIB_PATH = os.path.join(_HERE, "libconvnet_hotpath.so")
 
 OK = 0
 ERR_INVALID_ARG, ERR_TOO_LARGE, ERR_BAD_DTYPE, ERR_WORKSPACE, ERR_MISALIGNED, ERR_HIP = -1, -2, -3, -4, -5, -6
+ERR_SCRATCH_LIMIT = -7
+NOALLOC_SCRATCH_BYTES = 32 << 20
 DTYPE_F32, DTYPE_BF16, DTYPE_BF16_OUT_BF16 = 0, 1, 2
 OP_FWD, OP_BWD_DATA, OP_BWD_FILTER = 0, 1, 2
 
 EXPORTS = (
-    "conv_fwd", "conv_bwd_data", "conv_bwd_filter",
+    "conv_fwd", "conv_bwd_data", "conv_bwd_filter", "conv_bwd_filter_noalloc",
     "conv_fwd_ex", "conv_bwd_data_ex", "conv_bwd_filter_ex", "conv_fwd_bias_relu", "conv_bwd_data_relu",
     "conv_fwd_grouped", "conv_bwd_data_grouped", "conv_bwd_filter_grouped", "conv_workspace_bytes_grouped",
     "conv_workspace_bytes", "conv_output_extent", "conv_status_string", "conv_last_hip_error",
@@ -64,6 +66,8 @@ def lib():
         f = getattr(L, name + "_grouped")
         f.argtypes = [vp, vp, vp] + dims + [i, i, vp, sz, vp]
         f.restype = i
+    L.conv_bwd_filter_noalloc.argtypes = [vp, vp, vp] + dims + [i, vp]
+    L.conv_bwd_filter_noalloc.restype = i
     L.conv_fwd_bias_relu.argtypes = [vp, vp, vp, vp] + dims + [i, i, vp, sz, vp]
     L.conv_fwd_bias_relu.restype = i
     L.conv_bwd_data_relu.argtypes = [vp, vp, vp, vp] + dims + [i, vp, sz, vp]
@@ -290,6 +294,21 @@ def conv_bwd_filter(x, dy, R, S, stride, pad, dw=None, ws=None, stream=None):
     dims = (N, C, H, W, K, R, S, stride, pad)
     return _run("conv_bwd_filter", OP_BWD_FILTER, x, dy, dw, dims, _batch_stride(x), _batch_stride(dy),
                 _dtype_of(x), ws, stream)
+
+
+def conv_bwd_filter_noalloc(x, dy, R, S, stride, pad, dw=None, stream=None):
+    """conv_bwd_filter on dense tensors with the library's built-in scratch: no workspace argument.  `dw` must be
+    given by callers that may not allocate (this wrapper allocates it only when it is None)."""
+    N, C, H, W = x.shape
+    K = dy.shape[1]
+    _dense(x, dy, dw)
+    if dw is None:
+        dw = torch.empty((K, C, R, S), dtype=torch.float32, device=x.device)
+    rc = lib().conv_bwd_filter_noalloc(_ptr(x), _ptr(dy), _ptr(dw), N, C, H, W, K, R, S, stride, pad, _dtype_of(x),
+                                       _stream_handle(stream))
+    if rc != OK:
+        raise ConvError(rc, "conv_bwd_filter_noalloc")
+    return dw
 
 
 def _run_grouped(name, op, a, b, out, dims, groups, dtype, ws, stream):

@@ -14,6 +14,7 @@
 
 #include <stdio.h>
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 #include <stdlib.h>
 #include <string.h>
@@ -25,6 +26,10 @@ using namespace convnet;
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Scratch of conv_bwd_filter_noalloc: one copy per GPU, held until the process ends.  In host code this name is only
+// a handle for hipGetSymbolAddress; kernels and memory calls take the address that call returns.
+static __device__ __align__(256) unsigned char scratch[CONV_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -852,6 +857,44 @@ size_t conv_workspace_bytes(int op, int N, int C, int H, int W, int K, int R, in
     return make_plan(op, pb).total;
 }
 
+// Address of this GPU's copy of `scratch`, resolved once per device with that device current.
+static int noalloc_scratch(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static void *ptrs[kMaxDevices] = {};
+    static std::mutex mu;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!ptr || !aligned(ptr, 256)) return hip_fail(hipErrorInvalidSymbol);
+        ptrs[dev] = ptr;
+    }
+    *out = ptrs[dev];
+    return kStatusOk;
+}
+
+int conv_bwd_filter_noalloc(const void *x, const void *dy, void *dw, int N, int C, int H, int W, int K, int R, int S,
+                            int stride, int pad, int dtype, void *stream)
+{
+    if (!x || !dy || !dw) return kErrInvalidArg;
+    Problem pb;
+    int rc = make_problem(pb, N, C, H, W, K, R, S, stride, pad, 0, 0, dtype);
+    if (rc != kStatusOk) return rc;
+    if (!aligned(x, 16) || !aligned(dy, 16) || !aligned(dw, 16)) return kErrMisaligned;
+    const Plan pl = make_plan(kOpBwdFilter, pb);
+    if (pl.total > (size_t)CONV_NOALLOC_SCRATCH_BYTES) return kErrScratchLimit;
+    void *ws = nullptr;
+    rc = noalloc_scratch(&ws);
+    if (rc != kStatusOk) return rc;
+    return run_wgrad(x, dy, dw, pb, pl, ws, static_cast<hipStream_t>(stream));
+}
+
 int conv_output_extent(int in, int filt, int stride, int pad)
 {
     if (in <= 0 || filt <= 0 || stride <= 0 || pad < 0 || pad > (1 << 20)) return 0;
@@ -868,6 +911,7 @@ const char *conv_status_string(int status)
     case kErrWorkspace: return "workspace missing or too small";
     case kErrMisaligned: return "pointer not sufficiently aligned";
     case kErrHip: return "HIP runtime error";
+    case kErrScratchLimit: return "the pass needs more scratch than the library's built-in buffer holds";
     default: return "unknown status";
     }
 }

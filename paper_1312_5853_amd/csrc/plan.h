@@ -21,6 +21,7 @@ constexpr int kErrBadDtype = -3;
 constexpr int kErrWorkspace = -4;
 constexpr int kErrMisaligned = -5;
 constexpr int kErrHip = -6;
+constexpr int kErrScratchLimit = -7;
 
 constexpr int kOpFwd = 0, kOpBwdData = 1, kOpBwdFilter = 2;
 constexpr int kDtypeF32 = 0, kDtypeBf16 = 1, kDtypeBf16OutBf16 = 2;

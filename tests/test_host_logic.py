@@ -37,11 +37,11 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_status_strings(lib):
     seen = set()
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         s = lib.conv_status_string(code).decode()
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 7
+    assert len(seen) == 8
     assert lib.conv_status_string(-99).decode() == "unknown status"
     assert lib.conv_last_hip_error().decode() == ""
 
@@ -195,6 +195,31 @@ def test_host_planning_runs_clean_under_sanitizers(tmp_path):
     out = subprocess.run([exe], capture_output=True, text=True, env=SAN_ENV)
     assert out.returncode == 0, out.stdout + out.stderr
     assert "0 failures" in out.stdout and "runtime error" not in out.stderr
+
+
+def test_noalloc_entry_point_checks_before_any_gpu_call(lib):
+    """conv_bwd_filter_noalloc: the ordinary argument checks, and a pass that needs more scratch than the built-in
+    buffer is refused with its own status -- all on the host (no GPU here)."""
+    from paper_1312_5853_amd import binding as b
+    f = lib.conv_bwd_filter_noalloc
+    good = (2, 16, 13, 13, 32, 3, 3, 1, 1)
+    assert f(None, PTR, PTR, *good, 0, None) == b.ERR_INVALID_ARG
+    assert f(PTR, PTR, None, *good, 0, None) == b.ERR_INVALID_ARG
+    assert f(PTR, PTR, PTR, 0, 16, 13, 13, 32, 3, 3, 1, 1, 0, None) == b.ERR_INVALID_ARG
+    assert f(PTR, PTR, PTR, *good, 9, None) == b.ERR_BAD_DTYPE
+    assert f(PTR + 4, PTR, PTR, *good, 0, None) == b.ERR_MISALIGNED
+    # bf16 second layer at N = 256: about 100 MB of packed copies and partial sums
+    big = (256, 48, 27, 27, 128, 5, 5, 1, 2)
+    assert lib.conv_workspace_bytes(b.OP_BWD_FILTER, *big, 1) > b.NOALLOC_SCRATCH_BYTES
+    assert f(PTR, PTR, PTR, *big, 1, None) == b.ERR_SCRATCH_LIMIT
+    # fp32: every layer of the stack fits at every batch size of the workload list
+    from paper_1312_5853_amd import synth
+    for N in (64, 128, 256):
+        for name, L in synth.LAYERS.items():
+            dims = (N, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], L["stride"], L["pad"])
+            assert lib.conv_workspace_bytes(b.OP_BWD_FILTER, *dims, 0) <= b.NOALLOC_SCRATCH_BYTES, (N, name)
+    header = open(HEADER).read()
+    assert "#define CONV_NOALLOC_SCRATCH_BYTES (32u << 20)" in header
 
 
 def test_convert_argument_checks(lib):

@@ -1,0 +1,77 @@
+"""conv_bwd_filter_noalloc (the entry point for callers that cannot allocate): called through the C ABI, its result
+against conv_bwd_filter's on the same inputs, two calls in a row, the second with a smaller input."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1312_5853_amd import binding as hp
+from paper_1312_5853_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _call_noalloc(xd, dyd, dw, dims, dtype):
+    """Straight through ctypes: device pointers, extents, dtype code, stream."""
+    rc = hp.lib().conv_bwd_filter_noalloc(ctypes.c_void_p(xd.data_ptr()), ctypes.c_void_p(dyd.data_ptr()),
+                                          ctypes.c_void_p(dw.data_ptr()), *dims, dtype,
+                                          ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == hp.OK, hp.status_string(rc)
+
+
+def _case(shape, dtype, seed):
+    N, C, H, W, K, R, S, st, pad = shape
+    P, Q = hp.out_extent(H, R, st, pad), hp.out_extent(W, S, st, pad)
+    x = synth.gaussian((N, C, H, W), seed)
+    dy = synth.gaussian((N, K, P, Q), seed + 1)
+    if dtype == "bf16":
+        x, dy = oracle.bf16_round(x), oracle.bf16_round(dy)
+    to = (lambda a: torch.from_numpy(a).cuda().to(torch.bfloat16)) if dtype == "bf16" else \
+        (lambda a: torch.from_numpy(a).cuda())
+    return x, dy, to(x), to(dy)
+
+
+# (first call, second and smaller call): the split fast path twice; the tap-table path of a few-channel layer after
+# a large fast-path call; bf16 packed copies after an fp32 call
+PAIRS = [
+    ((128, 256, 13, 13, 384, 3, 3, 1, 1), "f32", (5, 64, 13, 13, 96, 3, 3, 1, 1), "f32"),
+    ((16, 48, 27, 27, 128, 5, 5, 1, 2), "f32", (3, 3, 23, 25, 48, 11, 11, 4, 2), "f32"),
+    ((8, 64, 13, 13, 64, 3, 3, 1, 1), "f32", (3, 64, 13, 13, 64, 3, 3, 1, 1), "bf16"),
+]
+
+
+@pytest.mark.parametrize("first,dt1,second,dt2", PAIRS)
+def test_noalloc_equals_workspace_entry_point_twice_in_a_row(first, dt1, second, dt2):
+    tol = {"f32": 1e-4, "bf16": 2e-2}
+    for i, (shape, dtype) in enumerate(((first, dt1), (second, dt2))):
+        N, C, H, W, K, R, S, st, pad = shape
+        x, dy, xd, dyd = _case(shape, dtype, 300 + 10 * i)
+        code = hp.DTYPE_BF16 if dtype == "bf16" else hp.DTYPE_F32
+        need = hp.workspace_bytes(hp.OP_BWD_FILTER, *shape, code)
+        assert 0 < need <= hp.NOALLOC_SCRATCH_BYTES
+        want = hp.conv_bwd_filter(xd, dyd, R, S, st, pad)                       # the existing entry point
+        got = torch.full((K, C, R, S), float("nan"), dtype=torch.float32, device="cuda")
+        _call_noalloc(xd, dyd, got, shape, code)
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), (shape, dtype)                           # same kernels, fixed order: bit for bit
+        ref = oracle.conv_bwd_filter(x, dy, R, S, st, pad)
+        err = np.abs(got.cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max()
+        assert err <= tol[dtype], (shape, dtype, err)
+
+
+def test_noalloc_refuses_what_does_not_fit_and_leaves_dw_alone():
+    shape = (256, 48, 27, 27, 128, 5, 5, 1, 2)                                  # bf16: about 100 MB of scratch
+    N, C, H, W, K, R, S, st, pad = shape
+    assert hp.workspace_bytes(hp.OP_BWD_FILTER, *shape, hp.DTYPE_BF16) > hp.NOALLOC_SCRATCH_BYTES
+    xd = torch.zeros((N, C, H, W), dtype=torch.bfloat16, device="cuda")
+    dyd = torch.zeros((N, K, H, W), dtype=torch.bfloat16, device="cuda")
+    dw = torch.full((K, C, R, S), 7.0, device="cuda")
+    rc = hp.lib().conv_bwd_filter_noalloc(ctypes.c_void_p(xd.data_ptr()), ctypes.c_void_p(dyd.data_ptr()),
+                                          ctypes.c_void_p(dw.data_ptr()), *shape, hp.DTYPE_BF16, None)
+    torch.cuda.synchronize()
+    assert rc == hp.ERR_SCRATCH_LIMIT and bool((dw == 7.0).all())
+    with pytest.raises(hp.ConvError) as e:
+        hp.conv_bwd_filter_noalloc(xd, dyd, R, S, st, pad, dw=dw)
+    assert e.value.status == hp.ERR_SCRATCH_LIMIT and "scratch" in str(e.value)
