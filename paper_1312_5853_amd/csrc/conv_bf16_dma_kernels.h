@@ -1,0 +1,332 @@
+// Forward / stride-1 backward-data with bf16 inputs, second generation: both operands go from global memory
+// straight into LDS (16 bytes per lane, no staging registers, no LDS store instructions).
+// Part of convnet_hotpath.hip: included there, inside its anonymous namespace, after conv_colgemm_kernels.h.
+//
+// Why: on gfx950 an LDS store instruction moves about 75 bytes per clock and CU (ds_write_b128: 13.5 clocks per
+// wavefront instruction) against 256 bytes per clock for ds_read_b128, and the vector memory path delivers 64 bytes
+// per clock and CU.  At bf16 matrix rates (one 32x32x16 instruction = 32 clocks) a 128 x 128 tile staged through
+// registers needs more LDS store time than matrix time.  Direct loads cost the memory path only, and a 128 x 256
+// tile brings 48 KB per 64-channel step through it in 768 clocks against 1024 clocks of matrix work.
+//
+// Layouts the two preparation kernels below write into the workspace:
+//   xb  activations, channel-blocked AND zero-padded: [n][channel block of 16][Hp][Wp][16 channels], 32 bytes per
+//       position and block.  With the padding in place a filter tap is a constant address offset: no bounds
+//       tests and no zero substitution remain in the main loop (a direct load could not substitute a zero).
+//       Padded row of output row oh under tap r:  oh*mul + r (forward, pad rows above = pad) or oh + (R-1-r)
+//       (backward-data, pad rows above = R-1-pad); columns alike.
+//   wt  filters [step = (channel block of KC, r, s)][Mpad rows][KC channels], the eight-channel (16-byte) chunks of
+//       a row stored at position chunk ^ swz(row): a linear copy into LDS then yields rows whose chunks are
+//       XOR-swizzled, and the 16 lanes of one ds_read_b128 phase (16 rows, one chunk each) cover all 64 banks.
+//       swz(row) = (row >> log2(256 / row bytes)) & (chunks - 1).
+// LDS: three buffers of (BM + BN) rows of KC bf16 (unpadded rows: a wavefront's direct load fills 1 KB
+// linearly).  Step s is multiplied out of buffer s % 3 while the loads of step s + 2 are in flight into the buffer
+// that step s - 1 used; before the barrier that ends step s every wave waits until its loads of step s + 1 have
+// landed (s_waitcnt vmcnt(loads per step)).
+struct ColGemmDmaArgs {
+    const void *At;        // wt (see above)
+    const void *xb;        // blocked, padded activations
+    void *dst;             // y or dx: fp32, or bfloat16 when out_bf16
+    float *part;           // ksplit > 1: partial outputs [ksplit][N][M][OH*OW]
+    int M, Mpad, ncols;
+    int OH, OW, mul;
+    int Wp;                // padded row pitch of xb in positions
+    int cb_bytes;          // bytes of one (sample, channel block): Hp * Wp * 32
+    int n_bytes;           // bytes of one sample: (channels / 16) * cb_bytes
+    int R, S, sign;        // sign +1: tap (r, s) reads padded (oh*mul + r, ow*mul + s); -1: (oh + R-1-r, ow + S-1-s)
+    int cblocks;           // channels / KC
+    int dst_bs, out_bf16;
+    int mtiles, ntiles, tiles_per_xcd, ksplit, steps_per_split;
+    int epi_on;
+    Epilogue epi;
+    FastDiv div_plane, div_ow, div_rs, div_s;
+};
+
+// 16 bytes per lane from global memory (sbase + voff, voff per lane) into LDS at lds_base + lane * 16
+// (lds_base wave-uniform, in bytes).  Counts on vmcnt like any vector memory load.  M0 (the LDS base of such loads)
+// is set inside the statement; the compiler keeps no value of its own in that register across statements.
+__device__ __forceinline__ void dma16(const void *sbase, unsigned voff, unsigned lds_base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_base), "v"(voff), "s"(sbase));
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N)); }
+
+template <int TM, int TN, int WM, int WN, int KC, int OCC>
+__global__ __launch_bounds__(kThreads, OCC) void colgemm_bf16_dma_kernel(const ColGemmDmaArgs p)
+{
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int RB = KC * 2;                 // bytes per LDS row
+    constexpr int CH = KC / 8;                 // 16-byte chunks per row
+    constexpr int SH = KC == 64 ? 1 : 2;       // log2(256 / RB)
+    constexpr int NK = KC / 16;                // matrix instructions per 32 x 32 block and step
+    constexpr int NA = BM * CH / kThreads;     // direct loads per thread and step: filters
+    constexpr int NB = BN * CH / kThreads;     // ... activations
+    constexpr int NL = NA + NB;
+    constexpr int BUF = (BM + BN) * RB;        // bytes per LDS buffer
+    static_assert(WM * WN == 4, "four waves per work-group");
+    static_assert(KC == 64 || KC == 32, "step depth");
+    static_assert(NK % 2 == 0, "slice 0 of the next step lands in fragment set 0");
+    static_assert((BM * CH) % kThreads == 0 && (BN * CH) % kThreads == 0, "whole wavefront loads");
+
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    const char *const lds = reinterpret_cast<const char *>(lds_fast);
+    const unsigned lds_base = (unsigned)(size_t)lds_fast;       // LDS byte address of buffer 0
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.tiles_per_xcd + idx;
+    const int ntile = p.mtiles * p.ntiles;
+    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit) return;
+    const int ks = unit / ntile;
+    const int tile = unit - ks * ntile;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    // --- activation loads: load u of this thread fills chunk slot (q % CH) of tile row q / CH, q = (wave*NB + u)*64 + lane,
+    // with the chunk (slot ^ swz(row)) of that row's position
+    unsigned boff[NB];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        const int q = (wave * NB + u) * 64 + lane;
+        const int row = q / CH, slot = q % CH;
+        const int c = slot ^ ((row >> SH) & (CH - 1));
+        int j = n0 + row;
+        j = j < p.ncols ? j : 0;                                 // columns past the end compute garbage that is never stored
+        const int n = (int)fastdiv((uint32_t)j, p.div_plane);
+        const int rem = j - n * (p.OH * p.OW);
+        const int oh = (int)fastdiv((uint32_t)rem, p.div_ow);
+        const int ow = rem - oh * p.OW;
+        boff[u] = (unsigned)(n * p.n_bytes + (oh * p.mul * p.Wp + ow * p.mul) * 32 + (c >> 1) * p.cb_bytes + (c & 1) * 16);
+    }
+    // --- filter loads: linear
+    const unsigned aoff = (unsigned)((wave * NA * 64 + lane) * 16);
+
+    const int step_begin = ks * p.steps_per_split;
+    const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
+    const size_t a_step_bytes = (size_t)p.Mpad * RB;
+    const char *a_base = static_cast<const char *>(p.At) + (size_t)step_begin * a_step_bytes + (size_t)m0 * RB;
+    // next step to load: channel block, tap
+    int r, s, cb;
+    {
+        cb = (int)fastdiv((uint32_t)step_begin, p.div_rs);
+        const int rs = step_begin - cb * (p.R * p.S);
+        r = (int)fastdiv((uint32_t)rs, p.div_s);
+        s = rs - r * p.S;
+    }
+    // The NL loads of a step are issued one at a time (load_one), spread between the matrix instructions: a wave
+    // that issues them in a burst stalls on the full memory queue, and with it its matrix pipe.
+    const char *xs = nullptr;        // activation base of the step being loaded (tap and channel block applied)
+    unsigned la = 0, lb = 0;         // LDS addresses of that step's filter / activation rows of this wave
+    auto begin_step_loads = [&](int buf) {
+        const int ar = p.sign > 0 ? r : p.R - 1 - r, as = p.sign > 0 ? s : p.S - 1 - s;
+        xs = static_cast<const char *>(p.xb) + (size_t)cb * (KC / 16) * p.cb_bytes + (ar * p.Wp + as) * 32;
+        la = lds_base + buf * BUF + wave * NA * 1024;
+        lb = lds_base + buf * BUF + BM * RB + wave * NB * 1024;
+    };
+    auto load_one = [&](int i) {     // i < NL, compile-time after unrolling
+        if (i < NA) dma16(a_base, aoff + i * 1024, la + i * 1024);
+        else dma16(xs, boff[i - NA], lb + (i - NA) * 1024);
+    };
+    auto end_step_loads = [&]() {
+        a_base += a_step_bytes;
+        s += 1;
+        if (s == p.S) { s = 0; r += 1; }
+        if (r == p.R) { r = 0; cb += 1; }
+    };
+    auto load_step = [&](int buf) {
+        begin_step_loads(buf);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) load_one(i);
+        end_step_loads();
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    // fragment addresses: row l32 of a 32-row block, chunk (2t + half) ^ swz(row); swz depends on l32 only
+    const int l32 = lane & 31, half = lane >> 5;
+    const int swzl = (l32 >> SH) & (CH - 1);
+    int koff[NK];
+#pragma unroll
+    for (int t = 0; t < NK; ++t) koff[t] = ((2 * t + half) ^ swzl) * 16;
+    const int a_row = (wm * TM * 32 + l32) * RB;
+    const int b_row = BM * RB + (wn * TN * 32 + l32) * RB;
+
+    u32x4 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](const char *bufp, int t, int set) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[set][i] = *reinterpret_cast<const u32x4 *>(bufp + a_row + i * 32 * RB + koff[t]);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) fb[set][jn] = *reinterpret_cast<const u32x4 *>(bufp + b_row + jn * 32 * RB + koff[t]);
+    };
+
+    if (nsteps > 0) load_step(0);
+    if (nsteps > 1) load_step(1);
+    if (nsteps > 1) wait_vmcnt<NL>(); else wait_vmcnt<0>();
+    __syncthreads();
+    if (nsteps > 0) read_frags(lds, 0, 0);
+
+    // One step.  Slices t = 0 .. NK-1 of 16 channels; the fragments of slice t + 1 are read while slice t is
+    // multiplied.  The loads of step + 2 are issued during slices 0 .. NK-2.  Before the LAST slice is multiplied:
+    // wait for this wave's loads of step + 1 and for its outstanding fragment reads, barrier, then read slice 0 of
+    // step + 1 -- its latency passes under the last slice's matrix instructions.
+    constexpr int MPS = TM * TN;                       // matrix instructions per slice
+    constexpr int SLOTS = (NK - 1) * MPS;              // ... in the slices that carry loads
+    constexpr int SPACING = SLOTS / NL > 0 ? SLOTS / NL : 1;
+    static_assert(NL <= SLOTS, "one load per matrix instruction at most");
+    int step = 0;
+    auto do_step = [&](auto more_c) {                  // more: the loads of step + 2 exist (compile-time)
+        constexpr bool more = decltype(more_c)::value;
+        const char *bufp = lds + (step % 3) * BUF;
+        const char *nextp = lds + ((step + 1) % 3) * BUF;
+        if (more) begin_step_loads((step + 2) % 3);
+#pragma unroll
+        for (int t = 0; t < NK; ++t) {
+            if (t + 1 < NK) {
+                read_frags(bufp, t + 1, (t + 1) & 1);
+            } else {
+                if (more) wait_vmcnt<NL>(); else wait_vmcnt<0>();
+                asm volatile("s_waitcnt lgkmcnt(0)");
+                __syncthreads();
+                if (more || step + 1 < nsteps) read_frags(nextp, 0, (t + 1) & 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int jn = 0; jn < TN; ++jn) {
+                    acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[t & 1][i]),
+                                                                         __builtin_bit_cast(bf16x8, fb[t & 1][jn]),
+                                                                         acc[i][jn], 0, 0, 0);
+                    const int m = t * MPS + i * TN + jn;           // index among the step's matrix instructions
+                    if (more && t + 1 < NK && m % SPACING == SPACING - 1 && m / SPACING < NL) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_one(m / SPACING);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more) end_step_loads();
+        ++step;
+    };
+    while (step + 2 < nsteps) do_step(std::true_type{});
+    while (step < nsteps) do_step(std::false_type{});
+
+    const int plane = p.OH * p.OW;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+        const int n = (int)fastdiv((uint32_t)col, p.div_plane);
+        const int rem = col - n * plane;
+        if (p.epi_on && p.ksplit == 1)            // split sums get it in reduce_split_outputs
+            epi_tile<TM, TN>(p.epi, acc, jn, m0 + wm * TM * 32 + half * 4, p.M, plane,
+                             (int64_t)n * p.epi.mask_bs + rem);
+        if (p.ksplit == 1 && p.out_bf16) {
+            unsigned short *out = static_cast<unsigned short *>(p.dst) + (size_t)n * p.dst_bs + rem;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + (v >> 2) * 8 + (v & 3);
+                    if (row < p.M) out[(size_t)row * plane] = bf16_round(acc[i][jn][v]);
+                }
+            }
+            continue;
+        }
+        float *out = p.ksplit > 1 ? p.part + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
+                                  : static_cast<float *>(p.dst) + (size_t)n * p.dst_bs + rem;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.M) out[(size_t)row * plane] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
+// One launch prepares both operands of colgemm_bf16_dma_kernel.
+//   blocks [0, xb_blocks): xb[n][cb][hp][wp][16] from NCHW bf16 src (samples src_bs elements apart), zeros in the
+//                          padding; one thread per (n, cb, hp, wp)
+//   the rest:              wt[step][Mpad][kc] from KCRS filters, chunks swizzled; one thread per 8-channel chunk
+struct DmaPrepArgs {
+    const unsigned short *src;
+    u32x4 *xb;
+    int N, CB, LH, LW, Hp, Wp, pad_h, pad_w;   // pad_h / pad_w: zero rows above / zero columns left of the data
+    int64_t src_bs;
+    int xb_blocks;
+    const unsigned short *w;
+    unsigned short *wt;
+    int M, Mpad, cblocks, RS, C, transposed, kc;
+    FastDiv div_wp, div_hp, div_cb;
+};
+
+__global__ __launch_bounds__(256) void bf16_dma_prepare(const DmaPrepArgs p)
+{
+    if ((int)blockIdx.x < p.xb_blocks) {
+        const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        const int64_t total = (int64_t)p.N * p.CB * p.Hp * p.Wp;
+        if (i >= total) return;
+        const uint32_t t1 = fastdiv((uint32_t)i, p.div_wp);          // (n*CB + cb)*Hp + hp
+        const int wp = (int)((uint32_t)i - t1 * (uint32_t)p.Wp);
+        const uint32_t t2 = fastdiv(t1, p.div_hp);                    // n*CB + cb
+        const int hp = (int)(t1 - t2 * (uint32_t)p.Hp);
+        const uint32_t n = fastdiv(t2, p.div_cb);
+        const int cb = (int)(t2 - n * (uint32_t)p.CB);
+        const int h = hp - p.pad_h, w = wp - p.pad_w;
+        u32x4 lo = {0u, 0u, 0u, 0u}, hi = {0u, 0u, 0u, 0u};
+        if ((unsigned)h < (unsigned)p.LH && (unsigned)w < (unsigned)p.LW) {
+            const int LHW = p.LH * p.LW;
+            const unsigned short *s = p.src + n * p.src_bs + (int64_t)cb * 16 * LHW + h * p.LW + w;
+            unsigned short v[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) v[k] = s[(int64_t)k * LHW];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                lo[k] = (unsigned)v[2 * k] | ((unsigned)v[2 * k + 1] << 16);
+                hi[k] = (unsigned)v[8 + 2 * k] | ((unsigned)v[8 + 2 * k + 1] << 16);
+            }
+        }
+        p.xb[2 * i] = lo;
+        p.xb[2 * i + 1] = hi;
+        return;
+    }
+    // filters: one thread per 16-byte chunk (8 consecutive channels of one row and tap)
+    const int chunks = p.kc / 8, sh = p.kc == 64 ? 1 : 2;
+    int64_t i = (int64_t)(blockIdx.x - p.xb_blocks) * 256 + threadIdx.x;
+    const int64_t total = (int64_t)p.cblocks * p.RS * p.Mpad * chunks;
+    if (i >= total) return;
+    const int c = (int)(i % chunks);
+    int64_t t = i / chunks;
+    const int m = (int)(t % p.Mpad);
+    t /= p.Mpad;
+    const int rs = (int)(t % p.RS);
+    const int cbk = (int)(t / p.RS);
+    const int ch0 = cbk * p.kc + c * 8;
+    unsigned short v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int ch = ch0 + k;
+        v[k] = m < p.M ? (p.transposed ? p.w[((int64_t)ch * p.C + m) * p.RS + rs] : p.w[((int64_t)m * p.C + ch) * p.RS + rs])
+                       : (unsigned short)0;
+    }
+    const u32x4 o = {(unsigned)v[0] | ((unsigned)v[1] << 16), (unsigned)v[2] | ((unsigned)v[3] << 16),
+                     (unsigned)v[4] | ((unsigned)v[5] << 16), (unsigned)v[6] | ((unsigned)v[7] << 16)};
+    const int pos = c ^ ((m >> sh) & (chunks - 1));
+    reinterpret_cast<u32x4 *>(p.wt)[(i - c) + pos] = o;
+}

@@ -41,6 +41,7 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 
 #include "device_common.h"
 #include "conv_colgemm_kernels.h"
+#include "conv_bf16_dma_kernels.h"
 #include "conv_wgrad_kernels.h"
 #include "fc_kernels.h"
 #include "glue_kernels.h"
@@ -162,6 +163,77 @@ void launch_colgemm_bf16(const TileShape &t, int kc, const ColGemmFastArgs &a, c
     else launch_colgemm_bf16_kc<16>(t, a, g, st);
 }
 
+int grid1d(int64_t n, int block) { return (int)((n + block - 1) / block); }
+
+template <typename Kern>
+void launch_dma(Kern kern, const ColGemmDmaArgs &a, int grid, int lds, hipStream_t st)
+{
+    if (lds > 64 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  160 * 1024);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, st, a);
+}
+
+// bf16 forward / stride-1 backward-data on the direct-to-LDS kernel: one preparation launch (padded channel-blocked
+// activations + swizzled filters), then the contraction
+int run_colgemm_dma(int op, const void *act, const void *w, void *out, const Problem &pb, const Plan &pl, void *ws,
+                    hipStream_t st, const Epilogue *ep, bool *ep_applied)
+{
+    char *wsb = static_cast<char *>(ws);
+    const bool fwd = op == kOpFwd;
+    const int Cr = fwd ? pb.C : pb.K, RS = pb.R * pb.S, kc = pl.dma_kc;
+    const int LH = fwd ? pb.H : pb.P, LW = fwd ? pb.W : pb.Q;
+    DmaPrepArgs q;
+    q.src = static_cast<const unsigned short *>(act);
+    q.xb = reinterpret_cast<u32x4 *>(wsb + pl.xb_off);
+    q.N = pb.N; q.CB = Cr / 16; q.LH = LH; q.LW = LW; q.Hp = pl.dma_hp; q.Wp = pl.dma_wp;
+    q.pad_h = pl.dma_ph; q.pad_w = pl.dma_pw;
+    q.src_bs = fwd ? pb.x_bs : pb.y_bs;
+    const int64_t positions = (int64_t)pb.N * q.CB * q.Hp * q.Wp;
+    q.xb_blocks = grid1d(positions, 256);
+    q.w = static_cast<const unsigned short *>(w);
+    q.wt = reinterpret_cast<unsigned short *>(wsb + pl.wt_off);
+    q.M = pl.M; q.Mpad = pl.Mpad; q.cblocks = Cr / kc; q.RS = RS; q.C = pb.C; q.transposed = fwd ? 0 : 1; q.kc = kc;
+    q.div_wp = make_fastdiv((uint32_t)q.Wp);
+    q.div_hp = make_fastdiv((uint32_t)q.Hp);
+    q.div_cb = make_fastdiv((uint32_t)q.CB);
+    const int64_t wt_elems = (int64_t)pl.Mpad * Cr * RS;
+    hipLaunchKernelGGL(bf16_dma_prepare, dim3(q.xb_blocks + grid1d(wt_elems / 8, 256)), dim3(256), 0, st, q);
+    int rc = check_launch();
+    if (rc != kStatusOk) return rc;
+
+    ColGemmDmaArgs a;
+    a.At = q.wt; a.xb = q.xb; a.dst = out; a.part = nullptr;
+    a.M = pl.M; a.Mpad = pl.Mpad;
+    a.OH = fwd ? pb.P : pb.H; a.OW = fwd ? pb.Q : pb.W; a.mul = fwd ? pb.stride : 1;
+    a.ncols = pb.N * a.OH * a.OW;
+    a.Wp = q.Wp; a.cb_bytes = q.Hp * q.Wp * 32; a.n_bytes = q.CB * a.cb_bytes;
+    a.R = pb.R; a.S = pb.S; a.sign = fwd ? 1 : -1;
+    a.cblocks = Cr / kc;
+    a.dst_bs = (int)(fwd ? pb.y_bs : pb.x_bs); a.out_bf16 = pb.out_bf16;
+    a.mtiles = pl.Mpad / pl.tile.bm();
+    a.ntiles = ceil_div(a.ncols, pl.tile.bn());
+    a.ksplit = 1; a.steps_per_split = a.cblocks * RS;
+    a.epi_on = ep != nullptr;
+    a.epi = ep ? *ep : Epilogue{};
+    *ep_applied = a.epi_on;
+    a.div_plane = make_fastdiv((uint32_t)(a.OH * a.OW));
+    a.div_ow = make_fastdiv((uint32_t)a.OW);
+    a.div_rs = make_fastdiv((uint32_t)RS);
+    a.div_s = make_fastdiv((uint32_t)pb.S);
+    a.tiles_per_xcd = ceil_div(a.mtiles * a.ntiles, 8);
+    const int grid = 8 * a.tiles_per_xcd;
+    const int lds = 3 * (pl.tile.bm() + pl.tile.bn()) * kc * 2;
+    const int tn = pl.tile.TN;
+    if (tn == 4 && kc == 64) launch_dma(colgemm_bf16_dma_kernel<2, 4, 2, 2, 64, 1>, a, grid, lds, st);
+    else if (tn == 4) launch_dma(colgemm_bf16_dma_kernel<2, 4, 2, 2, 32, 2>, a, grid, lds, st);
+    else if (tn == 3 && kc == 64) launch_dma(colgemm_bf16_dma_kernel<2, 3, 2, 2, 64, 1>, a, grid, lds, st);
+    else if (tn == 3) launch_dma(colgemm_bf16_dma_kernel<2, 3, 2, 2, 32, 2>, a, grid, lds, st);
+    else if (kc == 64) launch_dma(colgemm_bf16_dma_kernel<2, 2, 2, 2, 64, 1>, a, grid, lds, st);
+    else launch_dma(colgemm_bf16_dma_kernel<2, 2, 2, 2, 32, 2>, a, grid, lds, st);
+    return check_launch();
+}
+
 template <typename TI>
 void launch_wgrad_typed(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
 {
@@ -213,8 +285,6 @@ void launch_wgrad_fast(const TileShape &t, const WgradFastArgs &a, const GridPla
     else if (t.TM == 2) hipLaunchKernelGGL((wgrad_fast_kernel<2, 1, 1, 4>), grid, block, g.dyn_lds, st, a);
     else hipLaunchKernelGGL((wgrad_fast_kernel<1, 2, 1, 4>), grid, block, g.dyn_lds, st, a);
 }
-
-int grid1d(int64_t n, int block) { return (int)((n + block - 1) / block); }
 
 // Common front end of the three passes: checks, plan, workspace carving.
 int prepare(int op, const void *a, const void *b, void *out, int N, int C, int H, int W, int K, int R, int S,
@@ -312,6 +382,7 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
     const bool fast = Cr % kChunk == 0 && (fwd || pb.stride == 1);
     const bool bf = pb.dtype == kDtypeBf16 && !pl.widen_w;   // bf16 MFMA kernel reads the caller's tensors directly
     int64_t w_bs = (int64_t)pb.K * pb.C * RS;
+    if (pl.dma) return run_colgemm_dma(op, act, w, out, pb, pl, ws, st, ep, ep_applied);
     const float *actf = fwd ? as_f32(pl.widen, act, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st)
                             : as_f32(pl.widen, act, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 0, st);
     const float *wf = as_f32(pl.widen_w, w, 1, w_bs, &w_bs, wsb, pl, 1, st);

@@ -57,6 +57,7 @@ constexpr TileShape kTile96x128 = {3, 1, 1, 4, 32};
 constexpr TileShape kTile64x128 = {2, 1, 1, 4, 32};
 constexpr TileShape kTile32x256 = {1, 2, 1, 4, 32};
 constexpr TileShape kTile48x256 = {3, 4, 1, 4, 16};   // fp32 forward / backward-data fast path only
+constexpr TileShape kTile128x256 = {2, 4, 2, 2, 32};  // bf16 direct-to-LDS kernel only
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline int64_t round_up64(int64_t v, int64_t m) { return (v + m - 1) / m * m; }
@@ -148,8 +149,35 @@ struct Plan {
     // columns of a grouped layer run in ONE launch (fp32 kernels of the fast paths): the filter and partial-sum
     // regions then hold `groups` consecutive copies; otherwise the host runs the columns one after the other
     bool fused_groups;
+    // bf16 forward / stride-1 backward-data on the direct-to-LDS kernel: channel-blocked, zero-padded copy of the
+    // gathered tensor (dma_hp x dma_wp positions per plane, dma_ph rows / dma_pw columns of zeros before the data),
+    // dma_kc channels per step, dma_occ work-groups per CU
+    bool dma;
+    int dma_kc, dma_occ, dma_hp, dma_wp, dma_ph, dma_pw;
+    size_t xb_off, xb_bytes;
     size_t total;
 };
+
+constexpr TileShape kTile128x192 = {2, 3, 2, 2, 32};  // bf16 direct-to-LDS kernel only
+
+// Tile width, step depth and work-groups per CU of the direct-to-LDS bf16 kernel (128 rows per tile).  Width: the
+// one that needs the least time on 256 CUs, rounds of tiles x columns per tile (a wider tile moves less through the
+// memory path per matrix instruction, so ties go to it).  One round: 64-channel steps, one work-group per CU (three
+// LDS buffers of up to 48 KB).  More rounds: 32-channel steps so that two work-groups share a CU and hide each
+// other's barriers and epilogues.
+inline void pick_dma_tile(int channels, int mtiles, int64_t ncols, TileShape &tile, int &kc, int &occ)
+{
+    const TileShape cand[3] = {kTile128x256, kTile128x192, kTile128x128};
+    int64_t best = -1, best_rounds = 1;
+    for (int i = 0; i < 3; ++i) {
+        const int64_t tiles = mtiles * ((ncols + cand[i].bn() - 1) / cand[i].bn());
+        const int64_t rounds = (tiles + 255) / 256;
+        const int64_t cost = rounds * cand[i].bn();
+        if (best < 0 || cost < best) { best = cost; tile = cand[i]; best_rounds = rounds; }
+    }
+    if (best_rounds > 1 || channels % 64 != 0) { kc = 32; occ = 2; }
+    else { kc = 64; occ = 1; }
+}
 
 inline Plan make_plan(int op, const Problem &pb)
 {
@@ -162,6 +190,25 @@ inline Plan make_plan(int op, const Problem &pb)
     else { pl.M = pb.K; pl.Kg = pb.C * RS; }
     pl.tile = pick_tile(pl.M);
     {
+        // bf16 inputs, at least 97 GEMM rows, gathered channel count a multiple of 32: the direct-to-LDS kernel
+        const bool fwd = op == kOpFwd;
+        const int Cg = fwd ? pb.C : pb.K;
+        if (pb.dtype == kDtypeBf16 && G == 1 && (fwd || (op == kOpBwdData && pb.stride == 1)) && Cg % 32 == 0 &&
+            pl.M > 96) {
+            const int OH = fwd ? pb.P : pb.H, OW = fwd ? pb.Q : pb.W, mul = fwd ? pb.stride : 1;
+            const int ph = fwd ? pb.pad : pb.R - 1 - pb.pad, pw = fwd ? pb.pad : pb.S - 1 - pb.pad;
+            const int64_t hp = (int64_t)(OH - 1) * mul + pb.R, wp = (int64_t)(OW - 1) * mul + pb.S;
+            const int64_t bytes = (int64_t)pb.N * (Cg / 16) * hp * wp * 32;
+            if (ph >= 0 && pw >= 0 && bytes < kMaxSpanBytes) {
+                pl.dma = true;
+                pl.dma_hp = (int)hp; pl.dma_wp = (int)wp; pl.dma_ph = ph; pl.dma_pw = pw;
+                const int64_t ncols = (int64_t)pb.N * OH * OW;
+                pick_dma_tile(Cg, ceil_div(pl.M, 128), ncols, pl.tile, pl.dma_kc, pl.dma_occ);
+                pl.xb_bytes = (size_t)bytes;
+            }
+        }
+    }
+    if (!pl.dma) {
         // 33..48 rows on the fp32 fast path: 16 x 16 matrix blocks instead of padding to 64 rows
         const int Cg = op == kOpFwd ? pb.C : pb.K;
         if (pb.dtype == kDtypeF32 && pl.M > 32 && pl.M <= 48 && Cg % kChunk == 0 &&
@@ -223,7 +270,7 @@ inline Plan make_plan(int op, const Problem &pb)
         // as its fullest CU; the partial outputs cost one extra pass over memory per range.
         const int Cr = op == kOpFwd ? pb.C : pb.K;
         const int OH = op == kOpFwd ? pb.P : pb.H, OW = op == kOpFwd ? pb.Q : pb.W;
-        if (Cr % kChunk == 0 && (op == kOpFwd || pb.stride == 1)) {
+        if (Cr % kChunk == 0 && (op == kOpFwd || pb.stride == 1) && !pl.dma) {
             const int64_t ncols = (int64_t)pb.N * OH * OW;
             const int tiles = (pl.Mpad / pl.tile.bm()) * (int)((ncols + pl.tile.bn() - 1) / pl.tile.bn()) * GF;
             const double out_mb = (double)ncols * pl.M * 4.0 * GF / 1e6;
@@ -281,7 +328,10 @@ inline Plan make_plan(int op, const Problem &pb)
     const bool direct = pl.patch || (op == kOpBwdFilter && pb.C % kChunk != 0);   // kernels that read bf16 themselves
     pl.widen = bf16_in && !bf16_kernel && !direct;
     pl.widen_w = bf16_in && !bf16_kernel && op != kOpBwdFilter;
-    if (pb.dtype == kDtypeBf16 && bf16_kernel && op != kOpBwdFilter) {
+    if (pl.dma) {
+        pl.xb_off = off;
+        off += round_up64(pl.xb_bytes, 256);
+    } else if (pb.dtype == kDtypeBf16 && bf16_kernel && op != kOpBwdFilter) {
         pl.blk_off = off;
         pl.blk_bytes = (size_t)pb.N * Cr * (op == kOpFwd ? pb.H * pb.W : pb.P * pb.Q) * 2;
         off += round_up64(pl.blk_bytes, 256);
