@@ -53,7 +53,8 @@ def mfma_ceiling():
         raise RuntimeError("mfma_ceiling failed: %s" % res.stderr.strip())
     out = {}
     for line in res.stdout.splitlines():
-        m = re.match(r"(burst|sustained)\s.*TFLOP/s=([0-9.]+)", line)
+        m = re.match(r"(burst|sustained|bf16_sustained_random_operands|bf16_sustained_constant_operands)\s.*"
+                     r"TFLOP/s=([0-9.]+)", line)
         if m:
             out[m.group(1)] = float(m.group(2))
     if "sustained" not in out:
@@ -125,8 +126,11 @@ def tiny_oracle_seconds():
 
 
 class Timer:
-    """Median and minimum over TIMED_LAUNCHES event-timed launches after WARMUP_LAUNCHES untimed ones, on torch's
-    current stream (the stream the binding launches on)."""
+    """Per-launch time of `fn`: WARMUP_LAUNCHES untimed launches, then TIMED_LAUNCHES samples; a sample is GROUP
+    launches back to back between one pair of HIP events on torch's current stream (the stream the binding launches
+    on), divided by GROUP -- an event pair costs several microseconds of idle GPU, which single-launch samples would
+    add to calls of 50-100 us.  Reports the median and the minimum of the samples."""
+    GROUP = 4
 
     def __init__(self, torch):
         self.torch = torch
@@ -138,10 +142,11 @@ class Timer:
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for s, e in ev:
             s.record()
-            fn()
+            for _ in range(self.GROUP):
+                fn()
             e.record()
         torch.cuda.synchronize()
-        ms = sorted(s.elapsed_time(e) for s, e in ev)
+        ms = sorted(s.elapsed_time(e) / self.GROUP for s, e in ev)
         return {"ms": round(ms[len(ms) // 2], 4), "ms_min": round(ms[0], 4)}
 
 
@@ -450,8 +455,9 @@ def main():
         "conv_only_frac_peak": round(flops / conv_ms / 1e9 / PEAK_FP32_MFMA_TFLOPS, 4),
         "timing_protocol": "value: wall clock over `steps` steps after `warmup`; per-pass / per_config figures: HIP "
                            "events on the launch stream, %d warm-up launches, then median (ms) and minimum (ms_min) "
-                           "of %d launches; helper launches of a call (filter re-layout, split sums) are inside its "
-                           "time" % (WARMUP_LAUNCHES, TIMED_LAUNCHES),
+                           "of %d samples of %d back-to-back launches each (per_pass: one launch per sample, inside "
+                           "the running step); helper launches of a call (operand preparation, split sums) are "
+                           "inside its time" % (WARMUP_LAUNCHES, TIMED_LAUNCHES, Timer.GROUP),
         "per_pass": per_pass,
         "roofline": roofline,
         "per_config": per_config,

@@ -330,3 +330,200 @@ __global__ __launch_bounds__(256) void bf16_dma_prepare(const DmaPrepArgs p)
     const int pos = c ^ ((m >> sh) & (chunks - 1));
     reinterpret_cast<u32x4 *>(p.wt)[(i - c) + pos] = o;
 }
+
+// ---------------------------------------------------------------------------
+// Forward pass of a few-channel layer with bf16 inputs (the 11x11 stride-4 first layer) on
+// v_mfma_f32_32x32x16_bf16.  The reduction runs over (c, r) with the filter columns s inside, padded to 16: one
+// matrix instruction covers one filter ROW of one channel, and the eight consecutive s a lane feeds are eight
+// consecutive bf16 of a staged input row -- two aligned 8-byte LDS reads, no per-element gathers (the padding
+// s = S .. 15 multiplies real neighbouring pixels by zero filter entries).  45 % of the matrix work is that
+// padding, at a sixteenth of the fp32 instruction cost per product.
+//
+// Work-groups are persistent: the whole filter bank (C*R slices of [Mpad][16] bf16, 99 KB for 96 filters of
+// 3 x 11 x 11) stays in LDS, so the loop over a tile's slices has no barrier; a work-group walks over tiles of
+// 128 output positions of one image, staging each tile's input rows (zero padding in place) as in
+// colgemm_patch_kernel.  The global loads of the next tile's rows are issued before the current tile is
+// multiplied and written to LDS after it.
+// Needs: S <= 16, stride % 4 == 0, pad even, W % 8 == 0, batch stride % 8 == 0 (16-byte row loads, 8-byte aligned
+// fragment reads).
+// ---------------------------------------------------------------------------
+struct PatchBf16Args {
+    const void *Ft;       // filters [slice = c*R + r][Mpad][16 s] bf16, 8-element halves swapped where (row >> 3) & 1
+    const unsigned short *x;
+    void *y;              // fp32 or bfloat16 (the kernel's TO)
+    int M, Mpad, nslices;
+    int C, H, W, R, stride, pad;
+    int P, Q, PQ;
+    int NR, WP;           // staged rows per channel, LDS row pitch in elements (multiple of 4)
+    int x_bs, y_bs;
+    int jtiles, ntiles;   // position tiles per image, tiles in all
+    int epi_on;
+    Epilogue epi;
+    FastDiv div_q, div_j, div_nr, div_wv;
+};
+
+template <int TM, typename TO>
+__global__ __launch_bounds__(kThreads, 1) void conv_patch_bf16_kernel(const PatchBf16Args p)
+{
+    constexpr int NV = 8;                        // 16-byte row pieces per thread and tile (host checks the bound)
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    char *const fl = reinterpret_cast<char *>(lds_fast);                  // filters: nslices * Mpad * 32 bytes
+    const int fbytes = p.nslices * p.Mpad * 32;
+    unsigned short *const patch = reinterpret_cast<unsigned short *>(fl + fbytes);   // C * NR * WP elements
+    const unsigned lds_base = (unsigned)(size_t)lds_fast;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+
+    // filters: linear copy into LDS, 1 KB per wavefront load
+    for (int off = wave * 1024; off < fbytes; off += 4 * 1024)
+        if (off + lane * 16 < fbytes) dma16(p.Ft, (unsigned)(off + lane * 16), lds_base + off);
+    // patch: zero once (the padding columns stay zero for every tile)
+    const int pwords = p.C * p.NR * p.WP / 2;
+    for (int i = tid; i < pwords; i += kThreads) reinterpret_cast<unsigned *>(patch)[i] = 0u;
+
+    const int wv = p.W / 8;                      // 16-byte pieces per input row
+    const int pieces = p.C * p.NR * wv;
+    u32x4 stage[NV];
+    // global loads of a tile's rows into registers (zeros for rows outside the image)
+    auto load_tile = [&](int tile) {
+        const int n = (int)fastdiv((uint32_t)tile, p.div_j);
+        const int jt = tile - n * p.jtiles;
+        const int p0 = (int)fastdiv((uint32_t)(jt * 128), p.div_q);
+        const int h0 = p0 * p.stride - p.pad;
+        const unsigned short *xn = p.x + (size_t)n * p.x_bs;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int e = tid + u * kThreads;
+            const int ee = e < pieces ? e : 0;
+            const int row = (int)fastdiv((uint32_t)ee, p.div_wv);        // c * NR + i
+            const int v = ee - row * wv;
+            const int c = (int)fastdiv((uint32_t)row, p.div_nr);
+            const int h = h0 + row - c * p.NR;
+            const bool ok = (e < pieces) & ((unsigned)h < (unsigned)p.H);
+            const u32x4 val = *reinterpret_cast<const u32x4 *>(xn + (size_t)(ok ? (c * p.H + h) * p.W + v * 8 : 0));
+            stage[u] = ok ? val : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+    // ... and from the registers into the patch: piece v of row lands at element row*WP + pad + 8v (4-byte aligned)
+    auto store_tile = [&]() {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int e = tid + u * kThreads;
+            if (e < pieces) {
+                const int row = (int)fastdiv((uint32_t)e, p.div_wv);
+                const int v = e - row * wv;
+                unsigned *dst = reinterpret_cast<unsigned *>(patch + row * p.WP + p.pad + v * 8);
+                dst[0] = stage[u][0]; dst[1] = stage[u][1]; dst[2] = stage[u][2]; dst[3] = stage[u][3];
+            }
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < p.ntiles) load_tile(tile);
+    wait_vmcnt<0>();                             // the filter copy (and the first tile's rows) have landed
+    __syncthreads();                             // zero fill done before the rows are written over it
+
+    const int a_off = l32 * 32 + ((half ^ ((l32 >> 3) & 1)) * 16);        // this lane's 16 bytes of a 32-row block
+    for (; tile < p.ntiles; tile += gridDim.x) {
+        store_tile();
+        __syncthreads();
+        const int next = tile + gridDim.x;
+        if (next < p.ntiles) load_tile(next);
+
+        const int n = (int)fastdiv((uint32_t)tile, p.div_j);
+        const int jt = tile - n * p.jtiles;
+        const int j0 = jt * 128;
+        const int p0 = (int)fastdiv((uint32_t)j0, p.div_q);
+        const int j = j0 + wave * 32 + l32;
+        const bool jok = j < p.PQ;
+        int colbase;                             // element offset of this lane's position inside a channel's rows
+        {
+            const int jj = jok ? j : j0;
+            const int pp = (int)fastdiv((uint32_t)jj, p.div_q);
+            const int qq = jj - pp * p.Q;
+            colbase = (pp - p0) * p.stride * p.WP + qq * p.stride + 8 * half;
+        }
+        f32x16 acc[TM];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+        // slices: the fragments of slice sl + 1 are read while slice sl is multiplied
+        u32x4 fa[2][TM];
+        typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+        u32x2 fb[2][2];
+        auto read_slice = [&](int sl, int c, int r, int set) {
+            const char *a = fl + sl * p.Mpad * 32 + a_off;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[set][i] = *reinterpret_cast<const u32x4 *>(a + i * 1024);
+            const unsigned short *b = patch + (c * p.NR + r) * p.WP + colbase;
+            fb[set][0] = *reinterpret_cast<const u32x2 *>(b);
+            fb[set][1] = *reinterpret_cast<const u32x2 *>(b + 4);
+        };
+        int c = 0, r = 0;
+        read_slice(0, 0, 0, 0);
+        for (int sl = 0; sl < p.nslices; sl += 2) {
+#pragma unroll
+            for (int par = 0; par < 2; ++par) {
+                if (sl + par < p.nslices) {
+                    r += 1;
+                    if (r == p.R) { r = 0; c += 1; }
+                    if (sl + par + 1 < p.nslices) read_slice(sl + par + 1, c, r, par ^ 1);
+                    const u32x4 bq = {fb[par][0][0], fb[par][0][1], fb[par][1][0], fb[par][1][1]};
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[par][i]),
+                                                                         __builtin_bit_cast(bf16x8, bq), acc[i], 0, 0, 0);
+                }
+            }
+        }
+
+        if (jok) {
+            TO *out = static_cast<TO *>(p.y) + (size_t)n * p.y_bs + j;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int row0 = i * 32 + half * 4;
+                if (p.epi_on) {                                      // forward only: bias and ReLU, no mask
+                    float bv16[16];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        bv16[v] = p.epi.bias ? p.epi.bias[min(row0 + (v >> 2) * 8 + (v & 3), p.M - 1)] : 0.f;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float t = acc[i][v] + bv16[v];
+                        acc[i][v] = (p.epi.relu && !(t > 0.f)) ? 0.f : t;
+                    }
+                }
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + (v >> 2) * 8 + (v & 3);
+                    if (row < p.M) st_elem(out, (int64_t)row * p.PQ, acc[i][v]);
+                }
+            }
+        }
+        wait_vmcnt<0>();                         // next tile's rows are in the registers
+        __syncthreads();                         // every wave is done reading this tile's patch
+    }
+}
+
+// Filters for conv_patch_bf16_kernel: Ft[c*R + r][Mpad][16] bf16 from w[k][c][r][s]; zeros for s >= S and rows >= M;
+// the two 8-element halves of a row swapped where (row >> 3) & 1 (bank spread of the fragment reads)
+__global__ void relayout_filters_rows_bf16(const unsigned short *__restrict__ w, unsigned short *__restrict__ ft,
+                                           int M, int Mpad, int C, int R, int S)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t total = (int64_t)C * R * Mpad * 16;
+    if (i >= total) return;
+    const int s = (int)(i & 15);
+    int64_t t = i >> 4;
+    const int m = (int)(t % Mpad);
+    const int sl = (int)(t / Mpad);
+    const int c = sl / R, r = sl - c * R;
+    unsigned short v = 0;
+    if (m < M && s < S) v = w[(((int64_t)m * C + c) * R + r) * S + s];
+    const int pos = (s >> 3) ^ ((m >> 3) & 1);
+    ft[(i - s) + pos * 8 + (s & 7)] = v;
+}

@@ -234,6 +234,57 @@ int run_colgemm_dma(int op, const void *act, const void *w, void *out, const Pro
     return check_launch();
 }
 
+constexpr int kNotTaken = 1;          // a specialised path declined the shape: the caller goes on to the general one
+
+// Few-channel forward with bf16 inputs on the bf16 matrix instruction (conv_patch_bf16_kernel); kNotTaken where its
+// alignment or size conditions do not hold.
+int run_patch_bf16(const void *x, const void *w, void *out, const Problem &pb, const Plan &pl, void *ws,
+                   hipStream_t st, const Epilogue *ep, bool *ep_applied)
+{
+    const int tm = pl.patch_tm, mpad = tm * 32;
+    if (pb.S > 16 || pb.stride % 4 != 0 || pb.pad % 2 != 0 || pb.W % 8 != 0 || pb.x_bs % 8 != 0 || pl.M > mpad)
+        return kNotTaken;
+    const int need_w = std::max(pb.pad + pb.W, (pb.Q - 1) * pb.stride + 16);
+    const int wp = round_up(need_w, 4);
+    const int nslices = pb.C * pb.R;
+    const int64_t fbytes = (int64_t)nslices * mpad * 32;
+    const int64_t lds = fbytes + (int64_t)pb.C * pl.patch_nr * wp * 2;
+    const int64_t pieces = (int64_t)pb.C * pl.patch_nr * (pb.W / 8);
+    if (lds > 159 * 1024 || pieces > 8 * kThreads || fbytes > (int64_t)pl.wt_bytes) return kNotTaken;
+    char *wsb = static_cast<char *>(ws);
+    unsigned short *ft = reinterpret_cast<unsigned short *>(wsb + pl.wt_off);
+    hipLaunchKernelGGL(relayout_filters_rows_bf16, dim3(grid1d(fbytes / 2, 256)), dim3(256), 0, st,
+                       static_cast<const unsigned short *>(w), ft, pl.M, mpad, pb.C, pb.R, pb.S);
+    PatchBf16Args a;
+    a.Ft = ft; a.x = static_cast<const unsigned short *>(x); a.y = out;
+    a.M = pl.M; a.Mpad = mpad; a.nslices = nslices;
+    a.C = pb.C; a.H = pb.H; a.W = pb.W; a.R = pb.R; a.stride = pb.stride; a.pad = pb.pad;
+    a.P = pb.P; a.Q = pb.Q; a.PQ = pb.P * pb.Q; a.NR = pl.patch_nr; a.WP = wp;
+    a.x_bs = (int)pb.x_bs; a.y_bs = (int)pb.y_bs;
+    a.jtiles = ceil_div(a.PQ, 128); a.ntiles = pb.N * a.jtiles;
+    a.epi_on = ep != nullptr;
+    a.epi = ep ? *ep : Epilogue{};
+    *ep_applied = a.epi_on;
+    a.div_q = make_fastdiv((uint32_t)pb.Q);
+    a.div_j = make_fastdiv((uint32_t)a.jtiles);
+    a.div_nr = make_fastdiv((uint32_t)pl.patch_nr);
+    a.div_wv = make_fastdiv((uint32_t)(pb.W / 8));
+    const int grid = std::min(a.ntiles, 256);
+    const void *k = nullptr;
+    if (pb.out_bf16) {
+        k = tm == 1 ? (const void *)conv_patch_bf16_kernel<1, unsigned short> : tm == 2 ? (const void *)conv_patch_bf16_kernel<2, unsigned short>
+          : tm == 3 ? (const void *)conv_patch_bf16_kernel<3, unsigned short> : (const void *)conv_patch_bf16_kernel<4, unsigned short>;
+    } else {
+        k = tm == 1 ? (const void *)conv_patch_bf16_kernel<1, float> : tm == 2 ? (const void *)conv_patch_bf16_kernel<2, float>
+          : tm == 3 ? (const void *)conv_patch_bf16_kernel<3, float> : (const void *)conv_patch_bf16_kernel<4, float>;
+    }
+    (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    void *args[] = {&a};
+    hipError_t e = hipLaunchKernel(k, dim3(grid), dim3(kThreads), args, (size_t)lds, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return check_launch();
+}
+
 template <typename TI>
 void launch_wgrad_typed(const TileShape &t, const WgradArgs &a, int grid, hipStream_t st)
 {
@@ -383,6 +434,10 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
     const bool bf = pb.dtype == kDtypeBf16 && !pl.widen_w;   // bf16 MFMA kernel reads the caller's tensors directly
     int64_t w_bs = (int64_t)pb.K * pb.C * RS;
     if (pl.dma) return run_colgemm_dma(op, act, w, out, pb, pl, ws, st, ep, ep_applied);
+    if (pl.patch && pb.dtype == kDtypeBf16) {
+        const int rc = run_patch_bf16(act, w, out, pb, pl, ws, st, ep, ep_applied);
+        if (rc != kNotTaken) return rc;
+    }
     const float *actf = fwd ? as_f32(pl.widen, act, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st)
                             : as_f32(pl.widen, act, pb.N, (int64_t)pb.K * pb.P * pb.Q, &pb.y_bs, wsb, pl, 0, st);
     const float *wf = as_f32(pl.widen_w, w, 1, w_bs, &w_bs, wsb, pl, 1, st);

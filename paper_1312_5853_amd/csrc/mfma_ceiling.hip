@@ -1,6 +1,9 @@
-// Register-resident fp32 MFMA loop: what the matrix cores of this GPU sustain
-// with no memory traffic at all.  Used as a second denominator next to the
-// published peak.  Prints one line per case: work-groups, ms, TFLOP/s.
+// Register-resident MFMA loops: what the matrix cores of this GPU sustain with
+// no memory traffic at all, fp32 (v_mfma_f32_32x32x2_f32) and bf16
+// (v_mfma_f32_32x32x16_bf16; with operands that never change, and with eight
+// sets of pseudo-random operands cycled, which is what real data costs in
+// power and therefore in clock).  bench.py reports them as second denominators
+// next to the published peaks.  Prints one line per case.
 #include <hip/hip_runtime.h>
 
 #include <stdio.h>
@@ -18,6 +21,40 @@ __global__ __launch_bounds__(256) void mfma_loop(float *out, int iters, float a,
         for (int u = 0; u < 8; ++u)
 #pragma unroll
             for (int i = 0; i < 4; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ unsigned mix(unsigned x) { x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16; return x; }
+// a pair of bf16 values with magnitudes in [1, 2) and random signs and fractions (sums stay finite)
+__device__ unsigned bf16_pair(unsigned s) { return 0x3F803F80u | (mix(s) & 0x807F807Fu); }
+
+template <bool RANDOM>
+__global__ __launch_bounds__(256) void mfma_bf16_loop(float *out, int iters)
+{
+    f32x16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    u32x4 a[8], b[8];
+    for (int s = 0; s < 8; ++s)
+        for (int k = 0; k < 4; ++k) {
+            a[s][k] = RANDOM ? bf16_pair(threadIdx.x * 131 + s * 17 + k) : 0x3F803F80u;
+            b[s][k] = RANDOM ? bf16_pair(threadIdx.x * 257 + s * 29 + k + 99) : 0x3F803F80u;
+        }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[(u + i) & 7]),
+                                                                 __builtin_bit_cast(bf16x8, b[(u * 3 + i) & 7]),
+                                                                 acc[i], 0, 0, 0);
     }
     float s = 0.f;
     for (int i = 0; i < 4; ++i)
@@ -52,6 +89,22 @@ int main()
     CHECK(hipEventSynchronize(e1));
     CHECK(hipEventElapsedTime(&ms, e0, e1));
     printf("sustained  wgs=%d launches=10 ms=%.3f TFLOP/s=%.1f\n", wgs, ms, 10.0 * flops / ms / 1e9);
+    // bf16: 512 work-groups (two waves per SIMD), 0.1 s each
+    const int bwgs = 512, biters = 10000;
+    const double bflops = (double)bwgs * 4 * biters * 32 * 32768.0;      // waves x iterations x MFMAs x 32*32*16*2
+    for (int rnd = 0; rnd < 2; ++rnd) {
+        if (rnd) hipLaunchKernelGGL(mfma_bf16_loop<true>, dim3(bwgs), dim3(256), 0, 0, d, 100);
+        else hipLaunchKernelGGL(mfma_bf16_loop<false>, dim3(bwgs), dim3(256), 0, 0, d, 100);
+        CHECK(hipDeviceSynchronize());
+        CHECK(hipEventRecord(e0));
+        if (rnd) hipLaunchKernelGGL(mfma_bf16_loop<true>, dim3(bwgs), dim3(256), 0, 0, d, biters);
+        else hipLaunchKernelGGL(mfma_bf16_loop<false>, dim3(bwgs), dim3(256), 0, 0, d, biters);
+        CHECK(hipEventRecord(e1));
+        CHECK(hipEventSynchronize(e1));
+        CHECK(hipEventElapsedTime(&ms, e0, e1));
+        printf("%s wgs=%d ms=%.3f TFLOP/s=%.1f\n", rnd ? "bf16_sustained_random_operands  " : "bf16_sustained_constant_operands",
+               bwgs, ms, bflops / ms / 1e9);
+    }
     CHECK(hipFree(d));
     return 0;
 }

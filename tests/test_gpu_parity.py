@@ -130,6 +130,13 @@ BF16_SHAPES = [
     (2, 32, 27, 27, 128, 5, 5, 1, 2),
     (9, 16, 12, 9, 96, 1, 1, 1, 0),
     (4, 16, 5, 5, 128, 3, 3, 1, 1),
+    # few channels, stride 4, row length a multiple of 8: the forward kernel on the bf16 matrix instruction
+    # (filter rows padded to 16 columns); 32-, 64- and 128-row filter tiles, a ragged second position tile,
+    # more tiles than persistent work-groups
+    (2, 3, 24, 32, 40, 11, 11, 4, 2),
+    (2, 2, 16, 16, 20, 5, 7, 4, 2),
+    (1, 3, 64, 64, 100, 11, 11, 4, 2),
+    (70, 1, 56, 40, 33, 8, 16, 4, 0),
 ]
 
 
@@ -621,6 +628,7 @@ EPILOGUE_SHAPES = [
     (4, 64, 13, 13, 96, 3, 3, 1, 1),       # few tiles: reduction split, epilogue in the split-sum kernel
     (7, 48, 14, 14, 64, 5, 5, 1, 2),       # backward-data in the 48-row kernel: epilogue as a pass of its own
     (3, 3, 23, 25, 48, 11, 11, 4, 2),      # few-channel forward (patch kernel), strided backward-data (tap table)
+    (2, 3, 24, 32, 48, 11, 11, 4, 2),      # the same with rows of 32: the bf16 few-channel kernel applies bias / ReLU itself
     (2, 5, 8, 10, 130, 3, 3, 1, 5),        # tap-table kernels both ways
 ]
 
