@@ -57,6 +57,9 @@ def mfma_ceiling():
                      r"TFLOP/s=([0-9.]+)", line)
         if m:
             out[m.group(1)] = float(m.group(2))
+        m = re.match(r"rate_(\S+)\s+bytes_per_clk_per_cu=([0-9.]+)", line)
+        if m:
+            out.setdefault("bytes_per_clk_per_cu", {})[m.group(1)] = float(m.group(2))
     if "sustained" not in out:
         raise RuntimeError("mfma_ceiling printed no figure: %r" % res.stdout)
     return out
