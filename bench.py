@@ -274,6 +274,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=128)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stack-dtype", choices=("f32", "bf16"), default="f32",
+                    help="with --stack-only: element type of the profiled step (bf16 = bf16 tensors end to end); the "
+                         "default run always reports the fp32 step as `value`")
     ap.add_argument("--stack-only", action="store_true",
                     help="only the fp32 stack step (no per-config, two-column, bf16 or CPU blocks): the run the "
                          "profiles are taken on")
@@ -317,7 +320,9 @@ def main():
     timer = Timer(torch)
 
     N = args.batch
-    stack = ConvStack(N)
+    if args.stack_dtype != "f32" and not args.stack_only:
+        sys.exit("bench.py: --stack-dtype is a profiling option of --stack-only")
+    stack = ConvStack(N, dtype=args.stack_dtype)
     flops = stack_flops(N)
 
     for _ in range(args.warmup):
@@ -370,25 +375,32 @@ def main():
         med[(layer, p)] = vals[len(vals) // 2]
         conv_ms += med[(layer, p)]
         per_pass["%s.%s" % (layer, p)] = with_rates({"ms": round(med[(layer, p)], 4), "ms_min": round(vals[0], 4)},
-                                                    pass_flops(layer), PEAK_FP32_MFMA_TFLOPS)
+                                                    pass_flops(layer),
+                                                    PEAK_BF16_MFMA_TFLOPS if args.stack_dtype == "bf16"
+                                                    else PEAK_FP32_MFMA_TFLOPS)
 
-    # dominant kernel: the 128x128-tile implicit-GEMM kernel that runs forward of conv2 (both columns in one
-    # launch), conv3, conv4, conv5 and backward-data of conv3, conv4, conv5 (7 launches per step)
+    # dominant kernel.  fp32: the 128x128-tile implicit-GEMM kernel that runs forward of conv2 (both columns in one
+    # launch), conv3, conv4, conv5 and backward-data of conv3, conv4, conv5 (7 launches per step).  bf16 profiling
+    # run: the direct-to-LDS kernel (forward and backward-data of conv3, conv4, conv5; 6 launches per step).
+    bf16_run = args.stack_dtype == "bf16"
     dom_keys = [k for k in samples if k[1] in ("fwd", "dgrad") and k[0] != "conv1"]
-    dom_keys = [k for k in dom_keys if not (k[0] == "conv2" and k[1] == "dgrad")]
+    dom_keys = [k for k in dom_keys if not (k[0] == "conv2" and (k[1] == "dgrad" or bf16_run))]
     dom_flops = sum(pass_flops(k[0]) for k in dom_keys)
     dom_ms = sum(sum(samples[k]) for k in dom_keys) / reps          # mean launch duration over the timed region
     achieved = dom_flops / dom_ms / 1e9
+    peak = PEAK_BF16_MFMA_TFLOPS if bf16_run else PEAK_FP32_MFMA_TFLOPS
     roofline = {
-        "bound": "mfma", "kernel": "colgemm_fast_kernel<2,2,2,2,16> (fwd of conv2-5, dgrad of conv3-5)",
-        "achieved": round(achieved, 2), "peak": PEAK_FP32_MFMA_TFLOPS, "unit": "TFLOP/s",
-        "frac": round(achieved / PEAK_FP32_MFMA_TFLOPS, 4),
-        "traffic": traffic_from_profile(N),
+        "bound": "mfma",
+        "kernel": ("colgemm_bf16_dma_kernel (fwd and dgrad of conv3-5)" if bf16_run else
+                   "colgemm_fast_kernel<2,2,2,2,16> (fwd of conv2-5, dgrad of conv3-5)"),
+        "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+        "frac": round(achieved / peak, 4),
+        "traffic": None if bf16_run else traffic_from_profile(N),
         "traffic_source": "profiles/stack_n128_fp32_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)",
         "launches_per_step": len(dom_keys), "avg_launch_ms": round(dom_ms / len(dom_keys), 4),
         "flops_per_launch": dom_flops / len(dom_keys), "timed_launches_each": reps,
     }
-    if isinstance(ceiling, dict) and "sustained" in ceiling:
+    if isinstance(ceiling, dict) and "sustained" in ceiling and not bf16_run:
         roofline["frac_of_measured_mfma_ceiling"] = round(achieved / ceiling["sustained"], 4)
 
     def bf16_block():
@@ -443,13 +455,15 @@ def main():
 
     value = flops / ms_per_step / 1e9
     out = {
-        "metric": "conv-stack TFLOP/s at N=%d (conv1-5 fwd+dgrad+wgrad, fp32 MFMA, ReLU/pool glue in the step)" % N,
+        "metric": "conv-stack TFLOP/s at N=%d (conv1-5 fwd+dgrad+wgrad, %s, ReLU/pool glue in the step)"
+                  % (N, "fp32 MFMA" if args.stack_dtype == "f32" else "bf16 tensors, fp32 accumulation"),
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "5-conv AlexNet stack fwd+bwd, N=%d, fp32 (conv2 as two model-parallel columns)" % N,
+        "dtype": args.stack_dtype, "data": "synthetic",
+        "config": {"workload": "5-conv AlexNet stack fwd+bwd, N=%d, %s (conv2 as two model-parallel columns)"
+                               % (N, "fp32" if args.stack_dtype == "f32" else "bf16"),
                    "batch": N, "conv_gflop_per_step": round(flops / 1e9, 2)},
-        "frac_fp32_mfma_peak": round(value / PEAK_FP32_MFMA_TFLOPS, 4),
+        "frac_fp32_mfma_peak": round(value / PEAK_FP32_MFMA_TFLOPS, 4) if args.stack_dtype == "f32" else None,
         "mfma_ceiling_tflops": ceiling,
         "frac_of_measured_mfma_ceiling": (round(value / ceiling["sustained"], 4)
                                           if isinstance(ceiling, dict) and "sustained" in ceiling else None),

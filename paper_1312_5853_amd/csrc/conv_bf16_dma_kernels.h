@@ -53,21 +53,22 @@ template <int N>
 __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N)); }
 
 template <int TM, int TN, int WM, int WN, int KC, int OCC>
-__global__ __launch_bounds__(kThreads, OCC) void colgemm_bf16_dma_kernel(const ColGemmDmaArgs p)
+__global__ __launch_bounds__(WM * WN * 64, OCC) void colgemm_bf16_dma_kernel(const ColGemmDmaArgs p)
 {
+    constexpr int NT = WM * WN * 64;           // threads: four or eight waves
     constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
     constexpr int RB = KC * 2;                 // bytes per LDS row
     constexpr int CH = KC / 8;                 // 16-byte chunks per row
     constexpr int SH = KC == 64 ? 1 : 2;       // log2(256 / RB)
     constexpr int NK = KC / 16;                // matrix instructions per 32 x 32 block and step
-    constexpr int NA = BM * CH / kThreads;     // direct loads per thread and step: filters
-    constexpr int NB = BN * CH / kThreads;     // ... activations
+    constexpr int NA = BM * CH / NT;     // direct loads per thread and step: filters
+    constexpr int NB = BN * CH / NT;     // ... activations
     constexpr int NL = NA + NB;
     constexpr int BUF = (BM + BN) * RB;        // bytes per LDS buffer
-    static_assert(WM * WN == 4, "four waves per work-group");
+    static_assert(WM * WN == 4 || WM * WN == 8, "four or eight waves per work-group");
     static_assert(KC == 64 || KC == 32, "step depth");
     static_assert(NK % 2 == 0, "slice 0 of the next step lands in fragment set 0");
-    static_assert((BM * CH) % kThreads == 0 && (BN * CH) % kThreads == 0, "whole wavefront loads");
+    static_assert((BM * CH) % NT == 0 && (BN * CH) % NT == 0, "whole wavefront loads");
 
     extern __shared__ __attribute__((aligned(16))) float lds_fast[];
     const char *const lds = reinterpret_cast<const char *>(lds_fast);
@@ -270,6 +271,8 @@ struct DmaPrepArgs {
     int N, CB, LH, LW, Hp, Wp, pad_h, pad_w;   // pad_h / pad_w: zero rows above / zero columns left of the data
     int64_t src_bs;
     int xb_blocks;
+    int xb_planes;         // 1: block b < xb_blocks stages the 16 planes of (n, cb) = b in LDS (needs 16-byte aligned plane
+                           // groups and 32 * LH * LW bytes of dynamic LDS); 0: one thread per position, 2-byte gathers
     const unsigned short *w;
     unsigned short *wt;
     int M, Mpad, cblocks, RS, C, transposed, kc;
@@ -278,6 +281,38 @@ struct DmaPrepArgs {
 
 __global__ __launch_bounds__(256) void bf16_dma_prepare(const DmaPrepArgs p)
 {
+    if ((int)blockIdx.x < p.xb_blocks && p.xb_planes) {
+        // the 16 planes of one (sample, channel block) are one contiguous run of 32 * LH * LW bytes: copy it into LDS
+        // with 16-byte pieces, then every thread gathers the 16 channels of a padded position from LDS
+        extern __shared__ __attribute__((aligned(16))) unsigned short planes[];
+        const int LHW = p.LH * p.LW;
+        const uint32_t n = fastdiv((uint32_t)blockIdx.x, p.div_cb);
+        const int cb = (int)(blockIdx.x - n * (uint32_t)p.CB);
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(p.src + n * p.src_bs + (int64_t)cb * 16 * LHW);
+        for (int v = threadIdx.x; v < 2 * LHW; v += 256) reinterpret_cast<u32x4 *>(planes)[v] = src[v];
+        __syncthreads();
+        const int PP = p.Hp * p.Wp;
+        u32x4 *dst = p.xb + (int64_t)blockIdx.x * PP * 2;
+        for (int t = threadIdx.x; t < PP; t += 256) {
+            const int hp = (int)fastdiv((uint32_t)t, p.div_wp), wp = t - hp * p.Wp;
+            const int h = hp - p.pad_h, w = wp - p.pad_w;
+            u32x4 lo = {0u, 0u, 0u, 0u}, hi = {0u, 0u, 0u, 0u};
+            if ((unsigned)h < (unsigned)p.LH && (unsigned)w < (unsigned)p.LW) {
+                const unsigned short *s = planes + h * p.LW + w;
+                unsigned short v[16];
+#pragma unroll
+                for (int k = 0; k < 16; ++k) v[k] = s[k * LHW];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    lo[k] = (unsigned)v[2 * k] | ((unsigned)v[2 * k + 1] << 16);
+                    hi[k] = (unsigned)v[8 + 2 * k] | ((unsigned)v[8 + 2 * k + 1] << 16);
+                }
+            }
+            dst[2 * t] = lo;
+            dst[2 * t + 1] = hi;
+        }
+        return;
+    }
     if ((int)blockIdx.x < p.xb_blocks) {
         const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
         const int64_t total = (int64_t)p.N * p.CB * p.Hp * p.Wp;

@@ -867,11 +867,11 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const Wgrad
 // dyp[k][e], e < row_elems: image n = e / Jy, j = e % Jy = p*Wq + q; dy(n, k, p, q) where p < P and q < Q, else 0.
 // One thread per 8 consecutive elements (Jy and row_elems are multiples of 8, so they share k and n): eight
 // 2-byte loads along a row of dy, one 16-byte store.
-__global__ void pack_dy_lin(const unsigned short *__restrict__ dy, unsigned short *__restrict__ dyp, int N, int K,
-                            int P, int Q, int Wq, int Jy, int row_elems, int64_t dy_bs, FastDiv div_row,
-                            FastDiv div_jy, FastDiv div_wq)
+__device__ __forceinline__ void pack_dy_lin(int64_t i8, const unsigned short *__restrict__ dy,
+                                            unsigned short *__restrict__ dyp, int N, int K, int P, int Q, int Wq, int Jy,
+                                            int row_elems, int64_t dy_bs, FastDiv div_row, FastDiv div_jy,
+                                            FastDiv div_wq)
 {
-    const int64_t i8 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t i = i8 * 8;
     if (i >= (int64_t)K * row_elems) return;
     const uint32_t k = fastdiv((uint32_t)i, div_row), e = (uint32_t)i - k * (uint32_t)row_elems;
@@ -891,10 +891,10 @@ __global__ void pack_dy_lin(const unsigned short *__restrict__ dy, unsigned shor
 
 // xp[c][n][e], e < Jx: padded row hh = e / Wq, column ww = e % Wq; x(n, c, hh - pad, ww - pad) where inside, else 0.
 // One thread per 8 consecutive elements (Jx is a multiple of 8).
-__global__ void pack_x_lin(const unsigned short *__restrict__ x, unsigned short *__restrict__ xp, int N, int C, int H,
-                           int W, int pad, int Wq, int Jx, int64_t x_bs, FastDiv div_jx, FastDiv div_wq)
+__device__ __forceinline__ void pack_x_lin(int64_t i8, const unsigned short *__restrict__ x,
+                                           unsigned short *__restrict__ xp, int N, int C, int H, int W, int pad, int Wq,
+                                           int Jx, int64_t x_bs, FastDiv div_jx, FastDiv div_wq)
 {
-    const int64_t i8 = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t i = i8 * 8;
     if (i >= (int64_t)C * N * Jx) return;
     const uint32_t cn = fastdiv((uint32_t)i, div_jx), e = (uint32_t)i - cn * (uint32_t)Jx;
@@ -911,6 +911,25 @@ __global__ void pack_x_lin(const unsigned short *__restrict__ x, unsigned short 
     u32x4 o = {(uint32_t)v[0] | (uint32_t)v[1] << 16, (uint32_t)v[2] | (uint32_t)v[3] << 16,
                (uint32_t)v[4] | (uint32_t)v[5] << 16, (uint32_t)v[6] | (uint32_t)v[7] << 16};
     reinterpret_cast<u32x4 *>(xp)[i8] = o;
+}
+
+// Both packing passes in one launch: blocks [0, dy_blocks) pack dy, the rest pack x.
+struct PackLinArgs {
+    const unsigned short *dy, *x;
+    unsigned short *dyp, *xp;
+    int N, K, C, P, Q, H, W, pad, Wq, Jy, Jx, row_elems, dy_blocks;
+    int64_t dy_bs, x_bs;
+    FastDiv div_row, div_jy, div_jx, div_wq;
+};
+
+__global__ __launch_bounds__(256) void pack_lin(const PackLinArgs a)
+{
+    if ((int)blockIdx.x < a.dy_blocks)
+        pack_dy_lin((int64_t)blockIdx.x * 256 + threadIdx.x, a.dy, a.dyp, a.N, a.K, a.P, a.Q, a.Wq, a.Jy, a.row_elems,
+                    a.dy_bs, a.div_row, a.div_jy, a.div_wq);
+    else
+        pack_x_lin((int64_t)(blockIdx.x - a.dy_blocks) * 256 + threadIdx.x, a.x, a.xp, a.N, a.C, a.H, a.W, a.pad, a.Wq,
+                   a.Jx, a.x_bs, a.div_jx, a.div_wq);
 }
 
 // dw[k][c][rs] = part[0][k][rs*C + c] + part[1][k][rs*C + c] + ...  (fixed order)

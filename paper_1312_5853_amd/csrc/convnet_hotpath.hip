@@ -166,12 +166,12 @@ void launch_colgemm_bf16(const TileShape &t, int kc, const ColGemmFastArgs &a, c
 int grid1d(int64_t n, int block) { return (int)((n + block - 1) / block); }
 
 template <typename Kern>
-void launch_dma(Kern kern, const ColGemmDmaArgs &a, int grid, int lds, hipStream_t st)
+void launch_dma(Kern kern, const ColGemmDmaArgs &a, int grid, int lds, hipStream_t st, int threads = kThreads)
 {
     if (lds > 64 * 1024)
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                   160 * 1024);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), lds, st, a);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(threads), lds, st, a);
 }
 
 // bf16 forward / stride-1 backward-data on the direct-to-LDS kernel: one preparation launch (padded channel-blocked
@@ -190,7 +190,10 @@ int run_colgemm_dma(int op, const void *act, const void *w, void *out, const Pro
     q.pad_h = pl.dma_ph; q.pad_w = pl.dma_pw;
     q.src_bs = fwd ? pb.x_bs : pb.y_bs;
     const int64_t positions = (int64_t)pb.N * q.CB * q.Hp * q.Wp;
-    q.xb_blocks = grid1d(positions, 256);
+    // plane groups through LDS where they are 16-byte aligned and fit 64 KB; else one thread per position
+    const int plane_lds = 32 * LH * LW;
+    q.xb_planes = (q.src_bs % 8 == 0 && plane_lds <= 64 * 1024) ? 1 : 0;
+    q.xb_blocks = q.xb_planes ? pb.N * q.CB : grid1d(positions, 256);
     q.w = static_cast<const unsigned short *>(w);
     q.wt = reinterpret_cast<unsigned short *>(wsb + pl.wt_off);
     q.M = pl.M; q.Mpad = pl.Mpad; q.cblocks = Cr / kc; q.RS = RS; q.C = pb.C; q.transposed = fwd ? 0 : 1; q.kc = kc;
@@ -198,7 +201,8 @@ int run_colgemm_dma(int op, const void *act, const void *w, void *out, const Pro
     q.div_hp = make_fastdiv((uint32_t)q.Hp);
     q.div_cb = make_fastdiv((uint32_t)q.CB);
     const int64_t wt_elems = (int64_t)pl.Mpad * Cr * RS;
-    hipLaunchKernelGGL(bf16_dma_prepare, dim3(q.xb_blocks + grid1d(wt_elems / 8, 256)), dim3(256), 0, st, q);
+    hipLaunchKernelGGL(bf16_dma_prepare, dim3(q.xb_blocks + grid1d(wt_elems / 8, 256)), dim3(256),
+                       q.xb_planes ? plane_lds : 0, st, q);
     int rc = check_launch();
     if (rc != kStatusOk) return rc;
 
@@ -225,9 +229,11 @@ int run_colgemm_dma(int op, const void *act, const void *w, void *out, const Pro
     const int grid = 8 * a.tiles_per_xcd;
     const int lds = 3 * (pl.tile.bm() + pl.tile.bn()) * kc * 2;
     const int tn = pl.tile.TN;
-    if (tn == 4 && kc == 64) launch_dma(colgemm_bf16_dma_kernel<2, 4, 2, 2, 64, 1>, a, grid, lds, st);
+    // one work-group per CU (64-channel steps): eight waves, two per SIMD, so that a wave's waits (fragment reads,
+    // the barrier) leave the matrix pipe to the other; two work-groups per CU: four waves each
+    if (tn == 4 && kc == 64) launch_dma(colgemm_bf16_dma_kernel<2, 2, 2, 4, 64, 1>, a, grid, lds, st, 512);
     else if (tn == 4) launch_dma(colgemm_bf16_dma_kernel<2, 4, 2, 2, 32, 2>, a, grid, lds, st);
-    else if (tn == 3 && kc == 64) launch_dma(colgemm_bf16_dma_kernel<2, 3, 2, 2, 64, 1>, a, grid, lds, st);
+    else if (tn == 3 && kc == 64) launch_dma(colgemm_bf16_dma_kernel<1, 3, 4, 2, 64, 1>, a, grid, lds, st, 512);
     else if (tn == 3) launch_dma(colgemm_bf16_dma_kernel<2, 3, 2, 2, 32, 2>, a, grid, lds, st);
     else if (kc == 64) launch_dma(colgemm_bf16_dma_kernel<2, 2, 2, 2, 64, 1>, a, grid, lds, st);
     else launch_dma(colgemm_bf16_dma_kernel<2, 2, 2, 2, 32, 2>, a, grid, lds, st);
@@ -594,13 +600,19 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         unsigned short *dyp = reinterpret_cast<unsigned short *>(wsb + pl.lin_dy_off);
         unsigned short *xp = reinterpret_cast<unsigned short *>(wsb + pl.lin_x_off);
         const int row_elems = pl.lin_steps * 64;
-        hipLaunchKernelGGL(pack_dy_lin, dim3(grid1d((int64_t)pb.K * row_elems / 8, 256)), dim3(256), 0, st,
-                           static_cast<const unsigned short *>(dy), dyp, pb.N, pb.K, pb.P, pb.Q, pl.lin_wq, pl.lin_jy,
-                           row_elems, pb.y_bs, make_fastdiv((uint32_t)row_elems), make_fastdiv((uint32_t)pl.lin_jy),
-                           make_fastdiv((uint32_t)pl.lin_wq));
-        hipLaunchKernelGGL(pack_x_lin, dim3(grid1d((int64_t)pb.C * pb.N * pl.lin_jx / 8, 256)), dim3(256), 0, st,
-                           static_cast<const unsigned short *>(x), xp, pb.N, pb.C, pb.H, pb.W, pb.pad, pl.lin_wq,
-                           pl.lin_jx, pb.x_bs, make_fastdiv((uint32_t)pl.lin_jx), make_fastdiv((uint32_t)pl.lin_wq));
+        PackLinArgs q;
+        q.dy = static_cast<const unsigned short *>(dy); q.x = static_cast<const unsigned short *>(x);
+        q.dyp = dyp; q.xp = xp;
+        q.N = pb.N; q.K = pb.K; q.C = pb.C; q.P = pb.P; q.Q = pb.Q; q.H = pb.H; q.W = pb.W; q.pad = pb.pad;
+        q.Wq = pl.lin_wq; q.Jy = pl.lin_jy; q.Jx = pl.lin_jx; q.row_elems = row_elems;
+        q.dy_blocks = grid1d((int64_t)pb.K * row_elems / 8, 256);
+        q.dy_bs = pb.y_bs; q.x_bs = pb.x_bs;
+        q.div_row = make_fastdiv((uint32_t)row_elems);
+        q.div_jy = make_fastdiv((uint32_t)pl.lin_jy);
+        q.div_jx = make_fastdiv((uint32_t)pl.lin_jx);
+        q.div_wq = make_fastdiv((uint32_t)pl.lin_wq);
+        hipLaunchKernelGGL(pack_lin, dim3(q.dy_blocks + grid1d((int64_t)pb.C * pb.N * pl.lin_jx / 8, 256)), dim3(256),
+                           0, st, q);
         WgradLinArgs a;
         a.dyp = dyp; a.xp = xp; a.part = reinterpret_cast<float *>(wsb + pl.part_off);
         a.K = pb.K; a.C = pb.C; a.ncols = pl.Kg; a.S = pb.S; a.Wq = pl.lin_wq;
