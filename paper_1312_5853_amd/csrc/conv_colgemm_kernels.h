@@ -1047,8 +1047,9 @@ struct PatchArgs {
     int mtiles, jtiles;   // row tiles, position tiles per image
     int ntiles, tiles_per_xcd;
     int epi_on;           // bias / ReLU applied to each fp32 sum before it is stored (and, for TO = bfloat16, rounded)
+    int vec;              // fp32 rows staged in 16-byte pieces: W % 4 == 0, pad even, images 16-byte aligned
     Epilogue epi;
-    FastDiv div_q, div_rs, div_s, div_mj, div_m, div_wp, div_nr;
+    FastDiv div_q, div_rs, div_s, div_mj, div_m, div_wp, div_nr, div_pr;   // div_pr: W / 4 + 1 pieces per staged row
 };
 
 template <int TM, typename TI, typename TO>
@@ -1082,9 +1083,47 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
 
     // --- stage the patch: row (c, i) <- x[n][c][h0 + i][:], zero outside the image
     {
-        // 32 independent loads in flight per thread and batch (the first layer's patch is ~60 values per thread)
         const TI *xn = static_cast<const TI *>(p.x) + (size_t)n * p.x_bs;
-        const int total = p.C * p.NR * p.WP;
+        const int total = p.vec ? 0 : p.C * p.NR * p.WP;
+        if (sizeof(TI) == 4 && p.vec) {
+            // 16-byte pieces of the image rows, one more piece per row for the padding columns on both sides;
+            // sixteen loads in flight per thread (the first layer's patch is one batch)
+            const float *xf = reinterpret_cast<const float *>(xn);
+            const int pr = p.W >> 2, pieces = p.C * p.NR * (pr + 1);
+            constexpr int kNoPiece = -2147483647 - 1;
+            for (int e0 = tid; e0 < pieces; e0 += kThreads * 16) {
+                f32x4 tmp[16];
+                int dst[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    const int e = e0 + u * kThreads;
+                    const int ee = e < pieces ? e : 0;
+                    const int row = (int)fastdiv((uint32_t)ee, p.div_pr);
+                    const int pc = ee - row * (pr + 1);
+                    const int c = (int)fastdiv((uint32_t)row, p.div_nr);
+                    const int h = h0 + row - c * p.NR;
+                    const bool ok = (pc < pr) & ((unsigned)h < (unsigned)p.H);
+                    const f32x4 val = *reinterpret_cast<const f32x4 *>(xf + (ok ? (c * p.H + h) * p.W + pc * 4 : 0));
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+                    tmp[u] = ok ? val : zero;
+                    dst[u] = e < pieces ? (pc < pr ? row * p.WP + p.pad + pc * 4 : -1 - row * p.WP) : kNoPiece;
+                }
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                    if (dst[u] >= 0) {                         // patch rows and pad are even: 8-byte stores
+                        f32x2 *q = reinterpret_cast<f32x2 *>(&patch[dst[u]]);
+                        q[0] = f32x2{tmp[u][0], tmp[u][1]};
+                        q[1] = f32x2{tmp[u][2], tmp[u][3]};
+                    } else if (dst[u] != kNoPiece) {
+                        float *rowp = &patch[-1 - dst[u]];
+                        for (int v = 0; v < p.pad; v += 2) *reinterpret_cast<f32x2 *>(&rowp[v]) = f32x2{0.f, 0.f};
+                        for (int v = p.pad + p.W; v < p.WP; v += 2) *reinterpret_cast<f32x2 *>(&rowp[v]) = f32x2{0.f, 0.f};
+                    }
+                }
+            }
+        }
+        // any other shape or type, one value at a time: 32 independent loads in flight per thread and batch
         for (int e0 = tid; e0 < total; e0 += kThreads * 32) {
             float tmp[32];
 #pragma unroll

@@ -967,3 +967,24 @@ __global__ __launch_bounds__(256) void reduce_partials(const float *__restrict__
     __syncthreads();
     if (g == 0 && i < count) dw[i] = ((sums[0][o] + sums[1][o]) + sums[2][o]) + sums[3][o];
 }
+
+// The same for many partials and a count that is a multiple of four (16-byte aligned dw): four consecutive outputs
+// per thread, 16 lane groups; group g adds the partials g, g + 16, g + 32, ... in ascending order, then the sixteen
+// sums are added in group order.
+__global__ __launch_bounds__(256) void reduce_partials_x4(const float *__restrict__ part, float *__restrict__ dw,
+                                                           int count, int nsplit)
+{
+    __shared__ f32x4 sums[16][16];
+    const int o = threadIdx.x & 15, g = threadIdx.x >> 4;
+    const int i = (blockIdx.x * 16 + o) * 4;
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+    if (i < count)
+        for (int k = g; k < nsplit; k += 16) s += *reinterpret_cast<const f32x4 *>(part + (size_t)k * count + i);
+    sums[g][o] = s;
+    __syncthreads();
+    if (g == 0 && i < count) {
+        f32x4 t = sums[0][o];
+        for (int q = 1; q < 16; ++q) t += sums[q][o];
+        *reinterpret_cast<f32x4 *>(dw + i) = t;
+    }
+}

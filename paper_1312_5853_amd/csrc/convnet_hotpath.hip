@@ -42,6 +42,7 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 #include "device_common.h"
 #include "conv_colgemm_kernels.h"
 #include "conv_bf16_dma_kernels.h"
+#include "conv_wgrad_rows_bf16_kernels.h"
 #include "conv_wgrad_kernels.h"
 #include "fc_kernels.h"
 #include "glue_kernels.h"
@@ -544,6 +545,9 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         a.div_m = make_fastdiv((uint32_t)a.mtiles);
         a.div_wp = make_fastdiv((uint32_t)pl.patch_wp);
         a.div_nr = make_fastdiv((uint32_t)pl.patch_nr);
+        a.div_pr = make_fastdiv((uint32_t)(pb.W / 4 + 1));
+        a.vec = pb.dtype != kDtypeBf16 && pb.W % 4 == 0 && pb.pad % 2 == 0 && pl.patch_wp % 2 == 0 &&
+                pb.x_bs % 4 == 0 && reinterpret_cast<uintptr_t>(act) % 16 == 0;
         // forward only, so an epilogue here is bias / ReLU: applied to the fp32 sums in the kernel's store
         a.epi_on = ep != nullptr;
         a.epi = ep ? *ep : Epilogue{};
@@ -635,6 +639,34 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
                            pb.K, pb.C, RS, pl.nsplit, 1, make_fastdiv((uint32_t)(pb.K * pl.Kg)),
                            make_fastdiv((uint32_t)pl.Kg), make_fastdiv((uint32_t)pb.C));
+        return check_launch();
+    }
+    if (pl.rows && reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(dy) % 4 == 0) {
+        // few channels, stride 4, bf16: input rows as shifted copies in LDS, one partial result per work-group
+        WgradRowsArgs a;
+        a.x = static_cast<const unsigned short *>(x); a.dy = static_cast<const unsigned short *>(dy);
+        a.part = reinterpret_cast<float *>(wsb + pl.part_off);
+        a.N = pb.N; a.C = pb.C; a.H = pb.H; a.W = pb.W; a.K = pb.K; a.R = pb.R; a.S = pb.S; a.P = pb.P; a.Q = pb.Q;
+        a.Kg = pl.Kg;
+        a.x_bs = pb.x_bs; a.y_bs = pb.y_bs;
+        a.dy_elems = (int64_t)(pb.N - 1) * pb.y_bs + (int64_t)pb.K * pb.P * pb.Q;
+        a.splits = pl.rows_splits; a.units = pb.N * pl.rows_splits;
+        a.ng = ceil_div(pb.Q, 8); a.nkb = ceil_div(pb.Q, 16); a.nnew = pb.R < 4 ? pb.R : 4;
+        a.div_splits = make_fastdiv((uint32_t)a.splits);
+        a.div_ng = make_fastdiv((uint32_t)a.ng);
+        if (pl.rows_lds > 64 * 1024)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_rows_bf16_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipLaunchKernelGGL(wgrad_rows_bf16_kernel, dim3(pl.rows_wgs), dim3(256), pl.rows_lds, st, a);
+        int rc = check_launch();
+        if (rc != kStatusOk) return rc;
+        const int count = pb.K * pl.Kg;
+        if (count % 4 == 0 && reinterpret_cast<uintptr_t>(dw) % 16 == 0)
+            hipLaunchKernelGGL(reduce_partials_x4, dim3(grid1d(count, 64)), dim3(256), 0, st, a.part,
+                               static_cast<float *>(dw), count, pl.rows_wgs);
+        else
+            hipLaunchKernelGGL(reduce_partials, dim3(grid1d(count, 64)), dim3(256), 0, st, a.part,
+                               static_cast<float *>(dw), count, pl.rows_wgs);
         return check_launch();
     }
     const float *xf = as_f32(pl.widen, x, pb.N, (int64_t)pb.C * pb.H * pb.W, &pb.x_bs, wsb, pl, 0, st);

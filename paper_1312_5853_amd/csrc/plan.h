@@ -155,6 +155,11 @@ struct Plan {
     bool dma;
     int dma_kc, dma_occ, dma_hp, dma_wp, dma_ph, dma_pw;
     size_t xb_off, xb_bytes;
+    // bf16 backward-filter of a stride-4, pad-2 layer with at most four input channels on the bf16 matrix
+    // instruction (input rows staged as shifted copies in LDS): rows_splits output-row ranges per image,
+    // rows_wgs work-groups with one partial result each, rows_lds bytes of LDS
+    bool rows;
+    int rows_splits, rows_wgs, rows_lds;
     size_t total;
 };
 
@@ -256,6 +261,21 @@ inline Plan make_plan(int op, const Problem &pb)
         pl.part_off = off;
         const bool staged = pb.C % kChunk == 0;          // fast path always goes through the partials
         pl.part_bytes = (pl.nsplit > 1 || staged) ? (size_t)pl.nsplit * pb.K * pb.C * RS * 4 : 0;
+        if (pb.dtype == kDtypeBf16 && G == 1 && pb.stride == 4 && pb.pad == 2 && pb.S <= 11 && pb.R <= 12 &&
+            pb.C <= 4 && pl.Kg <= 384 && pb.K <= 96 && pb.Q <= 64 && pb.W % 8 == 0 && pb.x_bs % 8 == 0) {
+            const int lds = 2 * 96 * 144 + pb.C * 16 * pb.S * 144;
+            if (lds <= 150 * 1024) {
+                pl.rows = true;
+                pl.rows_lds = lds;
+                int splits = ceil_div(256, pb.N);
+                if (splits > pb.P) splits = pb.P;
+                pl.rows_splits = splits;
+                const int64_t units = (int64_t)pb.N * splits;
+                pl.rows_wgs = units < 256 ? (int)units : 256;
+                const size_t need = (size_t)pl.rows_wgs * pb.K * pl.Kg * 4;
+                if (need > pl.part_bytes) pl.part_bytes = need;     // the table path stays available at run time
+            }
+        }
         off += round_up64(pl.part_bytes * (pl.fused_groups ? G : 1), 256);
     } else {
         const int Cr_ = op == kOpFwd ? pb.C : pb.K;

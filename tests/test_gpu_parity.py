@@ -137,6 +137,13 @@ BF16_SHAPES = [
     (2, 2, 16, 16, 20, 5, 7, 4, 2),
     (1, 3, 64, 64, 100, 11, 11, 4, 2),
     (70, 1, 56, 40, 33, 8, 16, 4, 0),
+    # ... and the backward-filter kernel that stages input rows as shifted copies (stride 4, pad 2, at most four
+    # channels, 96 filters, 64 positions per output row): a last group of 8 positions that is part empty and two
+    # 16-position blocks, 96 filters, fewer filter rows than the stride, more (image, row range) units than
+    # work-groups so that a work-group restarts its ring of rows
+    (3, 3, 40, 120, 96, 11, 11, 4, 2),
+    (2, 4, 20, 24, 16, 3, 3, 4, 2),
+    (300, 1, 16, 16, 8, 5, 5, 4, 2),
 ]
 
 
