@@ -24,13 +24,16 @@ constexpr int kRowsM = 96;                 // filters per work-group (three 32-r
 constexpr int kRowsRing = 16;              // staged input rows per channel
 constexpr int kRowsCols = 384;             // taps per work-group (four waves x three 32-column blocks)
 constexpr int kRowsABuf = kRowsM * kRowsPitch;
+// LDS bytes behind E that idle lanes store to (lane L at L * 16 + s * kRowsPitch, s <= 10): the steady-state step has
+// no branch around a store, so that matrix instructions, the staging arithmetic and the LDS stores can be interleaved
+constexpr int kRowsTrash = 255 * 16 + 10 * kRowsPitch + 16;
 
 struct WgradRowsArgs {
     const unsigned short *x, *dy;
     float *part;                 // [work-group][K][Kg]
     int N, C, H, W, K, R, S, P, Q, Kg;         // stride 4, pad 2
-    int64_t x_bs, y_bs;          // elements between images
-    int64_t dy_elems;            // elements of dy that may be read: (N - 1) * y_bs + K * P * Q
+    int x_bs, y_bs;              // elements between images (every offset into x and dy fits 31 bits)
+    int dy_elems;                // elements of dy that may be read: (N - 1) * y_bs + K * P * Q
     int splits, units;           // output-row ranges per image; units = N * splits
     int ng;                      // groups of 8 positions per output row: ceil(Q / 8)
     int nkb;                     // 16-position blocks per output row: ceil(Q / 16)
@@ -46,33 +49,25 @@ __device__ __forceinline__ unsigned rows_mask(int nv, int i)
     return (2 * i < nv ? 0x0000FFFFu : 0u) | (2 * i + 1 < nv ? 0xFFFF0000u : 0u);
 }
 
-// The copies s = 6*HF .. 6*HF + 5 (s < S) of eight positions, from the window of five 16-byte pieces that starts
-// at input column 32g - 8 + 8*HF: position i of copy s is window element 4i + s + 6 - 8*HF.
-template <int HF>
-__device__ __forceinline__ void rows_store_copies(const u32x4 (&win)[5], char *dst, int S, int nv)
+// Copy s of eight positions from the window of six 16-byte pieces that starts at input column 32g - 8:
+// position i of copy s is window element 4i + s + 6.
+template <int S_>
+__device__ __forceinline__ void rows_store_copy(const u32x4 (&win)[6], char *dst, const unsigned (&mask)[4])
 {
-    unsigned w[20];
+    constexpr int o = (S_ + 6) >> 1;                                // word of element 0 of this copy
+    constexpr unsigned sel = (S_ & 1) ? 0x07060302u : 0x05040100u;  // high or low halves of the two words
+    u32x4 out;
 #pragma unroll
-    for (int k = 0; k < 5; ++k)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) w[4 * k + i] = win[k][i];
-    unsigned mask[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) mask[i] = rows_mask(nv, i);
-#pragma unroll
-    for (int sl = 0; sl < 6 - HF; ++sl) {
-        const int s = 6 * HF + sl;
-        const int o = ((s + 6) >> 1) - 4 * HF;                     // word of element 0 of this copy
-        const unsigned sel = (s & 1) ? 0x07060302u : 0x05040100u;  // high or low halves of the two words
-        if (s < S) {
-            u32x4 out;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) out[j] = __builtin_amdgcn_perm(w[4 * j + 2 + o], w[4 * j + o], sel) & mask[j];
-            *reinterpret_cast<u32x4 *>(dst + s * kRowsPitch) = out;
-        }
+    for (int j = 0; j < 4; ++j) {
+        const unsigned lo = win[(4 * j + o) >> 2][(4 * j + o) & 3], hi = win[(4 * j + 2 + o) >> 2][(4 * j + 2 + o) & 3];
+        out[j] = __builtin_amdgcn_perm(hi, lo, sel) & mask[j];
     }
+    *reinterpret_cast<u32x4 *>(dst + S_ * kRowsPitch) = out;
 }
 
+// FULL: S = 11 and Q in 49..64 (four 16-position blocks), the first layer's case: those two are compile-time, and
+// the LDS stores of the next row sit between the matrix instructions.
+template <bool FULL>
 __global__ __launch_bounds__(256, 1) void wgrad_rows_bf16_kernel(const WgradRowsArgs p)
 {
     extern __shared__ __attribute__((aligned(16))) float lds_fast[];
@@ -80,7 +75,8 @@ __global__ __launch_bounds__(256, 1) void wgrad_rows_bf16_kernel(const WgradRows
     char *const E = lds + 2 * kRowsABuf;
     const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
-    const int erow = p.S * kRowsPitch;                         // one staged input row: S copies
+    const int S = FULL ? 11 : p.S, nkb = FULL ? 4 : p.nkb;
+    const int erow = S * kRowsPitch;                           // one staged input row: S copies
     const int echan = kRowsRing * erow;
     const int lds_bytes = 2 * kRowsABuf + p.C * echan;
 
@@ -93,50 +89,73 @@ __global__ __launch_bounds__(256, 1) void wgrad_rows_bf16_kernel(const WgradRows
     for (int t = 0; t < 3; ++t) {
         const int j = 32 * (3 * wave + t) + l32;
         const int jj = j < p.Kg ? j : 0;                       // columns beyond the filter read tap 0, never stored
-        const int c = jj / (p.R * p.S), rs = jj - c * (p.R * p.S);
-        const int r = rs / p.S, s = rs - r * p.S;
+        const int c = jj / (p.R * S), rs = jj - c * (p.R * S);
+        const int r = rs / S, s = rs - r * S;
         tap_off[t] = c * echan + s * kRowsPitch + half * 16;
         tap_r[t] = r;
     }
 
-    // E building: waves 0, 2 make the copies s = 0..5 and waves 1, 3 the copies s = 6..10 of one (row, group of 8
-    // positions) pair per lane
-    const int hf = wave & 1;
-    const int pair = (wave >> 1) * 64 + lane;
-    // Loads and their use are kept apart (the loads of the next step are in flight while this step's matrix
-    // instructions run): a load always reads a valid address, and what lies outside the image becomes zero only
-    // when the piece is consumed.  Returns the mask of pieces that are inside.
-    auto e_load = [&](u32x4 (&win)[5], int n, int c, int hh, int g, bool on) -> unsigned {
+    // E building: one (input row, group of 8 positions) pair per lane: six 16-byte pieces of the
+    // row in (the window: input columns 32g - 8 .. 32g + 39), S copies out.  Loads and their use are kept apart (a
+    // row is loaded three steps before it is needed): a load always reads a valid address -- a piece outside the row
+    // reads the row's first piece, a row outside the image reads row 0 -- and zeros are put in when the window is
+    // consumed.  Only two words of a window can hold padding that a real position reads: word 3 (columns -2, -1, for
+    // g = 0) and word 0 of the piece that starts at column W (columns W, W + 1); everything else outside the row
+    // only feeds positions >= Q, which the position masks clear.  FULL uses that; the general variant clears whole
+    // pieces.
+    auto e_load = [&](u32x4 (&win)[6], const char *img, int c, int hh, int g, bool on) {
         const int h = hh - 2;
         const bool rok = on & ((unsigned)h < (unsigned)p.H);
-        const unsigned short *row = p.x + (size_t)n * p.x_bs + ((size_t)c * p.H + (rok ? h : 0)) * p.W;
-        unsigned inside = 0;
+        const unsigned rowb = (unsigned)((c * p.H + (rok ? h : 0)) * p.W) * 2u;
 #pragma unroll
-        for (int k = 0; k < 5; ++k) {
-            const int start = 32 * g - 8 + 8 * (hf + k);        // W is a multiple of 8: a piece is inside or outside
-            const bool ok = rok & ((unsigned)start < (unsigned)p.W);
-            win[k] = *reinterpret_cast<const u32x4 *>(row + (ok ? start : 0));
-            inside |= ok ? 1u << k : 0u;
+        for (int k = 0; k < 6; ++k) {
+            const int start = 32 * g - 8 + 8 * k;               // W is a multiple of 8: a piece is inside or outside
+            const bool ok = (unsigned)start < (unsigned)p.W;
+            win[k] = *reinterpret_cast<const u32x4 *>(img + (size_t)(rowb + (ok ? (unsigned)start * 2u : 0u)));
         }
-        return inside;
     };
-    auto e_store = [&](u32x4 (&win)[5], unsigned inside, int c, int hh, int g) {
+    // zeros for what lies outside the image; the position masks of the group
+    auto e_prepare = [&](u32x4 (&win)[6], unsigned (&mask)[4], int hh, int g) {
+        const bool rok = (unsigned)(hh - 2) < (unsigned)p.H;
+        if (FULL) {
+            if (g == 0) win[0][3] = 0u;
 #pragma unroll
-        for (int k = 0; k < 5; ++k)
-            if (!(inside >> k & 1)) win[k] = u32x4{0u, 0u, 0u, 0u};
-        char *dst = E + c * echan + (hh & (kRowsRing - 1)) * erow + g * 16;
-        const int nv = min(max(p.Q - 8 * g, 0), 8);
-        if (hf) rows_store_copies<1>(win, dst, p.S, nv);
-        else rows_store_copies<0>(win, dst, p.S, nv);
+            for (int k = 1; k < 6; ++k)
+                if (32 * g - 8 + 8 * k == p.W) win[k][0] = 0u;
+        } else {
+#pragma unroll
+            for (int k = 0; k < 6; ++k)
+                if (!((unsigned)(32 * g - 8 + 8 * k) < (unsigned)p.W)) win[k] = u32x4{0u, 0u, 0u, 0u};
+        }
+        const int nv = rok ? min(max(p.Q - 8 * g, 0), 8) : 0;  // a row outside the image: every position zero
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mask[i] = rows_mask(nv, i);
+    };
+    auto e_dst = [&](int c, int hh, int g) { return E + c * echan + (hh & (kRowsRing - 1)) * erow + g * 16; };
+    char *const trash = E + p.C * echan + tid * 16;
+    auto e_copy = [&](auto s_c, const u32x4 (&win)[6], char *dst, const unsigned (&mask)[4]) {
+        constexpr int S_ = decltype(s_c)::value;
+        if (S_ < S) rows_store_copy<S_>(win, dst, mask);
+    };
+    auto e_store_all = [&](u32x4 (&win)[6], int c, int hh, int g) {
+        unsigned mask[4];
+        e_prepare(win, mask, hh, g);
+        char *dst = e_dst(c, hh, g);
+        e_copy(std::integral_constant<int, 0>{}, win, dst, mask); e_copy(std::integral_constant<int, 1>{}, win, dst, mask);
+        e_copy(std::integral_constant<int, 2>{}, win, dst, mask); e_copy(std::integral_constant<int, 3>{}, win, dst, mask);
+        e_copy(std::integral_constant<int, 4>{}, win, dst, mask); e_copy(std::integral_constant<int, 5>{}, win, dst, mask);
+        e_copy(std::integral_constant<int, 6>{}, win, dst, mask); e_copy(std::integral_constant<int, 7>{}, win, dst, mask);
+        e_copy(std::integral_constant<int, 8>{}, win, dst, mask); e_copy(std::integral_constant<int, 9>{}, win, dst, mask);
+        e_copy(std::integral_constant<int, 10>{}, win, dst, mask);
     };
     // steady state: the nnew rows a step adds, per channel (c, i) and group g: fixed per lane
-    const int npairs_new = p.C * p.nnew * p.ng;
-    const bool e_on = pair < npairs_new;
-    int e_c, e_i, e_g;
+    // (eight lanes per row, lane g of them idle for g >= ng: the 16-byte LDS stores of eight consecutive lanes then
+    // go to one row's 128 consecutive bytes and never meet a bank twice)
+    const int e_g = tid & 7;
+    const bool e_on = (tid >> 3) < p.C * p.nnew && e_g < p.ng;
+    int e_c, e_i;
     {
-        const int pp = e_on ? pair : 0;
-        const int t = (int)fastdiv((uint32_t)pp, p.div_ng);
-        e_g = pp - t * p.ng;
+        const int t = e_on ? tid >> 3 : 0;
         e_c = t / p.nnew;
         e_i = t - e_c * p.nnew;
     }
@@ -155,42 +174,58 @@ __global__ __launch_bounds__(256, 1) void wgrad_rows_bf16_kernel(const WgradRows
     }
     // Five 4-byte words from the even element at or below the item's first one.  Where those 20 bytes would pass
     // the end of the tensor (the last group of its last row) the load reads element 0 instead and the item is
-    // fetched one element at a time when it is consumed (tail[u] = its first even element, else -1).
-    auto a_load = [&](unsigned (&d)[3][5], int (&sh)[3], int64_t (&tail)[3], int n, int prow) {
-        const int64_t rowbase = (int64_t)n * p.y_bs + (int64_t)prow * p.Q;
+    // fetched one element at a time when it is consumed.
+    unsigned a_mask[3][4];
+#pragma unroll
+    for (int u = 0; u < 3; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a_mask[u][i] = rows_mask(a_nv[u], i);
+    const char *const dyb = reinterpret_cast<const char *>(p.dy);
+    auto a_load = [&](unsigned (&d)[3][5], int n, int prow) {
+        const int rowbase = n * p.y_bs + prow * p.Q;
 #pragma unroll
         for (int u = 0; u < 3; ++u) {
-            const int64_t o = rowbase + a_base[u];
-            const int64_t oe = o & ~(int64_t)1;                 // 4-byte aligned element
-            sh[u] = (int)(o & 1) * 16;
-            const bool fits = oe + 10 <= p.dy_elems;
-            tail[u] = fits ? -1 : oe;
-            const unsigned short *src = p.dy + (fits ? oe : 0);
-            const u32x4_a4 v = *reinterpret_cast<const u32x4_a4 *>(src);
+            const int oe = (rowbase + a_base[u]) & ~1;          // 4-byte aligned element
+            const unsigned off = oe + 10 <= p.dy_elems ? (unsigned)oe * 2u : 0u;
+            const u32x4_a4 v = *reinterpret_cast<const u32x4_a4 *>(dyb + (size_t)off);
             d[u][0] = v[0]; d[u][1] = v[1]; d[u][2] = v[2]; d[u][3] = v[3];
-            d[u][4] = *reinterpret_cast<const unsigned *>(src + 8);
+            d[u][4] = *reinterpret_cast<const unsigned *>(dyb + (size_t)off + 16);
         }
     };
-    auto a_store = [&](unsigned (&d)[3][5], const int (&sh)[3], const int64_t (&tail)[3], int buf) {
+    auto a_shift_store = [&](int u, const unsigned (&d)[5], int o, char *dst) {
+        const unsigned sh = (unsigned)(o & 1) * 16;
+        u32x4 out;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) out[i] = __builtin_amdgcn_alignbit(d[i + 1], d[i], sh) & a_mask[u][i];
+        *reinterpret_cast<u32x4 *>(dst) = out;
+    };
+    // no branch: a thread without an item u stores to the trash area; an item at the tensor's end stores what the
+    // clamped load returned and is put right by a_fix_tail before the barrier
+    auto a_store_fast = [&](int u, const unsigned (&d)[5], int n, int prow, int buf) {
+        char *dst = tid + 256 * u < nitems ? lds + buf * kRowsABuf + a_dst[u] : trash;
+        a_shift_store(u, d, n * p.y_bs + prow * p.Q + a_base[u], dst);
+    };
+    auto a_fix_tail = [&](int n, int prow, int buf) {
 #pragma unroll
         for (int u = 0; u < 3; ++u) {
-            if (tid + 256 * u < nitems) {
-                if (tail[u] >= 0) {
+            const int o = n * p.y_bs + prow * p.Q + a_base[u];
+            const int oe = o & ~1;
+            if (tid + 256 * u < nitems && oe + 10 > p.dy_elems) {   // elements past the end lie beyond Q: masked
+                unsigned d[5];
 #pragma unroll
-                    for (int i = 0; i < 5; ++i) {
-                        const int64_t e = tail[u] + 2 * i;
-                        const unsigned lo = e < p.dy_elems ? p.dy[e] : 0u;
-                        const unsigned hi = e + 1 < p.dy_elems ? p.dy[e + 1] : 0u;
-                        d[u][i] = lo | (hi << 16);
-                    }
+                for (int i = 0; i < 5; ++i) {
+                    const unsigned lo = p.dy[min(oe + 2 * i, p.dy_elems - 1)];
+                    const unsigned hi = p.dy[min(oe + 2 * i + 1, p.dy_elems - 1)];
+                    d[i] = lo | (hi << 16);
                 }
-                u32x4 out;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    out[i] = __builtin_amdgcn_alignbit(d[u][i + 1], d[u][i], (unsigned)sh[u]) & rows_mask(a_nv[u], i);
-                *reinterpret_cast<u32x4 *>(lds + buf * kRowsABuf + a_dst[u]) = out;
+                a_shift_store(u, d, o, lds + buf * kRowsABuf + a_dst[u]);
             }
         }
+    };
+    // rows whose items can reach the tensor's end (a superset; a_fix_tail tests each item)
+    auto near_end = [&](int n, int prow) { return n == p.N - 1 && (p.P - prow) * p.Q <= 8 * p.ng + 12; };
+    auto a_store_one = [&](int u, const unsigned (&d)[5], int n, int prow, int buf) {
+        if (tid + 256 * u < nitems) a_store_fast(u, d, n, prow, buf);
     };
 
     f32x16 acc[3][3];
@@ -201,33 +236,9 @@ __global__ __launch_bounds__(256, 1) void wgrad_rows_bf16_kernel(const WgradRows
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][t][v] = 0.f;
 
-    auto compute = [&](int prow, int buf) {
-        const char *Ab = lds + buf * kRowsABuf + l32 * kRowsPitch + half * 16;
-        const char *Bb[3];
-#pragma unroll
-        for (int t = 0; t < 3; ++t) Bb[t] = E + tap_off[t] + ((4 * prow + tap_r[t]) & (kRowsRing - 1)) * erow;
-        bf16x8 fa[2][3], fb[2][3];
-        auto read = [&](int set, int kb) {
-#pragma unroll
-            for (int i = 0; i < 3; ++i)
-                fa[set][i] = *reinterpret_cast<const bf16x8 *>(Ab + i * 32 * kRowsPitch + kb * 32);
-#pragma unroll
-            for (int t = 0; t < 3; ++t) fb[set][t] = *reinterpret_cast<const bf16x8 *>(Bb[t] + kb * 32);
-        };
-        read(0, 0);
-#pragma unroll
-        for (int kb = 0; kb < 4; ++kb) {
-            if (kb < p.nkb) {
-                if (kb + 1 < p.nkb) read((kb + 1) & 1, kb + 1);
-#pragma unroll
-                for (int i = 0; i < 3; ++i)
-#pragma unroll
-                    for (int t = 0; t < 3; ++t)
-                        acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kb & 1][i], fb[kb & 1][t], acc[i][t],
-                                                                            0, 0, 0);
-            }
-        }
-    };
+    // three register stages: stage (row - p_begin) % 3 holds the loads of that output row
+    u32x4 win[3][6];
+    unsigned dd[3][3][5];
 
     for (int unit = blockIdx.x; unit < p.units; unit += gridDim.x) {
         const int n = (int)fastdiv((uint32_t)unit, p.div_splits);
@@ -235,47 +246,141 @@ __global__ __launch_bounds__(256, 1) void wgrad_rows_bf16_kernel(const WgradRows
         const int p_begin = (int)((int64_t)p.P * sp / p.splits), p_end = (int)((int64_t)p.P * (sp + 1) / p.splits);
         if (p_begin >= p_end) continue;
         __syncthreads();                                        // zero fill / the previous unit's reads are done
+        const char *const img = reinterpret_cast<const char *>(p.x + (size_t)n * p.x_bs);
+        auto issue = [&](auto st_c, int prow) {                 // loads of output row prow (clamped to the unit)
+            constexpr int ST = decltype(st_c)::value;
+            const int pr = min(prow, p_end - 1);
+            e_load(win[ST], img, e_c, 4 * pr + p.R - p.nnew + e_i, e_g, e_on);
+            a_load(dd[ST], n, pr);
+        };
         // every input row of the first output row, and its dy rows
         {
-            const int total = p.C * p.R * p.ng;
-            for (int q0 = 0; q0 < total; q0 += 128) {
-                const int pi = q0 + pair;
-                const bool on = pi < total;
-                const int pp = on ? pi : 0;
-                const int t = (int)fastdiv((uint32_t)pp, p.div_ng);
-                const int g = pp - t * p.ng, c = t / p.R, i = t - c * p.R;
-                u32x4 win[5];
-                const unsigned inside = e_load(win, n, c, 4 * p_begin + i, g, on);
-                if (on) e_store(win, inside, c, 4 * p_begin + i, g);
+            const int rows = p.C * p.R;
+            for (int t0 = 0; t0 < rows; t0 += 32) {
+                const int t1 = t0 + (tid >> 3), g = tid & 7;
+                const bool on = t1 < rows && g < p.ng;
+                const int t = on ? t1 : 0;
+                const int c = t / p.R, i = t - c * p.R;
+                e_load(win[0], img, c, 4 * p_begin + i, g, on);
+                if (on) e_store_all(win[0], c, 4 * p_begin + i, g);
             }
-            unsigned d[3][5];
-            int sh[3];
-            int64_t tail[3];
-            a_load(d, sh, tail, n, p_begin);
-            a_store(d, sh, tail, 0);
+            a_load(dd[0], n, p_begin);
+#pragma unroll
+            for (int u = 0; u < 3; ++u) a_store_one(u, dd[0][u], n, p_begin, 0);
+            if (near_end(n, p_begin)) a_fix_tail(n, p_begin, 0);
         }
+        issue(std::integral_constant<int, 1>{}, p_begin + 1);
+        issue(std::integral_constant<int, 2>{}, p_begin + 2);
         __syncthreads();
         int buf = 0;
-        for (int prow = p_begin; prow < p_end; ++prow) {
-            const bool more = prow + 1 < p_end;
-            // rows of the next step: loads now, LDS stores after this step's matrix instructions
+        // One output row: loads of row prow + 3 into the stage row prow used; matrix instructions of row prow; the
+        // stage of row prow + 1 goes to LDS (dy buffer buf ^ 1, ring rows no tap of row prow reads).  After the last
+        // row of the unit the stores repeat that row into places nothing reads before they are rewritten.
+        auto step = [&](auto st_c, int prow) {
+            constexpr int ST = decltype(st_c)::value, SN = (ST + 1) % 3;
+            issue(st_c, prow + 3);
+            const int pn = min(prow + 1, p_end - 1);            // the row stage SN holds
             const int hh_new = 4 * (prow + 1) + p.R - p.nnew + e_i;
-            u32x4 win[5];
-            unsigned d[3][5], inside = 0;
-            int sh[3];
-            int64_t tail[3];
-            if (more) {
-                inside = e_load(win, n, e_c, hh_new, e_g, e_on);
-                a_load(d, sh, tail, n, prow + 1);
-            }
-            compute(prow, buf);
-            if (more) {
-                if (e_on) e_store(win, inside, e_c, hh_new, e_g);
-                a_store(d, sh, tail, buf ^ 1);
+            const char *Ab = lds + buf * kRowsABuf + l32 * kRowsPitch + half * 16;
+            const char *Bb[3];
+#pragma unroll
+            for (int t = 0; t < 3; ++t) Bb[t] = E + tap_off[t] + ((4 * prow + tap_r[t]) & (kRowsRing - 1)) * erow;
+            bf16x8 fa[2][3], fb[2][3];
+            auto read = [&](int set, int kb) {
+#pragma unroll
+                for (int i = 0; i < 3; ++i)
+                    fa[set][i] = *reinterpret_cast<const bf16x8 *>(Ab + i * 32 * kRowsPitch + kb * 32);
+#pragma unroll
+                for (int t = 0; t < 3; ++t) fb[set][t] = *reinterpret_cast<const bf16x8 *>(Bb[t] + kb * 32);
+            };
+            unsigned mask[4];
+            char *dst = e_on ? e_dst(e_c, hh_new, e_g) : trash;
+            // store work in twelve slots: copy s of the new input rows in slot s, a dy item in slots 3, 7, 11.
+            // FULL: no branches (idle lanes store to the trash area), so the whole step is one scheduling region
+            auto slot = [&](auto k_c) {
+                constexpr int K_ = decltype(k_c)::value;
+                // (the four words of the window no copy reads stay allocated until here: the register allocator would
+                // otherwise hand them out while their load is in flight, and every such reuse waits for the load)
+                if (K_ == 0)
+                    asm volatile("" :: "v"(win[SN][0][0]), "v"(win[SN][0][1]), "v"(win[SN][0][2]), "v"(win[SN][5][3]));
+                if (FULL) {
+                    if (K_ == 0) e_prepare(win[SN], mask, 4 * pn + p.R - p.nnew + e_i, e_g);
+                    if (K_ < 11) e_copy(std::integral_constant<int, K_ < 11 ? K_ : 0>{}, win[SN], dst, mask);
+                    if (K_ % 4 == 3) a_store_fast(K_ / 4, dd[SN][K_ / 4], n, pn, buf ^ 1);
+                } else {
+                    if (K_ == 0 && e_on) e_prepare(win[SN], mask, 4 * pn + p.R - p.nnew + e_i, e_g);
+                    if (K_ < 11 && e_on) e_copy(std::integral_constant<int, K_ < 11 ? K_ : 0>{}, win[SN], dst, mask);
+                    if (K_ % 4 == 3) a_store_one(K_ / 4, dd[SN][K_ / 4], n, pn, buf ^ 1);
+                }
+            };
+            read(0, 0);
+            if (FULL) {
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb) {
+                    if (kb + 1 < 4) read((kb + 1) & 1, kb + 1);
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+#pragma unroll
+                        for (int t = 0; t < 3; ++t)
+                            acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kb & 1][i], fb[kb & 1][t], acc[i][t],
+                                                                                0, 0, 0);
+                        if (kb == 0) { if (i == 0) slot(std::integral_constant<int, 0>{}); if (i == 1) slot(std::integral_constant<int, 1>{}); if (i == 2) slot(std::integral_constant<int, 2>{}); }
+                        if (kb == 1) { if (i == 0) slot(std::integral_constant<int, 3>{}); if (i == 1) slot(std::integral_constant<int, 4>{}); if (i == 2) slot(std::integral_constant<int, 5>{}); }
+                        if (kb == 2) { if (i == 0) slot(std::integral_constant<int, 6>{}); if (i == 1) slot(std::integral_constant<int, 7>{}); if (i == 2) slot(std::integral_constant<int, 8>{}); }
+                        if (kb == 3) { if (i == 0) slot(std::integral_constant<int, 9>{}); if (i == 1) slot(std::integral_constant<int, 10>{}); if (i == 2) slot(std::integral_constant<int, 11>{}); }
+                    }
+                }
+                // A wave issues in order: while it waits to issue the next matrix instruction nothing else of it
+                // issues.  So one matrix instruction (32 clocks in its pipe) is followed by up to seven vector
+                // instructions (4 clocks each) and one LDS / memory instruction, 36 times.
+                // The fragments of the next 16 positions are read in one go before the nine instructions that
+                // hide their latency.
+                __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);          // LDS reads: fragments of block 0
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb) {
+                    if (kb < 3) __builtin_amdgcn_sched_group_barrier(0x100, 6, 0);
+#pragma unroll
+                    for (int g = 0; g < 9; ++g) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // matrix
+                        __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);  // vector ALU
+                        __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // LDS write
+                    }
+                }
+                if (near_end(n, pn)) a_fix_tail(n, pn, buf ^ 1);
+            } else {
+#pragma unroll
+                for (int kb = 0; kb < 4; ++kb) {
+                    if (kb < nkb) {
+                        if (kb + 1 < nkb) read((kb + 1) & 1, kb + 1);
+#pragma unroll
+                        for (int i = 0; i < 3; ++i)
+#pragma unroll
+                            for (int t = 0; t < 3; ++t)
+                                acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kb & 1][i], fb[kb & 1][t],
+                                                                                    acc[i][t], 0, 0, 0);
+                    }
+                }
+                slot(std::integral_constant<int, 0>{}); slot(std::integral_constant<int, 1>{});
+                slot(std::integral_constant<int, 2>{}); slot(std::integral_constant<int, 3>{});
+                slot(std::integral_constant<int, 4>{}); slot(std::integral_constant<int, 5>{});
+                slot(std::integral_constant<int, 6>{}); slot(std::integral_constant<int, 7>{});
+                slot(std::integral_constant<int, 8>{}); slot(std::integral_constant<int, 9>{});
+                slot(std::integral_constant<int, 10>{}); slot(std::integral_constant<int, 11>{});
+                if (near_end(n, pn)) a_fix_tail(n, pn, buf ^ 1);
             }
             __syncthreads();
             buf ^= 1;
+        };
+        // (no way out of the loop between its three steps: an edge from there back to the loop head would carry
+        // loads that were just issued, and the first register reuse at the head would wait for them)
+        int prow = p_begin;
+        for (; prow + 3 <= p_end; prow += 3) {
+            step(std::integral_constant<int, 0>{}, prow);
+            step(std::integral_constant<int, 1>{}, prow + 1);
+            step(std::integral_constant<int, 2>{}, prow + 2);
         }
+        if (prow < p_end) step(std::integral_constant<int, 0>{}, prow);
+        if (prow + 1 < p_end) step(std::integral_constant<int, 1>{}, prow + 1);
     }
 
     float *out = p.part + (size_t)blockIdx.x * p.K * p.Kg;

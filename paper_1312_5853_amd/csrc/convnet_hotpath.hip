@@ -648,16 +648,19 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         a.part = reinterpret_cast<float *>(wsb + pl.part_off);
         a.N = pb.N; a.C = pb.C; a.H = pb.H; a.W = pb.W; a.K = pb.K; a.R = pb.R; a.S = pb.S; a.P = pb.P; a.Q = pb.Q;
         a.Kg = pl.Kg;
-        a.x_bs = pb.x_bs; a.y_bs = pb.y_bs;
-        a.dy_elems = (int64_t)(pb.N - 1) * pb.y_bs + (int64_t)pb.K * pb.P * pb.Q;
+        a.x_bs = (int)pb.x_bs; a.y_bs = (int)pb.y_bs;         // N * stride * 4 bytes < 2^31 (problem checks)
+        a.dy_elems = (int)((int64_t)(pb.N - 1) * pb.y_bs + (int64_t)pb.K * pb.P * pb.Q);
         a.splits = pl.rows_splits; a.units = pb.N * pl.rows_splits;
         a.ng = ceil_div(pb.Q, 8); a.nkb = ceil_div(pb.Q, 16); a.nnew = pb.R < 4 ? pb.R : 4;
         a.div_splits = make_fastdiv((uint32_t)a.splits);
         a.div_ng = make_fastdiv((uint32_t)a.ng);
+        const bool full = pb.S == 11 && a.nkb == 4;             // the first layer: compile-time extents
+        const void *kern = full ? reinterpret_cast<const void *>(wgrad_rows_bf16_kernel<true>)
+                                : reinterpret_cast<const void *>(wgrad_rows_bf16_kernel<false>);
         if (pl.rows_lds > 64 * 1024)
-            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_rows_bf16_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        hipLaunchKernelGGL(wgrad_rows_bf16_kernel, dim3(pl.rows_wgs), dim3(256), pl.rows_lds, st, a);
+            (void)hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (full) hipLaunchKernelGGL(wgrad_rows_bf16_kernel<true>, dim3(pl.rows_wgs), dim3(256), pl.rows_lds, st, a);
+        else hipLaunchKernelGGL(wgrad_rows_bf16_kernel<false>, dim3(pl.rows_wgs), dim3(256), pl.rows_lds, st, a);
         int rc = check_launch();
         if (rc != kStatusOk) return rc;
         const int count = pb.K * pl.Kg;

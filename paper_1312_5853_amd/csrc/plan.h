@@ -263,7 +263,7 @@ inline Plan make_plan(int op, const Problem &pb)
         pl.part_bytes = (pl.nsplit > 1 || staged) ? (size_t)pl.nsplit * pb.K * pb.C * RS * 4 : 0;
         if (pb.dtype == kDtypeBf16 && G == 1 && pb.stride == 4 && pb.pad == 2 && pb.S <= 11 && pb.R <= 12 &&
             pb.C <= 4 && pl.Kg <= 384 && pb.K <= 96 && pb.Q <= 64 && pb.W % 8 == 0 && pb.x_bs % 8 == 0) {
-            const int lds = 2 * 96 * 144 + pb.C * 16 * pb.S * 144;
+            const int lds = 2 * 96 * 144 + pb.C * 16 * pb.S * 144 + (255 * 16 + 10 * 144 + 16);   // + trash area
             if (lds <= 150 * 1024) {
                 pl.rows = true;
                 pl.rows_lds = lds;
