@@ -757,7 +757,8 @@ int pool_fwd_typed(const void *x, void *y, int64_t planes, int H, int W, int PH,
 {
     const int64_t total = planes * PH * PW;
     hipLaunchKernelGGL((maxpool_fwd_kernel<RELU, T>), dim3(grid1d(total, 256)), dim3(256), 0, st,
-                       static_cast<const T *>(x), static_cast<T *>(y), total, H, W, PH, PW);
+                       static_cast<const T *>(x), static_cast<T *>(y), total, H, W, PH, PW,
+                       make_fastdiv((uint32_t)PW), make_fastdiv((uint32_t)PH));
     return check_launch();
 }
 
@@ -789,7 +790,7 @@ int pool_bwd_typed(const void *x, const void *dy, void *dx, int64_t planes, int 
         const int group = small ? (256 * 16) / HW : 1;
         int64_t blocks = (planes + group - 1) / group;
         if (blocks > 256 * 6) blocks = 256 * 6;
-        const size_t lds = (size_t)group * HW * 8;        // inputs + accumulators
+        const size_t lds = ((size_t)group * HW + 2) * 8;  // inputs + accumulators, one element of slack each
         const FastDiv dPP = make_fastdiv(PP), dPW = make_fastdiv(PW);
         if (small) {
             hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 16, T>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,

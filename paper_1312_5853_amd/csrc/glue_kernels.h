@@ -156,14 +156,24 @@ __device__ __forceinline__ int pool_argmax(const T *__restrict__ xp, int W, int 
 
 template <bool RELU, typename T>
 __global__ void maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int64_t total,
-                                   int H, int W, int PH, int PW)
+                                   int H, int W, int PH, int PW, FastDiv dPW, FastDiv dPH)
 {
     int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= total) return;
-    int j = (int)(t % PW);
-    int64_t u = t / PW;
-    int i = (int)(u % PH);
-    int64_t pl = u / PH;
+    int i, j;
+    int64_t pl;
+    if (total < ((int64_t)1 << 31)) {                // the usual case: two multiplies instead of 64-bit divisions
+        const uint32_t u = fastdiv((uint32_t)t, dPW);
+        j = (int)((uint32_t)t - u * (uint32_t)PW);
+        const uint32_t q = fastdiv(u, dPH);
+        i = (int)(u - q * (uint32_t)PH);
+        pl = q;
+    } else {
+        j = (int)(t % PW);
+        const int64_t u = t / PW;
+        i = (int)(u % PH);
+        pl = u / PH;
+    }
     float m;
     pool_argmax(x + pl * H * W, W, i, j, m);
     st_elem(y, t, RELU ? (m > 0.f ? m : 0.f) : m);
@@ -233,8 +243,11 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
     constexpr int KX = NR / EV + (EV > 1), KG = NG / EV + (EV > 1);
     extern __shared__ float pool_lds[];
     const int HW = H * W, PP = PH * PW;
+    // Element e of the staged group sits at index e + (shift of its pair grid): a bfloat16 pair then is two
+    // adjacent floats at an 8-byte aligned LDS address, one store / one load instead of two with a two-way bank
+    // conflict.  Both arrays have room for that one extra element.
     float *sx = pool_lds;                            // group * HW inputs
-    float *sacc = pool_lds + group * HW;             // group * HW routed gradients
+    float *sacc = pool_lds + ((group * HW + 2) & ~1);    // group * HW routed gradients
     const int tid = threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * group;
     float xr[KX][EV], gr[KG][EV];
@@ -258,13 +271,23 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
         const int np = (int)min((int64_t)group, planes - pl0);
         T *og = dx + pl0 * HW;
         const int os = align_shift(og);
+        const int xc = xs;                           // (xs moves on with the prefetch below)
+        float *const sxe = sx + xc, *const sae = sacc + xc;
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-        for (int k = 0; k < KX; ++k)
+        for (int k = 0; k < KX; ++k) {
+            const int e0 = EV * (tid + 256 * k) - xc;
+            if (EV == 2 && e0 >= 0 && e0 + 1 < np * HW) {
+                *reinterpret_cast<f32x2 *>(sxe + e0) = f32x2{xr[k][0], xr[k][EV - 1]};
+                *reinterpret_cast<f32x2 *>(sae + e0) = f32x2{0.f, 0.f};
+            } else {
 #pragma unroll
-            for (int u = 0; u < EV; ++u) {
-                const int e = EV * (tid + 256 * k) - xs + u;
-                if (e >= 0 && e < np * HW) { sx[e] = xr[k][u]; sacc[e] = 0.f; }
+                for (int u = 0; u < EV; ++u) {
+                    const int e = e0 + u;
+                    if (e >= 0 && e < np * HW) { sxe[e] = xr[k][u]; sae[e] = 0.f; }
+                }
             }
+        }
         __syncthreads();
         // every window's first maximum, once; cls = parity class (i % 2, j % 2) of the window, -1 = no window
         int best[KG][EV], cls[KG][EV];
@@ -279,7 +302,7 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
                     const int pl = (int)fastdiv((uint32_t)o, dPP), rem = o - pl * PP;
                     const int i = (int)fastdiv((uint32_t)rem, dPW), j = rem - i * PW;
                     float m;
-                    best[k][u] = pl * HW + pool_argmax(sx + pl * HW, W, i, j, m);
+                    best[k][u] = pl * HW + pool_argmax(sxe + pl * HW, W, i, j, m);
                     cls[k][u] = (i & 1) * 2 + (j & 1);
                 }
             }
@@ -292,23 +315,31 @@ __global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x
             for (int k = 0; k < KG; ++k)
 #pragma unroll
                 for (int u = 0; u < EV; ++u)
-                    if (cls[k][u] == c) sacc[best[k][u]] += g[k][u];
+                    if (cls[k][u] == c) sae[best[k][u]] += g[k][u];
             __syncthreads();
         }
 #pragma unroll
         for (int k = 0; k < KX; ++k) {
             float res[EV];
+            const int e0 = EV * (tid + 256 * k) - os;
+            if (EV == 2 && os == xc && e0 >= 0 && e0 + 1 < np * HW) {
+                const f32x2 a = *reinterpret_cast<const f32x2 *>(sae + e0);
+                const f32x2 v = *reinterpret_cast<const f32x2 *>(sxe + e0);
+                res[0] = (RELU && !(v[0] > 0.f)) ? 0.f : a[0];
+                res[EV - 1] = (RELU && !(v[1] > 0.f)) ? 0.f : a[1];
+            } else {
 #pragma unroll
-            for (int u = 0; u < EV; ++u) {
-                const int e = EV * (tid + 256 * k) - os + u;
-                float sum = 0.f;
-                if (e >= 0 && e < np * HW) {
-                    sum = sacc[e];
-                    if (RELU && !(sx[e] > 0.f)) sum = 0.f;
+                for (int u = 0; u < EV; ++u) {
+                    const int e = e0 + u;
+                    float sum = 0.f;
+                    if (e >= 0 && e < np * HW) {
+                        sum = sae[e];
+                        if (RELU && !(sxe[e] > 0.f)) sum = 0.f;
+                    }
+                    res[u] = sum;
                 }
-                res[u] = sum;
             }
-            st_group(og, EV * (tid + 256 * k) - os, np * HW, res);
+            st_group(og, e0, np * HW, res);
         }
         __syncthreads();
     }
