@@ -121,9 +121,10 @@ int conv_bwd_filter(const void *x, const void *dy, void *dw,
  * and frees nothing, on the device or through any library.
  *   - A pass whose conv_workspace_bytes(CONV_OP_BWD_FILTER, ...) exceeds
  *     CONV_NOALLOC_SCRATCH_BYTES returns CONV_ERR_SCRATCH_LIMIT before anything
- *     is enqueued.  fp32: the partial sums do not grow with N, and all five
- *     layers of the stack fit at any batch size.  bf16: the packed copies grow
- *     with N (the third layer needs 31 MB at N = 16, 46 MB at N = 64).
+ *     is enqueued.  fp32: the partial sums do not grow with N (at most 36 MB,
+ *     the first layer's 256 partial results), and all five layers of the stack
+ *     fit at any batch size.  bf16: the packed copies grow with N (the third
+ *     layer needs 31 MB at N = 16, 46 MB at N = 64).
  *   - All calls on one GPU share that GPU's array: calls that overlap in time
  *     on one GPU (different streams or threads) race.  Calls on one stream are
  *     ordered.  The array keeps the previous call's contents; every call
@@ -131,7 +132,7 @@ int conv_bwd_filter(const void *x, const void *dy, void *dw,
  *   - The first call on a device looks the array's address up
  *     (hipGetSymbolAddress); make that call before a stream capture begins.
  */
-#define CONV_NOALLOC_SCRATCH_BYTES (32u << 20)
+#define CONV_NOALLOC_SCRATCH_BYTES (48u << 20)
 int conv_bwd_filter_noalloc(const void *x, const void *dy, void *dw,
                             int N, int C, int H, int W, int K, int R, int S, int stride, int pad,
                             int dtype, void *stream);

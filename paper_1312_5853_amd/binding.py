@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libconvnet_hotpath.so")
 OK = 0
 ERR_INVALID_ARG, ERR_TOO_LARGE, ERR_BAD_DTYPE, ERR_WORKSPACE, ERR_MISALIGNED, ERR_HIP = -1, -2, -3, -4, -5, -6
 ERR_SCRATCH_LIMIT = -7
-NOALLOC_SCRATCH_BYTES = 32 << 20
+NOALLOC_SCRATCH_BYTES = 48 << 20
 DTYPE_F32, DTYPE_BF16, DTYPE_BF16_OUT_BF16 = 0, 1, 2
 OP_FWD, OP_BWD_DATA, OP_BWD_FILTER = 0, 1, 2
 

@@ -13,7 +13,7 @@ LIB = os.path.join(_HERE, "libconvnet_hotpath.so")
 CEILING_SRC = os.path.join(_HERE, "csrc", "mfma_ceiling.hip")
 CEILING_EXE = os.path.join(_HERE, "mfma_ceiling")
 DEPS = [SRC] + [os.path.join(_HERE, "csrc", h) for h in (
-    "plan.h", "fastdiv.h", "device_common.h", "conv_colgemm_kernels.h", "conv_bf16_dma_kernels.h", "conv_wgrad_rows_bf16_kernels.h",
+    "plan.h", "fastdiv.h", "device_common.h", "conv_colgemm_kernels.h", "conv_bf16_dma_kernels.h", "conv_wgrad_rows_kernels.h",
     "conv_wgrad_kernels.h", "fc_kernels.h",
     "glue_kernels.h")] + [os.path.join(os.path.dirname(_HERE), "include", "convnet_hotpath.h")]
 

@@ -1,7 +1,10 @@
-// Backward-filter for a stride-4 layer with few input channels (the 11x11 first layer) and bf16 tensors, on the
-// bf16 matrix instruction.  Part of convnet_hotpath.hip: included there, inside its anonymous namespace, after
-// conv_bf16_dma_kernels.h.
+// Backward-filter for layers with few input channels (the 11x11 stride-4 first layer): a work-group keeps the whole
+// K x (C*R*S) result in registers and walks the output rows of its share of the images with the input rows staged in
+// LDS.  Two kernels: bf16 tensors on the bf16 matrix instruction (stride 4, pad 2; below) and fp32 tensors on the
+// fp32 matrix instruction (second half of the file).
+// Part of convnet_hotpath.hip: included there, inside its anonymous namespace, after conv_bf16_dma_kernels.h.
 //
+// --- bf16 ---
 // GEMM view: dw[k][(c, r, s)] = sum over (n, p, q) of dy[n][k][p][q] * x[n][c][4p + r - 2][4q + s - 2], fp32 sums.
 // v_mfma_f32_32x32x16_bf16 wants, per lane, eight CONSECUTIVE reduction indices of one row (one column) in a
 // register quad.  The reduction runs along q inside one output row p (at most 64 positions, processed as
@@ -394,5 +397,197 @@ __global__ __launch_bounds__(256, 1) void wgrad_rows_bf16_kernel(const WgradRows
                 const int row = 32 * i + (v >> 2) * 8 + half * 4 + (v & 3);
                 if (row < p.K && col < p.Kg) out[(size_t)row * p.Kg + col] = acc[i][t][v];
             }
+        }
+}
+
+// ---------------------------------------------------------------------------
+// The same decomposition for fp32 tensors (v_mfma_f32_32x32x2_f32: one value per lane and operand, so no
+// alignment question and no shifted copies): a work-group owns the whole K x (C*R*S) result for its (image,
+// output-row range) units and walks the output rows.  Twelve waves, three per SIMD -- a wave that waits for its
+// LDS reads or at the barrier leaves the matrix pipe to the other two --, each with the 96 rows x 32 taps of one
+// column block in registers (3 blocks of 32 x 32).  Per output row p the LDS holds
+//   xr[c][ring row][WP]   the input rows stride*p .. (fp32, zero padding columns in place, ring of 16 rows per
+//                         channel; a step adds the `stride` rows the next output row needs)
+//   dyr[buf][m][58]       dy(n, m, p, 0..Q-1), zero from Q on; pitch 58: the 64 lanes (m, k parity) of one read
+//                         cover the 64 banks once
+// and reduction pair t (positions 2t, 2t+1) costs four single-word LDS reads per wave -- three dy values, one
+// input value at patch offset row*WP + stride*(2t + k) + s -- for three matrix instructions of 64 clocks, all
+// with immediate offsets.  One output row is 9 * ceil(Q/2) matrix instructions per SIMD (16 k clocks for the
+// first layer) against a few hundred clocks of staging, so the next row's loads simply sit in registers across
+// the row.
+// ---------------------------------------------------------------------------
+constexpr int kRowsF32Threads = 768;
+constexpr int kRowsF32DyPitch = 58;
+constexpr int kRowsF32DyBuf = kRowsM * kRowsF32DyPitch;       // floats per dy buffer
+constexpr int kRowsF32Slack = 64;                             // floats behind the input rows: reads one pair too far
+
+struct WgradRowsF32Args {
+    const float *x, *dy;
+    float *part;                 // [work-group][K][Kg]
+    int N, C, H, W, K, R, S, P, Q, Kg, stride, pad;
+    int x_bs, y_bs;
+    int splits, units;
+    int WP;                      // LDS row pitch in floats: >= W + 2 * pad, = 48 mod 64
+    int nnew;                    // input rows a step adds per channel: min(R, stride)
+    FastDiv div_splits;
+};
+
+__global__ __launch_bounds__(kRowsF32Threads, 1) void wgrad_rows_f32_kernel(const WgradRowsF32Args p)
+{
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    float *const dyr = lds_fast;                               // two buffers
+    float *const xr = lds_fast + 2 * kRowsF32DyBuf;
+    const int tid = threadIdx.x, lane = tid & 63, wave = uniform(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int xchan = kRowsRing * p.WP;
+    const int lds_floats = 2 * kRowsF32DyBuf + p.C * xchan + kRowsF32Slack;
+    for (int o = tid; o < lds_floats; o += kRowsF32Threads) lds_fast[o] = 0.f;   // padding, positions >= Q: zero
+
+    // this lane's tap: float offset of (c, ring row 0, column s + stride * k parity) and the filter row r
+    int tap_off, tap_r;
+    {
+        const int j = 32 * wave + l32;
+        const int jj = j < p.Kg ? j : 0;
+        const int c = jj / (p.R * p.S), rs = jj - c * (p.R * p.S);
+        const int r = rs / p.S, s = rs - r * p.S;
+        tap_off = c * xchan + s + p.stride * half;
+        tap_r = r;
+    }
+
+    f32x16 acc[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+
+    // Staging with addresses that cost nothing per element: thread t owns position q = t % 64 of the dy rows
+    // m = t / 64 + 12u (u = 0..7) and column w = t % 256 of the new input rows (c, i) = slot t / 256 + 3v
+    // (v = 0..5, slot = 4c + i); what changes from element to element is uniform.
+    constexpr int NDY = kRowsM / 12;                           // 8 dy values per thread
+    constexpr int NXR = 6;
+    const int dq = tid & 63, dm = tid >> 6;
+    const bool dq_on = dq < p.Q;
+    const int xw = tid & 255, xs0 = tid >> 8;
+    const int nfull = p.Q >> 1;                                // reduction pairs with both positions
+
+    for (int unit = blockIdx.x; unit < p.units; unit += gridDim.x) {
+        const int n = (int)fastdiv((uint32_t)unit, p.div_splits);
+        const int sp = unit - n * p.splits;
+        const int p_begin = (int)((int64_t)p.P * sp / p.splits), p_end = (int)((int64_t)p.P * (sp + 1) / p.splits);
+        if (p_begin >= p_end) continue;
+        const float *xn = p.x + (size_t)n * p.x_bs, *dyn = p.dy + (size_t)n * p.y_bs;
+        __syncthreads();
+        // input rows first_hh .. first_hh + rows - 1 (image row = hh - pad) of every channel; rows outside the
+        // image are zero.  (Loads read a clamped, always valid address and nothing touches the value before the
+        // matching store: a select on a loaded value would make the thread wait for each load in turn.)
+        auto load_x = [&](float (&v)[NXR], int first_hh, int rows) {
+            const int w = min(xw, p.W - 1);
+#pragma unroll
+            for (int u = 0; u < NXR; ++u) {
+                const int slot = xs0 + 3 * u, c = slot >> 2, i = slot & 3;
+                const int h = min(max(first_hh + i - p.pad, 0), p.H - 1);
+                v[u] = xn[(min(c, p.C - 1) * p.H + h) * p.W + w];
+            }
+        };
+        auto store_x = [&](const float (&v)[NXR], int first_hh, int rows) {
+#pragma unroll
+            for (int u = 0; u < NXR; ++u) {
+                const int slot = xs0 + 3 * u, c = slot >> 2, i = slot & 3;
+                if (c < p.C && i < rows && xw < p.W) {
+                    const bool inside = (unsigned)(first_hh + i - p.pad) < (unsigned)p.H;
+                    xr[c * xchan + ((first_hh + i) & (kRowsRing - 1)) * p.WP + p.pad + xw] = inside ? v[u] : 0.f;
+                }
+            }
+        };
+        auto load_dy = [&](float (&v)[NDY], int prow) {
+            const float *src = dyn + prow * p.Q + min(dq, p.Q - 1);
+#pragma unroll
+            for (int u = 0; u < NDY; ++u) v[u] = src[min(dm + 12 * u, p.K - 1) * p.P * p.Q];
+        };
+        auto store_dy = [&](const float (&v)[NDY], int buf) {
+            float *dst = dyr + buf * kRowsF32DyBuf + dm * kRowsF32DyPitch + dq;
+            if (dq_on) {
+#pragma unroll
+                for (int u = 0; u < NDY; ++u)
+                    if (dm + 12 * u < p.K) dst[12 * u * kRowsF32DyPitch] = v[u];
+            }
+        };
+        float vx[NXR], vdy[NDY];
+        // every input row of the first output row (R rows, in passes of nnew), and its dy row
+        for (int r0 = 0; r0 < p.R; r0 += p.nnew) {
+            const int rows = min(p.nnew, p.R - r0);
+            load_x(vx, p.stride * p_begin + r0, rows);
+            store_x(vx, p.stride * p_begin + r0, rows);
+        }
+        load_dy(vdy, p_begin);
+        store_dy(vdy, 0);
+        __syncthreads();
+        int buf = 0;
+        for (int prow = p_begin; prow < p_end; ++prow) {
+            const bool more = prow + 1 < p_end;
+            const int hh_new = p.stride * (prow + 1) + p.R - p.nnew;
+            if (more) {
+                load_x(vx, hh_new, p.nnew);
+                load_dy(vdy, prow + 1);
+            }
+            const float *Ab = dyr + buf * kRowsF32DyBuf + l32 * kRowsF32DyPitch + half;
+            const float *Bb = xr + tap_off + ((p.stride * prow + tap_r) & (kRowsRing - 1)) * p.WP;
+            float fa[2][3], fb[2];
+            // operands of pair tp; a pair past the last one may be read (never used): the reads stay inside LDS
+            auto read = [&](int set, int tp) {
+#pragma unroll
+                for (int i = 0; i < 3; ++i) fa[set][i] = Ab[i * 32 * kRowsF32DyPitch + 2 * tp];
+                fb[set] = Bb[2 * p.stride * tp];
+            };
+            auto mfmas = [&](int set) {
+#pragma unroll
+                for (int i = 0; i < 3; ++i)
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[set][i], fb[set], acc[i], 0, 0, 0);
+            };
+            read(0, 0);
+            int tp = 0;
+            // no branch inside (the waits count the reads), and the order is pinned: the reads of the next pair
+            // are issued before this pair's matrix instructions
+            for (; tp + 2 <= nfull; tp += 2) {
+                read(1, tp + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mfmas(0);
+                __builtin_amdgcn_sched_barrier(0);
+                read(0, tp + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                mfmas(1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (tp < nfull) {                                   // set 0 holds pair tp
+                if (p.Q & 1) read(1, tp + 1);
+                mfmas(0);
+                ++tp;
+                if (p.Q & 1) {
+                    // last position alone: the missing odd position reads dy's zero at Q and, for the input, that
+                    // same zero word, so that no input value is multiplied by it
+                    if (half) fb[1] = fa[1][0];
+                    mfmas(1);
+                }
+            } else if (p.Q & 1) {                               // set 0 holds the half pair nfull
+                if (half) fb[0] = fa[0][0];
+                mfmas(0);
+            }
+            if (more) {
+                store_x(vx, hh_new, p.nnew);
+                store_dy(vdy, buf ^ 1);
+            }
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    float *out = p.part + (size_t)blockIdx.x * p.K * p.Kg;
+    const int col = 32 * wave + l32;
+#pragma unroll
+    for (int i = 0; i < 3; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = 32 * i + (v >> 2) * 8 + half * 4 + (v & 3);
+            if (row < p.K && col < p.Kg) out[(size_t)row * p.Kg + col] = acc[i][v];
         }
 }

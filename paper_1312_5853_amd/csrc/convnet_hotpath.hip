@@ -42,7 +42,7 @@ __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirs
 #include "device_common.h"
 #include "conv_colgemm_kernels.h"
 #include "conv_bf16_dma_kernels.h"
-#include "conv_wgrad_rows_bf16_kernels.h"
+#include "conv_wgrad_rows_kernels.h"
 #include "conv_wgrad_kernels.h"
 #include "fc_kernels.h"
 #include "glue_kernels.h"
@@ -661,6 +661,32 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
             (void)hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (full) hipLaunchKernelGGL(wgrad_rows_bf16_kernel<true>, dim3(pl.rows_wgs), dim3(256), pl.rows_lds, st, a);
         else hipLaunchKernelGGL(wgrad_rows_bf16_kernel<false>, dim3(pl.rows_wgs), dim3(256), pl.rows_lds, st, a);
+        int rc = check_launch();
+        if (rc != kStatusOk) return rc;
+        const int count = pb.K * pl.Kg;
+        if (count % 4 == 0 && reinterpret_cast<uintptr_t>(dw) % 16 == 0)
+            hipLaunchKernelGGL(reduce_partials_x4, dim3(grid1d(count, 64)), dim3(256), 0, st, a.part,
+                               static_cast<float *>(dw), count, pl.rows_wgs);
+        else
+            hipLaunchKernelGGL(reduce_partials, dim3(grid1d(count, 64)), dim3(256), 0, st, a.part,
+                               static_cast<float *>(dw), count, pl.rows_wgs);
+        return check_launch();
+    }
+    if (pl.rows_f32) {
+        // few channels, fp32: the input rows of an output row in LDS, one partial result per work-group
+        WgradRowsF32Args a;
+        a.x = static_cast<const float *>(x); a.dy = static_cast<const float *>(dy);
+        a.part = reinterpret_cast<float *>(wsb + pl.part_off);
+        a.N = pb.N; a.C = pb.C; a.H = pb.H; a.W = pb.W; a.K = pb.K; a.R = pb.R; a.S = pb.S; a.P = pb.P; a.Q = pb.Q;
+        a.Kg = pl.Kg; a.stride = pb.stride; a.pad = pb.pad;
+        a.x_bs = (int)pb.x_bs; a.y_bs = (int)pb.y_bs;
+        a.splits = pl.rows_splits; a.units = pb.N * pl.rows_splits;
+        a.WP = pl.rows_wp; a.nnew = pb.R < pb.stride ? pb.R : pb.stride;
+        a.div_splits = make_fastdiv((uint32_t)a.splits);
+        if (pl.rows_lds > 64 * 1024)
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_rows_f32_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        hipLaunchKernelGGL(wgrad_rows_f32_kernel, dim3(pl.rows_wgs), dim3(kRowsF32Threads), pl.rows_lds, st, a);
         int rc = check_launch();
         if (rc != kStatusOk) return rc;
         const int count = pb.K * pl.Kg;

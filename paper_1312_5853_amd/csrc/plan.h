@@ -160,6 +160,9 @@ struct Plan {
     // rows_wgs work-groups with one partial result each, rows_lds bytes of LDS
     bool rows;
     int rows_splits, rows_wgs, rows_lds;
+    // the same decomposition for fp32 tensors (any stride up to 4): rows_wp = LDS pitch of a staged input row
+    bool rows_f32;
+    int rows_wp;
     size_t total;
 };
 
@@ -274,6 +277,23 @@ inline Plan make_plan(int op, const Problem &pb)
                 pl.rows_wgs = units < 256 ? (int)units : 256;
                 const size_t need = (size_t)pl.rows_wgs * pb.K * pl.Kg * 4;
                 if (need > pl.part_bytes) pl.part_bytes = need;     // the table path stays available at run time
+            }
+        }
+        if (pb.dtype == kDtypeF32 && G == 1 && pb.C <= 4 && pb.K > 48 && pb.K <= 96 && pl.Kg > 128 && pl.Kg <= 384 &&
+            pb.Q <= 57 && pb.R + pb.stride <= 16 && pb.stride <= 4 && pb.W <= 256) {
+            int wp = pb.W + 2 * pb.pad;                      // pitch = 48 mod 64: taps of up to four filter rows
+            wp += (48 - wp % 64 + 64) % 64;                  // read by one wave fall into different banks
+            const int64_t lds = ((int64_t)2 * 96 * 58 + (int64_t)pb.C * 16 * wp + 64) * 4;   // + slack
+            if (lds <= 150 * 1024) {
+                pl.rows_f32 = true;
+                pl.rows_lds = (int)lds;
+                pl.rows_wp = wp;
+                int splits = ceil_div(256, pb.N);
+                if (splits > pb.P) splits = pb.P;
+                pl.rows_splits = splits;
+                const int64_t units = (int64_t)pb.N * splits;
+                pl.rows_wgs = units < 256 ? (int)units : 256;
+                pl.part_bytes = (size_t)pl.rows_wgs * pb.K * pl.Kg * 4;
             }
         }
         off += round_up64(pl.part_bytes * (pl.fused_groups ? G : 1), 256);

@@ -101,6 +101,13 @@ ODD_SHAPES = [
     (1, 16, 3, 3, 1, 3, 3, 1, 0),          # dy has one element
     (3, 16, 1, 1, 1, 1, 1, 1, 0),          # dy has three elements
     (5, 16, 9, 11, 7, 3, 3, 2, 1),         # stride 2: P*Q = 5*6 = 30
+    # backward-filter with at most four channels, 49..96 filters and 129..384 taps (input rows staged in LDS,
+    # one partial result per work-group): an odd row length (last reduction pair half empty), stride 1 with one
+    # new row per step, more (image, row range) units than work-groups, a filter that fills the ring of 16 rows
+    (3, 3, 40, 120, 96, 11, 11, 4, 2),
+    (2, 4, 14, 17, 64, 5, 7, 1, 2),
+    (300, 2, 9, 12, 50, 9, 8, 3, 1),
+    (2, 3, 30, 20, 96, 12, 4, 4, 0),
 ]
 
 

@@ -223,7 +223,7 @@ def test_noalloc_entry_point_checks_before_any_gpu_call(lib):
             dims = (N, L["C"], L["H"], L["W"], L["K"], L["R"], L["S"], L["stride"], L["pad"])
             assert lib.conv_workspace_bytes(b.OP_BWD_FILTER, *dims, 0) <= b.NOALLOC_SCRATCH_BYTES, (N, name)
     header = open(HEADER).read()
-    assert "#define CONV_NOALLOC_SCRATCH_BYTES (32u << 20)" in header
+    assert "#define CONV_NOALLOC_SCRATCH_BYTES (48u << 20)" in header
 
 
 def test_convert_argument_checks(lib):
