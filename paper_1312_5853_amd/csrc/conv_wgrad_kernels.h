@@ -656,7 +656,7 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(const WgradFastArg
 // pad of the next), a row out of range in the zero rows above and below.  No
 // masks and no per-element addresses are left; positions where dy is zero cost
 // (Jy / (P*Q) - 1) extra matrix work, 9 % at 13x13.
-// The x loads are 2-byte aligned only (the tap shift is arbitrary).
+// The x loads are 4-byte aligned: xp is kept twice, the second copy moved up by one element for the odd tap shifts.
 // Columns in (r, s, c) order, partials [split][K][R*S*C] as in wgrad_fast_kernel.
 // ---------------------------------------------------------------------------
 struct WgradLinArgs {
@@ -673,7 +673,7 @@ struct WgradLinArgs {
     FastDiv div_c, div_s, div_g;
 };
 
-typedef u32x4 u32x4_align2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_align4 __attribute__((aligned(4)));
 
 template <int TM, int TN, int WM, int WN>
 __global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const WgradLinArgs p)
@@ -715,7 +715,8 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const Wgrad
         col = col < p.ncols ? col : 0;
         const int rs = (int)fastdiv((uint32_t)col, p.div_c), c = col - rs * p.C;
         const int r = (int)fastdiv((uint32_t)rs, p.div_s), sx = rs - r * p.S;
-        bbase[i] = (uint32_t)c * (uint32_t)p.row_x_bytes + 2u * (uint32_t)(r * p.Wq + sx);
+        const int shift = r * p.Wq + sx;                   // odd shifts read the copy that is moved up by one element
+        bbase[i] = (uint32_t)(c + (shift & 1) * p.C) * (uint32_t)p.row_x_bytes + 2u * (uint32_t)(shift & ~1);
     }
     // position of this thread's group: g = step*8 + jg = n*G + gg
     int n, gg;
@@ -741,7 +742,7 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const Wgrad
         if (i == RA - 1) aoff += 128u;
     };
     auto slot_b = [&](int set, int i) {
-        breg[set][i] = *reinterpret_cast<const u32x4_align2 *>(xp + (bbase[i] + boff));
+        breg[set][i] = *reinterpret_cast<const u32x4_align4 *>(xp + (bbase[i] + boff));
     };
     auto load_step = [&](int set) {
         slot_pos();
@@ -890,7 +891,10 @@ __device__ __forceinline__ void pack_dy_lin(int64_t i8, const unsigned short *__
 }
 
 // xp[c][n][e], e < Jx: padded row hh = e / Wq, column ww = e % Wq; x(n, c, hh - pad, ww - pad) where inside, else 0.
-// One thread per 8 consecutive elements (Jx is a multiple of 8).
+// One thread per 8 consecutive elements (Jx is a multiple of 8).  A second copy follows the first, moved up by one
+// element (copy 1 at e holds copy 0 at e + 1, zero at the end of a row): a tap with an odd shift reads it at shift - 1,
+// so that every operand load of the main kernel is 4-byte aligned -- 16-byte loads from addresses that are only 2-byte
+// aligned run at a quarter of the rate on this chip.
 __device__ __forceinline__ void pack_x_lin(int64_t i8, const unsigned short *__restrict__ x,
                                            unsigned short *__restrict__ xp, int N, int C, int H, int W, int pad, int Wq,
                                            int Jx, int64_t x_bs, FastDiv div_jx, FastDiv div_wq)
@@ -901,16 +905,20 @@ __device__ __forceinline__ void pack_x_lin(int64_t i8, const unsigned short *__r
     const uint32_t c = cn / (uint32_t)N, n = cn - c * (uint32_t)N;
     uint32_t hh = fastdiv(e, div_wq), ww = e - hh * (uint32_t)Wq;
     const unsigned short *src = x + n * x_bs + (int64_t)c * H * W;
-    unsigned short v[8];
+    unsigned short v[9];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
+    for (int t = 0; t < 9; ++t) {
         const int h = (int)hh - pad, w = (int)ww - pad;
-        v[t] = ((unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) ? src[h * W + w] : (unsigned short)0;
+        v[t] = (e + t < (uint32_t)Jx && (unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W) ? src[h * W + w]
+                                                                                                 : (unsigned short)0;
         if (++ww == (uint32_t)Wq) { ww = 0; ++hh; }
     }
     u32x4 o = {(uint32_t)v[0] | (uint32_t)v[1] << 16, (uint32_t)v[2] | (uint32_t)v[3] << 16,
                (uint32_t)v[4] | (uint32_t)v[5] << 16, (uint32_t)v[6] | (uint32_t)v[7] << 16};
     reinterpret_cast<u32x4 *>(xp)[i8] = o;
+    u32x4 o1 = {(uint32_t)v[1] | (uint32_t)v[2] << 16, (uint32_t)v[3] | (uint32_t)v[4] << 16,
+                (uint32_t)v[5] | (uint32_t)v[6] << 16, (uint32_t)v[7] | (uint32_t)v[8] << 16};
+    reinterpret_cast<u32x4 *>(xp + (int64_t)C * N * Jx)[i8] = o1;
 }
 
 // Both packing passes in one launch: blocks [0, dy_blocks) pack dy, the rest pack x.

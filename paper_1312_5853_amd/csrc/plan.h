@@ -249,7 +249,8 @@ inline Plan make_plan(int op, const Problem &pb)
             const int jy = round_up(pb.P * wq, 8);
             const int jx = round_up(jy + (pb.R - 1) * wq + pb.S, 8);
             const int64_t steps = ((int64_t)pb.N * jy + 63) / 64;
-            const int64_t dy_bytes = (int64_t)pb.K * steps * 64 * 2, x_bytes = (int64_t)pb.C * pb.N * jx * 2;
+            // (x is packed twice: the second copy, moved up by one element, serves the taps with an odd shift)
+            const int64_t dy_bytes = (int64_t)pb.K * steps * 64 * 2, x_bytes = (int64_t)2 * pb.C * pb.N * jx * 2;
             if (jy >= 64 && dy_bytes < kMaxSpanBytes && x_bytes < kMaxSpanBytes) {
                 pl.lin = true;
                 pl.lin_wq = wq; pl.lin_jy = jy; pl.lin_jx = jx; pl.lin_steps = (int)steps;
