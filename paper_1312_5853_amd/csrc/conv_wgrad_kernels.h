@@ -865,13 +865,218 @@ __global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const Wgrad
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same pass with both operands loaded from global memory straight into LDS (16 bytes per lane, no staging
+// registers and no LDS store instructions: at bf16 matrix rates the 32 KB a 128 x 128 tile stores into LDS per
+// 64-position step take as long as its matrix work, see conv_bf16_dma_kernels.h).  One eight-wave work-group per
+// CU owns a 128 x 256 tile (rows: filters, columns: taps (r, s, c)) for a range of the reduction; three LDS buffers
+// of (128 + 256) rows of 64 positions = 48 KB each; the loads of step s + 2 are in flight while step s is multiplied.
+// Operand layouts (pack_lin):
+//   dyT[step][Kpad][64]   dy with the zero padding in place as in dyp, but step-major, and the eight 16-byte chunks of
+//                         a row stored at position chunk ^ swz(row), swz(row) = (row >> 1) & 7: a step's 128 rows are
+//                         one contiguous 16 KB block that is copied linearly, and the 16 lanes of a fragment read
+//                         cover the 64 banks
+//   xp                    as above (two copies); lane (row, slot) of a load fetches chunk slot ^ swz(row) of its column's
+//                         row, so the LDS rows come out swizzled the same way
+// ---------------------------------------------------------------------------
+struct WgradLinDmaArgs {
+    const unsigned short *dyT;
+    const unsigned short *xp;
+    float *part;
+    int K, Kpad, C, ncols;
+    int S, Wq;
+    int N, G, Jx;             // G = Jy / 8 groups of 8 positions per image
+    int row_x_bytes;          // bytes per xp row (N * Jx * 2)
+    int steps, steps_per_split;
+    int mtiles, ntiles, nunits, units_per_xcd;
+    FastDiv div_c, div_s, div_g;
+};
+
+template <int TM, int TN, int WM, int WN>
+__global__ __launch_bounds__(WM * WN * 64, 1) void wgrad_bf16_lin_dma_kernel(const WgradLinDmaArgs p)
+{
+    constexpr int NT = WM * WN * 64;
+    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
+    constexpr int RB = 128, CH = 8, NK = 4;              // 64 positions per row and step
+    constexpr int NA = BM * CH / NT, NB = BN * CH / NT, NL = NA + NB;
+    constexpr int BUF = (BM + BN) * RB;
+    static_assert((BM * CH) % NT == 0 && (BN * CH) % NT == 0, "whole wavefront loads");
+    static_assert(NB % 2 == 0, "a thread's loads alternate between two chunks");
+
+    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
+    const char *const lds = reinterpret_cast<const char *>(lds_fast);
+    const unsigned lds_base = (unsigned)(size_t)lds_fast;
+
+    const int bid = blockIdx.x;
+    const int idx = bid >> 3;
+    const int unit = (bid & 7) * p.units_per_xcd + idx;
+    if (idx >= p.units_per_xcd || unit >= p.nunits) return;
+    const int ntile = p.mtiles * p.ntiles;
+    const int split = unit / ntile;
+    const int tile = unit - split * ntile;
+    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
+    const int m0 = mt * BM, n0 = nt * BN;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = uniform(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    const int step_begin = split * p.steps_per_split;
+    const int nsteps = min(p.steps - step_begin, p.steps_per_split);
+
+    // x loads: load u of this thread fills chunk slot (lane % 8) of tile row (wave*NB + u)*8 + lane / 8 with chunk
+    // slot ^ swz(row) of that column's row; swz(row) = (lane / 16 + 4 * ((wave*NB + u) & 1)) & 7, so a thread's loads
+    // alternate between two chunks (u even / odd), each with its own (image, group) position that moves on by 8 groups
+    // per step
+    unsigned bbase[NB];
+    const int slot = lane & 7;
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        const int row = (wave * NB + u) * 8 + (lane >> 3);
+        int col = n0 + row;
+        col = col < p.ncols ? col : 0;
+        const int rs = (int)fastdiv((uint32_t)col, p.div_c), c = col - rs * p.C;
+        const int r = (int)fastdiv((uint32_t)rs, p.div_s), sx = rs - r * p.S;
+        const int shift = r * p.Wq + sx;                   // odd shifts read the copy that is moved up by one element
+        bbase[u] = (uint32_t)(c + (shift & 1) * p.C) * (uint32_t)p.row_x_bytes + 2u * (uint32_t)(shift & ~1);
+    }
+    int pn[2], pg[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int chunk = slot ^ (((lane >> 4) + 4 * ((wave * NB + e) & 1)) & 7);
+        const int g = step_begin * 8 + chunk;
+        pn[e] = (int)fastdiv((uint32_t)g, p.div_g);
+        pg[e] = g - pn[e] * p.G;
+    }
+    const unsigned aoff = (unsigned)((wave * NA * 64 + lane) * 16);
+    const size_t a_step_bytes = (size_t)p.Kpad * RB;
+    const char *a_base = reinterpret_cast<const char *>(p.dyT) + (size_t)step_begin * a_step_bytes + (size_t)m0 * RB;
+    const char *const xpb = reinterpret_cast<const char *>(p.xp);
+
+    unsigned la = 0, lb = 0, pos[2] = {0u, 0u};
+    auto begin_step_loads = [&](int buf) {
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            pos[e] = 2u * (unsigned)(min(pn[e], p.N - 1) * p.Jx + pg[e] * 8);   // steps past the last image: zero dy
+            pg[e] += 8;
+            const bool wrap = pg[e] >= p.G;
+            pg[e] -= wrap ? p.G : 0;
+            pn[e] += wrap ? 1 : 0;
+        }
+        la = lds_base + buf * BUF + wave * NA * 1024;
+        lb = lds_base + buf * BUF + BM * RB + wave * NB * 1024;
+    };
+    auto load_one = [&](int i) {     // i < NL, compile-time after unrolling
+        if (i < NA) dma16(a_base, aoff + i * 1024, la + i * 1024);
+        else dma16(xpb, bbase[i - NA] + pos[(i - NA) & 1], lb + (i - NA) * 1024);
+    };
+    auto end_step_loads = [&]() { a_base += a_step_bytes; };
+    auto load_step = [&](int buf) {
+        begin_step_loads(buf);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) load_one(i);
+        end_step_loads();
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
+
+    const int l32 = lane & 31, half = lane >> 5;
+    const int swzl = (l32 >> 1) & 7;
+    int koff[NK];
+#pragma unroll
+    for (int t = 0; t < NK; ++t) koff[t] = ((2 * t + half) ^ swzl) * 16;
+    const int a_row = (wm * TM * 32 + l32) * RB;
+    const int b_row = BM * RB + (wn * TN * 32 + l32) * RB;
+
+    u32x4 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](const char *bufp, int t, int set) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[set][i] = *reinterpret_cast<const u32x4 *>(bufp + a_row + i * 32 * RB + koff[t]);
+#pragma unroll
+        for (int jn = 0; jn < TN; ++jn) fb[set][jn] = *reinterpret_cast<const u32x4 *>(bufp + b_row + jn * 32 * RB + koff[t]);
+    };
+
+    if (nsteps > 0) load_step(0);
+    if (nsteps > 1) load_step(1);
+    if (nsteps > 1) wait_vmcnt<NL>(); else wait_vmcnt<0>();
+    __syncthreads();
+    if (nsteps > 0) read_frags(lds, 0, 0);
+
+    // One step: see colgemm_bf16_dma_kernel (slices of 16 positions, the loads of step + 2 spread over slices
+    // 0 .. NK-2, the barrier before the last slice, slice 0 of the next step read behind it).
+    constexpr int MPS = TM * TN;
+    constexpr int SLOTS = (NK - 1) * MPS;
+    constexpr int SPACING = SLOTS / NL > 0 ? SLOTS / NL : 1;
+    static_assert(NL <= SLOTS, "one load per matrix instruction at most");
+    int step = 0;
+    auto do_step = [&](auto more_c) {
+        constexpr bool more = decltype(more_c)::value;
+        const char *bufp = lds + (step % 3) * BUF;
+        const char *nextp = lds + ((step + 1) % 3) * BUF;
+        if (more) begin_step_loads((step + 2) % 3);
+#pragma unroll
+        for (int t = 0; t < NK; ++t) {
+            if (t + 1 < NK) {
+                read_frags(bufp, t + 1, (t + 1) & 1);
+            } else {
+                if (more) wait_vmcnt<NL>(); else wait_vmcnt<0>();
+                asm volatile("s_waitcnt lgkmcnt(0)");
+                __syncthreads();
+                if (more || step + 1 < nsteps) read_frags(nextp, 0, (t + 1) & 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int jn = 0; jn < TN; ++jn) {
+                    acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[t & 1][i]),
+                                                                         __builtin_bit_cast(bf16x8, fb[t & 1][jn]),
+                                                                         acc[i][jn], 0, 0, 0);
+                    const int m = t * MPS + i * TN + jn;
+                    if (more && t + 1 < NK && m % SPACING == SPACING - 1 && m / SPACING < NL) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_one(m / SPACING);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (more) end_step_loads();
+        ++step;
+    };
+    while (step + 2 < nsteps) do_step(std::true_type{});
+    while (step < nsteps) do_step(std::false_type{});
+
+    float *out = p.part + (size_t)split * p.K * p.ncols;
+#pragma unroll
+    for (int jn = 0; jn < TN; ++jn) {
+        const int col = n0 + (wn * TN + jn) * 32 + l32;
+        if (col >= p.ncols) continue;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + (v >> 2) * 8 + (v & 3);
+                if (row < p.K) out[(size_t)row * p.ncols + col] = acc[i][jn][v];
+            }
+        }
+    }
+}
+
 // dyp[k][e], e < row_elems: image n = e / Jy, j = e % Jy = p*Wq + q; dy(n, k, p, q) where p < P and q < Q, else 0.
 // One thread per 8 consecutive elements (Jy and row_elems are multiples of 8, so they share k and n): eight
 // 2-byte loads along a row of dy, one 16-byte store.
 __device__ __forceinline__ void pack_dy_lin(int64_t i8, const unsigned short *__restrict__ dy,
                                             unsigned short *__restrict__ dyp, int N, int K, int P, int Q, int Wq, int Jy,
                                             int row_elems, int64_t dy_bs, FastDiv div_row, FastDiv div_jy,
-                                            FastDiv div_wq)
+                                            FastDiv div_wq, int kpad)
 {
     const int64_t i = i8 * 8;
     if (i >= (int64_t)K * row_elems) return;
@@ -887,7 +1092,13 @@ __device__ __forceinline__ void pack_dy_lin(int64_t i8, const unsigned short *__
     }
     u32x4 o = {(uint32_t)v[0] | (uint32_t)v[1] << 16, (uint32_t)v[2] | (uint32_t)v[3] << 16,
                (uint32_t)v[4] | (uint32_t)v[5] << 16, (uint32_t)v[6] | (uint32_t)v[7] << 16};
-    reinterpret_cast<u32x4 *>(dyp)[i8] = o;
+    if (kpad == 0) {
+        reinterpret_cast<u32x4 *>(dyp)[i8] = o;
+    } else {
+        // dyT[step][Kpad][64]: chunk (e % 64) / 8 of row k and step e / 64 goes to position chunk ^ swz(k)
+        const uint32_t st = e >> 6, chunk = (e >> 3) & 7;
+        reinterpret_cast<u32x4 *>(dyp)[((size_t)st * kpad + k) * 8 + (chunk ^ ((k >> 1) & 7))] = o;
+    }
 }
 
 // xp[c][n][e], e < Jx: padded row hh = e / Wq, column ww = e % Wq; x(n, c, hh - pad, ww - pad) where inside, else 0.
@@ -926,6 +1137,8 @@ struct PackLinArgs {
     const unsigned short *dy, *x;
     unsigned short *dyp, *xp;
     int N, K, C, P, Q, H, W, pad, Wq, Jy, Jx, row_elems, dy_blocks;
+    int kpad;              // > 0: dy goes to the step-major swizzled layout dyT[step][kpad][64] (rows K..kpad-1 are not
+                           // written: what the kernel computes from them is never stored)
     int64_t dy_bs, x_bs;
     FastDiv div_row, div_jy, div_jx, div_wq;
 };
@@ -934,7 +1147,7 @@ __global__ __launch_bounds__(256) void pack_lin(const PackLinArgs a)
 {
     if ((int)blockIdx.x < a.dy_blocks)
         pack_dy_lin((int64_t)blockIdx.x * 256 + threadIdx.x, a.dy, a.dyp, a.N, a.K, a.P, a.Q, a.Wq, a.Jy, a.row_elems,
-                    a.dy_bs, a.div_row, a.div_jy, a.div_wq);
+                    a.dy_bs, a.div_row, a.div_jy, a.div_wq, a.kpad);
     else
         pack_x_lin((int64_t)(blockIdx.x - a.dy_blocks) * 256 + threadIdx.x, a.x, a.xp, a.N, a.C, a.H, a.W, a.pad, a.Wq,
                    a.Jx, a.x_bs, a.div_jx, a.div_wq);

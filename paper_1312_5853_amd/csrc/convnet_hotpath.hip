@@ -610,6 +610,7 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         q.N = pb.N; q.K = pb.K; q.C = pb.C; q.P = pb.P; q.Q = pb.Q; q.H = pb.H; q.W = pb.W; q.pad = pb.pad;
         q.Wq = pl.lin_wq; q.Jy = pl.lin_jy; q.Jx = pl.lin_jx; q.row_elems = row_elems;
         q.dy_blocks = grid1d((int64_t)pb.K * row_elems / 8, 256);
+        q.kpad = round_up(pb.K, 128);
         q.dy_bs = pb.y_bs; q.x_bs = pb.x_bs;
         q.div_row = make_fastdiv((uint32_t)row_elems);
         q.div_jy = make_fastdiv((uint32_t)pl.lin_jy);
@@ -617,22 +618,25 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         q.div_wq = make_fastdiv((uint32_t)pl.lin_wq);
         hipLaunchKernelGGL(pack_lin, dim3(q.dy_blocks + grid1d((int64_t)pb.C * pb.N * pl.lin_jx / 8, 256)), dim3(256),
                            0, st, q);
-        WgradLinArgs a;
-        a.dyp = dyp; a.xp = xp; a.part = reinterpret_cast<float *>(wsb + pl.part_off);
-        a.K = pb.K; a.C = pb.C; a.ncols = pl.Kg; a.S = pb.S; a.Wq = pl.lin_wq;
+        WgradLinDmaArgs a;
+        a.dyT = dyp; a.xp = xp; a.part = reinterpret_cast<float *>(wsb + pl.part_off);
+        a.K = pb.K; a.Kpad = round_up(pb.K, 128); a.C = pb.C; a.ncols = pl.Kg; a.S = pb.S; a.Wq = pl.lin_wq;
         a.N = pb.N; a.G = pl.lin_jy / 8; a.Jx = pl.lin_jx;
-        a.row_a_bytes = row_elems * 2; a.row_x_bytes = pb.N * pl.lin_jx * 2;
+        a.row_x_bytes = pb.N * pl.lin_jx * 2;
         a.steps = pl.lin_steps; a.steps_per_split = pl.chunks_per_split;
-        a.mtiles = pl.Mpad / pl.tile.bm();
-        a.ntiles = ceil_div(pl.Kg, pl.tile.bn());
+        a.mtiles = a.Kpad / 128;
+        a.ntiles = ceil_div(pl.Kg, 256);
         a.nunits = a.mtiles * a.ntiles * pl.nsplit;
-        const int need_lds = 2 * (pl.tile.bm() + pl.tile.bn()) * (64 * 2 + 16);
-        const GridPlan g = plan_grid(a.nunits, need_lds);
-        a.units_per_xcd = g.tiles_per_xcd;
+        a.units_per_xcd = ceil_div(a.nunits, 8);
         a.div_c = make_fastdiv((uint32_t)pb.C);
         a.div_s = make_fastdiv((uint32_t)pb.S);
         a.div_g = make_fastdiv((uint32_t)a.G);
-        launch_wgrad_bf16_lin(pl.tile, a, g.grid, need_lds + g.dyn_lds, st);
+        {
+            const int lds = 3 * (128 + 256) * 128;
+            (void)hipFuncSetAttribute(reinterpret_cast<const void *>(wgrad_bf16_lin_dma_kernel<2, 2, 2, 4>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+            hipLaunchKernelGGL((wgrad_bf16_lin_dma_kernel<2, 2, 2, 4>), dim3(8 * a.units_per_xcd), dim3(512), lds, st, a);
+        }
         int rc = check_launch();
         if (rc != kStatusOk) return rc;
         const int count = pb.K * pl.Kg;

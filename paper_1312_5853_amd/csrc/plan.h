@@ -250,10 +250,14 @@ inline Plan make_plan(int op, const Problem &pb)
             const int jx = round_up(jy + (pb.R - 1) * wq + pb.S, 8);
             const int64_t steps = ((int64_t)pb.N * jy + 63) / 64;
             // (x is packed twice: the second copy, moved up by one element, serves the taps with an odd shift)
-            const int64_t dy_bytes = (int64_t)pb.K * steps * 64 * 2, x_bytes = (int64_t)2 * pb.C * pb.N * jx * 2;
+            // (dy is packed step-major with its rows padded to whole 128-row tiles: the direct-to-LDS kernel, one
+            // work-group of 128 x 256 per CU)
+            const int kpad = round_up(pb.K, 128);
+            const int64_t dy_bytes = (int64_t)kpad * steps * 64 * 2, x_bytes = (int64_t)2 * pb.C * pb.N * jx * 2;
             if (jy >= 64 && dy_bytes < kMaxSpanBytes && x_bytes < kMaxSpanBytes) {
                 pl.lin = true;
                 pl.lin_wq = wq; pl.lin_jy = jy; pl.lin_jx = jx; pl.lin_steps = (int)steps;
+                want = 256 / ((kpad / 128) * ceil_div(pl.Kg, 256));
                 int ns = want < (int)(steps / 4) ? want : (int)(steps / 4);     // at least 4 steps per split
                 if (ns < 1) ns = 1;
                 pl.chunks_per_split = ceil_div((int)steps, ns);
