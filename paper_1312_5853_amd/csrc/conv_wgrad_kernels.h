@@ -659,214 +659,8 @@ __global__ __launch_bounds__(kThreads) void wgrad_bf16_kernel(const WgradFastArg
 // The x loads are 4-byte aligned: xp is kept twice, the second copy moved up by one element for the odd tap shifts.
 // Columns in (r, s, c) order, partials [split][K][R*S*C] as in wgrad_fast_kernel.
 // ---------------------------------------------------------------------------
-struct WgradLinArgs {
-    const unsigned short *dyp;
-    const unsigned short *xp;
-    float *part;
-    int K, C, ncols;
-    int S, Wq;
-    int N, G, Jx;             // G = Jy / 8 groups of 8 positions per image
-    int row_a_bytes;          // bytes per dyp row
-    int row_x_bytes;          // bytes per xp row (N * Jx * 2)
-    int steps, steps_per_split;
-    int mtiles, ntiles, nunits, units_per_xcd;
-    FastDiv div_c, div_s, div_g;
-};
-
-typedef u32x4 u32x4_align4 __attribute__((aligned(4)));
-
-template <int TM, int TN, int WM, int WN>
-__global__ __launch_bounds__(kThreads, 2) void wgrad_bf16_lin_kernel(const WgradLinArgs p)
-{
-    constexpr int BM = TM * WM * 32, BN = TN * WN * 32;
-    constexpr int KJ = 64, NK = KJ / 16;
-    constexpr int PITCHB = KJ * 2 + 16;
-    constexpr int RA = BM / 32, RB = BN / 32;      // 16-byte vectors per thread and step
-    static_assert(WM * WN == 4, "four waves per work-group");
-
-    extern __shared__ __attribute__((aligned(16))) float lds_fast[];
-    char *const As0 = reinterpret_cast<char *>(lds_fast);
-    char *const Bs0 = As0 + 2 * BM * PITCHB;
-
-    const int bid = blockIdx.x;
-    const int idx = bid >> 3;
-    const int unit = (bid & 7) * p.units_per_xcd + idx;
-    if (idx >= p.units_per_xcd || unit >= p.nunits) return;
-    const int ntile = p.mtiles * p.ntiles;
-    const int split = unit / ntile;
-    const int tile = unit - split * ntile;
-    const int mt = tile % p.mtiles, nt = tile / p.mtiles;
-    const int m0 = mt * BM, n0 = nt * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = uniform(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
-    const int jg = tid & 7, r8 = tid >> 3;         // this thread's group of 8 positions in a step; its row inside 32
-
-    const int step_begin = split * p.steps_per_split;
-    const int nsteps = min(p.steps - step_begin, p.steps_per_split);
-
-    uint32_t abase[RA], bbase[RB];
-#pragma unroll
-    for (int i = 0; i < RA; ++i) abase[i] = (uint32_t)min(m0 + r8 + 32 * i, p.K - 1) * (uint32_t)p.row_a_bytes;
-#pragma unroll
-    for (int i = 0; i < RB; ++i) {
-        int col = n0 + r8 + 32 * i;
-        col = col < p.ncols ? col : 0;
-        const int rs = (int)fastdiv((uint32_t)col, p.div_c), c = col - rs * p.C;
-        const int r = (int)fastdiv((uint32_t)rs, p.div_s), sx = rs - r * p.S;
-        const int shift = r * p.Wq + sx;                   // odd shifts read the copy that is moved up by one element
-        bbase[i] = (uint32_t)(c + (shift & 1) * p.C) * (uint32_t)p.row_x_bytes + 2u * (uint32_t)(shift & ~1);
-    }
-    // position of this thread's group: g = step*8 + jg = n*G + gg
-    int n, gg;
-    {
-        const int g = step_begin * 8 + jg;
-        n = (int)fastdiv((uint32_t)g, p.div_g);
-        gg = g - n * p.G;
-    }
-    uint32_t aoff = (uint32_t)(step_begin * 8 + jg) * 16u, boff = 0;
-    const char *ap = reinterpret_cast<const char *>(p.dyp), *xp = reinterpret_cast<const char *>(p.xp);
-
-    // register set t & 1 and LDS buffer t & 1 hold step t (two-set pipeline of colgemm_fast_kernel)
-    u32x4 areg[2][RA], breg[2][RB];
-    auto slot_pos = [&]() {
-        boff = 2u * (uint32_t)(min(n, p.N - 1) * p.Jx + gg * 8);
-        gg += 8;
-        const bool wrap = gg >= p.G;
-        gg -= wrap ? p.G : 0;
-        n += wrap ? 1 : 0;
-    };
-    auto slot_a = [&](int set, int i) {
-        areg[set][i] = *reinterpret_cast<const u32x4 *>(ap + (abase[i] + aoff));
-        if (i == RA - 1) aoff += 128u;
-    };
-    auto slot_b = [&](int set, int i) {
-        breg[set][i] = *reinterpret_cast<const u32x4_align4 *>(xp + (bbase[i] + boff));
-    };
-    auto load_step = [&](int set) {
-        slot_pos();
-#pragma unroll
-        for (int i = 0; i < RA; ++i) slot_a(set, i);
-#pragma unroll
-        for (int i = 0; i < RB; ++i) slot_b(set, i);
-    };
-    auto store_a = [&](int set, int i) {
-        *reinterpret_cast<u32x4 *>(As0 + set * BM * PITCHB + (r8 + i * 32) * PITCHB + jg * 16) = areg[set][i];
-    };
-    auto store_b = [&](int set, int i) {
-        *reinterpret_cast<u32x4 *>(Bs0 + set * BN * PITCHB + (r8 + i * 32) * PITCHB + jg * 16) = breg[set][i];
-    };
-    auto store_step = [&](int set) {
-#pragma unroll
-        for (int i = 0; i < RA; ++i) store_a(set, i);
-#pragma unroll
-        for (int i = 0; i < RB; ++i) store_b(set, i);
-    };
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int jn = 0; jn < TN; ++jn)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][jn][v] = 0.f;
-
-    const int l32 = lane & 31, half = lane >> 5;
-    const int a_frag = (wm * TM * 32 + l32) * PITCHB + half * 16;
-    const int b_frag = (wn * TN * 32 + l32) * PITCHB + half * 16;
-    constexpr int NMMA = NK * TM * TN;
-    constexpr int NLOAD = 1 + RA + RB, NSTORE = RA + RB;
-    constexpr int SPM = (NLOAD + NSTORE + NMMA - 3) / (NMMA - 2);
-
-    if (nsteps > 0) {
-        load_step(0);
-        store_step(0);
-        if (nsteps > 1) load_step(1);
-    }
-    __syncthreads();
-    // mode 2: loads of step + 2 and stores of step + 1; 1: stores only; 0: neither (par, mode compile-time)
-    auto do_step = [&](auto par_c, auto mode_c) {
-        constexpr int par = decltype(par_c)::value, mode = decltype(mode_c)::value;
-        const char *As = As0 + par * BM * PITCHB, *Bs = Bs0 + par * BN * PITCHB;
-        u32x4 fa[TM][NK], fb[TN][NK];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int t = 0; t < NK; ++t)
-                fa[i][t] = *reinterpret_cast<const u32x4 *>(As + a_frag + i * 32 * PITCHB + t * 32);
-#pragma unroll
-        for (int jn = 0; jn < TN; ++jn)
-#pragma unroll
-            for (int t = 0; t < NK; ++t)
-                fb[jn][t] = *reinterpret_cast<const u32x4 *>(Bs + b_frag + jn * 32 * PITCHB + t * 32);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int m = 0; m < NMMA; ++m) {
-            const int t = m / (TM * TN), i = (m / TN) % TM, jn = m % TN;
-            acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[i][t]),
-                                                                 __builtin_bit_cast(bf16x8, fb[jn][t]),
-                                                                 acc[i][jn], 0, 0, 0);
-            if (mode > 0 && m * SPM < NLOAD + NSTORE) {
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int q = m * SPM; q < (m + 1) * SPM && q < NLOAD + NSTORE; ++q) {
-                    if (q < NLOAD) {
-                        if (mode == 2) {
-                            if (q == 0) slot_pos();
-                            else if (q - 1 < RA) slot_a(par, q - 1);
-                            else slot_b(par, q - 1 - RA);
-                        }
-                    } else {
-                        const int w = q - NLOAD;
-                        if (w < RA) store_a(par ^ 1, w);
-                        else store_b(par ^ 1, w - RA);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        if (mode > 0) __syncthreads();
-    };
-    using P0 = std::integral_constant<int, 0>;
-    using P1 = std::integral_constant<int, 1>;
-    using M2 = std::integral_constant<int, 2>;
-    int step = 0;
-    for (; step + 3 < nsteps; step += 2) {
-        do_step(P0{}, M2{});
-        do_step(P1{}, M2{});
-    }
-    const int rest = nsteps - step;
-    if (rest == 3) {
-        do_step(P0{}, M2{});
-        do_step(P1{}, P1{});
-        do_step(P0{}, P0{});
-    } else if (rest == 2) {
-        do_step(P0{}, P1{});
-        do_step(P1{}, P0{});
-    } else if (rest == 1) {
-        do_step(P0{}, P0{});
-    }
-
-    float *out = p.part + (size_t)split * p.K * p.ncols;
-#pragma unroll
-    for (int jn = 0; jn < TN; ++jn) {
-        const int col = n0 + (wn * TN + jn) * 32 + l32;
-        if (col >= p.ncols) continue;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + (v >> 2) * 8 + (v & 3);
-                if (row < p.K) out[(size_t)row * p.ncols + col] = acc[i][jn][v];
-            }
-        }
-    }
-}
-
 // ---------------------------------------------------------------------------
-// The same pass with both operands loaded from global memory straight into LDS (16 bytes per lane, no staging
+// The kernel: both operands are loaded from global memory straight into LDS (16 bytes per lane, no staging
 // registers and no LDS store instructions: at bf16 matrix rates the 32 KB a 128 x 128 tile stores into LDS per
 // 64-position step take as long as its matrix work, see conv_bf16_dma_kernels.h).  One eight-wave work-group per
 // CU owns a 128 x 256 tile (rows: filters, columns: taps (r, s, c)) for a range of the reduction; three LDS buffers
@@ -1156,6 +950,8 @@ __global__ __launch_bounds__(256) void pack_lin(const PackLinArgs a)
 // dw[k][c][rs] = part[0][k][rs*C + c] + part[1][k][rs*C + c] + ...  (fixed order)
 // groups > 1: K filters per column; the partials of column g follow those of column g - 1, dw holds the columns'
 // filters one after the other
+// (one thread per output word: a thread per (k, c) plane that loops over the taps and splits reads and writes
+// better-shaped runs but has 54 dependent loads in a row and was 4-10 times slower)
 __global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__ dw, int K, int C, int RS,
                              int nsplit, int groups, FastDiv div_kcols, FastDiv div_cols, FastDiv div_c)
 {

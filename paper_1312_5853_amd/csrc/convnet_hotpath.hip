@@ -323,18 +323,6 @@ void launch_wgrad_bf16(const TileShape &t, const WgradFastArgs &a, int grid, int
     else hipLaunchKernelGGL((wgrad_bf16_kernel<2, 1, 1, 4, KJ>), g, b, lds, st, a);
 }
 
-void launch_wgrad_bf16_lin(const TileShape &t, const WgradLinArgs &a, int grid, int lds, hipStream_t st)
-{
-    const void *k = (t.TM == 2 && t.TN == 2) ? (const void *)wgrad_bf16_lin_kernel<2, 2, 2, 2>
-                  : t.TM == 3 ? (const void *)wgrad_bf16_lin_kernel<3, 1, 1, 4>
-                              : (const void *)wgrad_bf16_lin_kernel<2, 1, 1, 4>;
-    if (lds > 64 * 1024) (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    const dim3 g(grid), b(kThreads);
-    if (t.TM == 2 && t.TN == 2) hipLaunchKernelGGL((wgrad_bf16_lin_kernel<2, 2, 2, 2>), g, b, lds, st, a);
-    else if (t.TM == 3) hipLaunchKernelGGL((wgrad_bf16_lin_kernel<3, 1, 1, 4>), g, b, lds, st, a);
-    else hipLaunchKernelGGL((wgrad_bf16_lin_kernel<2, 1, 1, 4>), g, b, lds, st, a);
-}
-
 void launch_wgrad_fast(const TileShape &t, const WgradFastArgs &a, const GridPlan &g, hipStream_t st)
 {
     const dim3 grid(g.grid), block(kThreads);
