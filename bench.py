@@ -233,7 +233,7 @@ def whole_network(N, hp, torch, steps, timer):
             out["%s.%s" % (name, pname)] = with_rates(timer(fn), 2.0 * N * i * o, PEAK_FP32_MFMA_TFLOPS)
     nparam = sum(p.numel() for p, _ in net.params)
     t = timer(net.update)
-    t.update({"params": nparam, "launches": len(net.params),
+    t.update({"params": nparam, "tensors": len(net.params), "launches": 1,
               "hbm_tb_per_s": round(nparam * 20 / t["ms"] / 1e9, 3),       # w, dw, v read; w, v written
               "frac_hbm_peak": round(nparam * 20 / t["ms"] / 1e9 / PEAK_HBM_TBS, 4)})
     out["sgd_update"] = t

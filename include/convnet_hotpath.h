@@ -323,6 +323,19 @@ size_t fc_workspace_bytes(int op, int N, int I, int O, int dtype);
 int sgd_update(void *w, const void *dw, void *vel, int64_t count, float lr, float momentum,
                float weight_decay, float grad_scale, void *stream);
 
+/*
+ * The same update (same formula, same training-procedure paragraph) for
+ * `ntensors` parameter tensors in one call: w, dw, vel and counts are HOST arrays
+ * of `ntensors` device pointers / element counts, read before the call returns.
+ * One kernel launch per 24 tensors instead of one per tensor; every parameter
+ * gets bit for bit what sgd_update gives it.  Tensors with count 0 are skipped
+ * (their pointers may be NULL); the argument checks of sgd_update apply to each
+ * tensor, and nothing is launched if one fails.
+ */
+int sgd_update_multi(void *const *w, const void *const *dw, void *const *vel, const int64_t *counts,
+                     int ntensors, float lr, float momentum, float weight_decay, float grad_scale,
+                     void *stream);
+
 #ifdef __cplusplus
 }
 #endif

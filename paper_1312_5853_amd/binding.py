@@ -29,7 +29,7 @@ EXPORTS = (
     "relu_fwd", "relu_bwd", "maxpool3x3s2_fwd", "maxpool3x3s2_bwd",
     "relu_maxpool3x3s2_fwd", "relu_maxpool3x3s2_bwd", "convert_f32_to_bf16",
     "bias_fwd", "bias_bwd", "bias_bwd_workspace_bytes",
-    "fc_fwd", "fc_bwd_data", "fc_bwd_filter", "fc_workspace_bytes", "sgd_update",
+    "fc_fwd", "fc_bwd_data", "fc_bwd_filter", "fc_workspace_bytes", "sgd_update", "sgd_update_multi",
 )
 
 _lib = None
@@ -79,7 +79,8 @@ def lib():
     L.fc_workspace_bytes.restype = sz
     f32 = ctypes.c_float
     L.sgd_update.argtypes = [vp, vp, vp, i64, f32, f32, f32, f32, vp]
-    for name in ("fc_fwd", "fc_bwd_data", "fc_bwd_filter", "sgd_update"):
+    L.sgd_update_multi.argtypes = [vp, vp, vp, vp, i, f32, f32, f32, f32, vp]
+    for name in ("fc_fwd", "fc_bwd_data", "fc_bwd_filter", "sgd_update", "sgd_update_multi"):
         getattr(L, name).restype = i
     L.conv_workspace_bytes_grouped.argtypes = [i] + dims + [i, i]
     L.conv_workspace_bytes_grouped.restype = sz
@@ -513,3 +514,19 @@ def sgd_update(w, dw, vel, lr, momentum=0.0, weight_decay=0.0, grad_scale=1.0, s
     _check(lib().sgd_update(_ptr(w), _ptr(dw), _ptr(vel), w.numel(), lr, momentum, weight_decay, grad_scale,
                             _stream_handle(stream)), "sgd_update")
     return w
+
+
+def sgd_update_multi(ws, dws, vels, lr, momentum=0.0, weight_decay=0.0, grad_scale=1.0, stream=None):
+    """sgd_update for lists of tensors in one call (one launch per 24 tensors)."""
+    n = len(ws)
+    if not (len(dws) == len(vels) == n):
+        raise ValueError("sgd_update_multi takes three lists of one length")
+    for w, dw, vel in zip(ws, dws, vels):
+        if not (w.dtype == dw.dtype == vel.dtype == torch.float32) or not (w.numel() == dw.numel() == vel.numel()):
+            raise ValueError("sgd_update_multi takes fp32 tensors, each triple of one size")
+        _dense(w, dw, vel)
+    ptrs = lambda ts: (ctypes.c_void_p * n)(*[t.data_ptr() for t in ts])
+    counts = (ctypes.c_int64 * n)(*[w.numel() for w in ws])
+    _check(lib().sgd_update_multi(ptrs(ws), ptrs(dws), ptrs(vels), counts, n, lr, momentum, weight_decay, grad_scale,
+                                  _stream_handle(stream)), "sgd_update_multi")
+    return ws

@@ -1300,4 +1300,45 @@ int sgd_update(void *w, const void *dw, void *vel, int64_t count, float lr, floa
     return check_launch();
 }
 
+int sgd_update_multi(void *const *w, const void *const *dw, void *const *vel, const int64_t *counts, int ntensors,
+                     float lr, float momentum, float weight_decay, float grad_scale, void *stream)
+{
+    if (ntensors < 0 || (ntensors > 0 && (!w || !dw || !vel || !counts))) return kErrInvalidArg;
+    for (int t = 0; t < ntensors; ++t) {
+        if (counts[t] < 0 || (counts[t] > 0 && (!w[t] || !dw[t] || !vel[t]))) return kErrInvalidArg;
+        if (counts[t] > 0 && (!aligned(w[t], 4) || !aligned(dw[t], 4) || !aligned(vel[t], 4))) return kErrMisaligned;
+    }
+    // launches of up to kSgdMaxTensors tensors each; tensors without parameters take no blocks
+    int t = 0;
+    while (t < ntensors) {
+        SgdMultiArgs a = {};
+        a.lr = lr; a.momentum = momentum; a.weight_decay = weight_decay; a.grad_scale = grad_scale;
+        int64_t blocks = 0;
+        while (t < ntensors && a.n < kSgdMaxTensors) {
+            if (counts[t] > 0) {
+                const int vec = aligned(w[t], 16) && aligned(dw[t], 16) && aligned(vel[t], 16);
+                const int64_t threads = vec ? std::max<int64_t>(counts[t] >> 2, 4) : counts[t];
+                const int64_t nb = (threads + 255) / 256;
+                if (blocks + nb >= ((int64_t)1 << 31)) {
+                    if (a.n == 0) return kErrTooLarge;
+                    break;                                  // this tensor starts the next launch
+                }
+                a.w[a.n] = static_cast<float *>(w[t]); a.dw[a.n] = static_cast<const float *>(dw[t]);
+                a.vel[a.n] = static_cast<float *>(vel[t]); a.count[a.n] = counts[t]; a.vec[a.n] = vec;
+                a.first_block[a.n] = (unsigned)blocks;
+                blocks += nb;
+                ++a.n;
+                a.first_block[a.n] = (unsigned)blocks;
+            }
+            ++t;
+        }
+        if (a.n == 0) continue;
+        hipLaunchKernelGGL(sgd_update_multi_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), a);
+        const int rc = check_launch();
+        if (rc != kStatusOk) return rc;
+    }
+    return kStatusOk;
+}
+
 }  // extern "C"

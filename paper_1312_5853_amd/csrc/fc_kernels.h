@@ -251,13 +251,38 @@ __global__ void fc_reduce_kernel(const float *__restrict__ part, float *__restri
     }
 }
 
+// The same update for up to kSgdMaxTensors parameter tensors in ONE launch: tensor t owns the blocks
+// [first_block[t], first_block[t + 1]) of 256 threads x 4 parameters (16-byte aligned tensors) or x 1 parameter.
+constexpr int kSgdMaxTensors = 24;
+struct SgdMultiArgs {
+    float *w[kSgdMaxTensors];
+    const float *dw[kSgdMaxTensors];
+    float *vel[kSgdMaxTensors];
+    int64_t count[kSgdMaxTensors];
+    unsigned first_block[kSgdMaxTensors + 1];
+    int vec[kSgdMaxTensors];
+    int n;
+    float lr, momentum, weight_decay, grad_scale;
+};
+
+__device__ __forceinline__ void sgd_update_elems(float *__restrict__ w, const float *__restrict__ dw,
+                                                 float *__restrict__ vel, int64_t count, int64_t i, float lr,
+                                                 float momentum, float weight_decay, float grad_scale, int vec);
+
+__global__ void sgd_update_multi_kernel(const SgdMultiArgs a)
+{
+    int t = 0;
+    while (t + 1 < a.n && blockIdx.x >= a.first_block[t + 1]) ++t;          // uniform: at most 23 steps
+    const int64_t i = (int64_t)(blockIdx.x - a.first_block[t]) * blockDim.x + threadIdx.x;
+    sgd_update_elems(a.w[t], a.dw[t], a.vel[t], a.count[t], i, a.lr, a.momentum, a.weight_decay, a.grad_scale, a.vec[t]);
+}
+
 // SGD with momentum and weight decay, one thread per four parameters:
 //   v = momentum * v - lr * (weight_decay * w + grad_scale * dw);  w += v
-__global__ void sgd_update_kernel(float *__restrict__ w, const float *__restrict__ dw, float *__restrict__ vel,
-                                  int64_t count, float lr, float momentum, float weight_decay, float grad_scale,
-                                  int vec)
+__device__ __forceinline__ void sgd_update_elems(float *__restrict__ w, const float *__restrict__ dw,
+                                                 float *__restrict__ vel, int64_t count, int64_t i, float lr,
+                                                 float momentum, float weight_decay, float grad_scale, int vec)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (vec) {
         const int64_t n4 = count >> 2;
         if (i < n4) {
@@ -283,4 +308,12 @@ __global__ void sgd_update_kernel(float *__restrict__ w, const float *__restrict
         vel[i] = v;
         w[i] += v;
     }
+}
+
+__global__ void sgd_update_kernel(float *__restrict__ w, const float *__restrict__ dw, float *__restrict__ vel,
+                                  int64_t count, float lr, float momentum, float weight_decay, float grad_scale,
+                                  int vec)
+{
+    sgd_update_elems(w, dw, vel, count, (int64_t)blockIdx.x * blockDim.x + threadIdx.x, lr, momentum, weight_decay,
+                     grad_scale, vec);
 }

@@ -210,8 +210,8 @@ class FullNetwork(ConvStack):
 
     def update(self):
         """Mean gradient over this shard's N samples (a data-parallel job would first sum the shards' gradients)."""
-        for (p, g), v in zip(self.params, self.vel):
-            hp.sgd_update(p, g, v, self.lr, self.momentum, self.weight_decay, 1.0 / self.N)
+        hp.sgd_update_multi([p for p, _ in self.params], [g for _, g in self.params], self.vel, self.lr,
+                            self.momentum, self.weight_decay, 1.0 / self.N)
 
     def step(self):
         self.forward()

@@ -912,6 +912,35 @@ def test_random_small_shapes_full_compare(dtype):
             raise AssertionError("shape %r: %s" % (shape, e))
 
 
+def test_sgd_update_multi_equals_the_per_tensor_update():
+    """One call for many tensors (more than one launch's worth, sizes with and without a multiple of four, an empty
+    tensor, a tensor that is not 16-byte aligned): every parameter bit for bit what sgd_update gives, and the oracle's
+    value within the fp32 tolerance."""
+    rng = np.random.Generator(np.random.Philox(6161))
+    sizes = [int(s) for s in rng.integers(1, 5000, size=27)] + [0, 4096, 1 << 20]
+    ws, gs, vs, ws1, vs1, host = [], [], [], [], [], []
+    for i, n in enumerate(sizes):
+        w, g, v = (synth.gaussian((n + 1,), 15000 + 3 * i + k) for k in range(3))
+        off = 1 if i % 5 == 2 else 0                              # a view one element in: 4-byte aligned only
+        wd, gd, vd = (torch.from_numpy(a).cuda()[off:off + n] for a in (w, g, v))
+        ws.append(wd); gs.append(gd); vs.append(vd)
+        ws1.append(wd.clone()); vs1.append(vd.clone())
+        host.append((w[off:off + n], g[off:off + n], v[off:off + n]))
+    hp.sgd_update_multi(ws, gs, vs, lr=0.01, momentum=0.9, weight_decay=5e-4, grad_scale=1.0 / 128)
+    for wd, gd, vd, (w, g, v) in zip(ws1, gs, vs1, host):
+        if wd.numel():
+            hp.sgd_update(wd, gd, vd, lr=0.01, momentum=0.9, weight_decay=5e-4, grad_scale=1.0 / 128)
+    torch.cuda.synchronize()
+    for i, (a, b, c, d, (w, g, v)) in enumerate(zip(ws, ws1, vs, vs1, host)):
+        assert torch.equal(a, b) and torch.equal(c, d), sizes[i]
+        if sizes[i]:
+            rw, rv = oracle.sgd_update(w, g, v, 0.01, 0.9, 5e-4, 1.0 / 128)
+            assert norm_err(a.cpu().numpy(), rw) <= TOL["f32"] and norm_err(c.cpu().numpy(), rv) <= TOL["f32"]
+    L = hp.lib()
+    assert L.sgd_update_multi(None, None, None, None, 0, 0.1, 0.0, 0.0, 1.0, None) == hp.OK
+    assert L.sgd_update_multi(None, None, None, None, 2, 0.1, 0.0, 0.0, 1.0, None) == hp.ERR_INVALID_ARG
+
+
 def test_random_fc_shapes_full_compare():
     """Forty seeded random fully connected shapes (batch up to 300, widths up to 600 in multiples of 4: one to
     five tiles each way, reductions of one to 38 steps with ragged ends and split ranges)."""

@@ -307,3 +307,12 @@ def test_fc_and_sgd_argument_checks(lib):
     assert lib.sgd_update(PTR, PTR, PTR, -1, f(0.1), f(0), f(0), f(1), None) == b.ERR_INVALID_ARG
     assert lib.sgd_update(PTR, PTR + 2, PTR, 4, f(0.1), f(0), f(0), f(1), None) == b.ERR_MISALIGNED
     assert lib.sgd_update(None, None, None, 0, f(0.1), f(0), f(0), f(1), None) == b.OK
+    ptrs = (ctypes.c_void_p * 2)(PTR, PTR)
+    odd = (ctypes.c_void_p * 2)(PTR, PTR + 2)
+    nul = (ctypes.c_void_p * 2)(PTR, None)
+    cnt = (ctypes.c_int64 * 2)(8, 8)
+    neg = (ctypes.c_int64 * 2)(8, -1)
+    assert lib.sgd_update_multi(ptrs, ptrs, nul, cnt, 2, f(0.1), f(0), f(0), f(1), None) == b.ERR_INVALID_ARG
+    assert lib.sgd_update_multi(ptrs, ptrs, ptrs, neg, 2, f(0.1), f(0), f(0), f(1), None) == b.ERR_INVALID_ARG
+    assert lib.sgd_update_multi(ptrs, odd, ptrs, cnt, 2, f(0.1), f(0), f(0), f(1), None) == b.ERR_MISALIGNED
+    assert lib.sgd_update_multi(None, None, None, None, 0, f(0.1), f(0), f(0), f(1), None) == b.OK
