@@ -770,9 +770,20 @@ int glue_elem_bytes(int dtype)
     return 0;
 }
 
+// window rows of loads a lane of the walking pooling kernels keeps in flight (4: best of 3, 4 and 6 as measured)
+constexpr int kPoolWalkDepth = 4;
+
 template <bool RELU, typename T>
 int pool_fwd_typed(const void *x, void *y, int64_t planes, int H, int W, int PH, int PW, hipStream_t st)
 {
+    if (PW + 1 <= 64) {                          // a plane's column pairs fit a wavefront: walk down the planes
+        const int seg = PW + 1, ppw = 64 / seg;
+        const int64_t waves = (planes + ppw - 1) / ppw;
+        hipLaunchKernelGGL((maxpool_fwd_walk<RELU, T, kPoolWalkDepth>), dim3((unsigned)((waves + 3) / 4)), dim3(256),
+                           0, st, static_cast<const T *>(x), static_cast<T *>(y), planes, H, W, PH, PW, seg, ppw,
+                           make_fastdiv((uint32_t)seg));
+        return check_launch();
+    }
     const int64_t total = planes * PH * PW;
     hipLaunchKernelGGL((maxpool_fwd_kernel<RELU, T>), dim3(grid1d(total, 256)), dim3(256), 0, st,
                        static_cast<const T *>(x), static_cast<T *>(y), total, H, W, PH, PW,
@@ -799,27 +810,13 @@ template <bool RELU, typename T>
 int pool_bwd_typed(const void *x, const void *dy, void *dx, int64_t planes, int H, int W, int PH, int PW,
                    hipStream_t st)
 {
-    const int HW = H * W, PP = PH * PW;
     const T *xp = static_cast<const T *>(x), *gp = static_cast<const T *>(dy);
     T *op = static_cast<T *>(dx);
-    if (HW <= 256 * 40) {
-        // planes staged whole: up to 16 elements per thread (several small planes), else one plane of up to 40
-        const bool small = HW <= 256 * 16;
-        const int group = small ? (256 * 16) / HW : 1;
-        int64_t blocks = (planes + group - 1) / group;
-        if (blocks > 256 * 6) blocks = 256 * 6;
-        const size_t lds = ((size_t)group * HW + 2) * 8;  // inputs + accumulators, one element of slack each
-        const FastDiv dPP = make_fastdiv(PP), dPW = make_fastdiv(PW);
-        if (small) {
-            hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 16, T>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
-                               planes, H, W, PH, PW, group, dPP, dPW);
-        } else {
-            if (lds > 64 * 1024)
-                (void)hipFuncSetAttribute(reinterpret_cast<const void *>(maxpool_bwd_tiled<RELU, 40, T>),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-            hipLaunchKernelGGL((maxpool_bwd_tiled<RELU, 40, T>), dim3((int)blocks), dim3(256), lds, st, xp, gp, op,
-                               planes, H, W, PH, PW, group, dPP, dPW);
-        }
+    if (PW + 1 <= 64) {                          // a plane's column pairs fit a wavefront: walk down the planes
+        const int seg = PW + 1, ppw = 64 / seg;
+        const int64_t waves = (planes + ppw - 1) / ppw;
+        hipLaunchKernelGGL((maxpool_bwd_walk<RELU, T, kPoolWalkDepth>), dim3((unsigned)((waves + 3) / 4)), dim3(256),
+                           0, st, xp, gp, op, planes, H, W, PH, PW, seg, ppw, make_fastdiv((uint32_t)seg));
     } else {
         const int64_t total = planes * H * W;
         hipLaunchKernelGGL((maxpool_bwd_kernel<RELU, T>), dim3(grid1d(total, 256)), dim3(256), 0, st, xp, gp, op,

@@ -179,174 +179,204 @@ __global__ void maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, i
     st_elem(y, t, RELU ? (m > 0.f ? m : 0.f) : m);
 }
 
-// Backward of the pooling (optionally of ReLU followed by pooling).  A
-// work-group stages a group of whole planes in LDS and finds every window's first
-// maximum once.  The gradients are then added into an LDS plane in four phases,
-// one per parity class (i % 2, j % 2) of the windows: windows of one class do not
-// overlap, so a phase needs no atomics, and an element always receives its (at
-// most four) gradients in the same order.
-// With RELU the input x is the pre-activation: the window maximum of relu(x)
-// sits where the maximum of x sits whenever it is positive, and a non-positive
-// maximum passes no gradient, so dx = [x > 0] * (pooled gradient routed by x).
+// Backward of the pooling (optionally of ReLU followed by pooling): every window's gradient goes to the window's
+// first maximum.  With RELU the input x is the pre-activation: the window maximum of relu(x) sits where the maximum
+// of x sits whenever it is positive, and a non-positive maximum passes no gradient, so
+// dx = [x > 0] * (pooled gradient routed by x).  The pass is HBM-bound: read x and dy, write dx, once each.
 //
-// The pass is HBM-bound (read x and dy, write dx once each), so the loop is
-// built to keep loads in flight: a thread holds NR elements of the next group
-// of planes (and its NR/4 gradients) in registers, fetched while the current
-// group is being worked on in LDS.
-// group * H*W <= 256 * NR; windows are fewer than a quarter of the elements.
-// A thread's unit of global access in the tiled pooling backward: one float, or two adjacent bfloat16 as
-// one aligned 32-bit access.  Indices outside [0, limit) do not exist (the pair grid is shifted by
-// align_shift() so that pairs are 4-byte aligned even where a plane group starts on an odd element).
-__device__ __forceinline__ int align_shift(const float *) { return 0; }
-__device__ __forceinline__ int align_shift(const unsigned short *p)
+// ---- pooling by walking down the plane: no LDS, no barriers -------------------------------------------------------
+// A lane owns two adjacent columns (2j, 2j + 1) of one plane and walks down its rows; lanes 0 .. PW - 1 of a plane's
+// segment also own window column j, lane PW only the last column(s).  The window's third column comes from the next
+// lane, and the gradient routed to it goes back to that lane, by a lane shift; the window's third row is carried to
+// the next window row in registers.  An element's up to four gradients are added in a fixed order (the lane's own two
+// window rows first, then the neighbour's sum).  So every element is read once and written once, as adjacent pairs (4 or 8 bytes,
+// element-aligned only: planes of odd extent start on odd elements), and a wave keeps D window rows of loads in flight.
+// seg = PW + 1 lanes per plane, ppw = 64 / seg planes per wave.
+typedef float pool_pair_f32 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ pool_pair_f32 ld_pair_raw(const float *p)
 {
-    return (int)((reinterpret_cast<uintptr_t>(p) >> 1) & 1);
+    pool_pair_f32 r;
+    __builtin_memcpy(&r, p, 8);
+    return r;
 }
-__device__ __forceinline__ void ld_group(const float *p, int e, int limit, float (&v)[1])
+__device__ __forceinline__ unsigned ld_pair_raw(const unsigned short *p)
 {
-    v[0] = e < limit ? p[e] : 0.f;
+    unsigned r;
+    __builtin_memcpy(&r, p, 4);
+    return r;
 }
-__device__ __forceinline__ void ld_group(const unsigned short *p, int e, int limit, float (&v)[2])
+__device__ __forceinline__ float pair_lo(pool_pair_f32 r) { return r[0]; }
+__device__ __forceinline__ float pair_hi(pool_pair_f32 r) { return r[1]; }
+__device__ __forceinline__ float pair_lo(unsigned r) { return __uint_as_float(r << 16); }
+__device__ __forceinline__ float pair_hi(unsigned r) { return __uint_as_float(r & 0xFFFF0000u); }
+__device__ __forceinline__ void st_pair(float *p, float a, float b)
 {
-    if (e >= 0 && e + 1 < limit) {
-        const unsigned u = *reinterpret_cast<const unsigned *>(p + e);
-        v[0] = __uint_as_float(u << 16);
-        v[1] = __uint_as_float(u & 0xFFFF0000u);
-    } else {
-        v[0] = (e >= 0 && e < limit) ? ld_elem(p, e) : 0.f;
-        v[1] = (e + 1 >= 0 && e + 1 < limit) ? ld_elem(p, e + 1) : 0.f;
-    }
+    const pool_pair_f32 r = {a, b};
+    __builtin_memcpy(p, &r, 8);
 }
-__device__ __forceinline__ void st_group(float *p, int e, int limit, const float (&v)[1])
+__device__ __forceinline__ void st_pair(unsigned short *p, float a, float b)
 {
-    if (e < limit) p[e] = v[0];
+    const unsigned r = (unsigned)bf16_round(a) | ((unsigned)bf16_round(b) << 16);
+    __builtin_memcpy(p, &r, 4);
 }
-__device__ __forceinline__ void st_group(unsigned short *p, int e, int limit, const float (&v)[2])
+__device__ __forceinline__ float raw_elem(float v) { return v; }
+__device__ __forceinline__ float raw_elem(unsigned short v) { return __uint_as_float((unsigned)v << 16); }
+
+// what a lane of the walking kernels knows about its place
+struct PoolWalkLane {
+    int j;              // column pair (2j, 2j + 1); window column j where j < PW
+    bool live;          // the lane has a plane
+    bool has1;          // column 2j + 1 exists
+    int64_t plane;      // its plane (a valid one also for idle lanes, which load but never store)
+    int lim;            // largest pair offset within the plane whose second element is still inside the tensor
+};
+__device__ __forceinline__ bool pool_walk_lane(PoolWalkLane &L, int64_t planes, int HW, int W, int seg, int ppw,
+                                               FastDiv dseg)
 {
-    if (e >= 0 && e + 1 < limit) {
-        *reinterpret_cast<unsigned *>(p + e) = (unsigned)bf16_round(v[0]) | ((unsigned)bf16_round(v[1]) << 16);
-    } else {
-        if (e >= 0 && e < limit) p[e] = bf16_round(v[0]);
-        if (e + 1 >= 0 && e + 1 < limit) p[e + 1] = bf16_round(v[1]);
-    }
+    const int lane = threadIdx.x & 63;
+    const int64_t first = ((int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) * ppw;
+    if (first >= planes) return false;                           // the whole wave is past the end
+    const int sub = (int)fastdiv((uint32_t)lane, dseg);
+    L.j = lane - sub * seg;
+    L.live = sub < ppw && first + sub < planes;
+    L.plane = L.live ? first + sub : first;
+    L.has1 = 2 * L.j + 1 < W;
+    L.lim = L.plane == planes - 1 ? HW - 2 : HW - 1;
+    return true;
 }
 
-template <bool RELU, int NR, typename T>
-__global__ __launch_bounds__(256) void maxpool_bwd_tiled(const T *__restrict__ x, const T *__restrict__ dy,
-                                                          T *__restrict__ dx, int64_t planes, int H, int W,
-                                                          int PH, int PW, int group, FastDiv dPP, FastDiv dPW)
+template <bool RELU, typename T, int D>
+__global__ __launch_bounds__(256) void maxpool_bwd_walk(const T *__restrict__ x, const T *__restrict__ dy,
+                                                         T *__restrict__ dx, int64_t planes, int H, int W, int PH,
+                                                         int PW, int seg, int ppw, FastDiv dseg)
 {
-    constexpr int NG = NR / 4;
-    constexpr int EV = 4 / (int)sizeof(T);          // adjacent elements per access: 1 float or 2 bfloat16
-    static_assert(NR % EV == 0 && NG % EV == 0, "whole access groups per thread");
-    // groups per thread; with pairs one more, since the pair grid may start one element early
-    constexpr int KX = NR / EV + (EV > 1), KG = NG / EV + (EV > 1);
-    extern __shared__ float pool_lds[];
-    const int HW = H * W, PP = PH * PW;
-    // Element e of the staged group sits at index e + (shift of its pair grid): a bfloat16 pair then is two
-    // adjacent floats at an 8-byte aligned LDS address, one store / one load instead of two with a two-way bank
-    // conflict.  Both arrays have room for that one extra element.
-    float *sx = pool_lds;                            // group * HW inputs
-    float *sacc = pool_lds + ((group * HW + 2) & ~1);    // group * HW routed gradients
-    const int tid = threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * group;
-    float xr[KX][EV], gr[KG][EV];
-    int xs = 0, gs = 0;                              // shifts of the pair grids of the fetched x and dy groups
+    PoolWalkLane L;
+    if (!pool_walk_lane(L, planes, H * W, W, seg, ppw, dseg)) return;
+    const int j = L.j, c0 = 2 * j;
+    const bool win = L.live && j < PW;
+    const T *xp = x + L.plane * (H * W);
+    const T *gp = dy + L.plane * (PH * PW) + (j < PW ? j : PW - 1);
+    T *op = dx + L.plane * (H * W);
+    typedef decltype(ld_pair_raw(xp)) Raw;
 
-    auto fetch = [&](int64_t pl0) {
-        const int np = (int)min((int64_t)group, planes - pl0);
-        const T *xg = x + pl0 * HW;
-        const T *gg = dy + pl0 * PP;
-        xs = align_shift(xg);
-        gs = align_shift(gg);
-#pragma unroll
-        for (int k = 0; k < KX; ++k) ld_group(xg, EV * (tid + 256 * k) - xs, np * HW, xr[k]);
-#pragma unroll
-        for (int k = 0; k < KG; ++k) ld_group(gg, EV * (tid + 256 * k) - gs, np * PP, gr[k]);
+    // the pair of row h, read from a clamped offset; pair_fix() undoes the clamp's shift of one element
+    auto pair_off = [&](int h) { const int o = h * W + c0; return o < L.lim ? o : L.lim; };
+    auto first_of = [&](Raw r, int h) { return h * W + c0 > L.lim ? pair_hi(r) : pair_lo(r); };
+    auto store_row = [&](int h, float d0, float d1) {
+        if (!L.live) return;
+        if (L.has1) st_pair(op + h * W + c0, d0, d1);
+        else st_elem(op, h * W + c0, d0);
     };
 
-    int64_t pl0 = (int64_t)blockIdx.x * group;
-    if (pl0 < planes) fetch(pl0);
-    for (; pl0 < planes; pl0 += stride) {
-        const int np = (int)min((int64_t)group, planes - pl0);
-        T *og = dx + pl0 * HW;
-        const int os = align_shift(og);
-        const int xc = xs;                           // (xs moves on with the prefetch below)
-        float *const sxe = sx + xc, *const sae = sacc + xc;
-        typedef float f32x2 __attribute__((ext_vector_type(2)));
+    Raw r1[D], r2[D];
+    T gr[D];
+    auto issue = [&](int slot, int i) {
+        const int ic = i < PH ? i : PH - 1;
+        r1[slot] = ld_pair_raw(xp + pair_off(2 * ic + 1));
+        r2[slot] = ld_pair_raw(xp + pair_off(2 * ic + 2));
+        gr[slot] = gp[ic * PW];
+    };
+    const Raw r0 = ld_pair_raw(xp + pair_off(0));
 #pragma unroll
-        for (int k = 0; k < KX; ++k) {
-            const int e0 = EV * (tid + 256 * k) - xc;
-            if (EV == 2 && e0 >= 0 && e0 + 1 < np * HW) {
-                *reinterpret_cast<f32x2 *>(sxe + e0) = f32x2{xr[k][0], xr[k][EV - 1]};
-                *reinterpret_cast<f32x2 *>(sae + e0) = f32x2{0.f, 0.f};
-            } else {
+    for (int d = 0; d < D; ++d) issue(d, d);
+
+    float a00 = first_of(r0, 0), a01 = pair_hi(r0), a02 = __shfl_down(a00, 1);
+    float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f;                    // gradients routed so far to row 2i of (2j, 2j+1, 2j+2)
+    auto finish_row = [&](int h, float e0, float e1, float e2, float v0, float v1) {
+        const float t = __shfl_up(e2, 1);
+        float d0 = j > 0 ? e0 + t : e0, d1 = e1;
+        if (RELU && !(v0 > 0.f)) d0 = 0.f;
+        if (RELU && !(v1 > 0.f)) d1 = 0.f;
+        store_row(h, d0, d1);
+    };
+    auto step = [&](int d, int i) {                              // window row i from slot d; refill the slot
+        const float a10 = first_of(r1[d], 2 * i + 1), a11 = pair_hi(r1[d]);
+        const float a20 = first_of(r2[d], 2 * i + 2), a21 = pair_hi(r2[d]);
+        const float g = win ? raw_elem(gr[d]) : 0.f;
+        issue(d, i + D);
+        const float a12 = __shfl_down(a10, 1), a22 = __shfl_down(a20, 1);
+        int best = 0;
+        float m = a00;
+        if (a01 > m) { m = a01; best = 1; }
+        if (a02 > m) { m = a02; best = 2; }
+        if (a10 > m) { m = a10; best = 3; }
+        if (a11 > m) { m = a11; best = 4; }
+        if (a12 > m) { m = a12; best = 5; }
+        if (a20 > m) { m = a20; best = 6; }
+        if (a21 > m) { m = a21; best = 7; }
+        if (a22 > m) { m = a22; best = 8; }
+        finish_row(2 * i, acc0 + (best == 0 ? g : 0.f), acc1 + (best == 1 ? g : 0.f), acc2 + (best == 2 ? g : 0.f),
+                   a00, a01);
+        finish_row(2 * i + 1, best == 3 ? g : 0.f, best == 4 ? g : 0.f, best == 5 ? g : 0.f, a10, a11);
+        acc0 = best == 6 ? g : 0.f; acc1 = best == 7 ? g : 0.f; acc2 = best == 8 ? g : 0.f;
+        a00 = a20; a01 = a21; a02 = a22;
+    };
+    // whole groups of D window rows without a branch between them (a branch would make the compiler wait for every
+    // load in flight), then the rest
+    int i0 = 0;
+    for (; i0 + D <= PH; i0 += D) {
 #pragma unroll
-                for (int u = 0; u < EV; ++u) {
-                    const int e = e0 + u;
-                    if (e >= 0 && e < np * HW) { sxe[e] = xr[k][u]; sae[e] = 0.f; }
-                }
-            }
-        }
-        __syncthreads();
-        // every window's first maximum, once; cls = parity class (i % 2, j % 2) of the window, -1 = no window
-        int best[KG][EV], cls[KG][EV];
-        float g[KG][EV];
-#pragma unroll
-        for (int k = 0; k < KG; ++k)
-#pragma unroll
-            for (int u = 0; u < EV; ++u) {
-                const int o = EV * (tid + 256 * k) - gs + u;
-                best[k][u] = 0; cls[k][u] = -1; g[k][u] = gr[k][u];
-                if (o >= 0 && o < np * PP) {
-                    const int pl = (int)fastdiv((uint32_t)o, dPP), rem = o - pl * PP;
-                    const int i = (int)fastdiv((uint32_t)rem, dPW), j = rem - i * PW;
-                    float m;
-                    best[k][u] = pl * HW + pool_argmax(sxe + pl * HW, W, i, j, m);
-                    cls[k][u] = (i & 1) * 2 + (j & 1);
-                }
-            }
-        if (pl0 + stride < planes) fetch(pl0 + stride);
-        // windows of one parity class are disjoint (stride 2, extent 3), so within a phase every accumulator has at
-        // most one writer; an element receives its up to four gradients in phase order
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-#pragma unroll
-            for (int k = 0; k < KG; ++k)
-#pragma unroll
-                for (int u = 0; u < EV; ++u)
-                    if (cls[k][u] == c) sae[best[k][u]] += g[k][u];
-            __syncthreads();
-        }
-#pragma unroll
-        for (int k = 0; k < KX; ++k) {
-            float res[EV];
-            const int e0 = EV * (tid + 256 * k) - os;
-            if (EV == 2 && os == xc && e0 >= 0 && e0 + 1 < np * HW) {
-                const f32x2 a = *reinterpret_cast<const f32x2 *>(sae + e0);
-                const f32x2 v = *reinterpret_cast<const f32x2 *>(sxe + e0);
-                res[0] = (RELU && !(v[0] > 0.f)) ? 0.f : a[0];
-                res[EV - 1] = (RELU && !(v[1] > 0.f)) ? 0.f : a[1];
-            } else {
-#pragma unroll
-                for (int u = 0; u < EV; ++u) {
-                    const int e = e0 + u;
-                    float sum = 0.f;
-                    if (e >= 0 && e < np * HW) {
-                        sum = sae[e];
-                        if (RELU && !(sxe[e] > 0.f)) sum = 0.f;
-                    }
-                    res[u] = sum;
-                }
-            }
-            st_group(og, e0, np * HW, res);
-        }
-        __syncthreads();
+        for (int d = 0; d < D; ++d) step(d, i0 + d);
     }
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d)
+        if (i0 + d < PH) step(d, i0 + d);
+    finish_row(2 * PH, acc0, acc1, acc2, a00, a01);
+    for (int h = 2 * PH + 1; h < H; ++h) store_row(h, 0.f, 0.f);      // a last row that no window reaches
 }
 
-// Fallback for planes too large to stage: one thread per input element
-// recomputes the windows that contain it.
+template <bool RELU, typename T, int D>
+__global__ __launch_bounds__(256) void maxpool_fwd_walk(const T *__restrict__ x, T *__restrict__ y, int64_t planes,
+                                                         int H, int W, int PH, int PW, int seg, int ppw, FastDiv dseg)
+{
+    PoolWalkLane L;
+    if (!pool_walk_lane(L, planes, H * W, W, seg, ppw, dseg)) return;
+    const int j = L.j, c0 = 2 * j;
+    const bool win = L.live && j < PW;
+    const T *xp = x + L.plane * (H * W);
+    T *yp = y + L.plane * (PH * PW) + j;
+    typedef decltype(ld_pair_raw(xp)) Raw;
+    auto pair_off = [&](int h) { const int o = h * W + c0; return o < L.lim ? o : L.lim; };
+    auto first_of = [&](Raw r, int h) { return h * W + c0 > L.lim ? pair_hi(r) : pair_lo(r); };
+
+    Raw r1[D], r2[D];
+    auto issue = [&](int slot, int i) {
+        const int ic = i < PH ? i : PH - 1;
+        r1[slot] = ld_pair_raw(xp + pair_off(2 * ic + 1));
+        r2[slot] = ld_pair_raw(xp + pair_off(2 * ic + 2));
+    };
+    const Raw r0 = ld_pair_raw(xp + pair_off(0));
+#pragma unroll
+    for (int d = 0; d < D; ++d) issue(d, d);
+    float a00 = first_of(r0, 0), a01 = pair_hi(r0), a02 = __shfl_down(a00, 1);
+    auto step = [&](int d, int i) {
+        const float a10 = first_of(r1[d], 2 * i + 1), a11 = pair_hi(r1[d]);
+        const float a20 = first_of(r2[d], 2 * i + 2), a21 = pair_hi(r2[d]);
+        issue(d, i + D);
+        const float a12 = __shfl_down(a10, 1), a22 = __shfl_down(a20, 1);
+        float m = a00;                                           // the same scan as pool_argmax
+        if (a01 > m) m = a01;
+        if (a02 > m) m = a02;
+        if (a10 > m) m = a10;
+        if (a11 > m) m = a11;
+        if (a12 > m) m = a12;
+        if (a20 > m) m = a20;
+        if (a21 > m) m = a21;
+        if (a22 > m) m = a22;
+        if (win) st_elem(yp, i * PW, RELU ? (m > 0.f ? m : 0.f) : m);
+        a00 = a20; a01 = a21; a02 = a22;
+    };
+    int i0 = 0;
+    for (; i0 + D <= PH; i0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) step(d, i0 + d);
+    }
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d)
+        if (i0 + d < PH) step(d, i0 + d);
+}
+
+// Planes wider than a wavefront's column pairs: one thread per input element recomputes the windows that contain it.
 template <bool RELU, typename T>
 __global__ void maxpool_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy,
                                    T *__restrict__ dx, int64_t total, int H, int W, int PH, int PW)

@@ -453,10 +453,11 @@ def test_relu_and_pool_match_oracle():
 
 def test_fused_relu_pool_matches_separate_oracle_calls():
     """relu_maxpool3x3s2_fwd/bwd take the pre-activation and must equal ReLU then pooling (and back)."""
-    # the last four: one large plane per work-group, the large-plane fallback, and plane counts beyond one
-    # round of the persistent grid (one plane per group, several planes per group)
+    # after the layer shapes: even extents (a last row / column that no window reaches), planes that fill a wavefront
+    # exactly (width 127, 128), the wide-plane fallback (129), and plane counts that leave lanes of the last wave idle
     for (N, C, H, W) in [(3, 5, 55, 55), (2, 7, 27, 27), (9, 33, 13, 13), (1, 1, 3, 3), (2, 2, 8, 5), (1, 3, 90, 100),
-                         (1, 2, 120, 115), (20, 83, 55, 55), (32, 251, 27, 27)]:
+                         (1, 2, 120, 115), (1, 2, 9, 127), (1, 3, 10, 128), (1, 2, 6, 129), (20, 83, 55, 55),
+                         (32, 251, 27, 27)]:
         x = synth.gaussian((N, C, H, W), 161)
         x[0, 0, :3, :3] = -1.0                                  # a window with no positive entry
         x[0, 0, 0, 0] = -0.5
@@ -469,7 +470,7 @@ def test_fused_relu_pool_matches_separate_oracle_calls():
         dx = hp.relu_maxpool3x3s2_bwd(xd, dev(g), dx=nan_like(x.shape))
         want = oracle.relu_bwd(x, oracle.maxpool3x3s2_bwd(r, g))
         assert norm_err(dx.cpu().numpy(), want) <= 1e-6
-        # the unfused entry points on the same planes (tiled kernel and large-plane fallback)
+        # the unfused entry points on the same planes
         dxp = hp.maxpool3x3s2_bwd(xd, dev(g), dx=nan_like(x.shape))
         assert norm_err(dxp.cpu().numpy(), oracle.maxpool3x3s2_bwd(x, g)) <= 1e-6
 
@@ -579,7 +580,7 @@ def test_bf16_glue_matches_oracle():
     """Glue on bfloat16 tensors: ReLU and pooling forward return input values (exact); pooling backward adds up to
     four bf16 gradients in fp32 and rounds once."""
     for (N, C, H, W) in [(3, 5, 55, 55), (2, 7, 27, 27), (9, 33, 13, 13), (1, 1, 3, 3), (2, 2, 8, 5), (1, 3, 90, 100),
-                         (1, 2, 120, 115), (1, 1, 7, 1003)]:
+                         (1, 2, 120, 115), (1, 2, 9, 127), (1, 3, 10, 128), (1, 1, 7, 1003)]:
         x = oracle.bf16_round(synth.gaussian((N, C, H, W), 171))
         x[0, 0, :3, :3] = 0.0
         xd = dev(x, "bf16")
