@@ -397,10 +397,13 @@ struct PatchBf16Args {
     FastDiv div_q, div_j, div_nr, div_wv;
 };
 
-template <int TM, typename TO>
+constexpr int kPatchBf16Pieces(int tn) { return tn == 1 ? 8 : 12; }   // 16-byte row pieces per thread and tile
+
+template <int TM, int TN, typename TO>
 __global__ __launch_bounds__(kThreads, 1) void conv_patch_bf16_kernel(const PatchBf16Args p)
 {
-    constexpr int NV = 8;                        // 16-byte row pieces per thread and tile (host checks the bound)
+    constexpr int NV = kPatchBf16Pieces(TN);     // (the host checks the bound)
+    constexpr int BN = 128 * TN;                 // positions per tile: 32 * TN per wave
     extern __shared__ __attribute__((aligned(16))) float lds_fast[];
     char *const fl = reinterpret_cast<char *>(lds_fast);                  // filters: nslices * Mpad * 32 bytes
     const int fbytes = p.nslices * p.Mpad * 32;
@@ -418,39 +421,61 @@ __global__ __launch_bounds__(kThreads, 1) void conv_patch_bf16_kernel(const Patc
     const int pwords = p.C * p.NR * p.WP / 2;
     for (int i = tid; i < pwords; i += kThreads) reinterpret_cast<unsigned *>(patch)[i] = 0u;
 
+    // this lane's bias values, once: accumulator element v of block i belongs to row i*32 + half*4 + (v>>2)*8 + (v&3)
+    float bias[TM][16];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            bias[i][v] = (p.epi_on && p.epi.bias) ? p.epi.bias[min(i * 32 + half * 4 + (v >> 2) * 8 + (v & 3), p.M - 1)] : 0.f;
+
+    // This thread's 16-byte pieces of a tile's rows; which piece of which row of which channel does not depend on
+    // the tile: piece e = tid + u * kThreads is piece v of staged row i of channel c.
     const int wv = p.W / 8;                      // 16-byte pieces per input row
     const int pieces = p.C * p.NR * wv;
+    int prow[NV];                                // staged row i, or a row no tile has (-NR - H) for e >= pieces
+    int pgoff[NV];                               // (c*H + i)*W + 8v: element offset in the image at h0 = 0
+    int pdst[NV];                                // element offset in the patch: (c*NR + i)*WP + pad + 8v (4-byte aligned)
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int e = tid + u * kThreads;
+        const int ee = e < pieces ? e : 0;
+        const int row = (int)fastdiv((uint32_t)ee, p.div_wv);            // c * NR + i
+        const int v = ee - row * wv;
+        const int c = (int)fastdiv((uint32_t)row, p.div_nr);
+        const int i = row - c * p.NR;
+        prow[u] = e < pieces ? i : -p.NR - p.H;
+        pgoff[u] = (c * p.H + i) * p.W + v * 8;
+        pdst[u] = row * p.WP + p.pad + v * 8;
+    }
     u32x4 stage[NV];
-    // global loads of a tile's rows into registers (zeros for rows outside the image)
+    auto first_row = [&](int tile) {             // input row of a tile's staged row 0
+        const int n = (int)fastdiv((uint32_t)tile, p.div_j);
+        const int p0 = (int)fastdiv((uint32_t)((tile - n * p.jtiles) * BN), p.div_q);
+        return p0 * p.stride - p.pad;
+    };
+    // global loads of a tile's rows into registers; rows outside the image are loaded from a valid address and
+    // replaced by zeros only when they are stored (a select on the loaded value here would wait for the load)
     auto load_tile = [&](int tile) {
         const int n = (int)fastdiv((uint32_t)tile, p.div_j);
-        const int jt = tile - n * p.jtiles;
-        const int p0 = (int)fastdiv((uint32_t)(jt * 128), p.div_q);
-        const int h0 = p0 * p.stride - p.pad;
-        const unsigned short *xn = p.x + (size_t)n * p.x_bs;
+        const int h0 = first_row(tile);
+        const unsigned short *xn = p.x + (size_t)n * p.x_bs + h0 * p.W;
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int e = tid + u * kThreads;
-            const int ee = e < pieces ? e : 0;
-            const int row = (int)fastdiv((uint32_t)ee, p.div_wv);        // c * NR + i
-            const int v = ee - row * wv;
-            const int c = (int)fastdiv((uint32_t)row, p.div_nr);
-            const int h = h0 + row - c * p.NR;
-            const bool ok = (e < pieces) & ((unsigned)h < (unsigned)p.H);
-            const u32x4 val = *reinterpret_cast<const u32x4 *>(xn + (size_t)(ok ? (c * p.H + h) * p.W + v * 8 : 0));
-            stage[u] = ok ? val : u32x4{0u, 0u, 0u, 0u};
+            const bool ok = (unsigned)(h0 + prow[u]) < (unsigned)p.H;
+            stage[u] = *reinterpret_cast<const u32x4 *>(ok ? xn + pgoff[u] : p.x);
         }
     };
-    // ... and from the registers into the patch: piece v of row lands at element row*WP + pad + 8v (4-byte aligned)
-    auto store_tile = [&]() {
+    // ... and from the registers into the patch
+    auto store_tile = [&](int tile) {
+        const int h0 = first_row(tile);
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
-            const int e = tid + u * kThreads;
-            if (e < pieces) {
-                const int row = (int)fastdiv((uint32_t)e, p.div_wv);
-                const int v = e - row * wv;
-                unsigned *dst = reinterpret_cast<unsigned *>(patch + row * p.WP + p.pad + v * 8);
-                dst[0] = stage[u][0]; dst[1] = stage[u][1]; dst[2] = stage[u][2]; dst[3] = stage[u][3];
+            if (prow[u] >= 0) {
+                const bool ok = (unsigned)(h0 + prow[u]) < (unsigned)p.H;
+                unsigned *dst = reinterpret_cast<unsigned *>(patch + pdst[u]);
+                dst[0] = ok ? stage[u][0] : 0u; dst[1] = ok ? stage[u][1] : 0u;
+                dst[2] = ok ? stage[u][2] : 0u; dst[3] = ok ? stage[u][3] : 0u;
             }
         }
     };
@@ -462,80 +487,165 @@ __global__ __launch_bounds__(kThreads, 1) void conv_patch_bf16_kernel(const Patc
 
     const int a_off = l32 * 32 + ((half ^ ((l32 >> 3) & 1)) * 16);        // this lane's 16 bytes of a 32-row block
     for (; tile < p.ntiles; tile += gridDim.x) {
-        store_tile();
+        store_tile(tile);
         __syncthreads();
         const int next = tile + gridDim.x;
         if (next < p.ntiles) load_tile(next);
 
         const int n = (int)fastdiv((uint32_t)tile, p.div_j);
         const int jt = tile - n * p.jtiles;
-        const int j0 = jt * 128;
+        const int j0 = jt * BN;
         const int p0 = (int)fastdiv((uint32_t)j0, p.div_q);
-        const int j = j0 + wave * 32 + l32;
-        const bool jok = j < p.PQ;
-        int colbase;                             // element offset of this lane's position inside a channel's rows
-        {
-            const int jj = jok ? j : j0;
+        const int jw = j0 + wave * (32 * TN) + l32;              // this lane's position in block 0; block b: + 32 b
+        int colbase[TN];                         // element offset of this lane's positions inside a channel's rows
+#pragma unroll
+        for (int b = 0; b < TN; ++b) {
+            const int j = jw + 32 * b;
+            const int jj = j < p.PQ ? j : j0;
             const int pp = (int)fastdiv((uint32_t)jj, p.div_q);
             const int qq = jj - pp * p.Q;
-            colbase = (pp - p0) * p.stride * p.WP + qq * p.stride + 8 * half;
+            colbase[b] = (pp - p0) * p.stride * p.WP + qq * p.stride + 8 * half;
         }
-        f32x16 acc[TM];
+        f32x16 acc[TM][TN];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+            for (int b = 0; b < TN; ++b)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][b][v] = 0.f;
 
-        // slices: the fragments of slice sl + 1 are read while slice sl is multiplied
-        u32x4 fa[2][TM];
+        // slices: three sets of fragments, so that the reads of slices sl + 1 and sl + 2 are in flight while slice
+        // sl is multiplied (one wave per SIMD: nothing else hides the LDS latency)
+        u32x4 fa[3][TM];
         typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-        u32x2 fb[2][2];
-        auto read_slice = [&](int sl, int c, int r, int set) {
-            const char *a = fl + sl * p.Mpad * 32 + a_off;
+        u32x2 fb[3][TN][2];
+        // next slice to read: its index, its filter row, the byte offsets of its filter block (this lane's) and of
+        // its first patch row.  With one wave per SIMD every bookkeeping instruction takes an issue slot that the
+        // matrix instructions do not hide, so the offsets advance by additions only.
+        int nxt = 0, r = 0;
+        unsigned a_cur = (unsigned)a_off, b_cur = 0;
+        const unsigned a_step = (unsigned)p.Mpad * 32, row_step = (unsigned)p.WP * 2,
+                       wrap_step = (unsigned)(p.NR - p.R + 1) * p.WP * 2;
+        unsigned colbytes[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[set][i] = *reinterpret_cast<const u32x4 *>(a + i * 1024);
-            const unsigned short *b = patch + (c * p.NR + r) * p.WP + colbase;
-            fb[set][0] = *reinterpret_cast<const u32x2 *>(b);
-            fb[set][1] = *reinterpret_cast<const u32x2 *>(b + 4);
+        for (int b = 0; b < TN; ++b) colbytes[b] = (unsigned)colbase[b] * 2;
+        const char *const pb = reinterpret_cast<const char *>(patch);
+        // No branch inside the loop (one would make the compiler wait for the fragment reads right after issuing
+        // them): past the last slice, that slice is read again instead.
+        auto read_into = [&](int set) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[set][i] = *reinterpret_cast<const u32x4 *>(fl + a_cur + i * 1024);
+#pragma unroll
+            for (int b = 0; b < TN; ++b) {
+                fb[set][b][0] = *reinterpret_cast<const u32x2 *>(pb + b_cur + colbytes[b]);
+                fb[set][b][1] = *reinterpret_cast<const u32x2 *>(pb + b_cur + colbytes[b] + 8);
+            }
+            const bool more = nxt + 1 < p.nslices;
+            const bool wrap = r + 1 == p.R;
+            nxt += more ? 1 : 0;
+            a_cur += more ? a_step : 0u;
+            b_cur += more ? (wrap ? wrap_step : row_step) : 0u;
+            r = wrap ? 0 : r + 1;
         };
-        int c = 0, r = 0;
-        read_slice(0, 0, 0, 0);
-        for (int sl = 0; sl < p.nslices; sl += 2) {
+        auto multiply = [&](int set) {
 #pragma unroll
-            for (int par = 0; par < 2; ++par) {
-                if (sl + par < p.nslices) {
-                    r += 1;
-                    if (r == p.R) { r = 0; c += 1; }
-                    if (sl + par + 1 < p.nslices) read_slice(sl + par + 1, c, r, par ^ 1);
-                    const u32x4 bq = {fb[par][0][0], fb[par][0][1], fb[par][1][0], fb[par][1][1]};
+            for (int b = 0; b < TN; ++b) {
+                const u32x4 bq = {fb[set][b][0][0], fb[set][b][0][1], fb[set][b][1][0], fb[set][b][1][1]};
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
-                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[par][i]),
-                                                                         __builtin_bit_cast(bf16x8, bq), acc[i], 0, 0, 0);
-                }
+                for (int i = 0; i < TM; ++i)
+                    acc[i][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[set][i]),
+                                                                        __builtin_bit_cast(bf16x8, bq), acc[i][b], 0, 0, 0);
+            }
+        };
+        read_into(0);
+        read_into(1);
+        int sl = 0;
+        // One phase = the reads of one slice and the matrix instructions of another.  The scheduling directives
+        // spread the phase's reads and bookkeeping between its matrix instructions (with one wave per SIMD an
+        // instruction issued between two matrix instructions is free, one issued before or after them is not) and
+        // keep the phases apart, so that the compiler cannot move a slice's matrix instructions up to its reads.
+        auto phase = [&](int rd, int mul) {
+            read_into(rd);
+            multiply(mul);
+#pragma unroll
+            for (int k = 0; k < TM * TN; ++k) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           // one matrix instruction
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);           // one LDS read
+                __builtin_amdgcn_sched_group_barrier(0x006, 4, 0);           // scalar / vector bookkeeping
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        for (; sl + 3 <= p.nslices; sl += 3) {
+            phase(2, 0);
+            phase(0, 1);
+            phase(1, 2);
+        }
+        if (sl < p.nslices) multiply(0);                         // sets 0 and 1 hold slices sl and sl + 1
+        if (sl + 1 < p.nslices) multiply(1);
+
+        if (p.epi_on) {                                              // forward only: bias and ReLU, no mask
+            if (p.epi.bias) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[i][b][v] += bias[i][v];
+            }
+            if (p.epi.relu) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int b = 0; b < TN; ++b)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) acc[i][b][v] = acc[i][b][v] > 0.f ? acc[i][b][v] : 0.f;
             }
         }
-
-        if (jok) {
-            TO *out = static_cast<TO *>(p.y) + (size_t)n * p.y_bs + j;
+        bool stored = false;
+        if constexpr (sizeof(TO) == 2) {
+            // bfloat16 output, every row and position of the tile inside the tensor: neighbouring lanes (positions
+            // j, j + 1) trade one value each, so that the even lane stores row a of both positions and the odd lane
+            // row a + 1 of both -- one 4-byte store per lane for two accumulator registers, rounded in hardware
+            // (byte offsets from the tensor's base in 32 bits, which the host has checked: one vector addition
+            // per store instead of a 64-bit one)
+            if (p.M == TM * 32 && j0 + BN <= p.PQ) {
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                const bool odd = l32 & 1;
+                char *const yb = static_cast<char *>(p.y);
+                const unsigned ob = 2u * ((unsigned)n * (unsigned)p.y_bs + (unsigned)(half * 4 + (odd ? 1 : 0)) * (unsigned)p.PQ +
+                                          (unsigned)(jw & ~1));
+                const unsigned row_bytes = 2u * (unsigned)p.PQ;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int row0 = i * 32 + half * 4;
-                if (p.epi_on) {                                      // forward only: bias and ReLU, no mask
-                    float bv16[16];
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        bv16[v] = p.epi.bias ? p.epi.bias[min(row0 + (v >> 2) * 8 + (v & 3), p.M - 1)] : 0.f;
+                    for (int b = 0; b < TN; ++b)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const float t = acc[i][v] + bv16[v];
-                        acc[i][v] = (p.epi.relu && !(t > 0.f)) ? 0.f : t;
-                    }
-                }
+                        for (int v = 0; v < 16; v += 2) {
+                            const float va = acc[i][b][v], vb = acc[i][b][v + 1];
+                            const float send = odd ? va : vb;
+                            const float recv = __builtin_bit_cast(
+                                float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+                            const f32x2 pr = {odd ? recv : va, odd ? vb : recv};
+                            const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
+                            __builtin_memcpy(yb + (ob + (unsigned)(i * 32 + (v >> 2) * 8 + (v & 3)) * row_bytes + 64u * b), &pk, 4);
+                        }
+                stored = true;
+            }
+        }
+        if (!stored) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int row = row0 + (v >> 2) * 8 + (v & 3);
-                    if (row < p.M) st_elem(out, (int64_t)row * p.PQ, acc[i][v]);
+            for (int b = 0; b < TN; ++b) {
+                const int j = jw + 32 * b;
+                if (j < p.PQ) {
+                    TO *out = static_cast<TO *>(p.y) + (size_t)n * p.y_bs + j;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            const int row = i * 32 + half * 4 + (v >> 2) * 8 + (v & 3);
+                            if (row < p.M) st_elem(out, (int64_t)row * p.PQ, acc[i][b][v]);
+                        }
                 }
             }
         }

@@ -245,19 +245,37 @@ constexpr int kNotTaken = 1;          // a specialised path declined the shape: 
 
 // Few-channel forward with bf16 inputs on the bf16 matrix instruction (conv_patch_bf16_kernel); kNotTaken where its
 // alignment or size conditions do not hold.
+template <int TN, typename TO>
+const void *patch_bf16_kernel(int tm)
+{
+    return tm == 1 ? (const void *)conv_patch_bf16_kernel<1, TN, TO> : tm == 2 ? (const void *)conv_patch_bf16_kernel<2, TN, TO>
+         : tm == 3 ? (const void *)conv_patch_bf16_kernel<3, TN, TO> : (const void *)conv_patch_bf16_kernel<4, TN, TO>;
+}
+
 int run_patch_bf16(const void *x, const void *w, void *out, const Problem &pb, const Plan &pl, void *ws,
                    hipStream_t st, const Epilogue *ep, bool *ep_applied)
 {
     const int tm = pl.patch_tm, mpad = tm * 32;
     if (pb.S > 16 || pb.stride % 4 != 0 || pb.pad % 2 != 0 || pb.W % 8 != 0 || pb.x_bs % 8 != 0 || pl.M > mpad)
         return kNotTaken;
+    if ((int64_t)pb.N * pb.y_bs * 2 >= ((int64_t)1 << 31)) return kNotTaken;     // 32-bit byte offsets into a bf16 output
     const int need_w = std::max(pb.pad + pb.W, (pb.Q - 1) * pb.stride + 16);
     const int wp = round_up(need_w, 4);
     const int nslices = pb.C * pb.R;
     const int64_t fbytes = (int64_t)nslices * mpad * 32;
-    const int64_t lds = fbytes + (int64_t)pb.C * pl.patch_nr * wp * 2;
-    const int64_t pieces = (int64_t)pb.C * pl.patch_nr * (pb.W / 8);
-    if (lds > 159 * 1024 || pieces > 8 * kThreads || fbytes > (int64_t)pl.wt_bytes) return kNotTaken;
+    if (fbytes > (int64_t)pl.wt_bytes) return kNotTaken;
+    // 256 positions per tile (each filter fragment read from LDS feeds two matrix instructions) where the tile's
+    // input rows fit beside the filters, else 128
+    int tn = 0, nr = 0;
+    int64_t lds = 0;
+    for (int t = tm <= 3 ? 2 : 1; t >= 1 && !tn; --t) {
+        const int span = std::min((pb.Q + 128 * t - 2) / pb.Q, pb.P - 1);     // output rows a tile can straddle, minus one
+        const int rows = span * pb.stride + pb.R;
+        const int64_t bytes = fbytes + (int64_t)pb.C * rows * wp * 2;
+        const int64_t pieces = (int64_t)pb.C * rows * (pb.W / 8);
+        if (bytes <= 159 * 1024 && pieces <= kPatchBf16Pieces(t) * kThreads) { tn = t; nr = rows; lds = bytes; }
+    }
+    if (!tn) return kNotTaken;
     char *wsb = static_cast<char *>(ws);
     unsigned short *ft = reinterpret_cast<unsigned short *>(wsb + pl.wt_off);
     hipLaunchKernelGGL(relayout_filters_rows_bf16, dim3(grid1d(fbytes / 2, 256)), dim3(256), 0, st,
@@ -266,25 +284,19 @@ int run_patch_bf16(const void *x, const void *w, void *out, const Problem &pb, c
     a.Ft = ft; a.x = static_cast<const unsigned short *>(x); a.y = out;
     a.M = pl.M; a.Mpad = mpad; a.nslices = nslices;
     a.C = pb.C; a.H = pb.H; a.W = pb.W; a.R = pb.R; a.stride = pb.stride; a.pad = pb.pad;
-    a.P = pb.P; a.Q = pb.Q; a.PQ = pb.P * pb.Q; a.NR = pl.patch_nr; a.WP = wp;
+    a.P = pb.P; a.Q = pb.Q; a.PQ = pb.P * pb.Q; a.NR = nr; a.WP = wp;
     a.x_bs = (int)pb.x_bs; a.y_bs = (int)pb.y_bs;
-    a.jtiles = ceil_div(a.PQ, 128); a.ntiles = pb.N * a.jtiles;
+    a.jtiles = ceil_div(a.PQ, 128 * tn); a.ntiles = pb.N * a.jtiles;
     a.epi_on = ep != nullptr;
     a.epi = ep ? *ep : Epilogue{};
     *ep_applied = a.epi_on;
     a.div_q = make_fastdiv((uint32_t)pb.Q);
     a.div_j = make_fastdiv((uint32_t)a.jtiles);
-    a.div_nr = make_fastdiv((uint32_t)pl.patch_nr);
+    a.div_nr = make_fastdiv((uint32_t)nr);
     a.div_wv = make_fastdiv((uint32_t)(pb.W / 8));
     const int grid = std::min(a.ntiles, 256);
-    const void *k = nullptr;
-    if (pb.out_bf16) {
-        k = tm == 1 ? (const void *)conv_patch_bf16_kernel<1, unsigned short> : tm == 2 ? (const void *)conv_patch_bf16_kernel<2, unsigned short>
-          : tm == 3 ? (const void *)conv_patch_bf16_kernel<3, unsigned short> : (const void *)conv_patch_bf16_kernel<4, unsigned short>;
-    } else {
-        k = tm == 1 ? (const void *)conv_patch_bf16_kernel<1, float> : tm == 2 ? (const void *)conv_patch_bf16_kernel<2, float>
-          : tm == 3 ? (const void *)conv_patch_bf16_kernel<3, float> : (const void *)conv_patch_bf16_kernel<4, float>;
-    }
+    const void *k = pb.out_bf16 ? (tn == 2 ? patch_bf16_kernel<2, unsigned short>(tm) : patch_bf16_kernel<1, unsigned short>(tm))
+                                : (tn == 2 ? patch_bf16_kernel<2, float>(tm) : patch_bf16_kernel<1, float>(tm));
     (void)hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     void *args[] = {&a};
     hipError_t e = hipLaunchKernel(k, dim3(grid), dim3(kThreads), args, (size_t)lds, st);
