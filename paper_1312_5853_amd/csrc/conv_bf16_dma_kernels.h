@@ -35,6 +35,7 @@ struct ColGemmDmaArgs {
     int R, S, sign;        // sign +1: tap (r, s) reads padded (oh*mul + r, ow*mul + s); -1: (oh + R-1-r, ow + S-1-s)
     int cblocks;           // channels / KC
     int dst_bs, out_bf16;
+    int dst_small;         // a bfloat16 dst is shorter than 2 GB: byte offsets into it fit 32 bits
     int mtiles, ntiles, tiles_per_xcd, ksplit, steps_per_split;
     int epi_on;
     Epilogue epi;
@@ -234,6 +235,45 @@ __global__ __launch_bounds__(WM * WN * 64, OCC) void colgemm_bf16_dma_kernel(con
         if (p.epi_on && p.ksplit == 1)            // split sums get it in reduce_split_outputs
             epi_tile<TM, TN>(p.epi, acc, jn, m0 + wm * TM * 32 + half * 4, p.M, plane,
                              (int64_t)n * p.epi.mask_bs + rem);
+        if (p.ksplit == 1 && p.out_bf16 && p.dst_small && m0 + BM <= p.M && n0 + BN <= p.ncols) {
+            // Whole tile inside the tensor: neighbouring lanes (positions col, col + 1 of one sample) trade a value
+            // so that the even lane stores row a of both positions and the odd lane row a + 1 of both: one 4-byte
+            // store per lane for two accumulator registers, rounded in hardware.  Lanes whose neighbour belongs to
+            // another sample store their values one by one.
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+            char *const yb = static_cast<char *>(p.dst);
+            const bool odd = l32 & 1;
+            const bool pair = odd ? rem >= 1 : rem + 1 < plane;
+            const unsigned own = (unsigned)n * (unsigned)p.dst_bs + (unsigned)rem;
+            const unsigned row_bytes = 2u * (unsigned)plane;
+            const unsigned rowb = (unsigned)(m0 + wm * TM * 32 + half * 4);
+            if (pair) {
+                const unsigned ob = 2u * (own - (odd ? 1u : 0u)) + (rowb + (odd ? 1u : 0u)) * row_bytes;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; v += 2) {
+                        const float va = acc[i][jn][v], vb = acc[i][jn][v + 1];
+                        const float send = odd ? va : vb;
+                        const float recv = __builtin_bit_cast(
+                            float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+                        const f32x2 pr = {odd ? recv : va, odd ? vb : recv};
+                        const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
+                        __builtin_memcpy(yb + (ob + (unsigned)(i * 32 + (v >> 2) * 8 + (v & 3)) * row_bytes), &pk, 4);
+                    }
+            } else {
+                const unsigned ob = 2u * own + rowb * row_bytes;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const __bf16 r = (__bf16)acc[i][jn][v];
+                        __builtin_memcpy(yb + (ob + (unsigned)(i * 32 + (v >> 2) * 8 + (v & 3)) * row_bytes), &r, 2);
+                    }
+            }
+            continue;
+        }
         if (p.ksplit == 1 && p.out_bf16) {
             unsigned short *out = static_cast<unsigned short *>(p.dst) + (size_t)n * p.dst_bs + rem;
 #pragma unroll

@@ -969,6 +969,30 @@ __global__ void finish_wgrad(const float *__restrict__ part, float *__restrict__
     dw[((size_t)k * C + c) * RS + rs] = s;
 }
 
+// The same for a channel count that is a multiple of four: a thread adds four consecutive columns (one tap, four
+// channels) of all splits with 16-byte loads, in the same order as above, and stores the four words.
+__global__ __launch_bounds__(256) void finish_wgrad_x4(const float *__restrict__ part, float *__restrict__ dw, int K,
+                                                        int C, int RS, int nsplit, int groups, FastDiv div_kquads,
+                                                        FastDiv div_quads, FastDiv div_c)
+{
+    const int ncols = RS * C, nquads = ncols / 4;
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= groups * K * nquads) return;
+    const int gcol = (int)fastdiv((uint32_t)i, div_kquads);
+    i -= gcol * (K * nquads);
+    part += (size_t)gcol * nsplit * K * ncols;
+    dw += (size_t)gcol * K * ncols;
+    const int k = (int)fastdiv((uint32_t)i, div_quads), col = 4 * (i - k * nquads);
+    const int rs = (int)fastdiv((uint32_t)col, div_c), c = col - rs * C;
+    const f32x4 *src = reinterpret_cast<const f32x4 *>(part + (size_t)k * ncols + col);
+    const size_t split_quads = (size_t)K * nquads;
+    f32x4 s = src[0];
+#pragma unroll 4
+    for (int t = 1; t < nsplit; ++t) s += src[t * split_quads];
+    float *out = dw + ((size_t)k * C + c) * RS + rs;
+    out[0] = s[0]; out[RS] = s[1]; out[2 * RS] = s[2]; out[3 * RS] = s[3];
+}
+
 // Sum of the split partials in a fixed order: 64 outputs per work-group; lane group g of four adds the
 // splits g, g + 4, g + 8, ... in ascending order, then the four sums are added in group order.
 __global__ __launch_bounds__(256) void reduce_partials(const float *__restrict__ part, float *__restrict__ dw,

@@ -216,6 +216,7 @@ int run_colgemm_dma(int op, const void *act, const void *w, void *out, const Pro
     a.R = pb.R; a.S = pb.S; a.sign = fwd ? 1 : -1;
     a.cblocks = Cr / kc;
     a.dst_bs = (int)(fwd ? pb.y_bs : pb.x_bs); a.out_bf16 = pb.out_bf16;
+    a.dst_small = (int64_t)pb.N * a.dst_bs * 2 < ((int64_t)1 << 31) ? 1 : 0;
     a.mtiles = pl.Mpad / pl.tile.bm();
     a.ntiles = ceil_div(a.ncols, pl.tile.bn());
     a.ksplit = 1; a.steps_per_split = a.cblocks * RS;
@@ -301,6 +302,23 @@ int run_patch_bf16(const void *x, const void *w, void *out, const Problem &pb, c
     void *args[] = {&a};
     hipError_t e = hipLaunchKernel(k, dim3(grid), dim3(kThreads), args, (size_t)lds, st);
     if (e != hipSuccess) return hip_fail(e);
+    return check_launch();
+}
+
+// dw[k][c][rs] from the split partials part[split][k][rs*C + c] of `groups` columns (K, C per column)
+int launch_finish_wgrad(const float *part, float *dw, int K, int C, int RS, int nsplit, int groups, hipStream_t st)
+{
+    const int ncols = RS * C;
+    if (C % 4 == 0 && reinterpret_cast<uintptr_t>(part) % 16 == 0) {
+        const int count = groups * K * (ncols / 4);
+        hipLaunchKernelGGL(finish_wgrad_x4, dim3(grid1d(count, 256)), dim3(256), 0, st, part, dw, K, C, RS, nsplit, groups,
+                           make_fastdiv((uint32_t)(K * (ncols / 4))), make_fastdiv((uint32_t)(ncols / 4)),
+                           make_fastdiv((uint32_t)C));
+    } else {
+        const int count = groups * K * ncols;
+        hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, part, dw, K, C, RS, nsplit, groups,
+                           make_fastdiv((uint32_t)(K * ncols)), make_fastdiv((uint32_t)ncols), make_fastdiv((uint32_t)C));
+    }
     return check_launch();
 }
 
@@ -639,11 +657,7 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         }
         int rc = check_launch();
         if (rc != kStatusOk) return rc;
-        const int count = pb.K * pl.Kg;
-        hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
-                           pb.K, pb.C, RS, pl.nsplit, 1, make_fastdiv((uint32_t)(pb.K * pl.Kg)),
-                           make_fastdiv((uint32_t)pl.Kg), make_fastdiv((uint32_t)pb.C));
-        return check_launch();
+        return launch_finish_wgrad(a.part, static_cast<float *>(dw), pb.K, pb.C, RS, pl.nsplit, 1, st);
     }
     if (pl.rows && reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(dy) % 4 == 0) {
         // few channels, stride 4, bf16: input rows as shifted copies in LDS, one partial result per work-group
@@ -730,11 +744,7 @@ int run_wgrad(const void *x, const void *dy, void *dw, const Problem &caller_pb,
         else launch_wgrad_fast(pl.tile, a, g, st);
         int rc = check_launch();
         if (rc != kStatusOk) return rc;
-        const int count = pb.K * pl.Kg * GF;
-        hipLaunchKernelGGL(finish_wgrad, dim3(grid1d(count, 256)), dim3(256), 0, st, a.part, static_cast<float *>(dw),
-                           pb.K, pb.C, RS, pl.nsplit, GF, make_fastdiv((uint32_t)(pb.K * pl.Kg)),
-                           make_fastdiv((uint32_t)pl.Kg), make_fastdiv((uint32_t)pb.C));
-        return check_launch();
+        return launch_finish_wgrad(a.part, static_cast<float *>(dw), pb.K, pb.C, RS, pl.nsplit, GF, st);
     }
     hipLaunchKernelGGL(build_tap_table, dim3(grid1d(pl.tab_len, 256)), dim3(256), 0, st, tab, pl.tab_len, pl.Kg, RS,
                        pb.S, pb.H * pb.W, pb.W, 1, 1);
