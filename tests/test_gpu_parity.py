@@ -178,7 +178,15 @@ def test_bf16_small_integers_are_exact():
 
 @pytest.mark.parametrize("shape", [(5, 64, 13, 13, 96, 3, 3, 1, 1),      # bf16 kernels
                                    (3, 3, 20, 21, 24, 5, 5, 2, 2),       # widened inputs, fp32 kernels
-                                   (4, 48, 9, 9, 40, 3, 3, 1, 1)])
+                                   (4, 48, 9, 9, 40, 3, 3, 1, 1),
+                                   # the direct-to-LDS kernels both ways: whole tiles store bf16 pairs (a pair that
+                                   # would straddle two samples falls back to single stores), the ragged last tile
+                                   # stores one value at a time
+                                   (2, 128, 13, 13, 128, 3, 3, 1, 1),
+                                   (5, 64, 14, 14, 256, 3, 3, 1, 1),
+                                   # the few-channel bf16 forward kernel: a whole 256-position tile and a ragged one
+                                   (2, 3, 72, 72, 64, 11, 11, 4, 2),
+                                   (3, 3, 64, 72, 96, 11, 11, 4, 2)])
 def test_bf16_outputs_are_the_rounded_fp32_results(shape):
     """dtype 2: y and dx come back as bfloat16 = the fp32 results of dtype 1 rounded to nearest even, written
     through batch strides; within the bf16 tolerance of the oracle."""
