@@ -416,9 +416,9 @@ __global__ __launch_bounds__(256) void bf16_dma_prepare(const DmaPrepArgs p)
 //
 // Work-groups are persistent: the whole filter bank (C*R slices of [Mpad][16] bf16, 99 KB for 96 filters of
 // 3 x 11 x 11) stays in LDS, so the loop over a tile's slices has no barrier; a work-group walks over tiles of
-// 128 output positions of one image, staging each tile's input rows (zero padding in place) as in
-// colgemm_patch_kernel.  The global loads of the next tile's rows are issued before the current tile is
-// multiplied and written to LDS after it.
+// 128 * TN output positions of one image (a wave owns 32 * TN of them, so that a filter fragment read from LDS feeds
+// TN matrix instructions), staging each tile's input rows (zero padding in place) as in colgemm_patch_kernel.  The
+// global loads of the next tile's rows are issued before the current tile is multiplied and written to LDS after it.
 // Needs: S <= 16, stride % 4 == 0, pad even, W % 8 == 0, batch stride % 8 == 0 (16-byte row loads, 8-byte aligned
 // fragment reads).
 // ---------------------------------------------------------------------------
