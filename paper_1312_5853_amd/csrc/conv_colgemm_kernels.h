@@ -234,6 +234,7 @@ struct ColGemmFastArgs {
     // At + g * at_gs, writes dst + g * dst_gs and the partials part + g * part_gs (all in floats)
     int groups;
     int64_t src_gs, dst_gs, at_gs, part_gs;
+    int64_t src_gb, dst_gb, at_gb;      // the same strides in bytes, for the bf16 kernel (bf16 copies, bf16 or fp32 dst)
     // applied where the final sums are stored (this kernel when ksplit == 1 and epi_on, else the split-sum kernel)
     int epi_on;
     Epilogue epi;
@@ -717,9 +718,11 @@ __global__ __launch_bounds__(kThreads, 2) void colgemm_bf16_kernel(const ColGemm
     const int idx = bid >> 3;
     const int unit = (bid & 7) * p.tiles_per_xcd + idx;
     const int ntile = p.mtiles * p.ntiles;
-    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit) return;
-    const int ks = unit / ntile;
-    const int tile = unit - ks * ntile;
+    if (idx >= p.tiles_per_xcd || unit >= ntile * p.ksplit * p.groups) return;
+    const int grp_col = unit / (ntile * p.ksplit);              // column of a grouped layer
+    const int unit_c = unit - grp_col * (ntile * p.ksplit);
+    const int ks = unit_c / ntile;
+    const int tile = unit_c - ks * ntile;
     const int mt = tile % p.mtiles, nt = tile / p.mtiles;
     const int m0 = mt * BM, n0 = nt * BN;
 
@@ -749,11 +752,12 @@ __global__ __launch_bounds__(kThreads, 2) void colgemm_bf16_kernel(const ColGemm
         const int c = grp * EPT + 8 * v;
         voff[v] = (c >> 4) * p.plane_bytes + (c & 15) * 2;
     }
-    const char *src_bytes = reinterpret_cast<const char *>(p.src);
+    const char *src_bytes = reinterpret_cast<const char *>(p.src) + (size_t)grp_col * p.src_gb;
     const size_t a_step = (size_t)p.Mpad * (KC / 8);          // 16-byte vectors per step
     const int step_begin = ks * p.steps_per_split;
     const int nsteps = min(p.cblocks * p.R * p.S - step_begin, p.steps_per_split);
-    const u32x4 *a_ptr = reinterpret_cast<const u32x4 *>(p.At) + (size_t)m0 * (KC / 8) + tid + step_begin * a_step;
+    const u32x4 *a_ptr = reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(p.At) + (size_t)grp_col * p.at_gb) +
+                         (size_t)m0 * (KC / 8) + tid + step_begin * a_step;
 
     // register set t & 1 and LDS buffer t & 1 hold step t (two-set pipeline of colgemm_fast_kernel)
     u32x4 areg[2][A4T];
@@ -909,7 +913,8 @@ __global__ __launch_bounds__(kThreads, 2) void colgemm_bf16_kernel(const ColGemm
             epi_tile<TM, TN>(p.epi, acc, jn, m0 + wm * TM * 32 + half * 4, p.M, plane,
                              (int64_t)n * p.epi.mask_bs + rem);
         if (p.ksplit == 1 && p.out_bf16) {
-            unsigned short *out = reinterpret_cast<unsigned short *>(p.dst) + (size_t)n * p.dst_bs + rem;
+            unsigned short *out = reinterpret_cast<unsigned short *>(reinterpret_cast<char *>(p.dst) + (size_t)grp_col * p.dst_gb) +
+                                  (size_t)n * p.dst_bs + rem;
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
                 const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
@@ -921,8 +926,10 @@ __global__ __launch_bounds__(kThreads, 2) void colgemm_bf16_kernel(const ColGemm
             }
             continue;
         }
-        float *out = p.ksplit > 1 ? p.part + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
-                                  : p.dst + (size_t)n * p.dst_bs + rem;
+        float *out = p.ksplit > 1
+                         ? p.part + (size_t)grp_col * p.part_gs + ((size_t)ks * (p.ncols / plane) + n) * ((size_t)p.M * plane) + rem
+                         : reinterpret_cast<float *>(reinterpret_cast<char *>(p.dst) + (size_t)grp_col * p.dst_gb) +
+                               (size_t)n * p.dst_bs + rem;
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int row0 = m0 + (wm * TM + i) * 32 + half * 4;
@@ -960,13 +967,19 @@ __global__ void block_channels_bf16(const unsigned short *__restrict__ src, u32x
     dst[2 * i + 1] = hi;
 }
 
-// bf16 filters for colgemm_bf16_kernel: wt[((cb*R + r)*S + s)][Mpad][kc]
+// bf16 filters for colgemm_bf16_kernel: wt[((cb*R + r)*S + s)][Mpad][kc]; groups > 1: the filters of column g
+// start w_gs elements after those of column g - 1, the copies are consecutive
 __global__ void relayout_filters_cblk_bf16(const unsigned short *__restrict__ w, unsigned short *__restrict__ wt,
-                                           int M, int Mpad, int cblocks, int RS, int C, int transposed, int kc)
+                                           int M, int Mpad, int cblocks, int RS, int C, int transposed, int kc,
+                                           int groups, int64_t w_gs)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t total = (int64_t)cblocks * RS * Mpad * kc;
-    if (i >= total) return;
+    const int64_t total = (int64_t)cblocks * RS * Mpad * kc;
+    if (i >= total * groups) return;
+    const int64_t gcol = i / total;
+    w += gcol * w_gs;
+    wt += gcol * total;
+    i -= gcol * total;
     int e = (int)(i % kc);
     int64_t t = i / kc;
     int m = (int)(t % Mpad);

@@ -472,9 +472,9 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         const int64_t wt_elems = (int64_t)pl.Mpad * Cr * RS;
         const int GF = pl.fused_groups ? pb.groups : 1;      // columns of a grouped layer run in this one launch
         if (bf)
-            hipLaunchKernelGGL(relayout_filters_cblk_bf16, dim3(grid1d(wt_elems, 256)), dim3(256), 0, st,
+            hipLaunchKernelGGL(relayout_filters_cblk_bf16, dim3(grid1d(wt_elems * GF, 256)), dim3(256), 0, st,
                                static_cast<const unsigned short *>(w), reinterpret_cast<unsigned short *>(wt), pl.M,
-                               pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc);
+                               pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc, GF, pb.w_gs);
         else
             hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d(wt_elems * GF, 256)), dim3(256), 0, st, wf, wt, pl.M,
                                pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc, GF, pb.w_gs);
@@ -490,15 +490,16 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         }
         a.plane_bytes = a.LH * a.LW * 4;
         if (bf) {
-            // channel-blocked copy of the gathered tensor: 32 bytes per position and block of 16 channels
+            // channel-blocked copy of the gathered tensor: 32 bytes per position and block of 16 channels (the
+            // columns of a grouped layer are consecutive channel ranges of one tensor: one copy for all of them)
             const int LHW = a.LH * a.LW;
-            const int64_t vecs = (int64_t)pb.N * (Cr / 16) * LHW;
+            const int64_t vecs = (int64_t)pb.N * (Cr * GF / 16) * LHW;
             u32x4 *blk = reinterpret_cast<u32x4 *>(wsb + pl.blk_off);
             hipLaunchKernelGGL(block_channels_bf16, dim3(grid1d(vecs, 256)), dim3(256), 0, st,
-                               static_cast<const unsigned short *>(act), blk, pb.N, Cr, LHW, (int64_t)a.src_bs,
+                               static_cast<const unsigned short *>(act), blk, pb.N, Cr * GF, LHW, (int64_t)a.src_bs,
                                make_fastdiv((uint32_t)LHW));
             a.src = reinterpret_cast<const float *>(blk);
-            a.src_bs = (Cr / 16) * LHW;
+            a.src_bs = (Cr * GF / 16) * LHW;
             a.plane_bytes = LHW * 32;
         }
         a.ncols = pb.N * a.OH * a.OW;
@@ -517,6 +518,9 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         a.dst_gs = fwd ? pb.y_gs : pb.x_gs;
         a.at_gs = wt_elems;
         a.part_gs = (int64_t)(pl.part_bytes / 4);
+        a.src_gb = (int64_t)(Cr / 16) * a.LH * a.LW * 32;          // bf16 kernel: channel blocks of one column
+        a.at_gb = wt_elems * 2;
+        a.dst_gb = a.dst_gs * (a.out_bf16 ? 2 : 4);
         // the 32 x 32 tile kernels and the split-sum kernel apply an epilogue themselves (one column only)
         a.epi_on = ep && GF == 1 && pb.groups == 1 && (bf || pl.tile.mfma != 16 || a.ksplit > 1);
         a.epi = ep ? *ep : Epilogue{};
@@ -530,9 +534,11 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         if (rc != kStatusOk || a.ksplit == 1) return rc;
         const int per_sample = a.M * a.OH * a.OW;
         if (a.out_bf16)
-            hipLaunchKernelGGL(reduce_split_outputs<unsigned short>, dim3(2048), dim3(256), 0, st, a.part,
-                               reinterpret_cast<unsigned short *>(a.dst), a.ksplit, per_sample, pb.N, a.dst_bs,
-                               make_fastdiv((uint32_t)per_sample), a.epi_on, a.epi, a.div_plane);
+            for (int gc = 0; gc < GF; ++gc)
+                hipLaunchKernelGGL(reduce_split_outputs<unsigned short>, dim3(2048), dim3(256), 0, st,
+                                   a.part + gc * a.part_gs, reinterpret_cast<unsigned short *>(a.dst) + gc * a.dst_gs,
+                                   a.ksplit, per_sample, pb.N, a.dst_bs, make_fastdiv((uint32_t)per_sample), a.epi_on,
+                                   a.epi, a.div_plane);
         else
             for (int gc = 0; gc < GF; ++gc)
                 hipLaunchKernelGGL(reduce_split_outputs<float>, dim3(2048), dim3(256), 0, st, a.part + gc * a.part_gs,

@@ -304,7 +304,9 @@ inline Plan make_plan(int op, const Problem &pb)
         off += round_up64(pl.part_bytes * (pl.fused_groups ? G : 1), 256);
     } else {
         const int Cr_ = op == kOpFwd ? pb.C : pb.K;
-        pl.fused_groups = G > 1 && pb.dtype == kDtypeF32 && Cr_ % kChunk == 0 && (op == kOpFwd || pb.stride == 1);
+        // (fp32 kernels, and the bf16 kernel that stages through registers: neither widens nor takes the direct-to-LDS path)
+        pl.fused_groups = G > 1 && (pb.dtype == kDtypeF32 || pb.dtype == kDtypeBf16) && Cr_ % kChunk == 0 &&
+                          (op == kOpFwd || pb.stride == 1) && !pl.dma;
         const int GF = pl.fused_groups ? G : 1;
         pl.wt_off = off;
         pl.wt_bytes = (size_t)pl.Mpad * pl.Kgpad * 4;
@@ -378,7 +380,7 @@ inline Plan make_plan(int op, const Problem &pb)
         off += round_up64(pl.xb_bytes, 256);
     } else if (pb.dtype == kDtypeBf16 && bf16_kernel && op != kOpBwdFilter) {
         pl.blk_off = off;
-        pl.blk_bytes = (size_t)pb.N * Cr * (op == kOpFwd ? pb.H * pb.W : pb.P * pb.Q) * 2;
+        pl.blk_bytes = (size_t)pb.N * Cr * (pl.fused_groups ? G : 1) * (op == kOpFwd ? pb.H * pb.W : pb.P * pb.Q) * 2;
         off += round_up64(pl.blk_bytes, 256);
     }
     if (pb.out_bf16 && op != kOpBwdFilter && !bf16_kernel && !pl.patch) {
