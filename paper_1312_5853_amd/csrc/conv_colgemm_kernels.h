@@ -1036,6 +1036,33 @@ __global__ void relayout_filters_cblk(const float *__restrict__ w, float *__rest
     wt[i] = v;
 }
 
+// The same re-layout with one thread per four consecutive channels (one 16-byte store) and 32-bit index arithmetic
+// with precomputed divisions: the launch is short (a few MB), so the per-element 64-bit divisions above were most of it.
+// Needs fewer than 2^31 elements in all.
+__global__ void relayout_filters_cblk_x4(const float *__restrict__ w, float *__restrict__ wt, int M, int Mpad,
+                                         int cblocks, int RS, int C, int transposed, int kc, int groups, int64_t w_gs,
+                                         FastDiv div_mpad, FastDiv div_rs, FastDiv div_cb)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t quads = (uint32_t)kc / 4;                        // 4 or 8
+    const uint32_t total = (uint32_t)groups * cblocks * RS * Mpad * quads;
+    if (i >= total) return;
+    const uint32_t q = i & (quads - 1), t0 = i / quads;             // (a shift: quads is a power of two)
+    const uint32_t t1 = fastdiv(t0, div_mpad), m = t0 - t1 * (uint32_t)Mpad;
+    const uint32_t t2 = fastdiv(t1, div_rs), rs = t1 - t2 * (uint32_t)RS;       // t2 = gcol * cblocks + cb
+    const uint32_t gcol = fastdiv(t2, div_cb), cb = t2 - gcol * (uint32_t)cblocks;
+    const float *wg = w + gcol * w_gs;
+    const uint32_t ch = cb * (uint32_t)kc + 4 * q;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (m < (uint32_t)M) {
+        const int64_t base = transposed ? ((int64_t)ch * C + m) * RS + rs : ((int64_t)m * C + ch) * RS + rs;
+        const int64_t stride = transposed ? (int64_t)C * RS : RS;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = wg[base + e * stride];
+    }
+    reinterpret_cast<f32x4 *>(wt)[i] = v;
+}
+
 // ---------------------------------------------------------------------------
 // Forward pass for layers with few input channels (the 11x11 stride-4 first
 // layer: C = 3).  A work-group owns 128 consecutive output positions of ONE

@@ -475,6 +475,11 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
             hipLaunchKernelGGL(relayout_filters_cblk_bf16, dim3(grid1d(wt_elems * GF, 256)), dim3(256), 0, st,
                                static_cast<const unsigned short *>(w), reinterpret_cast<unsigned short *>(wt), pl.M,
                                pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc, GF, pb.w_gs);
+        else if (wt_elems * GF < ((int64_t)1 << 31))
+            hipLaunchKernelGGL(relayout_filters_cblk_x4, dim3(grid1d(wt_elems * GF / 4, 256)), dim3(256), 0, st, wf, wt,
+                               pl.M, pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc, GF, pb.w_gs,
+                               make_fastdiv((uint32_t)pl.Mpad), make_fastdiv((uint32_t)RS),
+                               make_fastdiv((uint32_t)(Cr / kc)));
         else
             hipLaunchKernelGGL(relayout_filters_cblk, dim3(grid1d(wt_elems * GF, 256)), dim3(256), 0, st, wf, wt, pl.M,
                                pl.Mpad, Cr / kc, RS, pb.C, fwd ? 0 : 1, kc, GF, pb.w_gs);
