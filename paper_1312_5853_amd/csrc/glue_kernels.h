@@ -270,7 +270,8 @@ __global__ __launch_bounds__(256) void maxpool_bwd_walk(const T *__restrict__ x,
     T *op = dx + L.plane * (H * W);
     typedef decltype(ld_pair_raw(xp)) Raw;
 
-    // the pair of row h, read from a clamped offset; pair_fix() undoes the clamp's shift of one element
+    // the pair of row h, read from a clamped offset (only the last pair of the tensor is ever clamped, by one element:
+    // first_of() then takes the pair's second value as the lane's first column)
     auto pair_off = [&](int h) { const int o = h * W + c0; return o < L.lim ? o : L.lim; };
     auto first_of = [&](Raw r, int h) { return h * W + c0 > L.lim ? pair_hi(r) : pair_lo(r); };
     auto store_row = [&](int h, float d0, float d1) {
