@@ -1089,7 +1089,7 @@ struct PatchArgs {
     int epi_on;           // bias / ReLU applied to each fp32 sum before it is stored (and, for TO = bfloat16, rounded)
     int vec;              // fp32 rows staged in 16-byte pieces: W % 4 == 0, pad even, images 16-byte aligned
     Epilogue epi;
-    FastDiv div_q, div_rs, div_s, div_mj, div_m, div_wp, div_nr, div_pr;   // div_pr: W / 4 + 1 pieces per staged row
+    FastDiv div_q, div_rs, div_s, div_mj, div_m, div_wp, div_nr, div_pr;   // div_pr: W / 4 pieces per staged row
 };
 
 template <int TM, typename TI, typename TO>
@@ -1126,41 +1126,44 @@ __global__ __launch_bounds__(kThreads) void colgemm_patch_kernel(const PatchArgs
         const TI *xn = static_cast<const TI *>(p.x) + (size_t)n * p.x_bs;
         const int total = p.vec ? 0 : p.C * p.NR * p.WP;
         if (sizeof(TI) == 4 && p.vec) {
-            // 16-byte pieces of the image rows, one more piece per row for the padding columns on both sides;
-            // sixteen loads in flight per thread (the first layer's patch is one batch)
+            // 16-byte pieces of the image rows; sixteen loads in flight per thread (the first layer's patch is one
+            // batch).  Rows outside the image are loaded from a valid address and zeroed when they are stored: a
+            // select on the loaded value would wait for the load.  The store loop has one test per piece and no
+            // inner loops; the pad columns are zeroed by a pass of their own.
             const float *xf = reinterpret_cast<const float *>(xn);
-            const int pr = p.W >> 2, pieces = p.C * p.NR * (pr + 1);
-            constexpr int kNoPiece = -2147483647 - 1;
+            const int pr = p.W >> 2, pieces = p.C * p.NR * pr;
             for (int e0 = tid; e0 < pieces; e0 += kThreads * 16) {
                 f32x4 tmp[16];
                 int dst[16];
+                bool inside[16];
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
                     const int e = e0 + u * kThreads;
                     const int ee = e < pieces ? e : 0;
                     const int row = (int)fastdiv((uint32_t)ee, p.div_pr);
-                    const int pc = ee - row * (pr + 1);
+                    const int pc = ee - row * pr;
                     const int c = (int)fastdiv((uint32_t)row, p.div_nr);
                     const int h = h0 + row - c * p.NR;
-                    const bool ok = (pc < pr) & ((unsigned)h < (unsigned)p.H);
-                    const f32x4 val = *reinterpret_cast<const f32x4 *>(xf + (ok ? (c * p.H + h) * p.W + pc * 4 : 0));
-                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-                    tmp[u] = ok ? val : zero;
-                    dst[u] = e < pieces ? (pc < pr ? row * p.WP + p.pad + pc * 4 : -1 - row * p.WP) : kNoPiece;
+                    const bool ok = (unsigned)h < (unsigned)p.H;
+                    tmp[u] = *reinterpret_cast<const f32x4 *>(xf + (ok ? (c * p.H + h) * p.W + pc * 4 : 0));
+                    inside[u] = ok;
+                    dst[u] = e < pieces ? row * p.WP + p.pad + pc * 4 : -1;
                 }
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
                 for (int u = 0; u < 16; ++u) {
-                    typedef float f32x2 __attribute__((ext_vector_type(2)));
                     if (dst[u] >= 0) {                         // patch rows and pad are even: 8-byte stores
                         f32x2 *q = reinterpret_cast<f32x2 *>(&patch[dst[u]]);
-                        q[0] = f32x2{tmp[u][0], tmp[u][1]};
-                        q[1] = f32x2{tmp[u][2], tmp[u][3]};
-                    } else if (dst[u] != kNoPiece) {
-                        float *rowp = &patch[-1 - dst[u]];
-                        for (int v = 0; v < p.pad; v += 2) *reinterpret_cast<f32x2 *>(&rowp[v]) = f32x2{0.f, 0.f};
-                        for (int v = p.pad + p.W; v < p.WP; v += 2) *reinterpret_cast<f32x2 *>(&rowp[v]) = f32x2{0.f, 0.f};
+                        q[0] = inside[u] ? f32x2{tmp[u][0], tmp[u][1]} : f32x2{0.f, 0.f};
+                        q[1] = inside[u] ? f32x2{tmp[u][2], tmp[u][3]} : f32x2{0.f, 0.f};
                     }
                 }
+            }
+            for (int r = tid; r < p.C * p.NR; r += kThreads) {
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                float *rowp = &patch[r * p.WP];
+                for (int v = 0; v < p.pad; v += 2) *reinterpret_cast<f32x2 *>(&rowp[v]) = f32x2{0.f, 0.f};
+                for (int v = p.pad + p.W; v < p.WP; v += 2) *reinterpret_cast<f32x2 *>(&rowp[v]) = f32x2{0.f, 0.f};
             }
         }
         // any other shape or type, one value at a time: 32 independent loads in flight per thread and batch

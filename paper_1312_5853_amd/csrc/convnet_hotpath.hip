@@ -574,7 +574,7 @@ int run_colgemm_f32out(int op, const void *act, const void *w, void *out, const 
         a.div_m = make_fastdiv((uint32_t)a.mtiles);
         a.div_wp = make_fastdiv((uint32_t)pl.patch_wp);
         a.div_nr = make_fastdiv((uint32_t)pl.patch_nr);
-        a.div_pr = make_fastdiv((uint32_t)(pb.W / 4 + 1));
+        a.div_pr = make_fastdiv((uint32_t)std::max(pb.W / 4, 1));
         a.vec = pb.dtype != kDtypeBf16 && pb.W % 4 == 0 && pb.pad % 2 == 0 && pl.patch_wp % 2 == 0 &&
                 pb.x_bs % 4 == 0 && reinterpret_cast<uintptr_t>(act) % 16 == 0;
         // forward only, so an epilogue here is bias / ReLU: applied to the fp32 sums in the kernel's store
